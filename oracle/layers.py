@@ -1,0 +1,280 @@
+"""Sec. 4 "Model parallel layers": convolution, affine and pooling, each as
+(i) the plain sequential definition and (ii) the paper's distributed forward /
+adjoint algorithm composed from the primitives of Sec. 3, plus the point-wise
+and loss glue used by the Sec. 5 / App. C network.
+
+Shapes follow Sec. 4: x is [n_b, n_ci, m_0..m_{D-1}], w is
+[n_co, n_ci, k_0..k_{D-1}], y is [n_b, n_co, n_0..n_{D-1}]; the affine weight
+W is n_fo x n_fi and y = x W^T + b for x of shape [n_b, n_fi].
+"Conv" is the cross-correlation of the framework layer the paper wraps
+(Sec. 5 says the base layer function is the framework's own).
+
+Everything is fp64.  Test infrastructure only.
+"""
+import numpy as np
+
+from . import geometry as geo
+from . import primitives as prim
+
+_L = (slice(None), slice(None))
+
+# --------------------------------------------------------------------------
+# plain definitions (sequential layer functions)
+# --------------------------------------------------------------------------
+
+
+def _tap_view(xp, kappa, out_shape, stride, dilation, origin):
+    """View of a padded input holding, for every output index o, the cell
+    origin + o*s + kappa*dil read by kernel tap kappa."""
+    sl = tuple(slice(origin[d] + kappa[d] * dilation[d],
+                     origin[d] + kappa[d] * dilation[d] + stride[d] * (out_shape[d] - 1) + 1,
+                     stride[d]) for d in range(len(out_shape)))
+    return xp[_L + sl]
+
+
+def conv_valid(xp, w, bias, out_shape, stride, dilation, origin):
+    """y[n,co,o] = b[co] + sum_kappa sum_ci w[co,ci,kappa] xp[n,ci,origin+o*s+kappa*dil]
+    on an input that already contains whatever padding it needs."""
+    xp = np.asarray(xp, dtype=np.float64)
+    w = np.asarray(w, dtype=np.float64)
+    y = np.zeros((xp.shape[0], w.shape[0]) + tuple(out_shape))
+    for kappa in np.ndindex(*w.shape[2:]):
+        xs = _tap_view(xp, kappa, out_shape, stride, dilation, origin)
+        y += np.einsum("oc,nc...->no...", w[_L + kappa], xs)
+    if bias is not None:
+        y += np.asarray(bias, dtype=np.float64).reshape((1, -1) + (1,) * len(out_shape))
+    return y
+
+
+def conv_valid_adjoint(xp, w, dy, stride, dilation, origin, want_bias=True):
+    """Adjoint of the Jacobian of conv_valid with respect to xp, w and b:
+      dxp[n,ci,origin+o*s+kappa*dil] += sum_co w[co,ci,kappa] dy[n,co,o]
+      dw[co,ci,kappa] = sum_{n,o} dy[n,co,o] xp[n,ci,origin+o*s+kappa*dil]
+      db[co] = sum_{n,o} dy[n,co,o]."""
+    xp = np.asarray(xp, dtype=np.float64)
+    w = np.asarray(w, dtype=np.float64)
+    dy = np.asarray(dy, dtype=np.float64)
+    out_shape = dy.shape[2:]
+    dxp = np.zeros_like(xp)
+    dw = np.zeros_like(w)
+    for kappa in np.ndindex(*w.shape[2:]):
+        xs = _tap_view(xp, kappa, out_shape, stride, dilation, origin)
+        dw[_L + kappa] = np.einsum("nos,ncs->oc", dy.reshape(dy.shape[:2] + (-1,)),
+                                   xs.reshape(xs.shape[:2] + (-1,)))
+        dxs = _tap_view(dxp, kappa, out_shape, stride, dilation, origin)
+        dxs += np.einsum("oc,no...->nc...", w[_L + kappa], dy)
+    db = dy.sum(axis=(0,) + tuple(range(2, dy.ndim))) if want_bias else None
+    return dxp, dw, db
+
+
+def _zero_pad(x, padding):
+    return np.pad(np.asarray(x, dtype=np.float64),
+                  [(0, 0), (0, 0)] + [(p, p) for p in padding])
+
+
+def conv_forward(x, w, bias, stride, padding, dilation):
+    """Sequential convolution layer: zero-pad by `padding`, then conv_valid."""
+    D = x.ndim - 2
+    out = [geo.output_length(x.shape[2 + d], w.shape[2 + d], stride[d], padding[d], dilation[d])
+           for d in range(D)]
+    return conv_valid(_zero_pad(x, padding), w, bias, out, stride, dilation, [0] * D)
+
+
+def conv_backward(x, w, dy, stride, padding, dilation):
+    """(dx, dw, db) of the sequential layer; dx drops the padding cells."""
+    D = x.ndim - 2
+    dxp, dw, db = conv_valid_adjoint(_zero_pad(x, padding), w, dy, stride, dilation, [0] * D)
+    core = tuple(slice(padding[d], padding[d] + x.shape[2 + d]) for d in range(D))
+    return dxp[_L + core], dw, db
+
+
+def affine_forward(x, W, b):
+    """y = x W^T + b (Sec. 4 "Dense layers")."""
+    y = np.asarray(x, dtype=np.float64) @ np.asarray(W, dtype=np.float64).T
+    return y if b is None else y + np.asarray(b, dtype=np.float64)[None, :]
+
+
+def affine_backward(x, W, dy):
+    x, W, dy = (np.asarray(t, dtype=np.float64) for t in (x, W, dy))
+    return dy @ W, dy.T @ x, dy.sum(axis=0)        # dx, dW, db
+
+
+def relu(x):
+    return np.maximum(x, 0.0)
+
+
+def relu_backward(x, dy):
+    """Derivative taken as 0 at x == 0."""
+    return np.where(x > 0, dy, 0.0)
+
+
+def maxpool_valid(xp, ksize, stride, out_shape, origin):
+    """Max over each window of an already-trimmed / padded input; also returns,
+    per output, the row-major index of the first maximal tap."""
+    best = None
+    arg = None
+    for t, kappa in enumerate(np.ndindex(*ksize)):
+        xs = _tap_view(xp, kappa, out_shape, stride, [1] * len(ksize), origin)
+        if best is None:
+            best, arg = xs.copy(), np.zeros(xs.shape, dtype=np.int64)
+        else:
+            better = xs > best                      # strict: first maximum wins
+            best = np.where(better, xs, best)
+            arg = np.where(better, t, arg)
+    return best, arg
+
+
+def maxpool_valid_adjoint(dy, arg, xp_shape, ksize, stride, origin):
+    dxp = np.zeros(xp_shape)
+    out_shape = dy.shape[2:]
+    for t, kappa in enumerate(np.ndindex(*ksize)):
+        dxs = _tap_view(dxp, kappa, out_shape, stride, [1] * len(ksize), origin)
+        dxs += np.where(arg == t, dy, 0.0)
+    return dxp
+
+
+def mse_loss(y, target):
+    """mean((y - t)^2) over every element, and its gradient."""
+    diff = np.asarray(y, dtype=np.float64) - target
+    return float(np.mean(diff * diff)), 2.0 * diff / diff.size
+
+
+# --------------------------------------------------------------------------
+# distributed convolution, feature-space partition only (P_co = P_ci = 1)
+# --------------------------------------------------------------------------
+
+
+def dist_conv_forward(x_bufs, w, bias, part, stride, dilation):
+    """Forward Convolution Algorithm of Sec. 4 with P_co = P_ci = 1.
+    x_bufs: per-worker padded buffers with the bulk filled.  Steps, in the
+    paper's order: x <- H x; w^ <- B w; b^ <- B b; x^ <- B x (identity here);
+    y^ <- Conv(w^, b^; x^) on each worker's own buffer with no further
+    padding, starting at that worker's origin; y <- R y^ (identity here).
+    Returns the list of per-worker outputs; x_bufs holds H x afterwards."""
+    P = part.n_workers
+    prim.halo_exchange(x_bufs, part)
+    w_hat = prim.broadcast(np.asarray(w, dtype=np.float64), P)
+    b_hat = prim.broadcast(np.asarray(bias, dtype=np.float64), P) if bias is not None else [None] * P
+    y_hat = []
+    for wk in range(P):
+        origin = [part.g(wk, d)["origin"] for d in range(part.D)]
+        y_hat.append(conv_valid(x_bufs[wk], w_hat[wk], b_hat[wk], part.out_shape(wk),
+                                stride, dilation, origin))
+    return y_hat
+
+
+def dist_conv_adjoint(x_bufs, w, dy_parts, part, stride, dilation, want_bias=True):
+    """Adjoint Convolution Algorithm of Sec. 4 with P_co = P_ci = 1:
+    dy^ <- B dy (identity); (dw^, db^, dx^) <- [dConv]*(dy^) per worker, dx^
+    covering the whole padded buffer; dx <- R dx^ (identity); db <- R db^ and
+    dw <- R dw^ over all workers (adjoint of the forward broadcasts);
+    dx <- H* dx.  x_bufs must hold H x (saved by the forward pass).
+    Returns (dx_bufs, dw, db)."""
+    P = part.n_workers
+    w_hat = prim.broadcast(np.asarray(w, dtype=np.float64), P)
+    dx_hat, dw_hat, db_hat = [], [], []
+    for wk in range(P):
+        origin = [part.g(wk, d)["origin"] for d in range(part.D)]
+        dxp, dw_k, db_k = conv_valid_adjoint(x_bufs[wk], w_hat[wk], dy_parts[wk],
+                                             stride, dilation, origin, want_bias)
+        dx_hat.append(dxp)
+        dw_hat.append(dw_k)
+        db_hat.append(db_k)
+    dw = prim.sum_reduce(dw_hat)
+    db = prim.sum_reduce(db_hat) if want_bias else None
+    prim.halo_exchange_adjoint(dx_hat, part)
+    return dx_hat, dw, db
+
+
+# --------------------------------------------------------------------------
+# distributed pooling
+# --------------------------------------------------------------------------
+
+
+def dist_maxpool_forward(x_bufs, part, ksize, stride):
+    """Forward Pooling Algorithm of Sec. 4: x <- H x; y <- Pool(x), the local
+    pool starting at each worker's origin (which skips "extra" input)."""
+    prim.halo_exchange(x_bufs, part)
+    ys, args = [], []
+    for wk in range(part.n_workers):
+        origin = [part.g(wk, d)["origin"] for d in range(part.D)]
+        y, a = maxpool_valid(np.asarray(x_bufs[wk], dtype=np.float64), ksize, stride,
+                             part.out_shape(wk), origin)
+        ys.append(y)
+        args.append(a)
+    return ys, args
+
+
+def dist_maxpool_adjoint(dy_parts, args, part, buf_shapes, ksize, stride):
+    """Adjoint Pooling Algorithm of Sec. 4: dx <- [dPool]*(dy); dx <- H* dx."""
+    dx = []
+    for wk in range(part.n_workers):
+        origin = [part.g(wk, d)["origin"] for d in range(part.D)]
+        dx.append(maxpool_valid_adjoint(dy_parts[wk], args[wk], buf_shapes[wk], ksize, stride, origin))
+    prim.halo_exchange_adjoint(dx, part)
+    return dx
+
+
+# --------------------------------------------------------------------------
+# distributed affine on a P_fo x P_fi weight partition
+# --------------------------------------------------------------------------
+
+
+def feature_blocks(n, parts):
+    return [slice(s, s + z) for (s, z) in geo.balanced_split(n, parts)]
+
+
+def dist_affine_forward(x_parts, W_parts, b_parts, P_fo, P_fi):
+    """Forward Affine Algorithm of Sec. 4.  x_parts[j] is [n_b, fi_j];
+    W_parts[i][j] is [fo_i, fi_j]; b_parts[i] (or None) lives on column j = 0
+    only.  x^_ij <- B x_j along P_fo; y^_ij <- Affine(W_ij, b_ij; x^_ij);
+    y_i <- R over j of y^_ij."""
+    x_hat = [prim.broadcast(np.asarray(x_parts[j], dtype=np.float64), P_fo) for j in range(P_fi)]
+    y = []
+    for i in range(P_fo):
+        y_hat_i = []
+        for j in range(P_fi):
+            b_ij = b_parts[i] if (j == 0 and b_parts is not None) else None
+            y_hat_i.append(affine_forward(x_hat[j][i], W_parts[i][j], b_ij))
+        y.append(prim.sum_reduce(y_hat_i))
+    return y
+
+
+def dist_affine_adjoint(x_parts, W_parts, dy_parts, P_fo, P_fi):
+    """Adjoint Affine Algorithm of Sec. 4: dy^_ij <- B dy_i along P_fi;
+    (dW_ij, db_i [j = 0], dx^_ij) <- [dAffine]*(dy^_ij); dx_j <- R over i.
+    Returns (dx_parts, dW_parts, db_parts)."""
+    dy_hat = [prim.broadcast(np.asarray(dy_parts[i], dtype=np.float64), P_fi) for i in range(P_fo)]
+    dW = [[None] * P_fi for _ in range(P_fo)]
+    db = [None] * P_fo
+    dx_hat = [[None] * P_fo for _ in range(P_fi)]
+    for i in range(P_fo):
+        for j in range(P_fi):
+            dx_ij, dW_ij, db_ij = affine_backward(x_parts[j], W_parts[i][j], dy_hat[i][j])
+            dW[i][j] = dW_ij
+            dx_hat[j][i] = dx_ij
+            if j == 0:
+                db[i] = db_ij
+    dx = [prim.sum_reduce(dx_hat[j]) for j in range(P_fi)]
+    return dx, dW, db
+
+
+# --------------------------------------------------------------------------
+# repartition ("transpose" / generalized all-to-all glue, Sec. 3)
+# --------------------------------------------------------------------------
+
+
+def repartition_spatial_to_features(y_parts, part, P_fi):
+    """Block permutation (Sec. 3 "Generalized all-to-all"): gather the
+    spatially partitioned [n_b, c, h, w] blocks, flatten to [n_b, c*h*w]
+    (row-major, the framework's flatten) and split the features over P_fi."""
+    full = prim.gather_out(y_parts, part)
+    flat = full.reshape(full.shape[0], -1)
+    return [flat[:, s].copy() for s in feature_blocks(flat.shape[1], P_fi)]
+
+
+def repartition_features_to_spatial(dx_parts, part, n_c):
+    """Adjoint (= inverse) of the permutation above."""
+    flat = np.concatenate(dx_parts, axis=1)
+    full = flat.reshape((flat.shape[0], n_c) + part.global_out_shape())
+    return prim.scatter_out(full, part)
