@@ -1,0 +1,227 @@
+/* distdl.h -- C ABI of the MI355X (gfx950) library for the data-movement
+ * primitives and partitioned layers of Hewett & Grady, "A Linear Algebraic
+ * Approach to Model Parallelism in Deep Learning" (arXiv 2006.03108).
+ *
+ * All P "workers" (the paper's parallel workers, Sec. 3) are virtual
+ * partitions that live in one GPU's HBM.  A send-receive (Sec. 3 "Send and
+ * Receive": a copy C_{a->b} between two workers' memories) is a strided
+ * device copy between partition buffers; its adjoint adds into the source and
+ * clears the destination (Sec. 2 "Copy": C* = K_b S_{b->a}).
+ *
+ * Conventions
+ *  - C99, no C++ types, no exceptions across the boundary.
+ *  - Pointers named *_dev are DEVICE pointers owned by the caller.  Arrays of
+ *    pointers / sizes are HOST arrays read during the call; the library
+ *    copies what it needs, the caller may free them on return.
+ *  - All work is enqueued on `stream` (a hipStream_t passed as void*, NULL =
+ *    the default stream); calls are asynchronous and never synchronise.
+ *  - Return value: DISTDL_OK (0) or a negative error code; on error nothing
+ *    has been enqueued.  distdl_last_error() gives a thread-local message.
+ *  - Outputs named d* (gradients) are OVERWRITTEN, not accumulated into: each
+ *    call is an out-of-place adjoint (Sec. 3, first paragraph).
+ *  - Device pointers must be aligned to the element size; 16-byte alignment
+ *    (what any allocator gives) enables the vectorised kernels.
+ *  - One plan may be used from one host thread at a time.
+ *
+ * Memory layout of sliding-kernel tensors: CHANNELS-LAST.  The paper fixes
+ * only the logical shape n_b x n_c x m_0 x ... x m_{D-1} (Sec. 4 "Sparse
+ * layers") and leaves ordering and layout to the implementation (Sec. 2).
+ * Here a worker's padded buffer is the contiguous array
+ *        [n_b][buf_0]...[buf_{D-1}][n_c]          (n_c fastest)
+ * so that one feature-space cell is n_c contiguous elements: every halo
+ * face, edge and corner is then made of whole contiguous cells, and the
+ * channel axis is the contraction axis the matrix cores read.  Along each
+ * feature dimension a buffer is  [ pad_L | halo_L | bulk | halo_R | pad_R ].
+ * Outputs y are dense [n_b][out_0]...[out_{D-1}][n_co]; convolution weights
+ * keep the paper's shape [n_co][n_ci][k_0]...[k_{D-1}] (last fastest).
+ */
+#ifndef DISTDL_H
+#define DISTDL_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { DISTDL_F32 = 0, DISTDL_BF16 = 1 } distdl_dtype;
+
+enum {
+  DISTDL_OK = 0,
+  DISTDL_ERR_INVALID_ARG = -1,
+  DISTDL_ERR_NULL = -2,
+  DISTDL_ERR_UNSUPPORTED = -3,
+  DISTDL_ERR_EMPTY_PARTITION = -4, /* some worker would own no input or no output cell */
+  DISTDL_ERR_HALO_TOO_WIDE = -5,   /* a halo exceeds the adjacent worker's bulk (Sec. 3
+                                      assumes directly adjacent neighbours only) */
+  DISTDL_ERR_HIP = -6,
+  DISTDL_ERR_NOMEM = -7
+};
+
+#define DISTDL_MAX_DIMS 3
+
+/* ------------------------------------------------------------------------
+ * Sliding-kernel plan (Sec. 3 "Halo exchange", App. B.1).
+ *
+ * Splits a feature space of extent in_shape over the partition vector P
+ * (Sec. 4: workers per dimension; worker id is row-major over P) and derives,
+ * per dimension and worker, the halo / pad / extra widths from the worker's
+ * first and last output index and the kernel's size, stride, dilation and
+ * padding.  Per dimension, with n = in_shape, m = floor((n+2p-dil(k-1)-1)/s)+1:
+ *   balanced split of a length L: worker r gets floor(L/P)+(r < L mod P) cells;
+ *   inputs and outputs are split by it independently (output drives the load
+ *   balance, App. B.1);  outputs [j0,j1] need inputs [j0*s-p, j1*s-p+dil(k-1)];
+ *   pad = the part outside [0,n-1], halo = the in-domain part outside the
+ *   owned range, extra = owned cells outside the needed range.
+ * Errors: EMPTY_PARTITION, HALO_TOO_WIDE, INVALID_ARG (D not in 1..3, sizes
+ * < 1), UNSUPPORTED (dtype).
+ * ---------------------------------------------------------------------- */
+typedef struct distdl_plan distdl_plan; /* opaque, library-owned */
+
+int distdl_plan_create(distdl_plan** out, int D, int64_t n_b, int64_t n_c_in, int64_t n_c_out,
+                       const int64_t in_shape[], const int32_t P[], const int32_t ksize[],
+                       const int32_t stride[], const int32_t padding[], const int32_t dilation[],
+                       distdl_dtype dtype);
+
+/* Halo-only plan with user-given bulk sizes and halo widths and no padding,
+ * the form of the rank-2 example of App. B.2.  bulk_sizes holds, dimension
+ * after dimension, P[d] sizes; halo_lr holds, in the same order, (left,
+ * right) pairs.  conv_* calls reject such a plan (UNSUPPORTED). */
+int distdl_plan_create_explicit(distdl_plan** out, int D, int64_t n_b, int64_t n_c, const int32_t P[],
+                                const int64_t bulk_sizes[], const int32_t halo_lr[], distdl_dtype dtype);
+
+typedef struct {
+  int64_t in_start[DISTDL_MAX_DIMS], in_size[DISTDL_MAX_DIMS];   /* owned (bulk) input range   */
+  int64_t out_start[DISTDL_MAX_DIMS], out_size[DISTDL_MAX_DIMS]; /* owned output range         */
+  int32_t halo[DISTDL_MAX_DIMS][2], pad[DISTDL_MAX_DIMS][2], extra[DISTDL_MAX_DIMS][2]; /* [d][left,right] */
+  int64_t buf_shape[DISTDL_MAX_DIMS]; /* pad_L + halo_L + bulk + halo_R + pad_R              */
+  int64_t bulk_off[DISTDL_MAX_DIMS];  /* buffer coordinate of the first bulk cell           */
+  int64_t conv_origin[DISTDL_MAX_DIMS]; /* buffer coordinate of the first tap of the first
+                                           owned output (= extra_L)                           */
+} distdl_worker_geom;
+
+int distdl_plan_num_workers(const distdl_plan* plan); /* prod(P), or a negative error */
+int distdl_plan_query(const distdl_plan* plan, int worker, distdl_worker_geom* out);
+int distdl_plan_destroy(distdl_plan* plan);
+
+/* ------------------------------------------------------------------------
+ * Halo exchange H and its adjoint H* (Sec. 3 "Halo exchange", both displayed
+ * operator products; App. B.2).  In place on the P padded buffers
+ * bufs_dev[worker], each [n_b][buf_0..buf_{D-1}][n_c] of the plan's dtype.
+ *
+ * halo_fwd: every in-domain non-owned cell <- the owning worker's bulk value
+ *   (a bit-exact copy), every zero-padding cell <- 0, bulk untouched.  The
+ *   result does not depend on previous halo / pad contents.  This is what the
+ *   nested per-dimension exchange leaves behind, computed in one pass.
+ * halo_adj: every bulk cell += the sum of all halo cells (in other workers'
+ *   buffers) that alias it, summed in ascending source-worker order in fp32;
+ *   then every halo and pad cell <- 0.  Deterministic (no atomics).
+ * ---------------------------------------------------------------------- */
+int distdl_halo_fwd(distdl_plan* plan, void* const bufs_dev[], void* stream);
+int distdl_halo_adj(distdl_plan* plan, void* const gbufs_dev[], void* stream);
+
+/* ------------------------------------------------------------------------
+ * Broadcast B_{a->{k}} and sum-reduce R_{{k}->a} = B* over G independent
+ * groups of k replicas (Sec. 3 "Broadcast", "Sum-reduce and all-reduce").
+ * Group g has count[g] elements; replica i of group g is pointer [g*k + i].
+ *
+ * bcast_fwd / sumreduce_adj:  dst[g*k+i][e] = src[g][e]            (bit-exact)
+ * bcast_adj / sumreduce_fwd:  out[g][e] = sum_{i=0}^{k-1} in[g*k+i][e], summed
+ *   in index order in fp32, overwriting out.  With clear_inputs != 0 the
+ *   replicas are zeroed afterwards (the K_i of B* = sum_i K_i S_{i->a}).
+ * In and out buffers must not overlap.  Errors: NULL, INVALID_ARG (G, k < 1,
+ * count < 0).
+ * ---------------------------------------------------------------------- */
+int distdl_bcast_fwd(const void* const src_dev[], void* const dst_dev[], const int64_t count[], int G, int k,
+                     distdl_dtype dtype, void* stream);
+int distdl_bcast_adj(void* const gsrc_dev[], void* const gdst_dev[], const int64_t count[], int G, int k,
+                     distdl_dtype dtype, int clear_inputs, void* stream);
+int distdl_sumreduce_fwd(void* const src_dev[], void* const dst_dev[], const int64_t count[], int G, int k,
+                         distdl_dtype dtype, int clear_inputs, void* stream);
+int distdl_sumreduce_adj(const void* const gdst_dev[], void* const gsrc_dev[], const int64_t count[], int G,
+                         int k, distdl_dtype dtype, void* stream);
+
+/* ------------------------------------------------------------------------
+ * Partitioned convolution: the Forward / Adjoint Convolution Algorithms of
+ * Sec. 4 with the feature space partitioned only (P_co = P_ci = 1), fp32.
+ *
+ * conv_fwd: x <- H x in place on x_bufs_dev; w and b are read by every worker
+ *   directly (the broadcasts B w, B b without materialised replicas); each
+ *   worker's y[n][o][co] = b[co] + sum_{ci,kappa} w[co][ci][kappa] *
+ *   x^[n][origin + o*s + kappa*dil][ci] on its own buffer, no further padding.
+ *   y_dev[worker] is dense [n_b][out_0..][n_co].  bias_dev may be NULL.
+ * conv_bwd: x_bufs_dev must hold H x (as left by conv_fwd).  Computes the
+ *   local [dConv]* into the whole padded dx buffers, dw = sum over workers of
+ *   the local dw^ and db likewise (the sum-reduces R that are the adjoints of
+ *   B w and B b), then dx <- H* dx: on return each dx buffer holds the
+ *   gradient in its bulk and zeros in halo and pad cells.  dw_dev has the
+ *   shape of w; dbias_dev may be NULL.  workspace_dev must provide
+ *   distdl_conv_bwd_workspace(plan) bytes (16-byte aligned).
+ * Errors: UNSUPPORTED for a bf16 or explicit plan; INVALID_ARG for a short
+ * workspace.
+ * ---------------------------------------------------------------------- */
+int distdl_conv_fwd(distdl_plan* plan, void* const x_bufs_dev[], const void* w_dev, const void* bias_dev,
+                    void* const y_dev[], void* stream);
+int distdl_conv_bwd(distdl_plan* plan, const void* const x_bufs_dev[], const void* w_dev,
+                    const void* const dy_dev[], void* const dx_bufs_dev[], void* dw_dev, void* dbias_dev,
+                    void* workspace_dev, size_t workspace_bytes, void* stream);
+size_t distdl_conv_bwd_workspace(const distdl_plan* plan);
+
+/* ------------------------------------------------------------------------
+ * Partitioned affine layer: the Forward / Adjoint Affine Algorithms of
+ * Sec. 4 "Dense layers" on a P_fo x P_fi weight partition; worker (i, j) has
+ * id i*P_fi + j and holds W_ij [fo_i][fi_j] row-major.  Feature blocks follow
+ * the balanced split.  x_j is [n_b][fi_j], y_i is [n_b][fo_i], row-major.
+ *
+ * affine_fwd: y_i = sum_j x_j W_ij^T + b_i  -- the broadcast of x_j along
+ *   P_fo is a shared read, the sum-reduce along P_fi is the continuation of
+ *   the contraction over j (ascending); b_i is added once (it lives on column
+ *   j = 0 only).  b_dev, or any b_dev[i], may be NULL.
+ * affine_bwd: dW_ij = dy_i^T x_j;  db_i = sum_n dy_i[n][:];  dx_j = sum_i
+ *   dy_i W_ij (i ascending).  db_dev may be NULL.
+ * fp32: fp32 operands and accumulation.  bf16: bf16 operands, fp32
+ * accumulation, outputs rounded to bf16 (nearest even); b and db are bf16.
+ * ---------------------------------------------------------------------- */
+typedef struct distdl_affine_plan distdl_affine_plan;
+int distdl_affine_plan_create(distdl_affine_plan** out, int64_t n_b, int64_t n_fi, int64_t n_fo, int P_fo,
+                              int P_fi, distdl_dtype dtype);
+int distdl_affine_plan_destroy(distdl_affine_plan* plan);
+int distdl_affine_fwd(distdl_affine_plan* plan, const void* const x_dev[], const void* const W_dev[],
+                      const void* const b_dev[], void* const y_dev[], void* stream);
+int distdl_affine_bwd(distdl_affine_plan* plan, const void* const x_dev[], const void* const W_dev[],
+                      const void* const dy_dev[], void* const dx_dev[], void* const dW_dev[],
+                      void* const db_dev[], void* stream);
+
+/* ------------------------------------------------------------------------
+ * Euclidean inner product over a list of device arrays (Sec. 2, second
+ * displayed equation; the direct sum over workers of Sec. 3), accumulated in
+ * fp64 on the device.  result_dev points to ONE double in device memory.
+ * Used for the adjoint test |<Fx,y> - <x,F*y>| / max(...) (Sec. 3
+ * "Implementation") on device-resident data.
+ * ---------------------------------------------------------------------- */
+int distdl_dot(const void* const a_dev[], const void* const b_dev[], const int64_t count[], int n_arrays,
+               distdl_dtype dtype, double* result_dev, void* stream);
+
+/* ------------------------------------------------------------------------
+ * Introspection of the host planner (for tests that run without a GPU): the
+ * one-pass halo kernels are driven by a table of box tasks.  Task `index` of
+ * the forward (adjoint = 0) or adjoint table is written to out[] as
+ *   dst_worker, nsrc, org[3], ext[3], then per source: worker, org[3]
+ * in buffer-cell coordinates of 3 feature dims (leading dims of extent 1 when
+ * D < 3).  nsrc = 0: zero fill; forward nsrc = 1: dst box <- source box;
+ * adjoint nsrc >= 1: dst box += each source box, source boxes <- 0.
+ * get_task returns the number of ints written.
+ * ---------------------------------------------------------------------- */
+int distdl_debug_task_count(const distdl_plan* plan, int adjoint);
+/* floor(n / d) through the multiply-shift constants the kernels use to decode
+ * a flat work index (d >= 1). */
+uint32_t distdl_debug_fastdiv(uint32_t n, uint32_t d);
+int distdl_debug_get_task(const distdl_plan* plan, int adjoint, int index, int32_t out[], int cap);
+
+const char* distdl_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DISTDL_H */

@@ -1,0 +1,312 @@
+// Broadcast B, sum-reduce R = B* (Sec. 3 "Broadcast", "Sum-reduce and
+// all-reduce") over groups of replicas held in one HBM, and the Euclidean
+// inner product over a list of arrays (Sec. 2) for the adjoint test.
+//
+// Replica pointers travel as kernel arguments (at most kMaxPtrs per launch;
+// larger problems are split on the host: a broadcast over more replicas is
+// several independent launches, a reduction continues into its output in
+// replica order, so the summation order stays i = 0..k-1).
+#include "common.h"
+
+namespace distdl {
+
+constexpr int kMaxPtrs = 48;
+constexpr int kMaxGroups = 16;
+constexpr int kCollThreads = 256;
+
+__device__ inline float bf2f(uint32_t h) { return __uint_as_float(h << 16); }
+__device__ inline uint32_t f2bf(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return u >> 16;
+}
+
+struct CollArgs {
+  void* one[kMaxGroups];    // per group: the single (source / reduced) array
+  void* many[kMaxPtrs];     // replicas, group after group
+  int64_t count[kMaxGroups];
+  int32_t first[kMaxGroups];  // index of the group's first replica in many[]
+  int32_t k[kMaxGroups];      // replicas of the group in this launch
+  int32_t wide[kMaxGroups];   // all pointers of the group 16-byte aligned
+  int32_t accumulate;         // reduction continues into one[] instead of overwriting it
+  int32_t clear_inputs;
+};
+
+template <bool BF16>
+__global__ __launch_bounds__(kCollThreads) void bcast_kernel(CollArgs a) {
+  const int g = blockIdx.y;
+  const int64_t count = a.count[g];
+  constexpr int V = BF16 ? 8 : 4;
+  const int64_t nvec = a.wide[g] ? count / V : 0;
+  const int k = a.k[g];
+  void* const* rep = a.many + a.first[g];
+  const int64_t stride = (int64_t)gridDim.x * kCollThreads;
+  const int64_t tid = (int64_t)blockIdx.x * kCollThreads + threadIdx.x;
+  const uint4* src = (const uint4*)a.one[g];
+  for (int64_t u = tid; u < nvec; u += stride) {
+    uint4 v = src[u];
+    for (int i = 0; i < k; ++i) ((uint4*)rep[i])[u] = v;
+  }
+  for (int64_t e = nvec * V + tid; e < count; e += stride) {
+    if (BF16) {
+      uint16_t v = ((const uint16_t*)a.one[g])[e];
+      for (int i = 0; i < k; ++i) ((uint16_t*)rep[i])[e] = v;
+    } else {
+      uint32_t v = ((const uint32_t*)a.one[g])[e];
+      for (int i = 0; i < k; ++i) ((uint32_t*)rep[i])[e] = v;
+    }
+  }
+}
+
+template <bool BF16>
+__global__ __launch_bounds__(kCollThreads) void reduce_kernel(CollArgs a) {
+  const int g = blockIdx.y;
+  const int64_t count = a.count[g];
+  constexpr int V = BF16 ? 8 : 4;
+  const int64_t nvec = a.wide[g] ? count / V : 0;
+  const int k = a.k[g];
+  void* const* rep = a.many + a.first[g];
+  const int64_t stride = (int64_t)gridDim.x * kCollThreads;
+  const int64_t tid = (int64_t)blockIdx.x * kCollThreads + threadIdx.x;
+  for (int64_t u = tid; u < nvec; u += stride) {
+    float acc[V];
+    if (a.accumulate) {
+      uint4 o = ((const uint4*)a.one[g])[u];
+      const uint32_t w[4] = {o.x, o.y, o.z, o.w};
+      for (int j = 0; j < 4; ++j) {
+        if (BF16) {
+          acc[2 * j] = bf2f(w[j] & 0xffffu);
+          acc[2 * j + 1] = bf2f(w[j] >> 16);
+        } else {
+          acc[j] = __uint_as_float(w[j]);
+        }
+      }
+    } else {
+      for (int j = 0; j < V; ++j) acc[j] = 0.f;
+    }
+    for (int i = 0; i < k; ++i) {  // replica order i = 0 .. k-1
+      uint4 r = ((const uint4*)rep[i])[u];
+      const uint32_t w[4] = {r.x, r.y, r.z, r.w};
+      for (int j = 0; j < 4; ++j) {
+        if (BF16) {
+          acc[2 * j] += bf2f(w[j] & 0xffffu);
+          acc[2 * j + 1] += bf2f(w[j] >> 16);
+        } else {
+          acc[j] += __uint_as_float(w[j]);
+        }
+      }
+      if (a.clear_inputs) ((uint4*)rep[i])[u] = make_uint4(0, 0, 0, 0);
+    }
+    uint4 o;
+    if (BF16) {
+      o.x = f2bf(acc[0]) | (f2bf(acc[1]) << 16);
+      o.y = f2bf(acc[2]) | (f2bf(acc[3]) << 16);
+      o.z = f2bf(acc[4]) | (f2bf(acc[5]) << 16);
+      o.w = f2bf(acc[6]) | (f2bf(acc[7]) << 16);
+    } else {
+      o = make_uint4(__float_as_uint(acc[0]), __float_as_uint(acc[1]), __float_as_uint(acc[2]),
+                     __float_as_uint(acc[3]));
+    }
+    ((uint4*)a.one[g])[u] = o;
+  }
+  for (int64_t e = nvec * V + tid; e < count; e += stride) {
+    if (BF16) {
+      uint16_t* out = (uint16_t*)a.one[g];
+      float acc = a.accumulate ? bf2f(out[e]) : 0.f;
+      for (int i = 0; i < k; ++i) {
+        acc += bf2f(((const uint16_t*)rep[i])[e]);
+        if (a.clear_inputs) ((uint16_t*)rep[i])[e] = 0;
+      }
+      out[e] = (uint16_t)f2bf(acc);
+    } else {
+      float* out = (float*)a.one[g];
+      float acc = a.accumulate ? out[e] : 0.f;
+      for (int i = 0; i < k; ++i) {
+        acc += ((const float*)rep[i])[e];
+        if (a.clear_inputs) ((float*)rep[i])[e] = 0.f;
+      }
+      out[e] = acc;
+    }
+  }
+}
+
+static unsigned blocks_for(int64_t max_count, int vec) {
+  int64_t units = (max_count + vec - 1) / vec;
+  int64_t b = (units + kCollThreads * 4 - 1) / (kCollThreads * 4);  // ~4 units per thread
+  if (b < 1) b = 1;
+  if (b > 4096) b = 4096;
+  return (unsigned)b;
+}
+
+// Shared driver: reduce == false is the broadcast direction.
+static int run_collective(bool reduce, void* const one[], void* const many[], const int64_t count[], int G, int k,
+                          distdl_dtype dtype, int clear_inputs, hipStream_t st) {
+  if (!one || !many || !count) return set_error(DISTDL_ERR_NULL, "collective: null argument");
+  if (G < 1 || k < 1) return set_error(DISTDL_ERR_INVALID_ARG, "collective: G = %d, k = %d", G, k);
+  if (dtype != DISTDL_F32 && dtype != DISTDL_BF16) return set_error(DISTDL_ERR_UNSUPPORTED, "unknown dtype");
+  const size_t esz = dtype_size(dtype);
+  for (int g = 0; g < G; ++g) {
+    if (count[g] < 0) return set_error(DISTDL_ERR_INVALID_ARG, "group %d: negative count", g);
+    if (count[g] == 0) continue;
+    if (!one[g] || (uintptr_t)one[g] % esz) return set_error(DISTDL_ERR_NULL, "group %d: null or misaligned array", g);
+    for (int i = 0; i < k; ++i)
+      if (!many[(size_t)g * k + i] || (uintptr_t)many[(size_t)g * k + i] % esz)
+        return set_error(DISTDL_ERR_NULL, "group %d replica %d: null or misaligned array", g, i);
+  }
+  const int vec = dtype == DISTDL_F32 ? 4 : 8;
+  // replicas are consumed in chunks of at most kMaxPtrs; chunk c of every
+  // group runs after chunk c-1 (stream order), which keeps the summation order
+  for (int i0 = 0; i0 < k; i0 += kMaxPtrs) {
+    const int kc = std::min(kMaxPtrs, k - i0);
+    const int groups_per_launch = std::max(1, std::min(kMaxGroups, kMaxPtrs / kc));
+    for (int g0 = 0; g0 < G; g0 += groups_per_launch) {
+      CollArgs a{};
+      int ng = 0, np = 0;
+      int64_t max_count = 0;
+      for (int g = g0; g < std::min(G, g0 + groups_per_launch); ++g) {
+        if (count[g] == 0) continue;
+        a.one[ng] = one[g];
+        a.count[ng] = count[g];
+        a.first[ng] = np;
+        a.k[ng] = kc;
+        bool wide = (uintptr_t)one[g] % 16 == 0;
+        for (int i = 0; i < kc; ++i) {
+          a.many[np] = many[(size_t)g * k + i0 + i];
+          wide &= (uintptr_t)a.many[np] % 16 == 0;
+          ++np;
+        }
+        a.wide[ng] = wide;
+        max_count = std::max(max_count, count[g]);
+        ++ng;
+      }
+      if (ng == 0) continue;
+      a.accumulate = i0 > 0;
+      a.clear_inputs = clear_inputs;
+      dim3 grid(blocks_for(max_count, vec), ng), block(kCollThreads);
+      if (reduce) {
+        if (dtype == DISTDL_F32) hipLaunchKernelGGL(reduce_kernel<false>, grid, block, 0, st, a);
+        else hipLaunchKernelGGL(reduce_kernel<true>, grid, block, 0, st, a);
+      } else {
+        if (dtype == DISTDL_F32) hipLaunchKernelGGL(bcast_kernel<false>, grid, block, 0, st, a);
+        else hipLaunchKernelGGL(bcast_kernel<true>, grid, block, 0, st, a);
+      }
+    }
+  }
+  DISTDL_HIP_TRY(hipGetLastError());
+  return DISTDL_OK;
+}
+
+// ---- inner product ----------------------------------------------------------
+constexpr int kDotBlocks = 1024;
+constexpr int kDotArrays = 24;
+struct DotArgs {
+  const void* a[kDotArrays];
+  const void* b[kDotArrays];
+  int64_t count[kDotArrays];
+  int32_t n;
+  int32_t accumulate;
+};
+
+__device__ inline double wave_sum(double v) {
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off, 64);
+  return v;
+}
+
+template <bool BF16>
+__global__ __launch_bounds__(256) void dot_partial_kernel(DotArgs d, double* partial) {
+  double acc = 0.0;
+  const int64_t stride = (int64_t)gridDim.x * 256;
+  for (int j = 0; j < d.n; ++j) {
+    for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < d.count[j]; e += stride) {
+      double x, y;
+      if (BF16) {
+        x = bf2f(((const uint16_t*)d.a[j])[e]);
+        y = bf2f(((const uint16_t*)d.b[j])[e]);
+      } else {
+        x = ((const float*)d.a[j])[e];
+        y = ((const float*)d.b[j])[e];
+      }
+      acc += x * y;
+    }
+  }
+  __shared__ double red[4];
+  acc = wave_sum(acc);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = acc;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    double s = red[0] + red[1] + red[2] + red[3];
+    partial[blockIdx.x] = d.accumulate ? partial[blockIdx.x] + s : s;
+  }
+}
+
+__global__ __launch_bounds__(256) void dot_final_kernel(const double* partial, int n, double* out) {
+  double acc = 0.0;
+  for (int i = threadIdx.x; i < n; i += 256) acc += partial[i];
+  __shared__ double red[4];
+  acc = wave_sum(acc);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = acc;
+  __syncthreads();
+  if (threadIdx.x == 0) *out = red[0] + red[1] + red[2] + red[3];
+}
+
+static double* g_dot_partial[64] = {};
+
+}  // namespace distdl
+
+using namespace distdl;
+
+extern "C" {
+
+int distdl_bcast_fwd(const void* const src_dev[], void* const dst_dev[], const int64_t count[], int G, int k,
+                     distdl_dtype dtype, void* stream) {
+  return run_collective(false, (void* const*)src_dev, dst_dev, count, G, k, dtype, 0, (hipStream_t)stream);
+}
+
+int distdl_sumreduce_adj(const void* const gdst_dev[], void* const gsrc_dev[], const int64_t count[], int G, int k,
+                         distdl_dtype dtype, void* stream) {
+  return run_collective(false, (void* const*)gdst_dev, gsrc_dev, count, G, k, dtype, 0, (hipStream_t)stream);
+}
+
+int distdl_bcast_adj(void* const gsrc_dev[], void* const gdst_dev[], const int64_t count[], int G, int k,
+                     distdl_dtype dtype, int clear_inputs, void* stream) {
+  return run_collective(true, gsrc_dev, gdst_dev, count, G, k, dtype, clear_inputs, (hipStream_t)stream);
+}
+
+int distdl_sumreduce_fwd(void* const src_dev[], void* const dst_dev[], const int64_t count[], int G, int k,
+                         distdl_dtype dtype, int clear_inputs, void* stream) {
+  return run_collective(true, dst_dev, src_dev, count, G, k, dtype, clear_inputs, (hipStream_t)stream);
+}
+
+int distdl_dot(const void* const a_dev[], const void* const b_dev[], const int64_t count[], int n_arrays,
+               distdl_dtype dtype, double* result_dev, void* stream) {
+  if (!a_dev || !b_dev || !count || !result_dev) return set_error(DISTDL_ERR_NULL, "dot: null argument");
+  if (n_arrays < 1) return set_error(DISTDL_ERR_INVALID_ARG, "dot: n_arrays = %d", n_arrays);
+  if (dtype != DISTDL_F32 && dtype != DISTDL_BF16) return set_error(DISTDL_ERR_UNSUPPORTED, "unknown dtype");
+  hipStream_t st = (hipStream_t)stream;
+  int dev = 0;
+  DISTDL_HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= 64) return set_error(DISTDL_ERR_UNSUPPORTED, "device index %d", dev);
+  if (!g_dot_partial[dev]) DISTDL_HIP_TRY(hipMalloc((void**)&g_dot_partial[dev], kDotBlocks * sizeof(double)));
+  for (int j0 = 0; j0 < n_arrays; j0 += kDotArrays) {
+    DotArgs d{};
+    d.n = std::min(kDotArrays, n_arrays - j0);
+    d.accumulate = j0 > 0;
+    for (int j = 0; j < d.n; ++j) {
+      if (count[j0 + j] < 0) return set_error(DISTDL_ERR_INVALID_ARG, "dot: negative count");
+      if (count[j0 + j] > 0 && (!a_dev[j0 + j] || !b_dev[j0 + j])) return set_error(DISTDL_ERR_NULL, "dot: null array");
+      d.a[j] = a_dev[j0 + j];
+      d.b[j] = b_dev[j0 + j];
+      d.count[j] = count[j0 + j];
+    }
+    if (dtype == DISTDL_F32)
+      hipLaunchKernelGGL(dot_partial_kernel<false>, dim3(kDotBlocks), dim3(256), 0, st, d, g_dot_partial[dev]);
+    else
+      hipLaunchKernelGGL(dot_partial_kernel<true>, dim3(kDotBlocks), dim3(256), 0, st, d, g_dot_partial[dev]);
+  }
+  hipLaunchKernelGGL(dot_final_kernel, dim3(1), dim3(256), 0, st, g_dot_partial[dev], kDotBlocks, result_dev);
+  DISTDL_HIP_TRY(hipGetLastError());
+  return DISTDL_OK;
+}
+
+}  // extern "C"

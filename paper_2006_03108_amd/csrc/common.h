@@ -1,0 +1,153 @@
+// Internal declarations shared by the translation units of libdistdl.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstdarg>
+#include <cstdint>
+#include <cstdio>
+#include <vector>
+
+#include "distdl.h"
+
+namespace distdl {
+
+// ---- error reporting ------------------------------------------------------
+int set_error(int code, const char* fmt, ...);
+#define DISTDL_HIP_TRY(expr)                                                                  \
+  do {                                                                                        \
+    hipError_t e__ = (expr);                                                                  \
+    if (e__ != hipSuccess)                                                                    \
+      return ::distdl::set_error(DISTDL_ERR_HIP, "%s failed: %s", #expr, hipGetErrorString(e__)); \
+  } while (0)
+
+inline size_t dtype_size(distdl_dtype t) { return t == DISTDL_F32 ? 4 : 2; }
+
+// ---- exact unsigned division by a runtime constant ------------------------
+// Granlund & Montgomery, "Division by invariant integers using
+// multiplication" (PLDI 1994), unsigned round-up variant:
+//   l = ceil(log2 d), m' = floor(2^32 (2^l - d) / d) + 1,
+//   t = mulhi(m', n), q = (t + ((n - t) >> min(l,1))) >> max(l-1,0).
+struct FastDiv {
+  uint32_t mul, sh1, sh2, d;
+};
+inline FastDiv make_fastdiv(uint32_t d) {
+  FastDiv f;
+  f.d = d;
+  uint32_t l = 0;
+  while ((uint64_t(1) << l) < d) ++l;
+  f.mul = uint32_t(((uint64_t(1) << 32) * ((uint64_t(1) << l) - d)) / d + 1);
+  f.sh1 = l < 1 ? l : 1;
+  f.sh2 = l > 0 ? l - 1 : 0;
+  return f;
+}
+__host__ __device__ inline uint32_t fd_div(uint32_t n, const FastDiv& f) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  uint32_t t = __umulhi(f.mul, n);
+#else
+  uint32_t t = uint32_t((uint64_t(f.mul) * n) >> 32);
+#endif
+  return (t + ((n - t) >> f.sh1)) >> f.sh2;
+}
+
+// ---- geometry -------------------------------------------------------------
+struct DimGeom {
+  int64_t in_start, in_size, out_start, out_size;
+  int32_t halo[2], pad[2], extra[2];
+  int64_t buf, bulk_off, origin;
+};
+
+// Per-worker geometry as the kernels read it (3 feature dims, leading dims of
+// extent 1 when D < 3).
+struct WorkerDev {
+  int32_t buf[3];     // buffer extent in cells
+  int32_t out[3];     // owned output extent
+  int32_t origin[3];  // buffer coordinate of the first tap of the first output
+  int32_t bulk_off[3];
+  int32_t in_size[3];
+  int32_t pad_;
+};
+
+// One source of a box task: the same box seen in another worker's buffer.
+struct BoxSrc {
+  int32_t worker;
+  int32_t org[3];
+};
+
+// A rectangular box of cells in one worker's buffer that is zero-filled
+// (nsrc == 0), copied from src[0] (halo forward) or that gathers its sources,
+// adds them and clears them (halo adjoint).
+struct BoxTask {
+  int32_t dst_worker;
+  int32_t nsrc;
+  int32_t src_begin;  // index into the flat BoxSrc array
+  int32_t org[3];     // origin in the destination buffer (cells)
+  int32_t ext[3];     // extent (cells)
+  FastDiv div_row;    // by ext[2] * C / V  (vector units per contiguous run)
+  FastDiv div_e1;     // by ext[1]
+  FastDiv div_e0;     // by ext[0]
+};
+
+struct BlockRef {
+  int32_t task;
+  uint32_t unit0;  // first vector unit of the task this block handles
+};
+
+struct TaskTable {
+  std::vector<BoxTask> tasks;
+  std::vector<BoxSrc> srcs;
+  std::vector<BlockRef> blocks;
+  BoxTask* d_tasks = nullptr;
+  BoxSrc* d_srcs = nullptr;
+  BlockRef* d_blocks = nullptr;
+  int vec = 1;  // elements per vector unit the tables were built for
+  int64_t cells_copied = 0, cells_zeroed = 0, cells_band = 0;
+};
+
+// A device copy of a caller's host pointer array, re-uploaded only when it
+// changes.
+struct PtrTable {
+  std::vector<const void*> host;
+  void** dev = nullptr;
+  size_t cap = 0;
+  hipStream_t last_stream = nullptr;
+  bool valid = false;
+  int upload(const void* const* ptrs, size_t n, hipStream_t stream);
+  void release();
+};
+
+}  // namespace distdl
+
+struct distdl_plan {
+  int D = 0;
+  int64_t n_b = 0, n_ci = 0, n_co = 0;
+  distdl_dtype dtype = DISTDL_F32;
+  bool explicit_halo = false;
+  int32_t P[3] = {1, 1, 1};
+  int32_t ksize[3] = {1, 1, 1}, stride[3] = {1, 1, 1}, padding[3] = {0, 0, 0}, dilation[3] = {1, 1, 1};
+  int64_t in_shape[3] = {1, 1, 1}, out_shape[3] = {1, 1, 1};
+  std::vector<distdl::DimGeom> dims[3];  // index d in [0, D)
+  int n_workers = 0;
+  int device = 0;
+
+  // device-side tables
+  distdl::WorkerDev* d_workers = nullptr;
+  std::vector<distdl::WorkerDev> workers;
+  distdl::TaskTable fwd16, fwd1, adj16, adj1;  // 16-byte-vector and scalar variants
+  distdl::PtrTable tab_x, tab_y, tab_dx, tab_dy;
+  int64_t max_out_cells = 0, max_buf_cells = 0;
+
+  // weight re-layout scratch for the convolution kernels (library-owned)
+  float* d_wt = nullptr;
+  size_t wt_elems = 0;
+
+  int coords(int w, int d) const {
+    int c[3];
+    int t = w;
+    for (int k = 2; k >= 0; --k) {
+      c[k] = t % P[k];
+      t /= P[k];
+    }
+    return c[d];
+  }
+};

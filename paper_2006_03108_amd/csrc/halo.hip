@@ -1,0 +1,233 @@
+// Halo exchange H and adjoint H* (Sec. 3 "Halo exchange") as one-pass box
+// kernels over all workers, dimensions, faces, edges and corners.
+//
+// The nested per-dimension exchange of the paper leaves every in-domain
+// non-owned cell equal to its owner's bulk value; since all partitions share
+// one address space that end state is written directly: each box of halo
+// cells is one strided copy from the owner's buffer (pack + exchange + unpack
+// collapsed, exchange buffers never materialised), each box of padding cells
+// a zero fill.  The adjoint runs in gather form: the thread that owns a bulk
+// cell reads every halo copy of it (fixed ascending worker order), adds them
+// and clears them -- the "add into the bulk" of C* = K_b S_{b->a} without
+// atomics, so results are run-to-run identical.
+#include "common.h"
+
+namespace distdl {
+
+extern const int kHaloUnitsPerBlock = 1024;  // 256 threads x 4 vector units
+constexpr int kThreads = 256;
+constexpr int kUnroll = 4;
+
+// ---- element helpers --------------------------------------------------------
+__device__ inline float bf16_to_f32(uint32_t h) { return __uint_as_float(h << 16); }
+__device__ inline uint32_t f32_to_bf16(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;  // quiet NaN
+  u += 0x7fffu + ((u >> 16) & 1u);                                // round to nearest even
+  return u >> 16;
+}
+
+struct F32x4 {
+  using Store = float4;
+  static constexpr int N = 4;
+  __device__ static void unpack(const Store& s, float* a) { a[0] = s.x; a[1] = s.y; a[2] = s.z; a[3] = s.w; }
+  __device__ static Store pack(const float* a) { return make_float4(a[0], a[1], a[2], a[3]); }
+  __device__ static Store zero() { return make_float4(0.f, 0.f, 0.f, 0.f); }
+};
+struct F32x1 {
+  using Store = float;
+  static constexpr int N = 1;
+  __device__ static void unpack(const Store& s, float* a) { a[0] = s; }
+  __device__ static Store pack(const float* a) { return a[0]; }
+  __device__ static Store zero() { return 0.f; }
+};
+struct BF16x8 {
+  using Store = uint4;
+  static constexpr int N = 8;
+  __device__ static void unpack(const Store& s, float* a) {
+    const uint32_t w[4] = {s.x, s.y, s.z, s.w};
+    for (int i = 0; i < 4; ++i) {
+      a[2 * i] = bf16_to_f32(w[i] & 0xffffu);
+      a[2 * i + 1] = bf16_to_f32(w[i] >> 16);
+    }
+  }
+  __device__ static Store pack(const float* a) {
+    uint32_t w[4];
+    for (int i = 0; i < 4; ++i) w[i] = f32_to_bf16(a[2 * i]) | (f32_to_bf16(a[2 * i + 1]) << 16);
+    return make_uint4(w[0], w[1], w[2], w[3]);
+  }
+  __device__ static Store zero() { return make_uint4(0, 0, 0, 0); }
+};
+struct BF16x1 {
+  using Store = uint16_t;
+  static constexpr int N = 1;
+  __device__ static void unpack(const Store& s, float* a) { a[0] = bf16_to_f32(s); }
+  __device__ static Store pack(const float* a) { return (uint16_t)f32_to_bf16(a[0]); }
+  __device__ static Store zero() { return 0; }
+};
+
+// Offset (in vector units) of cell (n, c0, c1) + origin in a worker's buffer;
+// cv = vector units per cell.
+__device__ inline size_t box_offset(const WorkerDev& w, const int32_t org[3], uint32_t n, uint32_t c0, uint32_t c1,
+                                    uint32_t cv) {
+  uint32_t s1 = (uint32_t)w.buf[2] * cv;
+  uint32_t s0 = (uint32_t)w.buf[1] * s1;
+  size_t sn = (size_t)w.buf[0] * s0;
+  return n * sn + (size_t)((org[0] + c0) * s0 + (org[1] + c1) * s1 + org[2] * cv);
+}
+
+struct UnitPos {
+  uint32_t n, c0, c1, col;
+};
+__device__ inline UnitPos decode(uint32_t u, const BoxTask& t) {
+  UnitPos p;
+  uint32_t row = fd_div(u, t.div_row);
+  p.col = u - row * t.div_row.d;
+  uint32_t r1 = fd_div(row, t.div_e1);
+  p.c1 = row - r1 * t.div_e1.d;
+  p.n = fd_div(r1, t.div_e0);
+  p.c0 = r1 - p.n * t.div_e0.d;
+  return p;
+}
+
+// Forward: copy boxes (nsrc == 1) and zero boxes (nsrc == 0).
+template <class E>
+__global__ __launch_bounds__(kThreads) void halo_fwd_kernel(const BlockRef* __restrict__ blocks,
+                                                            const BoxTask* __restrict__ tasks,
+                                                            const BoxSrc* __restrict__ srcs,
+                                                            const WorkerDev* __restrict__ workers, void* const* bufs,
+                                                            uint32_t n_b, uint32_t cv) {
+  using S = typename E::Store;
+  const BlockRef br = blocks[blockIdx.x];
+  const BoxTask& t = tasks[br.task];
+  const uint32_t total = n_b * (uint32_t)t.ext[0] * (uint32_t)t.ext[1] * t.div_row.d;
+  const WorkerDev& wd = workers[t.dst_worker];
+  S* __restrict__ dst = (S*)bufs[t.dst_worker];
+  S vals[kUnroll];
+  size_t doff[kUnroll];
+  bool live[kUnroll];
+  if (t.nsrc == 0) {
+#pragma unroll
+    for (int i = 0; i < kUnroll; ++i) {
+      uint32_t u = br.unit0 + threadIdx.x + i * kThreads;
+      if (u < total) {
+        UnitPos p = decode(u, t);
+        dst[box_offset(wd, t.org, p.n, p.c0, p.c1, cv) + p.col] = E::zero();
+      }
+    }
+    return;
+  }
+  const BoxSrc& sr = srcs[t.src_begin];
+  const WorkerDev& ws = workers[sr.worker];
+  const S* __restrict__ src = (const S*)bufs[sr.worker];
+#pragma unroll
+  for (int i = 0; i < kUnroll; ++i) {
+    uint32_t u = br.unit0 + threadIdx.x + i * kThreads;
+    live[i] = u < total;
+    if (live[i]) {
+      UnitPos p = decode(u, t);
+      doff[i] = box_offset(wd, t.org, p.n, p.c0, p.c1, cv) + p.col;
+      vals[i] = src[box_offset(ws, sr.org, p.n, p.c0, p.c1, cv) + p.col];
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < kUnroll; ++i)
+    if (live[i]) dst[doff[i]] = vals[i];
+}
+
+// Adjoint: bulk boxes gather-add their halo copies and clear them; padding
+// boxes are cleared.
+template <class E>
+__global__ __launch_bounds__(kThreads) void halo_adj_kernel(const BlockRef* __restrict__ blocks,
+                                                            const BoxTask* __restrict__ tasks,
+                                                            const BoxSrc* __restrict__ srcs,
+                                                            const WorkerDev* __restrict__ workers, void* const* bufs,
+                                                            uint32_t n_b, uint32_t cv) {
+  using S = typename E::Store;
+  const BlockRef br = blocks[blockIdx.x];
+  const BoxTask& t = tasks[br.task];
+  const uint32_t total = n_b * (uint32_t)t.ext[0] * (uint32_t)t.ext[1] * t.div_row.d;
+  const WorkerDev& wd = workers[t.dst_worker];
+  S* dst = (S*)bufs[t.dst_worker];
+#pragma unroll
+  for (int i = 0; i < kUnroll; ++i) {
+    uint32_t u = br.unit0 + threadIdx.x + i * kThreads;
+    if (u >= total) continue;
+    UnitPos p = decode(u, t);
+    size_t d = box_offset(wd, t.org, p.n, p.c0, p.c1, cv) + p.col;
+    if (t.nsrc == 0) {
+      dst[d] = E::zero();
+      continue;
+    }
+    float acc[E::N], v[E::N];
+    E::unpack(dst[d], acc);
+    for (int s = 0; s < t.nsrc; ++s) {  // ascending source-worker order
+      const BoxSrc& sr = srcs[t.src_begin + s];
+      S* src = (S*)bufs[sr.worker];
+      size_t o = box_offset(workers[sr.worker], sr.org, p.n, p.c0, p.c1, cv) + p.col;
+      E::unpack(src[o], v);
+      src[o] = E::zero();
+#pragma unroll
+      for (int e = 0; e < E::N; ++e) acc[e] += v[e];
+    }
+    dst[d] = E::pack(acc);
+  }
+}
+
+int plan_prepare_device(distdl_plan* p);
+
+template <class E>
+static void launch(bool adjoint, const TaskTable& tt, const distdl_plan* p, void* const* bufs, hipStream_t st) {
+  dim3 grid((unsigned)tt.blocks.size()), block(kThreads);
+  uint32_t cv = (uint32_t)(p->n_ci / E::N);
+  if (adjoint)
+    hipLaunchKernelGGL(halo_adj_kernel<E>, grid, block, 0, st, tt.d_blocks, tt.d_tasks, tt.d_srcs, p->d_workers, bufs,
+                       (uint32_t)p->n_b, cv);
+  else
+    hipLaunchKernelGGL(halo_fwd_kernel<E>, grid, block, 0, st, tt.d_blocks, tt.d_tasks, tt.d_srcs, p->d_workers, bufs,
+                       (uint32_t)p->n_b, cv);
+}
+
+// Shared by the public halo calls and by conv_fwd / conv_bwd.
+int run_halo(distdl_plan* p, bool adjoint, PtrTable& tab, void* const* bufs_host, hipStream_t st) {
+  int rc = plan_prepare_device(p);
+  if (rc) return rc;
+  const size_t esz = dtype_size(p->dtype);
+  bool aligned16 = true;
+  for (int w = 0; w < p->n_workers; ++w) {
+    if (!bufs_host[w]) return set_error(DISTDL_ERR_NULL, "buffer of worker %d is null", w);
+    if ((uintptr_t)bufs_host[w] % esz) return set_error(DISTDL_ERR_INVALID_ARG, "buffer of worker %d is misaligned", w);
+    aligned16 &= ((uintptr_t)bufs_host[w] % 16) == 0;
+  }
+  const bool wide = aligned16 && !p->fwd16.tasks.empty();
+  const TaskTable& tt = adjoint ? (wide ? p->adj16 : p->adj1) : (wide ? p->fwd16 : p->fwd1);
+  if (tt.blocks.empty()) return DISTDL_OK;  // a single worker with no padding: H is the identity
+  if ((rc = tab.upload((const void* const*)bufs_host, p->n_workers, st))) return rc;
+  if (p->dtype == DISTDL_F32) {
+    if (wide) launch<F32x4>(adjoint, tt, p, tab.dev, st);
+    else launch<F32x1>(adjoint, tt, p, tab.dev, st);
+  } else {
+    if (wide) launch<BF16x8>(adjoint, tt, p, tab.dev, st);
+    else launch<BF16x1>(adjoint, tt, p, tab.dev, st);
+  }
+  DISTDL_HIP_TRY(hipGetLastError());
+  return DISTDL_OK;
+}
+
+}  // namespace distdl
+
+using namespace distdl;
+
+extern "C" {
+
+int distdl_halo_fwd(distdl_plan* plan, void* const bufs_dev[], void* stream) {
+  if (!plan || !bufs_dev) return set_error(DISTDL_ERR_NULL, "halo_fwd: null argument");
+  return run_halo(plan, false, plan->tab_x, bufs_dev, (hipStream_t)stream);
+}
+
+int distdl_halo_adj(distdl_plan* plan, void* const gbufs_dev[], void* stream) {
+  if (!plan || !gbufs_dev) return set_error(DISTDL_ERR_NULL, "halo_adj: null argument");
+  return run_halo(plan, true, plan->tab_dx, gbufs_dev, (hipStream_t)stream);
+}
+
+}  // extern "C"

@@ -1,0 +1,210 @@
+"""GPU parity of the data-movement primitives against the CPU oracle, through
+the C ABI: halo exchange H (bit-exact) and H* (rel 1e-5), broadcast
+(bit-exact), sum-reduce (rel 1e-5 fp32 / 2e-2 bf16), the adjoint test on the
+device results, edge cases."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2006_03108_amd as dd
+import synthetic_inputs as syn
+from oracle import geometry as geo
+from oracle import primitives as prim
+from tests.gpu_util import assert_close, from_cl, require_gpu, to_cl
+
+pytestmark = pytest.mark.gpu
+TOL32, TOL16 = 1e-5, 2e-2
+
+HALO_CASES = [
+    # name, D, n_b, n_c, in_shape, P, k, s, p, dil
+    ("cfg1", 1, 1, 1, (64,), (4,), (3,), (1,), (1,), (1,)),
+    ("cfg2", 2, 8, 16, (256, 256), (2, 2), (3, 3), (1, 1), (1, 1), (1, 1)),
+    ("cfg5-small", 3, 1, 32, (40, 40, 40), (4, 4, 4), (5, 5, 5), (2, 2, 2), (2, 2, 2), (1, 1, 1)),
+    ("cfg5u-small", 3, 1, 32, (38, 41, 43), (4, 4, 4), (5, 5, 5), (2, 2, 2), (2, 2, 2), (1, 1, 1)),
+    ("ragged-c3", 2, 3, 3, (17, 23), (3, 2), (5, 3), (1, 2), (2, 0), (1, 2)),
+    ("pad+halo", 1, 2, 4, (4,), (2,), (7,), (1,), (3,), (1,)),
+    ("pool", 2, 2, 8, (10, 20), (3, 6), (2, 2), (2, 2), (0, 0), (1, 1)),
+    ("single", 2, 1, 4, (9, 9), (1, 1), (3, 3), (1, 1), (1, 1), (1, 1)),
+    ("both-sides", 2, 1, 8, (9, 9), (3, 3), (5, 5), (1, 1), (2, 2), (1, 1)),
+]
+
+
+def _setup(case, dtype):
+    name, D, n_b, n_c, n, P, k, s, p, dil = case
+    part = geo.Partition.for_kernel(n, P, k, s, p, dil)
+    plan = dd.distdl_plan_create(D, n_b, n_c, n_c, n, P, k, s, p, dil, dtype)
+    return part, plan
+
+
+@pytest.mark.parametrize("case", HALO_CASES, ids=[c[0] for c in HALO_CASES])
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
+def test_halo_fwd_bit_exact(case, dtype):
+    require_gpu()
+    part, plan = _setup(case, dtype)
+    name, D, n_b, n_c, n = case[:5]
+    rng = syn.streams(11, 1)[0]
+    xg = syn.normal(rng, (n_b, n_c) + tuple(n))
+    if dtype == torch.bfloat16:
+        xg = syn.to_bf16_values(xg)
+    want = prim.halo_exchange(prim.scatter_bulk(xg, part, fill=np.float32(7.5)), part)
+    bufs = [to_cl(b, dtype) for b in prim.scatter_bulk(xg, part, fill=np.float32(-3.25))]
+    dd.distdl_halo_fwd(plan, bufs)
+    torch.cuda.synchronize()
+    for w in range(part.n_workers):
+        assert np.array_equal(from_cl(bufs[w]), want[w]), f"{name} worker {w}"
+
+
+@pytest.mark.parametrize("case", HALO_CASES, ids=[c[0] for c in HALO_CASES])
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
+def test_halo_adj_parity_and_adjoint_test(case, dtype):
+    require_gpu()
+    part, plan = _setup(case, dtype)
+    name, D, n_b, n_c = case[:4]
+    r = syn.streams(12, 2)
+    conv = syn.to_bf16_values if dtype == torch.bfloat16 else (lambda a: a)
+    x = [conv(syn.normal(r[0], (n_b, n_c) + part.buf_shape(w))) for w in range(part.n_workers)]
+    y = [conv(syn.normal(r[1], (n_b, n_c) + part.buf_shape(w))) for w in range(part.n_workers)]
+    want = prim.halo_exchange_adjoint([t.astype(np.float64) for t in y], part)
+    gy = [to_cl(t, dtype) for t in y]
+    dd.distdl_halo_adj(plan, gy)
+    torch.cuda.synchronize()
+    tol = TOL32 if dtype == torch.float32 else TOL16
+    for w in range(part.n_workers):
+        got = from_cl(gy[w])
+        assert_close(got, want[w], tol, f"{name} H* worker {w}")
+        mask = np.ones(part.buf_shape(w), dtype=bool)
+        mask[part.bulk_slices(w)] = False
+        assert not got[:, :, mask].any(), "halo / pad cells must end cleared"
+    if dtype == torch.float32 and part.n_workers > 1:
+        # adjoint test (Sec. 3 "Implementation") on device results, inner products on the device
+        gx = [to_cl(t) for t in x]
+        gx0 = [t.clone() for t in gx]
+        gy0 = [to_cl(t) for t in y]
+        dd.distdl_halo_fwd(plan, gx)
+        res = torch.zeros(6, dtype=torch.float64, device="cuda")
+        for i, (a, b) in enumerate([(gx, gy0), (gx0, gy), (gx, gx), (gy0, gy0), (gx0, gx0), (gy, gy)]):
+            dd.distdl_dot(a, b, res[i:i + 1])
+        torch.cuda.synchronize()
+        Fx_y, x_Fsy, Fx2, y2, x2, Fsy2 = res.cpu().tolist()
+        ratio = abs(Fx_y - x_Fsy) / max(np.sqrt(Fx2 * y2), np.sqrt(x2 * Fsy2))
+        assert ratio < TOL32, ratio
+        # the device inner product itself against the oracle's
+        assert abs(Fx_y - prim.inner([from_cl(t) for t in gx], y)) <= 1e-9 * np.sqrt(Fx2 * y2)
+
+
+def test_halo_adj_multiplicities_are_exact_integers():
+    require_gpu()
+    case = HALO_CASES[3]
+    part, plan = _setup(case, torch.float32)
+    ones = [torch.ones((1,) + part.buf_shape(w) + (32,), device="cuda") for w in range(part.n_workers)]
+    dd.distdl_halo_adj(plan, ones)
+    want = prim.halo_exchange_adjoint([np.ones((1, 32) + part.buf_shape(w)) for w in range(part.n_workers)], part)
+    torch.cuda.synchronize()
+    for w in range(part.n_workers):
+        assert np.array_equal(from_cl(ones[w]), want[w])
+    assert max(t.max().item() for t in ones) == 8.0
+
+
+def test_halo_run_to_run_deterministic_and_unaligned():
+    require_gpu()
+    case = HALO_CASES[4]
+    part, plan = _setup(case, torch.float32)
+    r = syn.streams(5, 1)[0]
+    y = [syn.normal(r, (3, 3) + part.buf_shape(w)) for w in range(part.n_workers)]
+    outs = []
+    for rep in range(2):
+        g = [to_cl(t) for t in y]
+        dd.distdl_halo_adj(plan, g)
+        torch.cuda.synchronize()
+        outs.append([t.cpu().numpy() for t in g])
+    for a, b in zip(*outs):
+        assert np.array_equal(a, b)
+    # buffers at 4-byte (not 16-byte) aligned addresses take the scalar path
+    n_c = 4
+    case = ("u", 2, 1, n_c, (12, 12), (2, 2), (3, 3), (1, 1), (1, 1), (1, 1))
+    part, plan = _setup(case, torch.float32)
+    xg = syn.normal(r, (1, n_c, 12, 12))
+    want = prim.halo_exchange(prim.scatter_bulk(xg, part, fill=np.float32(1.0)), part)
+    bufs = []
+    for b in prim.scatter_bulk(xg, part, fill=np.float32(2.0)):
+        flat = torch.zeros(b.size + 1, device="cuda")
+        view = flat[1:].view((1,) + b.shape[2:] + (n_c,))
+        view.copy_(to_cl(b))
+        assert view.data_ptr() % 16 == 4
+        bufs.append(view)
+    dd.distdl_halo_fwd(plan, bufs)
+    torch.cuda.synchronize()
+    for w in range(4):
+        assert np.array_equal(from_cl(bufs[w]), want[w])
+
+
+# ---------------------------------------------------------------- broadcast / sum-reduce
+COLL_CASES = [(16, 4, 1), (1, 1, 1), (5, 3, 2), (4099, 2, 3), (256 * 2048, 2, 2), (1000, 64, 1), (37, 100, 1),
+              (9 * 1024, 4, 16)]
+
+
+@pytest.mark.parametrize("count,k,G", COLL_CASES)
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
+def test_broadcast_and_sumreduce(count, k, G, dtype):
+    require_gpu()
+    case = syn.vector_case(0, count, k, G)
+    conv = syn.to_bf16_values if dtype == torch.bfloat16 else (lambda a: a)
+    src = [conv(t) for t in case["src"]]
+    reps = [conv(t) for t in case["reps"]]
+    tol = TOL32 if dtype == torch.float32 else TOL16
+    g_src = [torch.from_numpy(t).to(dtype).cuda() for t in src]
+    g_dst = [torch.full((count,), 9.0, dtype=dtype, device="cuda") for _ in range(G * k)]
+    dd.distdl_bcast_fwd(g_src, g_dst, k)
+    torch.cuda.synchronize()
+    for g in range(G):
+        want = prim.broadcast(src[g], k)
+        for i in range(k):
+            assert np.array_equal(g_dst[g * k + i].float().cpu().numpy(), want[i])
+    # B* (= R): sum in index order
+    g_rep = [torch.from_numpy(t).to(dtype).cuda() for t in reps]
+    g_out = [torch.full((count,), 5.0, dtype=dtype, device="cuda") for _ in range(G)]
+    dd.distdl_bcast_adj(g_out, g_rep, k, clear_inputs=False)
+    g_out2 = [torch.full((count,), 5.0, dtype=dtype, device="cuda") for _ in range(G)]
+    dd.distdl_sumreduce_fwd(g_rep, g_out2, k, clear_inputs=True)
+    torch.cuda.synchronize()
+    for g in range(G):
+        want = prim.sum_reduce([reps[g * k + i] for i in range(k)])
+        assert_close(g_out[g].float().cpu().numpy(), want, tol, "B*")
+        assert np.array_equal(g_out[g].float().cpu().numpy(), g_out2[g].float().cpu().numpy())
+    assert all(not t.any().item() for t in g_rep)          # K_i applied
+    # R* = B
+    g_back = [torch.empty(count, dtype=dtype, device="cuda") for _ in range(G * k)]
+    dd.distdl_sumreduce_adj(g_out, g_back, k)
+    torch.cuda.synchronize()
+    for g in range(G):
+        for i in range(k):
+            assert torch.equal(g_back[g * k + i], g_out[g])
+    if dtype == torch.float32:
+        # adjoint test <Bx, y> = <x, B*y>
+        Fx = [t.cpu().numpy() for t in g_dst]
+        Fsy = [t.cpu().numpy() for t in g_out]
+        assert prim.adjoint_test_ratio(Fx, reps, src, Fsy) < TOL32
+
+
+def test_sumreduce_integer_valued_is_exact_and_unaligned_pointers():
+    require_gpu()
+    k, count = 7, 1003
+    base = [torch.arange(count + 1, dtype=torch.float32, device="cuda") * (i + 1) for i in range(k)]
+    reps = [b[1:] for b in base]                        # 4-byte aligned only
+    out = torch.empty(count + 3, device="cuda")[3:]
+    dd.distdl_sumreduce_fwd(reps, [out], k)
+    torch.cuda.synchronize()
+    want = np.arange(1, count + 1, dtype=np.float64) * sum(range(1, k + 1))
+    assert np.array_equal(out.cpu().numpy(), want)
+
+
+def test_collective_errors():
+    require_gpu()
+    a = torch.zeros(4, device="cuda")
+    with pytest.raises(dd.DistdlError):
+        dd.distdl_bcast_fwd([a], [a], 0)
+    with pytest.raises(dd.DistdlError):
+        dd.distdl_bcast_fwd([a], [None], 1)
+    empty = torch.zeros(0, device="cuda")
+    dd.distdl_bcast_fwd([empty], [empty, empty], 2)     # empty input: no-op
+    torch.cuda.synchronize()
