@@ -1,0 +1,276 @@
+#!/usr/bin/env python3
+"""Benchmark of the partitioned-convolution hot path on one MI355X.
+
+One step = distdl_conv_fwd (halo exchange H + local convolution) followed by
+distdl_conv_bwd (local [dConv]* for dx and dw, sum-reduce of dw over the
+workers, adjoint halo exchange H*) on the volumetric configuration:
+fp32 [1, 32, 256^3] input, [32, 32, 5, 5, 5] weights, stride 2, padding 2,
+4 x 4 x 4 = 64 virtual workers.  Inputs are seeded synthetic N(0,1) tensors
+already resident in HBM when the timed region starts.
+
+Prints ONE JSON line (see the keys below).  `--workload cfg2|cfg3` times the
+other single-GPU configurations with the same harness.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_PEAK_TFLOPS = {"f32": 157.3, "bf16": 2500.0}
+
+
+def _dev_randn(shape, seed, std=1.0, dtype=None):
+    import torch
+    g = torch.Generator(device="cuda")
+    g.manual_seed(seed)
+    t = torch.randn(shape, generator=g, device="cuda", dtype=torch.float32)
+    if std != 1.0:
+        t *= std
+    return t if dtype is None else t.to(dtype)
+
+
+def _prod(v):
+    out = 1
+    for t in v:
+        out *= int(t)
+    return out
+
+
+class ConvWorkload:
+    """cfg5 / cfg2: partitioned convolution forward + backward."""
+
+    def __init__(self, name):
+        import torch
+        import paper_2006_03108_amd as dd
+        import synthetic_inputs as syn
+        self.dd, self.torch, self.name = dd, torch, name
+        c = self.cfg = dict(syn.CONFIGS[name])
+        self.plan = dd.distdl_plan_create(c["D"], c["n_b"], c["c_in"], c["c_out"], c["in_shape"], c["P"], c["ksize"],
+                                          c["stride"], c["padding"], c["dilation"])
+        P = self.plan.n_workers
+        geoms = [self.plan.query(w) for w in range(P)]
+        self.out_global = [max(g["out_start"][d] + g["out_size"][d] for g in geoms) for d in range(c["D"])]
+        taps = _prod(c["ksize"])
+        w_std = syn.he_normal_std((c["c_out"], c["c_in"]) + tuple(c["ksize"]))
+        # channels-last device buffers; bulk = N(0,1), halo / pad cells start as noise and are overwritten by H
+        self.x = [_dev_randn([c["n_b"]] + g["buf_shape"] + [c["c_in"]], 1000 + w) for w, g in enumerate(geoms)]
+        self.dy = [_dev_randn([c["n_b"]] + g["out_size"] + [c["c_out"]], 2000 + w) for w, g in enumerate(geoms)]
+        self.y = [torch.empty_like(t) for t in self.dy]
+        self.dx = [torch.empty_like(t) for t in self.x]
+        self.w = _dev_randn((c["c_out"], c["c_in"]) + tuple(c["ksize"]), 7, std=w_std)
+        self.dw = torch.empty_like(self.w)
+        self.ws = torch.empty(max(dd.distdl_conv_bwd_workspace(self.plan), 16), dtype=torch.uint8, device="cuda")
+        stats = dd.distdl_plan_stats(self.plan)
+        esz = 4
+        per_cell = c["n_b"] * c["c_in"] * esz
+        self.flops_fwd = 2.0 * c["n_b"] * c["c_out"] * c["c_in"] * taps * _prod(self.out_global)
+        self.flops_step = 3.0 * self.flops_fwd
+        nw = taps * c["c_in"] * c["c_out"]
+        self.alg = {   # algorithmic bytes or flops per launch, by kernel-name prefix
+            "halo_fwd": ("hbm", (2 * stats["halo_cells"] + stats["pad_cells"]) * per_cell),
+            "halo_adj": ("hbm", (2 * stats["halo_cells"] + 2 * stats["band_cells"] + stats["pad_cells"]) * per_cell),
+            "conv_fwd": ("mfma", self.flops_fwd),
+            "conv_bwd_data": ("mfma", self.flops_fwd),
+            "conv_bwd_weight": ("mfma", self.flops_fwd),
+            "conv_reduce_dw": ("hbm", None),     # filled from the workspace geometry below
+            "conv_relayout_w": ("hbm", 2 * nw * esz),
+        }
+        self.nw = nw
+        self.metric = "partitioned conv fwd+bwd TFLOP/s (halo exchange H, H* and dw sum-reduce included)"
+        self.unit = "TFLOP/s"
+        self.dtype = "f32"
+        self.describe = {"workload": f"{name}: conv{c['D']}d fwd+bwd fp32 x[{c['n_b']},{c['c_in']}," +
+                         ",".join(str(v) for v in c["in_shape"]) + f"] w[{c['c_out']},{c['c_in']}," +
+                         ",".join(str(v) for v in c["ksize"]) + f"] stride {c['stride'][0]} pad {c['padding'][0]}, " +
+                         "P=" + "x".join(str(v) for v in c["P"]) + f" ({P} virtual workers), channels-last",
+                         "halo_cells": stats["halo_cells"], "pad_cells": stats["pad_cells"],
+                         "band_cells": stats["band_cells"]}
+
+    def step(self):
+        dd = self.dd
+        dd.distdl_conv_fwd(self.plan, self.x, self.w, None, self.y)
+        dd.distdl_conv_bwd(self.plan, self.x, self.w, self.dy, self.dx, self.dw, None, self.ws)
+
+    def value(self, seconds_per_step):
+        return self.flops_step / seconds_per_step / 1e12
+
+    def cpu_baseline(self):
+        """The oracle's distributed conv forward + adjoint on a bounded sample
+        of the same workload: the same channels, kernel and stride on a 64^3
+        (cfg5) or 96^2, batch 2 (cfg2) input over 2 workers per dimension."""
+        import synthetic_inputs as syn
+        from oracle import geometry as geo, layers, primitives as prim
+        c = dict(self.cfg)
+        if c["D"] == 3:
+            c.update(in_shape=(64, 64, 64), P=(2, 2, 2))
+        else:
+            c.update(in_shape=(96, 96), n_b=2)
+        part = geo.Partition.for_kernel(c["in_shape"], c["P"], c["ksize"], c["stride"], c["padding"], c["dilation"])
+        case = syn.conv_case(c, part.global_out_shape())
+        t0 = time.perf_counter()
+        bufs = prim.scatter_bulk(case["x"].astype(np.float64), part)
+        layers.dist_conv_forward(bufs, case["w"], None, part, c["stride"], c["dilation"])
+        layers.dist_conv_adjoint(bufs, case["w"], prim.scatter_out(case["dy"], part), part, c["stride"],
+                                 c["dilation"], False)
+        dt = time.perf_counter() - t0
+        flops = 3 * 2.0 * c["n_b"] * c["c_out"] * c["c_in"] * _prod(c["ksize"]) * _prod(part.global_out_shape())
+        return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": 1, "kind": "oracle",
+                "sample": f"oracle dist_conv_forward+dist_conv_adjoint (numpy fp64, single thread) on x[{c['n_b']},"
+                          f"{c['c_in']}," + ",".join(str(v) for v in c["in_shape"]) + "], P=" +
+                          "x".join(str(v) for v in c["P"]) + f", {flops / 1e9:.2f} GFLOP in {dt:.1f} s"}
+
+
+class AffineWorkload:
+    """cfg3: distributed affine forward + backward (fp32 or bf16)."""
+
+    def __init__(self, name, dtype):
+        import torch
+        import paper_2006_03108_amd as dd
+        import synthetic_inputs as syn
+        self.dd, self.torch = dd, torch
+        c = self.cfg = dict(syn.CONFIGS["cfg3"])
+        td = torch.float32 if dtype == "f32" else torch.bfloat16
+        self.plan = dd.distdl_affine_plan_create(c["n_b"], c["n_fi"], c["n_fo"], c["P_fo"], c["P_fi"], td)
+        fo, fi = c["n_fo"] // c["P_fo"], c["n_fi"] // c["P_fi"]
+        bound = syn.xavier_uniform_bound(c["n_fo"], c["n_fi"])
+        self.x = [_dev_randn((c["n_b"], fi), 10 + j, dtype=td) for j in range(c["P_fi"])]
+        self.W = [((torch.rand((fo, fi), device="cuda", generator=torch.Generator(device="cuda").manual_seed(20 + k))
+                    * 2 - 1) * bound).to(td) for k in range(c["P_fo"] * c["P_fi"])]
+        self.b = [torch.zeros(fo, device="cuda", dtype=td) for _ in range(c["P_fo"])]
+        self.dy = [_dev_randn((c["n_b"], fo), 30 + i, dtype=td) for i in range(c["P_fo"])]
+        self.y = [torch.empty_like(t) for t in self.dy]
+        self.dx = [torch.empty_like(t) for t in self.x]
+        self.dW = [torch.empty_like(t) for t in self.W]
+        self.db = [torch.empty_like(t) for t in self.b]
+        self.flops_fwd = 2.0 * c["n_b"] * c["n_fi"] * c["n_fo"]
+        self.flops_step = 3.0 * self.flops_fwd
+        self.alg = {"affine_fwd": ("mfma", self.flops_fwd), "affine_bwd": ("mfma", 2 * self.flops_fwd)}
+        self.metric = "distributed affine fwd+bwd TFLOP/s (broadcast of x, sum-reduce over P_fi included)"
+        self.unit = "TFLOP/s"
+        self.dtype = dtype
+        self.describe = {"workload": f"cfg3: affine fwd+bwd {dtype} x[{c['n_b']},{c['n_fi']}] W[{c['n_fo']},{c['n_fi']}]"
+                                     f" on a {c['P_fo']}x{c['P_fi']} weight partition"}
+
+    def step(self):
+        self.dd.distdl_affine_fwd(self.plan, self.x, self.W, self.b, self.y)
+        self.dd.distdl_affine_bwd(self.plan, self.x, self.W, self.dy, self.dx, self.dW, self.db)
+
+    def value(self, seconds_per_step):
+        return self.flops_step / seconds_per_step / 1e12
+
+    def cpu_baseline(self):
+        import synthetic_inputs as syn
+        from oracle import layers
+        c = self.cfg
+        case = syn.affine_case(c)
+        rows, cols = layers.feature_blocks(c["n_fo"], c["P_fo"]), layers.feature_blocks(c["n_fi"], c["P_fi"])
+        x_parts = [case["x"][:, s] for s in cols]
+        W_parts = [[case["W"][r][:, s] for s in cols] for r in rows]
+        t0 = time.perf_counter()
+        layers.dist_affine_forward(x_parts, W_parts, [case["b"][r] for r in rows], c["P_fo"], c["P_fi"])
+        layers.dist_affine_adjoint(x_parts, W_parts, [case["dy"][:, r] for r in rows], c["P_fo"], c["P_fi"])
+        dt = time.perf_counter() - t0
+        import threadpoolctl
+        cores = max([p.get("num_threads", 1) for p in threadpoolctl.threadpool_info()] or [1])
+        return {"value": self.flops_step / dt / 1e12, "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
+                "sample": f"oracle dist_affine_forward+dist_affine_adjoint (numpy fp64 matmul) on the full cfg3 "
+                          f"shapes, {self.flops_step / 1e9:.1f} GFLOP in {dt:.1f} s"}
+
+
+def kernel_rooflines(workload, report, traffic):
+    """Per-kernel roofline entries from the library's HIP-event timings."""
+    out = {}
+    for name, (count, total_ms) in report.items():
+        key = next((k for k in sorted(workload.alg, key=len, reverse=True) if name.startswith(k)), None)
+        avg_ms = total_ms / count
+        entry = {"launches": count, "avg_ms": avg_ms, "total_ms": total_ms}
+        if key is not None:
+            bound, work = workload.alg[key]
+            if work is None and key == "conv_reduce_dw":
+                nparts = workload.dd.distdl_conv_bwd_workspace(workload.plan) // (4 * (workload.nw + workload.cfg["c_out"]))
+                work = (nparts + 1) * workload.nw * 4
+            if bound == "hbm":
+                ach = work / (avg_ms * 1e-3) / 1e9
+                entry.update(bound="hbm", achieved=ach, peak=HBM_PEAK_GBS, unit="GB/s", frac=ach / HBM_PEAK_GBS,
+                             algorithmic_bytes=work)
+            else:
+                ach = work / (avg_ms * 1e-3) / 1e12
+                peak = MFMA_PEAK_TFLOPS[workload.dtype]
+                entry.update(bound="mfma", achieved=ach, peak=peak, unit="TFLOP/s", frac=ach / peak,
+                             algorithmic_flops=work)
+            entry["traffic"] = traffic.get(f"{workload.describe['workload'].split(':')[0]}/{name}")
+        out[name] = entry
+    return out
+
+
+def load_traffic():
+    """HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+    (summaries under profiles/); keyed "<workload>/<kernel>"."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if os.path.exists(path):
+        with open(path) as f:
+            return json.load(f)
+    return {}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="cfg5", choices=["cfg5", "cfg2", "cfg3", "cfg3-bf16"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (all P virtual workers share its HBM); "
+              "--gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    import paper_2006_03108_amd as dd
+    torch.cuda.set_device(0)
+    if args.workload in ("cfg5", "cfg2"):
+        wl = ConvWorkload(args.workload)
+    else:
+        wl = AffineWorkload("cfg3", "bf16" if args.workload.endswith("bf16") else "f32")
+    for _ in range(args.warmup):
+        wl.step()
+    torch.cuda.synchronize()
+    dd.distdl_profile_enable(True)      # HIP events around every kernel, on the launch stream
+    dd.distdl_profile_report()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        wl.step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    report = dd.distdl_profile_report()
+    dd.distdl_profile_enable(False)
+    sec = elapsed / args.steps
+    kernels = kernel_rooflines(wl, report, load_traffic())
+    dominant = max(kernels, key=lambda k: kernels[k]["total_ms"])
+    dk = kernels[dominant]
+    roofline = {"kernel": dominant, "bound": dk.get("bound"), "achieved": dk.get("achieved"), "peak": dk.get("peak"),
+                "unit": dk.get("unit"), "frac": dk.get("frac"), "traffic": dk.get("traffic"),
+                "avg_ms": dk["avg_ms"], "launches": dk["launches"]}
+    line = {
+        "metric": wl.metric, "value": wl.value(sec), "unit": wl.unit, "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": sec * 1e3, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": wl.dtype, "data": "synthetic", "config": wl.describe,
+        "roofline": roofline, "kernels": kernels,
+    }
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = wl.cpu_baseline()
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

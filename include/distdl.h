@@ -204,6 +204,22 @@ int distdl_dot(const void* const a_dev[], const void* const b_dev[], const int64
                distdl_dtype dtype, double* result_dev, void* stream);
 
 /* ------------------------------------------------------------------------
+ * Measurement support.  plan_stats: cell counts behind the algorithmic-bytes
+ * figures of the halo kernels, summed over all workers and per sample and
+ * channel: out[0] halo cells (in-domain, non-owned), out[1] zero-padding
+ * cells, out[2] bulk cells of which some other worker holds a copy (the band
+ * the adjoint adds into), out[3] halo cells the adjoint gathers (= out[0]).
+ * profile_enable(1) makes every kernel launch of the library be bracketed by
+ * two HIP events on the launch stream; profile_report waits for them and
+ * writes one line "name launches total_ms" per kernel name into out (a
+ * NUL-terminated text of at most cap bytes), then forgets them.  Returns the
+ * text length.  Not thread-safe; meant for the benchmark.
+ * ---------------------------------------------------------------------- */
+int distdl_plan_stats(const distdl_plan* plan, int64_t out[4]);
+int distdl_profile_enable(int on);
+int distdl_profile_report(char* out, size_t cap);
+
+/* ------------------------------------------------------------------------
  * Introspection of the host planner (for tests that run without a GPU): the
  * one-pass halo kernels are driven by a table of box tasks.  Task `index` of
  * the forward (adjoint = 0) or adjoint table is written to out[] as

@@ -55,6 +55,9 @@ _SIGS = {
     "distdl_affine_fwd": [_vp, _pp, _pp, _pp, _pp, _vp],
     "distdl_affine_bwd": [_vp, _pp, _pp, _pp, _pp, _pp, _pp, _vp],
     "distdl_dot": [_pp, _pp, _p64, _i, _i, _vp, _vp],
+    "distdl_plan_stats": [_vp, _p64],
+    "distdl_profile_enable": [_i],
+    "distdl_profile_report": [C.c_char_p, C.c_size_t],
     "distdl_debug_task_count": [_vp, _i],
     "distdl_debug_get_task": [_vp, _i, _i, _p32, _i],
 }
@@ -230,6 +233,27 @@ def distdl_dot(a, b, result):
     """result: a 1-element float64 device tensor."""
     _check(lib.distdl_dot(_ptrs(a), _ptrs(b), _arr(C.c_int64, [t.numel() for t in a]), len(a),
                           _dtype_code(a[0].dtype), result.data_ptr(), _stream()))
+
+
+def distdl_plan_stats(plan):
+    out = (C.c_int64 * 4)()
+    _check(lib.distdl_plan_stats(plan.handle, out))
+    return dict(halo_cells=out[0], pad_cells=out[1], band_cells=out[2], gathered_cells=out[3])
+
+
+def distdl_profile_enable(on):
+    _check(lib.distdl_profile_enable(int(on)))
+
+
+def distdl_profile_report():
+    """{kernel name: (launches, total milliseconds)} since the last report."""
+    buf = C.create_string_buffer(1 << 16)
+    _check(lib.distdl_profile_report(buf, len(buf)))
+    out = {}
+    for line in buf.value.decode().splitlines():
+        name, count, ms = line.split()
+        out[name] = (int(count), float(ms))
+    return out
 
 
 def distdl_debug_tasks(plan, adjoint):

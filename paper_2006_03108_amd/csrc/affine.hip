@@ -8,6 +8,7 @@
 #include <algorithm>
 
 #include "common.h"
+#include "profile.h"
 
 struct distdl_affine_plan {
   int64_t n_b = 0, n_fi = 0, n_fo = 0;
@@ -134,12 +135,14 @@ static int prepare(distdl_affine_plan* p) {
 template <class T>
 static void fwd_direct(distdl_affine_plan* p, bool has_b, hipStream_t st_) {
   dim3 grid((unsigned)((p->n_b * p->max_fo + 255) / 256), p->P_fo);
+  ProfScope prof("affine_fwd_direct", st_);
   hipLaunchKernelGGL(affine_fwd_direct_kernel<T>, grid, dim3(256), 0, st_, p->tab_x.dev, p->tab_W.dev,
                      has_b ? p->tab_b.dev : (void**)nullptr, p->tab_y.dev, p->d_sizes, (int)p->n_b, p->P_fo, p->P_fi);
 }
 
 template <class T>
 static void bwd_direct(distdl_affine_plan* p, bool has_db, hipStream_t st_) {
+  ProfScope prof("affine_bwd_direct", st_);
   hipLaunchKernelGGL(affine_bwd_x_direct_kernel<T>, dim3((unsigned)((p->n_b * p->max_fi + 255) / 256), p->P_fi),
                      dim3(256), 0, st_, p->tab_dy.dev, p->tab_W.dev, p->tab_dx.dev, p->d_sizes, (int)p->n_b, p->P_fo,
                      p->P_fi);

@@ -6,7 +6,10 @@
 // larger problems are split on the host: a broadcast over more replicas is
 // several independent launches, a reduction continues into its output in
 // replica order, so the summation order stays i = 0..k-1).
+#include <algorithm>
+
 #include "common.h"
+#include "profile.h"
 
 namespace distdl {
 
@@ -184,6 +187,7 @@ static int run_collective(bool reduce, void* const one[], void* const many[], co
       a.accumulate = i0 > 0;
       a.clear_inputs = clear_inputs;
       dim3 grid(blocks_for(max_count, vec), ng), block(kCollThreads);
+      ProfScope prof(reduce ? "sumreduce" : "bcast", st);
       if (reduce) {
         if (dtype == DISTDL_F32) hipLaunchKernelGGL(reduce_kernel<false>, grid, block, 0, st, a);
         else hipLaunchKernelGGL(reduce_kernel<true>, grid, block, 0, st, a);

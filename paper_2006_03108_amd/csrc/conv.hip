@@ -10,6 +10,7 @@
 #include <algorithm>
 
 #include "common.h"
+#include "profile.h"
 
 namespace distdl {
 
@@ -210,6 +211,7 @@ static int prepare_weights(distdl_plan* p, const float* w, hipStream_t st) {
     DISTDL_HIP_TRY(hipMalloc((void**)&p->d_wt, n * sizeof(float)));
     p->wt_elems = n;
   }
+  ProfScope prof("conv_relayout_w", st);
   hipLaunchKernelGGL(relayout_w_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, w, p->d_wt, c.co, c.ci,
                      c.taps);
   return DISTDL_OK;
@@ -243,6 +245,7 @@ int distdl_conv_fwd(distdl_plan* plan, void* const x_bufs_dev[], const void* w_d
   ConvDev c = conv_params(plan);
   int64_t total = plan->n_b * plan->max_out_cells * c.co;
   dim3 grid((unsigned)((total + 255) / 256), plan->n_workers);
+  ProfScope prof("conv_fwd_direct", st);
   hipLaunchKernelGGL(conv_fwd_direct_kernel, grid, dim3(256), 0, st, plan->d_workers, plan->tab_x.dev, plan->d_wt,
                      (const float*)bias_dev, plan->tab_y.dev, c);
   DISTDL_HIP_TRY(hipGetLastError());
@@ -272,16 +275,25 @@ int distdl_conv_bwd(distdl_plan* plan, const void* const x_bufs_dev[], const voi
   ConvDev c = conv_params(plan);
   // [dConv]* with respect to x, into the whole padded buffers
   int64_t total = plan->n_b * plan->max_buf_cells * c.ci;
-  hipLaunchKernelGGL(conv_bwd_data_direct_kernel, dim3((unsigned)((total + 255) / 256), plan->n_workers), dim3(256), 0,
-                     st, plan->d_workers, plan->tab_dy.dev, plan->d_wt, plan->tab_dx.dev, c);
+  {
+    ProfScope prof("conv_bwd_data_direct", st);
+    hipLaunchKernelGGL(conv_bwd_data_direct_kernel, dim3((unsigned)((total + 255) / 256), plan->n_workers), dim3(256),
+                       0, st, plan->d_workers, plan->tab_dy.dev, plan->d_wt, plan->tab_dx.dev, c);
+  }
   // [dConv]* with respect to w and b, then R over the workers
   int nchunks = direct_chunks(plan);
   int nw = c.taps * c.ci * c.co + c.co;
-  hipLaunchKernelGGL(conv_bwd_weight_direct_kernel, dim3((unsigned)((nw + 255) / 256), nchunks, plan->n_workers),
-                     dim3(256), 0, st, plan->d_workers, plan->tab_x.dev, plan->tab_dy.dev, (float*)workspace_dev, c,
-                     nchunks);
-  hipLaunchKernelGGL(conv_reduce_dw_kernel, dim3((unsigned)((nw + 255) / 256)), dim3(256), 0, st,
-                     (const float*)workspace_dev, nchunks * plan->n_workers, (float*)dw_dev, (float*)dbias_dev, c);
+  {
+    ProfScope prof("conv_bwd_weight_direct", st);
+    hipLaunchKernelGGL(conv_bwd_weight_direct_kernel, dim3((unsigned)((nw + 255) / 256), nchunks, plan->n_workers),
+                       dim3(256), 0, st, plan->d_workers, plan->tab_x.dev, plan->tab_dy.dev, (float*)workspace_dev, c,
+                       nchunks);
+  }
+  {
+    ProfScope prof("conv_reduce_dw", st);
+    hipLaunchKernelGGL(conv_reduce_dw_kernel, dim3((unsigned)((nw + 255) / 256)), dim3(256), 0, st,
+                       (const float*)workspace_dev, nchunks * plan->n_workers, (float*)dw_dev, (float*)dbias_dev, c);
+  }
   DISTDL_HIP_TRY(hipGetLastError());
   // dx <- H* dx
   return run_halo(plan, true, plan->tab_dx, dx_bufs_dev, st);

@@ -11,6 +11,7 @@
 // and clears them -- the "add into the bulk" of C* = K_b S_{b->a} without
 // atomics, so results are run-to-run identical.
 #include "common.h"
+#include "profile.h"
 
 namespace distdl {
 
@@ -180,6 +181,7 @@ template <class E>
 static void launch(bool adjoint, const TaskTable& tt, const distdl_plan* p, void* const* bufs, hipStream_t st) {
   dim3 grid((unsigned)tt.blocks.size()), block(kThreads);
   uint32_t cv = (uint32_t)(p->n_ci / E::N);
+  ProfScope prof(adjoint ? "halo_adj" : "halo_fwd", st);
   if (adjoint)
     hipLaunchKernelGGL(halo_adj_kernel<E>, grid, block, 0, st, tt.d_blocks, tt.d_tasks, tt.d_srcs, p->d_workers, bufs,
                        (uint32_t)p->n_b, cv);
