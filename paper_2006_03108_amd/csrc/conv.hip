@@ -10,6 +10,7 @@
 #include <algorithm>
 
 #include "common.h"
+#include "conv_mfma.h"
 #include "profile.h"
 
 namespace distdl {
@@ -207,7 +208,10 @@ static int check_conv_plan(const distdl_plan* p) {
 static int prepare_weights(distdl_plan* p, const float* w, hipStream_t st) {
   ConvDev c = conv_params(p);
   size_t n = (size_t)c.taps * c.ci * c.co;
-  if (!p->d_wt) {
+  if (p->wt_elems < n) {
+    if (p->d_wt) (void)hipFree(p->d_wt);  // waits for kernels still reading it
+    p->d_wt = nullptr;
+    p->wt_elems = 0;
     DISTDL_HIP_TRY(hipMalloc((void**)&p->d_wt, n * sizeof(float)));
     p->wt_elems = n;
   }
@@ -227,7 +231,9 @@ size_t distdl_conv_bwd_workspace(const distdl_plan* plan) {
   if (!plan || plan->explicit_halo) return 0;
   ConvDev c = conv_params(plan);
   size_t nw = (size_t)c.taps * c.ci * c.co + c.co;
-  return nw * sizeof(float) * plan->n_workers * direct_chunks(plan);
+  int chunks = direct_chunks(plan);
+  if (wgrad_mfma_supported(plan)) chunks = std::max(chunks, wgrad_chunks(plan));
+  return nw * sizeof(float) * plan->n_workers * chunks;
 }
 
 int distdl_conv_fwd(distdl_plan* plan, void* const x_bufs_dev[], const void* w_dev, const void* bias_dev,
@@ -241,6 +247,13 @@ int distdl_conv_fwd(distdl_plan* plan, void* const x_bufs_dev[], const void* w_d
   if ((rc = run_halo(plan, false, plan->tab_x, x_bufs_dev, st))) return rc;  // x <- H x
   if ((rc = plan->tab_x.upload((const void* const*)x_bufs_dev, plan->n_workers, st))) return rc;
   if ((rc = plan->tab_y.upload((const void* const*)y_dev, plan->n_workers, st))) return rc;
+  bool aligned = (uintptr_t)w_dev % 16 == 0;
+  for (int w = 0; w < plan->n_workers; ++w) aligned &= (uintptr_t)x_bufs_dev[w] % 16 == 0;
+  if (aligned && corr_mfma_supported(plan)) {
+    if ((rc = conv_fwd_mfma(plan, (const float*)w_dev, (const float*)bias_dev, st))) return rc;
+    DISTDL_HIP_TRY(hipGetLastError());
+    return DISTDL_OK;
+  }
   if ((rc = prepare_weights(plan, (const float*)w_dev, st))) return rc;
   ConvDev c = conv_params(plan);
   int64_t total = plan->n_b * plan->max_out_cells * c.co;
@@ -271,19 +284,27 @@ int distdl_conv_bwd(distdl_plan* plan, const void* const x_bufs_dev[], const voi
   if ((rc = plan->tab_x.upload(x_bufs_dev, plan->n_workers, st))) return rc;
   if ((rc = plan->tab_dy.upload(dy_dev, plan->n_workers, st))) return rc;
   if ((rc = plan->tab_dx.upload((const void* const*)dx_bufs_dev, plan->n_workers, st))) return rc;
-  if ((rc = prepare_weights(plan, (const float*)w_dev, st))) return rc;
   ConvDev c = conv_params(plan);
+  bool aligned = true;
+  for (int w = 0; w < plan->n_workers; ++w) aligned &= (uintptr_t)dy_dev[w] % 16 == 0;
+  const bool data_mfma = aligned && corr_mfma_supported(plan);
+  const bool wgrad_mfma = wgrad_mfma_supported(plan) && plan->n_workers * wgrad_chunks(plan) <= 65535;
   // [dConv]* with respect to x, into the whole padded buffers
   int64_t total = plan->n_b * plan->max_buf_cells * c.ci;
-  {
+  if (data_mfma) {
+    if ((rc = conv_bwd_data_mfma(plan, (const float*)w_dev, st))) return rc;
+  } else {
+    if ((rc = prepare_weights(plan, (const float*)w_dev, st))) return rc;
     ProfScope prof("conv_bwd_data_direct", st);
     hipLaunchKernelGGL(conv_bwd_data_direct_kernel, dim3((unsigned)((total + 255) / 256), plan->n_workers), dim3(256),
                        0, st, plan->d_workers, plan->tab_dy.dev, plan->d_wt, plan->tab_dx.dev, c);
   }
   // [dConv]* with respect to w and b, then R over the workers
-  int nchunks = direct_chunks(plan);
+  int nchunks = wgrad_mfma ? wgrad_chunks(plan) : direct_chunks(plan);
   int nw = c.taps * c.ci * c.co + c.co;
-  {
+  if (wgrad_mfma) {
+    if ((rc = conv_wgrad_mfma(plan, (float*)workspace_dev, st))) return rc;
+  } else {
     ProfScope prof("conv_bwd_weight_direct", st);
     hipLaunchKernelGGL(conv_bwd_weight_direct_kernel, dim3((unsigned)((nw + 255) / 256), nchunks, plan->n_workers),
                        dim3(256), 0, st, plan->d_workers, plan->tab_x.dev, plan->tab_dy.dev, (float*)workspace_dev, c,

@@ -1,0 +1,46 @@
+// Argument blocks and entry points of the MFMA convolution kernels.
+#pragma once
+#include <cstddef>
+#include <cstdint>
+
+#include "common.h"
+
+namespace distdl {
+
+struct CorrArgs {
+  int32_t mode;  // 0: forward (x^ -> y), 1: one stride-parity class of the data gradient (dy -> dx^)
+  int32_t n_b, kc, nc;  // batch, contraction channels (input tensor), output channels
+  int32_t ntn;          // 32-wide output-channel tiles
+  int32_t n_workers;
+  int32_t nt[3];         // taps per dimension in this launch
+  int32_t tapoff[3][8];  // input offset of tap i along dimension d
+  int32_t tapid[3][8];   // index of that tap in the layer's kernel
+  int32_t tapmin[3], tapspan[3];
+  int32_t is[3];   // input step per output step
+  int32_t s[3];    // layer stride
+  int32_t par[3];  // parity class (mode 1)
+  int32_t oh_t;    // output rows (dimension 1) per workgroup tile
+  int32_t R, Cw, CwQ;  // patch rows, cells per row, cells per residue class of the row
+  int32_t a_vec4;      // patch size in 16-byte units
+  int32_t tiles_max;   // tiles of the largest worker
+  const float* wt;     // weights in staging order
+  const float* bias;   // may be null
+};
+
+struct WgradArgs {
+  int32_t n_b, ci, co;
+  int32_t k[3], s[3], dil[3];
+  int32_t nchunks;  // position chunks per worker
+  int64_t slot;     // floats per (worker, chunk) partial: taps*ci*co + co
+};
+
+bool corr_mfma_supported(const distdl_plan* p);
+bool wgrad_mfma_supported(const distdl_plan* p);
+size_t bwd_scratch_elems(const distdl_plan* p);
+int wgrad_chunks(const distdl_plan* p);
+// All three expect the plan's pointer tables (tab_x, tab_y, tab_dy, tab_dx) to be uploaded.
+int conv_fwd_mfma(distdl_plan* p, const float* w, const float* bias, hipStream_t st);
+int conv_bwd_data_mfma(distdl_plan* p, const float* w, hipStream_t st);
+int conv_wgrad_mfma(distdl_plan* p, float* partial, hipStream_t st);
+
+}  // namespace distdl

@@ -1,0 +1,528 @@
+// MFMA (matrix-core) kernels for the local convolution of the partitioned
+// layer (Sec. 4, "Conv" and "[dConv]*" steps), fp32, channels-last.
+//
+// corr_mfma_kernel: a strided correlation written as an implicit GEMM
+//     out[q][n] = sum_taps sum_k  W[tap][k][n] * in[base + q*step + tapoff][k]
+//   used (a) for the forward pass (in = x^, out = y) and (b) once per stride
+//   parity class for the data gradient (in = dy, out = the cells of dx^ whose
+//   coordinate is congruent to that class; out-of-range dy reads as zero).
+//   A workgroup owns a tile of OH_T output rows x 32 output columns; per
+//   (tap plane, 8-channel chunk) it stages the input patch and the weights in
+//   LDS once and all taps of that plane read it from there.
+// wgrad_mfma_kernel: dw^[tap][ci][co] = sum_pos x^[cell(pos,tap)][ci] dy[pos][co]
+//   per worker; both MFMA operands are read straight from global memory in
+//   their register layout (channels-last makes 32 channels one 128-byte row).
+//
+// v_mfma_f32_32x32x2_f32 operand layout: A lane l holds A[i = l%32][k = l/32],
+// B lane l holds B[k = l/32][j = l%32], D register v of lane l holds
+// D[i = 8*(v/4) + 4*(l/32) + v%4][j = l%32].
+#include <algorithm>
+
+#include "common.h"
+#include "conv_mfma.h"
+#include "profile.h"
+
+namespace distdl {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+struct PerWorker {
+  int32_t in_ext[3], in_base[3], nq[3], out_ext[3], out_base[3], os[3];
+};
+
+__host__ __device__ inline PerWorker derive(const WorkerDev& wd, const CorrArgs& a) {
+  PerWorker g;
+  for (int d = 0; d < 3; ++d) {
+    if (a.mode == 0) {
+      g.in_ext[d] = wd.buf[d];
+      g.in_base[d] = wd.origin[d];
+      g.nq[d] = wd.out[d];
+      g.out_ext[d] = wd.out[d];
+      g.out_base[d] = 0;
+      g.os[d] = 1;
+    } else {
+      const int s = a.s[d], op = wd.origin[d] + a.par[d];
+      const int first = op % s;  // first buffer cell of this parity class
+      g.in_ext[d] = wd.out[d];
+      g.in_base[d] = -(op / s);
+      g.nq[d] = first < wd.buf[d] ? (wd.buf[d] - 1 - first) / s + 1 : 0;
+      g.out_ext[d] = wd.buf[d];
+      g.out_base[d] = first;
+      g.os[d] = s;
+    }
+  }
+  return g;
+}
+
+__host__ __device__ inline int64_t tiles_of(const PerWorker& g, const CorrArgs& a) {
+  return (int64_t)a.n_b * g.nq[0] * ((g.nq[1] + a.oh_t - 1) / a.oh_t) * ((g.nq[2] + 31) / 32) * a.ntn;
+}
+
+constexpr int kMaxPieces = 14;
+
+template <int MT>
+__global__ __launch_bounds__(256, 2) void corr_mfma_kernel(const WorkerDev* __restrict__ workers,
+                                                           void* const* in_bufs, void* const* out_bufs, CorrArgs a) {
+  extern __shared__ float4 lds[];
+  float4* As = lds;
+  float4* Bs = lds + a.a_vec4;
+
+  // XCD-aware order: consecutive tiles (which share input rows) stay on one
+  // XCD, i.e. behind one L2
+  const uint32_t nblk = gridDim.x;
+  const uint32_t r = (blockIdx.x & 7u) * (nblk >> 3) + (blockIdx.x >> 3);
+  const uint32_t worker = r / a.tiles_max;
+  uint32_t tile = r - worker * a.tiles_max;
+  if (worker >= (uint32_t)a.n_workers) return;
+  const WorkerDev wd = workers[worker];
+  const PerWorker g = derive(wd, a);
+  if ((int64_t)tile >= tiles_of(g, a)) return;
+
+  const int nt2tiles = (g.nq[2] + 31) / 32, nt1tiles = (g.nq[1] + a.oh_t - 1) / a.oh_t;
+  const int q2_0 = (tile % nt2tiles) * 32; tile /= nt2tiles;
+  const int q1_0 = (tile % nt1tiles) * a.oh_t; tile /= nt1tiles;
+  const int ntile = tile % a.ntn; tile /= a.ntn;
+  const int q0 = tile % g.nq[0];
+  const int n = tile / g.nq[0];
+
+  const float* __restrict__ in = (const float*)in_bufs[worker];
+  float* __restrict__ out = (float*)out_bufs[worker];
+  const int si2 = a.kc, si1 = g.in_ext[2] * si2, si0 = g.in_ext[1] * si1;
+  const size_t sin = (size_t)g.in_ext[0] * si0;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, h = lane >> 5, m = lane & 31;
+
+  // per-thread patch pieces (16 bytes each): fixed for the whole tile
+  int32_t goff[kMaxPieces], loff[kMaxPieces];
+  const int npieces = a.R * a.Cw * 2;
+#pragma unroll
+  for (int i = 0; i < kMaxPieces; ++i) {
+    const int piece = tid + i * 256;
+    goff[i] = -1;
+    loff[i] = -1;
+    if (piece < npieces) {
+      const int ph = piece & 1, cell = piece >> 1;
+      const int rr = cell / a.Cw, c = cell - rr * a.Cw;
+      const int i1 = g.in_base[1] + q1_0 * a.is[1] + a.tapmin[1] + rr;
+      const int i2 = g.in_base[2] + q2_0 * a.is[2] + a.tapmin[2] + c;
+      loff[i] = ((rr * 2 + ph) * a.is[2] + c % a.is[2]) * a.CwQ + c / a.is[2];
+      if (i1 >= 0 && i1 < g.in_ext[1] && i2 >= 0 && i2 < g.in_ext[2]) goff[i] = i1 * si1 + i2 * si2 + ph * 4;
+    }
+  }
+
+  floatx16 acc[MT];
+#pragma unroll
+  for (int t = 0; t < MT; ++t)
+    for (int v = 0; v < 16; ++v) acc[t][v] = 0.f;
+
+  const int ncc = (a.kc + 7) / 8;
+  const int nb_vec4 = a.nt[1] * a.nt[2] * 64;
+  for (int t0 = 0; t0 < a.nt[0]; ++t0) {
+    const int i0 = g.in_base[0] + q0 * a.is[0] + a.tapoff[0][t0];
+    if (i0 < 0 || i0 >= g.in_ext[0]) continue;  // whole tap plane out of range: contributes zero
+    const float* plane = in + n * sin + (size_t)i0 * si0;
+    for (int cc = 0; cc < ncc; ++cc) {
+      // stage the input patch: rows x cells x 8 channels
+#pragma unroll
+      for (int i = 0; i < kMaxPieces; ++i) {
+        if (loff[i] >= 0) {
+          float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+          const int ph = (tid + i * 256) & 1;
+          if (goff[i] >= 0 && cc * 8 + ph * 4 < a.kc) v = *(const float4*)(plane + goff[i] + cc * 8);
+          As[loff[i]] = v;
+        }
+      }
+      // stage the weights of this tap plane and channel chunk
+      const float4* wsrc = (const float4*)a.wt + ((size_t)(ntile * a.nt[0] + t0) * ncc + cc) * nb_vec4;
+      for (int p = tid; p < nb_vec4; p += 256) Bs[p] = wsrc[p];
+      __syncthreads();
+      for (int t1 = 0; t1 < a.nt[1]; ++t1) {
+        const int rel1 = a.tapoff[1][t1] - a.tapmin[1];
+        for (int t2 = 0; t2 < a.nt[2]; ++t2) {
+          const int rel2 = a.tapoff[2][t2] - a.tapmin[2];
+          const int res = rel2 % a.is[2], cq = rel2 / a.is[2];
+          const float4 b = Bs[((t1 * a.nt[2] + t2) * 2 + h) * 32 + m];
+#pragma unroll
+          for (int mt = 0; mt < MT; ++mt) {
+            const int rr = (wave * MT + mt) * a.is[1] + rel1;
+            const float4 av = As[((rr * 2 + h) * a.is[2] + res) * a.CwQ + m + cq];
+            acc[mt] = __builtin_amdgcn_mfma_f32_32x32x2f32(av.x, b.x, acc[mt], 0, 0, 0);
+            acc[mt] = __builtin_amdgcn_mfma_f32_32x32x2f32(av.y, b.y, acc[mt], 0, 0, 0);
+            acc[mt] = __builtin_amdgcn_mfma_f32_32x32x2f32(av.z, b.z, acc[mt], 0, 0, 0);
+            acc[mt] = __builtin_amdgcn_mfma_f32_32x32x2f32(av.w, b.w, acc[mt], 0, 0, 0);
+          }
+        }
+      }
+      __syncthreads();
+    }
+  }
+
+  // store: register v of lane (h, m) is output column q2_0 + 8*(v/4) + 4*h + v%4, channel ntile*32 + m
+  const int ch = ntile * 32 + m;
+  if (ch >= a.nc) return;
+  const float bias = a.bias ? a.bias[ch] : 0.f;
+  const size_t so2 = a.nc, so1 = (size_t)g.out_ext[2] * so2, so0 = (size_t)g.out_ext[1] * so1,
+               son = (size_t)g.out_ext[0] * so0;
+  float* obase = out + n * son + (size_t)(g.out_base[0] + g.os[0] * q0) * so0 + ch;
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt) {
+    const int q1 = q1_0 + wave * MT + mt;
+    if (q1 >= g.nq[1]) continue;
+    float* orow = obase + (size_t)(g.out_base[1] + g.os[1] * q1) * so1;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int q2 = q2_0 + 8 * (v / 4) + 4 * h + (v % 4);
+      if (q2 < g.nq[2]) orow[(size_t)(g.out_base[2] + g.os[2] * q2) * so2] = acc[mt][v] + bias;
+    }
+  }
+}
+
+// Weights in the order the correlation kernel stages them:
+//   dst[ntile][t0][cc][t1][t2][h][nn][j] = W[tap(t0,t1,t2)][k = cc*8 + 4h + j][n = ntile*32 + nn]
+// with W[tap][k][n] = w[n][k][tap] (forward: n = co, k = ci) or w[k][n][tap]
+// (data gradient: k = co, n = ci), zero beyond the channel counts.
+__global__ __launch_bounds__(256) void corr_weights_kernel(const float* __restrict__ w, float* __restrict__ dst,
+                                                           CorrArgs a, int ci_n, int co_n, int taps, int k1, int k2) {
+  const int ncc = (a.kc + 7) / 8;
+  const int64_t total = (int64_t)a.ntn * a.nt[0] * ncc * a.nt[1] * a.nt[2] * 256;
+  int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= total) return;
+  const int j = idx & 3, nn = (idx >> 2) & 31, hh = (idx >> 7) & 1;
+  int64_t r = idx >> 8;
+  const int t2 = r % a.nt[2]; r /= a.nt[2];
+  const int t1 = r % a.nt[1]; r /= a.nt[1];
+  const int cc = r % ncc; r /= ncc;
+  const int t0 = r % a.nt[0];
+  const int ntile = (int)(r / a.nt[0]);
+  const int k = cc * 8 + 4 * hh + j, nch = ntile * 32 + nn;
+  float v = 0.f;
+  if (k < a.kc && nch < a.nc) {
+    const int tap = (a.tapid[0][t0] * k1 + a.tapid[1][t1]) * k2 + a.tapid[2][t2];
+    const int co = a.mode == 0 ? nch : k, ci = a.mode == 0 ? k : nch;
+    v = w[((size_t)co * ci_n + ci) * taps + tap];
+  }
+  dst[idx] = v;
+}
+
+// ---- weight gradient ----------------------------------------------------------
+
+constexpr int kMaxK2 = 8;
+
+// grid: (tap-row groups of 4, ci tiles * co tiles, workers * nchunks); wave w of a block owns tap row
+// (t0, t1) = group*4 + w and all k2 taps of that row.
+template <int K2>
+__global__ __launch_bounds__(256) void wgrad_mfma_kernel(const WorkerDev* __restrict__ workers, void* const* x_bufs,
+                                                         void* const* dy_bufs, float* __restrict__ partial,
+                                                         WgradArgs a) {
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, h = lane >> 5, m = lane & 31;
+  const int trow = blockIdx.x * 4 + wave;
+  if (trow >= a.k[0] * a.k[1]) return;
+  const int t0 = trow / a.k[1], t1 = trow - t0 * a.k[1];
+  const int nco_t = (a.co + 31) / 32;
+  const int ci_t = blockIdx.y / nco_t, co_t = blockIdx.y - ci_t * nco_t;
+  const int worker = blockIdx.z / a.nchunks, chunk = blockIdx.z - worker * a.nchunks;
+  const WorkerDev wd = workers[worker];
+  const float* __restrict__ x = (const float*)x_bufs[worker];
+  const float* __restrict__ dy = (const float*)dy_bufs[worker];
+  const int ci = ci_t * 32 + m, co = co_t * 32 + m;
+  const bool ci_ok = ci < a.ci, co_ok = co < a.co;
+
+  floatx16 acc[K2];
+#pragma unroll
+  for (int t = 0; t < K2; ++t)
+    for (int v = 0; v < 16; ++v) acc[t][v] = 0.f;
+
+  const int64_t sx2 = a.ci, sx1 = (int64_t)wd.buf[2] * sx2, sx0 = (int64_t)wd.buf[1] * sx1,
+                sxn = (int64_t)wd.buf[0] * sx0;
+  const int64_t sy2 = a.co, sy1 = (int64_t)wd.out[2] * sy2;
+  const int nrows = a.n_b * wd.out[0] * wd.out[1];
+  const int per = (nrows + a.nchunks - 1) / a.nchunks;
+  const int row_end = min(nrows, (chunk + 1) * per);
+  const int O2 = wd.out[2];
+  for (int row = chunk * per; row < row_end; ++row) {
+    const int o1 = row % wd.out[1];
+    const int r2 = row / wd.out[1];
+    const int o0 = r2 % wd.out[0], n = r2 / wd.out[0];
+    const float* xrow = x + n * sxn + (int64_t)(wd.origin[0] + o0 * a.s[0] + t0 * a.dil[0]) * sx0 +
+                        (int64_t)(wd.origin[1] + o1 * a.s[1] + t1 * a.dil[1]) * sx1 + (int64_t)wd.origin[2] * sx2 + ci;
+    const float* dyrow = dy + (int64_t)row * sy1 + co;
+    // two output positions per MFMA: lanes 0-31 take o2, lanes 32-63 take o2 + 1
+    for (int o2 = 0; o2 < O2; o2 += 2) {
+      const int p = o2 + h;
+      const bool pos_ok = p < O2;
+      const float b = (pos_ok && co_ok) ? dyrow[(int64_t)p * sy2] : 0.f;
+      float av[K2];
+#pragma unroll
+      for (int t2 = 0; t2 < K2; ++t2)
+        av[t2] = (pos_ok && ci_ok && t2 < a.k[2]) ? xrow[(int64_t)(p * a.s[2] + t2 * a.dil[2]) * sx2] : 0.f;
+#pragma unroll
+      for (int t2 = 0; t2 < K2; ++t2) acc[t2] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[t2], b, acc[t2], 0, 0, 0);
+    }
+  }
+  // acc[t2] register v of lane (h, m): dw^[tap][ci = ci_t*32 + 8*(v/4) + 4h + v%4][co = co_t*32 + m]
+  float* pbase = partial + (size_t)blockIdx.z * a.slot;
+#pragma unroll
+  for (int t2 = 0; t2 < K2; ++t2) {
+    if (t2 >= a.k[2]) break;
+    const int tap = (t0 * a.k[1] + t1) * a.k[2] + t2;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int cir = ci_t * 32 + 8 * (v / 4) + 4 * h + (v % 4);
+      if (cir < a.ci && co_ok) pbase[((size_t)tap * a.ci + cir) * a.co + co] = acc[t2][v];
+    }
+  }
+}
+
+// db^ partial of one (worker, chunk): sum of dy over the chunk's positions,
+// written to the slot's trailing Co entries.  One block per slot.
+__global__ __launch_bounds__(256) void bias_partial_kernel(const WorkerDev* __restrict__ workers, void* const* dy_bufs,
+                                                           float* __restrict__ partial, WgradArgs a) {
+  const int worker = blockIdx.x / a.nchunks, chunk = blockIdx.x - worker * a.nchunks;
+  const WorkerDev wd = workers[worker];
+  const float* __restrict__ dy = (const float*)dy_bufs[worker];
+  const int nrows = a.n_b * wd.out[0] * wd.out[1];
+  const int per = (nrows + a.nchunks - 1) / a.nchunks;
+  const int64_t p0 = (int64_t)chunk * per * wd.out[2];
+  const int64_t p1 = (int64_t)min(nrows, (chunk + 1) * per) * wd.out[2];
+  __shared__ float red[256];
+  const int nw = a.k[0] * a.k[1] * a.k[2] * a.ci * a.co;
+  for (int c0 = 0; c0 < a.co; c0 += 32) {
+    // 8 position lanes x 32 channels
+    const int co = c0 + (threadIdx.x & 31);
+    float acc = 0.f;
+    if (co < a.co)
+      for (int64_t p = p0 + (threadIdx.x >> 5); p < p1; p += 8) acc += dy[p * a.co + co];
+    red[threadIdx.x] = acc;
+    __syncthreads();
+    if (threadIdx.x < 32 && co < a.co) {
+      float s = 0.f;
+      for (int i = 0; i < 8; ++i) s += red[i * 32 + threadIdx.x];
+      partial[(size_t)blockIdx.x * a.slot + nw + co] = s;
+    }
+    __syncthreads();
+  }
+}
+
+// ---- host side ------------------------------------------------------------------
+
+static int lds_bytes(const CorrArgs& a) { return (a.a_vec4 + a.nt[1] * a.nt[2] * 64) * 16; }
+
+static void finish_args(CorrArgs& a, int mt) {
+  a.oh_t = 4 * mt;
+  for (int d = 0; d < 3; ++d) {
+    int lo = 0, hi = 0;
+    for (int i = 0; i < a.nt[d]; ++i) {
+      lo = i == 0 ? a.tapoff[d][i] : std::min(lo, a.tapoff[d][i]);
+      hi = i == 0 ? a.tapoff[d][i] : std::max(hi, a.tapoff[d][i]);
+    }
+    a.tapmin[d] = lo;
+    a.tapspan[d] = hi - lo;
+  }
+  a.R = (a.oh_t - 1) * a.is[1] + a.tapspan[1] + 1;
+  a.Cw = 31 * a.is[2] + a.tapspan[2] + 1;
+  a.CwQ = (a.Cw + a.is[2] - 1) / a.is[2];
+  a.a_vec4 = a.R * 2 * a.is[2] * a.CwQ;
+}
+
+// Chooses the rows-per-wave so that two workgroups fit in a CU's LDS when
+// possible; returns 0 when the patch does not fit at all.
+static int choose_mt(CorrArgs& a) {
+  for (int mt : {2, 1}) {
+    finish_args(a, mt);
+    if (lds_bytes(a) <= 80 * 1024 && a.R * a.Cw * 2 <= kMaxPieces * 256) return mt;
+  }
+  finish_args(a, 1);
+  if (lds_bytes(a) <= 160 * 1024 && a.R * a.Cw * 2 <= kMaxPieces * 256) return 1;
+  return 0;
+}
+
+bool corr_mfma_supported(const distdl_plan* p) {
+  if (p->dtype != DISTDL_F32 || p->explicit_halo) return false;
+  if (p->n_ci % 4 || p->n_co % 4) return false;  // 16-byte channel pieces
+  for (int d = 0; d < 3; ++d)
+    if (p->ksize[d] > 8) return false;
+  return true;
+}
+
+static CorrArgs forward_args(const distdl_plan* p) {
+  CorrArgs a{};
+  a.mode = 0;
+  a.n_b = (int32_t)p->n_b;
+  a.kc = (int32_t)p->n_ci;
+  a.nc = (int32_t)p->n_co;
+  a.ntn = (a.nc + 31) / 32;
+  a.n_workers = p->n_workers;
+  for (int d = 0; d < 3; ++d) {
+    a.nt[d] = p->ksize[d];
+    a.is[d] = p->stride[d];
+    a.s[d] = p->stride[d];
+    for (int i = 0; i < p->ksize[d]; ++i) {
+      a.tapoff[d][i] = i * p->dilation[d];
+      a.tapid[d][i] = i;
+    }
+  }
+  return a;
+}
+
+static CorrArgs class_args(const distdl_plan* p, const int par[3]) {
+  CorrArgs a{};
+  a.mode = 1;
+  a.n_b = (int32_t)p->n_b;
+  a.kc = (int32_t)p->n_co;
+  a.nc = (int32_t)p->n_ci;
+  a.ntn = (a.nc + 31) / 32;
+  a.n_workers = p->n_workers;
+  for (int d = 0; d < 3; ++d) {
+    a.is[d] = 1;
+    a.s[d] = p->stride[d];
+    a.par[d] = par[d];
+    a.nt[d] = 0;
+    for (int t = 0; t < p->ksize[d]; ++t) {
+      int off = t * p->dilation[d];
+      if (off % p->stride[d] != par[d] % p->stride[d]) continue;
+      // cell c = origin + par + s*q reads dy[q - (off - par)/s]
+      a.tapoff[d][a.nt[d]] = -((off - par[d]) / p->stride[d]);
+      a.tapid[d][a.nt[d]] = t;
+      ++a.nt[d];
+    }
+  }
+  return a;
+}
+
+static int64_t max_tiles(const distdl_plan* p, const CorrArgs& a) {
+  int64_t mx = 0;
+  for (const WorkerDev& wd : p->workers) mx = std::max(mx, tiles_of(derive(wd, a), a));
+  return mx;
+}
+
+static size_t corr_weight_elems(const CorrArgs& a) {
+  return (size_t)a.ntn * a.nt[0] * ((a.kc + 7) / 8) * a.nt[1] * a.nt[2] * 256;
+}
+
+static int launch_corr(distdl_plan* p, CorrArgs a, const float* w, float* wscratch, const float* bias, void** in_tab,
+                       void** out_tab, const char* name, hipStream_t st) {
+  const int mt = choose_mt(a);
+  if (mt == 0) return set_error(DISTDL_ERR_UNSUPPORTED, "conv: kernel footprint does not fit in LDS");
+  a.tiles_max = (int32_t)max_tiles(p, a);
+  if (a.tiles_max == 0) return DISTDL_OK;
+  a.wt = wscratch;
+  a.bias = bias;
+  const int taps = p->ksize[0] * p->ksize[1] * p->ksize[2];
+  const size_t welems = corr_weight_elems(a);
+  if (welems) {
+    ProfScope prof("conv_relayout_w", st);
+    hipLaunchKernelGGL(corr_weights_kernel, dim3((unsigned)((welems + 255) / 256)), dim3(256), 0, st, w, wscratch, a,
+                       (int)p->n_ci, (int)p->n_co, taps, p->ksize[1], p->ksize[2]);
+  }
+  int64_t blocks = (int64_t)a.tiles_max * p->n_workers;
+  blocks = (blocks + 7) / 8 * 8;
+  const int lds = lds_bytes(a);
+  ProfScope prof(name, st);
+  if (mt == 2) {
+    DISTDL_HIP_TRY(hipFuncSetAttribute((const void*)corr_mfma_kernel<2>, hipFuncAttributeMaxDynamicSharedMemorySize, lds));
+    hipLaunchKernelGGL(corr_mfma_kernel<2>, dim3((unsigned)blocks), dim3(256), lds, st, p->d_workers, in_tab, out_tab, a);
+  } else {
+    DISTDL_HIP_TRY(hipFuncSetAttribute((const void*)corr_mfma_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize, lds));
+    hipLaunchKernelGGL(corr_mfma_kernel<1>, dim3((unsigned)blocks), dim3(256), lds, st, p->d_workers, in_tab, out_tab, a);
+  }
+  return DISTDL_OK;
+}
+
+// Scratch for the re-laid-out weights: forward needs one set, the data
+// gradient one per parity class (used one after the other on the stream).
+static int ensure_wscratch(distdl_plan* p, size_t elems) {
+  if (p->wt_elems >= elems) return DISTDL_OK;
+  if (p->d_wt) (void)hipFree(p->d_wt);
+  p->d_wt = nullptr;
+  p->wt_elems = 0;
+  DISTDL_HIP_TRY(hipMalloc((void**)&p->d_wt, elems * sizeof(float)));
+  p->wt_elems = elems;
+  return DISTDL_OK;
+}
+
+int conv_fwd_mfma(distdl_plan* p, const float* w, const float* bias, hipStream_t st) {
+  CorrArgs a = forward_args(p);
+  finish_args(a, 1);
+  int rc = ensure_wscratch(p, std::max(corr_weight_elems(a), bwd_scratch_elems(p)));
+  if (rc) return rc;
+  return launch_corr(p, a, w, p->d_wt, bias, p->tab_x.dev, p->tab_y.dev, "conv_fwd_mfma", st);
+}
+
+size_t bwd_scratch_elems(const distdl_plan* p) {
+  size_t total = 0;
+  for (int p0 = 0; p0 < p->stride[0]; ++p0)
+    for (int p1 = 0; p1 < p->stride[1]; ++p1)
+      for (int p2 = 0; p2 < p->stride[2]; ++p2) {
+        const int par[3] = {p0, p1, p2};
+        CorrArgs a = class_args(p, par);
+        total += corr_weight_elems(a);
+      }
+  return total;
+}
+
+int conv_bwd_data_mfma(distdl_plan* p, const float* w, hipStream_t st) {
+  CorrArgs fa = forward_args(p);
+  int rc = ensure_wscratch(p, std::max(corr_weight_elems(fa), bwd_scratch_elems(p)));
+  if (rc) return rc;
+  size_t at = 0;
+  for (int p0 = 0; p0 < p->stride[0]; ++p0)
+    for (int p1 = 0; p1 < p->stride[1]; ++p1)
+      for (int p2 = 0; p2 < p->stride[2]; ++p2) {
+        const int par[3] = {p0, p1, p2};
+        CorrArgs a = class_args(p, par);
+        if ((rc = launch_corr(p, a, w, p->d_wt + at, nullptr, p->tab_dy.dev, p->tab_dx.dev, "conv_bwd_data_mfma", st)))
+          return rc;
+        at += corr_weight_elems(a);
+      }
+  return DISTDL_OK;
+}
+
+bool wgrad_mfma_supported(const distdl_plan* p) {
+  return p->dtype == DISTDL_F32 && !p->explicit_halo && p->ksize[2] <= kMaxK2;
+}
+
+int wgrad_chunks(const distdl_plan* p) {
+  // enough (worker, chunk) slots to fill the chip a few times over
+  int64_t groups = (p->ksize[0] * p->ksize[1] + 3) / 4;
+  int64_t tiles = ((p->n_ci + 31) / 32) * ((p->n_co + 31) / 32);
+  int64_t blocks = groups * tiles * p->n_workers;
+  int64_t want = (1536 + blocks - 1) / blocks;
+  int64_t rows = p->n_b * p->max_out_cells;  // upper bound on rows
+  return (int)std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(want, 32), rows));
+}
+
+int conv_wgrad_mfma(distdl_plan* p, float* partial, hipStream_t st) {
+  WgradArgs a{};
+  a.n_b = (int32_t)p->n_b;
+  a.ci = (int32_t)p->n_ci;
+  a.co = (int32_t)p->n_co;
+  for (int d = 0; d < 3; ++d) {
+    a.k[d] = p->ksize[d];
+    a.s[d] = p->stride[d];
+    a.dil[d] = p->dilation[d];
+  }
+  a.nchunks = wgrad_chunks(p);
+  a.slot = (int64_t)a.k[0] * a.k[1] * a.k[2] * a.ci * a.co + a.co;
+  dim3 grid((unsigned)((a.k[0] * a.k[1] + 3) / 4), (unsigned)(((a.ci + 31) / 32) * ((a.co + 31) / 32)),
+            (unsigned)(p->n_workers * a.nchunks));
+  {
+    ProfScope prof("conv_bwd_weight_mfma", st);
+    if (a.k[2] <= 3)
+      hipLaunchKernelGGL(wgrad_mfma_kernel<3>, grid, dim3(256), 0, st, p->d_workers, p->tab_x.dev, p->tab_dy.dev,
+                         partial, a);
+    else if (a.k[2] <= 5)
+      hipLaunchKernelGGL(wgrad_mfma_kernel<5>, grid, dim3(256), 0, st, p->d_workers, p->tab_x.dev, p->tab_dy.dev,
+                         partial, a);
+    else
+      hipLaunchKernelGGL(wgrad_mfma_kernel<8>, grid, dim3(256), 0, st, p->d_workers, p->tab_x.dev, p->tab_dy.dev,
+                         partial, a);
+  }
+  {
+    ProfScope prof("conv_bias_partial", st);
+    hipLaunchKernelGGL(bias_partial_kernel, dim3((unsigned)(p->n_workers * a.nchunks)), dim3(256), 0, st, p->d_workers,
+                       p->tab_dy.dev, partial, a);
+  }
+  return DISTDL_OK;
+}
+
+}  // namespace distdl

@@ -50,6 +50,14 @@ CONV_FULL = [
     ("cfg5u", dict(in_shape=(21, 23, 22), P=(2, 2, 2), c_in=32, c_out=32), False),
     ("cfg2", dict(in_shape=(19, 23), n_b=3, c_in=3, c_out=5, P=(2, 3), ksize=(3, 4), stride=(2, 1),
                   padding=(1, 2), dilation=(1, 2)), True),
+    # matrix-core path: channel counts that are multiples of 4, several output-channel tiles, odd geometry
+    ("cfg2", dict(in_shape=(23, 41), n_b=2, c_in=4, c_out=40, P=(2, 3), ksize=(3, 4), stride=(2, 1),
+                  padding=(1, 2), dilation=(1, 2)), True),
+    ("cfg1", dict(in_shape=(200,), n_b=3, c_in=8, c_out=8, P=(3,), ksize=(7,), stride=(3,), padding=(2,)), True),
+    ("cfg5", dict(in_shape=(13, 17, 40), P=(2, 2, 2), c_in=12, c_out=20, ksize=(2, 3, 4), stride=(1, 2, 3),
+                  padding=(1, 0, 2)), False),
+    ("cfg5", dict(in_shape=(18, 18, 70), P=(1, 2, 1), c_in=32, c_out=32, ksize=(5, 5, 5), stride=(2, 2, 2),
+                  padding=(2, 2, 2)), True),
     ("cfg2", dict(in_shape=(28, 28), n_b=4, c_in=1, c_out=6, ksize=(5, 5), padding=(2, 2)), True),   # cfg4 conv1
     ("cfg2", dict(in_shape=(14, 14), n_b=4, c_in=6, c_out=16, ksize=(5, 5), padding=(0, 0)), True),  # cfg4 conv2
 ]
