@@ -77,6 +77,8 @@ class ConvWorkload:
             "halo_fwd": ("hbm", (2 * stats["halo_cells"] + stats["pad_cells"]) * per_cell),
             "halo_adj": ("hbm", (2 * stats["halo_cells"] + 2 * stats["band_cells"] + stats["pad_cells"]) * per_cell),
             "conv_fwd": ("mfma", self.flops_fwd),
+            # launched once per stride-parity class; the classes share the layer's flops
+            "conv_bwd_data_mfma": ("mfma", self.flops_fwd / _prod(c["stride"])),
             "conv_bwd_data": ("mfma", self.flops_fwd),
             "conv_bwd_weight": ("mfma", self.flops_fwd),
             "conv_reduce_dw": ("hbm", None),     # filled from the workspace geometry below

@@ -19,11 +19,12 @@ struct CorrArgs {
   int32_t is[3];   // input step per output step
   int32_t s[3];    // layer stride
   int32_t par[3];  // parity class (mode 1)
-  int32_t oh_t;    // output rows (dimension 1) per workgroup tile
+  int32_t tr, tc;  // rows x columns (dimensions 1, 2) of a workgroup's output window
   int32_t R, Cw, CwQ;  // patch rows, cells per row, cells per residue class of the row
   int32_t a_vec4;      // patch size in 16-byte units
   int32_t tiles_max;   // tiles of the largest worker
   const float* wt;     // weights in staging order
+  const int* tapinfo;  // device tables behind the weights: 8 plane offsets, then one patch offset per (t1, t2)
   const float* bias;   // may be null
 };
 

@@ -6,7 +6,7 @@
 //   used (a) for the forward pass (in = x^, out = y) and (b) once per stride
 //   parity class for the data gradient (in = dy, out = the cells of dx^ whose
 //   coordinate is congruent to that class; out-of-range dy reads as zero).
-//   A workgroup owns a tile of OH_T output rows x 32 output columns; per
+//   A workgroup owns a window of tr x tc output positions (128 or 256); per
 //   (tap plane, 8-channel chunk) it stages the input patch and the weights in
 //   LDS once and all taps of that plane read it from there.
 // wgrad_mfma_kernel: dw^[tap][ci][co] = sum_pos x^[cell(pos,tap)][ci] dy[pos][co]
@@ -55,12 +55,14 @@ __host__ __device__ inline PerWorker derive(const WorkerDev& wd, const CorrArgs&
 }
 
 __host__ __device__ inline int64_t tiles_of(const PerWorker& g, const CorrArgs& a) {
-  return (int64_t)a.n_b * g.nq[0] * ((g.nq[1] + a.oh_t - 1) / a.oh_t) * ((g.nq[2] + 31) / 32) * a.ntn;
+  return (int64_t)a.n_b * g.nq[0] * ((g.nq[1] + a.tr - 1) / a.tr) * ((g.nq[2] + a.tc - 1) / a.tc) * a.ntn;
 }
 
 constexpr int kMaxPieces = 14;
+constexpr int kMaxBPieces = 8;  // weight pieces per thread held in registers (32 taps per plane)
 
-template <int MT>
+// MT: 32-position M-tiles per wave; PA / PB: 16-byte patch / weight pieces per thread and stage
+template <int MT, int PA, int PB>
 __global__ __launch_bounds__(256, 2) void corr_mfma_kernel(const WorkerDev* __restrict__ workers,
                                                            void* const* in_bufs, void* const* out_bufs, CorrArgs a) {
   extern __shared__ float4 lds[];
@@ -78,9 +80,9 @@ __global__ __launch_bounds__(256, 2) void corr_mfma_kernel(const WorkerDev* __re
   const PerWorker g = derive(wd, a);
   if ((int64_t)tile >= tiles_of(g, a)) return;
 
-  const int nt2tiles = (g.nq[2] + 31) / 32, nt1tiles = (g.nq[1] + a.oh_t - 1) / a.oh_t;
-  const int q2_0 = (tile % nt2tiles) * 32; tile /= nt2tiles;
-  const int q1_0 = (tile % nt1tiles) * a.oh_t; tile /= nt1tiles;
+  const int nt2tiles = (g.nq[2] + a.tc - 1) / a.tc, nt1tiles = (g.nq[1] + a.tr - 1) / a.tr;
+  const int q2_0 = (tile % nt2tiles) * a.tc; tile /= nt2tiles;
+  const int q1_0 = (tile % nt1tiles) * a.tr; tile /= nt1tiles;
   const int ntile = tile % a.ntn; tile /= a.ntn;
   const int q0 = tile % g.nq[0];
   const int n = tile / g.nq[0];
@@ -93,10 +95,10 @@ __global__ __launch_bounds__(256, 2) void corr_mfma_kernel(const WorkerDev* __re
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, h = lane >> 5, m = lane & 31;
 
   // per-thread patch pieces (16 bytes each): fixed for the whole tile
-  int32_t goff[kMaxPieces], loff[kMaxPieces];
+  int32_t goff[PA], loff[PA];
   const int npieces = a.R * a.Cw * 2;
 #pragma unroll
-  for (int i = 0; i < kMaxPieces; ++i) {
+  for (int i = 0; i < PA; ++i) {
     const int piece = tid + i * 256;
     goff[i] = -1;
     loff[i] = -1;
@@ -110,6 +112,17 @@ __global__ __launch_bounds__(256, 2) void corr_mfma_kernel(const WorkerDev* __re
     }
   }
 
+  // The workgroup's 128*MT output positions form a tr x tc window, row-major;
+  // lane m of M-tile (wave, mt) holds window position (wave*MT + mt)*32 + m.
+  int32_t abase[MT];
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt) {
+    const int pidx = (wave * MT + mt) * 32 + m;
+    int wr = pidx / a.tc, wc = pidx - wr * a.tc;
+    if (wr >= a.tr) wr = 0, wc = 0;  // idle position: read something in range, never stored
+    abase[mt] = wr * a.is[1] * 2 * a.is[2] * a.CwQ + wc;
+  }
+
   floatx16 acc[MT];
 #pragma unroll
   for (int t = 0; t < MT; ++t)
@@ -117,47 +130,110 @@ __global__ __launch_bounds__(256, 2) void corr_mfma_kernel(const WorkerDev* __re
 
   const int ncc = (a.kc + 7) / 8;
   const int nb_vec4 = a.nt[1] * a.nt[2] * 64;
-  for (int t0 = 0; t0 < a.nt[0]; ++t0) {
-    const int i0 = g.in_base[0] + q0 * a.is[0] + a.tapoff[0][t0];
-    if (i0 < 0 || i0 >= g.in_ext[0]) continue;  // whole tap plane out of range: contributes zero
-    const float* plane = in + n * sin + (size_t)i0 * si0;
-    for (int cc = 0; cc < ncc; ++cc) {
-      // stage the input patch: rows x cells x 8 channels
+  const int ntaps = a.nt[1] * a.nt[2];
+
+  // A stage is one (tap plane t0, 8-channel chunk cc); stages whose plane lies
+  // outside the input contribute zero and are skipped.  The global loads of
+  // stage s+1 are issued into registers before the MFMAs of stage s and written
+  // to LDS after them.
+  const int* __restrict__ tapinfo = a.tapinfo;  // [0..7]: plane offsets, [8..]: patch offset per (t1, t2)
+  const int nt0 = a.nt[0], in_base0 = g.in_base[0] + q0 * a.is[0], in_ext0 = g.in_ext[0];
+  auto plane_ok = [&](int t0) {
+    const int i0 = in_base0 + tapinfo[t0];
+    return i0 >= 0 && i0 < in_ext0;
+  };
+  auto next_stage = [&](int st) {  // smallest valid stage index > st, or nt0*ncc
+    ++st;
+    while (st < nt0 * ncc && !plane_ok(st / ncc)) st = (st / ncc + 1) * ncc;
+    return st;
+  };
+  const int kc = a.kc;
+  const float4* __restrict__ wbase = (const float4*)a.wt + (size_t)ntile * nt0 * ncc * nb_vec4;
+  float4 ra[PA], rb[PB];
 #pragma unroll
-      for (int i = 0; i < kMaxPieces; ++i) {
-        if (loff[i] >= 0) {
-          float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-          const int ph = (tid + i * 256) & 1;
-          if (goff[i] >= 0 && cc * 8 + ph * 4 < a.kc) v = *(const float4*)(plane + goff[i] + cc * 8);
-          As[loff[i]] = v;
-        }
-      }
-      // stage the weights of this tap plane and channel chunk
-      const float4* wsrc = (const float4*)a.wt + ((size_t)(ntile * a.nt[0] + t0) * ncc + cc) * nb_vec4;
-      for (int p = tid; p < nb_vec4; p += 256) Bs[p] = wsrc[p];
-      __syncthreads();
-      for (int t1 = 0; t1 < a.nt[1]; ++t1) {
-        const int rel1 = a.tapoff[1][t1] - a.tapmin[1];
-        for (int t2 = 0; t2 < a.nt[2]; ++t2) {
-          const int rel2 = a.tapoff[2][t2] - a.tapmin[2];
-          const int res = rel2 % a.is[2], cq = rel2 / a.is[2];
-          const float4 b = Bs[((t1 * a.nt[2] + t2) * 2 + h) * 32 + m];
+  for (int i = 0; i < PA; ++i) ra[i] = make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
-          for (int mt = 0; mt < MT; ++mt) {
-            const int rr = (wave * MT + mt) * a.is[1] + rel1;
-            const float4 av = As[((rr * 2 + h) * a.is[2] + res) * a.CwQ + m + cq];
-            acc[mt] = __builtin_amdgcn_mfma_f32_32x32x2f32(av.x, b.x, acc[mt], 0, 0, 0);
-            acc[mt] = __builtin_amdgcn_mfma_f32_32x32x2f32(av.y, b.y, acc[mt], 0, 0, 0);
-            acc[mt] = __builtin_amdgcn_mfma_f32_32x32x2f32(av.z, b.z, acc[mt], 0, 0, 0);
-            acc[mt] = __builtin_amdgcn_mfma_f32_32x32x2f32(av.w, b.w, acc[mt], 0, 0, 0);
-          }
+  for (int i = 0; i < PB; ++i) rb[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+  auto load_stage = [&](int st) {
+    const int t0 = st / ncc, cc = st - t0 * ncc;
+    const float* plane = in + n * sin + (size_t)(in_base0 + tapinfo[t0]) * si0 + cc * 8;
+#pragma unroll
+    for (int i = 0; i < PA; ++i) {
+      const int ph = (tid + i * 256) & 1;
+      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (goff[i] >= 0 && cc * 8 + ph * 4 < kc) v = *(const float4*)(plane + goff[i]);
+      ra[i] = v;
+    }
+    const float4* wsrc = wbase + (size_t)st * nb_vec4;
+#pragma unroll
+    for (int i = 0; i < PB; ++i) {
+      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (tid + i * 256 < nb_vec4) v = wsrc[tid + i * 256];
+      rb[i] = v;
+    }
+  };
+  auto write_stage = [&]() {
+#pragma unroll
+    for (int i = 0; i < PA; ++i)
+      if (loff[i] >= 0) As[loff[i]] = ra[i];
+#pragma unroll
+    for (int i = 0; i < PB; ++i)
+      if (tid + i * 256 < nb_vec4) Bs[tid + i * 256] = rb[i];
+  };
+  // per-tap patch offsets, tabulated once in LDS (read back as a broadcast)
+  int* tap_tab = (int*)(Bs + nb_vec4);
+  if (tid < ntaps) tap_tab[tid] = tapinfo[8 + tid];
+  const int hoff = h * a.is[2] * a.CwQ;
+  auto tap_offsets = [&](int tap, int& tapo, int& bo) {
+    tapo = tap_tab[tap] + hoff;
+    bo = (tap * 2 + h) * 32 + m;
+  };
+
+  const int nstages = nt0 * ncc;
+  int st = next_stage(-1);
+  if (st < nstages) {
+    load_stage(st);
+    write_stage();
+    __syncthreads();
+    while (true) {
+      const int nxt = next_stage(st);
+      if (nxt < nstages) load_stage(nxt);
+      // all taps of this plane from LDS; the operands of tap i+1 are read while tap i multiplies
+      int tapo, bo;
+      tap_offsets(0, tapo, bo);
+      float4 b = Bs[bo], av[MT];
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) av[mt] = As[abase[mt] + tapo];
+      for (int tap = 0; tap < ntaps; ++tap) {
+        float4 bn = b, avn[MT];
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) avn[mt] = av[mt];
+        if (tap + 1 < ntaps) {
+          tap_offsets(tap + 1, tapo, bo);
+          bn = Bs[bo];
+#pragma unroll
+          for (int mt = 0; mt < MT; ++mt) avn[mt] = As[abase[mt] + tapo];
         }
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+          acc[mt] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[mt].x, b.x, acc[mt], 0, 0, 0);
+          acc[mt] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[mt].y, b.y, acc[mt], 0, 0, 0);
+          acc[mt] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[mt].z, b.z, acc[mt], 0, 0, 0);
+          acc[mt] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[mt].w, b.w, acc[mt], 0, 0, 0);
+        }
+        b = bn;
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) av[mt] = avn[mt];
       }
+      __syncthreads();  // everyone is done reading this stage
+      if (nxt >= nstages) break;
+      write_stage();
       __syncthreads();
+      st = nxt;
     }
   }
 
-  // store: register v of lane (h, m) is output column q2_0 + 8*(v/4) + 4*h + v%4, channel ntile*32 + m
+  // store: register v of lane (h, m) is window position (wave*MT + mt)*32 + 8*(v/4) + 4*h + v%4, channel ntile*32 + m
   const int ch = ntile * 32 + m;
   if (ch >= a.nc) return;
   const float bias = a.bias ? a.bias[ch] : 0.f;
@@ -166,13 +242,14 @@ __global__ __launch_bounds__(256, 2) void corr_mfma_kernel(const WorkerDev* __re
   float* obase = out + n * son + (size_t)(g.out_base[0] + g.os[0] * q0) * so0 + ch;
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) {
-    const int q1 = q1_0 + wave * MT + mt;
-    if (q1 >= g.nq[1]) continue;
-    float* orow = obase + (size_t)(g.out_base[1] + g.os[1] * q1) * so1;
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
-      const int q2 = q2_0 + 8 * (v / 4) + 4 * h + (v % 4);
-      if (q2 < g.nq[2]) orow[(size_t)(g.out_base[2] + g.os[2] * q2) * so2] = acc[mt][v] + bias;
+      const int pidx = (wave * MT + mt) * 32 + 8 * (v / 4) + 4 * h + (v % 4);
+      const int wr = pidx / a.tc, wc = pidx - wr * a.tc;
+      const int q1 = q1_0 + wr, q2 = q2_0 + wc;
+      if (wr < a.tr && q1 < g.nq[1] && q2 < g.nq[2])
+        obase[(size_t)(g.out_base[1] + g.os[1] * q1) * so1 + (size_t)(g.out_base[2] + g.os[2] * q2) * so2] =
+            acc[mt][v] + bias;
     }
   }
 }
@@ -186,6 +263,15 @@ __global__ __launch_bounds__(256) void corr_weights_kernel(const float* __restri
   const int ncc = (a.kc + 7) / 8;
   const int64_t total = (int64_t)a.ntn * a.nt[0] * ncc * a.nt[1] * a.nt[2] * 256;
   int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (blockIdx.x == 0) {  // the tap tables the correlation kernel reads, stored behind the weights
+    int* tapinfo = (int*)(dst + total);
+    if (threadIdx.x < 8) tapinfo[threadIdx.x] = threadIdx.x < a.nt[0] ? a.tapoff[0][threadIdx.x] : 0;
+    if ((int)threadIdx.x < a.nt[1] * a.nt[2]) {
+      const int t1 = threadIdx.x / a.nt[2], t2 = threadIdx.x - t1 * a.nt[2];
+      const int rel1 = a.tapoff[1][t1] - a.tapmin[1], rel2 = a.tapoff[2][t2] - a.tapmin[2];
+      tapinfo[8 + threadIdx.x] = ((rel1 * 2) * a.is[2] + rel2 % a.is[2]) * a.CwQ + rel2 / a.is[2];
+    }
+  }
   if (idx >= total) return;
   const int j = idx & 3, nn = (idx >> 2) & 31, hh = (idx >> 7) & 1;
   int64_t r = idx >> 8;
@@ -211,7 +297,7 @@ constexpr int kMaxK2 = 8;
 // grid: (tap-row groups of 4, ci tiles * co tiles, workers * nchunks); wave w of a block owns tap row
 // (t0, t1) = group*4 + w and all k2 taps of that row.
 template <int K2>
-__global__ __launch_bounds__(256) void wgrad_mfma_kernel(const WorkerDev* __restrict__ workers, void* const* x_bufs,
+__global__ __launch_bounds__(256, 2) void wgrad_mfma_kernel(const WorkerDev* __restrict__ workers, void* const* x_bufs,
                                                          void* const* dy_bufs, float* __restrict__ partial,
                                                          WgradArgs a) {
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, h = lane >> 5, m = lane & 31;
@@ -237,27 +323,42 @@ __global__ __launch_bounds__(256) void wgrad_mfma_kernel(const WorkerDev* __rest
   const int64_t sy2 = a.co, sy1 = (int64_t)wd.out[2] * sy2;
   const int nrows = a.n_b * wd.out[0] * wd.out[1];
   const int per = (nrows + a.nchunks - 1) / a.nchunks;
-  const int row_end = min(nrows, (chunk + 1) * per);
-  const int O2 = wd.out[2];
-  for (int row = chunk * per; row < row_end; ++row) {
-    const int o1 = row % wd.out[1];
-    const int r2 = row / wd.out[1];
-    const int o0 = r2 % wd.out[0], n = r2 / wd.out[0];
-    const float* xrow = x + n * sxn + (int64_t)(wd.origin[0] + o0 * a.s[0] + t0 * a.dil[0]) * sx0 +
-                        (int64_t)(wd.origin[1] + o1 * a.s[1] + t1 * a.dil[1]) * sx1 + (int64_t)wd.origin[2] * sx2 + ci;
-    const float* dyrow = dy + (int64_t)row * sy1 + co;
-    // two output positions per MFMA: lanes 0-31 take o2, lanes 32-63 take o2 + 1
-    for (int o2 = 0; o2 < O2; o2 += 2) {
-      const int p = o2 + h;
-      const bool pos_ok = p < O2;
-      const float b = (pos_ok && co_ok) ? dyrow[(int64_t)p * sy2] : 0.f;
-      float av[K2];
-#pragma unroll
-      for (int t2 = 0; t2 < K2; ++t2)
-        av[t2] = (pos_ok && ci_ok && t2 < a.k[2]) ? xrow[(int64_t)(p * a.s[2] + t2 * a.dil[2]) * sx2] : 0.f;
-#pragma unroll
-      for (int t2 = 0; t2 < K2; ++t2) acc[t2] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[t2], b, acc[t2], 0, 0, 0);
+  const int row_begin = chunk * per, row_end = min(nrows, (chunk + 1) * per);
+  const int O2 = wd.out[2], pairs = (O2 + 1) / 2;
+  // two output positions per MFMA: lanes 0-31 take column 2*pr, lanes 32-63 column 2*pr + 1.
+  // The loads of step i+1 are issued before the MFMAs of step i.
+  int row = row_begin, pr = 0;
+  const float* xrow = nullptr;
+  const float* dyrow = nullptr;
+  auto fetch = [&](float& b, float (&av)[K2]) {
+    if (pr == 0) {
+      const int o1 = row % wd.out[1];
+      const int r2 = row / wd.out[1];
+      const int o0 = r2 % wd.out[0], n = r2 / wd.out[0];
+      xrow = x + n * sxn + (int64_t)(wd.origin[0] + o0 * a.s[0] + t0 * a.dil[0]) * sx0 +
+             (int64_t)(wd.origin[1] + o1 * a.s[1] + t1 * a.dil[1]) * sx1 + (int64_t)wd.origin[2] * sx2 + ci;
+      dyrow = dy + (int64_t)row * sy1 + co;
     }
+    const int p = 2 * pr + h;
+    const bool pos_ok = p < O2;
+    b = (pos_ok && co_ok) ? dyrow[(int64_t)p * sy2] : 0.f;
+#pragma unroll
+    for (int t2 = 0; t2 < K2; ++t2)
+      av[t2] = (pos_ok && ci_ok && t2 < a.k[2]) ? xrow[(int64_t)(p * a.s[2] + t2 * a.dil[2]) * sx2] : 0.f;
+    if (++pr == pairs) pr = 0, ++row;
+  };
+  const int64_t steps = (int64_t)max(row_end - row_begin, 0) * pairs;
+  float b0 = 0.f, b1 = 0.f, a0[K2], a1[K2];
+#pragma unroll
+  for (int t2 = 0; t2 < K2; ++t2) a0[t2] = a1[t2] = 0.f;
+  if (steps > 0) fetch(b0, a0);
+  for (int64_t it = 0; it < steps; ++it) {
+    if (it + 1 < steps) fetch(b1, a1);
+#pragma unroll
+    for (int t2 = 0; t2 < K2; ++t2) acc[t2] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0[t2], b0, acc[t2], 0, 0, 0);
+    b0 = b1;
+#pragma unroll
+    for (int t2 = 0; t2 < K2; ++t2) a0[t2] = a1[t2];
   }
   // acc[t2] register v of lane (h, m): dw^[tap][ci = ci_t*32 + 8*(v/4) + 4h + v%4][co = co_t*32 + m]
   float* pbase = partial + (size_t)blockIdx.z * a.slot;
@@ -290,8 +391,15 @@ __global__ __launch_bounds__(256) void bias_partial_kernel(const WorkerDev* __re
     // 8 position lanes x 32 channels
     const int co = c0 + (threadIdx.x & 31);
     float acc = 0.f;
-    if (co < a.co)
-      for (int64_t p = p0 + (threadIdx.x >> 5); p < p1; p += 8) acc += dy[p * a.co + co];
+    if (co < a.co) {
+      float part[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+      int64_t p = p0 + (threadIdx.x >> 5);
+      for (; p + 56 < p1; p += 64)
+#pragma unroll
+        for (int u = 0; u < 8; ++u) part[u] += dy[(p + 8 * u) * a.co + co];
+      for (; p < p1; p += 8) part[0] += dy[p * a.co + co];
+      acc = ((part[0] + part[1]) + (part[2] + part[3])) + ((part[4] + part[5]) + (part[6] + part[7]));
+    }
     red[threadIdx.x] = acc;
     __syncthreads();
     if (threadIdx.x < 32 && co < a.co) {
@@ -305,10 +413,22 @@ __global__ __launch_bounds__(256) void bias_partial_kernel(const WorkerDev* __re
 
 // ---- host side ------------------------------------------------------------------
 
-static int lds_bytes(const CorrArgs& a) { return (a.a_vec4 + a.nt[1] * a.nt[2] * 64) * 16; }
+static int lds_bytes(const CorrArgs& a) { return (a.a_vec4 + a.nt[1] * a.nt[2] * 64) * 16 + a.nt[1] * a.nt[2] * 4; }
 
-static void finish_args(CorrArgs& a, int mt) {
-  a.oh_t = 4 * mt;
+static void finish_args(CorrArgs& a, int mt, int nq2max) {
+  // window of 128*mt positions: full output rows when they fit, else 32-multiples
+  const int cap = 128 * mt;
+  if (nq2max <= cap) {
+    a.tc = std::max(nq2max, 1);
+  } else {
+    a.tc = 32;
+    double best = 1e30;
+    for (int c = 32; c <= cap; c += 32) {
+      double waste = (double)((nq2max + c - 1) / c) * c / nq2max;
+      if (waste < best - 1e-9 || (waste < best + 1e-9 && c > a.tc)) best = waste, a.tc = c;
+    }
+  }
+  a.tr = std::max(1, cap / a.tc);
   for (int d = 0; d < 3; ++d) {
     int lo = 0, hi = 0;
     for (int i = 0; i < a.nt[d]; ++i) {
@@ -318,22 +438,31 @@ static void finish_args(CorrArgs& a, int mt) {
     a.tapmin[d] = lo;
     a.tapspan[d] = hi - lo;
   }
-  a.R = (a.oh_t - 1) * a.is[1] + a.tapspan[1] + 1;
-  a.Cw = 31 * a.is[2] + a.tapspan[2] + 1;
+  a.R = (a.tr - 1) * a.is[1] + a.tapspan[1] + 1;
+  a.Cw = (a.tc - 1) * a.is[2] + a.tapspan[2] + 1;
   a.CwQ = (a.Cw + a.is[2] - 1) / a.is[2];
   a.a_vec4 = a.R * 2 * a.is[2] * a.CwQ;
 }
 
 // Chooses the rows-per-wave so that two workgroups fit in a CU's LDS when
 // possible; returns 0 when the patch does not fit at all.
-static int choose_mt(CorrArgs& a) {
+static int choose_mt(CorrArgs& a, int nq2max) {
   for (int mt : {2, 1}) {
-    finish_args(a, mt);
+    finish_args(a, mt, nq2max);
     if (lds_bytes(a) <= 80 * 1024 && a.R * a.Cw * 2 <= kMaxPieces * 256) return mt;
   }
-  finish_args(a, 1);
+  finish_args(a, 1, nq2max);
+  if (lds_bytes(a) <= 160 * 1024 && a.R * a.Cw * 2 <= kMaxPieces * 256) return 1;
+  // last resort: a 32-wide window
+  finish_args(a, 1, 32);
   if (lds_bytes(a) <= 160 * 1024 && a.R * a.Cw * 2 <= kMaxPieces * 256) return 1;
   return 0;
+}
+
+static int max_nq2(const distdl_plan* p, const CorrArgs& a) {
+  int mx = 0;
+  for (const WorkerDev& wd : p->workers) mx = std::max(mx, derive(wd, a).nq[2]);
+  return mx;
 }
 
 bool corr_mfma_supported(const distdl_plan* p) {
@@ -341,6 +470,7 @@ bool corr_mfma_supported(const distdl_plan* p) {
   if (p->n_ci % 4 || p->n_co % 4) return false;  // 16-byte channel pieces
   for (int d = 0; d < 3; ++d)
     if (p->ksize[d] > 8) return false;
+  if (p->ksize[1] * p->ksize[2] > kMaxBPieces * 4) return false;  // weight pieces held in registers per stage
   return true;
 }
 
@@ -398,10 +528,12 @@ static int64_t max_tiles(const distdl_plan* p, const CorrArgs& a) {
 static size_t corr_weight_elems(const CorrArgs& a) {
   return (size_t)a.ntn * a.nt[0] * ((a.kc + 7) / 8) * a.nt[1] * a.nt[2] * 256;
 }
+// weights + the tap tables (8 + 64 ints), kept 16-byte aligned
+static size_t corr_scratch_elems(const CorrArgs& a) { return corr_weight_elems(a) + 72; }
 
 static int launch_corr(distdl_plan* p, CorrArgs a, const float* w, float* wscratch, const float* bias, void** in_tab,
                        void** out_tab, const char* name, hipStream_t st) {
-  const int mt = choose_mt(a);
+  const int mt = choose_mt(a, max_nq2(p, a));
   if (mt == 0) return set_error(DISTDL_ERR_UNSUPPORTED, "conv: kernel footprint does not fit in LDS");
   a.tiles_max = (int32_t)max_tiles(p, a);
   if (a.tiles_max == 0) return DISTDL_OK;
@@ -409,22 +541,30 @@ static int launch_corr(distdl_plan* p, CorrArgs a, const float* w, float* wscrat
   a.bias = bias;
   const int taps = p->ksize[0] * p->ksize[1] * p->ksize[2];
   const size_t welems = corr_weight_elems(a);
-  if (welems) {
+  a.tapinfo = (const int*)(wscratch + welems);
+  {
     ProfScope prof("conv_relayout_w", st);
-    hipLaunchKernelGGL(corr_weights_kernel, dim3((unsigned)((welems + 255) / 256)), dim3(256), 0, st, w, wscratch, a,
-                       (int)p->n_ci, (int)p->n_co, taps, p->ksize[1], p->ksize[2]);
+    hipLaunchKernelGGL(corr_weights_kernel, dim3((unsigned)std::max<size_t>(1, (welems + 255) / 256)), dim3(256), 0,
+                       st, w, wscratch, a, (int)p->n_ci, (int)p->n_co, taps, p->ksize[1], p->ksize[2]);
   }
   int64_t blocks = (int64_t)a.tiles_max * p->n_workers;
   blocks = (blocks + 7) / 8 * 8;
   const int lds = lds_bytes(a);
+  const bool small = a.R * a.Cw * 2 <= 4 * 256 && a.nt[1] * a.nt[2] * 64 <= 3 * 256;
   ProfScope prof(name, st);
-  if (mt == 2) {
-    DISTDL_HIP_TRY(hipFuncSetAttribute((const void*)corr_mfma_kernel<2>, hipFuncAttributeMaxDynamicSharedMemorySize, lds));
-    hipLaunchKernelGGL(corr_mfma_kernel<2>, dim3((unsigned)blocks), dim3(256), lds, st, p->d_workers, in_tab, out_tab, a);
-  } else {
-    DISTDL_HIP_TRY(hipFuncSetAttribute((const void*)corr_mfma_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize, lds));
-    hipLaunchKernelGGL(corr_mfma_kernel<1>, dim3((unsigned)blocks), dim3(256), lds, st, p->d_workers, in_tab, out_tab, a);
-  }
+#define DISTDL_LAUNCH_CORR(MT_, PA_, PB_)                                                                            \
+  do {                                                                                                               \
+    if (lds > 64 * 1024)                                                                                             \
+      DISTDL_HIP_TRY(hipFuncSetAttribute((const void*)corr_mfma_kernel<MT_, PA_, PB_>,                               \
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, lds));                          \
+    hipLaunchKernelGGL((corr_mfma_kernel<MT_, PA_, PB_>), dim3((unsigned)blocks), dim3(256), lds, st, p->d_workers,  \
+                       in_tab, out_tab, a);                                                                          \
+  } while (0)
+  if (mt == 2 && small) DISTDL_LAUNCH_CORR(2, 4, 3);
+  else if (mt == 2) DISTDL_LAUNCH_CORR(2, kMaxPieces, kMaxBPieces);
+  else if (small) DISTDL_LAUNCH_CORR(1, 4, 3);
+  else DISTDL_LAUNCH_CORR(1, kMaxPieces, kMaxBPieces);
+#undef DISTDL_LAUNCH_CORR
   return DISTDL_OK;
 }
 
@@ -442,8 +582,7 @@ static int ensure_wscratch(distdl_plan* p, size_t elems) {
 
 int conv_fwd_mfma(distdl_plan* p, const float* w, const float* bias, hipStream_t st) {
   CorrArgs a = forward_args(p);
-  finish_args(a, 1);
-  int rc = ensure_wscratch(p, std::max(corr_weight_elems(a), bwd_scratch_elems(p)));
+  int rc = ensure_wscratch(p, std::max(corr_scratch_elems(a), bwd_scratch_elems(p)));
   if (rc) return rc;
   return launch_corr(p, a, w, p->d_wt, bias, p->tab_x.dev, p->tab_y.dev, "conv_fwd_mfma", st);
 }
@@ -455,14 +594,14 @@ size_t bwd_scratch_elems(const distdl_plan* p) {
       for (int p2 = 0; p2 < p->stride[2]; ++p2) {
         const int par[3] = {p0, p1, p2};
         CorrArgs a = class_args(p, par);
-        total += corr_weight_elems(a);
+        total += corr_scratch_elems(a);
       }
   return total;
 }
 
 int conv_bwd_data_mfma(distdl_plan* p, const float* w, hipStream_t st) {
   CorrArgs fa = forward_args(p);
-  int rc = ensure_wscratch(p, std::max(corr_weight_elems(fa), bwd_scratch_elems(p)));
+  int rc = ensure_wscratch(p, std::max(corr_scratch_elems(fa), bwd_scratch_elems(p)));
   if (rc) return rc;
   size_t at = 0;
   for (int p0 = 0; p0 < p->stride[0]; ++p0)
@@ -472,7 +611,7 @@ int conv_bwd_data_mfma(distdl_plan* p, const float* w, hipStream_t st) {
         CorrArgs a = class_args(p, par);
         if ((rc = launch_corr(p, a, w, p->d_wt + at, nullptr, p->tab_dy.dev, p->tab_dx.dev, "conv_bwd_data_mfma", st)))
           return rc;
-        at += corr_weight_elems(a);
+        at += corr_scratch_elems(a);
       }
   return DISTDL_OK;
 }
