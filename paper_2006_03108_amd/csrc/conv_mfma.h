@@ -32,6 +32,7 @@ struct WgradArgs {
   int32_t n_b, ci, co;
   int32_t k[3], s[3], dil[3];
   int32_t nchunks;  // position chunks per worker
+  int32_t ncell;    // input cells the taps of 32 consecutive output columns read
   int64_t slot;     // floats per (worker, chunk) partial: taps*ci*co + co
 };
 

@@ -374,6 +374,122 @@ __global__ __launch_bounds__(256, 2) void wgrad_mfma_kernel(const WorkerDev* __r
   }
 }
 
+// Same contraction with LDS staging: each wave copies, per 32 output columns, the input-row segment
+// its taps read (ncell cells x 32 channels) and the dy segment (32 x 32) into a private LDS area with
+// 16-byte loads, then feeds all K2 taps from there.  Every cell is fetched once per tap row instead of
+// once per tap; no workgroup barrier is needed because a wave only reads what it wrote itself.
+// Requires channel counts that are multiples of 4, 16-byte aligned buffers and ncell <= 64*XP/8.
+template <int K2, int XP>
+__global__ __launch_bounds__(256, 2) void wgrad_lds_kernel(const WorkerDev* __restrict__ workers, void* const* x_bufs,
+                                                           void* const* dy_bufs, float* __restrict__ partial,
+                                                           WgradArgs a) {
+  extern __shared__ float4 wg_lds[];
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, h = lane >> 5, m = lane & 31;
+  const int trow = blockIdx.x * 4 + wave;
+  if (trow >= a.k[0] * a.k[1]) return;  // no workgroup barrier below
+  const int t0 = trow / a.k[1], t1 = trow - t0 * a.k[1];
+  const int nco_t = (a.co + 31) / 32;
+  const int ci_t = blockIdx.y / nco_t, co_t = blockIdx.y - ci_t * nco_t;
+  const int worker = blockIdx.z / a.nchunks, chunk = blockIdx.z - worker * a.nchunks;
+  const WorkerDev wd = workers[worker];
+  const float* __restrict__ x = (const float*)x_bufs[worker];
+  const float* __restrict__ dy = (const float*)dy_bufs[worker];
+  const int ncell = a.ncell;
+  float4* xs4 = wg_lds + (size_t)wave * (ncell + 32) * 8;  // [ncell][32 ch]
+  float4* ys4 = xs4 + ncell * 8;                           // [32 pos][32 ch]
+  const float* xs = (const float*)xs4;
+  const float* ys = (const float*)ys4;
+
+  floatx16 acc[K2];
+#pragma unroll
+  for (int t = 0; t < K2; ++t)
+    for (int v = 0; v < 16; ++v) acc[t][v] = 0.f;
+
+  const int64_t sx2 = a.ci, sx1 = (int64_t)wd.buf[2] * sx2, sx0 = (int64_t)wd.buf[1] * sx1,
+                sxn = (int64_t)wd.buf[0] * sx0;
+  const int64_t sy2 = a.co, sy1 = (int64_t)wd.out[2] * sy2;
+  const int nrows = a.n_b * wd.out[0] * wd.out[1];
+  const int per = (nrows + a.nchunks - 1) / a.nchunks;
+  const int row_begin = chunk * per, row_end = min(nrows, (chunk + 1) * per);
+  const int O2 = wd.out[2], nseg = (O2 + 31) / 32;
+  const int row_cells = wd.buf[2] - wd.origin[2];  // cells from the first tap of column 0 to the row end
+  // this lane's 16-byte pieces: piece j = lane + 64*i covers cell (or position) j / 8, channels 4*(j % 8)..
+  const int q4 = (lane & 7) * 4;
+  const bool xch_ok = ci_t * 32 + q4 < a.ci, ych_ok = co_t * 32 + q4 < a.co;
+
+  float4 rx[XP], ry[4];
+  auto fetch = [&](int row, int seg) {
+    const int o1 = row % wd.out[1];
+    const int r2 = row / wd.out[1];
+    const int o0 = r2 % wd.out[0], n = r2 / wd.out[0];
+    const int c0 = seg * 32 * a.s[2];  // first cell of the segment, relative to the row's first tap
+    const float* xrow = x + n * sxn + (int64_t)(wd.origin[0] + o0 * a.s[0] + t0 * a.dil[0]) * sx0 +
+                        (int64_t)(wd.origin[1] + o1 * a.s[1] + t1 * a.dil[1]) * sx1 +
+                        (int64_t)(wd.origin[2] + c0) * sx2 + ci_t * 32 + q4;
+    const float* dyrow = dy + (int64_t)row * sy1 + (int64_t)seg * 32 * sy2 + co_t * 32 + q4;
+#pragma unroll
+    for (int i = 0; i < XP; ++i) {
+      const int cell = (lane >> 3) + 8 * i;
+      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (cell < ncell && c0 + cell < row_cells && xch_ok) v = *(const float4*)(xrow + (int64_t)cell * sx2);
+      rx[i] = v;
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int pos = (lane >> 3) + 8 * i;
+      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (seg * 32 + pos < O2 && ych_ok) v = *(const float4*)(dyrow + (int64_t)pos * sy2);
+      ry[i] = v;
+    }
+  };
+  auto stash = [&]() {
+#pragma unroll
+    for (int i = 0; i < XP; ++i)
+      if ((lane >> 3) + 8 * i < ncell) xs4[lane + 64 * i] = rx[i];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) ys4[lane + 64 * i] = ry[i];
+  };
+
+  const int s2 = a.s[2];
+  int toff[K2];  // cell offset of tap t2 (taps beyond the kernel re-read tap 0; their sums are never stored)
+#pragma unroll
+  for (int t2 = 0; t2 < K2; ++t2) toff[t2] = (t2 < a.k[2] ? t2 : 0) * a.dil[2];
+  const int total = max(row_end - row_begin, 0) * nseg;
+  if (total > 0) fetch(row_begin, 0);
+  for (int it = 0; it < total; ++it) {
+    __builtin_amdgcn_wave_barrier();
+    stash();
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    if (it + 1 < total) fetch(row_begin + (it + 1) / nseg, (it + 1) % nseg);
+    // 16 steps of two positions: lanes 0-31 take position 2*pr, lanes 32-63 position 2*pr + 1
+#pragma unroll 4
+    for (int pr = 0; pr < 16; ++pr) {
+      const int pl = 2 * pr + h;
+      const float b = ys[pl * 32 + m];
+      float av[K2];
+#pragma unroll
+      for (int t2 = 0; t2 < K2; ++t2) av[t2] = xs[(pl * s2 + toff[t2]) * 32 + m];
+#pragma unroll
+      for (int t2 = 0; t2 < K2; ++t2) acc[t2] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[t2], b, acc[t2], 0, 0, 0);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  }
+  const int co = co_t * 32 + m;
+  const bool co_ok = co < a.co;
+  float* pbase = partial + (size_t)blockIdx.z * a.slot;
+#pragma unroll
+  for (int t2 = 0; t2 < K2; ++t2) {
+    if (t2 >= a.k[2]) break;
+    const int tap = (t0 * a.k[1] + t1) * a.k[2] + t2;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int cir = ci_t * 32 + 8 * (v / 4) + 4 * h + (v % 4);
+      if (cir < a.ci && co_ok) pbase[((size_t)tap * a.ci + cir) * a.co + co] = acc[t2][v];
+    }
+  }
+}
+
 // db^ partial of one (worker, chunk): sum of dy over the chunk's positions,
 // written to the slot's trailing Co entries.  One block per slot.
 __global__ __launch_bounds__(256) void bias_partial_kernel(const WorkerDev* __restrict__ workers, void* const* dy_bufs,
@@ -644,9 +760,21 @@ int conv_wgrad_mfma(distdl_plan* p, float* partial, hipStream_t st) {
   a.slot = (int64_t)a.k[0] * a.k[1] * a.k[2] * a.ci * a.co + a.co;
   dim3 grid((unsigned)((a.k[0] * a.k[1] + 3) / 4), (unsigned)(((a.ci + 31) / 32) * ((a.co + 31) / 32)),
             (unsigned)(p->n_workers * a.nchunks));
+  // LDS-staged variant when 16-byte pieces are possible and the segment fits
+  a.ncell = 31 * a.s[2] + (a.k[2] - 1) * a.dil[2] + 1;
+  bool aligned = a.ci % 4 == 0 && a.co % 4 == 0;
+  for (int w = 0; w < p->n_workers && aligned; ++w)
+    aligned = (uintptr_t)p->tab_x.host[w] % 16 == 0 && (uintptr_t)p->tab_dy.host[w] % 16 == 0;
+  const int lds = 4 * (a.ncell + 32) * 128;
   {
     ProfScope prof("conv_bwd_weight_mfma", st);
-    if (a.k[2] <= 3)
+    if (aligned && a.ncell <= 72 && a.k[2] <= 3)
+      hipLaunchKernelGGL((wgrad_lds_kernel<3, 9>), grid, dim3(256), lds, st, p->d_workers, p->tab_x.dev,
+                         p->tab_dy.dev, partial, a);
+    else if (aligned && a.ncell <= 72 && a.k[2] <= 5)
+      hipLaunchKernelGGL((wgrad_lds_kernel<5, 9>), grid, dim3(256), lds, st, p->d_workers, p->tab_x.dev,
+                         p->tab_dy.dev, partial, a);
+    else if (a.k[2] <= 3)
       hipLaunchKernelGGL(wgrad_mfma_kernel<3>, grid, dim3(256), 0, st, p->d_workers, p->tab_x.dev, p->tab_dy.dev,
                          partial, a);
     else if (a.k[2] <= 5)
