@@ -55,22 +55,38 @@ __host__ __device__ inline PerWorker derive(const WorkerDev& wd, const CorrArgs&
 }
 
 __host__ __device__ inline int64_t tiles_of(const PerWorker& g, const CorrArgs& a) {
-  return (int64_t)a.n_b * g.nq[0] * ((g.nq[1] + a.tr - 1) / a.tr) * ((g.nq[2] + a.tc - 1) / a.tc) * a.ntn;
+  return (int64_t)a.n_b * ((g.nq[0] + a.g0 - 1) / a.g0) * ((g.nq[1] + a.tr - 1) / a.tr) *
+         ((g.nq[2] + a.tc - 1) / a.tc) * a.ntn;
 }
 
 constexpr int kMaxPieces = 14;
 constexpr int kMaxBPieces = 8;  // weight pieces per thread held in registers (32 taps per plane)
+constexpr uint32_t kOob = 0x7ffffff0u;  // buffer offset that always fails the range check (buffers are < 2 GiB)
 
-// MT: 32-position M-tiles per wave; PA / PB: 16-byte patch / weight pieces per thread and stage
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+__device__ inline __amdgpu_buffer_rsrc_t make_rsrc(const void* p, uint32_t bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)bytes, 0x00020000);
+}
+
+// On this target VALU instructions do not overlap with MFMA execution on the same SIMD, so the loops
+// below are written to issue as few of them as possible: every global access is a buffer instruction
+// with a precomputed per-lane offset (out-of-range pieces carry an offset that fails the range check:
+// loads return zero, stores are dropped), LDS addresses are precomputed, and the operands of tap i+1
+// are read from LDS into a second register set while tap i multiplies.
+//
+// MT: 32-position M-tiles per wave; PA / PB: 16-byte patch / weight pieces per thread and stage.
 template <int MT, int PA, int PB>
 __global__ __launch_bounds__(256, 2) void corr_mfma_kernel(const WorkerDev* __restrict__ workers,
                                                            void* const* in_bufs, void* const* out_bufs, CorrArgs a) {
   extern __shared__ float4 lds[];
   float4* As = lds;
   float4* Bs = lds + a.a_vec4;
+  const int nb_vec4 = a.nt[1] * a.nt[2] * 64;
+  const int dummy = a.a_vec4 + nb_vec4;  // one spare 16-byte slot that absorbs the pieces nobody needs
+  uint32_t* tap_tab = (uint32_t*)(lds + dummy + 1);  // byte offset into the patch per (t1, t2), read as a broadcast
 
-  // XCD-aware order: consecutive tiles (which share input rows) stay on one
-  // XCD, i.e. behind one L2
+  // XCD-aware order: consecutive tiles (which share input rows) stay on one XCD, i.e. behind one L2
   const uint32_t nblk = gridDim.x;
   const uint32_t r = (blockIdx.x & 7u) * (nblk >> 3) + (blockIdx.x >> 3);
   const uint32_t worker = r / a.tiles_max;
@@ -81,176 +97,168 @@ __global__ __launch_bounds__(256, 2) void corr_mfma_kernel(const WorkerDev* __re
   if ((int64_t)tile >= tiles_of(g, a)) return;
 
   const int nt2tiles = (g.nq[2] + a.tc - 1) / a.tc, nt1tiles = (g.nq[1] + a.tr - 1) / a.tr;
+  const int nq0chunks = (g.nq[0] + a.g0 - 1) / a.g0;
   const int q2_0 = (tile % nt2tiles) * a.tc; tile /= nt2tiles;
   const int q1_0 = (tile % nt1tiles) * a.tr; tile /= nt1tiles;
   const int ntile = tile % a.ntn; tile /= a.ntn;
-  const int q0 = tile % g.nq[0];
-  const int n = tile / g.nq[0];
+  const int q0_begin = (tile % nq0chunks) * a.g0;
+  const int q0_end = min(q0_begin + a.g0, g.nq[0]);
+  const int n = tile / nq0chunks;
 
-  const float* __restrict__ in = (const float*)in_bufs[worker];
-  float* __restrict__ out = (float*)out_bufs[worker];
   const int si2 = a.kc, si1 = g.in_ext[2] * si2, si0 = g.in_ext[1] * si1;
-  const size_t sin = (size_t)g.in_ext[0] * si0;
+  const uint32_t sin = (uint32_t)g.in_ext[0] * si0;
+  const uint32_t so2 = a.nc, so1 = g.out_ext[2] * so2, so0 = g.out_ext[1] * so1, son = g.out_ext[0] * so0;
+  const __amdgpu_buffer_rsrc_t rin = make_rsrc(in_bufs[worker], (uint32_t)a.n_b * sin * 4u);
+  const __amdgpu_buffer_rsrc_t rout = make_rsrc(out_bufs[worker], (uint32_t)a.n_b * son * 4u);
+  const int ncc = (a.kc + 7) / 8;
+  const int nt0 = a.nt[0];
+  const __amdgpu_buffer_rsrc_t rw =
+      make_rsrc(a.wt + (size_t)ntile * nt0 * ncc * nb_vec4 * 4, (uint32_t)(nt0 * ncc * nb_vec4) * 16u);
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, h = lane >> 5, m = lane & 31;
 
-  // per-thread patch pieces (16 bytes each): fixed for the whole tile
-  int32_t goff[PA], loff[PA];
+  // per-thread patch pieces: byte offset inside an input plane and LDS slot, fixed for the whole tile.
+  // When the channel count is not a multiple of 8, bit 0 marks the pieces of the upper half of a chunk:
+  // in the last chunk they lie beyond the channels and must read as zero.
+  uint32_t goff[PA], loff[PA];
   const int npieces = a.R * a.Cw * 2;
 #pragma unroll
   for (int i = 0; i < PA; ++i) {
     const int piece = tid + i * 256;
-    goff[i] = -1;
-    loff[i] = -1;
+    goff[i] = kOob;
+    loff[i] = dummy * 16;
     if (piece < npieces) {
       const int ph = piece & 1, cell = piece >> 1;
       const int rr = cell / a.Cw, c = cell - rr * a.Cw;
       const int i1 = g.in_base[1] + q1_0 * a.is[1] + a.tapmin[1] + rr;
       const int i2 = g.in_base[2] + q2_0 * a.is[2] + a.tapmin[2] + c;
-      loff[i] = ((rr * 2 + ph) * a.is[2] + c % a.is[2]) * a.CwQ + c / a.is[2];
-      if (i1 >= 0 && i1 < g.in_ext[1] && i2 >= 0 && i2 < g.in_ext[2]) goff[i] = i1 * si1 + i2 * si2 + ph * 4;
+      loff[i] = (((rr * 2 + ph) * a.is[2] + c % a.is[2]) * a.CwQ + c / a.is[2]) * 16;
+      if (i1 >= 0 && i1 < g.in_ext[1] && i2 >= 0 && i2 < g.in_ext[2])
+        goff[i] = ((i1 * si1 + i2 * si2 + ph * 4) * 4) | ((a.kc & 7) ? ph : 0);
     }
   }
+  uint32_t bl[PB];
+#pragma unroll
+  for (int i = 0; i < PB; ++i) bl[i] = (tid + i * 256 < nb_vec4 ? a.a_vec4 + tid + i * 256 : dummy) * 16;
 
-  // The workgroup's 128*MT output positions form a tr x tc window, row-major;
-  // lane m of M-tile (wave, mt) holds window position (wave*MT + mt)*32 + m.
-  int32_t abase[MT];
+  // The workgroup's 128*MT output positions form a tr x tc window, row-major; lane m of M-tile
+  // (wave, mt) multiplies window position (wave*MT + mt)*32 + m, and accumulator register v of lane
+  // (h, m) is window position (wave*MT + mt)*32 + 8*(v/4) + 4*h + v%4, channel ntile*32 + m.
+  uint32_t abase[MT], soff[MT][16];
+  const int ch = ntile * 32 + m;
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) {
     const int pidx = (wave * MT + mt) * 32 + m;
     int wr = pidx / a.tc, wc = pidx - wr * a.tc;
-    if (wr >= a.tr) wr = 0, wc = 0;  // idle position: read something in range, never stored
-    abase[mt] = wr * a.is[1] * 2 * a.is[2] * a.CwQ + wc;
+    if (wr >= a.tr) wr = 0, wc = 0;  // idle position: multiplies something in range, never stored
+    abase[mt] = (wr * a.is[1] * 2 * a.is[2] * a.CwQ + wc + h * a.is[2] * a.CwQ) * 16;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int po = (wave * MT + mt) * 32 + 8 * (v / 4) + 4 * h + (v % 4);
+      const int orow = po / a.tc, ocol = po - orow * a.tc;
+      const int q1 = q1_0 + orow, q2 = q2_0 + ocol;
+      soff[mt][v] = kOob;
+      if (orow < a.tr && q1 < g.nq[1] && q2 < g.nq[2] && ch < a.nc)
+        soff[mt][v] = ((g.out_base[1] + g.os[1] * q1) * so1 + (g.out_base[2] + g.os[2] * q2) * so2 + ch) * 4;
+    }
   }
+  const float bias = (a.bias && ch < a.nc) ? a.bias[ch] : 0.f;
+  const uint32_t boff0 = tid * 16, bread = ((h * 32 + m) + a.a_vec4) * 16;  // weight piece / operand addresses
 
-  floatx16 acc[MT];
-#pragma unroll
-  for (int t = 0; t < MT; ++t)
-    for (int v = 0; v < 16; ++v) acc[t][v] = 0.f;
-
-  const int ncc = (a.kc + 7) / 8;
-  const int nb_vec4 = a.nt[1] * a.nt[2] * 64;
-  const int ntaps = a.nt[1] * a.nt[2];
-
-  // A stage is one (tap plane t0, 8-channel chunk cc); stages whose plane lies
-  // outside the input contribute zero and are skipped.  The global loads of
-  // stage s+1 are issued into registers before the MFMAs of stage s and written
-  // to LDS after them.
   const int* __restrict__ tapinfo = a.tapinfo;  // [0..7]: plane offsets, [8..]: patch offset per (t1, t2)
-  const int nt0 = a.nt[0], in_base0 = g.in_base[0] + q0 * a.is[0], in_ext0 = g.in_ext[0];
-  auto plane_ok = [&](int t0) {
-    const int i0 = in_base0 + tapinfo[t0];
-    return i0 >= 0 && i0 < in_ext0;
-  };
-  auto next_stage = [&](int st) {  // smallest valid stage index > st, or nt0*ncc
+  const int ntaps = a.nt[1] * a.nt[2];
+  if (tid < ntaps) tap_tab[tid] = (uint32_t)tapinfo[8 + tid] * 16u;  // visible after the first barrier below
+  const int nstages = nt0 * ncc;
+  const bool ragged = (a.kc & 7) != 0;
+  char* const ldsb = (char*)lds;
+
+  // A stage is one (output plane q0, tap plane t0, 8-channel chunk cc); stages whose input plane lies
+  // outside the input contribute zero and are skipped.
+  auto plane_of = [&](int q0, int t0) { return g.in_base[0] + q0 * a.is[0] + tapinfo[t0]; };
+  auto advance = [&](int& q0, int& st) {  // next valid stage after (q0, st), or q0 == q0_end
     ++st;
-    while (st < nt0 * ncc && !plane_ok(st / ncc)) st = (st / ncc + 1) * ncc;
-    return st;
+    while (q0 < q0_end) {
+      while (st < nstages) {
+        const int i0 = plane_of(q0, st / ncc);
+        if (i0 >= 0 && i0 < g.in_ext[0]) return;
+        st = (st / ncc + 1) * ncc;
+      }
+      ++q0;
+      st = 0;
+    }
   };
-  const int kc = a.kc;
-  const float4* __restrict__ wbase = (const float4*)a.wt + (size_t)ntile * nt0 * ncc * nb_vec4;
-  float4 ra[PA], rb[PB];
-#pragma unroll
-  for (int i = 0; i < PA; ++i) ra[i] = make_float4(0.f, 0.f, 0.f, 0.f);
-#pragma unroll
-  for (int i = 0; i < PB; ++i) rb[i] = make_float4(0.f, 0.f, 0.f, 0.f);
-  auto load_stage = [&](int st) {
+  u32x4 ra[PA], rb[PB];
+  auto load_stage = [&](int q0, int st) {
     const int t0 = st / ncc, cc = st - t0 * ncc;
-    const float* plane = in + n * sin + (size_t)(in_base0 + tapinfo[t0]) * si0 + cc * 8;
+    const uint32_t sbase = ((uint32_t)n * sin + (uint32_t)plane_of(q0, t0) * si0 + cc * 8) * 4u;
+    if (ragged && cc == ncc - 1) {
 #pragma unroll
-    for (int i = 0; i < PA; ++i) {
-      const int ph = (tid + i * 256) & 1;
-      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (goff[i] >= 0 && cc * 8 + ph * 4 < kc) v = *(const float4*)(plane + goff[i]);
-      ra[i] = v;
-    }
-    const float4* wsrc = wbase + (size_t)st * nb_vec4;
+      for (int i = 0; i < PA; ++i)
+        ra[i] = __builtin_amdgcn_raw_buffer_load_b128(rin, (goff[i] & 1u) ? kOob : goff[i], sbase, 0);
+    } else if (ragged) {
 #pragma unroll
-    for (int i = 0; i < PB; ++i) {
-      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (tid + i * 256 < nb_vec4) v = wsrc[tid + i * 256];
-      rb[i] = v;
+      for (int i = 0; i < PA; ++i) ra[i] = __builtin_amdgcn_raw_buffer_load_b128(rin, goff[i] & ~1u, sbase, 0);
+    } else {
+#pragma unroll
+      for (int i = 0; i < PA; ++i) ra[i] = __builtin_amdgcn_raw_buffer_load_b128(rin, goff[i], sbase, 0);
     }
+    const uint32_t wbase = (uint32_t)st * nb_vec4 * 16u;
+#pragma unroll
+    for (int i = 0; i < PB; ++i) rb[i] = __builtin_amdgcn_raw_buffer_load_b128(rw, boff0, wbase + i * 4096u, 0);
   };
   auto write_stage = [&]() {
 #pragma unroll
-    for (int i = 0; i < PA; ++i)
-      if (loff[i] >= 0) As[loff[i]] = ra[i];
+    for (int i = 0; i < PA; ++i) *(u32x4*)(ldsb + loff[i]) = ra[i];
 #pragma unroll
-    for (int i = 0; i < PB; ++i)
-      if (tid + i * 256 < nb_vec4) Bs[tid + i * 256] = rb[i];
+    for (int i = 0; i < PB; ++i) *(u32x4*)(ldsb + bl[i]) = rb[i];
   };
-  // per-tap patch offsets, tabulated once in LDS (read back as a broadcast)
-  int* tap_tab = (int*)(Bs + nb_vec4);
-  if (tid < ntaps) tap_tab[tid] = tapinfo[8 + tid];
-  const int hoff = h * a.is[2] * a.CwQ;
-  auto tap_offsets = [&](int tap, int& tapo, int& bo) {
-    tapo = tap_tab[tap] + hoff;
-    bo = (tap * 2 + h) * 32 + m;
+  auto read_ops = [&](int tap, float4& b, float4 (&av)[MT]) {
+    const uint32_t tapo = tap_tab[tap];
+    b = *(const float4*)(ldsb + bread + tap * 1024);
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) av[mt] = *(const float4*)(ldsb + abase[mt] + tapo);
+  };
+  auto multiply = [&](floatx16 (&acc)[MT], const float4& b, const float4 (&av)[MT]) {
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      acc[mt] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[mt].x, b.x, acc[mt], 0, 0, 0);
+      acc[mt] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[mt].y, b.y, acc[mt], 0, 0, 0);
+      acc[mt] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[mt].z, b.z, acc[mt], 0, 0, 0);
+      acc[mt] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[mt].w, b.w, acc[mt], 0, 0, 0);
+    }
   };
 
-  const int nstages = nt0 * ncc;
-  int st = next_stage(-1);
-  if (st < nstages) {
-    load_stage(st);
-    write_stage();
-    __syncthreads();
-    while (true) {
-      const int nxt = next_stage(st);
-      if (nxt < nstages) load_stage(nxt);
-      // all taps of this plane from LDS; the operands of tap i+1 are read while tap i multiplies
-      int tapo, bo;
-      tap_offsets(0, tapo, bo);
-      float4 b = Bs[bo], av[MT];
+  floatx16 acc[MT];
+  int q0 = q0_begin, st = -1;
+  advance(q0, st);
+  if (q0 < q0_end) load_stage(q0, st);
+  for (int qo = q0_begin; qo < q0_end; ++qo) {  // output planes of this workgroup
 #pragma unroll
-      for (int mt = 0; mt < MT; ++mt) av[mt] = As[abase[mt] + tapo];
-      for (int tap = 0; tap < ntaps; ++tap) {
-        float4 bn = b, avn[MT];
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt) avn[mt] = av[mt];
-        if (tap + 1 < ntaps) {
-          tap_offsets(tap + 1, tapo, bo);
-          bn = Bs[bo];
-#pragma unroll
-          for (int mt = 0; mt < MT; ++mt) avn[mt] = As[abase[mt] + tapo];
-        }
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
-          acc[mt] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[mt].x, b.x, acc[mt], 0, 0, 0);
-          acc[mt] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[mt].y, b.y, acc[mt], 0, 0, 0);
-          acc[mt] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[mt].z, b.z, acc[mt], 0, 0, 0);
-          acc[mt] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[mt].w, b.w, acc[mt], 0, 0, 0);
-        }
-        b = bn;
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt) av[mt] = avn[mt];
-      }
-      __syncthreads();  // everyone is done reading this stage
-      if (nxt >= nstages) break;
+    for (int t = 0; t < MT; ++t)
+      for (int v = 0; v < 16; ++v) acc[t][v] = 0.f;
+    while (q0 == qo) {  // the stages that feed output plane qo
       write_stage();
       __syncthreads();
-      st = nxt;
+      advance(q0, st);
+      if (q0 < q0_end) load_stage(q0, st);  // in flight while this stage multiplies
+      float4 b0, b1, a0[MT], a1[MT];
+      read_ops(0, b0, a0);
+      int tap = 0;
+      for (; tap + 1 < ntaps; tap += 2) {
+        read_ops(tap + 1, b1, a1);
+        multiply(acc, b0, a0);
+        if (tap + 2 < ntaps) read_ops(tap + 2, b0, a0);
+        multiply(acc, b1, a1);
+      }
+      if (tap < ntaps) multiply(acc, b0, a0);
+      __syncthreads();  // everyone is done reading this stage
     }
-  }
-
-  // store: register v of lane (h, m) is window position (wave*MT + mt)*32 + 8*(v/4) + 4*h + v%4, channel ntile*32 + m
-  const int ch = ntile * 32 + m;
-  if (ch >= a.nc) return;
-  const float bias = a.bias ? a.bias[ch] : 0.f;
-  const size_t so2 = a.nc, so1 = (size_t)g.out_ext[2] * so2, so0 = (size_t)g.out_ext[1] * so1,
-               son = (size_t)g.out_ext[0] * so0;
-  float* obase = out + n * son + (size_t)(g.out_base[0] + g.os[0] * q0) * so0 + ch;
+    const uint32_t obase = ((uint32_t)n * son + (uint32_t)(g.out_base[0] + g.os[0] * qo) * so0) * 4u;
 #pragma unroll
-  for (int mt = 0; mt < MT; ++mt) {
+    for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      const int pidx = (wave * MT + mt) * 32 + 8 * (v / 4) + 4 * h + (v % 4);
-      const int wr = pidx / a.tc, wc = pidx - wr * a.tc;
-      const int q1 = q1_0 + wr, q2 = q2_0 + wc;
-      if (wr < a.tr && q1 < g.nq[1] && q2 < g.nq[2])
-        obase[(size_t)(g.out_base[1] + g.os[1] * q1) * so1 + (size_t)(g.out_base[2] + g.os[2] * q2) * so2] =
-            acc[mt][v] + bias;
-    }
+      for (int v = 0; v < 16; ++v)
+        __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(acc[mt][v] + bias), rout, soff[mt][v], obase, 0);
   }
 }
 
@@ -529,7 +537,7 @@ __global__ __launch_bounds__(256) void bias_partial_kernel(const WorkerDev* __re
 
 // ---- host side ------------------------------------------------------------------
 
-static int lds_bytes(const CorrArgs& a) { return (a.a_vec4 + a.nt[1] * a.nt[2] * 64) * 16 + a.nt[1] * a.nt[2] * 4; }
+static int lds_bytes(const CorrArgs& a) { return (a.a_vec4 + a.nt[1] * a.nt[2] * 64 + 1) * 16 + a.nt[1] * a.nt[2] * 4; }
 
 static void finish_args(CorrArgs& a, int mt, int nq2max) {
   // window of 128*mt positions: full output rows when they fit, else 32-multiples
@@ -584,6 +592,8 @@ static int max_nq2(const distdl_plan* p, const CorrArgs& a) {
 bool corr_mfma_supported(const distdl_plan* p) {
   if (p->dtype != DISTDL_F32 || p->explicit_halo) return false;
   if (p->n_ci % 4 || p->n_co % 4) return false;  // 16-byte channel pieces
+  // buffer instructions address one worker's tensor with 31-bit byte offsets
+  if ((double)p->n_b * p->max_buf_cells * std::max(p->n_ci, p->n_co) * 4.0 >= 2147480000.0) return false;
   for (int d = 0; d < 3; ++d)
     if (p->ksize[d] > 8) return false;
   if (p->ksize[1] * p->ksize[2] > kMaxBPieces * 4) return false;  // weight pieces held in registers per stage
@@ -651,6 +661,14 @@ static int launch_corr(distdl_plan* p, CorrArgs a, const float* w, float* wscrat
                        void** out_tab, const char* name, hipStream_t st) {
   const int mt = choose_mt(a, max_nq2(p, a));
   if (mt == 0) return set_error(DISTDL_ERR_UNSUPPORTED, "conv: kernel footprint does not fit in LDS");
+  // output planes per workgroup: as many as still leave about 2048 workgroups
+  a.g0 = 1;
+  {
+    int nq0max = 0;
+    for (const WorkerDev& wd : p->workers) nq0max = std::max(nq0max, derive(wd, a).nq[0]);
+    const int64_t wgs = max_tiles(p, a) * p->n_workers;
+    a.g0 = (int32_t)std::max<int64_t>(1, std::min<int64_t>(nq0max, wgs / 2048));
+  }
   a.tiles_max = (int32_t)max_tiles(p, a);
   if (a.tiles_max == 0) return DISTDL_OK;
   a.wt = wscratch;
