@@ -498,6 +498,165 @@ __global__ __launch_bounds__(256, 2) void wgrad_lds_kernel(const WorkerDev* __re
   }
 }
 
+// Weight gradient with input rows shared inside the workgroup.  Wave t1 of a workgroup owns kernel
+// row (t0, t1) and all K2 taps of it; the waves walk the output rows o1 together.  The input rows a
+// step needs, origin + o1*s1 + t1*dil1, form a window of `span` rows that advances by s1 rows per
+// step, so LDS holds them as a ring and every step fetches only the s1 new rows (plus the dy row
+// segment, shared by all waves).  Each input cell is read from memory once per t0 instead of once
+// per (t0, t1).  S2 (stride along the row) is a template parameter so that every LDS read of the
+// unrolled inner loop is an immediate offset from one per-step base address.
+template <int K2, int S2, int PX>
+__global__ __launch_bounds__(512, 2) void wgrad_rows_kernel(const WorkerDev* __restrict__ workers, void* const* x_bufs,
+                                                         void* const* dy_bufs, float* __restrict__ partial,
+                                                         WgradArgs a) {
+  extern __shared__ float4 wr_lds[];
+  const int nthreads = blockDim.x;  // 64 * k1
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, h = lane >> 5, m = lane & 31;
+  const int t0 = blockIdx.x, t1 = wave;
+  const int nco_t = (a.co + 31) / 32;
+  const int ci_t = blockIdx.y / nco_t, co_t = blockIdx.y - ci_t * nco_t;
+  const int worker = blockIdx.z / a.nchunks, chunk = blockIdx.z - worker * a.nchunks;
+  const WorkerDev wd = workers[worker];
+  const int ncell = a.ncell, span = a.span, s1 = a.s[1];
+  const int row_vec4 = ncell * 8;             // one staged input row: ncell cells x 32 channels
+  char* const ldsb = (char*)wr_lds;
+  const uint32_t ys_base = (uint32_t)span * row_vec4 * 16u;  // dy segment behind the ring
+
+  const uint32_t sx2 = a.ci, sx1 = wd.buf[2] * sx2, sx0 = wd.buf[1] * sx1, sxn = wd.buf[0] * sx0;
+  const uint32_t sy2 = a.co, sy1 = wd.out[2] * sy2, sy0 = wd.out[1] * sy1, syn = wd.out[0] * sy0;
+  const __amdgpu_buffer_rsrc_t rx = make_rsrc(x_bufs[worker], (uint32_t)a.n_b * sxn * 4u);
+  const __amdgpu_buffer_rsrc_t ry = make_rsrc(dy_bufs[worker], (uint32_t)a.n_b * syn * 4u);
+
+  floatx16 acc[K2];
+#pragma unroll
+  for (int t = 0; t < K2; ++t)
+    for (int v = 0; v < 16; ++v) acc[t][v] = 0.f;
+
+  // pieces of one step: the s1 new rows (s1 * row_vec4 pieces) followed by the dy segment (256)
+  const int step_pieces = s1 * row_vec4 + 256;
+  const int row_cells = wd.buf[2] - wd.origin[2];
+  const int O1 = wd.out[1], O2 = wd.out[2], nseg = (O2 + 31) / 32;
+  const int nplanes = a.n_b * wd.out[0];
+  const int per = (nplanes + a.nchunks - 1) / a.nchunks;
+  const int plane_end = min(nplanes, (chunk + 1) * per);
+
+  // piece -> (global byte offset relative to the step's base, LDS byte offset relative to the ring slot)
+  // is the same at every step except for the row index, which is folded into scalar bases below
+  uint32_t pg[PX], pl[PX];
+  bool pdy[PX];
+  auto setup_pieces = [&](int seg) {
+#pragma unroll
+    for (int i = 0; i < PX; ++i) {
+      const int piece = tid + i * nthreads;
+      pg[i] = kOob;
+      pl[i] = 0xffffffffu;  // no LDS write
+      pdy[i] = false;
+      if (piece < s1 * row_vec4) {
+        const int rr = piece / row_vec4, rest = piece - rr * row_vec4;
+        const int cell = rest >> 3, q4 = (rest & 7) * 4;
+        pl[i] = (uint32_t)rest * 16u + (uint32_t)rr * 0x01000000u;  // new-row index kept in the top byte
+        if (seg * 32 * S2 + cell < row_cells && ci_t * 32 + q4 < a.ci)
+          pg[i] = (rr * sx1 + (seg * 32 * S2 + cell) * sx2 + ci_t * 32 + q4) * 4u;
+      } else if (piece < step_pieces) {
+        const int rest = piece - s1 * row_vec4;
+        const int pos = rest >> 3, q4 = (rest & 7) * 4;
+        pdy[i] = true;
+        pl[i] = ys_base + (uint32_t)rest * 16u;
+        if (seg * 32 + pos < O2 && co_t * 32 + q4 < a.co) pg[i] = ((seg * 32 + pos) * sy2 + co_t * 32 + q4) * 4u;
+      }
+    }
+  };
+  u32x4 rp[PX];
+  // step o1 of plane (n, o0): new rows are the last s1 rows of its window
+  auto fetch = [&](int n, int o0, int o1) {
+    const int c0 = wd.origin[0] + o0 * a.s[0] + t0 * a.dil[0];
+    const int r_first = wd.origin[1] + o1 * s1 + span - s1;  // buffer row of new row 0
+    const uint32_t xb = ((uint32_t)n * sxn + (uint32_t)c0 * sx0 + (uint32_t)r_first * sx1 + wd.origin[2] * sx2) * 4u;
+    const uint32_t yb = ((uint32_t)n * syn + (uint32_t)o0 * sy0 + (uint32_t)o1 * sy1) * 4u;
+    const int rows_left = wd.buf[1] - r_first;  // new rows beyond the buffer read as zero
+#pragma unroll
+    for (int i = 0; i < PX; ++i) {
+      uint32_t off = pg[i];
+      if (!pdy[i] && (int)(pl[i] >> 24) >= rows_left) off = kOob;
+      rp[i] = __builtin_amdgcn_raw_buffer_load_b128(pdy[i] ? ry : rx, off, pdy[i] ? yb : xb, 0);
+    }
+  };
+  auto stash = [&](int o1) {
+    // new row rr of step o1 is window row o1*s1 + span - s1 + rr, kept in ring slot (that index) mod span
+    const int slot0 = (o1 * s1 + span - s1) % span;
+#pragma unroll
+    for (int i = 0; i < PX; ++i) {
+      if (pl[i] == 0xffffffffu) continue;
+      uint32_t dst = pl[i];
+      if (!pdy[i]) {
+        int slot = slot0 + (int)(pl[i] >> 24);
+        if (slot >= span) slot -= span;
+        dst = (pl[i] & 0x00ffffffu) + (uint32_t)slot * row_vec4 * 16u;
+      }
+      *(u32x4*)(ldsb + dst) = rp[i];
+    }
+  };
+
+  const uint32_t lane_x = (uint32_t)(h * S2 * 32 + m) * 4u, lane_y = ys_base + (uint32_t)(h * 32 + m) * 4u;
+  for (int plane = chunk * per; plane < plane_end; ++plane) {
+    const int o0 = plane % wd.out[0], n = plane / wd.out[0];
+    for (int seg = 0; seg < nseg; ++seg) {
+      setup_pieces(seg);
+      __syncthreads();  // previous plane / segment fully consumed
+      // prime the ring with window rows 0 .. span-s1-1 of step 0
+      {
+        const int c0 = wd.origin[0] + o0 * a.s[0] + t0 * a.dil[0];
+        const int prime = (span - s1) * row_vec4;
+        for (int piece = tid; piece < prime; piece += nthreads) {
+          const int rr = piece / row_vec4, rest = piece - rr * row_vec4;
+          const int cell = rest >> 3, q4 = (rest & 7) * 4;
+          uint32_t off = kOob;
+          if (seg * 32 * S2 + cell < row_cells && ci_t * 32 + q4 < a.ci && wd.origin[1] + rr < wd.buf[1])
+            off = (((uint32_t)n * sxn + (uint32_t)c0 * sx0 + (uint32_t)(wd.origin[1] + rr) * sx1 +
+                    (wd.origin[2] + seg * 32 * S2 + cell) * sx2 + ci_t * 32 + q4)) * 4u;
+          *(u32x4*)(ldsb + ((uint32_t)(rr % span) * row_vec4 + rest) * 16u) =
+              __builtin_amdgcn_raw_buffer_load_b128(rx, off, 0, 0);
+        }
+      }
+      fetch(n, o0, 0);
+      for (int o1 = 0; o1 < O1; ++o1) {
+        stash(o1);
+        __syncthreads();
+        if (o1 + 1 < O1) fetch(n, o0, o1 + 1);  // in flight while this step multiplies
+        const uint32_t slot = (uint32_t)((o1 * s1 + t1 * a.dil[1]) % span);
+        const char* xrow = ldsb + slot * row_vec4 * 16u + lane_x;
+        const char* yrow = ldsb + lane_y;
+        // 16 x two positions: lanes 0-31 take column 2*pr, lanes 32-63 column 2*pr + 1
+#pragma unroll 4
+        for (int pr = 0; pr < 16; ++pr) {
+          const float b = *(const float*)(yrow + pr * 256);
+          float av[K2];
+#pragma unroll
+          for (int t2 = 0; t2 < K2; ++t2)
+            av[t2] = *(const float*)(xrow + (2 * pr * S2 + (t2 < a.k[2] ? t2 : 0) * a.dil[2]) * 128);
+#pragma unroll
+          for (int t2 = 0; t2 < K2; ++t2)
+            acc[t2] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[t2], b, acc[t2], 0, 0, 0);
+        }
+        __syncthreads();  // all waves done with this step's rows before the ring advances
+      }
+    }
+  }
+  const int co = co_t * 32 + m;
+  const bool co_ok = co < a.co;
+  float* pbase = partial + (size_t)blockIdx.z * a.slot;
+#pragma unroll
+  for (int t2 = 0; t2 < K2; ++t2) {
+    if (t2 >= a.k[2]) break;
+    const int tap = (t0 * a.k[1] + t1) * a.k[2] + t2;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int cir = ci_t * 32 + 8 * (v / 4) + 4 * h + (v % 4);
+      if (cir < a.ci && co_ok) pbase[((size_t)tap * a.ci + cir) * a.co + co] = acc[t2][v];
+    }
+  }
+}
+
 // db^ partial of one (worker, chunk): sum of dy over the chunk's positions,
 // written to the slot's trailing Co entries.  One block per slot.
 __global__ __launch_bounds__(256) void bias_partial_kernel(const WorkerDev* __restrict__ workers, void* const* dy_bufs,
@@ -754,10 +913,36 @@ bool wgrad_mfma_supported(const distdl_plan* p) {
   return p->dtype == DISTDL_F32 && !p->explicit_halo && p->ksize[2] <= kMaxK2;
 }
 
+// The shared-rows kernel needs 16-byte channel pieces, a row stride of 1 or 2, at most 8 kernel rows
+// of at most 5 taps, and a ring that fits in LDS.
+static bool wgrad_rows_shape_ok(const distdl_plan* p) {
+  const int span = (p->ksize[1] - 1) * p->dilation[1] + 1;
+  const int ncell = 31 * p->stride[2] + (p->ksize[2] - 1) * p->dilation[2] + 1;
+  if (p->n_ci % 4 || p->n_co % 4) return false;
+  if (p->ksize[1] > 8 || p->ksize[2] > 5 || p->stride[2] > 2 || p->stride[1] > span) return false;
+  if ((size_t)span * ncell * 128 + 4096 > 96 * 1024) return false;
+  if (p->stride[1] * ncell * 8 + 256 > 6 * 64 * p->ksize[1]) return false;
+  if ((double)p->n_b * p->max_buf_cells * std::max(p->n_ci, p->n_co) * 4.0 >= 2147480000.0) return false;
+  return true;
+}
+
 int wgrad_chunks(const distdl_plan* p) {
+  int64_t tiles = ((p->n_ci + 31) / 32) * ((p->n_co + 31) / 32);
+  if (wgrad_rows_shape_ok(p)) {
+    // chunks of (n, o0) planes; about 2048 workgroups, preferring a chunk count that splits evenly
+    int64_t planes = 0;
+    for (const WorkerDev& wd : p->workers) planes = std::max<int64_t>(planes, p->n_b * wd.out[0]);
+    int64_t blocks = (int64_t)p->ksize[0] * tiles * p->n_workers;
+    int64_t want = std::max<int64_t>(1, std::min<int64_t>(planes, (2048 + blocks - 1) / blocks));
+    int64_t best = want, best_pad = INT64_MAX;
+    for (int64_t c = want; c <= std::min<int64_t>(planes, want + 4); ++c) {
+      int64_t pad = (planes + c - 1) / c * c - planes;
+      if (pad < best_pad) best_pad = pad, best = c;
+    }
+    return (int)best;
+  }
   // enough (worker, chunk) slots to fill the chip a few times over
   int64_t groups = (p->ksize[0] * p->ksize[1] + 3) / 4;
-  int64_t tiles = ((p->n_ci + 31) / 32) * ((p->n_co + 31) / 32);
   int64_t blocks = groups * tiles * p->n_workers;
   int64_t want = (1536 + blocks - 1) / blocks;
   int64_t rows = p->n_b * p->max_out_cells;  // upper bound on rows
@@ -778,13 +963,31 @@ int conv_wgrad_mfma(distdl_plan* p, float* partial, hipStream_t st) {
   a.slot = (int64_t)a.k[0] * a.k[1] * a.k[2] * a.ci * a.co + a.co;
   dim3 grid((unsigned)((a.k[0] * a.k[1] + 3) / 4), (unsigned)(((a.ci + 31) / 32) * ((a.co + 31) / 32)),
             (unsigned)(p->n_workers * a.nchunks));
-  // LDS-staged variant when 16-byte pieces are possible and the segment fits
+  // LDS-staged variants when 16-byte pieces are possible and the segment fits
   a.ncell = 31 * a.s[2] + (a.k[2] - 1) * a.dil[2] + 1;
+  a.span = (a.k[1] - 1) * a.dil[1] + 1;
   bool aligned = a.ci % 4 == 0 && a.co % 4 == 0;
   for (int w = 0; w < p->n_workers && aligned; ++w)
     aligned = (uintptr_t)p->tab_x.host[w] % 16 == 0 && (uintptr_t)p->tab_dy.host[w] % 16 == 0;
   const int lds = 4 * (a.ncell + 32) * 128;
-  {
+  if (aligned && wgrad_rows_shape_ok(p)) {
+    const int rlds = a.span * a.ncell * 128 + 4096;
+    dim3 rgrid((unsigned)a.k[0], grid.y, grid.z), rblock(64 * a.k[1]);
+    ProfScope prof("conv_bwd_weight_mfma", st);
+#define DISTDL_LAUNCH_ROWS(K2_, S2_)                                                                                \
+  do {                                                                                                              \
+    if (rlds > 64 * 1024)                                                                                           \
+      DISTDL_HIP_TRY(hipFuncSetAttribute((const void*)wgrad_rows_kernel<K2_, S2_, 6>,                               \
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, rlds));                        \
+    hipLaunchKernelGGL((wgrad_rows_kernel<K2_, S2_, 6>), rgrid, rblock, rlds, st, p->d_workers, p->tab_x.dev,       \
+                       p->tab_dy.dev, partial, a);                                                                  \
+  } while (0)
+    if (a.k[2] <= 3 && a.s[2] == 1) DISTDL_LAUNCH_ROWS(3, 1);
+    else if (a.k[2] <= 3) DISTDL_LAUNCH_ROWS(3, 2);
+    else if (a.s[2] == 1) DISTDL_LAUNCH_ROWS(5, 1);
+    else DISTDL_LAUNCH_ROWS(5, 2);
+#undef DISTDL_LAUNCH_ROWS
+  } else {
     ProfScope prof("conv_bwd_weight_mfma", st);
     if (aligned && a.ncell <= 72 && a.k[2] <= 3)
       hipLaunchKernelGGL((wgrad_lds_kernel<3, 9>), grid, dim3(256), lds, st, p->d_workers, p->tab_x.dev,
