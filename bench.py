@@ -153,7 +153,14 @@ class AffineWorkload:
         self.db = [torch.empty_like(t) for t in self.b]
         self.flops_fwd = 2.0 * c["n_b"] * c["n_fi"] * c["n_fo"]
         self.flops_step = 3.0 * self.flops_fwd
-        self.alg = {"affine_fwd": ("mfma", self.flops_fwd), "affine_bwd": ("mfma", 2 * self.flops_fwd)}
+        esz = 4 if dtype == "f32" else 2
+        self.alg = {"affine_fwd": ("mfma", self.flops_fwd), "affine_bwd_x": ("mfma", self.flops_fwd),
+                    "affine_bwd_w": ("mfma", self.flops_fwd), "affine_bwd_direct": ("mfma", 2 * self.flops_fwd),
+                    "affine_bias_grad": ("hbm", (c["n_b"] + 1) * c["n_fo"] * esz)}
+        # bytes every kernel must at least move (operands once, result once): the HBM side of the roofline
+        self.min_bytes = {"affine_fwd": (c["n_fi"] * c["n_fo"] + c["n_b"] * (c["n_fi"] + c["n_fo"])) * esz,
+                          "affine_bwd_x": (c["n_fi"] * c["n_fo"] + c["n_b"] * (c["n_fi"] + c["n_fo"])) * esz,
+                          "affine_bwd_w": (c["n_fi"] * c["n_fo"] + c["n_b"] * (c["n_fi"] + c["n_fo"])) * esz}
         self.metric = "distributed affine fwd+bwd TFLOP/s (broadcast of x, sum-reduce over P_fi included)"
         self.unit = "TFLOP/s"
         self.dtype = dtype
@@ -207,6 +214,10 @@ def kernel_rooflines(workload, report, traffic):
                 peak = MFMA_PEAK_TFLOPS[workload.dtype]
                 entry.update(bound="mfma", achieved=ach, peak=peak, unit="TFLOP/s", frac=ach / peak,
                              algorithmic_flops=work)
+                mb = getattr(workload, "min_bytes", {}).get(key)
+                if mb:   # also against min(MFMA peak, arithmetic intensity x HBM peak)
+                    roof = min(peak, work / mb * HBM_PEAK_GBS / 1e3)
+                    entry.update(min_bytes=mb, roofline_tflops=roof, frac_of_roofline=ach / roof)
             entry["traffic"] = traffic.get(f"{workload.describe['workload'].split(':')[0]}/{name}")
         out[name] = entry
     return out

@@ -7,8 +7,42 @@
 //   adjoint   dW_ij = dy_i^T x_j,  db_i = sum_n dy_i,  dx_j = sum_i dy_i W_ij
 #include <algorithm>
 
+#include <cstring>
+
 #include "common.h"
+#include "gemm_mfma.h"
 #include "profile.h"
+
+namespace distdl {
+// Device copy of a small descriptor array, re-uploaded only when its contents change.
+template <class T>
+struct DevArray {
+  std::vector<T> host;
+  T* dev = nullptr;
+  size_t cap = 0;
+  hipStream_t last_stream = nullptr;
+  int upload(const std::vector<T>& v, hipStream_t st) {
+    if (dev && host.size() == v.size() && last_stream == st &&
+        std::memcmp(host.data(), v.data(), v.size() * sizeof(T)) == 0)
+      return DISTDL_OK;
+    if (v.size() > cap) {
+      if (dev) (void)hipFree(dev);
+      dev = nullptr;
+      DISTDL_HIP_TRY(hipMalloc((void**)&dev, v.size() * sizeof(T)));
+      cap = v.size();
+    }
+    host = v;
+    DISTDL_HIP_TRY(hipMemcpyAsync(dev, host.data(), host.size() * sizeof(T), hipMemcpyHostToDevice, st));
+    last_stream = st;
+    return DISTDL_OK;
+  }
+  void release() {
+    if (dev) (void)hipFree(dev);
+    dev = nullptr;
+    cap = 0;
+  }
+};
+}  // namespace distdl
 
 struct distdl_affine_plan {
   int64_t n_b = 0, n_fi = 0, n_fo = 0;
@@ -18,6 +52,8 @@ struct distdl_affine_plan {
   int64_t max_fo = 0, max_fi = 0;
   distdl::PtrTable tab_x, tab_W, tab_b, tab_y, tab_dy, tab_dx, tab_dW, tab_db;
   int32_t* d_sizes = nullptr;  // [P_fo fo sizes][P_fi fi sizes]
+  distdl::DevArray<distdl::GemmBlock> g_fwd, g_dx, g_dw;
+  distdl::DevArray<distdl::ColsumBlock> g_db;
 };
 
 namespace distdl {
@@ -201,6 +237,10 @@ int distdl_affine_plan_destroy(distdl_affine_plan* p) {
   for (PtrTable* t : {&p->tab_x, &p->tab_W, &p->tab_b, &p->tab_y, &p->tab_dy, &p->tab_dx, &p->tab_dW, &p->tab_db})
     t->release();
   if (p->d_sizes) (void)hipFree(p->d_sizes);
+  p->g_fwd.release();
+  p->g_dx.release();
+  p->g_dw.release();
+  p->g_db.release();
   delete p;
   return DISTDL_OK;
 }
@@ -216,6 +256,28 @@ int distdl_affine_fwd(distdl_affine_plan* p, const void* const x_dev[], const vo
     return rc;
   if (b_dev && (rc = check_ptrs(b_dev, p->P_fo, esz, "b", true))) return rc;
   if ((rc = prepare(p))) return rc;
+  const bool bf16 = p->dtype == DISTDL_BF16;
+  {  // matrix-core path: y_i = sum_j x_j W_ij^T + b_i, the sum over j inside the K loop
+    std::vector<GemmBlock> blocks(p->P_fo);
+    for (int i = 0; i < p->P_fo; ++i) {
+      GemmBlock& g = blocks[i];
+      std::memset(&g, 0, sizeof g);
+      g.M = (int32_t)p->n_b;
+      g.N = g.ldc = (int32_t)p->fo_size[i];
+      g.c = y_dev[i];
+      g.bias = b_dev ? b_dev[i] : nullptr;
+      g.nseg = std::min(p->P_fi, kGemmMaxSeg + 1);
+      for (int j = 0; j < p->P_fi && j < kGemmMaxSeg; ++j)
+        g.seg[j] = GemmSeg{x_dev[j], W_dev[i * p->P_fi + j], (int32_t)p->fi_size[j], (int32_t)p->fi_size[j],
+                           (int32_t)p->fi_size[j], 0};
+    }
+    if (gemm_mfma_usable(blocks, bf16, true, true)) {
+      if ((rc = p->g_fwd.upload(blocks, st_))) return rc;
+      launch_gemm_mfma(p->g_fwd.dev, blocks, bf16, true, true, "affine_fwd_mfma", st_);
+      DISTDL_HIP_TRY(hipGetLastError());
+      return DISTDL_OK;
+    }
+  }
   if ((rc = p->tab_x.upload(x_dev, p->P_fi, st_)) || (rc = p->tab_W.upload(W_dev, p->P_fo * p->P_fi, st_)) ||
       (rc = p->tab_y.upload((const void* const*)y_dev, p->P_fo, st_)))
     return rc;
@@ -239,6 +301,45 @@ int distdl_affine_bwd(distdl_affine_plan* p, const void* const x_dev[], const vo
     return rc;
   if (db_dev && (rc = check_ptrs((const void* const*)db_dev, p->P_fo, esz, "db", true))) return rc;
   if ((rc = prepare(p))) return rc;
+  const bool bf16 = p->dtype == DISTDL_BF16;
+  {  // matrix-core path
+    std::vector<GemmBlock> bx(p->P_fi), bw((size_t)p->P_fo * p->P_fi);
+    std::vector<ColsumBlock> bb(p->P_fo);
+    for (int j = 0; j < p->P_fi; ++j) {  // dx_j = sum_i dy_i W_ij
+      GemmBlock& g = bx[j];
+      std::memset(&g, 0, sizeof g);
+      g.M = (int32_t)p->n_b;
+      g.N = g.ldc = (int32_t)p->fi_size[j];
+      g.c = dx_dev[j];
+      g.nseg = std::min(p->P_fo, kGemmMaxSeg + 1);
+      for (int i = 0; i < p->P_fo && i < kGemmMaxSeg; ++i)
+        g.seg[i] = GemmSeg{dy_dev[i], W_dev[i * p->P_fi + j], (int32_t)p->fo_size[i], (int32_t)p->fo_size[i],
+                           (int32_t)p->fi_size[j], 0};
+    }
+    for (int i = 0; i < p->P_fo; ++i) {
+      for (int j = 0; j < p->P_fi; ++j) {  // dW_ij = dy_i^T x_j
+        GemmBlock& g = bw[(size_t)i * p->P_fi + j];
+        std::memset(&g, 0, sizeof g);
+        g.M = (int32_t)p->fo_size[i];
+        g.N = g.ldc = (int32_t)p->fi_size[j];
+        g.c = dW_dev[i * p->P_fi + j];
+        g.nseg = 1;
+        g.seg[0] = GemmSeg{dy_dev[i], x_dev[j], (int32_t)p->n_b, (int32_t)p->fo_size[i], (int32_t)p->fi_size[j], 0};
+      }
+      bb[i] = ColsumBlock{dy_dev[i], db_dev ? db_dev[i] : nullptr, (int32_t)p->n_b, (int32_t)p->fo_size[i]};
+    }
+    if (gemm_mfma_usable(bx, bf16, true, false) && gemm_mfma_usable(bw, bf16, false, false)) {
+      if ((rc = p->g_dx.upload(bx, st_)) || (rc = p->g_dw.upload(bw, st_))) return rc;
+      launch_gemm_mfma(p->g_dx.dev, bx, bf16, true, false, "affine_bwd_x_mfma", st_);
+      launch_gemm_mfma(p->g_dw.dev, bw, bf16, false, false, "affine_bwd_w_mfma", st_);
+      if (db_dev) {
+        if ((rc = p->g_db.upload(bb, st_))) return rc;
+        launch_colsum(p->g_db.dev, p->P_fo, (int)p->max_fo, bf16, st_);
+      }
+      DISTDL_HIP_TRY(hipGetLastError());
+      return DISTDL_OK;
+    }
+  }
   if ((rc = p->tab_x.upload(x_dev, p->P_fi, st_)) || (rc = p->tab_W.upload(W_dev, p->P_fo * p->P_fi, st_)) ||
       (rc = p->tab_dy.upload(dy_dev, p->P_fo, st_)) ||
       (rc = p->tab_dx.upload((const void* const*)dx_dev, p->P_fi, st_)) ||

@@ -1,0 +1,38 @@
+// Block descriptors and launchers of the MFMA GEMM used by the partitioned affine layer.
+#pragma once
+#include <cstdint>
+#include <vector>
+
+#include <hip/hip_runtime.h>
+
+namespace distdl {
+
+constexpr int kGemmMaxSeg = 8;
+
+struct GemmSeg {
+  const void* a;  // A_{o,s}
+  const void* b;  // B_{o,s}
+  int32_t K, lda, ldb, pad_;
+};
+
+struct GemmBlock {
+  GemmSeg seg[kGemmMaxSeg];
+  void* c;
+  const void* bias;  // length N, or null
+  int32_t M, N, ldc, nseg;
+};
+
+struct ColsumBlock {
+  const void* in;  // [n_b][n_f]
+  void* out;       // [n_f], or null (skip)
+  int32_t n_b, n_f;
+};
+
+// True when every operand can be moved in aligned 16-byte pieces (the MFMA kernel's requirement).
+bool gemm_mfma_usable(const std::vector<GemmBlock>& blocks, bool bf16, bool a_kc, bool b_kc);
+// a_kc: A[m][k] is contiguous along k (else along m); b_kc: B[k][n] is contiguous along k (else along n).
+int launch_gemm_mfma(const GemmBlock* d_blocks, const std::vector<GemmBlock>& blocks, bool bf16, bool a_kc, bool b_kc,
+                     const char* name, hipStream_t st);
+int launch_colsum(const ColsumBlock* d_blocks, int nblocks, int max_f, bool bf16, hipStream_t st);
+
+}  // namespace distdl

@@ -167,3 +167,99 @@ def test_affine_fwd_bwd(n_b, n_fi, n_fo, P_fo, P_fi, dtype, use_bias):
     # whole-layer check against the sequential definition
     assert_close(np.concatenate([host(t) for t in g_y], axis=1), layers.affine_forward(x, W, b if use_bias else None),
                  tol, "y vs sequential")
+
+
+# ---------------------------------------------------------------- full-size volumetric configuration
+def _sample_indices(rng, shape, count):
+    return [tuple(int(rng.integers(0, s)) for s in shape) for _ in range(count)]
+
+
+@pytest.mark.parametrize("name", ["cfg5", "cfg5u"])
+def test_conv_full_size_sampled(name):
+    """The volumetric configuration at its full size, in the launch configuration the benchmark
+    times: sampled outputs against the plain definition of Sec. 4 (cross-correlation and its
+    adjoint), computed one by one in fp64; halo cells against the global tensor (exact)."""
+    require_gpu()
+    cfg = dict(syn.CONFIGS[name])
+    part = oracle_partition(cfg)
+    case = syn.conv_case(cfg, part.global_out_shape())
+    x, w, dy, bias = case["x"], case["w"].astype(np.float64), case["dy"], case["bias"]
+    x_bufs, y, dx_bufs, dw, db = _run_conv(cfg, part, case, True)
+    s, p, k = cfg["stride"], cfg["padding"], cfg["ksize"]
+    n_in, n_out = cfg["in_shape"], part.global_out_shape()
+    rng = np.random.default_rng(0)
+
+    # H: sampled workers' buffers equal the zero-extended global tensor, bit for bit
+    for wk in (0, 21, 42, 63):
+        assert np.array_equal(from_cl(x_bufs[wk]), prim.expected_buffer_after_halo(x, part, wk)), f"H worker {wk}"
+
+    def window(o):
+        """Input window of output index o with zero padding, [ci, k0, k1, k2] in fp64."""
+        win = np.zeros((cfg["c_in"],) + tuple(k))
+        lo = [o[d] * s[d] - p[d] for d in range(3)]
+        src = tuple(slice(max(lo[d], 0), min(lo[d] + k[d], n_in[d])) for d in range(3))
+        dst = tuple(slice(max(lo[d], 0) - lo[d], min(lo[d] + k[d], n_in[d]) - lo[d]) for d in range(3))
+        win[(slice(None),) + dst] = x[(0, slice(None)) + src]
+        return win
+
+    y_glob_scale = 0.0
+    errs = []
+    owner = {}
+    for wk in range(part.n_workers):
+        owner[tuple(part.g(wk, d)["out_start"] for d in range(3))] = wk
+    y_host = {}
+    for o in _sample_indices(rng, n_out, 200):
+        wk = next(wkk for wkk in range(part.n_workers)
+                  if all(part.g(wkk, d)["out_start"] <= o[d] < part.g(wkk, d)["out_start"] + part.g(wkk, d)["out_size"]
+                         for d in range(3)))
+        if wk not in y_host:
+            y_host[wk] = from_cl(y[wk])
+        lo = tuple(o[d] - part.g(wk, d)["out_start"] for d in range(3))
+        want = np.einsum("ocijk,cijk->o", w, window(o)) + bias
+        got = y_host[wk][(0, slice(None)) + lo]
+        errs.append(np.abs(got - want).max())
+        y_glob_scale = max(y_glob_scale, np.abs(want).max())
+    assert max(errs) <= TOL32 * y_glob_scale, (max(errs), y_glob_scale)
+
+    # dw: sampled entries; dw[co,ci,kappa] = sum_o dy[co,o] x[ci, o*s - p + kappa]
+    dw_host = dw.cpu().numpy()
+    dy64 = dy[0].astype(np.float64)
+    worst, scale = 0.0, np.abs(dw_host).max()
+    for (co, ci, k0, k1, k2) in _sample_indices(rng, (cfg["c_out"], cfg["c_in"]) + tuple(k), 24):
+        kap = (k0, k1, k2)
+        # output range whose tap kappa lies inside the input
+        o_lo = [max(0, -((kap[d] - p[d]) // s[d])) for d in range(3)]
+        o_hi = [min(n_out[d] - 1, (n_in[d] - 1 + p[d] - kap[d]) // s[d]) for d in range(3)]
+        osl = tuple(slice(o_lo[d], o_hi[d] + 1) for d in range(3))
+        isl = tuple(slice(o_lo[d] * s[d] - p[d] + kap[d], o_hi[d] * s[d] - p[d] + kap[d] + 1, s[d]) for d in range(3))
+        want = float(np.sum(dy64[(co,) + osl] * x[(0, ci) + isl].astype(np.float64)))
+        worst = max(worst, abs(dw_host[co, ci, k0, k1, k2] - want))
+    assert worst <= TOL32 * scale, (worst, scale)
+    db_want = dy64.sum(axis=(1, 2, 3))
+    assert_close(db.cpu().numpy(), db_want, TOL32, "db")
+
+    # dx: sampled input cells; dx[ci,i] = sum_{co,kappa: (i + p - kappa) % s == 0} w[co,ci,kappa] dy[co,(i+p-kappa)/s]
+    dx_host = {}
+    worst, scale = 0.0, 0.0
+    for i in _sample_indices(rng, n_in, 120):
+        wk = next(wkk for wkk in range(part.n_workers)
+                  if all(part.g(wkk, d)["in_start"] <= i[d] < part.g(wkk, d)["in_start"] + part.g(wkk, d)["in_size"]
+                         for d in range(3)))
+        if wk not in dx_host:
+            dx_host[wk] = from_cl(dx_bufs[wk])
+        loc = tuple(i[d] - part.g(wk, d)["in_start"] + part.g(wk, d)["bulk_off"] for d in range(3))
+        want = np.zeros(cfg["c_in"])
+        for kap in np.ndindex(*k):
+            q = [i[d] + p[d] - kap[d] for d in range(3)]
+            if all(q[d] % s[d] == 0 and 0 <= q[d] // s[d] < n_out[d] for d in range(3)):
+                o = tuple(q[d] // s[d] for d in range(3))
+                want += w[(slice(None), slice(None)) + kap].T @ dy64[(slice(None),) + o]
+        got = dx_host[wk][(0, slice(None)) + loc]
+        worst = max(worst, np.abs(got - want).max())
+        scale = max(scale, np.abs(want).max())
+    assert worst <= TOL32 * scale, (worst, scale)
+    # halo and pad cells of dx end cleared (H* ran)
+    for wk in list(dx_host)[:4]:
+        mask = np.ones(part.buf_shape(wk), dtype=bool)
+        mask[part.bulk_slices(wk)] = False
+        assert not dx_host[wk][:, :, mask].any()
