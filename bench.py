@@ -240,6 +240,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="cfg5", choices=["cfg5", "cfg2", "cfg3", "cfg3-bf16"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 1 GiB copy (bcast_kernel, k = 1) before the timed region, as the "
+                         "known-size reference for rocprofv3 FETCH_SIZE / WRITE_SIZE readings")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (all P virtual workers share its HBM); "
@@ -255,6 +258,12 @@ def main():
         wl = ConvWorkload(args.workload)
     else:
         wl = AffineWorkload("cfg3", "bf16" if args.workload.endswith("bf16") else "f32")
+    if args.calibrate_copy:
+        src = torch.ones(1 << 28, device="cuda")
+        dst = torch.empty_like(src)
+        dd.distdl_bcast_fwd([src], [dst], 1)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         wl.step()
     torch.cuda.synchronize()

@@ -393,9 +393,11 @@ __global__ __launch_bounds__(256, 2) void wgrad_lds_kernel(const WorkerDev* __re
                                                            WgradArgs a) {
   extern __shared__ float4 wg_lds[];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, h = lane >> 5, m = lane & 31;
+  // kernel rows (t0, t1) with t1 >= t1_first, four per workgroup
+  const int nleft = a.k[1] - a.t1_first;
   const int trow = blockIdx.x * 4 + wave;
-  if (trow >= a.k[0] * a.k[1]) return;  // no workgroup barrier below
-  const int t0 = trow / a.k[1], t1 = trow - t0 * a.k[1];
+  if (trow >= a.k[0] * nleft) return;  // no workgroup barrier below
+  const int t0 = trow / nleft, t1 = a.t1_first + trow - t0 * nleft;
   const int nco_t = (a.co + 31) / 32;
   const int ci_t = blockIdx.y / nco_t, co_t = blockIdx.y - ci_t * nco_t;
   const int worker = blockIdx.z / a.nchunks, chunk = blockIdx.z - worker * a.nchunks;
@@ -921,7 +923,8 @@ static bool wgrad_rows_shape_ok(const distdl_plan* p) {
   if (p->n_ci % 4 || p->n_co % 4) return false;
   if (p->ksize[1] > 8 || p->ksize[2] > 5 || p->stride[2] > 2 || p->stride[1] > span) return false;
   if ((size_t)span * ncell * 128 + 4096 > 96 * 1024) return false;
-  if (p->stride[1] * ncell * 8 + 256 > 6 * 64 * p->ksize[1]) return false;
+  if (p->stride[1] * ncell * 8 + 256 > 6 * 64 * std::min(p->ksize[1], 4)) return false;
+  if (ncell > 72) return false;  // the wave-private kernel takes the rows beyond the fourth
   if ((double)p->n_b * p->max_buf_cells * std::max(p->n_ci, p->n_co) * 4.0 >= 2147480000.0) return false;
   return true;
 }
@@ -971,8 +974,12 @@ int conv_wgrad_mfma(distdl_plan* p, float* partial, hipStream_t st) {
     aligned = (uintptr_t)p->tab_x.host[w] % 16 == 0 && (uintptr_t)p->tab_dy.host[w] % 16 == 0;
   const int lds = 4 * (a.ncell + 32) * 128;
   if (aligned && wgrad_rows_shape_ok(p)) {
+    // Kernel rows t1 < k1_main go to the shared-rows kernel, one wave per row and four waves (one per
+    // SIMD) when the kernel has at least four rows; the remaining rows go to the wave-private kernel.
+    const int k1_main = a.k[1] >= 4 ? 4 : a.k[1];
+    a.span = (k1_main - 1) * a.dil[1] + 1;
     const int rlds = a.span * a.ncell * 128 + 4096;
-    dim3 rgrid((unsigned)a.k[0], grid.y, grid.z), rblock(64 * a.k[1]);
+    dim3 rgrid((unsigned)a.k[0], grid.y, grid.z), rblock(64 * k1_main);
     ProfScope prof("conv_bwd_weight_mfma", st);
 #define DISTDL_LAUNCH_ROWS(K2_, S2_)                                                                                \
   do {                                                                                                              \
@@ -987,6 +994,17 @@ int conv_wgrad_mfma(distdl_plan* p, float* partial, hipStream_t st) {
     else if (a.s[2] == 1) DISTDL_LAUNCH_ROWS(5, 1);
     else DISTDL_LAUNCH_ROWS(5, 2);
 #undef DISTDL_LAUNCH_ROWS
+    if (k1_main < a.k[1]) {
+      a.t1_first = k1_main;
+      dim3 lgrid((unsigned)((a.k[0] * (a.k[1] - k1_main) + 3) / 4), grid.y, grid.z);
+      if (a.k[2] <= 3)
+        hipLaunchKernelGGL((wgrad_lds_kernel<3, 9>), lgrid, dim3(256), lds, st, p->d_workers, p->tab_x.dev,
+                           p->tab_dy.dev, partial, a);
+      else
+        hipLaunchKernelGGL((wgrad_lds_kernel<5, 9>), lgrid, dim3(256), lds, st, p->d_workers, p->tab_x.dev,
+                           p->tab_dy.dev, partial, a);
+      a.t1_first = 0;
+    }
   } else {
     ProfScope prof("conv_bwd_weight_mfma", st);
     if (aligned && a.ncell <= 72 && a.k[2] <= 3)
