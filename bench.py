@@ -51,6 +51,7 @@ class ConvWorkload:
         import paper_2006_03108_amd as dd
         import synthetic_inputs as syn
         self.dd, self.torch, self.name = dd, torch, name
+        self.tag = name
         c = self.cfg = dict(syn.CONFIGS[name])
         self.plan = dd.distdl_plan_create(c["D"], c["n_b"], c["c_in"], c["c_out"], c["in_shape"], c["P"], c["ksize"],
                                           c["stride"], c["padding"], c["dilation"])
@@ -137,6 +138,7 @@ class AffineWorkload:
         import paper_2006_03108_amd as dd
         import synthetic_inputs as syn
         self.dd, self.torch = dd, torch
+        self.tag = "cfg3" if dtype == "f32" else "cfg3-bf16"
         c = self.cfg = dict(syn.CONFIGS["cfg3"])
         td = torch.float32 if dtype == "f32" else torch.bfloat16
         self.plan = dd.distdl_affine_plan_create(c["n_b"], c["n_fi"], c["n_fo"], c["P_fo"], c["P_fi"], td)
@@ -218,14 +220,18 @@ def kernel_rooflines(workload, report, traffic):
                 if mb:   # also against min(MFMA peak, arithmetic intensity x HBM peak)
                     roof = min(peak, work / mb * HBM_PEAK_GBS / 1e3)
                     entry.update(min_bytes=mb, roofline_tflops=roof, frac_of_roofline=ach / roof)
-            entry["traffic"] = traffic.get(f"{workload.describe['workload'].split(':')[0]}/{name}")
+            tr = traffic.get(f"{workload.tag}/{name}")
+            entry["traffic"] = None if tr is None else tr["fetch_bytes"] + tr["write_bytes"]
+            if tr is not None:
+                entry["traffic_fetch"], entry["traffic_write"] = tr["fetch_bytes"], tr["write_bytes"]
         out[name] = entry
     return out
 
 
 def load_traffic():
-    """HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
-    (summaries under profiles/); keyed "<workload>/<kernel>"."""
+    """HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by the
+    readings of a plain 1 GiB copy (summaries and commands under profiles/); keyed
+    "<workload>/<profiling scope of the library>"."""
     path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
     if os.path.exists(path):
         with open(path) as f:

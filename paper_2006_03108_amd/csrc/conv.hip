@@ -174,19 +174,33 @@ __global__ __launch_bounds__(256) void conv_bwd_weight_direct_kernel(const Worke
 __global__ __launch_bounds__(256) void conv_reduce_dw_kernel(const float* __restrict__ partial, int nparts,
                                                              float* __restrict__ dw, float* __restrict__ db,
                                                              ConvDev c) {
+  // 64 elements per block, 4 lanes of partials each; every lane adds its partials in ascending order
+  // (four independent chains for latency), the lanes are then combined in a fixed order
   const int nw = c.taps * c.ci * c.co;
-  int idx = blockIdx.x * 256 + threadIdx.x;
-  if (idx >= nw + c.co) return;
-  float acc = 0.f;
-  for (int p = 0; p < nparts; ++p) acc += partial[(size_t)p * (nw + c.co) + idx];
+  const int e = threadIdx.x & 63, lanep = threadIdx.x >> 6;
+  const int idx = blockIdx.x * 64 + e;
+  const size_t slot = (size_t)nw + c.co;
+  float acc[4] = {0.f, 0.f, 0.f, 0.f};
+  if (idx < nw + c.co) {
+    int p = lanep;
+    for (; p + 12 < nparts; p += 16)
+#pragma unroll
+      for (int u = 0; u < 4; ++u) acc[u] += partial[(size_t)(p + 4 * u) * slot + idx];
+    for (; p < nparts; p += 4) acc[0] += partial[(size_t)p * slot + idx];
+  }
+  __shared__ float red[4][64];
+  red[lanep][e] = (acc[0] + acc[1]) + (acc[2] + acc[3]);
+  __syncthreads();
+  if (lanep != 0 || idx >= nw + c.co) return;
+  const float sum = (red[0][e] + red[1][e]) + (red[2][e] + red[3][e]);
   if (idx >= nw) {
-    if (db) db[idx - nw] = acc;
+    if (db) db[idx - nw] = sum;
   } else {
     int co = idx % c.co;
     int r = idx / c.co;
     int ci = r % c.ci;
     int t = r / c.ci;
-    dw[((size_t)co * c.ci + ci) * c.taps + t] = acc;
+    dw[((size_t)co * c.ci + ci) * c.taps + t] = sum;
   }
 }
 
@@ -312,7 +326,7 @@ int distdl_conv_bwd(distdl_plan* plan, const void* const x_bufs_dev[], const voi
   }
   {
     ProfScope prof("conv_reduce_dw", st);
-    hipLaunchKernelGGL(conv_reduce_dw_kernel, dim3((unsigned)((nw + 255) / 256)), dim3(256), 0, st,
+    hipLaunchKernelGGL(conv_reduce_dw_kernel, dim3((unsigned)((nw + 63) / 64)), dim3(256), 0, st,
                        (const float*)workspace_dev, nchunks * plan->n_workers, (float*)dw_dev, (float*)dbias_dev, c);
   }
   DISTDL_HIP_TRY(hipGetLastError());

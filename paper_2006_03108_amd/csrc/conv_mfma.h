@@ -36,6 +36,7 @@ struct WgradArgs {
   int32_t ncell;    // input cells the taps of 32 consecutive output columns read
   int32_t span;     // input rows the shared-rows kernel's taps cover: (rows - 1) * dil1 + 1
   int32_t t1_first; // first kernel row the wave-private kernel handles
+  int32_t ob;       // output rows per work unit of the shared-rows kernel
   int64_t slot;     // floats per (worker, chunk) partial: taps*ci*co + co
 };
 

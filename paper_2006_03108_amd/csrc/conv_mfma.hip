@@ -538,9 +538,11 @@ __global__ __launch_bounds__(512, 2) void wgrad_rows_kernel(const WorkerDev* __r
   const int step_pieces = s1 * row_vec4 + 256;
   const int row_cells = wd.buf[2] - wd.origin[2];
   const int O1 = wd.out[1], O2 = wd.out[2], nseg = (O2 + 31) / 32;
-  const int nplanes = a.n_b * wd.out[0];
-  const int per = (nplanes + a.nchunks - 1) / a.nchunks;
-  const int plane_end = min(nplanes, (chunk + 1) * per);
+  // work units: (plane (n, o0), block of a.ob output rows); a chunk is a contiguous range of units
+  const int nblk1 = (O1 + a.ob - 1) / a.ob;
+  const int nunits = a.n_b * wd.out[0] * nblk1;
+  const int per = (nunits + a.nchunks - 1) / a.nchunks;
+  const int unit_end = min(nunits, (chunk + 1) * per);
 
   // piece -> (global byte offset relative to the step's base, LDS byte offset relative to the ring slot)
   // is the same at every step except for the row index, which is folded into scalar bases below
@@ -600,12 +602,13 @@ __global__ __launch_bounds__(512, 2) void wgrad_rows_kernel(const WorkerDev* __r
   };
 
   const uint32_t lane_x = (uint32_t)(h * S2 * 32 + m) * 4u, lane_y = ys_base + (uint32_t)(h * 32 + m) * 4u;
-  for (int plane = chunk * per; plane < plane_end; ++plane) {
+  for (int unit = chunk * per; unit < unit_end; ++unit) {
+    const int plane = unit / nblk1, o1_begin = (unit - plane * nblk1) * a.ob, o1_end = min(O1, o1_begin + a.ob);
     const int o0 = plane % wd.out[0], n = plane / wd.out[0];
     for (int seg = 0; seg < nseg; ++seg) {
       setup_pieces(seg);
-      __syncthreads();  // previous plane / segment fully consumed
-      // prime the ring with window rows 0 .. span-s1-1 of step 0
+      __syncthreads();  // previous unit / segment fully consumed
+      // prime the ring with the first span-s1 window rows of step o1_begin
       {
         const int c0 = wd.origin[0] + o0 * a.s[0] + t0 * a.dil[0];
         const int prime = (span - s1) * row_vec4;
@@ -613,18 +616,19 @@ __global__ __launch_bounds__(512, 2) void wgrad_rows_kernel(const WorkerDev* __r
           const int rr = piece / row_vec4, rest = piece - rr * row_vec4;
           const int cell = rest >> 3, q4 = (rest & 7) * 4;
           uint32_t off = kOob;
-          if (seg * 32 * S2 + cell < row_cells && ci_t * 32 + q4 < a.ci && wd.origin[1] + rr < wd.buf[1])
-            off = (((uint32_t)n * sxn + (uint32_t)c0 * sx0 + (uint32_t)(wd.origin[1] + rr) * sx1 +
+          const int wrow = o1_begin * s1 + rr;  // window row, relative to the first tap of output row 0
+          if (seg * 32 * S2 + cell < row_cells && ci_t * 32 + q4 < a.ci && wd.origin[1] + wrow < wd.buf[1])
+            off = (((uint32_t)n * sxn + (uint32_t)c0 * sx0 + (uint32_t)(wd.origin[1] + wrow) * sx1 +
                     (wd.origin[2] + seg * 32 * S2 + cell) * sx2 + ci_t * 32 + q4)) * 4u;
-          *(u32x4*)(ldsb + ((uint32_t)(rr % span) * row_vec4 + rest) * 16u) =
+          *(u32x4*)(ldsb + ((uint32_t)(wrow % span) * row_vec4 + rest) * 16u) =
               __builtin_amdgcn_raw_buffer_load_b128(rx, off, 0, 0);
         }
       }
-      fetch(n, o0, 0);
-      for (int o1 = 0; o1 < O1; ++o1) {
+      fetch(n, o0, o1_begin);
+      for (int o1 = o1_begin; o1 < o1_end; ++o1) {
         stash(o1);
         __syncthreads();
-        if (o1 + 1 < O1) fetch(n, o0, o1 + 1);  // in flight while this step multiplies
+        if (o1 + 1 < o1_end) fetch(n, o0, o1 + 1);  // in flight while this step multiplies
         const uint32_t slot = (uint32_t)((o1 * s1 + t1 * a.dil[1]) % span);
         const char* xrow = ldsb + slot * row_vec4 * 16u + lane_x;
         const char* yrow = ldsb + lane_y;
@@ -929,17 +933,36 @@ static bool wgrad_rows_shape_ok(const distdl_plan* p) {
   return true;
 }
 
+// Output rows per work unit of the shared-rows kernel: whole planes when there are enough of them to
+// fill the chip, else blocks of rows (each block re-reads span - s1 rows to prime its ring).
+static int wgrad_row_block(const distdl_plan* p) {
+  int64_t planes = 0, o1max = 1;
+  for (const WorkerDev& wd : p->workers) {
+    planes = std::max<int64_t>(planes, p->n_b * wd.out[0]);
+    o1max = std::max<int64_t>(o1max, wd.out[1]);
+  }
+  int64_t tiles = ((p->n_ci + 31) / 32) * ((p->n_co + 31) / 32);
+  int64_t blocks = (int64_t)p->ksize[0] * tiles * p->n_workers;
+  int64_t want_units = (2048 + blocks - 1) / blocks;  // per worker
+  if (planes >= want_units) return (int)o1max;
+  int64_t per_plane = (want_units + planes - 1) / planes;
+  return (int)std::max<int64_t>(8, (o1max + per_plane - 1) / per_plane);
+}
+
 int wgrad_chunks(const distdl_plan* p) {
   int64_t tiles = ((p->n_ci + 31) / 32) * ((p->n_co + 31) / 32);
   if (wgrad_rows_shape_ok(p)) {
-    // chunks of (n, o0) planes; about 2048 workgroups, preferring a chunk count that splits evenly
-    int64_t planes = 0;
-    for (const WorkerDev& wd : p->workers) planes = std::max<int64_t>(planes, p->n_b * wd.out[0]);
+    // chunks of work units (plane, block of output rows); about 2048 workgroups, preferring a chunk
+    // count that splits the units evenly
+    int64_t units = 0;
+    const int ob = wgrad_row_block(p);
+    for (const WorkerDev& wd : p->workers)
+      units = std::max<int64_t>(units, p->n_b * wd.out[0] * ((wd.out[1] + ob - 1) / ob));
     int64_t blocks = (int64_t)p->ksize[0] * tiles * p->n_workers;
-    int64_t want = std::max<int64_t>(1, std::min<int64_t>(planes, (2048 + blocks - 1) / blocks));
+    int64_t want = std::max<int64_t>(1, std::min<int64_t>(units, (2048 + blocks - 1) / blocks));
     int64_t best = want, best_pad = INT64_MAX;
-    for (int64_t c = want; c <= std::min<int64_t>(planes, want + 4); ++c) {
-      int64_t pad = (planes + c - 1) / c * c - planes;
+    for (int64_t c = want; c <= std::min<int64_t>(units, want + 4); ++c) {
+      int64_t pad = (units + c - 1) / c * c - units;
       if (pad < best_pad) best_pad = pad, best = c;
     }
     return (int)best;
@@ -969,6 +992,7 @@ int conv_wgrad_mfma(distdl_plan* p, float* partial, hipStream_t st) {
   // LDS-staged variants when 16-byte pieces are possible and the segment fits
   a.ncell = 31 * a.s[2] + (a.k[2] - 1) * a.dil[2] + 1;
   a.span = (a.k[1] - 1) * a.dil[1] + 1;
+  a.ob = wgrad_row_block(p);
   bool aligned = a.ci % 4 == 0 && a.co % 4 == 0;
   for (int w = 0; w < p->n_workers && aligned; ++w)
     aligned = (uintptr_t)p->tab_x.host[w] % 16 == 0 && (uintptr_t)p->tab_dy.host[w] % 16 == 0;
