@@ -194,6 +194,45 @@ int distdl_affine_bwd(distdl_affine_plan* plan, const void* const x_dev[], const
                       void* const db_dev[], void* stream);
 
 /* ------------------------------------------------------------------------
+ * Glue of the example network (Sec. 5, App. C), fp32, channels-last.  Small,
+ * latency-bound calls that let a whole partitioned network step run through
+ * the library; same conventions as above.
+ *
+ * relu_fwd / relu_bwd: point-wise layers need no data movement (Sec. 4):
+ *   y = max(x, 0);  dx = x > 0 ? dy : 0, over n arrays of count[i] elements.
+ * maxpool_fwd / maxpool_bwd: the Forward / Adjoint Pooling Algorithms of
+ *   Sec. 4 on a sliding-kernel plan with n_c_in == n_c_out: x <- H x, then the
+ *   local max over each window starting at the worker's origin (which skips
+ *   "extra" input, App. B.1); backward routes dy to the first maximum of each
+ *   window (row-major tap order) over the whole padded buffer, then dx <- H* dx.
+ *   x_bufs_dev of maxpool_bwd must hold H x.
+ * bulk_copy: dense [n_b][in_size..][n_c] per worker <-> the bulk of the padded
+ *   buffers (to_bufs != 0: dense -> buffers), the hand-over between two layers
+ *   whose partitions of the same tensor agree.
+ * repartition_fwd / repartition_adj: the generalized all-to-all of Sec. 3 for
+ *   the case the example needs: the plan's per-worker OUTPUT blocks
+ *   [n_b][out_size..][n_c_out] -> P_f feature blocks [n_b][f_j] of the
+ *   row-major flattening of [n_c][out_0..] (balanced split); the adjoint is
+ *   the inverse permutation.
+ * mse_fwd_bwd: loss = mean over all elements of (y - t)^2 into *loss_dev (one
+ *   double in device memory), dy = 2 (y - t) / N; y, t, dy are lists of n <= 16
+ *   arrays.
+ * ---------------------------------------------------------------------- */
+int distdl_relu_fwd(const void* const x_dev[], void* const y_dev[], const int64_t count[], int n, void* stream);
+int distdl_relu_bwd(const void* const x_dev[], const void* const dy_dev[], void* const dx_dev[],
+                    const int64_t count[], int n, void* stream);
+int distdl_maxpool_fwd(distdl_plan* plan, void* const x_bufs_dev[], void* const y_dev[], void* stream);
+int distdl_maxpool_bwd(distdl_plan* plan, const void* const x_bufs_dev[], const void* const dy_dev[],
+                       void* const dx_bufs_dev[], void* stream);
+int distdl_bulk_copy(distdl_plan* plan, void* const dense_dev[], void* const bufs_dev[], int to_bufs, void* stream);
+int distdl_repartition_fwd(distdl_plan* plan, const void* const src_dev[], int P_f, void* const dst_dev[],
+                           void* stream);
+int distdl_repartition_adj(distdl_plan* plan, const void* const gdst_dev[], int P_f, void* const gsrc_dev[],
+                           void* stream);
+int distdl_mse_fwd_bwd(const void* const y_dev[], const void* const t_dev[], void* const dy_dev[],
+                       const int64_t count[], int n, double* loss_dev, void* stream);
+
+/* ------------------------------------------------------------------------
  * Euclidean inner product over a list of device arrays (Sec. 2, second
  * displayed equation; the direct sum over workers of Sec. 3), accumulated in
  * fp64 on the device.  result_dev points to ONE double in device memory.

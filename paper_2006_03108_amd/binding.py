@@ -55,6 +55,14 @@ _SIGS = {
     "distdl_affine_fwd": [_vp, _pp, _pp, _pp, _pp, _vp],
     "distdl_affine_bwd": [_vp, _pp, _pp, _pp, _pp, _pp, _pp, _vp],
     "distdl_dot": [_pp, _pp, _p64, _i, _i, _vp, _vp],
+    "distdl_relu_fwd": [_pp, _pp, _p64, _i, _vp],
+    "distdl_relu_bwd": [_pp, _pp, _pp, _p64, _i, _vp],
+    "distdl_maxpool_fwd": [_vp, _pp, _pp, _vp],
+    "distdl_maxpool_bwd": [_vp, _pp, _pp, _pp, _vp],
+    "distdl_bulk_copy": [_vp, _pp, _pp, _i, _vp],
+    "distdl_repartition_fwd": [_vp, _pp, _i, _pp, _vp],
+    "distdl_repartition_adj": [_vp, _pp, _i, _pp, _vp],
+    "distdl_mse_fwd_bwd": [_pp, _pp, _pp, _p64, _i, _vp, _vp],
     "distdl_plan_stats": [_vp, _p64],
     "distdl_profile_enable": [_i],
     "distdl_profile_report": [C.c_char_p, C.c_size_t],
@@ -227,6 +235,43 @@ def distdl_affine_fwd(plan, x, W, b, y):
 def distdl_affine_bwd(plan, x, W, dy, dx, dW, db):
     _check(lib.distdl_affine_bwd(plan.handle, _ptrs(x), _ptrs(W), _ptrs(dy), _ptrs(dx), _ptrs(dW),
                                  None if db is None else _ptrs(db), _stream()))
+
+
+def _numels(ts):
+    return _arr(C.c_int64, [t.numel() for t in ts])
+
+
+def distdl_relu_fwd(x, y):
+    _check(lib.distdl_relu_fwd(_ptrs(x), _ptrs(y), _numels(x), len(x), _stream()))
+
+
+def distdl_relu_bwd(x, dy, dx):
+    _check(lib.distdl_relu_bwd(_ptrs(x), _ptrs(dy), _ptrs(dx), _numels(x), len(x), _stream()))
+
+
+def distdl_maxpool_fwd(plan, x_bufs, y):
+    _check(lib.distdl_maxpool_fwd(plan.handle, _ptrs(x_bufs), _ptrs(y), _stream()))
+
+
+def distdl_maxpool_bwd(plan, x_bufs, dy, dx_bufs):
+    _check(lib.distdl_maxpool_bwd(plan.handle, _ptrs(x_bufs), _ptrs(dy), _ptrs(dx_bufs), _stream()))
+
+
+def distdl_bulk_copy(plan, dense, bufs, to_bufs):
+    _check(lib.distdl_bulk_copy(plan.handle, _ptrs(dense), _ptrs(bufs), int(to_bufs), _stream()))
+
+
+def distdl_repartition_fwd(plan, src, dst):
+    _check(lib.distdl_repartition_fwd(plan.handle, _ptrs(src), len(dst), _ptrs(dst), _stream()))
+
+
+def distdl_repartition_adj(plan, gdst, gsrc):
+    _check(lib.distdl_repartition_adj(plan.handle, _ptrs(gdst), len(gdst), _ptrs(gsrc), _stream()))
+
+
+def distdl_mse_fwd_bwd(y, t, dy, loss):
+    """loss: a 1-element float64 device tensor."""
+    _check(lib.distdl_mse_fwd_bwd(_ptrs(y), _ptrs(t), _ptrs(dy), _numels(y), len(y), loss.data_ptr(), _stream()))
 
 
 def distdl_dot(a, b, result):

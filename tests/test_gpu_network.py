@@ -1,0 +1,253 @@
+"""GPU parity of the small-CNN configuration end to end: one forward + backward step of
+conv5x5(6)-ReLU-maxpool2-conv5x5(16)-ReLU-maxpool2-affine 400-120-84-10 with MSE loss, conv / pool layers
+on a 2x2 feature-space partition, affine layers on 2x2 weight partitions, every step through the C ABI,
+against the oracle's distributed network (Sec. 5 / App. C), plus unit parity of the glue calls."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2006_03108_amd as dd
+import synthetic_inputs as syn
+from oracle import geometry as geo
+from oracle import layers
+from oracle import network
+from oracle import primitives as prim
+from tests.gpu_util import assert_close, from_cl, require_gpu, to_cl, w_to_dev
+
+pytestmark = pytest.mark.gpu
+TOL32 = 1e-5
+ONE2 = (1, 1)
+
+
+class ConvLayer:
+    def __init__(self, n_b, c_in, c_out, in_shape, P, k, pad):
+        self.plan = dd.distdl_plan_create(2, n_b, c_in, c_out, in_shape, P, (k, k), ONE2, (pad, pad), ONE2)
+        self.geoms = [self.plan.query(w) for w in range(self.plan.n_workers)]
+        self.x = [torch.zeros([n_b] + g["buf_shape"] + [c_in], device="cuda") for g in self.geoms]
+        self.y = [torch.empty([n_b] + g["out_size"] + [c_out], device="cuda") for g in self.geoms]
+        self.dx = [torch.empty_like(t) for t in self.x]
+        self.dense_in = [torch.empty([n_b] + g["in_size"] + [c_in], device="cuda") for g in self.geoms]
+        self.ws = torch.empty(max(dd.distdl_conv_bwd_workspace(self.plan), 16), dtype=torch.uint8, device="cuda")
+
+
+class PoolLayer:
+    def __init__(self, n_b, c, in_shape, P):
+        self.plan = dd.distdl_plan_create(2, n_b, c, c, in_shape, P, (2, 2), (2, 2), (0, 0), ONE2)
+        self.geoms = [self.plan.query(w) for w in range(self.plan.n_workers)]
+        self.x = [torch.zeros([n_b] + g["buf_shape"] + [c], device="cuda") for g in self.geoms]
+        self.y = [torch.empty([n_b] + g["out_size"] + [c], device="cuda") for g in self.geoms]
+        self.dx = [torch.empty_like(t) for t in self.x]
+        self.dense_in = [torch.empty([n_b] + g["in_size"] + [c], device="cuda") for g in self.geoms]
+
+
+def _split_affine(W, b, P_fo, P_fi):
+    rows, cols = layers.feature_blocks(W.shape[0], P_fo), layers.feature_blocks(W.shape[1], P_fi)
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).float().cuda()
+    return [dev(W[r][:, c]) for r in rows for c in cols], [dev(b[r]) for r in rows], rows, cols
+
+
+@pytest.mark.parametrize("n_b", [256, 6])
+def test_small_cnn_step_matches_oracle(n_b):
+    require_gpu()
+    case = syn.cnn_case(dict(syn.CONFIGS["cfg4"], n_b=n_b))
+    par = {k: v.astype(np.float64) for k, v in case["params"].items()}
+    rng = np.random.default_rng(2)
+    for k in par:                                      # non-zero biases exercise db
+        if k.endswith("_b"):
+            par[k] = (0.1 * rng.standard_normal(par[k].shape)).astype(np.float32).astype(np.float64)
+    img, tgt = case["images"], case["target"]
+    loss_want, out_want, g_want = network.distributed_step(img.astype(np.float64), tgt.astype(np.float64), par)
+
+    P, Pf = (2, 2), 2
+    c1 = ConvLayer(n_b, 1, 6, (28, 28), P, 5, 2)
+    p2 = PoolLayer(n_b, 6, (28, 28), P)
+    c3 = ConvLayer(n_b, 6, 16, (14, 14), P, 5, 0)
+    p4 = PoolLayer(n_b, 16, (10, 10), P)
+    part1 = geo.Partition.for_kernel((28, 28), P, (5, 5), ONE2, (2, 2), ONE2)
+    w1, b1 = w_to_dev(par["c1_w"]), w_to_dev(par["c1_b"])
+    w3, b3 = w_to_dev(par["c3_w"]), w_to_dev(par["c3_b"])
+    W5, B5, rows5, _ = _split_affine(par["c5_w"], par["c5_b"], Pf, Pf)
+    W6, B6, rows6, _ = _split_affine(par["f6_w"], par["f6_b"], Pf, Pf)
+    Wo, Bo, rowso, _ = _split_affine(par["out_w"], par["out_b"], Pf, Pf)
+    a5p = dd.distdl_affine_plan_create(n_b, 400, 120, Pf, Pf)
+    a6p = dd.distdl_affine_plan_create(n_b, 120, 84, Pf, Pf)
+    aop = dd.distdl_affine_plan_create(n_b, 84, 10, Pf, Pf)
+    new = lambda shapes: [torch.empty(s, device="cuda") for s in shapes]
+    like = lambda ts: [torch.empty_like(t) for t in ts]
+
+    # ---- forward
+    for w, b in enumerate(prim.scatter_bulk(img, part1, fill=np.float32(0.0))):
+        c1.x[w].copy_(to_cl(b))
+    dd.distdl_conv_fwd(c1.plan, c1.x, w1, b1, c1.y)
+    r1 = like(c1.y)
+    dd.distdl_relu_fwd(c1.y, r1)
+    dd.distdl_bulk_copy(p2.plan, r1, p2.x, True)
+    dd.distdl_maxpool_fwd(p2.plan, p2.x, p2.y)
+    dd.distdl_bulk_copy(c3.plan, p2.y, c3.x, True)
+    dd.distdl_conv_fwd(c3.plan, c3.x, w3, b3, c3.y)
+    r3 = like(c3.y)
+    dd.distdl_relu_fwd(c3.y, r3)
+    dd.distdl_bulk_copy(p4.plan, r3, p4.x, True)
+    dd.distdl_maxpool_fwd(p4.plan, p4.x, p4.y)
+    f = new([(n_b, 200), (n_b, 200)])
+    dd.distdl_repartition_fwd(p4.plan, p4.y, f)
+    a5 = new([(n_b, 60), (n_b, 60)])
+    dd.distdl_affine_fwd(a5p, f, W5, B5, a5)
+    r5 = like(a5)
+    dd.distdl_relu_fwd(a5, r5)
+    a6 = new([(n_b, 42), (n_b, 42)])
+    dd.distdl_affine_fwd(a6p, r5, W6, B6, a6)
+    r6 = like(a6)
+    dd.distdl_relu_fwd(a6, r6)
+    out = new([(n_b, 5), (n_b, 5)])
+    dd.distdl_affine_fwd(aop, r6, Wo, Bo, out)
+    t_parts = [torch.from_numpy(np.ascontiguousarray(tgt[:, r])).cuda() for r in rowso]
+    d_out = like(out)
+    loss = torch.zeros(1, dtype=torch.float64, device="cuda")
+    dd.distdl_mse_fwd_bwd(out, t_parts, d_out, loss)
+
+    # ---- backward
+    d_r6, dWo, dBo = like(r6), like(Wo), like(Bo)
+    dd.distdl_affine_bwd(aop, r6, Wo, d_out, d_r6, dWo, dBo)
+    d_a6 = like(a6)
+    dd.distdl_relu_bwd(a6, d_r6, d_a6)
+    d_r5, dW6, dB6 = like(r5), like(W6), like(B6)
+    dd.distdl_affine_bwd(a6p, r5, W6, d_a6, d_r5, dW6, dB6)
+    d_a5 = like(a5)
+    dd.distdl_relu_bwd(a5, d_r5, d_a5)
+    d_f, dW5, dB5 = like(f), like(W5), like(B5)
+    dd.distdl_affine_bwd(a5p, f, W5, d_a5, d_f, dW5, dB5)
+    d_s4 = like(p4.y)
+    dd.distdl_repartition_adj(p4.plan, d_f, d_s4)
+    dd.distdl_maxpool_bwd(p4.plan, p4.x, d_s4, p4.dx)
+    d_r3 = like(r3)
+    dd.distdl_bulk_copy(p4.plan, d_r3, p4.dx, False)
+    d_a3 = like(c3.y)
+    dd.distdl_relu_bwd(c3.y, d_r3, d_a3)
+    dw3, db3 = torch.empty_like(w3), torch.empty_like(b3)
+    dd.distdl_conv_bwd(c3.plan, c3.x, w3, d_a3, c3.dx, dw3, db3, c3.ws)
+    d_s2 = like(p2.y)
+    dd.distdl_bulk_copy(c3.plan, d_s2, c3.dx, False)
+    dd.distdl_maxpool_bwd(p2.plan, p2.x, d_s2, p2.dx)
+    d_r1 = like(r1)
+    dd.distdl_bulk_copy(p2.plan, d_r1, p2.dx, False)
+    d_a1 = like(c1.y)
+    dd.distdl_relu_bwd(c1.y, d_r1, d_a1)
+    dw1, db1 = torch.empty_like(w1), torch.empty_like(b1)
+    dd.distdl_conv_bwd(c1.plan, c1.x, w1, d_a1, c1.dx, dw1, db1, c1.ws)
+    torch.cuda.synchronize()
+
+    # ---- compare
+    host = lambda t: t.cpu().numpy()
+    assert abs(loss.item() - loss_want) <= TOL32 * abs(loss_want)
+    assert_close(np.concatenate([host(t) for t in out], axis=1), out_want, TOL32, "network output")
+    join = lambda parts, Pfo: np.block([[host(parts[i * Pf + j]) for j in range(Pf)] for i in range(Pfo)])
+    tol = 2e-5     # a chain of five fp32 layers
+    assert_close(join(dWo, Pf), g_want["out_w"], tol, "d out_w")
+    assert_close(np.concatenate([host(t) for t in dBo]), g_want["out_b"], tol, "d out_b")
+    assert_close(join(dW6, Pf), g_want["f6_w"], tol, "d f6_w")
+    assert_close(np.concatenate([host(t) for t in dB6]), g_want["f6_b"], tol, "d f6_b")
+    assert_close(join(dW5, Pf), g_want["c5_w"], tol, "d c5_w")
+    assert_close(np.concatenate([host(t) for t in dB5]), g_want["c5_b"], tol, "d c5_b")
+    assert_close(host(dw3), g_want["c3_w"], tol, "d c3_w")
+    assert_close(host(db3), g_want["c3_b"], tol, "d c3_b")
+    assert_close(host(dw1), g_want["c1_w"], tol, "d c1_w")
+    assert_close(host(db1), g_want["c1_b"], tol, "d c1_b")
+    assert_close(prim.gather_bulk([from_cl(t) for t in c1.dx], part1), g_want["images"], tol, "d images")
+
+
+def test_pool_and_repartition_against_oracle_on_unbalanced_geometry():
+    """App. B.1 fourth example extended to two dimensions: halos of 1 and 2 and "extra" input of 1 and 2."""
+    require_gpu()
+    n, P, n_b, c = (10, 20), (3, 6), 2, 8
+    part = geo.Partition.for_kernel(n, P, (2, 2), (2, 2), (0, 0), ONE2)
+    plan = dd.distdl_plan_create(2, n_b, c, c, n, P, (2, 2), (2, 2), (0, 0), ONE2)
+    r = syn.streams(9, 2)
+    x = syn.normal(r[0], (n_b, c) + n)
+    x[0, 0, :2, :2] = 1.5                              # a tie: the first tap must win
+    bufs_o = prim.scatter_bulk(x.astype(np.float64), part, fill=np.nan)
+    y_want, args = layers.dist_maxpool_forward(bufs_o, part, (2, 2), (2, 2))
+    dy = syn.normal(r[1], (n_b, c) + part.global_out_shape())
+    dx_want = layers.dist_maxpool_adjoint(prim.scatter_out(dy.astype(np.float64), part), args, part,
+                                          [b.shape for b in bufs_o], (2, 2), (2, 2))
+    g_x = [to_cl(b) for b in prim.scatter_bulk(x, part, fill=np.float32(4.0))]
+    g_y = [torch.empty((n_b,) + part.out_shape(w) + (c,), device="cuda") for w in range(part.n_workers)]
+    dd.distdl_maxpool_fwd(plan, g_x, g_y)
+    g_dy = [to_cl(t) for t in prim.scatter_out(dy, part)]
+    g_dx = [torch.full_like(t, 3.0) for t in g_x]
+    dd.distdl_maxpool_bwd(plan, g_x, g_dy, g_dx)
+    feats = [torch.empty((n_b, s.stop - s.start), device="cuda")
+             for s in layers.feature_blocks(c * 5 * 10, 3)]
+    dd.distdl_repartition_fwd(plan, g_y, feats)
+    back = [torch.zeros_like(t) for t in g_y]
+    dd.distdl_repartition_adj(plan, feats, back)
+    torch.cuda.synchronize()
+    for w in range(part.n_workers):
+        assert np.array_equal(from_cl(g_y[w]), y_want[w].astype(np.float32)), f"pool worker {w}"
+        assert_close(from_cl(g_dx[w]), dx_want[w], TOL32, f"pool dx worker {w}")
+        assert torch.equal(back[w], g_y[w])
+    f_want = layers.repartition_spatial_to_features(y_want, part, 3)
+    for j in range(3):
+        assert np.array_equal(feats[j].cpu().numpy(), f_want[j].astype(np.float32))
+
+
+def test_pointwise_and_loss_glue():
+    require_gpu()
+    r = syn.streams(21, 3)
+    sizes = [1, 63, 4097, 100003]                      # below one vector, ragged tails, several blocks
+    xs = [syn.normal(r[0], (s,)) for s in sizes]
+    for x in xs:
+        x[::7] = 0.0                                   # the kink of the ReLU: derivative 0 there
+    dys = [syn.normal(r[1], (s,)) for s in sizes]
+    ts = [syn.normal(r[2], (s,)) for s in sizes]
+    dev = lambda arrs: [torch.from_numpy(a).cuda() for a in arrs]
+    gx, gdy, gt = dev(xs), dev(dys), dev(ts)
+    gy, gdx, gd = [torch.empty_like(t) for t in gx], [torch.empty_like(t) for t in gx], \
+                  [torch.empty_like(t) for t in gx]
+    loss = torch.full((1,), 7.0, dtype=torch.float64, device="cuda")
+    dd.distdl_relu_fwd(gx, gy)
+    dd.distdl_relu_bwd(gx, gdy, gdx)
+    dd.distdl_mse_fwd_bwd(gx, gt, gd, loss)
+    torch.cuda.synchronize()
+    n_all = sum(sizes)
+    want_loss = sum(float(((x.astype(np.float64) - t) ** 2).sum()) for x, t in zip(xs, ts)) / n_all
+    assert abs(loss.item() - want_loss) <= 1e-12 * want_loss        # fp64 accumulation of fp32 inputs
+    for x, dy, t, y, dx, d in zip(xs, dys, ts, gy, gdx, gd):
+        assert np.array_equal(y.cpu().numpy(), layers.relu(x))
+        assert np.array_equal(dx.cpu().numpy(), layers.relu_backward(x, dy))
+        want_d = 2.0 * (x.astype(np.float64) - t) / n_all
+        assert_close(d.cpu().numpy(), want_d, 1e-6, "mse gradient")
+
+
+def test_bulk_copy_is_scatter_and_gather_of_the_bulk():
+    require_gpu()
+    n, P, n_b, c = (11, 9), (2, 3), 2, 5
+    k, pad = (3, 5), (1, 2)
+    part = geo.Partition.for_kernel(n, P, k, ONE2, pad, ONE2)
+    plan = dd.distdl_plan_create(2, n_b, c, c, n, P, k, ONE2, pad, ONE2)
+    x = syn.normal(syn.streams(5, 1)[0], (n_b, c) + n)
+    want = prim.scatter_bulk(x, part, fill=np.float32(-2.0))
+    dense = [to_cl(np.ascontiguousarray(x[(slice(None), slice(None)) + part.global_in_slices(w)]))
+             for w in range(part.n_workers)]
+    bufs = [torch.full((n_b,) + part.buf_shape(w) + (c,), -2.0, device="cuda") for w in range(part.n_workers)]
+    dd.distdl_bulk_copy(plan, dense, bufs, True)
+    back = [torch.zeros_like(t) for t in dense]
+    dd.distdl_bulk_copy(plan, back, bufs, False)
+    torch.cuda.synchronize()
+    for w in range(part.n_workers):
+        assert np.array_equal(from_cl(bufs[w]), want[w]), f"worker {w}: cells outside the bulk must be untouched"
+        assert torch.equal(back[w], dense[w])
+
+
+def test_glue_rejects_bad_arguments():
+    require_gpu()
+    plan = dd.distdl_plan_create(2, 2, 4, 6, (8, 8), (2, 2), (2, 2), (2, 2), (0, 0), ONE2)
+    bufs = [torch.zeros((2, 4, 4, 4), device="cuda") for _ in range(4)]
+    outs = [torch.zeros((2, 2, 2, 4), device="cuda") for _ in range(4)]
+    with pytest.raises(dd.DistdlError):                # pooling needs equal channel counts
+        dd.distdl_maxpool_fwd(plan, bufs, outs)
+    with pytest.raises(dd.DistdlError):                # more feature blocks than features
+        dd.distdl_repartition_fwd(plan, outs, [torch.zeros((2, 1), device="cuda")] * 500)
+    many = [torch.zeros(4, device="cuda")] * 17
+    with pytest.raises(dd.DistdlError):
+        dd.distdl_mse_fwd_bwd(many, many, many, torch.zeros(1, dtype=torch.float64, device="cuda"))
