@@ -195,6 +195,129 @@ class AffineWorkload:
                           f"shapes, {self.flops_step / 1e9:.1f} GFLOP in {dt:.1f} s"}
 
 
+class MovementWorkload:
+    """The data-movement primitives alone: H and H* on the cfg5 geometry (fp32, 32 channels, 4 x 4 x 4 workers,
+    buffers of 4.9 GB, far beyond the 256 MB cache) and B, B*, R, R* over k = 4 replicas of 256 MiB with two
+    rotating sets of arrays.  value = algorithmic bytes of the six calls / time."""
+
+    K, COUNT, SETS = 4, 1 << 26, 2
+
+    def __init__(self, sweep):
+        import torch
+        import paper_2006_03108_amd as dd
+        import synthetic_inputs as syn
+        self.dd, self.torch, self.tag, self.sweep_on = dd, torch, "movement", sweep
+        c = self.cfg = dict(syn.CONFIGS["cfg5"])
+        self.plan = dd.distdl_plan_create(c["D"], c["n_b"], c["c_in"], c["c_out"], c["in_shape"], c["P"], c["ksize"],
+                                          c["stride"], c["padding"], c["dilation"])
+        geoms = [self.plan.query(w) for w in range(self.plan.n_workers)]
+        self.x = [_dev_randn([c["n_b"]] + g["buf_shape"] + [c["c_in"]], 1000 + w) for w, g in enumerate(geoms)]
+        self.g = [_dev_randn([c["n_b"]] + g["buf_shape"] + [c["c_in"]], 3000 + w) for w, g in enumerate(geoms)]
+        k, n = self.K, self.COUNT
+        self.one = [_dev_randn((n,), 50 + s) for s in range(self.SETS)]
+        self.many = [[_dev_randn((n,), 60 + 10 * s + i) for i in range(k)] for s in range(self.SETS)]
+        self.turn = 0
+        stats = dd.distdl_plan_stats(self.plan)
+        per_cell = c["n_b"] * c["c_in"] * 4
+        coll = (k + 1) * n * 4
+        self.alg = {
+            "halo_fwd": ("hbm", (2 * stats["halo_cells"] + stats["pad_cells"]) * per_cell),
+            "halo_adj": ("hbm", (2 * stats["halo_cells"] + 2 * stats["band_cells"] + stats["pad_cells"]) * per_cell),
+            "bcast": ("hbm", coll), "sumreduce": ("hbm", coll),
+        }
+        self.bytes_step = self.alg["halo_fwd"][1] + self.alg["halo_adj"][1] + 4 * coll
+        self.metric = "halo + broadcast + sum-reduce forward and adjoint GB/s (algorithmic bytes)"
+        self.unit = "GB/s"
+        self.dtype = "f32"
+        self.describe = {"workload": "movement: H, H* on the cfg5 geometry (fp32 [1,32,256^3], P=4x4x4, halo 2/1, "
+                                     f"pad 2/1) + B, B*, R, R* over k={k} replicas of {n * 4 >> 20} MiB, channels-last",
+                         "halo_cells": stats["halo_cells"], "pad_cells": stats["pad_cells"],
+                         "band_cells": stats["band_cells"]}
+
+    def step(self):
+        dd, s = self.dd, self.turn % self.SETS
+        self.turn += 1
+        dd.distdl_halo_fwd(self.plan, self.x)
+        dd.distdl_halo_adj(self.plan, self.g)
+        dd.distdl_bcast_fwd([self.one[s]], self.many[s], self.K)
+        dd.distdl_bcast_adj([self.one[s]], self.many[s], self.K, False)
+        dd.distdl_sumreduce_fwd(self.many[s], [self.one[s]], self.K, False)
+        dd.distdl_sumreduce_adj([self.one[s]], self.many[s], self.K)
+
+    def value(self, seconds_per_step):
+        return self.bytes_step / seconds_per_step / 1e9
+
+    def sweep(self):
+        """B and R over k in {2, 4, 64} replicas of 1 MiB .. 1 GiB (fp32), array sets rotated through a pool of
+        20 GiB so that no call finds its operands in the cache; kernel time from the library's HIP events."""
+        dd, torch = self.dd, self.torch
+        pool = torch.empty(5 << 30, dtype=torch.float32, device="cuda")
+        pool.normal_()
+        dd.distdl_profile_enable(True)
+        rows = []
+        for k in (2, 4, 64):
+            for mib in (1, 4, 16, 64, 256, 1024):
+                n = mib << 18
+                per_set = (k + 1) * n
+                if per_set > pool.numel():
+                    continue
+                nsets = min(pool.numel() // per_set, max(2, (1 << 30) // (per_set * 4) + 1), 16)
+                sets = [[pool[(s * (k + 1) + i) * n:(s * (k + 1) + i + 1) * n] for i in range(k + 1)]
+                        for s in range(nsets)]
+                reps = max(nsets, 8)
+                for direction in ("bcast", "sumreduce"):
+                    torch.cuda.synchronize()
+                    dd.distdl_profile_report()
+                    for r in range(reps):
+                        a = sets[r % nsets]
+                        if direction == "bcast":
+                            dd.distdl_bcast_fwd([a[0]], a[1:], k)
+                        else:
+                            dd.distdl_sumreduce_fwd(a[1:], [a[0]], k, False)
+                    rep = dd.distdl_profile_report()
+                    ms = sum(v[1] for v in rep.values()) / reps
+                    gbs = per_set * 4 / (ms * 1e-3) / 1e9
+                    rows.append({"op": direction, "k": k, "MiB_per_replica": mib, "ms": round(ms, 5),
+                                 "GB/s": round(gbs, 1), "frac_hbm_peak": round(gbs / HBM_PEAK_GBS, 3),
+                                 "cache_resident": per_set * 4 * nsets <= (256 << 20)})
+        dd.distdl_profile_enable(False)
+        return rows
+
+    def cpu_baseline(self):
+        """The oracle's nested halo exchange and adjoint plus broadcast / sum-reduce and adjoints on a bounded
+        sample: 32 channels on a 192^3 volume over 2 x 2 x 2 workers, k = 4 replicas of 32 Mi elements."""
+        import synthetic_inputs as syn
+        from oracle import geometry as geo, primitives as prim
+        c = dict(self.cfg)
+        c.update(in_shape=(192, 192, 192), P=(2, 2, 2))
+        part = geo.Partition.for_kernel(c["in_shape"], c["P"], c["ksize"], c["stride"], c["padding"], c["dilation"])
+        r = syn.streams(11, 3)
+        x = syn.normal(r[0], (c["n_b"], c["c_in"]) + tuple(c["in_shape"])).astype(np.float64)
+        bufs = prim.scatter_bulk(x, part)
+        gb = [syn.normal(r[1], b.shape).astype(np.float64) for b in bufs]
+        v = syn.normal(r[2], (1 << 25,)).astype(np.float64)
+        halo = pad = 0
+        for w in range(part.n_workers):
+            g = [part.g(w, d) for d in range(part.D)]
+            inner = _prod(d["halo"][0] + d["in_size"] + d["halo"][1] for d in g)
+            halo += inner - _prod(d["in_size"] for d in g)
+            pad += _prod(part.buf_shape(w)) - inner
+        t0 = time.perf_counter()
+        prim.halo_exchange(bufs, part)
+        prim.halo_exchange_adjoint(gb, part)
+        reps = prim.broadcast(v, self.K)
+        prim.broadcast_adjoint(reps)
+        prim.sum_reduce(reps)
+        prim.sum_reduce_adjoint(v, self.K)
+        dt = time.perf_counter() - t0
+        per_cell = c["n_b"] * c["c_in"] * 8
+        moved = (4 * halo + 2 * pad) * per_cell + 4 * (self.K + 1) * v.size * 8
+        return {"value": moved / dt / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
+                "sample": f"oracle halo_exchange + halo_exchange_adjoint (nested form, numpy fp64) on x[1,32,192,192,192], "
+                          f"P=2x2x2, and broadcast / sum_reduce and adjoints over k={self.K} replicas of 32 Mi fp64 "
+                          f"elements; {moved / 1e6:.0f} MB (fp64; the band term of H* counted as halo) in {dt:.2f} s"}
+
+
 def kernel_rooflines(workload, report, traffic):
     """Per-kernel roofline entries from the library's HIP-event timings."""
     out = {}
@@ -244,7 +367,9 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="cfg5", choices=["cfg5", "cfg2", "cfg3", "cfg3-bf16"])
+    ap.add_argument("--workload", default="cfg5", choices=["cfg5", "cfg2", "cfg3", "cfg3-bf16", "movement"])
+    ap.add_argument("--sweep", action="store_true",
+                    help="with --workload movement: also the size sweep of broadcast / sum-reduce")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB copy (bcast_kernel, k = 1) before the timed region, as the "
@@ -260,7 +385,9 @@ def main():
         sys.exit(2)
     import paper_2006_03108_amd as dd
     torch.cuda.set_device(0)
-    if args.workload in ("cfg5", "cfg2"):
+    if args.workload == "movement":
+        wl = MovementWorkload(args.sweep)
+    elif args.workload in ("cfg5", "cfg2"):
         wl = ConvWorkload(args.workload)
     else:
         wl = AffineWorkload("cfg3", "bf16" if args.workload.endswith("bf16") else "f32")
@@ -295,6 +422,8 @@ def main():
         "vs_baseline": None, "dtype": wl.dtype, "data": "synthetic", "config": wl.describe,
         "roofline": roofline, "kernels": kernels,
     }
+    if getattr(wl, "sweep_on", False):
+        line["sweep"] = wl.sweep()
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = wl.cpu_baseline()
     print(json.dumps(line))

@@ -13,7 +13,7 @@
 
 namespace distdl {
 
-constexpr int kMaxPtrs = 48;
+constexpr int kMaxPtrs = 64;
 constexpr int kMaxGroups = 16;
 constexpr int kCollThreads = 256;
 
@@ -36,6 +36,12 @@ struct CollArgs {
   int32_t clear_inputs;
 };
 
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// Both kernels stream: every element is touched once, so loads carry the
+// non-temporal hint, and the grid covers the longest group with one 16-byte
+// vector per thread (many short-lived workgroups keep more requests in flight
+// than a grid-stride loop over few); the loop only matters beyond 2^31 threads.
 template <bool BF16>
 __global__ __launch_bounds__(kCollThreads) void bcast_kernel(CollArgs a) {
   const int g = blockIdx.y;
@@ -46,10 +52,10 @@ __global__ __launch_bounds__(kCollThreads) void bcast_kernel(CollArgs a) {
   void* const* rep = a.many + a.first[g];
   const int64_t stride = (int64_t)gridDim.x * kCollThreads;
   const int64_t tid = (int64_t)blockIdx.x * kCollThreads + threadIdx.x;
-  const uint4* src = (const uint4*)a.one[g];
+  const u32x4* src = (const u32x4*)a.one[g];
   for (int64_t u = tid; u < nvec; u += stride) {
-    uint4 v = src[u];
-    for (int i = 0; i < k; ++i) ((uint4*)rep[i])[u] = v;
+    u32x4 v = __builtin_nontemporal_load(src + u);
+    for (int i = 0; i < k; ++i) ((u32x4*)rep[i])[u] = v;
   }
   for (int64_t e = nvec * V + tid; e < count; e += stride) {
     if (BF16) {
@@ -72,46 +78,43 @@ __global__ __launch_bounds__(kCollThreads) void reduce_kernel(CollArgs a) {
   void* const* rep = a.many + a.first[g];
   const int64_t stride = (int64_t)gridDim.x * kCollThreads;
   const int64_t tid = (int64_t)blockIdx.x * kCollThreads + threadIdx.x;
+  const bool clear = a.clear_inputs != 0;
   for (int64_t u = tid; u < nvec; u += stride) {
     float acc[V];
     if (a.accumulate) {
-      uint4 o = ((const uint4*)a.one[g])[u];
-      const uint32_t w[4] = {o.x, o.y, o.z, o.w};
+      u32x4 o = ((const u32x4*)a.one[g])[u];
       for (int j = 0; j < 4; ++j) {
         if (BF16) {
-          acc[2 * j] = bf2f(w[j] & 0xffffu);
-          acc[2 * j + 1] = bf2f(w[j] >> 16);
+          acc[2 * j] = bf2f(o[j] & 0xffffu);
+          acc[2 * j + 1] = bf2f(o[j] >> 16);
         } else {
-          acc[j] = __uint_as_float(w[j]);
+          acc[j] = __uint_as_float(o[j]);
         }
       }
     } else {
       for (int j = 0; j < V; ++j) acc[j] = 0.f;
     }
-    for (int i = 0; i < k; ++i) {  // replica order i = 0 .. k-1
-      uint4 r = ((const uint4*)rep[i])[u];
-      const uint32_t w[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll 8
+    for (int i = 0; i < k; ++i) {  // replica order i = 0 .. k-1; the unrolled loads are issued together
+      u32x4 r = __builtin_nontemporal_load((const u32x4*)rep[i] + u);
       for (int j = 0; j < 4; ++j) {
         if (BF16) {
-          acc[2 * j] += bf2f(w[j] & 0xffffu);
-          acc[2 * j + 1] += bf2f(w[j] >> 16);
+          acc[2 * j] += bf2f(r[j] & 0xffffu);
+          acc[2 * j + 1] += bf2f(r[j] >> 16);
         } else {
-          acc[j] += __uint_as_float(w[j]);
+          acc[j] += __uint_as_float(r[j]);
         }
       }
-      if (a.clear_inputs) ((uint4*)rep[i])[u] = make_uint4(0, 0, 0, 0);
     }
-    uint4 o;
+    if (clear)
+      for (int i = 0; i < k; ++i) ((u32x4*)rep[i])[u] = u32x4{0, 0, 0, 0};
+    u32x4 o;
     if (BF16) {
-      o.x = f2bf(acc[0]) | (f2bf(acc[1]) << 16);
-      o.y = f2bf(acc[2]) | (f2bf(acc[3]) << 16);
-      o.z = f2bf(acc[4]) | (f2bf(acc[5]) << 16);
-      o.w = f2bf(acc[6]) | (f2bf(acc[7]) << 16);
+      for (int j = 0; j < 4; ++j) o[j] = f2bf(acc[2 * j]) | (f2bf(acc[2 * j + 1]) << 16);
     } else {
-      o = make_uint4(__float_as_uint(acc[0]), __float_as_uint(acc[1]), __float_as_uint(acc[2]),
-                     __float_as_uint(acc[3]));
+      for (int j = 0; j < 4; ++j) o[j] = __float_as_uint(acc[j]);
     }
-    ((uint4*)a.one[g])[u] = o;
+    __builtin_nontemporal_store(o, (u32x4*)a.one[g] + u);
   }
   for (int64_t e = nvec * V + tid; e < count; e += stride) {
     if (BF16) {
@@ -119,7 +122,7 @@ __global__ __launch_bounds__(kCollThreads) void reduce_kernel(CollArgs a) {
       float acc = a.accumulate ? bf2f(out[e]) : 0.f;
       for (int i = 0; i < k; ++i) {
         acc += bf2f(((const uint16_t*)rep[i])[e]);
-        if (a.clear_inputs) ((uint16_t*)rep[i])[e] = 0;
+        if (clear) ((uint16_t*)rep[i])[e] = 0;
       }
       out[e] = (uint16_t)f2bf(acc);
     } else {
@@ -127,7 +130,7 @@ __global__ __launch_bounds__(kCollThreads) void reduce_kernel(CollArgs a) {
       float acc = a.accumulate ? out[e] : 0.f;
       for (int i = 0; i < k; ++i) {
         acc += ((const float*)rep[i])[e];
-        if (a.clear_inputs) ((float*)rep[i])[e] = 0.f;
+        if (clear) ((float*)rep[i])[e] = 0.f;
       }
       out[e] = acc;
     }
@@ -135,10 +138,10 @@ __global__ __launch_bounds__(kCollThreads) void reduce_kernel(CollArgs a) {
 }
 
 static unsigned blocks_for(int64_t max_count, int vec) {
-  int64_t units = (max_count + vec - 1) / vec;
-  int64_t b = (units + kCollThreads * 4 - 1) / (kCollThreads * 4);  // ~4 units per thread
+  int64_t units = (max_count + vec - 1) / vec;  // one unit per thread
+  int64_t b = (units + kCollThreads - 1) / kCollThreads;
   if (b < 1) b = 1;
-  if (b > 4096) b = 4096;
+  if (b > (int64_t(1) << 22)) b = int64_t(1) << 22;
   return (unsigned)b;
 }
 

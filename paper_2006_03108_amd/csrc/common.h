@@ -93,12 +93,33 @@ struct BlockRef {
   uint32_t unit0;  // first vector unit of the task this block handles
 };
 
+// Device form of a box: the same box as one worker's buffer addresses it, in
+// vector units (offset of a unit = base + n * sn + c0 * s0 + c1 * s1 + col).
+struct HaloView {
+  int32_t worker;
+  uint32_t s1, s0;
+  uint32_t pad_;
+  uint64_t sn;
+  uint64_t base;
+};
+// Device form of a task: everything a workgroup needs in one record, so that
+// the only dependent loads before the data are block -> task -> pointer.
+struct HaloTaskDev {
+  HaloView dst;
+  HaloView src0;     // first source (nsrc >= 1)
+  int32_t nsrc;
+  int32_t src_begin;  // sources 1 .. nsrc-1 are views[src_begin + 1 ...]
+  uint32_t total;     // vector units of the task
+  uint32_t pad_;
+  FastDiv div_row, div_e1, div_e0;
+};
+
 struct TaskTable {
   std::vector<BoxTask> tasks;
   std::vector<BoxSrc> srcs;
   std::vector<BlockRef> blocks;
-  BoxTask* d_tasks = nullptr;
-  BoxSrc* d_srcs = nullptr;
+  HaloTaskDev* d_tasks = nullptr;
+  HaloView* d_views = nullptr;  // one per BoxSrc, same indexing
   BlockRef* d_blocks = nullptr;
   int vec = 1;  // elements per vector unit the tables were built for
   int64_t cells_copied = 0, cells_zeroed = 0, cells_band = 0;

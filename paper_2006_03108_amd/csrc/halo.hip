@@ -67,20 +67,38 @@ struct BF16x1 {
   __device__ static Store zero() { return 0; }
 };
 
-// Offset (in vector units) of cell (n, c0, c1) + origin in a worker's buffer;
-// cv = vector units per cell.
-__device__ inline size_t box_offset(const WorkerDev& w, const int32_t org[3], uint32_t n, uint32_t c0, uint32_t c1,
-                                    uint32_t cv) {
-  uint32_t s1 = (uint32_t)w.buf[2] * cv;
-  uint32_t s0 = (uint32_t)w.buf[1] * s1;
-  size_t sn = (size_t)w.buf[0] * s0;
-  return n * sn + (size_t)((org[0] + c0) * s0 + (org[1] + c1) * s1 + org[2] * cv);
+// Every halo, padding and band cell is touched once per call: stream them past
+// the caches with the non-temporal hint.
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+// The buffers are device allocations: the address-space cast makes these
+// global_load / global_store instead of flat accesses.
+#define DISTDL_GLOBAL __attribute__((address_space(1)))
+template <class S>
+__device__ inline S nt_load(const S* p) {
+  if constexpr (sizeof(S) == 16) {
+    u32x4 v = __builtin_nontemporal_load((const DISTDL_GLOBAL u32x4*)p);
+    S out;
+    __builtin_memcpy(&out, &v, 16);
+    return out;
+  } else {
+    return __builtin_nontemporal_load((const DISTDL_GLOBAL S*)p);
+  }
+}
+template <class S>
+__device__ inline void nt_store(S* p, const S& val) {
+  if constexpr (sizeof(S) == 16) {
+    u32x4 v;
+    __builtin_memcpy(&v, &val, 16);
+    __builtin_nontemporal_store(v, (DISTDL_GLOBAL u32x4*)p);
+  } else {
+    __builtin_nontemporal_store(val, (DISTDL_GLOBAL S*)p);
+  }
 }
 
 struct UnitPos {
   uint32_t n, c0, c1, col;
 };
-__device__ inline UnitPos decode(uint32_t u, const BoxTask& t) {
+__device__ inline UnitPos decode(uint32_t u, const HaloTaskDev& t) {
   UnitPos p;
   uint32_t row = fd_div(u, t.div_row);
   p.col = u - row * t.div_row.d;
@@ -90,89 +108,107 @@ __device__ inline UnitPos decode(uint32_t u, const BoxTask& t) {
   p.c0 = r1 - p.n * t.div_e0.d;
   return p;
 }
+__device__ inline size_t view_offset(const HaloView& v, const UnitPos& p) {
+  return v.base + p.n * v.sn + (size_t)(p.c0 * v.s0 + p.c1 * v.s1 + p.col);
+}
 
-// Forward: copy boxes (nsrc == 1) and zero boxes (nsrc == 0).
+// Forward: copy boxes (nsrc == 1) and zero boxes (nsrc == 0).  A thread
+// handles kUnroll units: all loads are issued before the first store.
 template <class E>
 __global__ __launch_bounds__(kThreads) void halo_fwd_kernel(const BlockRef* __restrict__ blocks,
-                                                            const BoxTask* __restrict__ tasks,
-                                                            const BoxSrc* __restrict__ srcs,
-                                                            const WorkerDev* __restrict__ workers, void* const* bufs,
-                                                            uint32_t n_b, uint32_t cv) {
+                                                            const HaloTaskDev* __restrict__ tasks,
+                                                            void* const* __restrict__ bufs) {
   using S = typename E::Store;
   const BlockRef br = blocks[blockIdx.x];
-  const BoxTask& t = tasks[br.task];
-  const uint32_t total = n_b * (uint32_t)t.ext[0] * (uint32_t)t.ext[1] * t.div_row.d;
-  const WorkerDev& wd = workers[t.dst_worker];
-  S* __restrict__ dst = (S*)bufs[t.dst_worker];
-  S vals[kUnroll];
-  size_t doff[kUnroll];
-  bool live[kUnroll];
+  const HaloTaskDev t = tasks[br.task];  // by value: the record is read once into scalar registers
+  const uint32_t total = t.total;
+  S* __restrict__ dst = (S*)bufs[t.dst.worker];
   if (t.nsrc == 0) {
 #pragma unroll
     for (int i = 0; i < kUnroll; ++i) {
       uint32_t u = br.unit0 + threadIdx.x + i * kThreads;
-      if (u < total) {
-        UnitPos p = decode(u, t);
-        dst[box_offset(wd, t.org, p.n, p.c0, p.c1, cv) + p.col] = E::zero();
-      }
+      if (u < total) nt_store(dst + view_offset(t.dst, decode(u, t)), E::zero());
     }
     return;
   }
-  const BoxSrc& sr = srcs[t.src_begin];
-  const WorkerDev& ws = workers[sr.worker];
-  const S* __restrict__ src = (const S*)bufs[sr.worker];
+  const S* __restrict__ src = (const S*)bufs[t.src0.worker];
+  S vals[kUnroll];
+  size_t doff[kUnroll];
+  bool live[kUnroll];
 #pragma unroll
   for (int i = 0; i < kUnroll; ++i) {
     uint32_t u = br.unit0 + threadIdx.x + i * kThreads;
     live[i] = u < total;
-    if (live[i]) {
-      UnitPos p = decode(u, t);
-      doff[i] = box_offset(wd, t.org, p.n, p.c0, p.c1, cv) + p.col;
-      vals[i] = src[box_offset(ws, sr.org, p.n, p.c0, p.c1, cv) + p.col];
+    UnitPos p = decode(live[i] ? u : total - 1, t);  // clamped: loads need no branch
+    doff[i] = view_offset(t.dst, p);
+    vals[i] = nt_load(src + view_offset(t.src0, p));
+  }
+#pragma unroll
+  for (int i = 0; i < kUnroll; ++i)
+    if (live[i]) nt_store(dst + doff[i], vals[i]);
+}
+
+// Adjoint: bulk boxes gather-add their halo copies and clear them; padding
+// boxes are cleared.  Per source, the loads of all kUnroll units are issued
+// before the clears, and the destination is loaded together with the first
+// source, so that a thread has 2 * kUnroll requests in flight.
+template <class E>
+__global__ __launch_bounds__(kThreads) void halo_adj_kernel(const BlockRef* __restrict__ blocks,
+                                                            const HaloTaskDev* __restrict__ tasks,
+                                                            const HaloView* __restrict__ views,
+                                                            void* const* __restrict__ bufs) {
+  using S = typename E::Store;
+  const BlockRef br = blocks[blockIdx.x];
+  const HaloTaskDev t = tasks[br.task];  // by value: the record is read once into scalar registers
+  const uint32_t total = t.total;
+  S* dst = (S*)bufs[t.dst.worker];
+  if (t.nsrc == 0) {
+#pragma unroll
+    for (int i = 0; i < kUnroll; ++i) {
+      uint32_t u = br.unit0 + threadIdx.x + i * kThreads;
+      if (u < total) nt_store(dst + view_offset(t.dst, decode(u, t)), E::zero());
+    }
+    return;
+  }
+  UnitPos pos[kUnroll];
+  bool live[kUnroll];
+  S dv[kUnroll], sv[kUnroll];
+  float acc[kUnroll][E::N];
+  S* src = (S*)bufs[t.src0.worker];
+#pragma unroll
+  for (int i = 0; i < kUnroll; ++i) {
+    uint32_t u = br.unit0 + threadIdx.x + i * kThreads;
+    live[i] = u < total;
+    pos[i] = decode(live[i] ? u : total - 1, t);  // clamped: loads need no branch
+    dv[i] = nt_load(dst + view_offset(t.dst, pos[i]));
+    sv[i] = nt_load(src + view_offset(t.src0, pos[i]));
+  }
+#pragma unroll
+  for (int i = 0; i < kUnroll; ++i) {
+    float v[E::N];
+    E::unpack(dv[i], acc[i]);
+    E::unpack(sv[i], v);
+    if (live[i]) nt_store(src + view_offset(t.src0, pos[i]), E::zero());
+#pragma unroll
+    for (int e = 0; e < E::N; ++e) acc[i][e] += v[e];
+  }
+  for (int s = 1; s < t.nsrc; ++s) {  // ascending source-worker order
+    const HaloView sr = views[t.src_begin + s];
+    src = (S*)bufs[sr.worker];
+#pragma unroll
+    for (int i = 0; i < kUnroll; ++i) sv[i] = nt_load(src + view_offset(sr, pos[i]));
+#pragma unroll
+    for (int i = 0; i < kUnroll; ++i) {
+      float v[E::N];
+      E::unpack(sv[i], v);
+      if (live[i]) nt_store(src + view_offset(sr, pos[i]), E::zero());
+#pragma unroll
+      for (int e = 0; e < E::N; ++e) acc[i][e] += v[e];
     }
   }
 #pragma unroll
   for (int i = 0; i < kUnroll; ++i)
-    if (live[i]) dst[doff[i]] = vals[i];
-}
-
-// Adjoint: bulk boxes gather-add their halo copies and clear them; padding
-// boxes are cleared.
-template <class E>
-__global__ __launch_bounds__(kThreads) void halo_adj_kernel(const BlockRef* __restrict__ blocks,
-                                                            const BoxTask* __restrict__ tasks,
-                                                            const BoxSrc* __restrict__ srcs,
-                                                            const WorkerDev* __restrict__ workers, void* const* bufs,
-                                                            uint32_t n_b, uint32_t cv) {
-  using S = typename E::Store;
-  const BlockRef br = blocks[blockIdx.x];
-  const BoxTask& t = tasks[br.task];
-  const uint32_t total = n_b * (uint32_t)t.ext[0] * (uint32_t)t.ext[1] * t.div_row.d;
-  const WorkerDev& wd = workers[t.dst_worker];
-  S* dst = (S*)bufs[t.dst_worker];
-#pragma unroll
-  for (int i = 0; i < kUnroll; ++i) {
-    uint32_t u = br.unit0 + threadIdx.x + i * kThreads;
-    if (u >= total) continue;
-    UnitPos p = decode(u, t);
-    size_t d = box_offset(wd, t.org, p.n, p.c0, p.c1, cv) + p.col;
-    if (t.nsrc == 0) {
-      dst[d] = E::zero();
-      continue;
-    }
-    float acc[E::N], v[E::N];
-    E::unpack(dst[d], acc);
-    for (int s = 0; s < t.nsrc; ++s) {  // ascending source-worker order
-      const BoxSrc& sr = srcs[t.src_begin + s];
-      S* src = (S*)bufs[sr.worker];
-      size_t o = box_offset(workers[sr.worker], sr.org, p.n, p.c0, p.c1, cv) + p.col;
-      E::unpack(src[o], v);
-      src[o] = E::zero();
-#pragma unroll
-      for (int e = 0; e < E::N; ++e) acc[e] += v[e];
-    }
-    dst[d] = E::pack(acc);
-  }
+    if (live[i]) nt_store(dst + view_offset(t.dst, pos[i]), E::pack(acc[i]));
 }
 
 int plan_prepare_device(distdl_plan* p);
@@ -180,14 +216,12 @@ int plan_prepare_device(distdl_plan* p);
 template <class E>
 static void launch(bool adjoint, const TaskTable& tt, const distdl_plan* p, void* const* bufs, hipStream_t st) {
   dim3 grid((unsigned)tt.blocks.size()), block(kThreads);
-  uint32_t cv = (uint32_t)(p->n_ci / E::N);
+  (void)p;
   ProfScope prof(adjoint ? "halo_adj" : "halo_fwd", st);
   if (adjoint)
-    hipLaunchKernelGGL(halo_adj_kernel<E>, grid, block, 0, st, tt.d_blocks, tt.d_tasks, tt.d_srcs, p->d_workers, bufs,
-                       (uint32_t)p->n_b, cv);
+    hipLaunchKernelGGL(halo_adj_kernel<E>, grid, block, 0, st, tt.d_blocks, tt.d_tasks, tt.d_views, bufs);
   else
-    hipLaunchKernelGGL(halo_fwd_kernel<E>, grid, block, 0, st, tt.d_blocks, tt.d_tasks, tt.d_srcs, p->d_workers, bufs,
-                       (uint32_t)p->n_b, cv);
+    hipLaunchKernelGGL(halo_fwd_kernel<E>, grid, block, 0, st, tt.d_blocks, tt.d_tasks, bufs);
 }
 
 // Shared by the public halo calls and by conv_fwd / conv_bwd.

@@ -301,20 +301,60 @@ static int to_device(const std::vector<T>& v, T** out) {
   return DISTDL_OK;
 }
 
-static int upload_table(TaskTable& tt) {
+// Resolves the box tables into the records the kernels read (strides and
+// origins in vector units) and checks that the last unit of every view lies
+// inside its worker's buffer.
+static int upload_table(const distdl_plan& p, TaskTable& tt) {
+  if (tt.tasks.empty()) return DISTDL_OK;
+  const int64_t n_c = p.n_ci;
+  const int64_t cv = n_c / tt.vec;
+  auto view = [&](int worker, const int32_t org[3], const BoxTask& t, HaloView* out) {
+    const WorkerDev& w = p.workers[worker];
+    HaloView v{};
+    v.worker = worker;
+    v.s1 = (uint32_t)(w.buf[2] * cv);
+    v.s0 = (uint32_t)(w.buf[1] * (int64_t)v.s1);
+    v.sn = (uint64_t)w.buf[0] * v.s0;
+    v.base = (uint64_t)org[0] * v.s0 + (uint64_t)org[1] * v.s1 + (uint64_t)org[2] * cv;
+    uint64_t last = v.base + (uint64_t)(p.n_b - 1) * v.sn + (uint64_t)(t.ext[0] - 1) * v.s0 +
+                    (uint64_t)(t.ext[1] - 1) * v.s1 + (uint64_t)t.ext[2] * cv - 1;
+    if (last >= (uint64_t)p.n_b * v.sn) return false;
+    *out = v;
+    return true;
+  };
+  std::vector<HaloTaskDev> tasks(tt.tasks.size());
+  std::vector<HaloView> views(tt.srcs.size());
+  for (size_t i = 0; i < tt.tasks.size(); ++i) {
+    const BoxTask& t = tt.tasks[i];
+    HaloTaskDev d{};
+    bool ok = view(t.dst_worker, t.org, t, &d.dst);
+    for (int s = 0; s < t.nsrc && ok; ++s)
+      ok = view(tt.srcs[t.src_begin + s].worker, tt.srcs[t.src_begin + s].org, t, &views[t.src_begin + s]);
+    if (!ok) return set_error(DISTDL_ERR_INVALID_ARG, "internal: task view out of range");
+    if (t.nsrc > 0) d.src0 = views[t.src_begin];
+    d.nsrc = t.nsrc;
+    d.src_begin = t.src_begin;
+    int64_t total = p.n_b * t.ext[0] * t.ext[1] * (int64_t)t.div_row.d;
+    if (total >= (int64_t(1) << 32)) return set_error(DISTDL_ERR_UNSUPPORTED, "internal: task too large");
+    d.total = (uint32_t)total;
+    d.div_row = t.div_row;
+    d.div_e1 = t.div_e1;
+    d.div_e0 = t.div_e0;
+    tasks[i] = d;
+  }
   int rc;
-  if ((rc = to_device(tt.tasks, &tt.d_tasks))) return rc;
-  if ((rc = to_device(tt.srcs, &tt.d_srcs))) return rc;
+  if ((rc = to_device(tasks, &tt.d_tasks))) return rc;
+  if ((rc = to_device(views, &tt.d_views))) return rc;
   if ((rc = to_device(tt.blocks, &tt.d_blocks))) return rc;
   return DISTDL_OK;
 }
 
 static void free_table(TaskTable& tt) {
   if (tt.d_tasks) (void)hipFree(tt.d_tasks);
-  if (tt.d_srcs) (void)hipFree(tt.d_srcs);
+  if (tt.d_views) (void)hipFree(tt.d_views);
   if (tt.d_blocks) (void)hipFree(tt.d_blocks);
   tt.d_tasks = nullptr;
-  tt.d_srcs = nullptr;
+  tt.d_views = nullptr;
   tt.d_blocks = nullptr;
 }
 
@@ -385,8 +425,8 @@ int plan_prepare_device(distdl_plan* p) {
   DISTDL_HIP_TRY(hipGetDevice(&p->device));
   int rc;
   if ((rc = to_device(p->workers, &p->d_workers))) return rc;
-  if ((rc = upload_table(p->fwd16)) || (rc = upload_table(p->adj16)) || (rc = upload_table(p->fwd1)) ||
-      (rc = upload_table(p->adj1)))
+  if ((rc = upload_table(*p, p->fwd16)) || (rc = upload_table(*p, p->adj16)) || (rc = upload_table(*p, p->fwd1)) ||
+      (rc = upload_table(*p, p->adj1)))
     return rc;
   return DISTDL_OK;
 }
