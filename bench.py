@@ -318,6 +318,168 @@ class MovementWorkload:
                           f"elements; {moved / 1e6:.0f} MB (fp64; the band term of H* counted as halo) in {dt:.2f} s"}
 
 
+class SmallCnn:
+    """cfg4: conv5x5(6)-ReLU-pool2-conv5x5(16)-ReLU-pool2-affine 400-120-84-10 (ReLU after the first two affine
+    layers), MSE loss; conv / pool layers on a 2 x 2 spatial partition, affine layers on 2 x 2 weight partitions.
+    Every step is a call of the library; this class only owns the device tensors and the order of the calls.
+    `params`: the numpy weights (c1_w, c1_b, c3_w, c3_b, c5_w, c5_b, f6_w, f6_b, out_w, out_b)."""
+
+    P, PF = (2, 2), 2
+
+    def __init__(self, n_b, params):
+        import torch
+        import paper_2006_03108_amd as dd
+        self.dd, self.torch, self.n_b = dd, torch, n_b
+        one = (1, 1)
+        dev = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
+        new = lambda shapes: [torch.empty(s, device="cuda") for s in shapes]
+        like = lambda ts: [torch.empty_like(t) for t in ts]
+
+        def sliding(c_in, c_out, in_shape, k, stride, pad):
+            plan = dd.distdl_plan_create(2, n_b, c_in, c_out, in_shape, self.P, (k, k), (stride, stride), (pad, pad), one)
+            geoms = [plan.query(w) for w in range(plan.n_workers)]
+            x = [torch.zeros([n_b] + g["buf_shape"] + [c_in], device="cuda") for g in geoms]
+            y = [torch.empty([n_b] + g["out_size"] + [c_out], device="cuda") for g in geoms]
+            return plan, x, y, like(x)
+
+        self.c1, self.c1_x, self.c1_y, self.c1_dx = sliding(1, 6, (28, 28), 5, 1, 2)
+        self.p2, self.p2_x, self.p2_y, self.p2_dx = sliding(6, 6, (28, 28), 2, 2, 0)
+        self.c3, self.c3_x, self.c3_y, self.c3_dx = sliding(6, 16, (14, 14), 5, 1, 0)
+        self.p4, self.p4_x, self.p4_y, self.p4_dx = sliding(16, 16, (10, 10), 2, 2, 0)
+        self.c1_ws = torch.empty(max(dd.distdl_conv_bwd_workspace(self.c1), 16), dtype=torch.uint8, device="cuda")
+        self.c3_ws = torch.empty(max(dd.distdl_conv_bwd_workspace(self.c3), 16), dtype=torch.uint8, device="cuda")
+        # conv weights in the library's [c_out][c_in][taps] order == the usual [c_out, c_in, k, k], contiguous
+        self.w1, self.b1, self.w3, self.b3 = dev(params["c1_w"]), dev(params["c1_b"]), dev(params["c3_w"]), dev(params["c3_b"])
+        self.dw1, self.db1, self.dw3, self.db3 = (torch.empty_like(t) for t in (self.w1, self.b1, self.w3, self.b3))
+
+        def split(n, parts):
+            out, at = [], 0
+            for r in range(parts):
+                z = n // parts + (1 if r < n % parts else 0)
+                out.append(slice(at, at + z))
+                at += z
+            return out
+
+        def affine(W, b):
+            n_fo, n_fi = W.shape
+            rows, cols = split(n_fo, self.PF), split(n_fi, self.PF)
+            plan = dd.distdl_affine_plan_create(n_b, n_fi, n_fo, self.PF, self.PF)
+            Wp = [dev(W[r][:, c]) for r in rows for c in cols]
+            bp = [dev(b[r]) for r in rows]
+            y = new([(n_b, r.stop - r.start) for r in rows])
+            return dict(plan=plan, W=Wp, b=bp, y=y, dW=like(Wp), db=like(bp), rows=rows, cols=cols)
+
+        self.a5 = affine(params["c5_w"], params["c5_b"])
+        self.a6 = affine(params["f6_w"], params["f6_b"])
+        self.ao = affine(params["out_w"], params["out_b"])
+        self.r1, self.r3 = like(self.c1_y), like(self.c3_y)
+        self.f = new([(n_b, c.stop - c.start) for c in self.a5["cols"]])
+        self.r5, self.r6 = like(self.a5["y"]), like(self.a6["y"])
+        self.t = like(self.ao["y"])
+        self.d_out, self.d_r6, self.d_a6, self.d_r5, self.d_a5 = (like(self.ao["y"]), like(self.r6), like(self.a6["y"]),
+                                                                 like(self.r5), like(self.a5["y"]))
+        self.d_f, self.d_s4, self.d_r3, self.d_a3 = like(self.f), like(self.p4_y), like(self.r3), like(self.c3_y)
+        self.d_s2, self.d_r1, self.d_a1 = like(self.p2_y), like(self.r1), like(self.c1_y)
+        self.loss = torch.zeros(1, dtype=torch.float64, device="cuda")
+
+    def load_batch(self, image_bufs, target):
+        """image_bufs: per worker the channels-last padded buffer [n_b, buf_0, buf_1, 1] of conv1 with the bulk
+        filled; target: [n_b, 10] one-hot."""
+        for dst, src in zip(self.c1_x, image_bufs):
+            dst.copy_(src)
+        for dst, rows in zip(self.t, self.ao["rows"]):
+            dst.copy_(self.torch.from_numpy(np.ascontiguousarray(target[:, rows], dtype=np.float32)))
+
+    def step(self):
+        dd = self.dd
+        a5, a6, ao = self.a5, self.a6, self.ao
+        # forward
+        dd.distdl_conv_fwd(self.c1, self.c1_x, self.w1, self.b1, self.c1_y)
+        dd.distdl_relu_fwd(self.c1_y, self.r1)
+        dd.distdl_bulk_copy(self.p2, self.r1, self.p2_x, True)
+        dd.distdl_maxpool_fwd(self.p2, self.p2_x, self.p2_y)
+        dd.distdl_bulk_copy(self.c3, self.p2_y, self.c3_x, True)
+        dd.distdl_conv_fwd(self.c3, self.c3_x, self.w3, self.b3, self.c3_y)
+        dd.distdl_relu_fwd(self.c3_y, self.r3)
+        dd.distdl_bulk_copy(self.p4, self.r3, self.p4_x, True)
+        dd.distdl_maxpool_fwd(self.p4, self.p4_x, self.p4_y)
+        dd.distdl_repartition_fwd(self.p4, self.p4_y, self.f)
+        dd.distdl_affine_fwd(a5["plan"], self.f, a5["W"], a5["b"], a5["y"])
+        dd.distdl_relu_fwd(a5["y"], self.r5)
+        dd.distdl_affine_fwd(a6["plan"], self.r5, a6["W"], a6["b"], a6["y"])
+        dd.distdl_relu_fwd(a6["y"], self.r6)
+        dd.distdl_affine_fwd(ao["plan"], self.r6, ao["W"], ao["b"], ao["y"])
+        dd.distdl_mse_fwd_bwd(ao["y"], self.t, self.d_out, self.loss)
+        # backward
+        dd.distdl_affine_bwd(ao["plan"], self.r6, ao["W"], self.d_out, self.d_r6, ao["dW"], ao["db"])
+        dd.distdl_relu_bwd(a6["y"], self.d_r6, self.d_a6)
+        dd.distdl_affine_bwd(a6["plan"], self.r5, a6["W"], self.d_a6, self.d_r5, a6["dW"], a6["db"])
+        dd.distdl_relu_bwd(a5["y"], self.d_r5, self.d_a5)
+        dd.distdl_affine_bwd(a5["plan"], self.f, a5["W"], self.d_a5, self.d_f, a5["dW"], a5["db"])
+        dd.distdl_repartition_adj(self.p4, self.d_f, self.d_s4)
+        dd.distdl_maxpool_bwd(self.p4, self.p4_x, self.d_s4, self.p4_dx)
+        dd.distdl_bulk_copy(self.p4, self.d_r3, self.p4_dx, False)
+        dd.distdl_relu_bwd(self.c3_y, self.d_r3, self.d_a3)
+        dd.distdl_conv_bwd(self.c3, self.c3_x, self.w3, self.d_a3, self.c3_dx, self.dw3, self.db3, self.c3_ws)
+        dd.distdl_bulk_copy(self.c3, self.d_s2, self.c3_dx, False)
+        dd.distdl_maxpool_bwd(self.p2, self.p2_x, self.d_s2, self.p2_dx)
+        dd.distdl_bulk_copy(self.p2, self.d_r1, self.p2_dx, False)
+        dd.distdl_relu_bwd(self.c1_y, self.d_r1, self.d_a1)
+        dd.distdl_conv_bwd(self.c1, self.c1_x, self.w1, self.d_a1, self.c1_dx, self.dw1, self.db1, self.c1_ws)
+
+
+class SmallCnnWorkload:
+    """cfg4 end to end: one forward + backward step of the small CNN on batch 256; launch-latency bound, so the
+    figure is the step time and the number of kernel launches, not a roofline fraction."""
+
+    def __init__(self):
+        import torch
+        import paper_2006_03108_amd as dd
+        import synthetic_inputs as syn
+        self.dd, self.torch, self.tag = dd, torch, "cfg4"
+        self.case = syn.cnn_case(syn.CONFIGS["cfg4"])
+        n_b = self.case["images"].shape[0]
+        self.net = SmallCnn(n_b, self.case["params"])
+        geoms = [self.net.c1.query(w) for w in range(4)]
+        bufs = []
+        img = torch.from_numpy(self.case["images"]).cuda()           # [n_b, 1, 28, 28]
+        for g in geoms:
+            b = torch.zeros([n_b] + g["buf_shape"] + [1], device="cuda")
+            sl = [slice(g["in_start"][d], g["in_start"][d] + g["in_size"][d]) for d in range(2)]
+            o = g["bulk_off"]
+            b[:, o[0]:o[0] + g["in_size"][0], o[1]:o[1] + g["in_size"][1], 0] = img[:, 0, sl[0], sl[1]]
+            bufs.append(b)
+        self.net.load_batch(bufs, self.case["target"])
+        self.alg = {}
+        self.flops_step = 3 * 2.0 * n_b * (6 * 25 * 28 * 28 + 16 * 6 * 25 * 10 * 10 + 400 * 120 + 120 * 84 + 84 * 10)
+        self.metric = "small CNN forward + backward step time (launch-latency bound)"
+        self.unit = "us/step"
+        self.dtype = "f32"
+        self.higher_is_better = False
+        self.describe = {"workload": f"cfg4: conv5x5(6)-pool2-conv5x5(16)-pool2-affine 400-120-84-10 with ReLU, MSE, "
+                                     f"batch {n_b} of 28x28 images, conv / pool P=2x2, affine 2x2 weight partitions, fp32",
+                         "flops_per_step": self.flops_step}
+
+    def step(self):
+        self.net.step()
+
+    def value(self, seconds_per_step):
+        return seconds_per_step * 1e6
+
+    def cpu_baseline(self):
+        from oracle import network
+        c = self.case
+        par = {k: v.astype(np.float64) for k, v in c["params"].items()}
+        t0 = time.perf_counter()
+        reps = 0
+        while time.perf_counter() - t0 < 10.0:
+            network.distributed_step(c["images"].astype(np.float64), c["target"].astype(np.float64), par)
+            reps += 1
+        dt = (time.perf_counter() - t0) / reps
+        return {"value": dt * 1e6, "unit": "us/step", "cores": 1, "kind": "oracle",
+                "sample": f"oracle network.distributed_step (numpy fp64) on the full cfg4 batch, mean of {reps} steps"}
+
+
 def kernel_rooflines(workload, report, traffic):
     """Per-kernel roofline entries from the library's HIP-event timings."""
     out = {}
@@ -367,7 +529,9 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="cfg5", choices=["cfg5", "cfg2", "cfg3", "cfg3-bf16", "movement"])
+    ap.add_argument("--workload", default="cfg5", choices=["cfg5", "cfg2", "cfg3", "cfg3-bf16", "cfg4", "movement"])
+    ap.add_argument("--no-movement", action="store_true",
+                    help="with the default workload: skip the movement kernels' own figures")
     ap.add_argument("--sweep", action="store_true",
                     help="with --workload movement: also the size sweep of broadcast / sum-reduce")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -387,6 +551,8 @@ def main():
     torch.cuda.set_device(0)
     if args.workload == "movement":
         wl = MovementWorkload(args.sweep)
+    elif args.workload == "cfg4":
+        wl = SmallCnnWorkload()
     elif args.workload in ("cfg5", "cfg2"):
         wl = ConvWorkload(args.workload)
     else:
@@ -411,6 +577,7 @@ def main():
     dd.distdl_profile_enable(False)
     sec = elapsed / args.steps
     kernels = kernel_rooflines(wl, report, load_traffic())
+    launches_per_step = sum(k["launches"] for k in kernels.values()) / args.steps
     dominant = max(kernels, key=lambda k: kernels[k]["total_ms"])
     dk = kernels[dominant]
     roofline = {"kernel": dominant, "bound": dk.get("bound"), "achieved": dk.get("achieved"), "peak": dk.get("peak"),
@@ -418,10 +585,31 @@ def main():
                 "avg_ms": dk["avg_ms"], "launches": dk["launches"]}
     line = {
         "metric": wl.metric, "value": wl.value(sec), "unit": wl.unit, "n_gpus": 1, "steps": args.steps,
-        "warmup": args.warmup, "ms_per_step": sec * 1e3, "higher_is_better": True, "scaling": "weak",
+        "warmup": args.warmup, "ms_per_step": sec * 1e3, "higher_is_better": getattr(wl, "higher_is_better", True),
+        "scaling": "weak", "kernel_launches_per_step": launches_per_step,
         "vs_baseline": None, "dtype": wl.dtype, "data": "synthetic", "config": wl.describe,
         "roofline": roofline, "kernels": kernels,
     }
+    if args.workload == "cfg5" and not args.no_movement:
+        # the other half of the metric: the movement primitives on their own (H, H* on this geometry, B, R and
+        # adjoints on large arrays), timed after the convolution step
+        del wl.y, wl.dx, wl.ws
+        mv = MovementWorkload(False)
+        for _ in range(2):
+            mv.step()
+        torch.cuda.synchronize()
+        dd.distdl_profile_enable(True)
+        dd.distdl_profile_report()
+        t0 = time.perf_counter()
+        for _ in range(10):
+            mv.step()
+        torch.cuda.synchronize()
+        mv_sec = (time.perf_counter() - t0) / 10
+        mv_kernels = kernel_rooflines(mv, dd.distdl_profile_report(), load_traffic())
+        dd.distdl_profile_enable(False)
+        line["movement"] = {"metric": mv.metric, "value": mv.value(mv_sec), "unit": mv.unit, "steps": 10,
+                            "ms_per_step": mv_sec * 1e3, "frac_hbm_peak": mv.value(mv_sec) / HBM_PEAK_GBS,
+                            "config": mv.describe, "kernels": mv_kernels}
     if getattr(wl, "sweep_on", False):
         line["sweep"] = wl.sweep()
     if not args.no_cpu_baseline:

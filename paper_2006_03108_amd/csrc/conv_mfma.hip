@@ -500,105 +500,112 @@ __global__ __launch_bounds__(256, 2) void wgrad_lds_kernel(const WorkerDev* __re
   }
 }
 
-// Weight gradient with input rows shared inside the workgroup.  Wave t1 of a workgroup owns kernel
-// row (t0, t1) and all K2 taps of it; the waves walk the output rows o1 together.  The input rows a
-// step needs, origin + o1*s1 + t1*dil1, form a window of `span` rows that advances by s1 rows per
-// step, so LDS holds them as a ring and every step fetches only the s1 new rows (plus the dy row
-// segment, shared by all waves).  Each input cell is read from memory once per t0 instead of once
-// per (t0, t1).  S2 (stride along the row) is a template parameter so that every LDS read of the
-// unrolled inner loop is an immediate offset from one per-step base address.
-template <int K2, int S2, int PX>
-__global__ __launch_bounds__(512, 2) void wgrad_rows_kernel(const WorkerDev* __restrict__ workers, void* const* x_bufs,
-                                                         void* const* dy_bufs, float* __restrict__ partial,
-                                                         WgradArgs a) {
-  extern __shared__ float4 wr_lds[];
-  const int nthreads = blockDim.x;  // 64 * k1
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, h = lane >> 5, m = lane & 31;
-  const int t0 = blockIdx.x, t1 = wave;
+// Weight gradient with all taps of one kernel plane t0 in a workgroup of four waves (one per SIMD).
+// The k1 * k2 taps of the plane, in row-major order, are split into four contiguous ranges of at most
+// TW taps; a wave accumulates its taps in TW accumulator tiles.  The waves walk the output rows o1
+// together: the input rows a step reads, origin + o1*s1 + [0, span), are kept in LDS as a ring of
+// span + s1 rows, every step fetches only its s1 new rows plus the dy row segment (both one step ahead,
+// through registers), and because the ring has s1 spare rows and the dy segment two buffers, the rows of
+// step o1 + 1 can be written while slower waves still multiply step o1: one barrier per step.  Each
+// input cell is read from memory once per t0.  Per step a wave issues 16 * TW MFMAs and a handful of
+// vector instructions: ring slots advance in scalar registers, out-of-range rows are switched off through
+// the scalar offset of the buffer load, and every LDS read of the inner loop is an immediate offset.
+// A wave with TW - 1 taps repeats its last tap (never stored), so all waves stay in step.
+template <int TW, int S2>
+__global__ __launch_bounds__(256, 2) void wgrad_taps_kernel(const WorkerDev* __restrict__ workers, void* const* x_bufs,
+                                                            void* const* dy_bufs, float* __restrict__ partial,
+                                                            WgradArgs a) {
+  extern __shared__ float4 wt_lds[];
+  constexpr int NX = 5;  // input-row pieces per thread and step
+  const int tid = threadIdx.x, lane = tid & 63, h = lane >> 5, m = lane & 31;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int t0 = blockIdx.x;
   const int nco_t = (a.co + 31) / 32;
   const int ci_t = blockIdx.y / nco_t, co_t = blockIdx.y - ci_t * nco_t;
   const int worker = blockIdx.z / a.nchunks, chunk = blockIdx.z - worker * a.nchunks;
   const WorkerDev wd = workers[worker];
-  const int ncell = a.ncell, span = a.span, s1 = a.s[1];
-  const int row_vec4 = ncell * 8;             // one staged input row: ncell cells x 32 channels
-  char* const ldsb = (char*)wr_lds;
-  const uint32_t ys_base = (uint32_t)span * row_vec4 * 16u;  // dy segment behind the ring
+  const int s1 = a.s[1], span = a.span, ring = span + s1;
+  const int rowp = (a.ncell * 8 + 63) & ~63;  // 16-byte pieces per staged row, rounded up to whole waves
+  const uint32_t pitch = (uint32_t)rowp * 16u;
+  char* const ldsb = (char*)wt_lds;
+  const uint32_t ys_base = (uint32_t)ring * pitch;  // two dy segments of 4 KiB behind the ring
+
+  const int T = a.k[1] * a.k[2];
+  const int tbase = T >> 2, trem = T & 3;
+  const int tap_first = wave * tbase + min(wave, trem);
+  const int ntw = tbase + (wave < trem ? 1 : 0);
+  int tap_t1[TW], tap_t2[TW];
+#pragma unroll
+  for (int i = 0; i < TW; ++i) {
+    const int j = tap_first + min(i, ntw - 1);
+    tap_t1[i] = j / a.k[2];
+    tap_t2[i] = j - tap_t1[i] * a.k[2];
+  }
 
   const uint32_t sx2 = a.ci, sx1 = wd.buf[2] * sx2, sx0 = wd.buf[1] * sx1, sxn = wd.buf[0] * sx0;
   const uint32_t sy2 = a.co, sy1 = wd.out[2] * sy2, sy0 = wd.out[1] * sy1, syn = wd.out[0] * sy0;
   const __amdgpu_buffer_rsrc_t rx = make_rsrc(x_bufs[worker], (uint32_t)a.n_b * sxn * 4u);
   const __amdgpu_buffer_rsrc_t ry = make_rsrc(dy_bufs[worker], (uint32_t)a.n_b * syn * 4u);
 
-  floatx16 acc[K2];
+  floatx16 acc[TW];
 #pragma unroll
-  for (int t = 0; t < K2; ++t)
+  for (int t = 0; t < TW; ++t)
     for (int v = 0; v < 16; ++v) acc[t][v] = 0.f;
 
-  // pieces of one step: the s1 new rows (s1 * row_vec4 pieces) followed by the dy segment (256)
-  const int step_pieces = s1 * row_vec4 + 256;
   const int row_cells = wd.buf[2] - wd.origin[2];
   const int O1 = wd.out[1], O2 = wd.out[2], nseg = (O2 + 31) / 32;
-  // work units: (plane (n, o0), block of a.ob output rows); a chunk is a contiguous range of units
   const int nblk1 = (O1 + a.ob - 1) / a.ob;
   const int nunits = a.n_b * wd.out[0] * nblk1;
   const int per = (nunits + a.nchunks - 1) / a.nchunks;
   const int unit_end = min(nunits, (chunk + 1) * per);
 
-  // piece -> (global byte offset relative to the step's base, LDS byte offset relative to the ring slot)
-  // is the same at every step except for the row index, which is folded into scalar bases below
-  uint32_t pg[PX], pl[PX];
-  bool pdy[PX];
+  // Slot i of a thread is piece i*256 + tid of a step's s1 * rowp input pieces; rowp is a multiple of 64,
+  // so the new-row index prr[i] of a slot is the same for a whole wave.
+  int prr[NX];
+  uint32_t prest[NX], pg[NX], pgy;
+#pragma unroll
+  for (int i = 0; i < NX; ++i) {
+    const int piece0 = i * 256 + wave * 64;
+    prr[i] = piece0 / rowp;
+    prest[i] = (uint32_t)(piece0 - prr[i] * rowp + lane);
+  }
   auto setup_pieces = [&](int seg) {
 #pragma unroll
-    for (int i = 0; i < PX; ++i) {
-      const int piece = tid + i * nthreads;
-      pg[i] = kOob;
-      pl[i] = 0xffffffffu;  // no LDS write
-      pdy[i] = false;
-      if (piece < s1 * row_vec4) {
-        const int rr = piece / row_vec4, rest = piece - rr * row_vec4;
-        const int cell = rest >> 3, q4 = (rest & 7) * 4;
-        pl[i] = (uint32_t)rest * 16u + (uint32_t)rr * 0x01000000u;  // new-row index kept in the top byte
-        if (seg * 32 * S2 + cell < row_cells && ci_t * 32 + q4 < a.ci)
-          pg[i] = (rr * sx1 + (seg * 32 * S2 + cell) * sx2 + ci_t * 32 + q4) * 4u;
-      } else if (piece < step_pieces) {
-        const int rest = piece - s1 * row_vec4;
-        const int pos = rest >> 3, q4 = (rest & 7) * 4;
-        pdy[i] = true;
-        pl[i] = ys_base + (uint32_t)rest * 16u;
-        if (seg * 32 + pos < O2 && co_t * 32 + q4 < a.co) pg[i] = ((seg * 32 + pos) * sy2 + co_t * 32 + q4) * 4u;
-      }
+    for (int i = 0; i < NX; ++i) {
+      const int cell = prest[i] >> 3, q4 = (prest[i] & 7) * 4;
+      pg[i] = kOob;  // pieces beyond the row's cells or channels stage zeros
+      if (cell < a.ncell && seg * 32 * S2 + cell < row_cells && ci_t * 32 + q4 < a.ci)
+        pg[i] = ((seg * 32 * S2 + cell) * sx2 + ci_t * 32 + q4) * 4u;
     }
+    const int pos = tid >> 3, q4 = (tid & 7) * 4;
+    pgy = kOob;
+    if (seg * 32 + pos < O2 && co_t * 32 + q4 < a.co) pgy = ((seg * 32 + pos) * sy2 + co_t * 32 + q4) * 4u;
   };
-  u32x4 rp[PX];
-  // step o1 of plane (n, o0): new rows are the last s1 rows of its window
+  u32x4 rp[NX], rpy;
   auto fetch = [&](int n, int o0, int o1) {
     const int c0 = wd.origin[0] + o0 * a.s[0] + t0 * a.dil[0];
     const int r_first = wd.origin[1] + o1 * s1 + span - s1;  // buffer row of new row 0
     const uint32_t xb = ((uint32_t)n * sxn + (uint32_t)c0 * sx0 + (uint32_t)r_first * sx1 + wd.origin[2] * sx2) * 4u;
-    const uint32_t yb = ((uint32_t)n * syn + (uint32_t)o0 * sy0 + (uint32_t)o1 * sy1) * 4u;
-    const int rows_left = wd.buf[1] - r_first;  // new rows beyond the buffer read as zero
 #pragma unroll
-    for (int i = 0; i < PX; ++i) {
-      uint32_t off = pg[i];
-      if (!pdy[i] && (int)(pl[i] >> 24) >= rows_left) off = kOob;
-      rp[i] = __builtin_amdgcn_raw_buffer_load_b128(pdy[i] ? ry : rx, off, pdy[i] ? yb : xb, 0);
+    for (int i = 0; i < NX; ++i) {
+      // rows beyond the buffer (and unused slots) read as zero: the scalar offset fails the range check
+      const uint32_t so = (prr[i] < s1 && r_first + prr[i] < wd.buf[1]) ? xb + (uint32_t)prr[i] * sx1 * 4u : kOob;
+      rp[i] = __builtin_amdgcn_raw_buffer_load_b128(rx, pg[i], so, 0);
     }
+    rpy = __builtin_amdgcn_raw_buffer_load_b128(ry, pgy, ((uint32_t)n * syn + (uint32_t)o0 * sy0 + (uint32_t)o1 * sy1) * 4u, 0);
   };
+  int nslot = 0;      // ring slot of the step's new row 0
+  int tslot[TW];      // ring slot of the row each tap reads
   auto stash = [&](int o1) {
-    // new row rr of step o1 is window row o1*s1 + span - s1 + rr, kept in ring slot (that index) mod span
-    const int slot0 = (o1 * s1 + span - s1) % span;
 #pragma unroll
-    for (int i = 0; i < PX; ++i) {
-      if (pl[i] == 0xffffffffu) continue;
-      uint32_t dst = pl[i];
-      if (!pdy[i]) {
-        int slot = slot0 + (int)(pl[i] >> 24);
-        if (slot >= span) slot -= span;
-        dst = (pl[i] & 0x00ffffffu) + (uint32_t)slot * row_vec4 * 16u;
+    for (int i = 0; i < NX; ++i) {
+      if (prr[i] < s1) {  // uniform per wave
+        int slot = nslot + prr[i];
+        if (slot >= ring) slot -= ring;
+        *(u32x4*)(ldsb + prest[i] * 16u + (uint32_t)slot * pitch) = rp[i];
       }
-      *(u32x4*)(ldsb + dst) = rp[i];
     }
+    *(u32x4*)(ldsb + ys_base + (uint32_t)(o1 & 1) * 4096u + (uint32_t)tid * 16u) = rpy;
   };
 
   const uint32_t lane_x = (uint32_t)(h * S2 * 32 + m) * 4u, lane_y = ys_base + (uint32_t)(h * 32 + m) * 4u;
@@ -607,44 +614,55 @@ __global__ __launch_bounds__(512, 2) void wgrad_rows_kernel(const WorkerDev* __r
     const int o0 = plane % wd.out[0], n = plane / wd.out[0];
     for (int seg = 0; seg < nseg; ++seg) {
       setup_pieces(seg);
+      nslot = (o1_begin * s1 + span - s1) % ring;
+#pragma unroll
+      for (int i = 0; i < TW; ++i) tslot[i] = (o1_begin * s1 + tap_t1[i] * a.dil[1]) % ring;
       __syncthreads();  // previous unit / segment fully consumed
-      // prime the ring with the first span-s1 window rows of step o1_begin
+      // prime the ring with the first span - s1 window rows of step o1_begin
       {
         const int c0 = wd.origin[0] + o0 * a.s[0] + t0 * a.dil[0];
-        const int prime = (span - s1) * row_vec4;
-        for (int piece = tid; piece < prime; piece += nthreads) {
-          const int rr = piece / row_vec4, rest = piece - rr * row_vec4;
-          const int cell = rest >> 3, q4 = (rest & 7) * 4;
-          uint32_t off = kOob;
+        for (int rr = 0; rr < span - s1; ++rr) {
           const int wrow = o1_begin * s1 + rr;  // window row, relative to the first tap of output row 0
-          if (seg * 32 * S2 + cell < row_cells && ci_t * 32 + q4 < a.ci && wd.origin[1] + wrow < wd.buf[1])
-            off = (((uint32_t)n * sxn + (uint32_t)c0 * sx0 + (uint32_t)(wd.origin[1] + wrow) * sx1 +
-                    (wd.origin[2] + seg * 32 * S2 + cell) * sx2 + ci_t * 32 + q4)) * 4u;
-          *(u32x4*)(ldsb + ((uint32_t)(wrow % span) * row_vec4 + rest) * 16u) =
-              __builtin_amdgcn_raw_buffer_load_b128(rx, off, 0, 0);
+          const bool row_ok = wd.origin[1] + wrow < wd.buf[1];
+          const uint32_t rb = ((uint32_t)n * sxn + (uint32_t)c0 * sx0 + (uint32_t)(wd.origin[1] + wrow) * sx1 +
+                               (wd.origin[2] + seg * 32 * S2) * sx2 + ci_t * 32) * 4u;
+          for (int rest = tid; rest < rowp; rest += 256) {
+            const int cell = rest >> 3, q4 = (rest & 7) * 4;
+            uint32_t off = kOob;
+            if (row_ok && cell < a.ncell && seg * 32 * S2 + cell < row_cells && ci_t * 32 + q4 < a.ci)
+              off = (cell * sx2 + q4) * 4u;
+            *(u32x4*)(ldsb + (uint32_t)(wrow % ring) * pitch + (uint32_t)rest * 16u) =
+                __builtin_amdgcn_raw_buffer_load_b128(rx, off, rb, 0);
+          }
         }
       }
       fetch(n, o0, o1_begin);
       for (int o1 = o1_begin; o1 < o1_end; ++o1) {
         stash(o1);
-        __syncthreads();
+        __syncthreads();  // step o1 staged; every wave has finished step o1 - 1
         if (o1 + 1 < o1_end) fetch(n, o0, o1 + 1);  // in flight while this step multiplies
-        const uint32_t slot = (uint32_t)((o1 * s1 + t1 * a.dil[1]) % span);
-        const char* xrow = ldsb + slot * row_vec4 * 16u + lane_x;
-        const char* yrow = ldsb + lane_y;
+        const char* ta[TW];
+#pragma unroll
+        for (int i = 0; i < TW; ++i)
+          ta[i] = ldsb + (uint32_t)tslot[i] * pitch + (uint32_t)(tap_t2[i] * a.dil[2]) * 128u + lane_x;
+        const char* yrow = ldsb + lane_y + (uint32_t)(o1 & 1) * 4096u;
         // 16 x two positions: lanes 0-31 take column 2*pr, lanes 32-63 column 2*pr + 1
-#pragma unroll 4
+#pragma unroll
         for (int pr = 0; pr < 16; ++pr) {
           const float b = *(const float*)(yrow + pr * 256);
-          float av[K2];
+          float av[TW];
 #pragma unroll
-          for (int t2 = 0; t2 < K2; ++t2)
-            av[t2] = *(const float*)(xrow + (2 * pr * S2 + (t2 < a.k[2] ? t2 : 0) * a.dil[2]) * 128);
+          for (int i = 0; i < TW; ++i) av[i] = *(const float*)(ta[i] + pr * (2 * S2 * 128));
 #pragma unroll
-          for (int t2 = 0; t2 < K2; ++t2)
-            acc[t2] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[t2], b, acc[t2], 0, 0, 0);
+          for (int i = 0; i < TW; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[i], b, acc[i], 0, 0, 0);
         }
-        __syncthreads();  // all waves done with this step's rows before the ring advances
+        nslot += s1;
+        if (nslot >= ring) nslot -= ring;
+#pragma unroll
+        for (int i = 0; i < TW; ++i) {
+          tslot[i] += s1;
+          if (tslot[i] >= ring) tslot[i] -= ring;
+        }
       }
     }
   }
@@ -652,13 +670,13 @@ __global__ __launch_bounds__(512, 2) void wgrad_rows_kernel(const WorkerDev* __r
   const bool co_ok = co < a.co;
   float* pbase = partial + (size_t)blockIdx.z * a.slot;
 #pragma unroll
-  for (int t2 = 0; t2 < K2; ++t2) {
-    if (t2 >= a.k[2]) break;
-    const int tap = (t0 * a.k[1] + t1) * a.k[2] + t2;
+  for (int i = 0; i < TW; ++i) {
+    if (i >= ntw) break;
+    const int tap = (t0 * a.k[1] + tap_t1[i]) * a.k[2] + tap_t2[i];
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
       const int cir = ci_t * 32 + 8 * (v / 4) + 4 * h + (v % 4);
-      if (cir < a.ci && co_ok) pbase[((size_t)tap * a.ci + cir) * a.co + co] = acc[t2][v];
+      if (cir < a.ci && co_ok) pbase[((size_t)tap * a.ci + cir) * a.co + co] = acc[i][v];
     }
   }
 }
@@ -919,16 +937,25 @@ bool wgrad_mfma_supported(const distdl_plan* p) {
   return p->dtype == DISTDL_F32 && !p->explicit_halo && p->ksize[2] <= kMaxK2;
 }
 
-// The shared-rows kernel needs 16-byte channel pieces, a row stride of 1 or 2, at most 8 kernel rows
-// of at most 5 taps, and a ring that fits in LDS.
+// Taps per wave of the plane-per-workgroup weight-gradient kernel (0: fewer taps than waves).
+static int wgrad_taps_per_wave(const distdl_plan* p) {
+  const int T = p->ksize[1] * p->ksize[2];
+  return T >= 4 ? (T + 3) / 4 : 0;
+}
+
+// The plane-per-workgroup kernel needs 16-byte channel pieces, a row stride of 1 or 2, a tap count
+// per wave it is instantiated for, s1 new rows per step that fit the five piece slots of a thread,
+// and a ring that fits in LDS.
 static bool wgrad_rows_shape_ok(const distdl_plan* p) {
   const int span = (p->ksize[1] - 1) * p->dilation[1] + 1;
   const int ncell = 31 * p->stride[2] + (p->ksize[2] - 1) * p->dilation[2] + 1;
+  const int rowp = (ncell * 8 + 63) & ~63;
+  const int tw = wgrad_taps_per_wave(p);
   if (p->n_ci % 4 || p->n_co % 4) return false;
-  if (p->ksize[1] > 8 || p->ksize[2] > 5 || p->stride[2] > 2 || p->stride[1] > span) return false;
-  if ((size_t)span * ncell * 128 + 4096 > 96 * 1024) return false;
-  if (p->stride[1] * ncell * 8 + 256 > 6 * 64 * std::min(p->ksize[1], 4)) return false;
-  if (ncell > 72) return false;  // the wave-private kernel takes the rows beyond the fourth
+  if (tw != 3 && tw != 4 && tw != 7) return false;
+  if (p->stride[2] > 2 || p->stride[1] > span) return false;
+  if (p->stride[1] * rowp > 5 * 256) return false;
+  if ((size_t)(span + p->stride[1]) * rowp * 16 + 8192 > 160 * 1024) return false;
   if ((double)p->n_b * p->max_buf_cells * std::max(p->n_ci, p->n_co) * 4.0 >= 2147480000.0) return false;
   return true;
 }
@@ -998,37 +1025,26 @@ int conv_wgrad_mfma(distdl_plan* p, float* partial, hipStream_t st) {
     aligned = (uintptr_t)p->tab_x.host[w] % 16 == 0 && (uintptr_t)p->tab_dy.host[w] % 16 == 0;
   const int lds = 4 * (a.ncell + 32) * 128;
   if (aligned && wgrad_rows_shape_ok(p)) {
-    // Kernel rows t1 < k1_main go to the shared-rows kernel, one wave per row and four waves (one per
-    // SIMD) when the kernel has at least four rows; the remaining rows go to the wave-private kernel.
-    const int k1_main = a.k[1] >= 4 ? 4 : a.k[1];
-    a.span = (k1_main - 1) * a.dil[1] + 1;
-    const int rlds = a.span * a.ncell * 128 + 4096;
-    dim3 rgrid((unsigned)a.k[0], grid.y, grid.z), rblock(64 * k1_main);
+    const int rowp = (a.ncell * 8 + 63) & ~63;
+    const int rlds = (a.span + a.s[1]) * rowp * 16 + 8192;
+    const int tw = wgrad_taps_per_wave(p);
+    dim3 rgrid((unsigned)a.k[0], grid.y, grid.z), rblock(256);
     ProfScope prof("conv_bwd_weight_mfma", st);
-#define DISTDL_LAUNCH_ROWS(K2_, S2_)                                                                                \
+#define DISTDL_LAUNCH_TAPS(TW_, S2_)                                                                                \
   do {                                                                                                              \
     if (rlds > 64 * 1024)                                                                                           \
-      DISTDL_HIP_TRY(hipFuncSetAttribute((const void*)wgrad_rows_kernel<K2_, S2_, 6>,                               \
+      DISTDL_HIP_TRY(hipFuncSetAttribute((const void*)wgrad_taps_kernel<TW_, S2_>,                                  \
                                          hipFuncAttributeMaxDynamicSharedMemorySize, rlds));                        \
-    hipLaunchKernelGGL((wgrad_rows_kernel<K2_, S2_, 6>), rgrid, rblock, rlds, st, p->d_workers, p->tab_x.dev,       \
+    hipLaunchKernelGGL((wgrad_taps_kernel<TW_, S2_>), rgrid, rblock, rlds, st, p->d_workers, p->tab_x.dev,          \
                        p->tab_dy.dev, partial, a);                                                                  \
   } while (0)
-    if (a.k[2] <= 3 && a.s[2] == 1) DISTDL_LAUNCH_ROWS(3, 1);
-    else if (a.k[2] <= 3) DISTDL_LAUNCH_ROWS(3, 2);
-    else if (a.s[2] == 1) DISTDL_LAUNCH_ROWS(5, 1);
-    else DISTDL_LAUNCH_ROWS(5, 2);
-#undef DISTDL_LAUNCH_ROWS
-    if (k1_main < a.k[1]) {
-      a.t1_first = k1_main;
-      dim3 lgrid((unsigned)((a.k[0] * (a.k[1] - k1_main) + 3) / 4), grid.y, grid.z);
-      if (a.k[2] <= 3)
-        hipLaunchKernelGGL((wgrad_lds_kernel<3, 9>), lgrid, dim3(256), lds, st, p->d_workers, p->tab_x.dev,
-                           p->tab_dy.dev, partial, a);
-      else
-        hipLaunchKernelGGL((wgrad_lds_kernel<5, 9>), lgrid, dim3(256), lds, st, p->d_workers, p->tab_x.dev,
-                           p->tab_dy.dev, partial, a);
-      a.t1_first = 0;
-    }
+    if (tw == 3 && a.s[2] == 1) DISTDL_LAUNCH_TAPS(3, 1);
+    else if (tw == 3) DISTDL_LAUNCH_TAPS(3, 2);
+    else if (tw == 4 && a.s[2] == 1) DISTDL_LAUNCH_TAPS(4, 1);
+    else if (tw == 4) DISTDL_LAUNCH_TAPS(4, 2);
+    else if (a.s[2] == 1) DISTDL_LAUNCH_TAPS(7, 1);
+    else DISTDL_LAUNCH_TAPS(7, 2);
+#undef DISTDL_LAUNCH_TAPS
   } else {
     ProfScope prof("conv_bwd_weight_mfma", st);
     if (aligned && a.ncell <= 72 && a.k[2] <= 3)

@@ -12,43 +12,19 @@ from oracle import geometry as geo
 from oracle import layers
 from oracle import network
 from oracle import primitives as prim
-from tests.gpu_util import assert_close, from_cl, require_gpu, to_cl, w_to_dev
+from tests.gpu_util import assert_close, from_cl, require_gpu, to_cl
 
 pytestmark = pytest.mark.gpu
 TOL32 = 1e-5
 ONE2 = (1, 1)
 
 
-class ConvLayer:
-    def __init__(self, n_b, c_in, c_out, in_shape, P, k, pad):
-        self.plan = dd.distdl_plan_create(2, n_b, c_in, c_out, in_shape, P, (k, k), ONE2, (pad, pad), ONE2)
-        self.geoms = [self.plan.query(w) for w in range(self.plan.n_workers)]
-        self.x = [torch.zeros([n_b] + g["buf_shape"] + [c_in], device="cuda") for g in self.geoms]
-        self.y = [torch.empty([n_b] + g["out_size"] + [c_out], device="cuda") for g in self.geoms]
-        self.dx = [torch.empty_like(t) for t in self.x]
-        self.dense_in = [torch.empty([n_b] + g["in_size"] + [c_in], device="cuda") for g in self.geoms]
-        self.ws = torch.empty(max(dd.distdl_conv_bwd_workspace(self.plan), 16), dtype=torch.uint8, device="cuda")
-
-
-class PoolLayer:
-    def __init__(self, n_b, c, in_shape, P):
-        self.plan = dd.distdl_plan_create(2, n_b, c, c, in_shape, P, (2, 2), (2, 2), (0, 0), ONE2)
-        self.geoms = [self.plan.query(w) for w in range(self.plan.n_workers)]
-        self.x = [torch.zeros([n_b] + g["buf_shape"] + [c], device="cuda") for g in self.geoms]
-        self.y = [torch.empty([n_b] + g["out_size"] + [c], device="cuda") for g in self.geoms]
-        self.dx = [torch.empty_like(t) for t in self.x]
-        self.dense_in = [torch.empty([n_b] + g["in_size"] + [c], device="cuda") for g in self.geoms]
-
-
-def _split_affine(W, b, P_fo, P_fi):
-    rows, cols = layers.feature_blocks(W.shape[0], P_fo), layers.feature_blocks(W.shape[1], P_fi)
-    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).float().cuda()
-    return [dev(W[r][:, c]) for r in rows for c in cols], [dev(b[r]) for r in rows], rows, cols
-
-
 @pytest.mark.parametrize("n_b", [256, 6])
 def test_small_cnn_step_matches_oracle(n_b):
+    """The network driver the benchmark times (bench.SmallCnn: device tensors and the order of the library
+    calls, nothing else) against the oracle's distributed network."""
     require_gpu()
+    from bench import SmallCnn
     case = syn.cnn_case(dict(syn.CONFIGS["cfg4"], n_b=n_b))
     par = {k: v.astype(np.float64) for k, v in case["params"].items()}
     rng = np.random.default_rng(2)
@@ -58,102 +34,27 @@ def test_small_cnn_step_matches_oracle(n_b):
     img, tgt = case["images"], case["target"]
     loss_want, out_want, g_want = network.distributed_step(img.astype(np.float64), tgt.astype(np.float64), par)
 
-    P, Pf = (2, 2), 2
-    c1 = ConvLayer(n_b, 1, 6, (28, 28), P, 5, 2)
-    p2 = PoolLayer(n_b, 6, (28, 28), P)
-    c3 = ConvLayer(n_b, 6, 16, (14, 14), P, 5, 0)
-    p4 = PoolLayer(n_b, 16, (10, 10), P)
-    part1 = geo.Partition.for_kernel((28, 28), P, (5, 5), ONE2, (2, 2), ONE2)
-    w1, b1 = w_to_dev(par["c1_w"]), w_to_dev(par["c1_b"])
-    w3, b3 = w_to_dev(par["c3_w"]), w_to_dev(par["c3_b"])
-    W5, B5, rows5, _ = _split_affine(par["c5_w"], par["c5_b"], Pf, Pf)
-    W6, B6, rows6, _ = _split_affine(par["f6_w"], par["f6_b"], Pf, Pf)
-    Wo, Bo, rowso, _ = _split_affine(par["out_w"], par["out_b"], Pf, Pf)
-    a5p = dd.distdl_affine_plan_create(n_b, 400, 120, Pf, Pf)
-    a6p = dd.distdl_affine_plan_create(n_b, 120, 84, Pf, Pf)
-    aop = dd.distdl_affine_plan_create(n_b, 84, 10, Pf, Pf)
-    new = lambda shapes: [torch.empty(s, device="cuda") for s in shapes]
-    like = lambda ts: [torch.empty_like(t) for t in ts]
-
-    # ---- forward
-    for w, b in enumerate(prim.scatter_bulk(img, part1, fill=np.float32(0.0))):
-        c1.x[w].copy_(to_cl(b))
-    dd.distdl_conv_fwd(c1.plan, c1.x, w1, b1, c1.y)
-    r1 = like(c1.y)
-    dd.distdl_relu_fwd(c1.y, r1)
-    dd.distdl_bulk_copy(p2.plan, r1, p2.x, True)
-    dd.distdl_maxpool_fwd(p2.plan, p2.x, p2.y)
-    dd.distdl_bulk_copy(c3.plan, p2.y, c3.x, True)
-    dd.distdl_conv_fwd(c3.plan, c3.x, w3, b3, c3.y)
-    r3 = like(c3.y)
-    dd.distdl_relu_fwd(c3.y, r3)
-    dd.distdl_bulk_copy(p4.plan, r3, p4.x, True)
-    dd.distdl_maxpool_fwd(p4.plan, p4.x, p4.y)
-    f = new([(n_b, 200), (n_b, 200)])
-    dd.distdl_repartition_fwd(p4.plan, p4.y, f)
-    a5 = new([(n_b, 60), (n_b, 60)])
-    dd.distdl_affine_fwd(a5p, f, W5, B5, a5)
-    r5 = like(a5)
-    dd.distdl_relu_fwd(a5, r5)
-    a6 = new([(n_b, 42), (n_b, 42)])
-    dd.distdl_affine_fwd(a6p, r5, W6, B6, a6)
-    r6 = like(a6)
-    dd.distdl_relu_fwd(a6, r6)
-    out = new([(n_b, 5), (n_b, 5)])
-    dd.distdl_affine_fwd(aop, r6, Wo, Bo, out)
-    t_parts = [torch.from_numpy(np.ascontiguousarray(tgt[:, r])).cuda() for r in rowso]
-    d_out = like(out)
-    loss = torch.zeros(1, dtype=torch.float64, device="cuda")
-    dd.distdl_mse_fwd_bwd(out, t_parts, d_out, loss)
-
-    # ---- backward
-    d_r6, dWo, dBo = like(r6), like(Wo), like(Bo)
-    dd.distdl_affine_bwd(aop, r6, Wo, d_out, d_r6, dWo, dBo)
-    d_a6 = like(a6)
-    dd.distdl_relu_bwd(a6, d_r6, d_a6)
-    d_r5, dW6, dB6 = like(r5), like(W6), like(B6)
-    dd.distdl_affine_bwd(a6p, r5, W6, d_a6, d_r5, dW6, dB6)
-    d_a5 = like(a5)
-    dd.distdl_relu_bwd(a5, d_r5, d_a5)
-    d_f, dW5, dB5 = like(f), like(W5), like(B5)
-    dd.distdl_affine_bwd(a5p, f, W5, d_a5, d_f, dW5, dB5)
-    d_s4 = like(p4.y)
-    dd.distdl_repartition_adj(p4.plan, d_f, d_s4)
-    dd.distdl_maxpool_bwd(p4.plan, p4.x, d_s4, p4.dx)
-    d_r3 = like(r3)
-    dd.distdl_bulk_copy(p4.plan, d_r3, p4.dx, False)
-    d_a3 = like(c3.y)
-    dd.distdl_relu_bwd(c3.y, d_r3, d_a3)
-    dw3, db3 = torch.empty_like(w3), torch.empty_like(b3)
-    dd.distdl_conv_bwd(c3.plan, c3.x, w3, d_a3, c3.dx, dw3, db3, c3.ws)
-    d_s2 = like(p2.y)
-    dd.distdl_bulk_copy(c3.plan, d_s2, c3.dx, False)
-    dd.distdl_maxpool_bwd(p2.plan, p2.x, d_s2, p2.dx)
-    d_r1 = like(r1)
-    dd.distdl_bulk_copy(p2.plan, d_r1, p2.dx, False)
-    d_a1 = like(c1.y)
-    dd.distdl_relu_bwd(c1.y, d_r1, d_a1)
-    dw1, db1 = torch.empty_like(w1), torch.empty_like(b1)
-    dd.distdl_conv_bwd(c1.plan, c1.x, w1, d_a1, c1.dx, dw1, db1, c1.ws)
+    net = SmallCnn(n_b, par)
+    part1 = geo.Partition.for_kernel((28, 28), (2, 2), (5, 5), ONE2, (2, 2), ONE2)
+    net.load_batch([to_cl(b) for b in prim.scatter_bulk(img, part1, fill=np.float32(0.0))], tgt)
+    net.step()
+    net.step()                                         # a second step must not depend on left-over state
     torch.cuda.synchronize()
 
-    # ---- compare
     host = lambda t: t.cpu().numpy()
-    assert abs(loss.item() - loss_want) <= TOL32 * abs(loss_want)
-    assert_close(np.concatenate([host(t) for t in out], axis=1), out_want, TOL32, "network output")
-    join = lambda parts, Pfo: np.block([[host(parts[i * Pf + j]) for j in range(Pf)] for i in range(Pfo)])
+    cat = lambda parts: np.concatenate([host(t) for t in parts])
+    join = lambda parts: np.block([[host(parts[i * 2 + j]) for j in range(2)] for i in range(2)])
+    assert abs(net.loss.item() - loss_want) <= TOL32 * abs(loss_want)
+    assert_close(np.concatenate([host(t) for t in net.ao["y"]], axis=1), out_want, TOL32, "network output")
     tol = 2e-5     # a chain of five fp32 layers
-    assert_close(join(dWo, Pf), g_want["out_w"], tol, "d out_w")
-    assert_close(np.concatenate([host(t) for t in dBo]), g_want["out_b"], tol, "d out_b")
-    assert_close(join(dW6, Pf), g_want["f6_w"], tol, "d f6_w")
-    assert_close(np.concatenate([host(t) for t in dB6]), g_want["f6_b"], tol, "d f6_b")
-    assert_close(join(dW5, Pf), g_want["c5_w"], tol, "d c5_w")
-    assert_close(np.concatenate([host(t) for t in dB5]), g_want["c5_b"], tol, "d c5_b")
-    assert_close(host(dw3), g_want["c3_w"], tol, "d c3_w")
-    assert_close(host(db3), g_want["c3_b"], tol, "d c3_b")
-    assert_close(host(dw1), g_want["c1_w"], tol, "d c1_w")
-    assert_close(host(db1), g_want["c1_b"], tol, "d c1_b")
-    assert_close(prim.gather_bulk([from_cl(t) for t in c1.dx], part1), g_want["images"], tol, "d images")
+    for name, layer in (("out", net.ao), ("f6", net.a6), ("c5", net.a5)):
+        assert_close(join(layer["dW"]), g_want[name + "_w"], tol, "d " + name + "_w")
+        assert_close(cat(layer["db"]), g_want[name + "_b"], tol, "d " + name + "_b")
+    assert_close(host(net.dw3), g_want["c3_w"], tol, "d c3_w")
+    assert_close(host(net.db3), g_want["c3_b"], tol, "d c3_b")
+    assert_close(host(net.dw1), g_want["c1_w"], tol, "d c1_w")
+    assert_close(host(net.db1), g_want["c1_b"], tol, "d c1_b")
+    assert_close(prim.gather_bulk([from_cl(t) for t in net.c1_dx], part1), g_want["images"], tol, "d images")
 
 
 def test_pool_and_repartition_against_oracle_on_unbalanced_geometry():
