@@ -34,9 +34,8 @@ struct WgradArgs {
   int32_t k[3], s[3], dil[3];
   int32_t nchunks;  // position chunks per worker
   int32_t ncell;    // input cells the taps of 32 consecutive output columns read
-  int32_t span;     // input rows the shared-rows kernel's taps cover: (rows - 1) * dil1 + 1
-  int32_t t1_first; // first kernel row the wave-private kernel handles
-  int32_t ob;       // output rows per work unit of the shared-rows kernel
+  int32_t span;     // input rows the taps of one output row cover: (rows - 1) * dil1 + 1
+  int32_t ob;       // output rows per work unit of the plane-per-workgroup kernel
   int64_t slot;     // floats per (worker, chunk) partial: taps*ci*co + co
 };
 

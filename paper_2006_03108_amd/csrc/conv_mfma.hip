@@ -12,6 +12,9 @@
 // wgrad_mfma_kernel: dw^[tap][ci][co] = sum_pos x^[cell(pos,tap)][ci] dy[pos][co]
 //   per worker; both MFMA operands are read straight from global memory in
 //   their register layout (channels-last makes 32 channels one 128-byte row).
+//   wgrad_lds_kernel stages the row segments in wave-private LDS; wgrad_taps_kernel
+//   (the fast path) gives a workgroup all taps of one kernel plane and shares the
+//   input rows between its waves through an LDS ring.
 //
 // v_mfma_f32_32x32x2_f32 operand layout: A lane l holds A[i = l%32][k = l/32],
 // B lane l holds B[k = l/32][j = l%32], D register v of lane l holds
@@ -76,14 +79,17 @@ __device__ inline __amdgpu_buffer_rsrc_t make_rsrc(const void* p, uint32_t bytes
 // are read from LDS into a second register set while tap i multiplies.
 //
 // MT: 32-position M-tiles per wave; PA / PB: 16-byte patch / weight pieces per thread and stage.
-template <int MT, int PA, int PB>
+// NT: taps per plane (nt[1] * nt[2]) known at compile time, or 0: with NT > 0 the tap loop is unrolled,
+// the LDS address of every (M-tile, tap) operand is computed once per workgroup and the weight operand
+// of tap t is an immediate offset, which removes the per-tap address arithmetic from the stage loop.
+template <int MT, int PA, int PB, int NT>
 __global__ __launch_bounds__(256, 2) void corr_mfma_kernel(const WorkerDev* __restrict__ workers,
                                                            void* const* in_bufs, void* const* out_bufs, CorrArgs a) {
   extern __shared__ float4 lds[];
-  float4* As = lds;
-  float4* Bs = lds + a.a_vec4;
+  // LDS: patch (a_vec4 16-byte units), weights (nb_vec4), one spare unit that absorbs the pieces nobody
+  // needs, then the tap table.
   const int nb_vec4 = a.nt[1] * a.nt[2] * 64;
-  const int dummy = a.a_vec4 + nb_vec4;  // one spare 16-byte slot that absorbs the pieces nobody needs
+  const int dummy = a.a_vec4 + nb_vec4;
   uint32_t* tap_tab = (uint32_t*)(lds + dummy + 1);  // byte offset into the patch per (t1, t2), read as a broadcast
 
   // XCD-aware order: consecutive tiles (which share input rows) stay on one XCD, i.e. behind one L2
@@ -144,7 +150,7 @@ __global__ __launch_bounds__(256, 2) void corr_mfma_kernel(const WorkerDev* __re
   // The workgroup's 128*MT output positions form a tr x tc window, row-major; lane m of M-tile
   // (wave, mt) multiplies window position (wave*MT + mt)*32 + m, and accumulator register v of lane
   // (h, m) is window position (wave*MT + mt)*32 + 8*(v/4) + 4*h + v%4, channel ntile*32 + m.
-  uint32_t abase[MT], soff[MT][16];
+  uint32_t abase[MT];
   const int ch = ntile * 32 + m;
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) {
@@ -152,6 +158,11 @@ __global__ __launch_bounds__(256, 2) void corr_mfma_kernel(const WorkerDev* __re
     int wr = pidx / a.tc, wc = pidx - wr * a.tc;
     if (wr >= a.tr) wr = 0, wc = 0;  // idle position: multiplies something in range, never stored
     abase[mt] = (wr * a.is[1] * 2 * a.is[2] * a.CwQ + wc + h * a.is[2] * a.CwQ) * 16;
+  }
+  // store offset of accumulator register v of M-tile mt (kOob: nothing to store)
+  uint32_t soff[MT][16];
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt) {
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
       const int po = (wave * MT + mt) * 32 + 8 * (v / 4) + 4 * h + (v % 4);
@@ -168,28 +179,28 @@ __global__ __launch_bounds__(256, 2) void corr_mfma_kernel(const WorkerDev* __re
   const int* __restrict__ tapinfo = a.tapinfo;  // [0..7]: plane offsets, [8..]: patch offset per (t1, t2)
   const int ntaps = a.nt[1] * a.nt[2];
   if (tid < ntaps) tap_tab[tid] = (uint32_t)tapinfo[8 + tid] * 16u;  // visible after the first barrier below
-  const int nstages = nt0 * ncc;
   const bool ragged = (a.kc & 7) != 0;
   char* const ldsb = (char*)lds;
 
   // A stage is one (output plane q0, tap plane t0, 8-channel chunk cc); stages whose input plane lies
   // outside the input contribute zero and are skipped.
   auto plane_of = [&](int q0, int t0) { return g.in_base[0] + q0 * a.is[0] + tapinfo[t0]; };
-  auto advance = [&](int& q0, int& st) {  // next valid stage after (q0, st), or q0 == q0_end
-    ++st;
+  auto advance = [&](int& q0, int& t0, int& cc) {  // next valid stage after (q0, t0, cc), or q0 == q0_end
+    if (++cc < ncc) return;  // same plane, next chunk
+    cc = 0;
+    ++t0;
     while (q0 < q0_end) {
-      while (st < nstages) {
-        const int i0 = plane_of(q0, st / ncc);
+      while (t0 < nt0) {
+        const int i0 = plane_of(q0, t0);
         if (i0 >= 0 && i0 < g.in_ext[0]) return;
-        st = (st / ncc + 1) * ncc;
+        ++t0;
       }
       ++q0;
-      st = 0;
+      t0 = 0;
     }
   };
   u32x4 ra[PA], rb[PB];
-  auto load_stage = [&](int q0, int st) {
-    const int t0 = st / ncc, cc = st - t0 * ncc;
+  auto load_stage = [&](int q0, int t0, int cc) {
     const uint32_t sbase = ((uint32_t)n * sin + (uint32_t)plane_of(q0, t0) * si0 + cc * 8) * 4u;
     if (ragged && cc == ncc - 1) {
 #pragma unroll
@@ -202,7 +213,7 @@ __global__ __launch_bounds__(256, 2) void corr_mfma_kernel(const WorkerDev* __re
 #pragma unroll
       for (int i = 0; i < PA; ++i) ra[i] = __builtin_amdgcn_raw_buffer_load_b128(rin, goff[i], sbase, 0);
     }
-    const uint32_t wbase = (uint32_t)st * nb_vec4 * 16u;
+    const uint32_t wbase = (uint32_t)(t0 * ncc + cc) * nb_vec4 * 16u;
 #pragma unroll
     for (int i = 0; i < PB; ++i) rb[i] = __builtin_amdgcn_raw_buffer_load_b128(rw, boff0, wbase + i * 4096u, 0);
   };
@@ -212,26 +223,79 @@ __global__ __launch_bounds__(256, 2) void corr_mfma_kernel(const WorkerDev* __re
 #pragma unroll
     for (int i = 0; i < PB; ++i) *(u32x4*)(ldsb + bl[i]) = rb[i];
   };
-  auto read_ops = [&](int tap, float4& b, float4 (&av)[MT]) {
-    const uint32_t tapo = tap_tab[tap];
-    b = *(const float4*)(ldsb + bread + tap * 1024);
+  // operand addresses per (M-tile, tap), fixed for the whole workgroup (NT > 0 only)
+  uint32_t aaddr[MT][NT > 0 ? NT : 1];
+  if constexpr (NT > 0) {
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) av[mt] = *(const float4*)(ldsb + abase[mt] + tapo);
+    for (int t = 0; t < NT; ++t) {
+      const uint32_t tapo = (uint32_t)tapinfo[8 + t] * 16u;
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) aaddr[mt][t] = abase[mt] + tapo;
+    }
+  }
+  auto read_ops = [&](int tap, float4& b, float4 (&av)[MT]) {
+    const char* lb = ldsb;
+    if constexpr (NT > 0) {
+      b = *(const float4*)(lb + bread + tap * 1024);
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) av[mt] = *(const float4*)(lb + aaddr[mt][tap]);
+    } else {
+      const uint32_t tapo = tap_tab[tap];
+      b = *(const float4*)(lb + bread + tap * 1024);
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) av[mt] = *(const float4*)(lb + abase[mt] + tapo);
+    }
   };
   auto multiply = [&](floatx16 (&acc)[MT], const float4& b, const float4 (&av)[MT]) {
+    // M-tiles interleaved, so that consecutive MFMAs do not depend on each other
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-      acc[mt] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[mt].x, b.x, acc[mt], 0, 0, 0);
-      acc[mt] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[mt].y, b.y, acc[mt], 0, 0, 0);
-      acc[mt] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[mt].z, b.z, acc[mt], 0, 0, 0);
-      acc[mt] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[mt].w, b.w, acc[mt], 0, 0, 0);
+    for (int mt = 0; mt < MT; ++mt) acc[mt] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[mt].x, b.x, acc[mt], 0, 0, 0);
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) acc[mt] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[mt].y, b.y, acc[mt], 0, 0, 0);
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) acc[mt] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[mt].z, b.z, acc[mt], 0, 0, 0);
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) acc[mt] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[mt].w, b.w, acc[mt], 0, 0, 0);
+  };
+
+  // The operands of tap t + 1 are read while tap t multiplies; the scheduling barriers keep the
+  // compiler from sinking the LDS reads down to their first use, which would expose their latency.
+  auto compute = [&](floatx16 (&acc)[MT]) {
+    float4 b0, b1, a0[MT], a1[MT];
+    read_ops(0, b0, a0);
+    if constexpr (NT > 0) {
+#pragma unroll
+      for (int tap = 0; tap + 1 < NT; tap += 2) {
+        read_ops(tap + 1, b1, a1);
+        __builtin_amdgcn_sched_barrier(0);
+        multiply(acc, b0, a0);
+        __builtin_amdgcn_sched_barrier(0);
+        if (tap + 2 < NT) read_ops(tap + 2, b0, a0);
+        __builtin_amdgcn_sched_barrier(0);
+        multiply(acc, b1, a1);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      if (NT & 1) multiply(acc, b0, a0);
+    } else {
+      int tap = 0;
+      for (; tap + 1 < ntaps; tap += 2) {
+        read_ops(tap + 1, b1, a1);
+        __builtin_amdgcn_sched_barrier(0);
+        multiply(acc, b0, a0);
+        __builtin_amdgcn_sched_barrier(0);
+        if (tap + 2 < ntaps) read_ops(tap + 2, b0, a0);
+        __builtin_amdgcn_sched_barrier(0);
+        multiply(acc, b1, a1);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      if (tap < ntaps) multiply(acc, b0, a0);
     }
   };
 
   floatx16 acc[MT];
-  int q0 = q0_begin, st = -1;
-  advance(q0, st);
-  if (q0 < q0_end) load_stage(q0, st);
+  int q0 = q0_begin, t0 = -1, cc = ncc - 1;  // the stage whose loads are in flight
+  advance(q0, t0, cc);
+  if (q0 < q0_end) load_stage(q0, t0, cc);
   for (int qo = q0_begin; qo < q0_end; ++qo) {  // output planes of this workgroup
 #pragma unroll
     for (int t = 0; t < MT; ++t)
@@ -239,18 +303,9 @@ __global__ __launch_bounds__(256, 2) void corr_mfma_kernel(const WorkerDev* __re
     while (q0 == qo) {  // the stages that feed output plane qo
       write_stage();
       __syncthreads();
-      advance(q0, st);
-      if (q0 < q0_end) load_stage(q0, st);  // in flight while this stage multiplies
-      float4 b0, b1, a0[MT], a1[MT];
-      read_ops(0, b0, a0);
-      int tap = 0;
-      for (; tap + 1 < ntaps; tap += 2) {
-        read_ops(tap + 1, b1, a1);
-        multiply(acc, b0, a0);
-        if (tap + 2 < ntaps) read_ops(tap + 2, b0, a0);
-        multiply(acc, b1, a1);
-      }
-      if (tap < ntaps) multiply(acc, b0, a0);
+      advance(q0, t0, cc);
+      if (q0 < q0_end) load_stage(q0, t0, cc);  // in flight while this stage multiplies
+      compute(acc);
       __syncthreads();  // everyone is done reading this stage
     }
     const uint32_t obase = ((uint32_t)n * son + (uint32_t)(g.out_base[0] + g.os[0] * qo) * so0) * 4u;
@@ -393,11 +448,10 @@ __global__ __launch_bounds__(256, 2) void wgrad_lds_kernel(const WorkerDev* __re
                                                            WgradArgs a) {
   extern __shared__ float4 wg_lds[];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, h = lane >> 5, m = lane & 31;
-  // kernel rows (t0, t1) with t1 >= t1_first, four per workgroup
-  const int nleft = a.k[1] - a.t1_first;
+  // kernel rows (t0, t1), four per workgroup
   const int trow = blockIdx.x * 4 + wave;
-  if (trow >= a.k[0] * nleft) return;  // no workgroup barrier below
-  const int t0 = trow / nleft, t1 = a.t1_first + trow - t0 * nleft;
+  if (trow >= a.k[0] * a.k[1]) return;  // no workgroup barrier below
+  const int t0 = trow / a.k[1], t1 = trow - t0 * a.k[1];
   const int nco_t = (a.co + 31) / 32;
   const int ci_t = blockIdx.y / nco_t, co_t = blockIdx.y - ci_t * nco_t;
   const int worker = blockIdx.z / a.nchunks, chunk = blockIdx.z - worker * a.nchunks;
@@ -844,13 +898,14 @@ static int launch_corr(distdl_plan* p, CorrArgs a, const float* w, float* wscrat
                        void** out_tab, const char* name, hipStream_t st) {
   const int mt = choose_mt(a, max_nq2(p, a));
   if (mt == 0) return set_error(DISTDL_ERR_UNSUPPORTED, "conv: kernel footprint does not fit in LDS");
-  // output planes per workgroup: as many as still leave about 2048 workgroups
+  // output planes per workgroup: as many as still leave about 2048 workgroups (3584 for the shorter
+  // workgroups of the data-gradient classes)
   a.g0 = 1;
   {
     int nq0max = 0;
     for (const WorkerDev& wd : p->workers) nq0max = std::max(nq0max, derive(wd, a).nq[0]);
     const int64_t wgs = max_tiles(p, a) * p->n_workers;
-    a.g0 = (int32_t)std::max<int64_t>(1, std::min<int64_t>(nq0max, wgs / 2048));
+    a.g0 = (int32_t)std::max<int64_t>(1, std::min<int64_t>(nq0max, wgs / (a.mode == 1 ? 3584 : 2048)));
   }
   a.tiles_max = (int32_t)max_tiles(p, a);
   if (a.tiles_max == 0) return DISTDL_OK;
@@ -869,18 +924,22 @@ static int launch_corr(distdl_plan* p, CorrArgs a, const float* w, float* wscrat
   const int lds = lds_bytes(a);
   const bool small = a.R * a.Cw * 2 <= 4 * 256 && a.nt[1] * a.nt[2] * 64 <= 3 * 256;
   ProfScope prof(name, st);
-#define DISTDL_LAUNCH_CORR(MT_, PA_, PB_)                                                                            \
+#define DISTDL_LAUNCH_CORR(MT_, PA_, PB_, NT_)                                                                       \
   do {                                                                                                               \
     if (lds > 64 * 1024)                                                                                             \
-      DISTDL_HIP_TRY(hipFuncSetAttribute((const void*)corr_mfma_kernel<MT_, PA_, PB_>,                               \
+      DISTDL_HIP_TRY(hipFuncSetAttribute((const void*)corr_mfma_kernel<MT_, PA_, PB_, NT_>,                          \
                                          hipFuncAttributeMaxDynamicSharedMemorySize, lds));                          \
-    hipLaunchKernelGGL((corr_mfma_kernel<MT_, PA_, PB_>), dim3((unsigned)blocks), dim3(256), lds, st, p->d_workers,  \
-                       in_tab, out_tab, a);                                                                          \
+    hipLaunchKernelGGL((corr_mfma_kernel<MT_, PA_, PB_, NT_>), dim3((unsigned)blocks), dim3(256), lds, st,           \
+                       p->d_workers, in_tab, out_tab, a);                                                            \
   } while (0)
-  if (mt == 2 && small) DISTDL_LAUNCH_CORR(2, 4, 3);
-  else if (mt == 2) DISTDL_LAUNCH_CORR(2, kMaxPieces, kMaxBPieces);
-  else if (small) DISTDL_LAUNCH_CORR(1, 4, 3);
-  else DISTDL_LAUNCH_CORR(1, kMaxPieces, kMaxBPieces);
+  const int ntaps = a.nt[1] * a.nt[2];
+  if (mt == 2 && small && ntaps == 9) DISTDL_LAUNCH_CORR(2, 4, 3, 9);
+  else if (mt == 2 && small && ntaps == 6) DISTDL_LAUNCH_CORR(2, 4, 3, 6);
+  else if (mt == 2 && small && ntaps == 4) DISTDL_LAUNCH_CORR(2, 4, 3, 4);
+  else if (mt == 2 && small) DISTDL_LAUNCH_CORR(2, 4, 3, 0);
+  else if (mt == 2) DISTDL_LAUNCH_CORR(2, kMaxPieces, kMaxBPieces, 0);
+  else if (small) DISTDL_LAUNCH_CORR(1, 4, 3, 0);
+  else DISTDL_LAUNCH_CORR(1, kMaxPieces, kMaxBPieces, 0);
 #undef DISTDL_LAUNCH_CORR
   return DISTDL_OK;
 }
@@ -960,7 +1019,7 @@ static bool wgrad_rows_shape_ok(const distdl_plan* p) {
   return true;
 }
 
-// Output rows per work unit of the shared-rows kernel: whole planes when there are enough of them to
+// Output rows per work unit of the plane-per-workgroup kernel: whole planes when there are enough of them to
 // fill the chip, else blocks of rows (each block re-reads span - s1 rows to prime its ring).
 static int wgrad_row_block(const distdl_plan* p) {
   int64_t planes = 0, o1max = 1;
