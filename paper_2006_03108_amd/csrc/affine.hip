@@ -54,6 +54,8 @@ struct distdl_affine_plan {
   int32_t* d_sizes = nullptr;  // [P_fo fo sizes][P_fi fi sizes]
   distdl::DevArray<distdl::GemmBlock> g_fwd, g_dx, g_dw;
   distdl::DevArray<distdl::ColsumBlock> g_db;
+  float* d_partial = nullptr;  // fp32 partial tiles of K-split GEMM launches
+  size_t partial_floats = 0;
 };
 
 namespace distdl {
@@ -241,7 +243,18 @@ int distdl_affine_plan_destroy(distdl_affine_plan* p) {
   p->g_dx.release();
   p->g_dw.release();
   p->g_db.release();
+  if (p->d_partial) (void)hipFree(p->d_partial);
   delete p;
+  return DISTDL_OK;
+}
+
+static int ensure_partial(distdl_affine_plan* p, size_t floats) {
+  if (floats <= p->partial_floats) return DISTDL_OK;
+  if (p->d_partial) (void)hipFree(p->d_partial);
+  p->d_partial = nullptr;
+  p->partial_floats = 0;
+  DISTDL_HIP_TRY(hipMalloc((void**)&p->d_partial, floats * sizeof(float)));
+  p->partial_floats = floats;
   return DISTDL_OK;
 }
 
@@ -272,8 +285,9 @@ int distdl_affine_fwd(distdl_affine_plan* p, const void* const x_dev[], const vo
                            (int32_t)p->fi_size[j], 0};
     }
     if (gemm_mfma_usable(blocks, bf16, true, true)) {
-      if ((rc = p->g_fwd.upload(blocks, st_))) return rc;
-      launch_gemm_mfma(p->g_fwd.dev, blocks, bf16, true, true, "affine_fwd_mfma", st_);
+      const int ns = gemm_mfma_splits(blocks, bf16);
+      if ((rc = p->g_fwd.upload(blocks, st_)) || (rc = ensure_partial(p, gemm_mfma_partial_floats(blocks, ns)))) return rc;
+      if ((rc = launch_gemm_mfma(p->g_fwd.dev, blocks, bf16, true, true, ns, p->d_partial, "affine_fwd_mfma", st_))) return rc;
       DISTDL_HIP_TRY(hipGetLastError());
       return DISTDL_OK;
     }
@@ -329,9 +343,14 @@ int distdl_affine_bwd(distdl_affine_plan* p, const void* const x_dev[], const vo
       bb[i] = ColsumBlock{dy_dev[i], db_dev ? db_dev[i] : nullptr, (int32_t)p->n_b, (int32_t)p->fo_size[i]};
     }
     if (gemm_mfma_usable(bx, bf16, true, false) && gemm_mfma_usable(bw, bf16, false, false)) {
-      if ((rc = p->g_dx.upload(bx, st_)) || (rc = p->g_dw.upload(bw, st_))) return rc;
-      launch_gemm_mfma(p->g_dx.dev, bx, bf16, true, false, "affine_bwd_x_mfma", st_);
-      launch_gemm_mfma(p->g_dw.dev, bw, bf16, false, false, "affine_bwd_w_mfma", st_);
+      const int nsx = gemm_mfma_splits(bx, bf16), nsw = gemm_mfma_splits(bw, bf16);
+      if ((rc = p->g_dx.upload(bx, st_)) || (rc = p->g_dw.upload(bw, st_)) ||
+          (rc = ensure_partial(p, std::max(gemm_mfma_partial_floats(bx, nsx), gemm_mfma_partial_floats(bw, nsw)))))
+        return rc;
+      // the two launches use the partial buffer one after the other on the stream
+      if ((rc = launch_gemm_mfma(p->g_dx.dev, bx, bf16, true, false, nsx, p->d_partial, "affine_bwd_x_mfma", st_)) ||
+          (rc = launch_gemm_mfma(p->g_dw.dev, bw, bf16, false, false, nsw, p->d_partial, "affine_bwd_w_mfma", st_)))
+        return rc;
       if (db_dev) {
         if ((rc = p->g_db.upload(bb, st_))) return rc;
         launch_colsum(p->g_db.dev, p->P_fo, (int)p->max_fo, bf16, st_);

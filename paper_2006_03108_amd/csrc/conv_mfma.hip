@@ -178,13 +178,14 @@ __global__ __launch_bounds__(256, 2) void corr_mfma_kernel(const WorkerDev* __re
 
   const int* __restrict__ tapinfo = a.tapinfo;  // [0..7]: plane offsets, [8..]: patch offset per (t1, t2)
   const int ntaps = a.nt[1] * a.nt[2];
-  if (tid < ntaps) tap_tab[tid] = (uint32_t)tapinfo[8 + tid] * 16u;  // visible after the first barrier below
+  if (tid < ntaps + 4) tap_tab[tid] = tid < ntaps ? (uint32_t)tapinfo[8 + tid] * 16u : 0u;  // visible after the first barrier below
   const bool ragged = (a.kc & 7) != 0;
   char* const ldsb = (char*)lds;
 
   // A stage is one (output plane q0, tap plane t0, 8-channel chunk cc); stages whose input plane lies
   // outside the input contribute zero and are skipped.
-  auto plane_of = [&](int q0, int t0) { return g.in_base[0] + q0 * a.is[0] + tapinfo[t0]; };
+  // (the table entry is the same for all lanes: saying so keeps the stage base offsets in scalar registers)
+  auto plane_of = [&](int q0, int t0) { return g.in_base[0] + q0 * a.is[0] + __builtin_amdgcn_readfirstlane(tapinfo[t0]); };
   auto advance = [&](int& q0, int& t0, int& cc) {  // next valid stage after (q0, t0, cc), or q0 == q0_end
     if (++cc < ncc) return;  // same plane, next chunk
     cc = 0;
@@ -233,17 +234,17 @@ __global__ __launch_bounds__(256, 2) void corr_mfma_kernel(const WorkerDev* __re
       for (int mt = 0; mt < MT; ++mt) aaddr[mt][t] = abase[mt] + tapo;
     }
   }
-  auto read_ops = [&](int tap, float4& b, float4 (&av)[MT]) {
-    const char* lb = ldsb;
+  // tapo: byte offset of the tap inside the patch (NT == 0: read from the LDS table two taps ahead of
+  // its use, so that the table read is never waited for)
+  auto read_ops = [&](int tap, uint32_t tapo, float4& b, float4 (&av)[MT]) {
     if constexpr (NT > 0) {
-      b = *(const float4*)(lb + bread + tap * 1024);
+      b = *(const float4*)(ldsb + bread + tap * 1024);
 #pragma unroll
-      for (int mt = 0; mt < MT; ++mt) av[mt] = *(const float4*)(lb + aaddr[mt][tap]);
+      for (int mt = 0; mt < MT; ++mt) av[mt] = *(const float4*)(ldsb + aaddr[mt][tap]);
     } else {
-      const uint32_t tapo = tap_tab[tap];
-      b = *(const float4*)(lb + bread + tap * 1024);
+      b = *(const float4*)(ldsb + bread + tap * 1024);
 #pragma unroll
-      for (int mt = 0; mt < MT; ++mt) av[mt] = *(const float4*)(lb + abase[mt] + tapo);
+      for (int mt = 0; mt < MT; ++mt) av[mt] = *(const float4*)(ldsb + abase[mt] + tapo);
     }
   };
   auto multiply = [&](floatx16 (&acc)[MT], const float4& b, const float4 (&av)[MT]) {
@@ -262,28 +263,33 @@ __global__ __launch_bounds__(256, 2) void corr_mfma_kernel(const WorkerDev* __re
   // compiler from sinking the LDS reads down to their first use, which would expose their latency.
   auto compute = [&](floatx16 (&acc)[MT]) {
     float4 b0, b1, a0[MT], a1[MT];
-    read_ops(0, b0, a0);
     if constexpr (NT > 0) {
+      read_ops(0, 0, b0, a0);
 #pragma unroll
       for (int tap = 0; tap + 1 < NT; tap += 2) {
-        read_ops(tap + 1, b1, a1);
+        read_ops(tap + 1, 0, b1, a1);
         __builtin_amdgcn_sched_barrier(0);
         multiply(acc, b0, a0);
         __builtin_amdgcn_sched_barrier(0);
-        if (tap + 2 < NT) read_ops(tap + 2, b0, a0);
+        if (tap + 2 < NT) read_ops(tap + 2, 0, b0, a0);
         __builtin_amdgcn_sched_barrier(0);
         multiply(acc, b1, a1);
         __builtin_amdgcn_sched_barrier(0);
       }
       if (NT & 1) multiply(acc, b0, a0);
     } else {
+      // tap_tab has two spare entries behind the last tap, so the look-ahead reads stay in the table
+      uint32_t o1 = tap_tab[1], o2 = tap_tab[2];
+      read_ops(0, tap_tab[0], b0, a0);
       int tap = 0;
       for (; tap + 1 < ntaps; tap += 2) {
-        read_ops(tap + 1, b1, a1);
+        read_ops(tap + 1, o1, b1, a1);
+        o1 = tap_tab[tap + 3];
         __builtin_amdgcn_sched_barrier(0);
         multiply(acc, b0, a0);
         __builtin_amdgcn_sched_barrier(0);
-        if (tap + 2 < ntaps) read_ops(tap + 2, b0, a0);
+        if (tap + 2 < ntaps) read_ops(tap + 2, o2, b0, a0);
+        o2 = tap_tab[tap + 4];
         __builtin_amdgcn_sched_barrier(0);
         multiply(acc, b1, a1);
         __builtin_amdgcn_sched_barrier(0);
@@ -774,7 +780,7 @@ __global__ __launch_bounds__(256) void bias_partial_kernel(const WorkerDev* __re
 
 // ---- host side ------------------------------------------------------------------
 
-static int lds_bytes(const CorrArgs& a) { return (a.a_vec4 + a.nt[1] * a.nt[2] * 64 + 1) * 16 + a.nt[1] * a.nt[2] * 4; }
+static int lds_bytes(const CorrArgs& a) { return (a.a_vec4 + a.nt[1] * a.nt[2] * 64 + 1) * 16 + (a.nt[1] * a.nt[2] + 4) * 4; }
 
 static void finish_args(CorrArgs& a, int mt, int nq2max) {
   // window of 128*mt positions: full output rows when they fit, else 32-multiples

@@ -31,8 +31,12 @@ struct ColsumBlock {
 // True when every operand can be moved in aligned 16-byte pieces (the MFMA kernel's requirement).
 bool gemm_mfma_usable(const std::vector<GemmBlock>& blocks, bool bf16, bool a_kc, bool b_kc);
 // a_kc: A[m][k] is contiguous along k (else along m); b_kc: B[k][n] is contiguous along k (else along n).
+// nsplit > 1: K split over nsplit workgroups per tile through the fp32 buffer `partial`
+// (gemm_mfma_partial_floats(blocks, nsplit) floats), summed by a second kernel.
+int gemm_mfma_splits(const std::vector<GemmBlock>& blocks, bool bf16);
+size_t gemm_mfma_partial_floats(const std::vector<GemmBlock>& blocks, int nsplit);
 int launch_gemm_mfma(const GemmBlock* d_blocks, const std::vector<GemmBlock>& blocks, bool bf16, bool a_kc, bool b_kc,
-                     const char* name, hipStream_t st);
+                     int nsplit, float* partial, const char* name, hipStream_t st);
 int launch_colsum(const ColsumBlock* d_blocks, int nblocks, int max_f, bool bf16, hipStream_t st);
 
 }  // namespace distdl

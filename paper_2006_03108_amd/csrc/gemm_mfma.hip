@@ -9,7 +9,7 @@
 // Operands are addressed by (pointer, leading dimension, which index is contiguous):
 //   A "K-contiguous":  A[m][k] at a[m*lda + k];   "M-contiguous": a[k*lda + m]
 //   B "K-contiguous":  B[k][n] at b[n*ldb + k];   "N-contiguous": b[k*ldb + n]
-// Tiles are 64 x 64 per workgroup (4 waves, one 32 x 32 MFMA tile each), staged through LDS with
+// Tiles are 64 x 64 or 128 x 128 per workgroup (4 waves, 1 or 2 x 2 MFMA tiles of 32 x 32 each), staged through LDS with
 // 16-byte buffer loads (rows beyond the matrix fail the range check and read as zero), double
 // buffered: one barrier per stage.
 //
@@ -44,37 +44,52 @@ __device__ inline uint32_t f32_to_bf16_rne(float f) {
 }
 
 // BF16 = false: T is float, BK = 32 floats per stage.  BF16 = true: T is bf16 bits, BK = 64 per stage.
-// Row pitch in LDS is BK + 16 bytes for the K-contiguous layout, 64 elements + 16 bytes for the other.
-template <bool BF16, bool A_KC, bool B_KC>
-__global__ __launch_bounds__(256) void gemm_mfma_kernel(const GemmBlock* __restrict__ blocks, int tiles_n_max) {
+// TM x TN: 32 x 32 MFMA tiles per wave; the workgroup tile is 64*TM x 64*TN (4 waves, 2 x 2).
+// Row pitch in LDS is BK + 16 bytes for the K-contiguous layout, tile extent + 16 bytes for the other.
+//
+// nsplit > 1 (grid.y): the K stages of every segment are dealt to nsplit workgroups per tile, each of which
+// writes its fp32 partial tile to `partial` ([block][split][M][N]); gemm_reduce_kernel then sums the splits
+// in ascending order, adds the bias and rounds.  This is the sum-reduce R of the layer left un-fused: with a
+// small batch a launch has too few tiles to fill the chip, and the splits supply the missing workgroups.
+template <bool BF16, bool A_KC, bool B_KC, int TM, int TN>
+__global__ __launch_bounds__(256) void gemm_mfma_kernel(const GemmBlock* __restrict__ blocks, float* __restrict__ partial,
+                                                        int64_t partial_stride) {
   constexpr int ES = BF16 ? 2 : 4;             // element size
   constexpr int BK = BF16 ? 64 : 32;           // k per stage
   constexpr int VE = 16 / ES;                  // elements per 16-byte piece
+  constexpr int TILE_M = 64 * TM, TILE_N = 64 * TN;
   constexpr int PITCH_KC = BK * ES + 16;       // bytes per tile row, K-contiguous staging [row][k]
-  constexpr int PITCH_TC = 64 * ES + 16;       // bytes per k line, transposed staging [k][row]
-  constexpr int TILE_BYTES = (64 * PITCH_KC > BK * PITCH_TC) ? 64 * PITCH_KC : BK * PITCH_TC;
-  constexpr int PIECES = 64 * BK * ES / 16 / 256;  // 16-byte pieces per thread, operand and stage
-  __shared__ __attribute__((aligned(16))) char smem[4 * TILE_BYTES];  // A0 B0 A1 B1
+  constexpr int PITCH_TA = TILE_M * ES + 16;   // bytes per k line, transposed staging [k][row]
+  constexpr int PITCH_TB = TILE_N * ES + 16;
+  constexpr int A_BYTES = A_KC ? TILE_M * PITCH_KC : BK * PITCH_TA;
+  constexpr int B_BYTES = B_KC ? TILE_N * PITCH_KC : BK * PITCH_TB;
+  constexpr int PA = TILE_M * BK * ES / 16 / 256;  // 16-byte pieces per thread and stage
+  constexpr int PB = TILE_N * BK * ES / 16 / 256;
+  extern __shared__ __attribute__((aligned(16))) char smem[];  // A0 B0 A1 B1
 
   const GemmBlock& gb = blocks[blockIdx.z];
-  const int tiles_n = (gb.N + 63) / 64, tiles_m = (gb.M + 63) / 64;
+  const int tiles_n = (gb.N + TILE_N - 1) / TILE_N, tiles_m = (gb.M + TILE_M - 1) / TILE_M;
   // consecutive tiles share the B tile (weights: m walks fastest); workgroups are dealt to the 8 XCDs
   // round-robin, so give each XCD a contiguous range of tiles and keep that sharing behind one L2
   const int tile = (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
   if (tile >= tiles_m * tiles_n) return;
   const int tm = tile % tiles_m, tn = tile / tiles_m;
-  const int m0 = tm * 64, n0 = tn * 64;
+  const int m0 = tm * TILE_M, n0 = tn * TILE_N;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, h = lane >> 5, ml = lane & 31;
   const int wy = wave >> 1, wx = wave & 1;
 
-  floatx16 acc;
-  for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+  floatx16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
   // piece -> (row or k line, 16-byte column) of this thread, fixed
-  //   K-contiguous: 64 rows x (BK/VE) pieces per row; transposed: BK lines x (64/VE) pieces per line
-  u32x4 ra[PIECES], rb[PIECES];
-  uint32_t a_goff[PIECES], b_goff[PIECES], a_loff[PIECES], b_loff[PIECES];
-  int a_k[PIECES], b_k[PIECES];  // k of the piece's first element (to cut the K tail)
+  //   K-contiguous: rows x (BK/VE) pieces per row; transposed: BK lines x (rows/VE) pieces per line
+  u32x4 ra[PA], rb[PB];
+  uint32_t a_goff[PA], b_goff[PB], a_loff[PA], b_loff[PB];
+  int a_k[PA], b_k[PB];  // k of the piece's first element (to cut the K tail)
 
   for (int s = 0; s < gb.nseg; ++s) {
     const GemmSeg& sg = gb.seg[s];
@@ -84,7 +99,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(const GemmBlock* __restr
     const uint32_t b_bytes = (uint32_t)(B_KC ? gb.N : K) * sg.ldb * ES;
     const __amdgpu_buffer_rsrc_t ra_rs = gemm_rsrc(sg.a, a_bytes), rb_rs = gemm_rsrc(sg.b, b_bytes);
 #pragma unroll
-    for (int i = 0; i < PIECES; ++i) {
+    for (int i = 0; i < PA; ++i) {
       const int piece = tid + i * 256;
       if (A_KC) {
         const int row = piece / (BK / VE), kq = piece % (BK / VE);
@@ -92,21 +107,25 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(const GemmBlock* __restr
         a_loff[i] = row * PITCH_KC + kq * 16;
         a_k[i] = kq * VE;
       } else {
-        const int kl = piece / (64 / VE), mq = piece % (64 / VE);
+        const int kl = piece / (TILE_M / VE), mq = piece % (TILE_M / VE);
         a_goff[i] = ((uint32_t)kl * sg.lda + m0 + mq * VE) * ES;
-        a_loff[i] = kl * PITCH_TC + mq * 16;
+        a_loff[i] = kl * PITCH_TA + mq * 16;
         a_k[i] = kl;
         if (m0 + mq * VE >= gb.M) a_goff[i] = kGemmOob;  // columns beyond M (whole pieces: M % VE == 0)
       }
+    }
+#pragma unroll
+    for (int i = 0; i < PB; ++i) {
+      const int piece = tid + i * 256;
       if (B_KC) {
         const int row = piece / (BK / VE), kq = piece % (BK / VE);
         b_goff[i] = ((uint32_t)(n0 + row) * sg.ldb + kq * VE) * ES;
         b_loff[i] = row * PITCH_KC + kq * 16;
         b_k[i] = kq * VE;
       } else {
-        const int kl = piece / (64 / VE), nq = piece % (64 / VE);
+        const int kl = piece / (TILE_N / VE), nq = piece % (TILE_N / VE);
         b_goff[i] = ((uint32_t)kl * sg.ldb + n0 + nq * VE) * ES;
-        b_loff[i] = kl * PITCH_TC + nq * 16;
+        b_loff[i] = kl * PITCH_TB + nq * 16;
         b_k[i] = kl;
         if (n0 + nq * VE >= gb.N) b_goff[i] = kGemmOob;
       }
@@ -114,106 +133,235 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(const GemmBlock* __restr
     auto load = [&](int k0) {
       const uint32_t a_base = (uint32_t)k0 * (A_KC ? 1u : sg.lda) * ES;
       const uint32_t b_base = (uint32_t)k0 * (B_KC ? 1u : sg.ldb) * ES;
+      // K tail: pieces are whole (K % VE == 0 for K-contiguous operands), lines beyond K fail the range check
 #pragma unroll
-      for (int i = 0; i < PIECES; ++i) {
-        // K tail: pieces are whole (K % VE == 0 for K-contiguous operands), lines beyond K fail the range check
+      for (int i = 0; i < PA; ++i)
         ra[i] = __builtin_amdgcn_raw_buffer_load_b128(ra_rs, (A_KC && k0 + a_k[i] >= K) ? kGemmOob : a_goff[i], a_base, 0);
+#pragma unroll
+      for (int i = 0; i < PB; ++i)
         rb[i] = __builtin_amdgcn_raw_buffer_load_b128(rb_rs, (B_KC && k0 + b_k[i] >= K) ? kGemmOob : b_goff[i], b_base, 0);
-      }
     };
     auto stash = [&](int buf) {
-      char* sa = smem + buf * 2 * TILE_BYTES;
-      char* sb = sa + TILE_BYTES;
+      char* sa = smem + buf * (A_BYTES + B_BYTES);
+      char* sb = sa + A_BYTES;
 #pragma unroll
-      for (int i = 0; i < PIECES; ++i) {
-        *(u32x4*)(sa + a_loff[i]) = ra[i];
-        *(u32x4*)(sb + b_loff[i]) = rb[i];
-      }
+      for (int i = 0; i < PA; ++i) *(u32x4*)(sa + a_loff[i]) = ra[i];
+#pragma unroll
+      for (int i = 0; i < PB; ++i) *(u32x4*)(sb + b_loff[i]) = rb[i];
     };
-    const int nstage = (K + BK - 1) / BK;
-    load(0);
+    const int nstage_all = (K + BK - 1) / BK;
+    // this workgroup's share of the segment's stages
+    const int st_first = (int)((int64_t)nstage_all * blockIdx.y / gridDim.y);
+    const int nstage = (int)((int64_t)nstage_all * (blockIdx.y + 1) / gridDim.y) - st_first;
+    if (nstage == 0) continue;
+    load(st_first * BK);
     __syncthreads();  // previous segment's last stage fully consumed
     stash(0);
     __syncthreads();
     for (int st = 0; st < nstage; ++st) {
-      if (st + 1 < nstage) load((st + 1) * BK);
-      const char* sa = smem + (st & 1) * 2 * TILE_BYTES;
-      const char* sb = sa + TILE_BYTES;
-      if (!BF16) {
+      if (st + 1 < nstage) load((st_first + st + 1) * BK);
+      const char* sa = smem + (st & 1) * (A_BYTES + B_BYTES);
+      const char* sb = sa + A_BYTES;
+      // The LDS reads of k group g + 1 are issued before the MFMAs of group g; the scheduling barriers
+      // pin that order (left alone, the compiler sinks the reads to their first use and the LDS latency
+      // is paid once per group).
+      if constexpr (!BF16) {
+        auto rd = [&](int kk, float (&av)[TM][4], float (&bv)[TN][4]) {
 #pragma unroll
-        for (int kk = 0; kk < BK; kk += 8) {
-          float av[4], bv[4];
-          if (A_KC) {
-            const float4 t = *(const float4*)(sa + (32 * wy + ml) * PITCH_KC + (kk + 4 * h) * 4);
-            av[0] = t.x; av[1] = t.y; av[2] = t.z; av[3] = t.w;
-          } else {
+          for (int i = 0; i < TM; ++i) {
+            const int row = 32 * (wy * TM + i) + ml;
+            if (A_KC) {
+              const float4 t = *(const float4*)(sa + row * PITCH_KC + (kk + 4 * h) * 4);
+              av[i][0] = t.x; av[i][1] = t.y; av[i][2] = t.z; av[i][3] = t.w;
+            } else {
 #pragma unroll
-            for (int j = 0; j < 4; ++j) av[j] = *(const float*)(sa + (kk + 4 * h + j) * PITCH_TC + (32 * wy + ml) * 4);
-          }
-          if (B_KC) {
-            const float4 t = *(const float4*)(sb + (32 * wx + ml) * PITCH_KC + (kk + 4 * h) * 4);
-            bv[0] = t.x; bv[1] = t.y; bv[2] = t.z; bv[3] = t.w;
-          } else {
-#pragma unroll
-            for (int j = 0; j < 4; ++j) bv[j] = *(const float*)(sb + (kk + 4 * h + j) * PITCH_TC + (32 * wx + ml) * 4);
+              for (int j = 0; j < 4; ++j) av[i][j] = *(const float*)(sa + (kk + 4 * h + j) * PITCH_TA + row * 4);
+            }
           }
 #pragma unroll
-          for (int j = 0; j < 4; ++j) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av[j], bv[j], acc, 0, 0, 0);
-        }
+          for (int i = 0; i < TN; ++i) {
+            const int row = 32 * (wx * TN + i) + ml;
+            if (B_KC) {
+              const float4 t = *(const float4*)(sb + row * PITCH_KC + (kk + 4 * h) * 4);
+              bv[i][0] = t.x; bv[i][1] = t.y; bv[i][2] = t.z; bv[i][3] = t.w;
+            } else {
+#pragma unroll
+              for (int j = 0; j < 4; ++j) bv[i][j] = *(const float*)(sb + (kk + 4 * h + j) * PITCH_TB + row * 4);
+            }
+          }
+        };
+        auto mm = [&](const float (&av)[TM][4], const float (&bv)[TN][4]) {
+#pragma unroll
+          for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int im = 0; im < TM; ++im)
+#pragma unroll
+              for (int in = 0; in < TN; ++in)
+                acc[im][in] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[im][j], bv[in][j], acc[im][in], 0, 0, 0);
+        };
+        float a0[TM][4], b0[TN][4], a1[TM][4], b1[TN][4];
+        static_assert(BK == 32, "four k groups of 8 per stage");
+        rd(0, a0, b0);
+        rd(8, a1, b1);
+        __builtin_amdgcn_sched_barrier(0);
+        mm(a0, b0);
+        __builtin_amdgcn_sched_barrier(0);
+        rd(16, a0, b0);
+        __builtin_amdgcn_sched_barrier(0);
+        mm(a1, b1);
+        __builtin_amdgcn_sched_barrier(0);
+        rd(24, a1, b1);
+        __builtin_amdgcn_sched_barrier(0);
+        mm(a0, b0);
+        __builtin_amdgcn_sched_barrier(0);
+        mm(a1, b1);
       } else {
+        union Frag { u32x4 u; bf16x8 v; uint16_t e[8]; };
+        auto rd = [&](int kk, Frag (&av)[TM], Frag (&bv)[TN]) {
 #pragma unroll
-        for (int kk = 0; kk < BK; kk += 16) {
-          union { u32x4 u; bf16x8 v; uint16_t e[8]; } av, bv;
-          if (A_KC) {
-            av.u = *(const u32x4*)(sa + (32 * wy + ml) * PITCH_KC + (kk + 8 * h) * 2);
-          } else {
+          for (int i = 0; i < TM; ++i) {
+            const int row = 32 * (wy * TM + i) + ml;
+            if (A_KC) {
+              av[i].u = *(const u32x4*)(sa + row * PITCH_KC + (kk + 8 * h) * 2);
+            } else {
 #pragma unroll
-            for (int j = 0; j < 8; ++j) av.e[j] = *(const uint16_t*)(sa + (kk + 8 * h + j) * PITCH_TC + (32 * wy + ml) * 2);
+              for (int j = 0; j < 8; ++j) av[i].e[j] = *(const uint16_t*)(sa + (kk + 8 * h + j) * PITCH_TA + row * 2);
+            }
           }
-          if (B_KC) {
-            bv.u = *(const u32x4*)(sb + (32 * wx + ml) * PITCH_KC + (kk + 8 * h) * 2);
-          } else {
 #pragma unroll
-            for (int j = 0; j < 8; ++j) bv.e[j] = *(const uint16_t*)(sb + (kk + 8 * h + j) * PITCH_TC + (32 * wx + ml) * 2);
+          for (int i = 0; i < TN; ++i) {
+            const int row = 32 * (wx * TN + i) + ml;
+            if (B_KC) {
+              bv[i].u = *(const u32x4*)(sb + row * PITCH_KC + (kk + 8 * h) * 2);
+            } else {
+#pragma unroll
+              for (int j = 0; j < 8; ++j) bv[i].e[j] = *(const uint16_t*)(sb + (kk + 8 * h + j) * PITCH_TB + row * 2);
+            }
           }
-          acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av.v, bv.v, acc, 0, 0, 0);
-        }
+        };
+        auto mm = [&](const Frag (&av)[TM], const Frag (&bv)[TN]) {
+#pragma unroll
+          for (int im = 0; im < TM; ++im)
+#pragma unroll
+            for (int in = 0; in < TN; ++in)
+              acc[im][in] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[im].v, bv[in].v, acc[im][in], 0, 0, 0);
+        };
+        Frag a0[TM], b0[TN], a1[TM], b1[TN];
+        static_assert(BK == 64 || !BF16, "four k groups of 16 per stage");
+        rd(0, a0, b0);
+        rd(16, a1, b1);
+        __builtin_amdgcn_sched_barrier(0);
+        mm(a0, b0);
+        __builtin_amdgcn_sched_barrier(0);
+        rd(32, a0, b0);
+        __builtin_amdgcn_sched_barrier(0);
+        mm(a1, b1);
+        __builtin_amdgcn_sched_barrier(0);
+        rd(48, a1, b1);
+        __builtin_amdgcn_sched_barrier(0);
+        mm(a0, b0);
+        __builtin_amdgcn_sched_barrier(0);
+        mm(a1, b1);
       }
       if (st + 1 < nstage) stash((st + 1) & 1);
       __syncthreads();
     }
   }
 
-  // epilogue: D register v of lane (h, ml) is C[m0 + 32*wy + 8*(v/4) + 4*h + v%4][n0 + 32*wx + ml]
-  const int col = n0 + 32 * wx + ml;
-  if (col >= gb.N) return;
-  float bias = 0.f;
-  if (gb.bias) bias = BF16 ? __uint_as_float((uint32_t)((const uint16_t*)gb.bias)[col] << 16) : ((const float*)gb.bias)[col];
+  // epilogue: D register v of lane (h, ml) of MFMA tile (im, in) is
+  //   C[m0 + 32*(wy*TM + im) + 8*(v/4) + 4*h + v%4][n0 + 32*(wx*TN + in) + ml]
+  float* pc = nullptr;
+  if (gridDim.y > 1) pc = partial + ((size_t)blockIdx.z * gridDim.y + blockIdx.y) * partial_stride;
 #pragma unroll
-  for (int v = 0; v < 16; ++v) {
-    const int row = m0 + 32 * wy + 8 * (v / 4) + 4 * h + (v % 4);
-    if (row >= gb.M) continue;
-    const float r = acc[v] + bias;
-    if (BF16) ((uint16_t*)gb.c)[(size_t)row * gb.ldc + col] = (uint16_t)f32_to_bf16_rne(r);
-    else ((float*)gb.c)[(size_t)row * gb.ldc + col] = r;
+  for (int in = 0; in < TN; ++in) {
+    const int col = n0 + 32 * (wx * TN + in) + ml;
+    if (col >= gb.N) continue;
+    float bias = 0.f;
+    if (!pc && gb.bias)
+      bias = BF16 ? __uint_as_float((uint32_t)((const uint16_t*)gb.bias)[col] << 16) : ((const float*)gb.bias)[col];
+#pragma unroll
+    for (int im = 0; im < TM; ++im) {
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int row = m0 + 32 * (wy * TM + im) + 8 * (v / 4) + 4 * h + (v % 4);
+        if (row >= gb.M) continue;
+        if (pc) {  // fp32 partial of this split
+          pc[(size_t)row * gb.N + col] = acc[im][in][v];
+          continue;
+        }
+        const float r = acc[im][in][v] + bias;
+        if (BF16) ((uint16_t*)gb.c)[(size_t)row * gb.ldc + col] = (uint16_t)f32_to_bf16_rne(r);
+        else ((float*)gb.c)[(size_t)row * gb.ldc + col] = r;
+      }
+    }
   }
 }
 
-// db_i[f] = sum over the batch of dy_i[n][f]: one block per 64 features, 4 batch lanes each.
+// C_o = sum over the splits (ascending) of the fp32 partials + bias, rounded to the output type.
+// grid: (ceil(max M*N / 4 / 256), blocks); M*N is a multiple of 4 whenever the MFMA path is used.
+template <bool BF16>
+__global__ __launch_bounds__(256) void gemm_reduce_kernel(const GemmBlock* __restrict__ blocks,
+                                                          const float* __restrict__ partial, int64_t partial_stride,
+                                                          int nsplit) {
+  const GemmBlock& gb = blocks[blockIdx.y];
+  const int64_t q = (int64_t)blockIdx.x * 256 + threadIdx.x;  // group of 4 consecutive elements
+  const int64_t e = q * 4;
+  if (e >= (int64_t)gb.M * gb.N) return;
+  const int row = (int)(e / gb.N), col = (int)(e - (int64_t)row * gb.N);  // N % 4 == 0: a group stays in one row
+  const float* pp = partial + (size_t)blockIdx.y * nsplit * partial_stride + e;
+  float4 acc = *(const float4*)pp;
+  for (int s = 1; s < nsplit; ++s) {
+    const float4 t = *(const float4*)(pp + (size_t)s * partial_stride);
+    acc.x += t.x; acc.y += t.y; acc.z += t.z; acc.w += t.w;
+  }
+  if (gb.bias) {
+    if (BF16) {
+      const uint16_t* b = (const uint16_t*)gb.bias + col;
+      acc.x += __uint_as_float((uint32_t)b[0] << 16); acc.y += __uint_as_float((uint32_t)b[1] << 16);
+      acc.z += __uint_as_float((uint32_t)b[2] << 16); acc.w += __uint_as_float((uint32_t)b[3] << 16);
+    } else {
+      const float* b = (const float*)gb.bias + col;
+      acc.x += b[0]; acc.y += b[1]; acc.z += b[2]; acc.w += b[3];
+    }
+  }
+  if (BF16) {
+    uint16_t* c = (uint16_t*)gb.c + (size_t)row * gb.ldc + col;
+    c[0] = (uint16_t)f32_to_bf16_rne(acc.x); c[1] = (uint16_t)f32_to_bf16_rne(acc.y);
+    c[2] = (uint16_t)f32_to_bf16_rne(acc.z); c[3] = (uint16_t)f32_to_bf16_rne(acc.w);
+  } else {
+    float* c = (float*)gb.c + (size_t)row * gb.ldc + col;
+    c[0] = acc.x; c[1] = acc.y; c[2] = acc.z; c[3] = acc.w;
+  }
+}
+
+// db_i[f] = sum over the batch of dy_i[n][f]: one block per 16 features, 16 batch lanes each (many small
+// blocks: the matrix is short and wide, so the parallelism has to come from the feature axis).
 template <bool BF16>
 __global__ __launch_bounds__(256) void colsum_kernel(const ColsumBlock* __restrict__ blocks) {
   const ColsumBlock& cb = blocks[blockIdx.y];
-  const int f = blockIdx.x * 64 + (threadIdx.x & 63), lanegrp = threadIdx.x >> 6;
-  __shared__ float red[4][64];
+  const int fl = threadIdx.x & 15, lanegrp = threadIdx.x >> 4;
+  const int f = blockIdx.x * 16 + fl;
+  __shared__ float red[16][17];
   float acc = 0.f;
-  if (f < cb.n_f && cb.out)
-    for (int n = lanegrp; n < cb.n_b; n += 4)
-      acc += BF16 ? __uint_as_float((uint32_t)((const uint16_t*)cb.in)[(size_t)n * cb.n_f + f] << 16)
-                  : ((const float*)cb.in)[(size_t)n * cb.n_f + f];
-  red[lanegrp][threadIdx.x & 63] = acc;
+  if (f < cb.n_f && cb.out) {
+    float part[4] = {0.f, 0.f, 0.f, 0.f};
+    int n = lanegrp;
+    for (; n + 48 < cb.n_b; n += 64)
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+        part[u] += BF16 ? __uint_as_float((uint32_t)((const uint16_t*)cb.in)[(size_t)(n + 16 * u) * cb.n_f + f] << 16)
+                        : ((const float*)cb.in)[(size_t)(n + 16 * u) * cb.n_f + f];
+    for (; n < cb.n_b; n += 16)
+      part[0] += BF16 ? __uint_as_float((uint32_t)((const uint16_t*)cb.in)[(size_t)n * cb.n_f + f] << 16)
+                      : ((const float*)cb.in)[(size_t)n * cb.n_f + f];
+    acc = (part[0] + part[1]) + (part[2] + part[3]);
+  }
+  red[lanegrp][fl] = acc;
   __syncthreads();
   if (lanegrp == 0 && f < cb.n_f && cb.out) {
-    const float s = (red[0][threadIdx.x] + red[1][threadIdx.x]) + (red[2][threadIdx.x] + red[3][threadIdx.x]);
+    float s = 0.f;
+#pragma unroll
+    for (int g = 0; g < 16; ++g) s += red[g][fl];
     if (BF16) ((uint16_t*)cb.out)[f] = (uint16_t)f32_to_bf16_rne(s);
     else ((float*)cb.out)[f] = s;
   }
@@ -241,14 +389,76 @@ bool gemm_mfma_usable(const std::vector<GemmBlock>& blocks, bool bf16, bool a_kc
   return true;
 }
 
+// 128 x 128 workgroup tiles (2 x 2 MFMA tiles per wave) when every block is at least that large.
+static bool gemm_big_tiles(const std::vector<GemmBlock>& blocks) {
+  for (const GemmBlock& b : blocks)
+    if (b.M < 128 || b.N < 128) return false;
+  return !blocks.empty();
+}
+
+// Number of K splits for a launch: enough workgroups for about two (large tiles) or four per compute unit,
+// every split at least four stages long, at most 8.
+int gemm_mfma_splits(const std::vector<GemmBlock>& blocks, bool bf16) {
+  const int bk = bf16 ? 64 : 32;
+  const int t = gemm_big_tiles(blocks) ? 128 : 64;
+  int64_t tiles = 0, macs = 0;
+  int min_stages = INT32_MAX;
+  for (const GemmBlock& b : blocks) {
+    tiles += (int64_t)((b.M + t - 1) / t) * ((b.N + t - 1) / t);
+    int stages = 0;
+    for (int s = 0; s < b.nseg; ++s) {
+      stages += (b.seg[s].K + bk - 1) / bk;
+      macs += (int64_t)b.M * b.N * b.seg[s].K;
+    }
+    min_stages = std::min(min_stages, stages);
+    if (b.N % 4) return 1;  // the reduction works on groups of 4 elements of a row
+  }
+  const int64_t target = t == 128 ? 512 : 1024;
+  if (tiles == 0 || tiles >= target * 3 / 4) return 1;
+  if (macs < (int64_t(1) << 28)) return 1;  // a launch this small is latency-bound either way: no second kernel
+  int64_t want = (target + tiles - 1) / tiles;
+  want = std::min<int64_t>(want, std::max(1, min_stages / 4));
+  return (int)std::max<int64_t>(1, std::min<int64_t>(want, 8));
+}
+
+size_t gemm_mfma_partial_floats(const std::vector<GemmBlock>& blocks, int nsplit) {
+  if (nsplit <= 1) return 0;
+  int64_t mx = 0;
+  for (const GemmBlock& b : blocks) mx = std::max<int64_t>(mx, (int64_t)b.M * b.N);
+  return (size_t)mx * nsplit * blocks.size();
+}
+
+template <bool BF16, bool A_KC, bool B_KC, int T>
+static int launch_gemm_variant(dim3 grid, const GemmBlock* d_blocks, float* partial, int64_t max_mn, hipStream_t st) {
+  constexpr int ES = BF16 ? 2 : 4, BK = BF16 ? 64 : 32, TILE = 64 * T;
+  constexpr int A_BYTES = A_KC ? TILE * (BK * ES + 16) : BK * (TILE * ES + 16);
+  constexpr int B_BYTES = B_KC ? TILE * (BK * ES + 16) : BK * (TILE * ES + 16);
+  constexpr int LDS = 2 * (A_BYTES + B_BYTES);
+  if (LDS > 64 * 1024)
+    DISTDL_HIP_TRY(hipFuncSetAttribute((const void*)gemm_mfma_kernel<BF16, A_KC, B_KC, T, T>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, LDS));
+  hipLaunchKernelGGL((gemm_mfma_kernel<BF16, A_KC, B_KC, T, T>), grid, dim3(256), LDS, st, d_blocks, partial, max_mn);
+  return DISTDL_OK;
+}
+
 int launch_gemm_mfma(const GemmBlock* d_blocks, const std::vector<GemmBlock>& blocks, bool bf16, bool a_kc, bool b_kc,
-                     const char* name, hipStream_t st) {
+                     int nsplit, float* partial, const char* name, hipStream_t st) {
+  const bool big = gemm_big_tiles(blocks);
+  const int t = big ? 128 : 64;
   int tiles = 0;
-  for (const GemmBlock& b : blocks) tiles = std::max(tiles, ((b.M + 63) / 64) * ((b.N + 63) / 64));
+  int64_t max_mn = 0;
+  for (const GemmBlock& b : blocks) {
+    tiles = std::max(tiles, ((b.M + t - 1) / t) * ((b.N + t - 1) / t));
+    max_mn = std::max<int64_t>(max_mn, (int64_t)b.M * b.N);
+  }
   tiles = (tiles + 7) / 8 * 8;
-  dim3 grid((unsigned)tiles, 1, (unsigned)blocks.size()), block(256);
+  if (nsplit > 1 && !partial) return set_error(DISTDL_ERR_INVALID_ARG, "gemm: split launch without a partial buffer");
+  dim3 grid((unsigned)tiles, (unsigned)std::max(nsplit, 1), (unsigned)blocks.size()), block(256);
   ProfScope prof(name, st);
-#define DISTDL_GEMM(BF_, A_, B_) hipLaunchKernelGGL((gemm_mfma_kernel<BF_, A_, B_>), grid, block, 0, st, d_blocks, 0)
+  int rc;
+#define DISTDL_GEMM(BF_, A_, B_)                                                                \
+  rc = big ? launch_gemm_variant<BF_, A_, B_, 2>(grid, d_blocks, partial, max_mn, st)           \
+           : launch_gemm_variant<BF_, A_, B_, 1>(grid, d_blocks, partial, max_mn, st)
   if (!bf16) {
     if (a_kc && b_kc) DISTDL_GEMM(false, true, true);
     else if (a_kc) DISTDL_GEMM(false, true, false);
@@ -261,11 +471,17 @@ int launch_gemm_mfma(const GemmBlock* d_blocks, const std::vector<GemmBlock>& bl
     else DISTDL_GEMM(true, false, false);
   }
 #undef DISTDL_GEMM
+  if (rc) return rc;
+  if (nsplit > 1) {
+    dim3 rgrid((unsigned)((max_mn / 4 + 255) / 256), (unsigned)blocks.size());
+    if (bf16) hipLaunchKernelGGL(gemm_reduce_kernel<true>, rgrid, block, 0, st, d_blocks, partial, max_mn, nsplit);
+    else hipLaunchKernelGGL(gemm_reduce_kernel<false>, rgrid, block, 0, st, d_blocks, partial, max_mn, nsplit);
+  }
   return DISTDL_OK;
 }
 
 int launch_colsum(const ColsumBlock* d_blocks, int nblocks, int max_f, bool bf16, hipStream_t st) {
-  dim3 grid((unsigned)((max_f + 63) / 64), (unsigned)nblocks), block(256);
+  dim3 grid((unsigned)((max_f + 15) / 16), (unsigned)nblocks), block(256);
   ProfScope prof("affine_bias_grad", st);
   if (bf16) hipLaunchKernelGGL(colsum_kernel<true>, grid, block, 0, st, d_blocks);
   else hipLaunchKernelGGL(colsum_kernel<false>, grid, block, 0, st, d_blocks);
