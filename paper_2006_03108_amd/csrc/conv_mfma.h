@@ -23,6 +23,7 @@ struct CorrArgs {
   int32_t g0;      // output planes (dimension 0) a workgroup walks through
   int32_t R, Cw, CwQ;  // patch rows, cells per row, cells per residue class of the row
   int32_t a_vec4;      // patch size in 16-byte units
+  FastDiv div_cw, div_tc, div_is2;  // exact division by Cw, tc, is[2] in the per-workgroup set-up
   int32_t tiles_max;   // tiles of the largest worker
   const float* wt;     // weights in staging order
   const int* tapinfo;  // device tables behind the weights: 8 plane offsets, then one patch offset per (t1, t2)

@@ -58,7 +58,8 @@ __host__ __device__ inline PerWorker derive(const WorkerDev& wd, const CorrArgs&
 }
 
 __host__ __device__ inline int64_t tiles_of(const PerWorker& g, const CorrArgs& a) {
-  return (int64_t)a.n_b * ((g.nq[0] + a.g0 - 1) / a.g0) * ((g.nq[1] + a.tr - 1) / a.tr) *
+  // chunks of g0 consecutive (sample, dimension-0 position) planes x windows x channel tiles
+  return (((int64_t)a.n_b * g.nq[0] + a.g0 - 1) / a.g0) * ((g.nq[1] + a.tr - 1) / a.tr) *
          ((g.nq[2] + a.tc - 1) / a.tc) * a.ntn;
 }
 
@@ -103,13 +104,12 @@ __global__ __launch_bounds__(256, 2) void corr_mfma_kernel(const WorkerDev* __re
   if ((int64_t)tile >= tiles_of(g, a)) return;
 
   const int nt2tiles = (g.nq[2] + a.tc - 1) / a.tc, nt1tiles = (g.nq[1] + a.tr - 1) / a.tr;
-  const int nq0chunks = (g.nq[0] + a.g0 - 1) / a.g0;
   const int q2_0 = (tile % nt2tiles) * a.tc; tile /= nt2tiles;
   const int q1_0 = (tile % nt1tiles) * a.tr; tile /= nt1tiles;
   const int ntile = tile % a.ntn; tile /= a.ntn;
-  const int q0_begin = (tile % nq0chunks) * a.g0;
-  const int q0_end = min(q0_begin + a.g0, g.nq[0]);
-  const int n = tile / nq0chunks;
+  // output planes of this workgroup: p = n * nq[0] + q0 in [p_begin, p_end)
+  const int nq0 = g.nq[0];
+  const int p_begin = tile * a.g0, p_end = min(p_begin + a.g0, a.n_b * nq0);
 
   const int si2 = a.kc, si1 = g.in_ext[2] * si2, si0 = g.in_ext[1] * si1;
   const uint32_t sin = (uint32_t)g.in_ext[0] * si0;
@@ -135,10 +135,11 @@ __global__ __launch_bounds__(256, 2) void corr_mfma_kernel(const WorkerDev* __re
     loff[i] = dummy * 16;
     if (piece < npieces) {
       const int ph = piece & 1, cell = piece >> 1;
-      const int rr = cell / a.Cw, c = cell - rr * a.Cw;
+      const int rr = (int)fd_div((uint32_t)cell, a.div_cw), c = cell - rr * a.Cw;
       const int i1 = g.in_base[1] + q1_0 * a.is[1] + a.tapmin[1] + rr;
       const int i2 = g.in_base[2] + q2_0 * a.is[2] + a.tapmin[2] + c;
-      loff[i] = (((rr * 2 + ph) * a.is[2] + c % a.is[2]) * a.CwQ + c / a.is[2]) * 16;
+      const int cq = (int)fd_div((uint32_t)c, a.div_is2), cr = c - cq * a.is[2];
+      loff[i] = (((rr * 2 + ph) * a.is[2] + cr) * a.CwQ + cq) * 16;
       if (i1 >= 0 && i1 < g.in_ext[1] && i2 >= 0 && i2 < g.in_ext[2])
         goff[i] = ((i1 * si1 + i2 * si2 + ph * 4) * 4) | ((a.kc & 7) ? ph : 0);
     }
@@ -155,7 +156,7 @@ __global__ __launch_bounds__(256, 2) void corr_mfma_kernel(const WorkerDev* __re
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) {
     const int pidx = (wave * MT + mt) * 32 + m;
-    int wr = pidx / a.tc, wc = pidx - wr * a.tc;
+    int wr = (int)fd_div((uint32_t)pidx, a.div_tc), wc = pidx - wr * a.tc;
     if (wr >= a.tr) wr = 0, wc = 0;  // idle position: multiplies something in range, never stored
     abase[mt] = (wr * a.is[1] * 2 * a.is[2] * a.CwQ + wc + h * a.is[2] * a.CwQ) * 16;
   }
@@ -166,7 +167,7 @@ __global__ __launch_bounds__(256, 2) void corr_mfma_kernel(const WorkerDev* __re
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
       const int po = (wave * MT + mt) * 32 + 8 * (v / 4) + 4 * h + (v % 4);
-      const int orow = po / a.tc, ocol = po - orow * a.tc;
+      const int orow = (int)fd_div((uint32_t)po, a.div_tc), ocol = po - orow * a.tc;
       const int q1 = q1_0 + orow, q2 = q2_0 + ocol;
       soff[mt][v] = kOob;
       if (orow < a.tr && q1 < g.nq[1] && q2 < g.nq[2] && ch < a.nc)
@@ -186,23 +187,29 @@ __global__ __launch_bounds__(256, 2) void corr_mfma_kernel(const WorkerDev* __re
   // outside the input contribute zero and are skipped.
   // (the table entry is the same for all lanes: saying so keeps the stage base offsets in scalar registers)
   auto plane_of = [&](int q0, int t0) { return g.in_base[0] + q0 * a.is[0] + __builtin_amdgcn_readfirstlane(tapinfo[t0]); };
-  auto advance = [&](int& q0, int& t0, int& cc) {  // next valid stage after (q0, t0, cc), or q0 == q0_end
-    if (++cc < ncc) return;  // same plane, next chunk
-    cc = 0;
-    ++t0;
-    while (q0 < q0_end) {
-      while (t0 < nt0) {
-        const int i0 = plane_of(q0, t0);
+  // a stage position: plane p = (n, q0), tap plane t0, chunk cc
+  struct StagePos {
+    int p, n, q0, t0, cc;
+  };
+  auto advance = [&](StagePos& sp) {  // next valid stage after sp, or sp.p == p_end
+    if (++sp.cc < ncc) return;  // same plane, next chunk
+    sp.cc = 0;
+    ++sp.t0;
+    while (sp.p < p_end) {
+      while (sp.t0 < nt0) {
+        const int i0 = plane_of(sp.q0, sp.t0);
         if (i0 >= 0 && i0 < g.in_ext[0]) return;
-        ++t0;
+        ++sp.t0;
       }
-      ++q0;
-      t0 = 0;
+      ++sp.p;
+      sp.t0 = 0;
+      if (++sp.q0 == nq0) sp.q0 = 0, ++sp.n;
     }
   };
   u32x4 ra[PA], rb[PB];
-  auto load_stage = [&](int q0, int t0, int cc) {
-    const uint32_t sbase = ((uint32_t)n * sin + (uint32_t)plane_of(q0, t0) * si0 + cc * 8) * 4u;
+  auto load_stage = [&](const StagePos& sp) {
+    const int t0 = sp.t0, cc = sp.cc;
+    const uint32_t sbase = ((uint32_t)sp.n * sin + (uint32_t)plane_of(sp.q0, t0) * si0 + cc * 8) * 4u;
     if (ragged && cc == ncc - 1) {
 #pragma unroll
       for (int i = 0; i < PA; ++i)
@@ -299,22 +306,24 @@ __global__ __launch_bounds__(256, 2) void corr_mfma_kernel(const WorkerDev* __re
   };
 
   floatx16 acc[MT];
-  int q0 = q0_begin, t0 = -1, cc = ncc - 1;  // the stage whose loads are in flight
-  advance(q0, t0, cc);
-  if (q0 < q0_end) load_stage(q0, t0, cc);
-  for (int qo = q0_begin; qo < q0_end; ++qo) {  // output planes of this workgroup
+  StagePos sp{p_begin, p_begin / nq0, p_begin % nq0, -1, ncc - 1};  // the stage whose loads are in flight
+  advance(sp);
+  if (sp.p < p_end) load_stage(sp);
+  int on = p_begin / nq0, oq0 = p_begin % nq0;
+  for (int po = p_begin; po < p_end; ++po) {  // output planes of this workgroup
 #pragma unroll
     for (int t = 0; t < MT; ++t)
       for (int v = 0; v < 16; ++v) acc[t][v] = 0.f;
-    while (q0 == qo) {  // the stages that feed output plane qo
+    while (sp.p == po) {  // the stages that feed output plane po
       write_stage();
       __syncthreads();
-      advance(q0, t0, cc);
-      if (q0 < q0_end) load_stage(q0, t0, cc);  // in flight while this stage multiplies
+      advance(sp);
+      if (sp.p < p_end) load_stage(sp);  // in flight while this stage multiplies
       compute(acc);
       __syncthreads();  // everyone is done reading this stage
     }
-    const uint32_t obase = ((uint32_t)n * son + (uint32_t)(g.out_base[0] + g.os[0] * qo) * so0) * 4u;
+    const uint32_t obase = ((uint32_t)on * son + (uint32_t)(g.out_base[0] + g.os[0] * oq0) * so0) * 4u;
+    if (++oq0 == nq0) oq0 = 0, ++on;
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
@@ -809,6 +818,9 @@ static void finish_args(CorrArgs& a, int mt, int nq2max) {
   a.Cw = (a.tc - 1) * a.is[2] + a.tapspan[2] + 1;
   a.CwQ = (a.Cw + a.is[2] - 1) / a.is[2];
   a.a_vec4 = a.R * 2 * a.is[2] * a.CwQ;
+  a.div_cw = make_fastdiv((uint32_t)a.Cw);
+  a.div_tc = make_fastdiv((uint32_t)a.tc);
+  a.div_is2 = make_fastdiv((uint32_t)a.is[2]);
 }
 
 // Chooses the rows-per-wave so that two workgroups fit in a CU's LDS when
@@ -904,14 +916,22 @@ static int launch_corr(distdl_plan* p, CorrArgs a, const float* w, float* wscrat
                        void** out_tab, const char* name, hipStream_t st) {
   const int mt = choose_mt(a, max_nq2(p, a));
   if (mt == 0) return set_error(DISTDL_ERR_UNSUPPORTED, "conv: kernel footprint does not fit in LDS");
-  // output planes per workgroup: as many as still leave about 2048 workgroups (3584 for the shorter
-  // workgroups of the data-gradient classes)
+  // Output planes per workgroup.  A workgroup pays a fixed set-up (its address tables, about 8 * 10^3
+  // cycles) and then about `per_plane` cycles per plane; the chip runs about 512 workgroups at a time.
+  // Pick the chunk length with the smallest estimated time, preferring shorter chunks among near-ties.
   a.g0 = 1;
   {
-    int nq0max = 0;
-    for (const WorkerDev& wd : p->workers) nq0max = std::max(nq0max, derive(wd, a).nq[0]);
-    const int64_t wgs = max_tiles(p, a) * p->n_workers;
-    a.g0 = (int32_t)std::max<int64_t>(1, std::min<int64_t>(nq0max, wgs / (a.mode == 1 ? 3584 : 2048)));
+    int64_t planes_max = 0;
+    for (const WorkerDev& wd : p->workers) planes_max = std::max<int64_t>(planes_max, p->n_b * derive(wd, a).nq[0]);
+    const int64_t per_plane_wgs = max_tiles(p, a) / std::max<int64_t>(planes_max, 1) * p->n_workers;  // with g0 == 1
+    const double setup = 8.0e3;
+    const double per_plane = (double)a.nt[0] * ((a.kc + 7) / 8) * a.nt[1] * a.nt[2] * mt * 4 * 64.0 * 2.0;
+    double best = 1e300;
+    for (int64_t g0 = 1; g0 <= planes_max; ++g0) {
+      const int64_t wgs = (planes_max + g0 - 1) / g0 * per_plane_wgs;
+      const double cost = (double)((wgs + 511) / 512) * (setup + g0 * per_plane);
+      if (cost < best * 0.97) best = cost, a.g0 = (int32_t)g0;
+    }
   }
   a.tiles_max = (int32_t)max_tiles(p, a);
   if (a.tiles_max == 0) return DISTDL_OK;
