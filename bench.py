@@ -531,7 +531,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="cfg5", choices=["cfg5", "cfg2", "cfg3", "cfg3-bf16", "cfg4", "movement"])
     ap.add_argument("--no-movement", action="store_true",
-                    help="with the default workload: skip the movement kernels' own figures")
+                    help="with the default workload: skip the movement kernels' own figures and the other configurations")
     ap.add_argument("--sweep", action="store_true",
                     help="with --workload movement: also the size sweep of broadcast / sum-reduce")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -590,26 +590,44 @@ def main():
         "vs_baseline": None, "dtype": wl.dtype, "data": "synthetic", "config": wl.describe,
         "roofline": roofline, "kernels": kernels,
     }
-    if args.workload == "cfg5" and not args.no_movement:
-        # the other half of the metric: the movement primitives on their own (H, H* on this geometry, B, R and
-        # adjoints on large arrays), timed after the convolution step
-        del wl.y, wl.dx, wl.ws
-        mv = MovementWorkload(False)
-        for _ in range(2):
-            mv.step()
+    def side_run(make, steps):
+        """One more workload timed with the same harness (profiling scopes on); its own small report."""
+        w = make()
+        for _ in range(3):
+            w.step()
         torch.cuda.synchronize()
         dd.distdl_profile_enable(True)
         dd.distdl_profile_report()
         t0 = time.perf_counter()
-        for _ in range(10):
-            mv.step()
+        for _ in range(steps):
+            w.step()
         torch.cuda.synchronize()
-        mv_sec = (time.perf_counter() - t0) / 10
-        mv_kernels = kernel_rooflines(mv, dd.distdl_profile_report(), load_traffic())
+        s_sec = (time.perf_counter() - t0) / steps
+        kern = kernel_rooflines(w, dd.distdl_profile_report(), load_traffic())
         dd.distdl_profile_enable(False)
-        line["movement"] = {"metric": mv.metric, "value": mv.value(mv_sec), "unit": mv.unit, "steps": 10,
-                            "ms_per_step": mv_sec * 1e3, "frac_hbm_peak": mv.value(mv_sec) / HBM_PEAK_GBS,
-                            "config": mv.describe, "kernels": mv_kernels}
+        return w, {"metric": w.metric, "value": w.value(s_sec), "unit": w.unit, "steps": steps,
+                   "ms_per_step": s_sec * 1e3, "dtype": w.dtype, "config": w.describe, "kernels": kern}
+
+    if args.workload == "cfg5" and not args.no_movement:
+        # the other half of the metric: the movement primitives on their own (H, H* on this geometry, B, R and
+        # adjoints on large arrays), timed after the convolution step
+        del wl.y, wl.dx, wl.ws, wl.x, wl.dy
+        torch.cuda.empty_cache()
+        mv, rep = side_run(lambda: MovementWorkload(False), 10)
+        rep["frac_hbm_peak"] = rep["value"] / HBM_PEAK_GBS
+        line["movement"] = rep
+        del mv
+        torch.cuda.empty_cache()
+        # the remaining single-GPU configurations, for reference (same harness, no CPU leg)
+        line["other_configs"] = {}
+        for tag, make, steps in (("cfg2", lambda: ConvWorkload("cfg2"), 50),
+                                 ("cfg3", lambda: AffineWorkload("cfg3", "f32"), 50),
+                                 ("cfg3-bf16", lambda: AffineWorkload("cfg3", "bf16"), 50),
+                                 ("cfg4", lambda: SmallCnnWorkload(), 50)):
+            w, rep = side_run(make, steps)
+            rep["kernel_launches_per_step"] = sum(k["launches"] for k in rep["kernels"].values()) / steps
+            line["other_configs"][tag] = rep
+            del w
     if getattr(wl, "sweep_on", False):
         line["sweep"] = wl.sweep()
     if not args.no_cpu_baseline:
