@@ -292,6 +292,29 @@ def halo_exchange_adjoint_direct(bufs, part):
     return bufs
 
 
+def adjoint_multiplicity(part, w):
+    """H* applied to a buffer of ones, in closed form (a pin for H*, Sec. 3
+    "Halo exchange"): bulk cell i of worker w ends as the number of buffer
+    cells, in all workers, that hold global index i, i.e. the product over
+    the dimensions of 1 + (neighbours along d whose halo covers i_d).  Returns
+    an integer array over the worker's bulk."""
+    out = np.ones([part.g(w, d)["in_size"] for d in range(part.D)], dtype=np.int64)
+    for d in range(part.D):
+        g = part.g(w, d)
+        count = np.ones(g["in_size"], dtype=np.int64)
+        left, right = part.neighbour(w, d, 0), part.neighbour(w, d, 1)
+        if left is not None:            # the left neighbour's right halo covers my first cells
+            count[:part.g(left, d)["halo"][1]] += 1
+        if right is not None:           # the right neighbour's left halo covers my last cells
+            hl = part.g(right, d)["halo"][0]
+            if hl:
+                count[-hl:] += 1
+        shape = [1] * part.D
+        shape[d] = g["in_size"]
+        out = out * count.reshape(shape)
+    return out
+
+
 def expected_buffer_after_halo(x_global, part, w):
     """Worker w's buffer after H, by slicing the zero-extended global tensor
     (vectorised statement of halo_exchange_direct for one worker; used for

@@ -208,3 +208,87 @@ def test_collective_errors():
     empty = torch.zeros(0, device="cuda")
     dd.distdl_bcast_fwd([empty], [empty, empty], 2)     # empty input: no-op
     torch.cuda.synchronize()
+
+
+def test_halo_full_size_sampled_properties():
+    """H and H* at the size and launch configuration the benchmark times (cfg5: 64 buffers of 67^3 cells x 32
+    channels): the bulk holds an index pattern, so every sampled buffer cell has a known value after H (the
+    pattern at its global index, or zero outside the domain); H* of all-ones must give the closed-form copy
+    counts on the bulk and zero elsewhere (both exact in fp32)."""
+    require_gpu()
+    cfg = syn.CONFIGS["cfg5"]
+    part = geo.Partition.for_kernel(cfg["in_shape"], cfg["P"], cfg["ksize"], cfg["stride"], cfg["padding"],
+                                    cfg["dilation"])
+    plan = dd.distdl_plan_create(cfg["D"], cfg["n_b"], cfg["c_in"], cfg["c_out"], cfg["in_shape"], cfg["P"],
+                                 cfg["ksize"], cfg["stride"], cfg["padding"], cfg["dilation"])
+    C, n = cfg["c_in"], cfg["in_shape"]
+    pattern = lambda g0, g1, g2, c: (g0 * 65536 + g1 * 256 + g2 + 7 * c) % 16777216     # < 2^24: exact in fp32
+    bufs, ones = [], []
+    for w in range(part.n_workers):
+        shp = part.buf_shape(w)
+        b = torch.full((1,) + shp + (C,), -1.0, device="cuda")
+        sl = part.bulk_slices(w)
+        g = [torch.arange(part.g(w, d)["in_start"], part.g(w, d)["in_start"] + part.g(w, d)["in_size"],
+                          device="cuda", dtype=torch.int64) for d in range(3)]
+        c = torch.arange(C, device="cuda", dtype=torch.int64)
+        val = pattern(g[0][:, None, None, None], g[1][None, :, None, None], g[2][None, None, :, None], c[None, None, None, :])
+        b[0, sl[0], sl[1], sl[2], :] = val.to(torch.float32)
+        bufs.append(b)
+        ones.append(torch.ones((1,) + shp + (C,), device="cuda"))
+    dd.distdl_halo_fwd(plan, bufs)
+    dd.distdl_halo_adj(plan, ones)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(3)
+    for w in range(part.n_workers):
+        shp = part.buf_shape(w)
+        m = 3000
+        idx = [rng.integers(0, shp[d], size=m) for d in range(3)]
+        # make sure faces, edges and corners of the buffer are sampled too
+        for d in range(3):
+            idx[d][:200] = rng.choice([0, 1, 2, shp[d] - 2, shp[d] - 1], size=200)
+        ch = rng.integers(0, C, size=m)
+        gi = [prim._global_index_of(part, w, d, idx[d]) for d in range(3)]
+        inside = np.ones(m, dtype=bool)
+        for d in range(3):
+            inside &= (gi[d] >= 0) & (gi[d] < n[d])
+        want = np.where(inside, pattern(gi[0], gi[1], gi[2], ch), 0).astype(np.float32)
+        ti = [torch.from_numpy(a).cuda() for a in idx] + [torch.from_numpy(ch).cuda()]
+        got = bufs[w][0, ti[0], ti[1], ti[2], ti[3]].cpu().numpy()
+        assert np.array_equal(got, want), f"H worker {w}"
+        mult = np.zeros(shp, dtype=np.float32)
+        mult[part.bulk_slices(w)] = prim.adjoint_multiplicity(part, w)
+        got = ones[w][0, ti[0], ti[1], ti[2], ti[3]].cpu().numpy()
+        assert np.array_equal(got, mult[idx[0], idx[1], idx[2]]), f"H* worker {w}"
+    # whole-tensor invariant of H* on ones: the total is the number of buffer cells that are in the domain
+    total = sum(t.sum(dtype=torch.float64).item() for t in ones)
+    in_domain = 0
+    for w in range(part.n_workers):
+        cells = 1
+        for d in range(3):
+            g = part.g(w, d)
+            cells *= g["halo"][0] + g["in_size"] + g["halo"][1]
+        in_domain += cells
+    assert total == in_domain * C
+
+
+@pytest.mark.parametrize("k,count", [(4, 1 << 26), (64, 1 << 22)])
+def test_collectives_full_size_exact(k, count):
+    """B and R at the sizes the benchmark times, with integer-valued data so that every sum is exact."""
+    require_gpu()
+    g = torch.Generator(device="cuda").manual_seed(5)
+    reps = [torch.randint(-8, 9, (count,), generator=g, device="cuda").to(torch.float32) for _ in range(k)]
+    out = torch.empty(count, device="cuda")
+    dd.distdl_sumreduce_fwd(reps, [out], k, False)
+    want = torch.zeros(count, device="cuda", dtype=torch.float64)
+    for r in reps:                                  # index order, exact in fp64 (plumbing, not the product path)
+        want += r
+    assert torch.equal(out.to(torch.float64), want)
+    copies = [torch.empty(count, device="cuda") for _ in range(k)]
+    dd.distdl_bcast_fwd([out], copies, k)
+    torch.cuda.synchronize()
+    idx = torch.randint(0, count, (100000,), generator=g, device="cuda")
+    host = out[idx].cpu().numpy()
+    rows = np.stack([r[idx].cpu().numpy().astype(np.float64) for r in reps])
+    assert np.array_equal(host.astype(np.float64), prim.sum_reduce(list(rows)))    # sampled against the oracle
+    for c in copies:
+        assert torch.equal(c, out)

@@ -210,3 +210,18 @@ def test_halo_operator_matrix_is_transposed():
     Hs = np.stack([apply(prim.halo_exchange_adjoint, e) for e in np.eye(total)], axis=1)
     assert np.array_equal(Hs, H.T)
     assert set(np.unique(H)) == {0.0, 1.0}
+
+
+@pytest.mark.parametrize("n,P,k,s,p", [((11,), (3,), (5,), (1,), (2,)), ((10, 20), (3, 6), (2, 2), (2, 2), (0, 0)),
+                                       ((9, 9), (3, 3), (5, 5), (1, 1), (2, 2)),
+                                       ((20, 18, 22), (2, 3, 2), (5, 3, 5), (2, 1, 2), (2, 1, 2))])
+def test_adjoint_multiplicity_closed_form_matches_nested_adjoint(n, P, k, s, p):
+    """H* of all-ones counts the copies of every cell (an exact integer pin that a wrong slab, a dropped
+    corner or a missed clear would break); the closed form used at full size on the GPU agrees with it."""
+    part = geo.Partition.for_kernel(n, P, k, s, p, (1,) * len(n))
+    ones = [np.ones((1, 2) + part.buf_shape(w)) for w in range(part.n_workers)]
+    got = prim.halo_exchange_adjoint(ones, part)
+    for w in range(part.n_workers):
+        want = np.zeros(part.buf_shape(w))
+        want[part.bulk_slices(w)] = prim.adjoint_multiplicity(part, w)
+        assert np.array_equal(got[w][0, 0], want) and np.array_equal(got[w][0, 1], want)
