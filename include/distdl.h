@@ -206,6 +206,12 @@ int distdl_affine_bwd(distdl_affine_plan* plan, const void* const x_dev[], const
  *   "extra" input, App. B.1); backward routes dy to the first maximum of each
  *   window (row-major tap order) over the whole padded buffer, then dx <- H* dx.
  *   x_bufs_dev of maxpool_bwd must hold H x.
+ * avgpool_fwd / avgpool_bwd: the same two algorithms with the mean as the
+ *   local pool: y = (sum of the window's taps) / window size, zero-padding
+ *   cells counted as the zeros they hold; it is linear, so the backward call
+ *   needs no saved input: dx <- H* ([dPool]* dy), every tap of a window
+ *   receiving dy / window size.  Kernel size, stride and dilation are the
+ *   plan's, any values the planner accepts (App. B.1 unbalanced cases included).
  * bulk_copy: dense [n_b][in_size..][n_c] per worker <-> the bulk of the padded
  *   buffers (to_bufs != 0: dense -> buffers), the hand-over between two layers
  *   whose partitions of the same tensor agree.
@@ -224,6 +230,8 @@ int distdl_relu_bwd(const void* const x_dev[], const void* const dy_dev[], void*
 int distdl_maxpool_fwd(distdl_plan* plan, void* const x_bufs_dev[], void* const y_dev[], void* stream);
 int distdl_maxpool_bwd(distdl_plan* plan, const void* const x_bufs_dev[], const void* const dy_dev[],
                        void* const dx_bufs_dev[], void* stream);
+int distdl_avgpool_fwd(distdl_plan* plan, void* const x_bufs_dev[], void* const y_dev[], void* stream);
+int distdl_avgpool_bwd(distdl_plan* plan, const void* const dy_dev[], void* const dx_bufs_dev[], void* stream);
 int distdl_bulk_copy(distdl_plan* plan, void* const dense_dev[], void* const bufs_dev[], int to_bufs, void* stream);
 int distdl_repartition_fwd(distdl_plan* plan, const void* const src_dev[], int P_f, void* const dst_dev[],
                            void* stream);
@@ -231,6 +239,16 @@ int distdl_repartition_adj(distdl_plan* plan, const void* const gdst_dev[], int 
                            void* stream);
 int distdl_mse_fwd_bwd(const void* const y_dev[], const void* const t_dev[], void* const dy_dev[],
                        const int64_t count[], int n, double* loss_dev, void* stream);
+
+/* ------------------------------------------------------------------------
+ * All-reduce A = B R (Sec. 3 "Sum-reduce and all-reduce": the sum-reduction
+ * composed with the broadcast; self-adjoint).  In place: every one of the k
+ * replicas of group g, bufs_dev[g*k + i], ends as the sum of the group's
+ * replicas, added in index order i = 0 .. k-1 (so all replicas end
+ * bit-identical).  Replicas of a group must not overlap.  Errors as for the
+ * calls above.
+ * ---------------------------------------------------------------------- */
+int distdl_allreduce(void* const bufs_dev[], const int64_t count[], int G, int k, distdl_dtype dtype, void* stream);
 
 /* ------------------------------------------------------------------------
  * Euclidean inner product over a list of device arrays (Sec. 2, second

@@ -133,6 +133,30 @@ def maxpool_valid_adjoint(dy, arg, xp_shape, ksize, stride, origin):
     return dxp
 
 
+def avgpool_valid(xp, ksize, stride, out_shape, origin):
+    """Mean over each window of an already-trimmed / padded input: the sum of
+    the window's taps divided by the window size (padding cells count as the
+    zeros they hold)."""
+    xp = np.asarray(xp, dtype=np.float64)
+    y = None
+    for kappa in np.ndindex(*ksize):
+        xs = _tap_view(xp, kappa, out_shape, stride, [1] * len(ksize), origin)
+        y = xs.copy() if y is None else y + xs
+    return y / float(np.prod(ksize))
+
+
+def avgpool_valid_adjoint(dy, xp_shape, ksize, stride, origin):
+    """Adjoint of avgpool_valid (it is linear): every tap of window o receives
+    dy[o] / window size."""
+    dxp = np.zeros(xp_shape)
+    out_shape = dy.shape[2:]
+    share = np.asarray(dy, dtype=np.float64) / float(np.prod(ksize))
+    for kappa in np.ndindex(*ksize):
+        dxs = _tap_view(dxp, kappa, out_shape, stride, [1] * len(ksize), origin)
+        dxs += share
+    return dxp
+
+
 def mse_loss(y, target):
     """mean((y - t)^2) over every element, and its gradient."""
     diff = np.asarray(y, dtype=np.float64) - target
@@ -211,6 +235,21 @@ def dist_maxpool_adjoint(dy_parts, args, part, buf_shapes, ksize, stride):
     for wk in range(part.n_workers):
         origin = [part.g(wk, d)["origin"] for d in range(part.D)]
         dx.append(maxpool_valid_adjoint(dy_parts[wk], args[wk], buf_shapes[wk], ksize, stride, origin))
+    prim.halo_exchange_adjoint(dx, part)
+    return dx
+
+
+def dist_avgpool_forward(x_bufs, part, ksize, stride):
+    """Forward Pooling Algorithm of Sec. 4 with the mean as the local pool."""
+    prim.halo_exchange(x_bufs, part)
+    return [avgpool_valid(x_bufs[wk], ksize, stride, part.out_shape(wk),
+                          [part.g(wk, d)["origin"] for d in range(part.D)]) for wk in range(part.n_workers)]
+
+
+def dist_avgpool_adjoint(dy_parts, part, buf_shapes, ksize, stride):
+    """Adjoint Pooling Algorithm of Sec. 4 with the mean: dx <- [dPool]*(dy); dx <- H* dx."""
+    dx = [avgpool_valid_adjoint(dy_parts[wk], buf_shapes[wk], ksize, stride,
+                                [part.g(wk, d)["origin"] for d in range(part.D)]) for wk in range(part.n_workers)]
     prim.halo_exchange_adjoint(dx, part)
     return dx
 

@@ -48,6 +48,7 @@ _SIGS = {
     "distdl_bcast_adj": [_pp, _pp, _p64, _i, _i, _i, _i, _vp],
     "distdl_sumreduce_fwd": [_pp, _pp, _p64, _i, _i, _i, _i, _vp],
     "distdl_sumreduce_adj": [_pp, _pp, _p64, _i, _i, _i, _vp],
+    "distdl_allreduce": [_pp, _p64, _i, _i, _i, _vp],
     "distdl_conv_fwd": [_vp, _pp, _vp, _vp, _pp, _vp],
     "distdl_conv_bwd": [_vp, _pp, _vp, _pp, _pp, _vp, _vp, _vp, C.c_size_t, _vp],
     "distdl_affine_plan_create": [C.POINTER(_vp), _i64, _i64, _i64, _i, _i, _i],
@@ -59,6 +60,8 @@ _SIGS = {
     "distdl_relu_bwd": [_pp, _pp, _pp, _p64, _i, _vp],
     "distdl_maxpool_fwd": [_vp, _pp, _pp, _vp],
     "distdl_maxpool_bwd": [_vp, _pp, _pp, _pp, _vp],
+    "distdl_avgpool_fwd": [_vp, _pp, _pp, _vp],
+    "distdl_avgpool_bwd": [_vp, _pp, _pp, _vp],
     "distdl_bulk_copy": [_vp, _pp, _pp, _i, _vp],
     "distdl_repartition_fwd": [_vp, _pp, _i, _pp, _vp],
     "distdl_repartition_adj": [_vp, _pp, _i, _pp, _vp],
@@ -191,6 +194,13 @@ def distdl_sumreduce_adj(gdst, gsrc, k):
                                     _dtype_code(gdst[0].dtype), _stream()))
 
 
+def distdl_allreduce(bufs, k):
+    """bufs: G*k tensors, group after group; all replicas of a group end as the group's sum."""
+    G = len(bufs) // k
+    counts = _arr(C.c_int64, [bufs[g * k].numel() for g in range(G)])
+    _check(lib.distdl_allreduce(_ptrs(bufs), counts, G, k, _dtype_code(bufs[0].dtype), _stream()))
+
+
 def distdl_conv_bwd_workspace(plan):
     return int(lib.distdl_conv_bwd_workspace(plan.handle))
 
@@ -255,6 +265,14 @@ def distdl_maxpool_fwd(plan, x_bufs, y):
 
 def distdl_maxpool_bwd(plan, x_bufs, dy, dx_bufs):
     _check(lib.distdl_maxpool_bwd(plan.handle, _ptrs(x_bufs), _ptrs(dy), _ptrs(dx_bufs), _stream()))
+
+
+def distdl_avgpool_fwd(plan, x_bufs, y):
+    _check(lib.distdl_avgpool_fwd(plan.handle, _ptrs(x_bufs), _ptrs(y), _stream()))
+
+
+def distdl_avgpool_bwd(plan, dy, dx_bufs):
+    _check(lib.distdl_avgpool_bwd(plan.handle, _ptrs(dy), _ptrs(dx_bufs), _stream()))
 
 
 def distdl_bulk_copy(plan, dense, bufs, to_bufs):

@@ -7,6 +7,7 @@
 // several independent launches, a reduction continues into its output in
 // replica order, so the summation order stays i = 0..k-1).
 #include <algorithm>
+#include <vector>
 
 #include "common.h"
 #include "profile.h"
@@ -283,6 +284,21 @@ int distdl_bcast_adj(void* const gsrc_dev[], void* const gdst_dev[], const int64
 int distdl_sumreduce_fwd(void* const src_dev[], void* const dst_dev[], const int64_t count[], int G, int k,
                          distdl_dtype dtype, int clear_inputs, void* stream) {
   return run_collective(true, dst_dev, src_dev, count, G, k, dtype, clear_inputs, (hipStream_t)stream);
+}
+
+int distdl_allreduce(void* const bufs_dev[], const int64_t count[], int G, int k, distdl_dtype dtype, void* stream) {
+  if (!bufs_dev || !count) return set_error(DISTDL_ERR_NULL, "allreduce: null argument");
+  if (G < 1 || k < 1) return set_error(DISTDL_ERR_INVALID_ARG, "allreduce: G = %d, k = %d", G, k);
+  // A = B R: the sum lands in replica 0 of each group (a thread reads all replicas of its elements before it
+  // writes, so reducing in place is safe), then replica 0 is broadcast to the other k - 1
+  std::vector<void*> first(G), rest((size_t)G * std::max(k - 1, 1));
+  for (int g = 0; g < G; ++g) {
+    first[g] = bufs_dev[(size_t)g * k];
+    for (int i = 1; i < k; ++i) rest[(size_t)g * (k - 1) + i - 1] = bufs_dev[(size_t)g * k + i];
+  }
+  int rc = run_collective(true, first.data(), bufs_dev, count, G, k, dtype, 0, (hipStream_t)stream);
+  if (rc || k == 1) return rc;
+  return run_collective(false, first.data(), rest.data(), count, G, k - 1, dtype, 0, (hipStream_t)stream);
 }
 
 int distdl_dot(const void* const a_dev[], const void* const b_dev[], const int64_t count[], int n_arrays,

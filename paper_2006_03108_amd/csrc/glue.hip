@@ -82,8 +82,9 @@ static PoolDev pool_params(const distdl_plan* p) {
 }
 
 // y[n][o][c] = max over the window of x^[n][origin + o*s + t*dil][c]
-__global__ __launch_bounds__(256) void maxpool_fwd_kernel(const WorkerDev* __restrict__ workers, void* const* x_bufs,
-                                                          void* const* y_bufs, PoolDev d) {
+template <bool AVG>
+__global__ __launch_bounds__(256) void pool_fwd_kernel(const WorkerDev* __restrict__ workers, void* const* x_bufs,
+                                                       void* const* y_bufs, PoolDev d) {
   const WorkerDev wd = workers[blockIdx.y];
   const int64_t total = (int64_t)d.n_b * wd.out[0] * wd.out[1] * wd.out[2] * d.c;
   int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
@@ -97,7 +98,7 @@ __global__ __launch_bounds__(256) void maxpool_fwd_kernel(const WorkerDev* __res
   int o0 = (int)(r % wd.out[0]);
   int n = (int)(r / wd.out[0]);
   const int64_t s2 = d.c, s1 = (int64_t)wd.buf[2] * s2, s0 = (int64_t)wd.buf[1] * s1, sn = (int64_t)wd.buf[0] * s0;
-  float best = 0.f;
+  float best = 0.f, sum = 0.f;
   bool first = true;
   for (int t0 = 0; t0 < d.k[0]; ++t0)
     for (int t1 = 0; t1 < d.k[1]; ++t1)
@@ -106,20 +107,23 @@ __global__ __launch_bounds__(256) void maxpool_fwd_kernel(const WorkerDev* __res
                           (wd.origin[1] + o1 * d.s[1] + t1 * d.dil[1]) * s1 +
                           (wd.origin[2] + o2 * d.s[2] + t2 * d.dil[2]) * s2 + c];
         if (first || v > best) best = v;
+        sum += v;  // row-major tap order
         first = false;
       }
-  y[idx] = best;
+  y[idx] = AVG ? sum / (float)(d.k[0] * d.k[1] * d.k[2]) : best;
 }
 
 // [dPool]* in gather form over the whole padded buffer: a cell receives dy[o] from every window o that
 // contains it and whose first maximum (row-major tap order) it is.
-__global__ __launch_bounds__(256) void maxpool_bwd_kernel(const WorkerDev* __restrict__ workers, void* const* x_bufs,
-                                                          void* const* dy_bufs, void* const* dx_bufs, PoolDev d) {
+// For the mean every window that contains the cell contributes dy[o] / window size.
+template <bool AVG>
+__global__ __launch_bounds__(256) void pool_bwd_kernel(const WorkerDev* __restrict__ workers, void* const* x_bufs,
+                                                       void* const* dy_bufs, void* const* dx_bufs, PoolDev d) {
   const WorkerDev wd = workers[blockIdx.y];
   const int64_t total = (int64_t)d.n_b * wd.buf[0] * wd.buf[1] * wd.buf[2] * d.c;
   int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (idx >= total) return;
-  const float* __restrict__ x = (const float*)x_bufs[blockIdx.y];
+  const float* __restrict__ x = AVG ? nullptr : (const float*)x_bufs[blockIdx.y];
   const float* __restrict__ dy = (const float*)dy_bufs[blockIdx.y];
   float* __restrict__ dx = (float*)dx_bufs[blockIdx.y];
   int c = (int)(idx % d.c);
@@ -140,6 +144,10 @@ __global__ __launch_bounds__(256) void maxpool_bwd_kernel(const WorkerDev* __res
         if (q0 < 0 || q1 < 0 || q2 < 0 || q0 % d.s[0] || q1 % d.s[1] || q2 % d.s[2]) continue;
         const int o0 = q0 / d.s[0], o1 = q1 / d.s[1], o2 = q2 / d.s[2];
         if (o0 >= wd.out[0] || o1 >= wd.out[1] || o2 >= wd.out[2]) continue;
+        if (AVG) {
+          acc += dy[n * son + o0 * so0 + o1 * so1 + o2 * so2 + c];
+          continue;
+        }
         // is this cell (tap index `tap`) the first maximum of window o?
         float best = 0.f;
         int arg = -1, u = 0;
@@ -153,7 +161,7 @@ __global__ __launch_bounds__(256) void maxpool_bwd_kernel(const WorkerDev* __res
             }
         if (arg == tap) acc += dy[n * son + o0 * so0 + o1 * so1 + o2 * so2 + c];
       }
-  dx[idx] = acc;
+  dx[idx] = AVG ? acc / (float)(d.k[0] * d.k[1] * d.k[2]) : acc;
 }
 
 // dense [n][in_size..][c] <-> bulk of the padded buffer
@@ -280,47 +288,70 @@ int distdl_relu_bwd(const void* const x_dev[], const void* const dy_dev[], void*
   return run_elementwise<1>(x_dev, dy_dev, dx_dev, count, n, 0.f, "relu_bwd", (hipStream_t)stream);
 }
 
-int distdl_maxpool_fwd(distdl_plan* plan, void* const x_bufs_dev[], void* const y_dev[], void* stream) {
-  if (!plan || !x_bufs_dev || !y_dev) return set_error(DISTDL_ERR_NULL, "maxpool_fwd: null argument");
-  int rc = check_pool_plan(plan, "maxpool_fwd");
+static int pool_fwd(distdl_plan* plan, void* const x_bufs_dev[], void* const y_dev[], bool avg, hipStream_t st) {
+  const char* what = avg ? "avgpool_fwd" : "maxpool_fwd";
+  if (!plan || !x_bufs_dev || !y_dev) return set_error(DISTDL_ERR_NULL, "%s: null argument", what);
+  int rc = check_pool_plan(plan, what);
   if (rc) return rc;
-  if ((rc = check_list((const void* const*)y_dev, plan->n_workers, "maxpool_fwd y"))) return rc;
-  hipStream_t st = (hipStream_t)stream;
+  if ((rc = check_list((const void* const*)y_dev, plan->n_workers, what))) return rc;
   if ((rc = run_halo(plan, false, plan->tab_x, x_bufs_dev, st))) return rc;  // x <- H x
   if ((rc = plan->tab_x.upload((const void* const*)x_bufs_dev, plan->n_workers, st))) return rc;
   if ((rc = plan->tab_y.upload((const void* const*)y_dev, plan->n_workers, st))) return rc;
   PoolDev d = pool_params(plan);
   int64_t total = plan->n_b * plan->max_out_cells * d.c;
-  ProfScope prof("maxpool_fwd", st);
-  hipLaunchKernelGGL(maxpool_fwd_kernel, dim3((unsigned)((total + 255) / 256), plan->n_workers), dim3(256), 0, st,
-                     plan->d_workers, plan->tab_x.dev, plan->tab_y.dev, d);
+  ProfScope prof(what, st);
+  dim3 grid((unsigned)((total + 255) / 256), plan->n_workers);
+  if (avg) hipLaunchKernelGGL(pool_fwd_kernel<true>, grid, dim3(256), 0, st, plan->d_workers, plan->tab_x.dev, plan->tab_y.dev, d);
+  else hipLaunchKernelGGL(pool_fwd_kernel<false>, grid, dim3(256), 0, st, plan->d_workers, plan->tab_x.dev, plan->tab_y.dev, d);
   DISTDL_HIP_TRY(hipGetLastError());
   return DISTDL_OK;
 }
 
-int distdl_maxpool_bwd(distdl_plan* plan, const void* const x_bufs_dev[], const void* const dy_dev[],
-                       void* const dx_bufs_dev[], void* stream) {
-  if (!plan || !x_bufs_dev || !dy_dev || !dx_bufs_dev) return set_error(DISTDL_ERR_NULL, "maxpool_bwd: null argument");
-  int rc = check_pool_plan(plan, "maxpool_bwd");
+static int pool_bwd(distdl_plan* plan, const void* const x_bufs_dev[], const void* const dy_dev[],
+                    void* const dx_bufs_dev[], bool avg, hipStream_t st) {
+  const char* what = avg ? "avgpool_bwd" : "maxpool_bwd";
+  if (!plan || (!avg && !x_bufs_dev) || !dy_dev || !dx_bufs_dev) return set_error(DISTDL_ERR_NULL, "%s: null argument", what);
+  int rc = check_pool_plan(plan, what);
   if (rc) return rc;
-  if ((rc = check_list(x_bufs_dev, plan->n_workers, "maxpool_bwd x")) ||
-      (rc = check_list(dy_dev, plan->n_workers, "maxpool_bwd dy")) ||
-      (rc = check_list((const void* const*)dx_bufs_dev, plan->n_workers, "maxpool_bwd dx")))
+  if ((!avg && (rc = check_list(x_bufs_dev, plan->n_workers, what))) || (rc = check_list(dy_dev, plan->n_workers, what)) ||
+      (rc = check_list((const void* const*)dx_bufs_dev, plan->n_workers, what)))
     return rc;
-  hipStream_t st = (hipStream_t)stream;
   if ((rc = plan_prepare_device(plan))) return rc;
-  if ((rc = plan->tab_x.upload(x_bufs_dev, plan->n_workers, st)) || (rc = plan->tab_dy.upload(dy_dev, plan->n_workers, st)) ||
+  if ((!avg && (rc = plan->tab_x.upload(x_bufs_dev, plan->n_workers, st))) ||
+      (rc = plan->tab_dy.upload(dy_dev, plan->n_workers, st)) ||
       (rc = plan->tab_dx.upload((const void* const*)dx_bufs_dev, plan->n_workers, st)))
     return rc;
   PoolDev d = pool_params(plan);
   int64_t total = plan->n_b * plan->max_buf_cells * d.c;
   {
-    ProfScope prof("maxpool_bwd", st);
-    hipLaunchKernelGGL(maxpool_bwd_kernel, dim3((unsigned)((total + 255) / 256), plan->n_workers), dim3(256), 0, st,
-                       plan->d_workers, plan->tab_x.dev, plan->tab_dy.dev, plan->tab_dx.dev, d);
+    ProfScope prof(what, st);
+    dim3 grid((unsigned)((total + 255) / 256), plan->n_workers);
+    if (avg)
+      hipLaunchKernelGGL(pool_bwd_kernel<true>, grid, dim3(256), 0, st, plan->d_workers, (void* const*)nullptr,
+                         plan->tab_dy.dev, plan->tab_dx.dev, d);
+    else
+      hipLaunchKernelGGL(pool_bwd_kernel<false>, grid, dim3(256), 0, st, plan->d_workers, plan->tab_x.dev,
+                         plan->tab_dy.dev, plan->tab_dx.dev, d);
   }
   DISTDL_HIP_TRY(hipGetLastError());
   return run_halo(plan, true, plan->tab_dx, dx_bufs_dev, st);  // dx <- H* dx
+}
+
+int distdl_maxpool_fwd(distdl_plan* plan, void* const x_bufs_dev[], void* const y_dev[], void* stream) {
+  return pool_fwd(plan, x_bufs_dev, y_dev, false, (hipStream_t)stream);
+}
+
+int distdl_maxpool_bwd(distdl_plan* plan, const void* const x_bufs_dev[], const void* const dy_dev[],
+                       void* const dx_bufs_dev[], void* stream) {
+  return pool_bwd(plan, x_bufs_dev, dy_dev, dx_bufs_dev, false, (hipStream_t)stream);
+}
+
+int distdl_avgpool_fwd(distdl_plan* plan, void* const x_bufs_dev[], void* const y_dev[], void* stream) {
+  return pool_fwd(plan, x_bufs_dev, y_dev, true, (hipStream_t)stream);
+}
+
+int distdl_avgpool_bwd(distdl_plan* plan, const void* const dy_dev[], void* const dx_bufs_dev[], void* stream) {
+  return pool_bwd(plan, nullptr, dy_dev, dx_bufs_dev, true, (hipStream_t)stream);
 }
 
 int distdl_bulk_copy(distdl_plan* plan, void* const dense_dev[], void* const bufs_dev[], int to_bufs, void* stream) {

@@ -212,6 +212,33 @@ def test_maxpool_tie_goes_to_first_tap():
     assert np.array_equal(dxp[0, 0], [[1, 0], [0, 0]])
 
 
+@pytest.mark.parametrize("n,P,k,s,p", [((28, 28), (2, 2), (2, 2), (2, 2), (0, 0)), ((10, 20), (3, 6), (2, 2), (2, 2), (0, 0)),
+                                       ((13, 11), (2, 2), (3, 3), (2, 2), (1, 1)), ((12,), (3,), (4,), (2,), (1,))])
+def test_distributed_avgpool_equals_library_pool_and_is_adjoint(n, P, k, s, p):
+    """Pinned against torch's avg_pool (zero padding counted in the divisor) and its autograd, against the
+    reshape-mean closed form when windows tile the input, and by the dot-product test of the whole operator."""
+    D = len(n)
+    part = geo.Partition.for_kernel(n, P, k, s, p, (1,) * D)
+    x = RNG.standard_normal((2, 3) + n)
+    tx = T(x).requires_grad_(True)
+    pool = F.avg_pool2d if D == 2 else F.avg_pool1d
+    ty = pool(tx, k, s, p, count_include_pad=True)
+    dy = RNG.standard_normal(tuple(ty.shape))
+    ty.backward(T(dy))
+    bufs = prim.scatter_bulk(x, part, fill=np.nan)
+    ys = layers.dist_avgpool_forward(bufs, part, k, s)
+    np.testing.assert_allclose(prim.gather_out(ys, part), ty.detach().numpy(), rtol=0, atol=1e-14)
+    dx = layers.dist_avgpool_adjoint(prim.scatter_out(dy, part), part, [b.shape for b in bufs], k, s)
+    np.testing.assert_allclose(prim.gather_bulk(dx, part), tx.grad.numpy(), rtol=0, atol=1e-14)
+    if k == s and all(pp == 0 for pp in p) and all(nn % kk == 0 for nn, kk in zip(n, k)):
+        blocks = x.reshape(2, 3, n[0] // k[0], k[0], n[1] // k[1], k[1]).mean(axis=(3, 5))
+        np.testing.assert_allclose(prim.gather_out(ys, part), blocks, rtol=0, atol=1e-14)
+    # <Pool x, dy> == <x, Pool* dy> on the partitioned spaces (halo and pad cells of x do not matter: H overwrites them)
+    lhs = sum(np.sum(a * b) for a, b in zip(ys, prim.scatter_out(dy, part)))
+    rhs = np.sum(prim.gather_bulk(dx, part) * x)
+    assert abs(lhs - rhs) <= 1e-12 * max(abs(lhs), 1.0)
+
+
 def test_relu_and_mse():
     x = np.array([-1.0, 0.0, 2.0])
     assert np.array_equal(layers.relu(x), [0, 0, 2])
