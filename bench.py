@@ -280,6 +280,49 @@ class MovementWorkload:
                     rows.append({"op": direction, "k": k, "MiB_per_replica": mib, "ms": round(ms, 5),
                                  "GB/s": round(gbs, 1), "frac_hbm_peak": round(gbs / HBM_PEAK_GBS, 3),
                                  "cache_resident": per_set * 4 * nsets <= (256 << 20)})
+        del pool, sets
+        torch.cuda.empty_cache()
+
+        def timed(name, call, nbytes, reps=6, extra=None):
+            for _ in range(2):
+                call()
+            torch.cuda.synchronize()
+            dd.distdl_profile_report()
+            for _ in range(reps):
+                call()
+            rep = dd.distdl_profile_report()
+            ms = sum(v[1] for v in rep.values()) / reps
+            row = {"op": name, "ms": round(ms, 5), "GB/s": round(nbytes / (ms * 1e-3) / 1e9, 1),
+                   "frac_hbm_peak": round(nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 3), "algorithmic_bytes": nbytes,
+                   "kernels": {k: round(v[1] / reps, 5) for k, v in rep.items()}}
+            row.update(extra or {})
+            rows.append(row)
+
+        # all-reduce A = B R in place over k = 4 replicas of 256 MiB: k reads + k writes
+        reps4 = [_dev_randn((1 << 26,), 70 + i) for i in range(4)]
+        timed("allreduce", lambda: dd.distdl_allreduce(reps4, 4), 2 * 4 * (1 << 28), extra={"k": 4, "MiB_per_replica": 256})
+        del reps4
+        # generalized all-to-all of a 1 GiB tensor: spatial 4 x 4 blocks -> (batch, channel) 4 x 4 blocks
+        shape = (32, 32, 512, 512)
+        rp = dd.distdl_repart_plan_create(shape, (1, 1, 4, 4), (4, 4, 1, 1))
+        src = [_dev_randn(sz, 80 + w) for w, (_, sz) in enumerate(rp.blocks(0))]
+        dst = [torch.empty(sz, device="cuda") for (_, sz) in rp.blocks(1)]
+        timed("repart_fwd", lambda: dd.distdl_repart_fwd(rp, src, dst), 2 * 4 * _prod(shape), extra={"shape": list(shape)})
+        timed("repart_adj", lambda: dd.distdl_repart_adj(rp, dst, src), 2 * 4 * _prod(shape), extra={"shape": list(shape)})
+        del src, dst
+        # pooling 2^3 / stride 2 on the volumetric input, 4 x 4 x 4 workers (no halos: reads the input, writes 1/8)
+        c = self.cfg
+        pp = dd.distdl_plan_create(3, 1, c["c_in"], c["c_in"], c["in_shape"], c["P"], (2, 2, 2), (2, 2, 2), (0, 0, 0), (1, 1, 1))
+        geoms = [pp.query(w) for w in range(pp.n_workers)]
+        px = [_dev_randn([1] + g["buf_shape"] + [c["c_in"]], 90 + w) for w, g in enumerate(geoms)]
+        py = [torch.empty([1] + g["out_size"] + [c["c_in"]], device="cuda") for g in geoms]
+        pdx = [torch.empty_like(t) for t in px]
+        n_in = sum(t.numel() for t in px) * 4
+        n_out = sum(t.numel() for t in py) * 4
+        timed("maxpool_fwd", lambda: dd.distdl_maxpool_fwd(pp, px, py), n_in + n_out)
+        timed("avgpool_fwd", lambda: dd.distdl_avgpool_fwd(pp, px, py), n_in + n_out)
+        timed("maxpool_bwd", lambda: dd.distdl_maxpool_bwd(pp, px, py, pdx), 2 * n_in + n_out)
+        timed("avgpool_bwd", lambda: dd.distdl_avgpool_bwd(pp, py, pdx), n_in + n_out)
         dd.distdl_profile_enable(False)
         return rows
 

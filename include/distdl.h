@@ -241,6 +241,35 @@ int distdl_mse_fwd_bwd(const void* const y_dev[], const void* const t_dev[], voi
                        const int64_t count[], int n, double* loss_dev, void* stream);
 
 /* ------------------------------------------------------------------------
+ * Generalized all-to-all / repartition (Sec. 3, the "all-to-all" that
+ * re-partitions a tensor; App. C uses it between the convolutional and the
+ * dense layers).  A tensor of rank R <= 4 and the given shape is held as one
+ * dense row-major block per worker of a partition P_src (worker id row-major
+ * over P_src, every dimension split by the balanced rule: block r of a length
+ * L gets floor(L / P) + (r < L mod P) entries); repart_fwd re-cuts it into
+ * the blocks of partition P_dst.  It is a permutation of the elements, so
+ * repart_adj (the adjoint) is the inverse: it takes blocks of P_dst and
+ * writes the blocks of P_src.  Outputs are overwritten in full.
+ *   repart_plan_block: start[R] / size[R] of block `worker` of side 0 (P_src)
+ *   or 1 (P_dst); repart_plan_num_blocks: number of blocks of that side.
+ *   src_dev / dst_dev: one device pointer per block of the respective side,
+ *   element-aligned; 16-byte accesses are used when every pointer is 16-byte
+ *   aligned and every block row and intersection is a whole number of
+ *   16-byte vectors.  Source and destination blocks must not overlap.
+ * Errors: INVALID_ARG for bad rank / extents, EMPTY_PARTITION when a dimension
+ * is split into more parts than it has entries, UNSUPPORTED for blocks beyond
+ * 2^32 elements per leading index, NULL for null or misaligned pointers.
+ * ---------------------------------------------------------------------- */
+typedef struct distdl_repart_plan distdl_repart_plan;
+int distdl_repart_plan_create(distdl_repart_plan** out, int R, const int64_t shape[], const int32_t P_src[],
+                              const int32_t P_dst[], distdl_dtype dtype);
+int distdl_repart_plan_destroy(distdl_repart_plan* plan);
+int distdl_repart_plan_num_blocks(const distdl_repart_plan* plan, int side);
+int distdl_repart_plan_block(const distdl_repart_plan* plan, int side, int worker, int64_t start[], int64_t size[]);
+int distdl_repart_fwd(distdl_repart_plan* plan, const void* const src_dev[], void* const dst_dev[], void* stream);
+int distdl_repart_adj(distdl_repart_plan* plan, const void* const gdst_dev[], void* const gsrc_dev[], void* stream);
+
+/* ------------------------------------------------------------------------
  * All-reduce A = B R (Sec. 3 "Sum-reduce and all-reduce": the sum-reduction
  * composed with the broadcast; self-adjoint).  In place: every one of the k
  * replicas of group g, bufs_dev[g*k + i], ends as the sum of the group's

@@ -333,3 +333,31 @@ def expected_buffer_after_halo(x_global, part, w):
     sl = (slice(None), slice(None))
     out[sl + dst] = x_global[sl + src]
     return out
+
+
+# --------------------------------------------------------------------------
+# generalized all-to-all: the same tensor under another partition
+# --------------------------------------------------------------------------
+
+
+def partition_blocks(shape, P):
+    """Per worker (row-major over the partition vector P) the tuple of slices
+    of its block of a tensor of the given shape, every dimension split by the
+    balanced rule."""
+    import itertools
+    from . import geometry as geo
+    splits = [geo.balanced_split(int(n), int(p)) for n, p in zip(shape, P)]
+    return [tuple(slice(splits[d][c][0], splits[d][c][0] + splits[d][c][1]) for d, c in enumerate(coords))
+            for coords in itertools.product(*[range(int(p)) for p in P])]
+
+
+def repartition(blocks_src, shape, P_src, P_dst):
+    """Generalized all-to-all of Sec. 3 ("all-to-all" / repartition): the
+    tensor held as blocks of partition P_src, re-cut into the blocks of
+    partition P_dst.  Stated through the global tensor: gather, then scatter
+    (Sec. 3 "Scatter and Gather").  A permutation of the elements, so its
+    adjoint is the inverse: repartition(., shape, P_dst, P_src)."""
+    full = np.empty(tuple(int(n) for n in shape), dtype=np.asarray(blocks_src[0]).dtype)
+    for blk, sl in zip(blocks_src, partition_blocks(shape, P_src)):
+        full[sl] = blk
+    return [full[sl].copy() for sl in partition_blocks(shape, P_dst)]

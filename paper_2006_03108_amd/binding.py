@@ -49,6 +49,12 @@ _SIGS = {
     "distdl_sumreduce_fwd": [_pp, _pp, _p64, _i, _i, _i, _i, _vp],
     "distdl_sumreduce_adj": [_pp, _pp, _p64, _i, _i, _i, _vp],
     "distdl_allreduce": [_pp, _p64, _i, _i, _i, _vp],
+    "distdl_repart_plan_create": [C.POINTER(_vp), _i, _p64, C.POINTER(C.c_int32), C.POINTER(C.c_int32), _i],
+    "distdl_repart_plan_destroy": [_vp],
+    "distdl_repart_plan_num_blocks": [_vp, _i, ],
+    "distdl_repart_plan_block": [_vp, _i, _i, _p64, _p64],
+    "distdl_repart_fwd": [_vp, _pp, _pp, _vp],
+    "distdl_repart_adj": [_vp, _pp, _pp, _vp],
     "distdl_conv_fwd": [_vp, _pp, _vp, _vp, _pp, _vp],
     "distdl_conv_bwd": [_vp, _pp, _vp, _pp, _pp, _vp, _vp, _vp, C.c_size_t, _vp],
     "distdl_affine_plan_create": [C.POINTER(_vp), _i64, _i64, _i64, _i, _i, _i],
@@ -199,6 +205,42 @@ def distdl_allreduce(bufs, k):
     G = len(bufs) // k
     counts = _arr(C.c_int64, [bufs[g * k].numel() for g in range(G)])
     _check(lib.distdl_allreduce(_ptrs(bufs), counts, G, k, _dtype_code(bufs[0].dtype), _stream()))
+
+
+class RepartPlan:
+    """Owner of a distdl_repart_plan handle."""
+
+    def __init__(self, handle, R):
+        self.handle, self.R = handle, R
+
+    def blocks(self, side):
+        """[(start tuple, size tuple)] of every block of side 0 (source) or 1 (destination)."""
+        out = []
+        for w in range(_check(lib.distdl_repart_plan_num_blocks(self.handle, side))):
+            st, sz = (C.c_int64 * self.R)(), (C.c_int64 * self.R)()
+            _check(lib.distdl_repart_plan_block(self.handle, side, w, st, sz))
+            out.append((tuple(st), tuple(sz)))
+        return out
+
+    def __del__(self):
+        if getattr(self, "handle", None):
+            lib.distdl_repart_plan_destroy(self.handle)
+            self.handle = None
+
+
+def distdl_repart_plan_create(shape, P_src, P_dst, dtype=torch.float32):
+    h = C.c_void_p()
+    _check(lib.distdl_repart_plan_create(C.byref(h), len(shape), _arr(C.c_int64, shape), _arr(C.c_int32, P_src),
+                                         _arr(C.c_int32, P_dst), _dtype_code(dtype)))
+    return RepartPlan(h, len(shape))
+
+
+def distdl_repart_fwd(plan, src, dst):
+    _check(lib.distdl_repart_fwd(plan.handle, _ptrs(src), _ptrs(dst), _stream()))
+
+
+def distdl_repart_adj(plan, gdst, gsrc):
+    _check(lib.distdl_repart_adj(plan.handle, _ptrs(gdst), _ptrs(gsrc), _stream()))
 
 
 def distdl_conv_bwd_workspace(plan):

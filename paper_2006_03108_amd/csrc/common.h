@@ -160,6 +160,7 @@ struct distdl_plan {
 
   // weight re-layout scratch for the convolution kernels (library-owned)
   float* d_wt = nullptr;
+  distdl::FastDiv* d_pooldiv = nullptr;  // per worker: division by buf[1], buf[2], out[1], out[2] (pooling kernels)
   size_t wt_elems = 0;
 
   int coords(int w, int d) const {

@@ -3,6 +3,7 @@
 // fp32, channels-last.  These calls are small and latency-bound; they exist so that a whole partitioned
 // network step can run through the library.
 #include <algorithm>
+#include <vector>
 
 #include "common.h"
 #include "profile.h"
@@ -67,6 +68,7 @@ static int run_elementwise(const void* const a[], const void* const b[], void* c
 struct PoolDev {
   int32_t n_b, c;
   int32_t k[3], s[3], dil[3];
+  FastDiv div_c4, div_s[3];  // by c / 4 and by the strides (vector kernels)
 };
 
 static PoolDev pool_params(const distdl_plan* p) {
@@ -78,6 +80,8 @@ static PoolDev pool_params(const distdl_plan* p) {
     d.s[i] = p->stride[i];
     d.dil[i] = p->dilation[i];
   }
+  d.div_c4 = make_fastdiv((uint32_t)std::max<int64_t>(1, p->n_ci / 4));
+  for (int i = 0; i < 3; ++i) d.div_s[i] = make_fastdiv((uint32_t)p->stride[i]);
   return d;
 }
 
@@ -162,6 +166,126 @@ __global__ __launch_bounds__(256) void pool_bwd_kernel(const WorkerDev* __restri
         if (arg == tap) acc += dy[n * son + o0 * so0 + o1 * so1 + o2 * so2 + c];
       }
   dx[idx] = AVG ? acc / (float)(d.k[0] * d.k[1] * d.k[2]) : acc;
+}
+
+// Faster forms for channel counts that are multiples of 4 and 16-byte aligned buffers: a thread owns four
+// channels of one cell (one 16-byte access per tap).
+template <bool AVG>
+__global__ __launch_bounds__(256) void pool_fwd_vec_kernel(const WorkerDev* __restrict__ workers,
+                                                           const FastDiv* __restrict__ divs, void* const* x_bufs,
+                                                           void* const* y_bufs, PoolDev d) {
+  const WorkerDev wd = workers[blockIdx.y];
+  const FastDiv div_o1 = divs[blockIdx.y * 4 + 2], div_o2 = divs[blockIdx.y * 4 + 3];
+  const int c4 = d.c >> 2;
+  const int64_t total = (int64_t)d.n_b * wd.out[0] * wd.out[1] * wd.out[2] * c4;  // < 2^32 (host check)
+  const uint32_t idx = blockIdx.x * 256u + threadIdx.x;
+  if (idx >= total) return;
+  const float4* __restrict__ x = (const float4*)x_bufs[blockIdx.y];
+  float4* __restrict__ y = (float4*)y_bufs[blockIdx.y];
+  uint32_t r = fd_div(idx, d.div_c4);
+  const int c = (int)(idx - r * c4);
+  uint32_t q = fd_div(r, div_o2);
+  const int o2 = (int)(r - q * wd.out[2]);
+  r = fd_div(q, div_o1);
+  const int o1 = (int)(q - r * wd.out[1]);
+  const int n = (int)(r / (uint32_t)wd.out[0]), o0 = (int)(r - (uint32_t)n * wd.out[0]);
+  const int64_t s2 = c4, s1 = (int64_t)wd.buf[2] * s2, s0 = (int64_t)wd.buf[1] * s1, sn = (int64_t)wd.buf[0] * s0;
+  float4 best = make_float4(0.f, 0.f, 0.f, 0.f), sum = best;
+  bool first = true;
+  for (int t0 = 0; t0 < d.k[0]; ++t0)
+    for (int t1 = 0; t1 < d.k[1]; ++t1)
+      for (int t2 = 0; t2 < d.k[2]; ++t2) {
+        const float4 v = x[n * sn + (wd.origin[0] + o0 * d.s[0] + t0 * d.dil[0]) * s0 +
+                           (wd.origin[1] + o1 * d.s[1] + t1 * d.dil[1]) * s1 +
+                           (wd.origin[2] + o2 * d.s[2] + t2 * d.dil[2]) * s2 + c];
+        if (first || v.x > best.x) best.x = v.x;
+        if (first || v.y > best.y) best.y = v.y;
+        if (first || v.z > best.z) best.z = v.z;
+        if (first || v.w > best.w) best.w = v.w;
+        sum.x += v.x; sum.y += v.y; sum.z += v.z; sum.w += v.w;  // row-major tap order
+        first = false;
+      }
+  const float inv = (float)(d.k[0] * d.k[1] * d.k[2]);
+  y[idx] = AVG ? make_float4(sum.x / inv, sum.y / inv, sum.z / inv, sum.w / inv) : best;
+}
+
+// [dPool]* for windows that do not overlap (stride >= kernel extent, no dilation), in two kernels that
+// together write every cell of dx once.  pool_bwd_window_kernel: a thread owns one window (four channels):
+// it reads the window once, finds the first maximum per channel (the mean needs no read) and writes every tap
+// of the window, dy or zero (dy / window size for the mean).  pool_bwd_uncovered_kernel: the cells that lie
+// in no window ("extra" input, the gaps of a stride larger than the kernel, the buffer's tail) are cleared.
+template <bool AVG>
+__global__ __launch_bounds__(256) void pool_bwd_window_kernel(const WorkerDev* __restrict__ workers,
+                                                              const FastDiv* __restrict__ divs, void* const* x_bufs,
+                                                              void* const* dy_bufs, void* const* dx_bufs, PoolDev d) {
+  const WorkerDev wd = workers[blockIdx.y];
+  const FastDiv div_o1 = divs[blockIdx.y * 4 + 2], div_o2 = divs[blockIdx.y * 4 + 3];
+  const int c4 = d.c >> 2;
+  const int64_t total = (int64_t)d.n_b * wd.out[0] * wd.out[1] * wd.out[2] * c4;  // < 2^32 (host check)
+  const uint32_t idx = blockIdx.x * 256u + threadIdx.x;
+  if (idx >= total) return;
+  const float4* __restrict__ x = AVG ? nullptr : (const float4*)x_bufs[blockIdx.y];
+  const float4* __restrict__ dy = (const float4*)dy_bufs[blockIdx.y];
+  float4* __restrict__ dx = (float4*)dx_bufs[blockIdx.y];
+  uint32_t r = fd_div(idx, d.div_c4);
+  const int c = (int)(idx - r * c4);
+  uint32_t q = fd_div(r, div_o2);
+  const int o2 = (int)(r - q * wd.out[2]);
+  r = fd_div(q, div_o1);
+  const int o1 = (int)(q - r * wd.out[1]);
+  const int n = (int)(r / (uint32_t)wd.out[0]), o0 = (int)(r - (uint32_t)n * wd.out[0]);
+  const int64_t s2 = c4, s1 = (int64_t)wd.buf[2] * s2, s0 = (int64_t)wd.buf[1] * s1, sn = (int64_t)wd.buf[0] * s0;
+  const int64_t base = n * sn + (wd.origin[0] + o0 * d.s[0]) * s0 + (wd.origin[1] + o1 * d.s[1]) * s1 +
+                       (wd.origin[2] + o2 * d.s[2]) * s2 + c;
+  const float4 g = dy[idx];
+  int ax = 0, ay = 0, az = 0, aw = 0;  // tap of the first maximum, per channel
+  if (!AVG) {
+    float4 best = make_float4(0.f, 0.f, 0.f, 0.f);
+    int u = 0;
+    for (int u0 = 0; u0 < d.k[0]; ++u0)
+      for (int u1 = 0; u1 < d.k[1]; ++u1)
+        for (int u2 = 0; u2 < d.k[2]; ++u2, ++u) {
+          const float4 v = x[base + u0 * s0 + u1 * s1 + u2 * s2];
+          if (u == 0 || v.x > best.x) best.x = v.x, ax = u;
+          if (u == 0 || v.y > best.y) best.y = v.y, ay = u;
+          if (u == 0 || v.z > best.z) best.z = v.z, az = u;
+          if (u == 0 || v.w > best.w) best.w = v.w, aw = u;
+        }
+  }
+  const float inv = (float)(d.k[0] * d.k[1] * d.k[2]);
+  const float4 share = make_float4(g.x / inv, g.y / inv, g.z / inv, g.w / inv);
+  int u = 0;
+  for (int u0 = 0; u0 < d.k[0]; ++u0)
+    for (int u1 = 0; u1 < d.k[1]; ++u1)
+      for (int u2 = 0; u2 < d.k[2]; ++u2, ++u)
+        dx[base + u0 * s0 + u1 * s1 + u2 * s2] =
+            AVG ? share : make_float4(u == ax ? g.x : 0.f, u == ay ? g.y : 0.f, u == az ? g.z : 0.f, u == aw ? g.w : 0.f);
+}
+
+__global__ __launch_bounds__(256) void pool_bwd_uncovered_kernel(const WorkerDev* __restrict__ workers,
+                                                                 const FastDiv* __restrict__ divs, void* const* dx_bufs,
+                                                                 PoolDev d) {
+  const WorkerDev wd = workers[blockIdx.y];
+  const FastDiv div_b1 = divs[blockIdx.y * 4 + 0], div_b2 = divs[blockIdx.y * 4 + 1];
+  const int c4 = d.c >> 2;
+  const int64_t total = (int64_t)d.n_b * wd.buf[0] * wd.buf[1] * wd.buf[2] * c4;  // < 2^32 (host check)
+  const uint32_t idx = blockIdx.x * 256u + threadIdx.x;
+  if (idx >= total) return;
+  uint32_t r = fd_div(idx, d.div_c4);
+  uint32_t q = fd_div(r, div_b2);
+  const int c2 = (int)(r - q * wd.buf[2]);
+  r = fd_div(q, div_b1);
+  const int c1 = (int)(q - r * wd.buf[1]);
+  const int c0 = (int)(r % (uint32_t)wd.buf[0]);
+  const int q0 = c0 - wd.origin[0], q1 = c1 - wd.origin[1], q2 = c2 - wd.origin[2];
+  bool covered = q0 >= 0 && q1 >= 0 && q2 >= 0;
+  if (covered) {
+    const int o0 = (int)fd_div((uint32_t)q0, d.div_s[0]), o1 = (int)fd_div((uint32_t)q1, d.div_s[1]),
+              o2 = (int)fd_div((uint32_t)q2, d.div_s[2]);
+    covered = q0 - o0 * d.s[0] < d.k[0] && q1 - o1 * d.s[1] < d.k[1] && q2 - o2 * d.s[2] < d.k[2] && o0 < wd.out[0] &&
+              o1 < wd.out[1] && o2 < wd.out[2];
+  }
+  if (!covered) ((float4*)dx_bufs[blockIdx.y])[idx] = make_float4(0.f, 0.f, 0.f, 0.f);
 }
 
 // dense [n][in_size..][c] <-> bulk of the padded buffer
@@ -267,6 +391,28 @@ static int check_pool_plan(const distdl_plan* p, const char* what) {
   return DISTDL_OK;
 }
 
+// division constants of every worker's buffer and output extents, built on first use
+static int ensure_pooldiv(distdl_plan* p) {
+  if (p->d_pooldiv) return DISTDL_OK;
+  std::vector<FastDiv> h((size_t)p->n_workers * 4);
+  for (int w = 0; w < p->n_workers; ++w) {
+    const WorkerDev& wd = p->workers[w];
+    h[w * 4 + 0] = make_fastdiv((uint32_t)wd.buf[1]);
+    h[w * 4 + 1] = make_fastdiv((uint32_t)wd.buf[2]);
+    h[w * 4 + 2] = make_fastdiv((uint32_t)wd.out[1]);
+    h[w * 4 + 3] = make_fastdiv((uint32_t)wd.out[2]);
+  }
+  DISTDL_HIP_TRY(hipMalloc((void**)&p->d_pooldiv, h.size() * sizeof(FastDiv)));
+  DISTDL_HIP_TRY(hipMemcpy(p->d_pooldiv, h.data(), h.size() * sizeof(FastDiv), hipMemcpyHostToDevice));
+  return DISTDL_OK;
+}
+
+static bool all_aligned16(const void* const* v, int n) {
+  for (int i = 0; i < n; ++i)
+    if ((uintptr_t)v[i] % 16) return false;
+  return true;
+}
+
 static int check_list(const void* const* v, int n, const char* what) {
   for (int i = 0; i < n; ++i)
     if (!v[i] || (uintptr_t)v[i] % 4) return set_error(DISTDL_ERR_NULL, "%s: array %d null or misaligned", what, i);
@@ -300,6 +446,15 @@ static int pool_fwd(distdl_plan* plan, void* const x_bufs_dev[], void* const y_d
   PoolDev d = pool_params(plan);
   int64_t total = plan->n_b * plan->max_out_cells * d.c;
   ProfScope prof(what, st);
+  if (d.c % 4 == 0 && all_aligned16((const void* const*)x_bufs_dev, plan->n_workers) &&
+      all_aligned16((const void* const*)y_dev, plan->n_workers) && total / 4 < (int64_t(1) << 31) &&
+      ensure_pooldiv(plan) == DISTDL_OK) {
+    dim3 grid((unsigned)((total / 4 + 255) / 256), plan->n_workers);
+    if (avg) hipLaunchKernelGGL(pool_fwd_vec_kernel<true>, grid, dim3(256), 0, st, plan->d_workers, plan->d_pooldiv, plan->tab_x.dev, plan->tab_y.dev, d);
+    else hipLaunchKernelGGL(pool_fwd_vec_kernel<false>, grid, dim3(256), 0, st, plan->d_workers, plan->d_pooldiv, plan->tab_x.dev, plan->tab_y.dev, d);
+    DISTDL_HIP_TRY(hipGetLastError());
+    return DISTDL_OK;
+  }
   dim3 grid((unsigned)((total + 255) / 256), plan->n_workers);
   if (avg) hipLaunchKernelGGL(pool_fwd_kernel<true>, grid, dim3(256), 0, st, plan->d_workers, plan->tab_x.dev, plan->tab_y.dev, d);
   else hipLaunchKernelGGL(pool_fwd_kernel<false>, grid, dim3(256), 0, st, plan->d_workers, plan->tab_x.dev, plan->tab_y.dev, d);
@@ -325,6 +480,24 @@ static int pool_bwd(distdl_plan* plan, const void* const x_bufs_dev[], const voi
   int64_t total = plan->n_b * plan->max_buf_cells * d.c;
   {
     ProfScope prof(what, st);
+    bool tiled = d.c % 4 == 0 && all_aligned16(dy_dev, plan->n_workers) &&
+                 all_aligned16((const void* const*)dx_bufs_dev, plan->n_workers) &&
+                 (avg || all_aligned16(x_bufs_dev, plan->n_workers));
+    for (int i = 0; i < 3; ++i) tiled = tiled && d.dil[i] == 1 && d.s[i] >= d.k[i];
+    tiled = tiled && total / 4 < (int64_t(1) << 31) && ensure_pooldiv(plan) == DISTDL_OK;
+    if (tiled) {
+      const int64_t wtotal = plan->n_b * plan->max_out_cells * (d.c / 4);
+      dim3 wgrid((unsigned)((wtotal + 255) / 256), plan->n_workers);
+      dim3 ugrid((unsigned)((total / 4 + 255) / 256), plan->n_workers);
+      if (avg)
+        hipLaunchKernelGGL(pool_bwd_window_kernel<true>, wgrid, dim3(256), 0, st, plan->d_workers, plan->d_pooldiv,
+                           (void* const*)nullptr, plan->tab_dy.dev, plan->tab_dx.dev, d);
+      else
+        hipLaunchKernelGGL(pool_bwd_window_kernel<false>, wgrid, dim3(256), 0, st, plan->d_workers, plan->d_pooldiv,
+                           plan->tab_x.dev, plan->tab_dy.dev, plan->tab_dx.dev, d);
+      hipLaunchKernelGGL(pool_bwd_uncovered_kernel, ugrid, dim3(256), 0, st, plan->d_workers, plan->d_pooldiv,
+                         plan->tab_dx.dev, d);
+    } else {
     dim3 grid((unsigned)((total + 255) / 256), plan->n_workers);
     if (avg)
       hipLaunchKernelGGL(pool_bwd_kernel<true>, grid, dim3(256), 0, st, plan->d_workers, (void* const*)nullptr,
@@ -332,6 +505,7 @@ static int pool_bwd(distdl_plan* plan, const void* const x_bufs_dev[], const voi
     else
       hipLaunchKernelGGL(pool_bwd_kernel<false>, grid, dim3(256), 0, st, plan->d_workers, plan->tab_x.dev,
                          plan->tab_dy.dev, plan->tab_dx.dev, d);
+    }
   }
   DISTDL_HIP_TRY(hipGetLastError());
   return run_halo(plan, true, plan->tab_dx, dx_bufs_dev, st);  // dx <- H* dx

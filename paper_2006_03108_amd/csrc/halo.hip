@@ -224,6 +224,21 @@ static void launch(bool adjoint, const TaskTable& tt, const distdl_plan* p, void
     hipLaunchKernelGGL(halo_fwd_kernel<E>, grid, block, 0, st, tt.d_blocks, tt.d_tasks, bufs);
 }
 
+// Copy boxes between arbitrary buffers with the forward kernel (used by the generalized repartition): the
+// tasks' views index one pointer table that holds sources and destinations; unit_bytes is 16, 4 or 2.
+int run_box_copy(int unit_bytes, const BlockRef* d_blocks, const HaloTaskDev* d_tasks, size_t nblocks, void* const* d_bufs,
+                 const char* name, hipStream_t st) {
+  if (nblocks == 0) return DISTDL_OK;
+  dim3 grid((unsigned)nblocks), block(kThreads);
+  ProfScope prof(name, st);
+  if (unit_bytes == 16) hipLaunchKernelGGL(halo_fwd_kernel<F32x4>, grid, block, 0, st, d_blocks, d_tasks, d_bufs);
+  else if (unit_bytes == 4) hipLaunchKernelGGL(halo_fwd_kernel<F32x1>, grid, block, 0, st, d_blocks, d_tasks, d_bufs);
+  else if (unit_bytes == 2) hipLaunchKernelGGL(halo_fwd_kernel<BF16x1>, grid, block, 0, st, d_blocks, d_tasks, d_bufs);
+  else return set_error(DISTDL_ERR_INVALID_ARG, "internal: box copy unit of %d bytes", unit_bytes);
+  DISTDL_HIP_TRY(hipGetLastError());
+  return DISTDL_OK;
+}
+
 // Shared by the public halo calls and by conv_fwd / conv_bwd.
 int run_halo(distdl_plan* p, bool adjoint, PtrTable& tab, void* const* bufs_host, hipStream_t st) {
   int rc = plan_prepare_device(p);

@@ -615,6 +615,7 @@ int distdl_plan_destroy(distdl_plan* plan) {
   plan->tab_dy.release();
   if (plan->d_workers) (void)hipFree(plan->d_workers);
   if (plan->d_wt) (void)hipFree(plan->d_wt);
+  if (plan->d_pooldiv) (void)hipFree(plan->d_pooldiv);
   delete plan;
   return DISTDL_OK;
 }

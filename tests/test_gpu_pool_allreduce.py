@@ -22,6 +22,9 @@ POOL_CASES = [
     (2, 2, 5, (13, 11), (2, 2), (3, 3), (2, 2), (1, 1)),       # overlapping windows with zero padding
     (1, 2, 4, (12,), (3,), (4,), (2,), (1,)),
     (3, 1, 16, (12, 10, 14), (2, 2, 2), (2, 3, 2), (2, 1, 2), (0, 1, 0)),
+    (2, 2, 8, (13, 17), (2, 2), (2, 2), (3, 3), (0, 0)),       # stride > kernel: cells that no window covers
+    (3, 2, 16, (12, 10, 14), (2, 2, 2), (2, 2, 2), (2, 2, 2), (0, 0, 0)),
+    (2, 1, 32, (64, 48), (4, 3), (2, 2), (2, 2), (1, 1)),      # zero padding inside tiled windows
 ]
 
 

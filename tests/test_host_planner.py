@@ -199,3 +199,21 @@ def test_index_decode_division_is_exact():
         for n in edge + [0, d - 1, d, d + 1, 2 * d - 1, 2 * d] + [rnd.randint(0, 2**32 - 1) for _ in range(40)]:
             n &= 0xFFFFFFFF
             assert dd.lib.distdl_debug_fastdiv(n, d) == n // d, (n, d)
+
+
+def test_repartition_plan_blocks_follow_the_balanced_rule_and_errors():
+    """The generalized all-to-all's planner (no GPU): its blocks are the oracle's balanced blocks, row-major."""
+    from oracle import primitives as prim
+    for shape, Ps, Pd in [((3, 10, 9, 8), (1, 2, 3, 2), (3, 1, 2, 4)), ((11,), (4,), (3,)), ((6, 7), (2, 3), (3, 1))]:
+        plan = dd.distdl_repart_plan_create(shape, Ps, Pd)
+        for side, P in ((0, Ps), (1, Pd)):
+            want = [(tuple(s.start for s in sl), tuple(s.stop - s.start for s in sl))
+                    for sl in prim.partition_blocks(shape, P)]
+            assert plan.blocks(side) == want
+    with pytest.raises(dd.DistdlError) as e:
+        dd.distdl_repart_plan_create((3, 4), (4, 1), (1, 1))
+    assert e.value.code == dd.binding.ERR_EMPTY_PARTITION
+    with pytest.raises(dd.DistdlError):
+        dd.distdl_repart_plan_create((3, 4, 5, 6, 7), (1,) * 5, (1,) * 5)
+    with pytest.raises(dd.DistdlError):
+        dd.distdl_repart_plan_create((0, 4), (1, 1), (1, 1))
