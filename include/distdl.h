@@ -241,6 +241,39 @@ int distdl_mse_fwd_bwd(const void* const y_dev[], const void* const t_dev[], voi
                        const int64_t count[], int n, double* loss_dev, void* stream);
 
 /* ------------------------------------------------------------------------
+ * Convolution with the channels partitioned as well (Sec. 4, Forward / Adjoint
+ * Convolution Algorithms on a P_co x P_ci x feature-space partition; the
+ * weights live on the P_co x P_ci grid, the bias on its ci = 0 column), fp32.
+ * Channel blocks follow the balanced rule.  With S = prod P spatial workers:
+ *   x_bufs_dev[j*S + s]: padded buffer [n_b][buf..][ci_j] of input block j on
+ *       spatial worker s (bulk filled; holds H x afterwards, which bwd expects);
+ *   w_dev[i*P_ci + j]:   [co_i][ci_j][taps]; bias_dev[i]: [co_i] or null array;
+ *   y_dev[i*S + s]:      dense [n_b][out..][co_i].
+ * fwd: x_j <- H x_j; y^_ij <- Conv(w_ij, b_i if j == 0; x_j) (the broadcast
+ * of x along P_co is a shared read); y_i <- sum over j in ascending order.
+ * bwd: (dx^_ij, dw_ij, db_i) <- [dConv]*(dy_i), dw_ij / db_i summed over the
+ * spatial workers; dx_j <- sum over i ascending; dx_j <- H* dx_j.  All
+ * outputs are overwritten.  Partial results and the backward workspace are
+ * plan-owned device memory, allocated on first use.
+ * convcp_block_plan returns the sliding-kernel plan of block (i, j) (owned by
+ * the layer plan) for geometry queries; convcp_channels the channel range of
+ * input block (output_side = 0) or output block (1).
+ * ---------------------------------------------------------------------- */
+typedef struct distdl_convcp_plan distdl_convcp_plan;
+int distdl_convcp_plan_create(distdl_convcp_plan** out, int D, int64_t n_b, int64_t n_c_in, int64_t n_c_out,
+                              const int64_t in_shape[], const int32_t P[], int P_co, int P_ci, const int32_t ksize[],
+                              const int32_t stride[], const int32_t padding[], const int32_t dilation[],
+                              distdl_dtype dtype);
+int distdl_convcp_plan_destroy(distdl_convcp_plan* plan);
+const distdl_plan* distdl_convcp_block_plan(const distdl_convcp_plan* plan, int i, int j);
+int distdl_convcp_channels(const distdl_convcp_plan* plan, int output_side, int block, int64_t* start, int64_t* size);
+int distdl_convcp_fwd(distdl_convcp_plan* plan, void* const x_bufs_dev[], const void* const w_dev[],
+                      const void* const bias_dev[], void* const y_dev[], void* stream);
+int distdl_convcp_bwd(distdl_convcp_plan* plan, const void* const x_bufs_dev[], const void* const w_dev[],
+                      const void* const dy_dev[], void* const dx_bufs_dev[], void* const dw_dev[],
+                      void* const dbias_dev[], void* stream);
+
+/* ------------------------------------------------------------------------
  * Generalized all-to-all / repartition (Sec. 3, the "all-to-all" that
  * re-partitions a tensor; App. C uses it between the convolutional and the
  * dense layers).  A tensor of rank R <= 4 and the given shape is held as one

@@ -211,6 +211,68 @@ def dist_conv_adjoint(x_bufs, w, dy_parts, part, stride, dilation, want_bias=Tru
 
 
 # --------------------------------------------------------------------------
+# distributed convolution with the channels partitioned too (P_co, P_ci >= 1)
+# --------------------------------------------------------------------------
+
+
+def dist_conv_cp_forward(x_bufs, w_blocks, b_blocks, part, P_co, P_ci, stride, dilation):
+    """Forward Convolution Algorithm of Sec. 4 on a P_co x P_ci x (feature
+    space) partition.  x_bufs[j][s]: padded buffer of input-channel block j on
+    spatial worker s; w_blocks[i][j]: [co_i, ci_j, k..]; b_blocks[i] (or None)
+    lives on the ci = 0 sub-partition only.  Steps in the paper's order:
+    x <- H x (per channel block); x^ <- B x along P_co; y^_ij <- Conv(w_ij,
+    b_i if j == 0; x^_j) per worker; y_i <- R over j of y^_ij.
+    Returns y[i][s]; x_bufs holds H x afterwards."""
+    S = part.n_workers
+    for j in range(P_ci):
+        prim.halo_exchange(x_bufs[j], part)
+    x_hat = [[prim.broadcast(np.asarray(x_bufs[j][s], dtype=np.float64), P_co) for s in range(S)] for j in range(P_ci)]
+    y = []
+    for i in range(P_co):
+        y_i = []
+        for s in range(S):
+            origin = [part.g(s, d)["origin"] for d in range(part.D)]
+            y_hat = [conv_valid(x_hat[j][s][i], w_blocks[i][j], b_blocks[i] if (b_blocks is not None and j == 0) else None,
+                                part.out_shape(s), stride, dilation, origin) for j in range(P_ci)]
+            y_i.append(prim.sum_reduce(y_hat))
+        y.append(y_i)
+    return y
+
+
+def dist_conv_cp_adjoint(x_bufs, w_blocks, dy, part, P_co, P_ci, stride, dilation, want_bias=True):
+    """Adjoint Convolution Algorithm of Sec. 4 on the same partition:
+    dy^_ij <- B dy_i along P_ci (adjoint of the forward sum-reduce);
+    (dw^_ijs, db^_is, dx^_ijs) <- [dConv]*(dy^_ij) per worker; dx_j <- R over i
+    of dx^_ij (adjoint of the forward broadcast of x); dw_ij, db_i <- R over
+    the spatial workers; dx_j <- H* dx_j.  x_bufs must hold H x.
+    Returns (dx[j][s], dw[i][j], db[i])."""
+    S = part.n_workers
+    dy_hat = [[prim.broadcast(np.asarray(dy[i][s], dtype=np.float64), P_ci) for s in range(S)] for i in range(P_co)]
+    dw = [[None] * P_ci for _ in range(P_co)]
+    db = [None] * P_co
+    dx_hat = [[[None] * S for _ in range(P_co)] for _ in range(P_ci)]
+    for i in range(P_co):
+        for j in range(P_ci):
+            dw_s, db_s = [], []
+            for s in range(S):
+                origin = [part.g(s, d)["origin"] for d in range(part.D)]
+                dxp, dw_k, db_k = conv_valid_adjoint(x_bufs[j][s], w_blocks[i][j], dy_hat[i][s][j], stride, dilation,
+                                                     origin, want_bias and j == 0)
+                dx_hat[j][i][s] = dxp
+                dw_s.append(dw_k)
+                db_s.append(db_k)
+            dw[i][j] = prim.sum_reduce(dw_s)
+            if want_bias and j == 0:
+                db[i] = prim.sum_reduce(db_s)
+    dx = []
+    for j in range(P_ci):
+        dx_j = [prim.sum_reduce([dx_hat[j][i][s] for i in range(P_co)]) for s in range(S)]
+        prim.halo_exchange_adjoint(dx_j, part)
+        dx.append(dx_j)
+    return dx, dw, (db if want_bias else None)
+
+
+# --------------------------------------------------------------------------
 # distributed pooling
 # --------------------------------------------------------------------------
 

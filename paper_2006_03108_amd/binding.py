@@ -49,6 +49,12 @@ _SIGS = {
     "distdl_sumreduce_fwd": [_pp, _pp, _p64, _i, _i, _i, _i, _vp],
     "distdl_sumreduce_adj": [_pp, _pp, _p64, _i, _i, _i, _vp],
     "distdl_allreduce": [_pp, _p64, _i, _i, _i, _vp],
+    "distdl_convcp_plan_create": [C.POINTER(_vp), _i, _i64, _i64, _i64, _p64, _p32, _i, _i, _p32, _p32, _p32, _p32, _i],
+    "distdl_convcp_plan_destroy": [_vp],
+    "distdl_convcp_block_plan": [_vp, _i, _i],
+    "distdl_convcp_channels": [_vp, _i, _i, _p64, _p64],
+    "distdl_convcp_fwd": [_vp, _pp, _pp, _pp, _pp, _vp],
+    "distdl_convcp_bwd": [_vp, _pp, _pp, _pp, _pp, _pp, _pp, _vp],
     "distdl_repart_plan_create": [C.POINTER(_vp), _i, _p64, C.POINTER(C.c_int32), C.POINTER(C.c_int32), _i],
     "distdl_repart_plan_destroy": [_vp],
     "distdl_repart_plan_num_blocks": [_vp, _i, ],
@@ -86,6 +92,7 @@ lib.distdl_conv_bwd_workspace.argtypes = [_vp]
 lib.distdl_conv_bwd_workspace.restype = C.c_size_t
 lib.distdl_debug_fastdiv.argtypes = [C.c_uint32, C.c_uint32]
 lib.distdl_debug_fastdiv.restype = C.c_uint32
+lib.distdl_convcp_block_plan.restype = C.c_void_p
 lib.distdl_last_error.argtypes = []
 lib.distdl_last_error.restype = C.c_char_p
 
@@ -205,6 +212,58 @@ def distdl_allreduce(bufs, k):
     G = len(bufs) // k
     counts = _arr(C.c_int64, [bufs[g * k].numel() for g in range(G)])
     _check(lib.distdl_allreduce(_ptrs(bufs), counts, G, k, _dtype_code(bufs[0].dtype), _stream()))
+
+
+class _BorrowedPlan(Plan):
+    """A sliding-kernel plan owned by another object (queries only)."""
+
+    def destroy(self):
+        self.handle = None
+
+
+class ConvCpPlan:
+    """Owner of a distdl_convcp_plan handle (channel-partitioned convolution layer)."""
+
+    def __init__(self, handle, D, P_co, P_ci):
+        self.handle, self.D, self.P_co, self.P_ci = handle, D, P_co, P_ci
+        self.spatial = self.block_plan(0, 0)
+        self.S = self.spatial.n_workers
+
+    def block_plan(self, i, j):
+        h = lib.distdl_convcp_block_plan(self.handle, i, j)
+        if not h:
+            raise DistdlError(ERR_INVALID_ARG, lib.distdl_last_error().decode())
+        return _BorrowedPlan(C.c_void_p(h), self.D)
+
+    def channels(self, output_side, block):
+        st, sz = C.c_int64(), C.c_int64()
+        _check(lib.distdl_convcp_channels(self.handle, int(output_side), block, C.byref(st), C.byref(sz)))
+        return st.value, sz.value
+
+    def __del__(self):
+        if getattr(self, "handle", None):
+            lib.distdl_convcp_plan_destroy(self.handle)
+            self.handle = None
+
+
+def distdl_convcp_plan_create(D, n_b, n_c_in, n_c_out, in_shape, P, P_co, P_ci, ksize, stride, padding, dilation,
+                              dtype=torch.float32):
+    h = C.c_void_p()
+    _check(lib.distdl_convcp_plan_create(C.byref(h), D, n_b, n_c_in, n_c_out, _arr(C.c_int64, in_shape),
+                                         _arr(C.c_int32, P), P_co, P_ci, _arr(C.c_int32, ksize), _arr(C.c_int32, stride),
+                                         _arr(C.c_int32, padding), _arr(C.c_int32, dilation), _dtype_code(dtype)))
+    return ConvCpPlan(h, D, P_co, P_ci)
+
+
+def distdl_convcp_fwd(plan, x_bufs, w, bias, y):
+    """x_bufs: P_ci * S buffers (block-major), w: P_co * P_ci blocks, bias: P_co arrays or None, y: P_co * S."""
+    _check(lib.distdl_convcp_fwd(plan.handle, _ptrs(x_bufs), _ptrs(w), _ptrs(bias) if bias is not None else None,
+                                 _ptrs(y), _stream()))
+
+
+def distdl_convcp_bwd(plan, x_bufs, w, dy, dx_bufs, dw, dbias):
+    _check(lib.distdl_convcp_bwd(plan.handle, _ptrs(x_bufs), _ptrs(w), _ptrs(dy), _ptrs(dx_bufs), _ptrs(dw),
+                                 _ptrs(dbias) if dbias is not None else None, _stream()))
 
 
 class RepartPlan:

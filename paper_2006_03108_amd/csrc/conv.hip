@@ -10,6 +10,7 @@
 #include <algorithm>
 
 #include "common.h"
+#include "conv_core.h"
 #include "conv_mfma.h"
 #include "profile.h"
 
@@ -252,13 +253,36 @@ size_t distdl_conv_bwd_workspace(const distdl_plan* plan) {
 
 int distdl_conv_fwd(distdl_plan* plan, void* const x_bufs_dev[], const void* w_dev, const void* bias_dev,
                     void* const y_dev[], void* stream) {
+  return distdl::conv_fwd_core(plan, x_bufs_dev, w_dev, bias_dev, y_dev, (hipStream_t)stream, true);
+}
+
+int distdl_conv_bwd(distdl_plan* plan, const void* const x_bufs_dev[], const void* w_dev, const void* const dy_dev[],
+                    void* const dx_bufs_dev[], void* dw_dev, void* dbias_dev, void* workspace_dev,
+                    size_t workspace_bytes, void* stream) {
+  return distdl::conv_bwd_core(plan, x_bufs_dev, w_dev, dy_dev, dx_bufs_dev, dw_dev, dbias_dev, workspace_dev,
+                               workspace_bytes, (hipStream_t)stream, true);
+}
+
+}  // extern "C"
+
+namespace distdl {
+
+// The two layer calls; `halo` = false leaves out H (forward) / H* (backward) for callers that apply them
+// themselves (the channel-partitioned layer exchanges halos once per input block, not once per weight block).
+int conv_fwd_core(distdl_plan* plan, void* const x_bufs_dev[], const void* w_dev, const void* bias_dev,
+                  void* const y_dev[], hipStream_t st, bool halo) {
   if (!plan || !x_bufs_dev || !w_dev || !y_dev) return set_error(DISTDL_ERR_NULL, "conv_fwd: null argument");
   int rc = check_conv_plan(plan);
   if (rc) return rc;
-  hipStream_t st = (hipStream_t)stream;
   for (int w = 0; w < plan->n_workers; ++w)
     if (!y_dev[w] || (uintptr_t)y_dev[w] % 4) return set_error(DISTDL_ERR_NULL, "conv_fwd: y of worker %d null or misaligned", w);
-  if ((rc = run_halo(plan, false, plan->tab_x, x_bufs_dev, st))) return rc;  // x <- H x
+  if (halo) {
+    if ((rc = run_halo(plan, false, plan->tab_x, x_bufs_dev, st))) return rc;  // x <- H x
+  } else {
+    if ((rc = plan_prepare_device(plan))) return rc;
+    for (int w = 0; w < plan->n_workers; ++w)
+      if (!x_bufs_dev[w] || (uintptr_t)x_bufs_dev[w] % 4) return set_error(DISTDL_ERR_NULL, "conv_fwd: x of worker %d null or misaligned", w);
+  }
   if ((rc = plan->tab_x.upload((const void* const*)x_bufs_dev, plan->n_workers, st))) return rc;
   if ((rc = plan->tab_y.upload((const void* const*)y_dev, plan->n_workers, st))) return rc;
   bool aligned = (uintptr_t)w_dev % 16 == 0;
@@ -279,9 +303,9 @@ int distdl_conv_fwd(distdl_plan* plan, void* const x_bufs_dev[], const void* w_d
   return DISTDL_OK;
 }
 
-int distdl_conv_bwd(distdl_plan* plan, const void* const x_bufs_dev[], const void* w_dev, const void* const dy_dev[],
-                    void* const dx_bufs_dev[], void* dw_dev, void* dbias_dev, void* workspace_dev,
-                    size_t workspace_bytes, void* stream) {
+int conv_bwd_core(distdl_plan* plan, const void* const x_bufs_dev[], const void* w_dev, const void* const dy_dev[],
+                  void* const dx_bufs_dev[], void* dw_dev, void* dbias_dev, void* workspace_dev, size_t workspace_bytes,
+                  hipStream_t st, bool halo) {
   if (!plan || !x_bufs_dev || !w_dev || !dy_dev || !dx_bufs_dev || !dw_dev || !workspace_dev)
     return set_error(DISTDL_ERR_NULL, "conv_bwd: null argument");
   int rc = check_conv_plan(plan);
@@ -289,7 +313,6 @@ int distdl_conv_bwd(distdl_plan* plan, const void* const x_bufs_dev[], const voi
   if (workspace_bytes < distdl_conv_bwd_workspace(plan) || (uintptr_t)workspace_dev % 16)
     return set_error(DISTDL_ERR_INVALID_ARG, "conv_bwd: workspace too small or misaligned (%zu < %zu)", workspace_bytes,
                      distdl_conv_bwd_workspace(plan));
-  hipStream_t st = (hipStream_t)stream;
   for (int w = 0; w < plan->n_workers; ++w) {
     if (!x_bufs_dev[w] || !dy_dev[w] || !dx_bufs_dev[w]) return set_error(DISTDL_ERR_NULL, "conv_bwd: worker %d has a null array", w);
     if ((uintptr_t)x_bufs_dev[w] % 4 || (uintptr_t)dy_dev[w] % 4) return set_error(DISTDL_ERR_INVALID_ARG, "conv_bwd: misaligned array");
@@ -331,7 +354,7 @@ int distdl_conv_bwd(distdl_plan* plan, const void* const x_bufs_dev[], const voi
   }
   DISTDL_HIP_TRY(hipGetLastError());
   // dx <- H* dx
-  return run_halo(plan, true, plan->tab_dx, dx_bufs_dev, st);
+  return halo ? run_halo(plan, true, plan->tab_dx, dx_bufs_dev, st) : DISTDL_OK;
 }
 
-}  // extern "C"
+}  // namespace distdl

@@ -186,6 +186,39 @@ def test_distributed_affine_equals_sequential(n_b, n_fi, n_fo, P_fo, P_fi):
     assert abs(lhs - np.sum(W * dW_s)) < 1e-10 * max(1, abs(lhs))
 
 
+@pytest.mark.parametrize("n,P,k,s,p,ci,co,Pco,Pci", [((9, 8), (2, 2), (3, 3), (1, 1), (1, 1), 5, 4, 2, 2),
+                                                     ((11,), (3,), (5,), (2,), (2,), 6, 7, 3, 2),
+                                                     ((8, 6, 7), (2, 1, 2), (3, 3, 3), (2, 1, 1), (1, 1, 1), 4, 3, 1, 3)])
+def test_channel_partitioned_conv_equals_unpartitioned(n, P, k, s, p, ci, co, Pco, Pci):
+    """The full Sec. 4 algorithm (broadcast of x over P_co, sum-reduce of y over P_ci, bias on one sub-partition)
+    against the plain definition of the layer and of its adjoint."""
+    D = len(n)
+    dil = (1,) * D
+    part = geo.Partition.for_kernel(n, P, k, s, p, dil)
+    x = RNG.standard_normal((2, ci) + n)
+    w = RNG.standard_normal((co, ci) + k)
+    b = RNG.standard_normal(co)
+    y_ref = layers.conv_forward(x, w, b, s, p, dil)
+    dy = RNG.standard_normal(y_ref.shape)
+    dx_ref, dw_ref, db_ref = layers.conv_backward(x, w, dy, s, p, dil)
+    rows, cols = layers.feature_blocks(co, Pco), layers.feature_blocks(ci, Pci)
+    x_bufs = [prim.scatter_bulk(x[:, c], part, fill=np.nan) for c in cols]
+    w_blocks = [[w[r][:, c] for c in cols] for r in rows]
+    y = layers.dist_conv_cp_forward(x_bufs, w_blocks, [b[r] for r in rows], part, Pco, Pci, s, dil)
+    got = np.concatenate([prim.gather_out(y[i], part) for i in range(Pco)], axis=1)
+    np.testing.assert_allclose(got, y_ref, rtol=1e-12, atol=1e-12)
+    dy_parts = [prim.scatter_out(dy[:, r], part) for r in rows]
+    dx, dw, db = layers.dist_conv_cp_adjoint(x_bufs, w_blocks, dy_parts, part, Pco, Pci, s, dil)
+    np.testing.assert_allclose(np.concatenate([prim.gather_bulk(dx[j], part) for j in range(Pci)], axis=1), dx_ref,
+                               rtol=1e-12, atol=1e-12)
+    dw_full = np.zeros_like(dw_ref)
+    for i, r in enumerate(rows):
+        for j, c in enumerate(cols):
+            dw_full[r, c] = dw[i][j]
+    np.testing.assert_allclose(dw_full, dw_ref, rtol=1e-12, atol=1e-12)
+    np.testing.assert_allclose(np.concatenate(db), db_ref, rtol=1e-12, atol=1e-12)
+
+
 # ------------------------------------------------------------ pooling and glue
 @pytest.mark.parametrize("n,P", [((28, 28), (2, 2)), ((10, 10), (2, 2)), ((10, 20), (3, 6)), ((11, 9), (2, 2))])
 def test_distributed_maxpool_equals_torch(n, P):
