@@ -58,6 +58,13 @@ CONV_FULL = [
                   padding=(1, 0, 2)), False),
     ("cfg5", dict(in_shape=(18, 18, 70), P=(1, 2, 1), c_in=32, c_out=32, ksize=(5, 5, 5), stride=(2, 2, 2),
                   padding=(2, 2, 2)), True),
+    # dilated kernels at matrix-core shapes (32 and 64 channels), 3-D and 2-D, with stride
+    ("cfg5", dict(in_shape=(26, 22, 70), P=(2, 2, 1), c_in=32, c_out=32, ksize=(3, 3, 3), stride=(1, 1, 1),
+                  padding=(2, 2, 2), dilation=(2, 2, 2)), True),
+    ("cfg5", dict(in_shape=(30, 30, 76), P=(2, 1, 2), c_in=32, c_out=64, ksize=(3, 2, 3), stride=(2, 1, 2),
+                  padding=(3, 1, 2), dilation=(3, 2, 2)), False),
+    ("cfg2", dict(in_shape=(70, 90), n_b=2, c_in=16, c_out=16, ksize=(3, 3), stride=(1, 1), padding=(2, 2),
+                  dilation=(2, 2)), True),
     ("cfg2", dict(in_shape=(28, 28), n_b=4, c_in=1, c_out=6, ksize=(5, 5), padding=(2, 2)), True),   # cfg4 conv1
     ("cfg2", dict(in_shape=(14, 14), n_b=4, c_in=6, c_out=16, ksize=(5, 5), padding=(0, 0)), True),  # cfg4 conv2
 ]

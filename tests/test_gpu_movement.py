@@ -271,6 +271,82 @@ def test_halo_full_size_sampled_properties():
     assert total == in_domain * C
 
 
+EXPLICIT_CASES = [
+    # the rank-2 example of App. B.2 (unbalanced widths given by hand), then wider variants
+    ("app-b2", [[5, 7], [6, 4]], [[(0, 2), (4, 0)], [(0, 0), (3, 0)]], 2, 3),
+    ("three-wide", [[6, 5, 9], [4, 8]], [[(0, 3), (2, 0), (5, 0)], [(0, 1), (4, 0)]], 1, 8),
+    ("rank-3", [[4, 4], [5, 3], [6, 6]], [[(0, 1), (1, 0)], [(0, 3), (0, 0)], [(0, 6), (6, 0)]], 1, 4),
+]
+
+
+@pytest.mark.parametrize("case", EXPLICIT_CASES, ids=[c[0] for c in EXPLICIT_CASES])
+def test_halo_explicit_widths_parity(case):
+    """H (bit-exact) and H* on plans with user-given bulk sizes and halo widths (App. B.2)."""
+    require_gpu()
+    name, bulk, halo, n_b, n_c = case
+    part = geo.Partition.explicit(bulk, halo)
+    P = [len(b) for b in bulk]
+    plan = dd.distdl_plan_create_explicit(len(P), n_b, n_c, P, bulk, halo)
+    r = syn.streams(17, 2)
+    xg = syn.normal(r[0], (n_b, n_c) + part.global_in_shape())
+    want = prim.halo_exchange(prim.scatter_bulk(xg, part, fill=np.float32(7.5)), part)
+    bufs = [to_cl(b) for b in prim.scatter_bulk(xg, part, fill=np.float32(-3.25))]
+    dd.distdl_halo_fwd(plan, bufs)
+    y = [syn.normal(r[1], (n_b, n_c) + part.buf_shape(w)) for w in range(part.n_workers)]
+    want_adj = prim.halo_exchange_adjoint([t.astype(np.float64) for t in y], part)
+    gy = [to_cl(t) for t in y]
+    dd.distdl_halo_adj(plan, gy)
+    torch.cuda.synchronize()
+    for w in range(part.n_workers):
+        assert np.array_equal(from_cl(bufs[w]), want[w]), f"{name} H worker {w}"
+        assert_close(from_cl(gy[w]), want_adj[w], TOL32, f"{name} H* worker {w}")
+
+
+def test_halo_explicit_widths_at_scale():
+    """The 2 x 2 unbalanced example of App. B.2 with every width scaled by 192 and 16 channels (about 0.5 GB of
+    buffers): index pattern through H, closed-form copy counts through H*, both exact."""
+    require_gpu()
+    f, C = 192, 16
+    bulk = [[5 * f, 7 * f], [6 * f, 4 * f]]
+    halo = [[(0, 2 * f), (4 * f, 0)], [(0, 0), (3 * f, 0)]]
+    part = geo.Partition.explicit(bulk, halo)
+    plan = dd.distdl_plan_create_explicit(2, 1, C, [2, 2], bulk, halo)
+    n = part.global_in_shape()
+    pattern = lambda g0, g1, c: (g0 * 4096 + g1 + 5 * c) % 16777216
+    bufs, ones = [], []
+    for w in range(part.n_workers):
+        shp = part.buf_shape(w)
+        b = torch.full((1,) + shp + (C,), -1.0, device="cuda")
+        sl = part.bulk_slices(w)
+        g = [torch.arange(part.g(w, d)["in_start"], part.g(w, d)["in_start"] + part.g(w, d)["in_size"],
+                          device="cuda", dtype=torch.int64) for d in range(2)]
+        c = torch.arange(C, device="cuda", dtype=torch.int64)
+        b[0, sl[0], sl[1], :] = pattern(g[0][:, None, None], g[1][None, :, None], c[None, None, :]).to(torch.float32)
+        bufs.append(b)
+        ones.append(torch.ones((1,) + shp + (C,), device="cuda"))
+    dd.distdl_halo_fwd(plan, bufs)
+    dd.distdl_halo_adj(plan, ones)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(5)
+    for w in range(part.n_workers):
+        shp = part.buf_shape(w)
+        m = 20000
+        idx = [rng.integers(0, shp[d], size=m) for d in range(2)]
+        for d in range(2):
+            idx[d][:500] = rng.choice([0, 1, shp[d] - 2, shp[d] - 1], size=500)
+        ch = rng.integers(0, C, size=m)
+        gi = [prim._global_index_of(part, w, d, idx[d]) for d in range(2)]
+        assert all(((gi[d] >= 0) & (gi[d] < n[d])).all() for d in range(2))   # no padding in an explicit plan
+        want = pattern(gi[0], gi[1], ch).astype(np.float32)
+        ti = [torch.from_numpy(a).cuda() for a in idx] + [torch.from_numpy(ch).cuda()]
+        assert np.array_equal(bufs[w][0, ti[0], ti[1], ti[2]].cpu().numpy(), want), f"H worker {w}"
+        mult = np.zeros(shp, dtype=np.float32)
+        mult[part.bulk_slices(w)] = prim.adjoint_multiplicity(part, w)
+        assert np.array_equal(ones[w][0, ti[0], ti[1], ti[2]].cpu().numpy(), mult[idx[0], idx[1]]), f"H* worker {w}"
+    total = sum(t.sum(dtype=torch.float64).item() for t in ones)
+    assert total == sum(int(np.prod(part.buf_shape(w))) for w in range(part.n_workers)) * C
+
+
 @pytest.mark.parametrize("k,count", [(4, 1 << 26), (64, 1 << 22)])
 def test_collectives_full_size_exact(k, count):
     """B and R at the sizes the benchmark times, with integer-valued data so that every sum is exact."""

@@ -227,6 +227,17 @@ def test_adjoint_multiplicity_closed_form_matches_nested_adjoint(n, P, k, s, p):
         assert np.array_equal(got[w][0, 0], want) and np.array_equal(got[w][0, 1], want)
 
 
+@pytest.mark.parametrize("bulk,halo", [([[5, 7], [6, 4]], [[(0, 2), (4, 0)], [(0, 0), (3, 0)]]),
+                                       ([[4, 4], [5, 3], [6, 6]], [[(0, 1), (1, 0)], [(0, 3), (0, 0)], [(0, 6), (6, 0)]])])
+def test_adjoint_multiplicity_on_explicit_widths(bulk, halo):
+    """Same pin on partitions with hand-given widths (App. B.2), against the cell-by-cell statement of H*."""
+    part = geo.Partition.explicit(bulk, halo)
+    ones = [np.ones((1, 1) + part.buf_shape(w)) for w in range(part.n_workers)]
+    got = prim.halo_exchange_adjoint_direct(ones, part)
+    for w in range(part.n_workers):
+        assert np.array_equal(got[w][0, 0][part.bulk_slices(w)], prim.adjoint_multiplicity(part, w))
+
+
 @pytest.mark.parametrize("shape,Ps,Pd", [((6, 7), (2, 3), (3, 1)), ((4, 16, 5, 5), (1, 1, 2, 2), (1, 2, 1, 1)),
                                          ((3, 10, 9, 8), (1, 2, 3, 2), (3, 1, 2, 4)), ((11,), (4,), (3,))])
 def test_repartition_is_a_permutation_with_inverse_adjoint(shape, Ps, Pd):
