@@ -323,6 +323,33 @@ class MovementWorkload:
         timed("avgpool_fwd", lambda: dd.distdl_avgpool_fwd(pp, px, py), n_in + n_out)
         timed("maxpool_bwd", lambda: dd.distdl_maxpool_bwd(pp, px, py, pdx), 2 * n_in + n_out)
         timed("avgpool_bwd", lambda: dd.distdl_avgpool_bwd(pp, py, pdx), n_in + n_out)
+        del px, py, pdx
+        # channel-partitioned convolution: 64 -> 64 channels as 2 x 2 blocks of 32, 5^3 / stride 2 on 128^3 over
+        # 2 x 2 x 2 spatial workers (every block is the cfg5 per-worker contraction); reported in TFLOP/s
+        cp_shape, cp_P, cc = (128, 128, 128), (2, 2, 2), 64
+        cp = dd.distdl_convcp_plan_create(3, 1, cc, cc, cp_shape, cp_P, 2, 2, c["ksize"], c["stride"], c["padding"],
+                                          c["dilation"])
+        S = cp.S
+        g0 = [cp.block_plan(0, 0).query(w) for w in range(S)]
+        cx = [_dev_randn([1] + g["buf_shape"] + [32], 200 + i) for i in range(2) for g in g0]
+        cw = [_dev_randn((32, 32) + tuple(c["ksize"]), 210 + i) * 0.02 for i in range(4)]
+        cb = [_dev_randn((32,), 220 + i) for i in range(2)]
+        cy = [torch.empty([1] + g["out_size"] + [32], device="cuda") for i in range(2) for g in g0]
+        cdy = [_dev_randn(list(t.shape), 230 + i) for i, t in enumerate(cy)]
+        cdx = [torch.empty_like(t) for t in cx]
+        cdw = [torch.empty_like(t) for t in cw]
+        cdb = [torch.empty_like(t) for t in cb]
+        out_cells = sum(_prod(g["out_size"]) for g in g0)
+        fl = 2 * out_cells * cc * cc * _prod(c["ksize"])
+        for name, call, nfl in (("convcp_fwd", lambda: dd.distdl_convcp_fwd(cp, cx, cw, cb, cy), fl),
+                                ("convcp_bwd", lambda: dd.distdl_convcp_bwd(cp, cx, cw, cdy, cdx, cdw, cdb), 2 * fl)):
+            timed(name, call, 0, reps=3)
+            row = rows[-1]
+            row.update({"TFLOP/s": round(nfl / (row["ms"] * 1e-3) / 1e12, 1), "algorithmic_flops": nfl,
+                        "frac_mfma_peak": round(nfl / (row["ms"] * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS["f32"], 3),
+                        "config": "64->64 channels, P_co x P_ci = 2 x 2, 128^3 over 2x2x2 workers, 5^3 stride 2"})
+            for key in ("GB/s", "frac_hbm_peak", "algorithmic_bytes"):
+                row.pop(key)
         dd.distdl_profile_enable(False)
         return rows
 
