@@ -791,19 +791,10 @@ __global__ __launch_bounds__(256) void bias_partial_kernel(const WorkerDev* __re
 
 static int lds_bytes(const CorrArgs& a) { return (a.a_vec4 + a.nt[1] * a.nt[2] * 64 + 1) * 16 + (a.nt[1] * a.nt[2] + 4) * 4; }
 
-static void finish_args(CorrArgs& a, int mt, int nq2max) {
-  // window of 128*mt positions: full output rows when they fit, else 32-multiples
+// Window of tr x tc output positions (tr * tc <= 128 * mt) and everything derived from it.
+static void finish_args(CorrArgs& a, int mt, int tc) {
   const int cap = 128 * mt;
-  if (nq2max <= cap) {
-    a.tc = std::max(nq2max, 1);
-  } else {
-    a.tc = 32;
-    double best = 1e30;
-    for (int c = 32; c <= cap; c += 32) {
-      double waste = (double)((nq2max + c - 1) / c) * c / nq2max;
-      if (waste < best - 1e-9 || (waste < best + 1e-9 && c > a.tc)) best = waste, a.tc = c;
-    }
-  }
+  a.tc = std::max(1, std::min(tc, cap));
   a.tr = std::max(1, cap / a.tc);
   for (int d = 0; d < 3; ++d) {
     int lo = 0, hi = 0;
@@ -823,14 +814,44 @@ static void finish_args(CorrArgs& a, int mt, int nq2max) {
   a.div_is2 = make_fastdiv((uint32_t)a.is[2]);
 }
 
+// Fraction of the multiplied window positions that are outputs, for an nq1 x nq2 plane cut into tr x tc windows.
+static double window_efficiency(int cap, int tc, int nq1, int nq2) {
+  const int tr = std::max(1, cap / tc);
+  const double cols = (double)nq2 / ((double)((nq2 + tc - 1) / tc) * tc);
+  const double rows = (double)nq1 / ((double)((nq1 + tr - 1) / tr) * tr);
+  return (double)(tr * tc) / cap * cols * rows;
+}
+
+// Window width: full output rows when they fit (else the multiple of 32 with the least padding), unless a
+// narrower window wastes clearly fewer of the multiplied positions (e.g. rows of 130 in 256 positions).
+static int choose_tc(int cap, int nq1max, int nq2max) {
+  int tc0 = std::max(nq2max, 1);
+  if (nq2max > cap) {
+    tc0 = 32;
+    double best = 1e30;
+    for (int c = 32; c <= cap; c += 32) {
+      double waste = (double)((nq2max + c - 1) / c) * c / nq2max;
+      if (waste < best - 1e-9 || (waste < best + 1e-9 && c > tc0)) best = waste, tc0 = c;
+    }
+  }
+  const double eff0 = window_efficiency(cap, tc0, nq1max, nq2max);
+  int best_tc = tc0;
+  double best_eff = eff0 * 1.05;
+  for (int tc = 8; tc <= std::min(cap, std::max(nq2max, 1)); ++tc) {
+    const double eff = window_efficiency(cap, tc, nq1max, nq2max);
+    if (eff >= best_eff - 1e-9) best_eff = eff, best_tc = tc;  // ties: the wider window
+  }
+  return best_tc;
+}
+
 // Chooses the rows-per-wave so that two workgroups fit in a CU's LDS when
 // possible; returns 0 when the patch does not fit at all.
-static int choose_mt(CorrArgs& a, int nq2max) {
+static int choose_mt(CorrArgs& a, int nq1max, int nq2max) {
   for (int mt : {2, 1}) {
-    finish_args(a, mt, nq2max);
+    finish_args(a, mt, choose_tc(128 * mt, nq1max, nq2max));
     if (lds_bytes(a) <= 80 * 1024 && a.R * a.Cw * 2 <= kMaxPieces * 256) return mt;
   }
-  finish_args(a, 1, nq2max);
+  finish_args(a, 1, choose_tc(128, nq1max, nq2max));
   if (lds_bytes(a) <= 160 * 1024 && a.R * a.Cw * 2 <= kMaxPieces * 256) return 1;
   // last resort: a 32-wide window
   finish_args(a, 1, 32);
@@ -838,10 +859,13 @@ static int choose_mt(CorrArgs& a, int nq2max) {
   return 0;
 }
 
-static int max_nq2(const distdl_plan* p, const CorrArgs& a) {
-  int mx = 0;
-  for (const WorkerDev& wd : p->workers) mx = std::max(mx, derive(wd, a).nq[2]);
-  return mx;
+static void max_nq(const distdl_plan* p, const CorrArgs& a, int& nq1, int& nq2) {
+  nq1 = nq2 = 0;
+  for (const WorkerDev& wd : p->workers) {
+    const PerWorker g = derive(wd, a);
+    nq1 = std::max(nq1, g.nq[1]);
+    nq2 = std::max(nq2, g.nq[2]);
+  }
 }
 
 bool corr_mfma_supported(const distdl_plan* p) {
@@ -914,7 +938,9 @@ static size_t corr_scratch_elems(const CorrArgs& a) { return corr_weight_elems(a
 
 static int launch_corr(distdl_plan* p, CorrArgs a, const float* w, float* wscratch, const float* bias, void** in_tab,
                        void** out_tab, const char* name, hipStream_t st) {
-  const int mt = choose_mt(a, max_nq2(p, a));
+  int nq1max, nq2max;
+  max_nq(p, a, nq1max, nq2max);
+  const int mt = choose_mt(a, std::max(nq1max, 1), nq2max);
   if (mt == 0) return set_error(DISTDL_ERR_UNSUPPORTED, "conv: kernel footprint does not fit in LDS");
   // Output planes per workgroup.  A workgroup pays a fixed set-up (its address tables, about 8 * 10^3
   // cycles) and then about `per_plane` cycles per plane; the chip runs about 512 workgroups at a time.
