@@ -5,7 +5,7 @@ import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
-SOURCES = ["plan.cpp", "profile.cpp", "halo.hip", "collective.hip", "conv.hip", "conv_mfma.hip", "affine.hip", "gemm_mfma.hip", "glue.hip", "repart.hip", "convcp.hip"]
+SOURCES = ["plan.cpp", "profile.cpp", "halo.hip", "collective.hip", "conv.hip", "conv_mfma.hip", "conv_small.hip", "affine.hip", "gemm_mfma.hip", "glue.hip", "repart.hip", "convcp.hip"]
 LIB = os.path.join(HERE, "libdistdl.so")
 
 

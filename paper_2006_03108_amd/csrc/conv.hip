@@ -172,28 +172,33 @@ __global__ __launch_bounds__(256) void conv_bwd_weight_direct_kernel(const Worke
 
 // R dw^, R db^ (Sec. 4, adjoint algorithm): sum the partials in worker order
 // and write dw in the caller's [Co][Ci][T] shape.
+template <int E>
 __global__ __launch_bounds__(256) void conv_reduce_dw_kernel(const float* __restrict__ partial, int nparts,
                                                              float* __restrict__ dw, float* __restrict__ db,
                                                              ConvDev c) {
-  // 64 elements per block, 4 lanes of partials each; every lane adds its partials in ascending order
-  // (four independent chains for latency), the lanes are then combined in a fixed order
+  // E elements per block, L = 256 / E lanes of partials each (few elements: more lanes, so that the launch still
+  // has enough blocks); every lane adds its partials in ascending order (four independent chains for latency),
+  // the lanes are then combined in ascending order
+  constexpr int L = 256 / E;
   const int nw = c.taps * c.ci * c.co;
-  const int e = threadIdx.x & 63, lanep = threadIdx.x >> 6;
-  const int idx = blockIdx.x * 64 + e;
+  const int e = threadIdx.x % E, lanep = threadIdx.x / E;
+  const int idx = blockIdx.x * E + e;
   const size_t slot = (size_t)nw + c.co;
   float acc[4] = {0.f, 0.f, 0.f, 0.f};
   if (idx < nw + c.co) {
     int p = lanep;
-    for (; p + 12 < nparts; p += 16)
+    for (; p + 3 * L < nparts; p += 4 * L)
 #pragma unroll
-      for (int u = 0; u < 4; ++u) acc[u] += partial[(size_t)(p + 4 * u) * slot + idx];
-    for (; p < nparts; p += 4) acc[0] += partial[(size_t)p * slot + idx];
+      for (int u = 0; u < 4; ++u) acc[u] += partial[(size_t)(p + L * u) * slot + idx];
+    for (; p < nparts; p += L) acc[0] += partial[(size_t)p * slot + idx];
   }
-  __shared__ float red[4][64];
+  __shared__ float red[L][E];
   red[lanep][e] = (acc[0] + acc[1]) + (acc[2] + acc[3]);
   __syncthreads();
   if (lanep != 0 || idx >= nw + c.co) return;
-  const float sum = (red[0][e] + red[1][e]) + (red[2][e] + red[3][e]);
+  float sum = red[0][e];
+#pragma unroll
+  for (int l = 1; l < L; ++l) sum += red[l][e];
   if (idx >= nw) {
     if (db) db[idx - nw] = sum;
   } else {
@@ -248,6 +253,7 @@ size_t distdl_conv_bwd_workspace(const distdl_plan* plan) {
   size_t nw = (size_t)c.taps * c.ci * c.co + c.co;
   int chunks = direct_chunks(plan);
   if (wgrad_mfma_supported(plan)) chunks = std::max(chunks, wgrad_chunks(plan));
+  chunks = std::max(chunks, std::max(wgrad16_chunks(plan, true), wgrad16_chunks(plan, false)));
   return nw * sizeof(float) * plan->n_workers * chunks;
 }
 
@@ -287,6 +293,13 @@ int conv_fwd_core(distdl_plan* plan, void* const x_bufs_dev[], const void* w_dev
   if ((rc = plan->tab_y.upload((const void* const*)y_dev, plan->n_workers, st))) return rc;
   bool aligned = (uintptr_t)w_dev % 16 == 0;
   for (int w = 0; w < plan->n_workers; ++w) aligned &= (uintptr_t)x_bufs_dev[w] % 16 == 0;
+  bool xvec = true;
+  for (int w = 0; w < plan->n_workers; ++w) xvec &= (uintptr_t)x_bufs_dev[w] % 16 == 0;
+  if (corr16_fwd_supported(plan, xvec)) {  // few channels: 16 x 16 tiles
+    if ((rc = conv_fwd16(plan, (const float*)w_dev, (const float*)bias_dev, xvec, st))) return rc;
+    DISTDL_HIP_TRY(hipGetLastError());
+    return DISTDL_OK;
+  }
   if (aligned && corr_mfma_supported(plan)) {
     if ((rc = conv_fwd_mfma(plan, (const float*)w_dev, (const float*)bias_dev, st))) return rc;
     DISTDL_HIP_TRY(hipGetLastError());
@@ -325,10 +338,15 @@ int conv_bwd_core(distdl_plan* plan, const void* const x_bufs_dev[], const void*
   bool aligned = true;
   for (int w = 0; w < plan->n_workers; ++w) aligned &= (uintptr_t)dy_dev[w] % 16 == 0;
   const bool data_mfma = aligned && corr_mfma_supported(plan);
-  const bool wgrad_mfma = wgrad_mfma_supported(plan) && plan->n_workers * wgrad_chunks(plan) <= 65535;
+  bool vec16 = aligned && plan->n_ci % 4 == 0 && plan->n_co % 4 == 0;
+  for (int w = 0; w < plan->n_workers; ++w) vec16 &= (uintptr_t)x_bufs_dev[w] % 16 == 0;
+  const bool wgrad16 = wgrad16_supported(plan, vec16);
+  const bool wgrad_mfma = !wgrad16 && wgrad_mfma_supported(plan) && plan->n_workers * wgrad_chunks(plan) <= 65535;
   // [dConv]* with respect to x, into the whole padded buffers
   int64_t total = plan->n_b * plan->max_buf_cells * c.ci;
-  if (data_mfma) {
+  if (corr16_bwd_supported(plan, aligned)) {
+    if ((rc = conv_bwd_data16(plan, (const float*)w_dev, aligned, st))) return rc;
+  } else if (data_mfma) {
     if ((rc = conv_bwd_data_mfma(plan, (const float*)w_dev, st))) return rc;
   } else {
     if ((rc = prepare_weights(plan, (const float*)w_dev, st))) return rc;
@@ -337,9 +355,11 @@ int conv_bwd_core(distdl_plan* plan, const void* const x_bufs_dev[], const void*
                        0, st, plan->d_workers, plan->tab_dy.dev, plan->d_wt, plan->tab_dx.dev, c);
   }
   // [dConv]* with respect to w and b, then R over the workers
-  int nchunks = wgrad_mfma ? wgrad_chunks(plan) : direct_chunks(plan);
+  int nchunks = wgrad16 ? wgrad16_chunks(plan, vec16) : wgrad_mfma ? wgrad_chunks(plan) : direct_chunks(plan);
   int nw = c.taps * c.ci * c.co + c.co;
-  if (wgrad_mfma) {
+  if (wgrad16) {
+    if ((rc = conv_wgrad16(plan, (float*)workspace_dev, vec16, st))) return rc;
+  } else if (wgrad_mfma) {
     if ((rc = conv_wgrad_mfma(plan, (float*)workspace_dev, st))) return rc;
   } else {
     ProfScope prof("conv_bwd_weight_direct", st);
@@ -349,8 +369,12 @@ int conv_bwd_core(distdl_plan* plan, const void* const x_bufs_dev[], const void*
   }
   {
     ProfScope prof("conv_reduce_dw", st);
-    hipLaunchKernelGGL(conv_reduce_dw_kernel, dim3((unsigned)((nw + 63) / 64)), dim3(256), 0, st,
-                       (const float*)workspace_dev, nchunks * plan->n_workers, (float*)dw_dev, (float*)dbias_dev, c);
+    if (nw <= 8192)
+      hipLaunchKernelGGL(conv_reduce_dw_kernel<16>, dim3((unsigned)((nw + 15) / 16)), dim3(256), 0, st,
+                         (const float*)workspace_dev, nchunks * plan->n_workers, (float*)dw_dev, (float*)dbias_dev, c);
+    else
+      hipLaunchKernelGGL(conv_reduce_dw_kernel<64>, dim3((unsigned)((nw + 63) / 64)), dim3(256), 0, st,
+                         (const float*)workspace_dev, nchunks * plan->n_workers, (float*)dw_dev, (float*)dbias_dev, c);
   }
   DISTDL_HIP_TRY(hipGetLastError());
   // dx <- H* dx

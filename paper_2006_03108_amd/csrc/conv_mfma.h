@@ -40,6 +40,42 @@ struct WgradArgs {
   int64_t slot;     // floats per (worker, chunk) partial: taps*ci*co + co
 };
 
+// Geometry of one worker as a correlation launch sees it: extent and first cell of the tensor it reads,
+// number of output positions per dimension, extent / first cell / step of the tensor it writes.
+struct PerWorker {
+  int32_t in_ext[3], in_base[3], nq[3], out_ext[3], out_base[3], os[3];
+};
+
+__host__ __device__ inline PerWorker derive(const WorkerDev& wd, const CorrArgs& a) {
+  PerWorker g;
+  for (int d = 0; d < 3; ++d) {
+    if (a.mode == 0) {
+      g.in_ext[d] = wd.buf[d];
+      g.in_base[d] = wd.origin[d];
+      g.nq[d] = wd.out[d];
+      g.out_ext[d] = wd.out[d];
+      g.out_base[d] = 0;
+      g.os[d] = 1;
+    } else {
+      const int s = a.s[d], op = wd.origin[d] + a.par[d];
+      const int first = op % s;  // first buffer cell of this parity class
+      g.in_ext[d] = wd.out[d];
+      g.in_base[d] = -(op / s);
+      g.nq[d] = first < wd.buf[d] ? (wd.buf[d] - 1 - first) / s + 1 : 0;
+      g.out_ext[d] = wd.buf[d];
+      g.out_base[d] = first;
+      g.os[d] = s;
+    }
+  }
+  return g;
+}
+
+// Arguments of the forward correlation and of one stride-parity class of the data gradient (taps, steps).
+CorrArgs forward_args(const distdl_plan* p);
+CorrArgs class_args(const distdl_plan* p, const int par[3]);
+// Grows the plan's weight re-layout scratch to at least `elems` floats.
+int ensure_wscratch(distdl_plan* p, size_t elems);
+
 bool corr_mfma_supported(const distdl_plan* p);
 bool wgrad_mfma_supported(const distdl_plan* p);
 size_t bwd_scratch_elems(const distdl_plan* p);
@@ -48,5 +84,15 @@ int wgrad_chunks(const distdl_plan* p);
 int conv_fwd_mfma(distdl_plan* p, const float* w, const float* bias, hipStream_t st);
 int conv_bwd_data_mfma(distdl_plan* p, const float* w, hipStream_t st);
 int conv_wgrad_mfma(distdl_plan* p, float* partial, hipStream_t st);
+
+// Kernels for layers with at most 16 input and 16 output channels (16 x 16 MFMA tiles).  `vec`: channel counts
+// are multiples of 4 and every array is 16-byte aligned.
+bool corr16_fwd_supported(const distdl_plan* p, bool vec);
+bool corr16_bwd_supported(const distdl_plan* p, bool vec);
+int conv_fwd16(distdl_plan* p, const float* w, const float* bias, bool vec, hipStream_t st);
+int conv_bwd_data16(distdl_plan* p, const float* w, bool vec, hipStream_t st);
+bool wgrad16_supported(const distdl_plan* p, bool vec);
+int wgrad16_chunks(const distdl_plan* p, bool vec);
+int conv_wgrad16(distdl_plan* p, float* partial, bool vec, hipStream_t st);
 
 }  // namespace distdl

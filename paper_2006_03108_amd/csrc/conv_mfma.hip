@@ -29,34 +29,6 @@ namespace distdl {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
-struct PerWorker {
-  int32_t in_ext[3], in_base[3], nq[3], out_ext[3], out_base[3], os[3];
-};
-
-__host__ __device__ inline PerWorker derive(const WorkerDev& wd, const CorrArgs& a) {
-  PerWorker g;
-  for (int d = 0; d < 3; ++d) {
-    if (a.mode == 0) {
-      g.in_ext[d] = wd.buf[d];
-      g.in_base[d] = wd.origin[d];
-      g.nq[d] = wd.out[d];
-      g.out_ext[d] = wd.out[d];
-      g.out_base[d] = 0;
-      g.os[d] = 1;
-    } else {
-      const int s = a.s[d], op = wd.origin[d] + a.par[d];
-      const int first = op % s;  // first buffer cell of this parity class
-      g.in_ext[d] = wd.out[d];
-      g.in_base[d] = -(op / s);
-      g.nq[d] = first < wd.buf[d] ? (wd.buf[d] - 1 - first) / s + 1 : 0;
-      g.out_ext[d] = wd.buf[d];
-      g.out_base[d] = first;
-      g.os[d] = s;
-    }
-  }
-  return g;
-}
-
 __host__ __device__ inline int64_t tiles_of(const PerWorker& g, const CorrArgs& a) {
   // chunks of g0 consecutive (sample, dimension-0 position) planes x windows x channel tiles
   return (((int64_t)a.n_b * g.nq[0] + a.g0 - 1) / a.g0) * ((g.nq[1] + a.tr - 1) / a.tr) *
@@ -879,7 +851,7 @@ bool corr_mfma_supported(const distdl_plan* p) {
   return true;
 }
 
-static CorrArgs forward_args(const distdl_plan* p) {
+CorrArgs forward_args(const distdl_plan* p) {
   CorrArgs a{};
   a.mode = 0;
   a.n_b = (int32_t)p->n_b;
@@ -899,7 +871,7 @@ static CorrArgs forward_args(const distdl_plan* p) {
   return a;
 }
 
-static CorrArgs class_args(const distdl_plan* p, const int par[3]) {
+CorrArgs class_args(const distdl_plan* p, const int par[3]) {
   CorrArgs a{};
   a.mode = 1;
   a.n_b = (int32_t)p->n_b;
@@ -998,7 +970,7 @@ static int launch_corr(distdl_plan* p, CorrArgs a, const float* w, float* wscrat
 
 // Scratch for the re-laid-out weights: forward needs one set, the data
 // gradient one per parity class (used one after the other on the stream).
-static int ensure_wscratch(distdl_plan* p, size_t elems) {
+int ensure_wscratch(distdl_plan* p, size_t elems) {
   if (p->wt_elems >= elems) return DISTDL_OK;
   if (p->d_wt) (void)hipFree(p->d_wt);
   p->d_wt = nullptr;

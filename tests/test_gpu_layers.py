@@ -65,6 +65,17 @@ CONV_FULL = [
                   padding=(3, 1, 2), dilation=(3, 2, 2)), False),
     ("cfg2", dict(in_shape=(70, 90), n_b=2, c_in=16, c_out=16, ksize=(3, 3), stride=(1, 1), padding=(2, 2),
                   dilation=(2, 2)), True),
+    # few channels (16 x 16 matrix-core tiles): planes stacked per unit, ragged batches and partitions, 3-D, dilation
+    ("cfg2", dict(in_shape=(28, 28), n_b=37, c_in=1, c_out=6, ksize=(5, 5), padding=(2, 2)), True),
+    ("cfg2", dict(in_shape=(14, 14), n_b=37, c_in=6, c_out=16, ksize=(5, 5), padding=(0, 0)), True),
+    ("cfg2", dict(in_shape=(45, 150), n_b=3, c_in=16, c_out=16, P=(3, 1)), True),
+    ("cfg2", dict(in_shape=(33, 29), n_b=5, c_in=16, c_out=12, ksize=(5, 5), padding=(2, 2), P=(2, 3)), False),
+    ("cfg2", dict(in_shape=(31, 37), n_b=2, c_in=3, c_out=8, ksize=(3, 3), padding=(2, 2), dilation=(2, 2), P=(2, 2)), True),
+    ("cfg5", dict(in_shape=(11, 14, 19), P=(2, 1, 2), c_in=4, c_out=8, ksize=(3, 3, 3), stride=(2, 1, 1),
+                  padding=(1, 1, 1)), True),
+    ("cfg1", dict(in_shape=(300,), n_b=4, c_in=5, c_out=7, P=(3,), ksize=(5,), padding=(2,)), True),
+    ("cfg1", dict(in_shape=(130,), n_b=9, c_in=8, c_out=8, P=(2,), ksize=(7,), padding=(3,)), False),
+    ("cfg2", dict(in_shape=(20, 24), n_b=6, c_in=12, c_out=4, ksize=(1, 1), padding=(0, 0)), True),
     ("cfg2", dict(in_shape=(28, 28), n_b=4, c_in=1, c_out=6, ksize=(5, 5), padding=(2, 2)), True),   # cfg4 conv1
     ("cfg2", dict(in_shape=(14, 14), n_b=4, c_in=6, c_out=16, ksize=(5, 5), padding=(0, 0)), True),  # cfg4 conv2
 ]
