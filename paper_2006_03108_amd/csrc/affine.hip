@@ -121,35 +121,56 @@ __global__ __launch_bounds__(256) void affine_bwd_x_direct_kernel(void* const* d
   st((T*)dx[j], idx, acc);
 }
 
-// grid: (ceil(max_fo * max_fi / 256), P_fo * P_fi)
+// grid: (ceil(max_fo * max_fi / 16), P_fo * P_fi).  16 outputs x 16 slices of the batch per block: the layers
+// that come here are small, so the sum over the batch is split to get enough threads; the slices are added
+// in ascending order.
 template <class T>
 __global__ __launch_bounds__(256) void affine_bwd_w_direct_kernel(void* const* dy, void* const* x, void* const* dW,
                                                                   const int32_t* sizes, int n_b, int P_fo, int P_fi) {
   const int i = blockIdx.y / P_fi, j = blockIdx.y % P_fi;
   const int fo = sizes[i], fi = sizes[P_fo + j];
-  int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (idx >= (int64_t)fo * fi) return;
-  int k = (int)(idx % fi);
-  int f = (int)(idx / fi);
-  const T* dyi = (const T*)dy[i];
-  const T* xj = (const T*)x[j];
+  const int o = threadIdx.x & 15, sl = threadIdx.x >> 4;
+  const int64_t idx = (int64_t)blockIdx.x * 16 + o;
+  const bool live = idx < (int64_t)fo * fi;
+  __shared__ float red[16][16];
   float acc = 0.f;
-  for (int n = 0; n < n_b; ++n) acc = fmaf(ld(dyi, (size_t)n * fo + f), ld(xj, (size_t)n * fi + k), acc);
-  st((T*)dW[blockIdx.y], idx, acc);
+  if (live) {
+    const int k = (int)(idx % fi), f = (int)(idx / fi);
+    const T* dyi = (const T*)dy[i];
+    const T* xj = (const T*)x[j];
+    for (int n = sl; n < n_b; n += 16) acc = fmaf(ld(dyi, (size_t)n * fo + f), ld(xj, (size_t)n * fi + k), acc);
+  }
+  red[sl][o] = acc;
+  __syncthreads();
+  if (sl != 0 || !live) return;
+  float sum = red[0][o];
+#pragma unroll
+  for (int t = 1; t < 16; ++t) sum += red[t][o];
+  st((T*)dW[blockIdx.y], idx, sum);
 }
 
-// grid: (ceil(max_fo / 256), P_fo)
+// grid: (ceil(max_fo / 16), P_fo), same 16 x 16 split
 template <class T>
 __global__ __launch_bounds__(256) void affine_bwd_b_direct_kernel(void* const* dy, void* const* db,
                                                                   const int32_t* sizes, int n_b) {
   const int i = blockIdx.y;
   const int fo = sizes[i];
-  int f = blockIdx.x * 256 + threadIdx.x;
-  if (f >= fo || !db[i]) return;
-  const T* dyi = (const T*)dy[i];
+  const int o = threadIdx.x & 15, sl = threadIdx.x >> 4;
+  const int f = blockIdx.x * 16 + o;
+  const bool live = f < fo && db[i];
+  __shared__ float red[16][16];
   float acc = 0.f;
-  for (int n = 0; n < n_b; ++n) acc += ld(dyi, (size_t)n * fo + f);
-  st((T*)db[i], f, acc);
+  if (live) {
+    const T* dyi = (const T*)dy[i];
+    for (int n = sl; n < n_b; n += 16) acc += ld(dyi, (size_t)n * fo + f);
+  }
+  red[sl][o] = acc;
+  __syncthreads();
+  if (sl != 0 || !live) return;
+  float sum = red[0][o];
+#pragma unroll
+  for (int t = 1; t < 16; ++t) sum += red[t][o];
+  st((T*)db[i], f, sum);
 }
 
 static int check_ptrs(const void* const* p, int n, size_t esz, const char* what, bool nullable = false) {
@@ -185,10 +206,10 @@ static void bwd_direct(distdl_affine_plan* p, bool has_db, hipStream_t st_) {
                      dim3(256), 0, st_, p->tab_dy.dev, p->tab_W.dev, p->tab_dx.dev, p->d_sizes, (int)p->n_b, p->P_fo,
                      p->P_fi);
   hipLaunchKernelGGL(affine_bwd_w_direct_kernel<T>,
-                     dim3((unsigned)((p->max_fo * p->max_fi + 255) / 256), p->P_fo * p->P_fi), dim3(256), 0, st_,
+                     dim3((unsigned)((p->max_fo * p->max_fi + 15) / 16), p->P_fo * p->P_fi), dim3(256), 0, st_,
                      p->tab_dy.dev, p->tab_x.dev, p->tab_dW.dev, p->d_sizes, (int)p->n_b, p->P_fo, p->P_fi);
   if (has_db)
-    hipLaunchKernelGGL(affine_bwd_b_direct_kernel<T>, dim3((unsigned)((p->max_fo + 255) / 256), p->P_fo), dim3(256), 0,
+    hipLaunchKernelGGL(affine_bwd_b_direct_kernel<T>, dim3((unsigned)((p->max_fo + 15) / 16), p->P_fo), dim3(256), 0,
                        st_, p->tab_dy.dev, p->tab_db.dev, p->d_sizes, (int)p->n_b);
 }
 

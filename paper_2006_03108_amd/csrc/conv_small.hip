@@ -321,12 +321,15 @@ bool wgrad16_shape(const distdl_plan* p, bool vec, Wgrad16Shape& s) {
 // stride-parity class of dx^), with all contraction channels staged at once (no channel chunks) and, for
 // layers whose planes are single samples, tp samples stacked in one window so that small images still fill
 // the 256 positions of a workgroup.  A lane reads KM consecutive channels of its cell (KM = 1, 2, 4 for
-// kc <= 4, 8, 16) and issues KM MFMAs per tap.
+// kc <= 4, 8, 16) and issues KM MFMAs per tap.  The patch is kept in LDS as four channel groups (group kg =
+// channels KM * kg ... of every cell, groups a.ps bytes apart), so that the 16 lanes of a group read
+// consecutive addresses.
 
 struct Corr16Args {
   CorrArgs c;                  // taps, steps and parity class of the launch
   int32_t tp, tr, tc;          // window: planes x rows x columns (tp * tr * tc <= 256)
   int32_t R, Cw;               // patch rows and cells per row of one plane
+  int32_t ps;                  // bytes between the four channel groups of the patch in LDS
   int32_t tapmin1, tapmin2;    // smallest tap offset along dimensions 1, 2
   int32_t g0;                  // window steps along the planes per workgroup
   int32_t tiles_max, ntaps;    // tiles of the largest worker; taps per kernel plane
@@ -363,7 +366,7 @@ __global__ __launch_bounds__(256, 2) void corr16_kernel(const WorkerDev* __restr
   extern __shared__ float lds[];
   typedef typename VecK<KM>::T OT;
   typedef typename Piece<V>::T PT;
-  constexpr uint32_t CB = KM * 16;  // bytes per cell in LDS
+  constexpr uint32_t CG = KM * 4;  // bytes per cell and channel group in LDS
   const CorrArgs& c = a.c;
   // XCD-aware order: consecutive tiles stay behind one L2
   const uint32_t nblk = gridDim.x;
@@ -393,9 +396,9 @@ __global__ __launch_bounds__(256, 2) void corr16_kernel(const WorkerDev* __restr
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, kg = lane >> 4, ij = lane & 15;
   char* const ldsb = (char*)lds;
   const uint32_t plane_cells = (uint32_t)a.R * a.Cw, ncells = a.tp * plane_cells;
-  const uint32_t wl = ncells * CB;  // weights behind the patch
+  const uint32_t ps = (uint32_t)a.ps, wl = 4u * ps;  // weights behind the patch
   // channel padding of the patch must read as zero
-  for (uint32_t i = tid; i < ncells * KM; i += 256) ((float4*)lds)[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+  for (uint32_t i = tid; i < ps / 4u; i += 256) ((float4*)lds)[i] = make_float4(0.f, 0.f, 0.f, 0.f);
 
   // per-thread patch pieces: global byte offset inside the first plane of a stage (kOobS: the cell lies outside
   // the input and reads as zero) and LDS byte offset with the piece's plane in bits 24-29
@@ -414,7 +417,8 @@ __global__ __launch_bounds__(256, 2) void corr16_kernel(const WorkerDev* __restr
         const uint32_t rr = div_small(rem, a.Cw, r_cw), cc = rem - rr * a.Cw;
         const int i1 = g.in_base[1] + q1_0 * c.is[1] + a.tapmin1 + (int)rr;
         const int i2 = g.in_base[2] + q2_0 * c.is[2] + a.tapmin2 + (int)cc;
-        loff[i] = (cell * CB + part * V * 4u) | (wp << 24);
+        const uint32_t ch = part * V;  // first channel of the piece
+        loff[i] = (cell * CG + (ch / KM) * ps + (ch % KM) * 4u) | (wp << 24);
         if (i1 >= 0 && i1 < g.in_ext[1] && i2 >= 0 && i2 < g.in_ext[2])
           goff[i] = (wp * sin + (uint32_t)i1 * si1 + (uint32_t)i2 * si2 + part * V) * 4u;
       }
@@ -431,18 +435,21 @@ __global__ __launch_bounds__(256, 2) void corr16_kernel(const WorkerDev* __restr
     if (pidx >= (uint32_t)npos) pidx = 0;  // idle position: multiplies something in range, never stored
     const uint32_t wp = div_small(pidx, trtc, r_trtc), rem = pidx - wp * trtc;
     const uint32_t wr = div_small(rem, a.tc, r_tc), wc = rem - wr * a.tc;
-    abase[mt] = ((wp * a.R + wr * c.is[1]) * a.Cw + wc * c.is[2]) * CB + kg * KM * 4u;
+    abase[mt] = ((wp * a.R + wr * c.is[1]) * a.Cw + wc * c.is[2]) * CG + kg * ps;
+    // the four positions of this lane's accumulator registers are consecutive: walk (plane, row, column)
+    uint32_t po = (wave * 4 + mt) * 16 + 4 * kg;
+    uint32_t op = div_small(po, trtc, r_trtc);
+    uint32_t orow = div_small(po - op * trtc, a.tc, r_tc), ocol = po - op * trtc - orow * a.tc;
 #pragma unroll
     for (int v = 0; v < 4; ++v) {
-      const uint32_t po = (wave * 4 + mt) * 16 + 4 * kg + v;
       soff[mt][v] = kOobS;
-      if (po < (uint32_t)npos) {
-        const uint32_t op = div_small(po, trtc, r_trtc), orem = po - op * trtc;
-        const uint32_t orow = div_small(orem, a.tc, r_tc), ocol = orem - orow * a.tc;
-        const int q1 = q1_0 + (int)orow, q2 = q2_0 + (int)ocol;
-        if (q1 < g.nq[1] && q2 < g.nq[2] && ij < c.nc)
-          soff[mt][v] = (op * son + (uint32_t)(g.out_base[1] + g.os[1] * q1) * so1 +
-                         (uint32_t)(g.out_base[2] + g.os[2] * q2) * so2 + ij) * 4u;
+      const int q1 = q1_0 + (int)orow, q2 = q2_0 + (int)ocol;
+      if (po + v < (uint32_t)npos && q1 < g.nq[1] && q2 < g.nq[2] && ij < c.nc)
+        soff[mt][v] = (op * son + (uint32_t)(g.out_base[1] + g.os[1] * q1) * so1 +
+                       (uint32_t)(g.out_base[2] + g.os[2] * q2) * so2 + ij) * 4u;
+      if (++ocol == (uint32_t)a.tc) {
+        ocol = 0;
+        if (++orow == (uint32_t)a.tr) orow = 0, ++op;
       }
     }
   }
@@ -486,7 +493,18 @@ __global__ __launch_bounds__(256, 2) void corr16_kernel(const WorkerDev* __restr
   auto write_stage = [&](bool weights) {
 #pragma unroll
     for (int i = 0; i < kPA16; ++i)
-      if (loff[i] != kSkip) *(PT*)(ldsb + (loff[i] & 0xffffu)) = ra[i];
+      if (loff[i] != kSkip) {
+        const uint32_t o = loff[i] & 0xffffu;
+        if constexpr (V == 1 || KM == 4) {
+          *(PT*)(ldsb + o) = ra[i];
+        } else if constexpr (KM == 2) {  // a 16-byte piece covers two channel groups
+          *(uint2*)(ldsb + o) = make_uint2(ra[i][0], ra[i][1]);
+          *(uint2*)(ldsb + o + ps) = make_uint2(ra[i][2], ra[i][3]);
+        } else {  // KM == 1: four groups of one channel
+#pragma unroll
+          for (int j = 0; j < 4; ++j) *(uint32_t*)(ldsb + o + j * ps) = ra[i][j];
+        }
+      }
     if (weights) {
 #pragma unroll
       for (int i = 0; i < kPB16; ++i) {
@@ -598,7 +616,7 @@ __global__ __launch_bounds__(256) void corr16_weights_kernel(const float* __rest
 }
 
 struct Corr16Shape {
-  int km, tp, tr, tc, R, Cw, tapmin1, tapmin2, g0, tiles_max, lds;
+  int km, tp, tr, tc, R, Cw, ps, tapmin1, tapmin2, g0, tiles_max, lds;
 };
 
 bool corr16_shape(const distdl_plan* p, const CorrArgs& c, bool vec, Corr16Shape& s) {
@@ -632,7 +650,6 @@ bool corr16_shape(const distdl_plan* p, const CorrArgs& c, bool vec, Corr16Shape
   }
   if (nq1max < 1 || nq2max < 1 || planes_max < 1) return false;
   const bool stack = c.nt[0] <= 1 && nq0max == 1 && p->n_b > 1;
-  const int cb = s.km * 16;
   double best = -1.0;
   for (int tc = 1; tc <= std::min(nq2max, 256); ++tc)
     for (int tr = 1; tr <= std::min(nq1max, 256 / tc); ++tr) {
@@ -641,7 +658,11 @@ bool corr16_shape(const distdl_plan* p, const CorrArgs& c, bool vec, Corr16Shape
       for (; tp >= 1; --tp) {
         const int R = (tr - 1) * c.is[1] + span[1] + 1, Cw = (tc - 1) * c.is[2] + span[2] + 1;
         const int64_t cells = (int64_t)tp * R * Cw;
-        const int64_t lds = cells * cb + (int64_t)ntaps * 64 * s.km * 4;
+        // dwords between channel groups: at least the cells of a group, congruent to 16 * km modulo 64 so that
+        // the four groups of an operand read fall on different banks
+        int64_t psd = cells * s.km;
+        psd += ((16 * s.km - psd) % 64 + 64) % 64;
+        const int64_t lds = 16 * psd + (int64_t)ntaps * 64 * s.km * 4;
         if (cells * (c.kc / V) > kPA16 * 256 || lds > 64 * 1024) continue;
         const double used = (double)(tp * tr * tc) / 256.0;
         const double cols = (double)nq2max / ((double)((nq2max + tc - 1) / tc) * tc);
@@ -651,7 +672,7 @@ bool corr16_shape(const distdl_plan* p, const CorrArgs& c, bool vec, Corr16Shape
         const double score = used * cols * rows * pl / (1.0 + 0.3 * std::max(0.0, ratio - 1.0));
         if (score > best + 1e-12) {
           best = score;
-          s.tp = tp, s.tr = tr, s.tc = tc, s.R = R, s.Cw = Cw, s.lds = (int)lds;
+          s.tp = tp, s.tr = tr, s.tc = tc, s.R = R, s.Cw = Cw, s.ps = (int)(4 * psd), s.lds = (int)lds;
         }
         break;  // the largest plane count that fits is the one to score
       }
@@ -667,6 +688,7 @@ bool corr16_shape(const distdl_plan* p, const CorrArgs& c, bool vec, Corr16Shape
   // a workgroup's set-up (its address tables) costs about as much as two window steps of a 3 x 3 kernel, so walk
   // through several steps when there are more tiles than the chip runs at a time (two workgroups per CU)
   s.g0 = (int)std::max<int64_t>(1, std::min<int64_t>(steps_max, (tiles1 * p->n_workers + 511) / 512));
+  s.g0 = (int)((steps_max + (steps_max + s.g0 - 1) / s.g0 - 1) / ((steps_max + s.g0 - 1) / s.g0));  // even groups
   tiles1 = 0;
   for (const WorkerDev& wd : p->workers) {
     const PerWorker g = derive(wd, c);
@@ -690,14 +712,14 @@ int launch_corr16(distdl_plan* p, const CorrArgs& c, bool vec, const float* w, f
   if (s.tiles_max == 0) return DISTDL_OK;
   Corr16Args a{};
   a.c = c;
-  a.tp = s.tp, a.tr = s.tr, a.tc = s.tc, a.R = s.R, a.Cw = s.Cw;
+  a.tp = s.tp, a.tr = s.tr, a.tc = s.tc, a.R = s.R, a.Cw = s.Cw, a.ps = s.ps;
   a.tapmin1 = s.tapmin1, a.tapmin2 = s.tapmin2;
   a.g0 = s.g0;
   a.tiles_max = s.tiles_max;
   a.ntaps = c.nt[1] * c.nt[2];
   for (int t1 = 0; t1 < c.nt[1]; ++t1)
     for (int t2 = 0; t2 < c.nt[2]; ++t2)
-      a.tapo[t1 * c.nt[2] + t2] = ((c.tapoff[1][t1] - s.tapmin1) * s.Cw + (c.tapoff[2][t2] - s.tapmin2)) * s.km * 16;
+      a.tapo[t1 * c.nt[2] + t2] = ((c.tapoff[1][t1] - s.tapmin1) * s.Cw + (c.tapoff[2][t2] - s.tapmin2)) * s.km * 4;
   a.wt = wscratch;
   a.bias = bias;
   const int taps = p->ksize[0] * p->ksize[1] * p->ksize[2];
