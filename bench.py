@@ -678,6 +678,33 @@ def main():
         return w, {"metric": w.metric, "value": w.value(s_sec), "unit": w.unit, "steps": steps,
                    "ms_per_step": s_sec * 1e3, "dtype": w.dtype, "config": w.describe, "kernels": kern}
 
+    def graph_step_ms(w, steps):
+        """Launch-bound workloads: the same step recorded once into a HIP graph and replayed (a warmed-up step
+        allocates nothing and copies no tables).  None if the runtime refuses the capture."""
+        try:
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(side):
+                for _ in range(3):
+                    w.step()
+            side.synchronize()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=side):
+                w.step()
+            for _ in range(3):
+                graph.replay()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(steps):
+                graph.replay()
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t0) / steps * 1e3
+        except RuntimeError as e:
+            print(f"bench.py: graph capture failed: {e}", file=sys.stderr)
+            return None
+
+    if args.workload in ("cfg2", "cfg4"):
+        line["ms_per_step_graph"] = graph_step_ms(wl, args.steps)
     if args.workload == "cfg5" and not args.no_movement:
         # the other half of the metric: the movement primitives on their own (H, H* on this geometry, B, R and
         # adjoints on large arrays), timed after the convolution step
@@ -696,6 +723,8 @@ def main():
                                  ("cfg4", lambda: SmallCnnWorkload(), 50)):
             w, rep = side_run(make, steps)
             rep["kernel_launches_per_step"] = sum(k["launches"] for k in rep["kernels"].values()) / steps
+            if tag in ("cfg2", "cfg4"):
+                rep["ms_per_step_graph"] = graph_step_ms(w, steps)
             line["other_configs"][tag] = rep
             del w
     if getattr(wl, "sweep_on", False):

@@ -125,14 +125,24 @@ struct TaskTable {
   int64_t cells_copied = 0, cells_zeroed = 0, cells_band = 0;
 };
 
-// A device copy of a caller's host pointer array, re-uploaded only when it
-// changes.
+// Device copies of a caller's host pointer arrays.  A call site sees a few arrays in turn (the activations of
+// the forward pass, the gradients of the backward pass, ...): the table keeps the last kSlots of them, each in
+// its own device block, so that in steady state upload() finds its array and copies nothing -- which also keeps
+// a warmed-up call free of copies when the caller records it into a graph.  `dev` and `host` are the block and
+// the array selected by the last upload().
 struct PtrTable {
+  static constexpr int kSlots = 8;
+  struct Entry {
+    std::vector<const void*> ptrs;
+    void** dev = nullptr;
+    size_t cap = 0;
+    hipStream_t stream = nullptr;
+    uint64_t used = 0;
+  };
+  std::vector<Entry> entries;
   std::vector<const void*> host;
   void** dev = nullptr;
-  size_t cap = 0;
-  hipStream_t last_stream = nullptr;
-  bool valid = false;
+  uint64_t clock = 0;
   int upload(const void* const* ptrs, size_t n, hipStream_t stream);
   void release();
 };

@@ -19,28 +19,46 @@ int set_error(int code, const char* fmt, ...) {
 }
 
 int PtrTable::upload(const void* const* ptrs, size_t n, hipStream_t stream) {
-  if (valid && host.size() == n && last_stream == stream && std::memcmp(host.data(), ptrs, n * sizeof(void*)) == 0)
-    return DISTDL_OK;
-  if (n > cap) {
-    if (dev) (void)hipFree(dev);
-    dev = nullptr;
-    DISTDL_HIP_TRY(hipMalloc((void**)&dev, n * sizeof(void*)));
-    cap = n;
+  ++clock;
+  Entry* pick = nullptr;
+  for (Entry& e : entries)
+    if (e.dev && e.stream == stream && e.ptrs.size() == n && std::memcmp(e.ptrs.data(), ptrs, n * sizeof(void*)) == 0) {
+      pick = &e;
+      break;
+    }
+  if (!pick) {
+    if ((int)entries.size() < kSlots) {
+      entries.emplace_back();
+      pick = &entries.back();
+    } else {
+      pick = &entries[0];
+      for (Entry& e : entries)
+        if (e.used < pick->used) pick = &e;  // least recently used
+    }
+    if (n > pick->cap) {
+      if (pick->dev) (void)hipFree(pick->dev);
+      pick->dev = nullptr;
+      pick->cap = 0;
+      DISTDL_HIP_TRY(hipMalloc((void**)&pick->dev, n * sizeof(void*)));
+      pick->cap = n;
+    }
+    pick->ptrs.assign(ptrs, ptrs + n);
+    // pageable source: the runtime stages the bytes before returning, and the copy is ordered on the stream
+    // after earlier kernels that read the block
+    DISTDL_HIP_TRY(hipMemcpyAsync(pick->dev, pick->ptrs.data(), n * sizeof(void*), hipMemcpyHostToDevice, stream));
+    pick->stream = stream;
   }
-  host.assign(ptrs, ptrs + n);
-  // pageable source: the runtime stages the bytes before returning, and the
-  // copy is ordered on the stream after earlier kernels that read the table
-  DISTDL_HIP_TRY(hipMemcpyAsync(dev, host.data(), n * sizeof(void*), hipMemcpyHostToDevice, stream));
-  last_stream = stream;
-  valid = true;
+  pick->used = clock;
+  dev = pick->dev;
+  host = pick->ptrs;
   return DISTDL_OK;
 }
 
 void PtrTable::release() {
-  if (dev) (void)hipFree(dev);
+  for (Entry& e : entries)
+    if (e.dev) (void)hipFree(e.dev);
+  entries.clear();
   dev = nullptr;
-  cap = 0;
-  valid = false;
 }
 
 // ---- per-dimension geometry ------------------------------------------------

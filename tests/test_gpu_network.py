@@ -57,6 +57,40 @@ def test_small_cnn_step_matches_oracle(n_b):
     assert_close(prim.gather_bulk([from_cl(t) for t in net.c1_dx], part1), g_want["images"], tol, "d images")
 
 
+def test_small_cnn_step_replayed_from_a_graph_matches_eager():
+    """A warmed-up step allocates nothing and copies no tables, so it can be recorded into a HIP graph: three
+    replays, each on a new batch loaded by eager copies in between, must reproduce the eager step bit for bit."""
+    require_gpu()
+    from bench import SmallCnn
+    n_b = 32
+    case = syn.cnn_case(dict(syn.CONFIGS["cfg4"], n_b=n_b))
+    net = SmallCnn(n_b, case["params"])
+    part1 = geo.Partition.for_kernel((28, 28), (2, 2), (5, 5), ONE2, (2, 2), ONE2)
+    rng = np.random.default_rng(8)
+    batches = [(rng.standard_normal(case["images"].shape).astype(np.float32),
+                rng.standard_normal(case["target"].shape).astype(np.float32)) for _ in range(3)]
+    load = lambda img, tgt: net.load_batch([to_cl(b) for b in prim.scatter_bulk(img, part1, fill=np.float32(0.0))], tgt)
+    snapshot = lambda: [net.loss.clone(), net.dw1.clone(), net.db3.clone(), net.a5["dW"][3].clone(), net.c1_dx[2].clone()]
+    side = torch.cuda.Stream()
+    eager = []
+    with torch.cuda.stream(side):
+        for img, tgt in batches:                       # eager steps on the stream the graph will be recorded on
+            load(img, tgt)
+            net.step()
+            eager.append(snapshot())
+    side.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        net.step()
+    for (img, tgt), want in zip(batches, eager):
+        load(img, tgt)                                 # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for got, ref in zip(snapshot(), want):
+            assert torch.equal(got, ref)
+
+
 def test_pool_and_repartition_against_oracle_on_unbalanced_geometry():
     """App. B.1 fourth example extended to two dimensions: halos of 1 and 2 and "extra" input of 1 and 2."""
     require_gpu()
