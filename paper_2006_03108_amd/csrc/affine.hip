@@ -60,19 +60,6 @@ struct distdl_affine_plan {
 
 namespace distdl {
 
-__device__ inline float ld(const float* p, size_t i) { return p[i]; }
-__device__ inline float ld(const uint16_t* p, size_t i) { return __uint_as_float((uint32_t)p[i] << 16); }
-__device__ inline void st(float* p, size_t i, float v) { p[i] = v; }
-__device__ inline void st(uint16_t* p, size_t i, float v) {
-  uint32_t u = __float_as_uint(v);
-  if ((u & 0x7fffffffu) > 0x7f800000u) {
-    p[i] = (uint16_t)((u >> 16) | 0x40u);
-    return;
-  }
-  u += 0x7fffu + ((u >> 16) & 1u);
-  p[i] = (uint16_t)(u >> 16);
-}
-
 // ---- reference-shaped kernels (any sizes) -----------------------------------
 
 // grid: (ceil(n_b * max_fo / 256), P_fo)

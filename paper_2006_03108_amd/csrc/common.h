@@ -57,6 +57,20 @@ struct DimGeom {
   int64_t buf, bulk_off, origin;
 };
 
+// Element access by storage type (uint16_t holds bf16: widened on load, rounded to nearest even on store).
+__device__ inline float ld(const float* p, size_t i) { return p[i]; }
+__device__ inline float ld(const uint16_t* p, size_t i) { return __uint_as_float((uint32_t)p[i] << 16); }
+__device__ inline void st(float* p, size_t i, float v) { p[i] = v; }
+__device__ inline void st(uint16_t* p, size_t i, float v) {
+  uint32_t u = __float_as_uint(v);
+  if ((u & 0x7fffffffu) > 0x7f800000u) {
+    p[i] = (uint16_t)((u >> 16) | 0x40u);
+    return;
+  }
+  u += 0x7fffu + ((u >> 16) & 1u);
+  p[i] = (uint16_t)(u >> 16);
+}
+
 // Per-worker geometry as the kernels read it (3 feature dims, leading dims of
 // extent 1 when D < 3).
 struct WorkerDev {

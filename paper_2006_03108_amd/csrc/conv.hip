@@ -41,7 +41,8 @@ static ConvDev conv_params(const distdl_plan* p) {
 }
 
 // wt[(t*Ci + ci)*Co + co] = w[(co*Ci + ci)*T + t]
-__global__ void relayout_w_kernel(const float* __restrict__ w, float* __restrict__ wt, int co_n, int ci_n, int taps) {
+template <class T>
+__global__ void relayout_w_kernel(const T* __restrict__ w, float* __restrict__ wt, int co_n, int ci_n, int taps) {
   int idx = blockIdx.x * blockDim.x + threadIdx.x;
   int total = co_n * ci_n * taps;
   if (idx >= total) return;
@@ -49,44 +50,46 @@ __global__ void relayout_w_kernel(const float* __restrict__ w, float* __restrict
   int r = idx / co_n;
   int ci = r % ci_n;
   int t = r / ci_n;
-  wt[idx] = w[((size_t)co * ci_n + ci) * taps + t];
+  wt[idx] = ld(w, ((size_t)co * ci_n + ci) * taps + t);
 }
 
 // ---- reference-shaped kernels: any D, stride, dilation, channel count -------
 
+template <class T>
 __global__ __launch_bounds__(256) void conv_fwd_direct_kernel(const WorkerDev* __restrict__ workers,
                                                               void* const* x_bufs, const float* __restrict__ wt,
-                                                              const float* __restrict__ bias, void* const* y_bufs,
+                                                              const T* __restrict__ bias, void* const* y_bufs,
                                                               ConvDev c) {
   const WorkerDev wd = workers[blockIdx.y];
   const int64_t total = (int64_t)c.n_b * wd.out[0] * wd.out[1] * wd.out[2] * c.co;
   int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (idx >= total) return;
-  const float* __restrict__ x = (const float*)x_bufs[blockIdx.y];
-  float* __restrict__ y = (float*)y_bufs[blockIdx.y];
+  const T* __restrict__ x = (const T*)x_bufs[blockIdx.y];
+  T* __restrict__ y = (T*)y_bufs[blockIdx.y];
   int co = (int)(idx % c.co);
   int64_t r = idx / c.co;
   int o2 = (int)(r % wd.out[2]); r /= wd.out[2];
   int o1 = (int)(r % wd.out[1]); r /= wd.out[1];
   int o0 = (int)(r % wd.out[0]);
   int n = (int)(r / wd.out[0]);
-  float acc = bias ? bias[co] : 0.f;
+  float acc = bias ? ld(bias, co) : 0.f;
   const int64_t s2 = c.ci, s1 = (int64_t)wd.buf[2] * s2, s0 = (int64_t)wd.buf[1] * s1, sn = (int64_t)wd.buf[0] * s0;
-  const float* xn = x + n * sn;
+  const T* xn = x + n * sn;
   int t = 0;
   for (int t0 = 0; t0 < c.k[0]; ++t0)
     for (int t1 = 0; t1 < c.k[1]; ++t1)
       for (int t2 = 0; t2 < c.k[2]; ++t2, ++t) {
-        const float* xc = xn + (wd.origin[0] + o0 * c.s[0] + t0 * c.dil[0]) * s0 +
+        const T* xc = xn + (wd.origin[0] + o0 * c.s[0] + t0 * c.dil[0]) * s0 +
                           (wd.origin[1] + o1 * c.s[1] + t1 * c.dil[1]) * s1 +
                           (wd.origin[2] + o2 * c.s[2] + t2 * c.dil[2]) * s2;
         const float* wp = wt + (size_t)t * c.ci * c.co + co;
-        for (int ci = 0; ci < c.ci; ++ci) acc = fmaf(wp[(size_t)ci * c.co], xc[ci], acc);
+        for (int ci = 0; ci < c.ci; ++ci) acc = fmaf(wp[(size_t)ci * c.co], ld(xc, ci), acc);
       }
-  y[idx] = acc;
+  st(y, idx, acc);
 }
 
 // dx^[n][cell][ci] over the whole padded buffer (cells no output reads get 0).
+template <class T>
 __global__ __launch_bounds__(256) void conv_bwd_data_direct_kernel(const WorkerDev* __restrict__ workers,
                                                                    void* const* dy_bufs, const float* __restrict__ wt,
                                                                    void* const* dx_bufs, ConvDev c) {
@@ -94,8 +97,8 @@ __global__ __launch_bounds__(256) void conv_bwd_data_direct_kernel(const WorkerD
   const int64_t total = (int64_t)c.n_b * wd.buf[0] * wd.buf[1] * wd.buf[2] * c.ci;
   int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (idx >= total) return;
-  const float* __restrict__ dy = (const float*)dy_bufs[blockIdx.y];
-  float* __restrict__ dx = (float*)dx_bufs[blockIdx.y];
+  const T* __restrict__ dy = (const T*)dy_bufs[blockIdx.y];
+  T* __restrict__ dx = (T*)dx_bufs[blockIdx.y];
   int ci = (int)(idx % c.ci);
   int64_t r = idx / c.ci;
   int c2 = (int)(r % wd.buf[2]); r /= wd.buf[2];
@@ -116,17 +119,18 @@ __global__ __launch_bounds__(256) void conv_bwd_data_direct_kernel(const WorkerD
         int q2 = c2 - wd.origin[2] - t2 * c.dil[2];
         bool ok2 = q2 >= 0 && q2 % c.s[2] == 0 && q2 / c.s[2] < wd.out[2];
         if (!(ok0 && ok1 && ok2)) continue;
-        const float* dyc = dy + n * son + (q0 / c.s[0]) * so0 + (q1 / c.s[1]) * so1 + (q2 / c.s[2]) * so2;
+        const T* dyc = dy + n * son + (q0 / c.s[0]) * so0 + (q1 / c.s[1]) * so1 + (q2 / c.s[2]) * so2;
         const float* wp = wt + ((size_t)t * c.ci + ci) * c.co;
-        for (int co = 0; co < c.co; ++co) acc = fmaf(wp[co], dyc[co], acc);
+        for (int co = 0; co < c.co; ++co) acc = fmaf(wp[co], ld(dyc, co), acc);
       }
     }
   }
-  dx[idx] = acc;
+  st(dx, idx, acc);
 }
 
 // Partial dw^ / db^ of one worker over one chunk of its (n, o) positions, in
 // the wt layout followed by Co bias slots.
+template <class T>
 __global__ __launch_bounds__(256) void conv_bwd_weight_direct_kernel(const WorkerDev* __restrict__ workers,
                                                                      void* const* x_bufs, void* const* dy_bufs,
                                                                      float* __restrict__ partial, ConvDev c,
@@ -136,15 +140,15 @@ __global__ __launch_bounds__(256) void conv_bwd_weight_direct_kernel(const Worke
   const int nw = c.taps * c.ci * c.co;
   int idx = blockIdx.x * 256 + threadIdx.x;
   if (idx >= nw + c.co) return;
-  const float* __restrict__ x = (const float*)x_bufs[worker];
-  const float* __restrict__ dy = (const float*)dy_bufs[worker];
+  const T* __restrict__ x = (const T*)x_bufs[worker];
+  const T* __restrict__ dy = (const T*)dy_bufs[worker];
   const int64_t npos = (int64_t)c.n_b * wd.out[0] * wd.out[1] * wd.out[2];
   const int64_t per = (npos + nchunks - 1) / nchunks;
   const int64_t p0 = chunk * per, p1 = std::min<int64_t>(npos, p0 + per);
   float acc = 0.f;
   if (idx >= nw) {  // bias gradient slot
     int co = idx - nw;
-    for (int64_t p = p0; p < p1; ++p) acc += dy[p * c.co + co];
+    for (int64_t p = p0; p < p1; ++p) acc += ld(dy, p * c.co + co);
   } else {
     int co = idx % c.co;
     int r = idx / c.co;
@@ -161,10 +165,10 @@ __global__ __launch_bounds__(256) void conv_bwd_weight_direct_kernel(const Worke
       int o1 = (int)(rr % wd.out[1]); rr /= wd.out[1];
       int o0 = (int)(rr % wd.out[0]);
       int n = (int)(rr / wd.out[0]);
-      const float xv = x[n * sn + (wd.origin[0] + o0 * c.s[0] + t0 * c.dil[0]) * s0 +
-                         (wd.origin[1] + o1 * c.s[1] + t1 * c.dil[1]) * s1 +
-                         (wd.origin[2] + o2 * c.s[2] + t2 * c.dil[2]) * s2 + ci];
-      acc = fmaf(dy[p * c.co + co], xv, acc);
+      const float xv = ld(x, n * sn + (wd.origin[0] + o0 * c.s[0] + t0 * c.dil[0]) * s0 +
+                                (wd.origin[1] + o1 * c.s[1] + t1 * c.dil[1]) * s1 +
+                                (wd.origin[2] + o2 * c.s[2] + t2 * c.dil[2]) * s2 + ci);
+      acc = fmaf(ld(dy, p * c.co + co), xv, acc);
     }
   }
   partial[((size_t)worker * nchunks + chunk) * (nw + c.co) + idx] = acc;
@@ -172,10 +176,9 @@ __global__ __launch_bounds__(256) void conv_bwd_weight_direct_kernel(const Worke
 
 // R dw^, R db^ (Sec. 4, adjoint algorithm): sum the partials in worker order
 // and write dw in the caller's [Co][Ci][T] shape.
-template <int E>
+template <int E, class T>
 __global__ __launch_bounds__(256) void conv_reduce_dw_kernel(const float* __restrict__ partial, int nparts,
-                                                             float* __restrict__ dw, float* __restrict__ db,
-                                                             ConvDev c) {
+                                                             T* __restrict__ dw, T* __restrict__ db, ConvDev c) {
   // E elements per block, L = 256 / E lanes of partials each (few elements: more lanes, so that the launch still
   // has enough blocks); every lane adds its partials in ascending order (four independent chains for latency),
   // the lanes are then combined in ascending order
@@ -200,13 +203,13 @@ __global__ __launch_bounds__(256) void conv_reduce_dw_kernel(const float* __rest
 #pragma unroll
   for (int l = 1; l < L; ++l) sum += red[l][e];
   if (idx >= nw) {
-    if (db) db[idx - nw] = sum;
+    if (db) st(db, idx - nw, sum);
   } else {
     int co = idx % c.co;
     int r = idx / c.co;
     int ci = r % c.ci;
     int t = r / c.ci;
-    dw[((size_t)co * c.ci + ci) * c.taps + t] = sum;
+    st(dw, ((size_t)co * c.ci + ci) * c.taps + t, sum);
   }
 }
 
@@ -221,11 +224,10 @@ static int direct_chunks(const distdl_plan* p) {
 
 static int check_conv_plan(const distdl_plan* p) {
   if (p->explicit_halo) return set_error(DISTDL_ERR_UNSUPPORTED, "conv: plan has no kernel (explicit halo plan)");
-  if (p->dtype != DISTDL_F32) return set_error(DISTDL_ERR_UNSUPPORTED, "conv: only fp32 is implemented");
   return DISTDL_OK;
 }
 
-static int prepare_weights(distdl_plan* p, const float* w, hipStream_t st) {
+static int prepare_weights(distdl_plan* p, const void* w, hipStream_t st) {
   ConvDev c = conv_params(p);
   size_t n = (size_t)c.taps * c.ci * c.co;
   if (p->wt_elems < n) {
@@ -236,8 +238,12 @@ static int prepare_weights(distdl_plan* p, const float* w, hipStream_t st) {
     p->wt_elems = n;
   }
   ProfScope prof("conv_relayout_w", st);
-  hipLaunchKernelGGL(relayout_w_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, w, p->d_wt, c.co, c.ci,
-                     c.taps);
+  if (p->dtype == DISTDL_BF16)
+    hipLaunchKernelGGL(relayout_w_kernel<uint16_t>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st,
+                       (const uint16_t*)w, p->d_wt, c.co, c.ci, c.taps);
+  else
+    hipLaunchKernelGGL(relayout_w_kernel<float>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, (const float*)w,
+                       p->d_wt, c.co, c.ci, c.taps);
   return DISTDL_OK;
 }
 
@@ -280,14 +286,16 @@ int conv_fwd_core(distdl_plan* plan, void* const x_bufs_dev[], const void* w_dev
   if (!plan || !x_bufs_dev || !w_dev || !y_dev) return set_error(DISTDL_ERR_NULL, "conv_fwd: null argument");
   int rc = check_conv_plan(plan);
   if (rc) return rc;
+  const bool bf16 = plan->dtype == DISTDL_BF16;
+  const uintptr_t esz = bf16 ? 2 : 4;
   for (int w = 0; w < plan->n_workers; ++w)
-    if (!y_dev[w] || (uintptr_t)y_dev[w] % 4) return set_error(DISTDL_ERR_NULL, "conv_fwd: y of worker %d null or misaligned", w);
+    if (!y_dev[w] || (uintptr_t)y_dev[w] % esz) return set_error(DISTDL_ERR_NULL, "conv_fwd: y of worker %d null or misaligned", w);
   if (halo) {
     if ((rc = run_halo(plan, false, plan->tab_x, x_bufs_dev, st))) return rc;  // x <- H x
   } else {
     if ((rc = plan_prepare_device(plan))) return rc;
     for (int w = 0; w < plan->n_workers; ++w)
-      if (!x_bufs_dev[w] || (uintptr_t)x_bufs_dev[w] % 4) return set_error(DISTDL_ERR_NULL, "conv_fwd: x of worker %d null or misaligned", w);
+      if (!x_bufs_dev[w] || (uintptr_t)x_bufs_dev[w] % esz) return set_error(DISTDL_ERR_NULL, "conv_fwd: x of worker %d null or misaligned", w);
   }
   if ((rc = plan->tab_x.upload((const void* const*)x_bufs_dev, plan->n_workers, st))) return rc;
   if ((rc = plan->tab_y.upload((const void* const*)y_dev, plan->n_workers, st))) return rc;
@@ -301,17 +309,21 @@ int conv_fwd_core(distdl_plan* plan, void* const x_bufs_dev[], const void* w_dev
     return DISTDL_OK;
   }
   if (aligned && corr_mfma_supported(plan)) {
-    if ((rc = conv_fwd_mfma(plan, (const float*)w_dev, (const float*)bias_dev, st))) return rc;
+    if ((rc = conv_fwd_mfma(plan, w_dev, bias_dev, st))) return rc;
     DISTDL_HIP_TRY(hipGetLastError());
     return DISTDL_OK;
   }
-  if ((rc = prepare_weights(plan, (const float*)w_dev, st))) return rc;
+  if ((rc = prepare_weights(plan, w_dev, st))) return rc;
   ConvDev c = conv_params(plan);
   int64_t total = plan->n_b * plan->max_out_cells * c.co;
   dim3 grid((unsigned)((total + 255) / 256), plan->n_workers);
   ProfScope prof("conv_fwd_direct", st);
-  hipLaunchKernelGGL(conv_fwd_direct_kernel, grid, dim3(256), 0, st, plan->d_workers, plan->tab_x.dev, plan->d_wt,
-                     (const float*)bias_dev, plan->tab_y.dev, c);
+  if (bf16)
+    hipLaunchKernelGGL(conv_fwd_direct_kernel<uint16_t>, grid, dim3(256), 0, st, plan->d_workers, plan->tab_x.dev,
+                       plan->d_wt, (const uint16_t*)bias_dev, plan->tab_y.dev, c);
+  else
+    hipLaunchKernelGGL(conv_fwd_direct_kernel<float>, grid, dim3(256), 0, st, plan->d_workers, plan->tab_x.dev,
+                       plan->d_wt, (const float*)bias_dev, plan->tab_y.dev, c);
   DISTDL_HIP_TRY(hipGetLastError());
   return DISTDL_OK;
 }
@@ -323,12 +335,15 @@ int conv_bwd_core(distdl_plan* plan, const void* const x_bufs_dev[], const void*
     return set_error(DISTDL_ERR_NULL, "conv_bwd: null argument");
   int rc = check_conv_plan(plan);
   if (rc) return rc;
+  const bool bf16 = plan->dtype == DISTDL_BF16;
+  const uintptr_t esz = bf16 ? 2 : 4;
   if (workspace_bytes < distdl_conv_bwd_workspace(plan) || (uintptr_t)workspace_dev % 16)
     return set_error(DISTDL_ERR_INVALID_ARG, "conv_bwd: workspace too small or misaligned (%zu < %zu)", workspace_bytes,
                      distdl_conv_bwd_workspace(plan));
   for (int w = 0; w < plan->n_workers; ++w) {
     if (!x_bufs_dev[w] || !dy_dev[w] || !dx_bufs_dev[w]) return set_error(DISTDL_ERR_NULL, "conv_bwd: worker %d has a null array", w);
-    if ((uintptr_t)x_bufs_dev[w] % 4 || (uintptr_t)dy_dev[w] % 4) return set_error(DISTDL_ERR_INVALID_ARG, "conv_bwd: misaligned array");
+    if ((uintptr_t)x_bufs_dev[w] % esz || (uintptr_t)dy_dev[w] % esz || (uintptr_t)dx_bufs_dev[w] % esz)
+      return set_error(DISTDL_ERR_INVALID_ARG, "conv_bwd: misaligned array");
   }
   if ((rc = plan_prepare_device(plan))) return rc;
   if ((rc = plan->tab_x.upload(x_bufs_dev, plan->n_workers, st))) return rc;
@@ -341,18 +356,24 @@ int conv_bwd_core(distdl_plan* plan, const void* const x_bufs_dev[], const void*
   bool vec16 = aligned && plan->n_ci % 4 == 0 && plan->n_co % 4 == 0;
   for (int w = 0; w < plan->n_workers; ++w) vec16 &= (uintptr_t)x_bufs_dev[w] % 16 == 0;
   const bool wgrad16 = wgrad16_supported(plan, vec16);
-  const bool wgrad_mfma = !wgrad16 && wgrad_mfma_supported(plan) && plan->n_workers * wgrad_chunks(plan) <= 65535;
+  const bool wgrad_mfma = !wgrad16 && wgrad_mfma_supported(plan) && plan->n_workers * wgrad_chunks(plan) <= 65535 &&
+                          (!bf16 || vec16);
   // [dConv]* with respect to x, into the whole padded buffers
   int64_t total = plan->n_b * plan->max_buf_cells * c.ci;
   if (corr16_bwd_supported(plan, aligned)) {
     if ((rc = conv_bwd_data16(plan, (const float*)w_dev, aligned, st))) return rc;
   } else if (data_mfma) {
-    if ((rc = conv_bwd_data_mfma(plan, (const float*)w_dev, st))) return rc;
+    if ((rc = conv_bwd_data_mfma(plan, w_dev, st))) return rc;
   } else {
-    if ((rc = prepare_weights(plan, (const float*)w_dev, st))) return rc;
+    if ((rc = prepare_weights(plan, w_dev, st))) return rc;
     ProfScope prof("conv_bwd_data_direct", st);
-    hipLaunchKernelGGL(conv_bwd_data_direct_kernel, dim3((unsigned)((total + 255) / 256), plan->n_workers), dim3(256),
-                       0, st, plan->d_workers, plan->tab_dy.dev, plan->d_wt, plan->tab_dx.dev, c);
+    const dim3 dgrid((unsigned)((total + 255) / 256), plan->n_workers);
+    if (bf16)
+      hipLaunchKernelGGL(conv_bwd_data_direct_kernel<uint16_t>, dgrid, dim3(256), 0, st, plan->d_workers,
+                         plan->tab_dy.dev, plan->d_wt, plan->tab_dx.dev, c);
+    else
+      hipLaunchKernelGGL(conv_bwd_data_direct_kernel<float>, dgrid, dim3(256), 0, st, plan->d_workers,
+                         plan->tab_dy.dev, plan->d_wt, plan->tab_dx.dev, c);
   }
   // [dConv]* with respect to w and b, then R over the workers
   int nchunks = wgrad16 ? wgrad16_chunks(plan, vec16) : wgrad_mfma ? wgrad_chunks(plan) : direct_chunks(plan);
@@ -363,18 +384,30 @@ int conv_bwd_core(distdl_plan* plan, const void* const x_bufs_dev[], const void*
     if ((rc = conv_wgrad_mfma(plan, (float*)workspace_dev, st))) return rc;
   } else {
     ProfScope prof("conv_bwd_weight_direct", st);
-    hipLaunchKernelGGL(conv_bwd_weight_direct_kernel, dim3((unsigned)((nw + 255) / 256), nchunks, plan->n_workers),
-                       dim3(256), 0, st, plan->d_workers, plan->tab_x.dev, plan->tab_dy.dev, (float*)workspace_dev, c,
-                       nchunks);
+    const dim3 wgrid((unsigned)((nw + 255) / 256), nchunks, plan->n_workers);
+    if (bf16)
+      hipLaunchKernelGGL(conv_bwd_weight_direct_kernel<uint16_t>, wgrid, dim3(256), 0, st, plan->d_workers,
+                         plan->tab_x.dev, plan->tab_dy.dev, (float*)workspace_dev, c, nchunks);
+    else
+      hipLaunchKernelGGL(conv_bwd_weight_direct_kernel<float>, wgrid, dim3(256), 0, st, plan->d_workers,
+                         plan->tab_x.dev, plan->tab_dy.dev, (float*)workspace_dev, c, nchunks);
   }
   {
     ProfScope prof("conv_reduce_dw", st);
-    if (nw <= 8192)
-      hipLaunchKernelGGL(conv_reduce_dw_kernel<16>, dim3((unsigned)((nw + 15) / 16)), dim3(256), 0, st,
-                         (const float*)workspace_dev, nchunks * plan->n_workers, (float*)dw_dev, (float*)dbias_dev, c);
+    const float* part = (const float*)workspace_dev;
+    const int nparts = nchunks * plan->n_workers;
+    if (nw <= 8192 && bf16)
+      hipLaunchKernelGGL((conv_reduce_dw_kernel<16, uint16_t>), dim3((unsigned)((nw + 15) / 16)), dim3(256), 0, st, part,
+                         nparts, (uint16_t*)dw_dev, (uint16_t*)dbias_dev, c);
+    else if (nw <= 8192)
+      hipLaunchKernelGGL((conv_reduce_dw_kernel<16, float>), dim3((unsigned)((nw + 15) / 16)), dim3(256), 0, st, part,
+                         nparts, (float*)dw_dev, (float*)dbias_dev, c);
+    else if (bf16)
+      hipLaunchKernelGGL((conv_reduce_dw_kernel<64, uint16_t>), dim3((unsigned)((nw + 63) / 64)), dim3(256), 0, st, part,
+                         nparts, (uint16_t*)dw_dev, (uint16_t*)dbias_dev, c);
     else
-      hipLaunchKernelGGL(conv_reduce_dw_kernel<64>, dim3((unsigned)((nw + 63) / 64)), dim3(256), 0, st,
-                         (const float*)workspace_dev, nchunks * plan->n_workers, (float*)dw_dev, (float*)dbias_dev, c);
+      hipLaunchKernelGGL((conv_reduce_dw_kernel<64, float>), dim3((unsigned)((nw + 63) / 64)), dim3(256), 0, st, part,
+                         nparts, (float*)dw_dev, (float*)dbias_dev, c);
   }
   DISTDL_HIP_TRY(hipGetLastError());
   // dx <- H* dx

@@ -27,7 +27,7 @@ struct CorrArgs {
   int32_t tiles_max;   // tiles of the largest worker
   const float* wt;     // weights in staging order
   const int* tapinfo;  // device tables behind the weights: 8 plane offsets, then one patch offset per (t1, t2)
-  const float* bias;   // may be null
+  const void* bias;    // may be null; element type of the tensors
 };
 
 struct WgradArgs {
@@ -81,8 +81,8 @@ bool wgrad_mfma_supported(const distdl_plan* p);
 size_t bwd_scratch_elems(const distdl_plan* p);
 int wgrad_chunks(const distdl_plan* p);
 // All three expect the plan's pointer tables (tab_x, tab_y, tab_dy, tab_dx) to be uploaded.
-int conv_fwd_mfma(distdl_plan* p, const float* w, const float* bias, hipStream_t st);
-int conv_bwd_data_mfma(distdl_plan* p, const float* w, hipStream_t st);
+int conv_fwd_mfma(distdl_plan* p, const void* w, const void* bias, hipStream_t st);
+int conv_bwd_data_mfma(distdl_plan* p, const void* w, hipStream_t st);
 int conv_wgrad_mfma(distdl_plan* p, float* partial, hipStream_t st);
 
 // Kernels for layers with at most 16 input and 16 output channels (16 x 16 MFMA tiles).  `vec`: channel counts

@@ -45,6 +45,32 @@ __device__ inline __amdgpu_buffer_rsrc_t make_rsrc(const void* p, uint32_t bytes
   return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)bytes, 0x00020000);
 }
 
+// Four consecutive channels as fp32 bit patterns: a 16-byte piece of an fp32 tensor, or an 8-byte piece of a
+// bf16 tensor widened on the way (bf16 tensors are multiplied in fp32 on the matrix cores).
+template <bool BF16>
+__device__ inline u32x4 load4(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff) {
+  if constexpr (BF16) {
+    const auto t = __builtin_amdgcn_raw_buffer_load_b64(r, voff, soff, 0);
+    return u32x4{t[0] << 16, t[0] & 0xffff0000u, t[1] << 16, t[1] & 0xffff0000u};
+  } else {
+    return __builtin_amdgcn_raw_buffer_load_b128(r, voff, soff, 0);
+  }
+}
+
+// fp32 -> bf16, round to nearest even, NaN kept quiet
+__device__ inline uint16_t to_bf16(float v) {
+  uint32_t u = __float_as_uint(v);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+
+template <bool BF16>
+__device__ inline float load_scalar(const void* p, size_t i) {
+  if constexpr (BF16) return __uint_as_float((uint32_t)((const uint16_t*)p)[i] << 16);
+  else return ((const float*)p)[i];
+}
+
 // On this target VALU instructions do not overlap with MFMA execution on the same SIMD, so the loops
 // below are written to issue as few of them as possible: every global access is a buffer instruction
 // with a precomputed per-lane offset (out-of-range pieces carry an offset that fails the range check:
@@ -55,10 +81,12 @@ __device__ inline __amdgpu_buffer_rsrc_t make_rsrc(const void* p, uint32_t bytes
 // NT: taps per plane (nt[1] * nt[2]) known at compile time, or 0: with NT > 0 the tap loop is unrolled,
 // the LDS address of every (M-tile, tap) operand is computed once per workgroup and the weight operand
 // of tap t is an immediate offset, which removes the per-tap address arithmetic from the stage loop.
-template <int MT, int PA, int PB, int NT>
+// BF16: the tensors in memory (input, output, bias) are bf16; the weights were widened by the re-layout kernel.
+template <int MT, int PA, int PB, int NT, bool BF16>
 __global__ __launch_bounds__(256, 2) void corr_mfma_kernel(const WorkerDev* __restrict__ workers,
                                                            void* const* in_bufs, void* const* out_bufs, CorrArgs a) {
   extern __shared__ float4 lds[];
+  constexpr uint32_t ES = BF16 ? 2u : 4u;  // bytes per element in memory
   // LDS: patch (a_vec4 16-byte units), weights (nb_vec4), one spare unit that absorbs the pieces nobody
   // needs, then the tap table.
   const int nb_vec4 = a.nt[1] * a.nt[2] * 64;
@@ -86,8 +114,8 @@ __global__ __launch_bounds__(256, 2) void corr_mfma_kernel(const WorkerDev* __re
   const int si2 = a.kc, si1 = g.in_ext[2] * si2, si0 = g.in_ext[1] * si1;
   const uint32_t sin = (uint32_t)g.in_ext[0] * si0;
   const uint32_t so2 = a.nc, so1 = g.out_ext[2] * so2, so0 = g.out_ext[1] * so1, son = g.out_ext[0] * so0;
-  const __amdgpu_buffer_rsrc_t rin = make_rsrc(in_bufs[worker], (uint32_t)a.n_b * sin * 4u);
-  const __amdgpu_buffer_rsrc_t rout = make_rsrc(out_bufs[worker], (uint32_t)a.n_b * son * 4u);
+  const __amdgpu_buffer_rsrc_t rin = make_rsrc(in_bufs[worker], (uint32_t)a.n_b * sin * ES);
+  const __amdgpu_buffer_rsrc_t rout = make_rsrc(out_bufs[worker], (uint32_t)a.n_b * son * ES);
   const int ncc = (a.kc + 7) / 8;
   const int nt0 = a.nt[0];
   const __amdgpu_buffer_rsrc_t rw =
@@ -113,7 +141,7 @@ __global__ __launch_bounds__(256, 2) void corr_mfma_kernel(const WorkerDev* __re
       const int cq = (int)fd_div((uint32_t)c, a.div_is2), cr = c - cq * a.is[2];
       loff[i] = (((rr * 2 + ph) * a.is[2] + cr) * a.CwQ + cq) * 16;
       if (i1 >= 0 && i1 < g.in_ext[1] && i2 >= 0 && i2 < g.in_ext[2])
-        goff[i] = ((i1 * si1 + i2 * si2 + ph * 4) * 4) | ((a.kc & 7) ? ph : 0);
+        goff[i] = ((i1 * si1 + i2 * si2 + ph * 4) * ES) | ((a.kc & 7) ? ph : 0);
     }
   }
   uint32_t bl[PB];
@@ -143,10 +171,10 @@ __global__ __launch_bounds__(256, 2) void corr_mfma_kernel(const WorkerDev* __re
       const int q1 = q1_0 + orow, q2 = q2_0 + ocol;
       soff[mt][v] = kOob;
       if (orow < a.tr && q1 < g.nq[1] && q2 < g.nq[2] && ch < a.nc)
-        soff[mt][v] = ((g.out_base[1] + g.os[1] * q1) * so1 + (g.out_base[2] + g.os[2] * q2) * so2 + ch) * 4;
+        soff[mt][v] = ((g.out_base[1] + g.os[1] * q1) * so1 + (g.out_base[2] + g.os[2] * q2) * so2 + ch) * ES;
     }
   }
-  const float bias = (a.bias && ch < a.nc) ? a.bias[ch] : 0.f;
+  const float bias = (a.bias && ch < a.nc) ? load_scalar<BF16>(a.bias, ch) : 0.f;
   const uint32_t boff0 = tid * 16, bread = ((h * 32 + m) + a.a_vec4) * 16;  // weight piece / operand addresses
 
   const int* __restrict__ tapinfo = a.tapinfo;  // [0..7]: plane offsets, [8..]: patch offset per (t1, t2)
@@ -181,17 +209,17 @@ __global__ __launch_bounds__(256, 2) void corr_mfma_kernel(const WorkerDev* __re
   u32x4 ra[PA], rb[PB];
   auto load_stage = [&](const StagePos& sp) {
     const int t0 = sp.t0, cc = sp.cc;
-    const uint32_t sbase = ((uint32_t)sp.n * sin + (uint32_t)plane_of(sp.q0, t0) * si0 + cc * 8) * 4u;
+    const uint32_t sbase = ((uint32_t)sp.n * sin + (uint32_t)plane_of(sp.q0, t0) * si0 + cc * 8) * ES;
     if (ragged && cc == ncc - 1) {
 #pragma unroll
       for (int i = 0; i < PA; ++i)
-        ra[i] = __builtin_amdgcn_raw_buffer_load_b128(rin, (goff[i] & 1u) ? kOob : goff[i], sbase, 0);
+        ra[i] = load4<BF16>(rin, (goff[i] & 1u) ? kOob : goff[i], sbase);
     } else if (ragged) {
 #pragma unroll
-      for (int i = 0; i < PA; ++i) ra[i] = __builtin_amdgcn_raw_buffer_load_b128(rin, goff[i] & ~1u, sbase, 0);
+      for (int i = 0; i < PA; ++i) ra[i] = load4<BF16>(rin, goff[i] & ~1u, sbase);
     } else {
 #pragma unroll
-      for (int i = 0; i < PA; ++i) ra[i] = __builtin_amdgcn_raw_buffer_load_b128(rin, goff[i], sbase, 0);
+      for (int i = 0; i < PA; ++i) ra[i] = load4<BF16>(rin, goff[i], sbase);
     }
     const uint32_t wbase = (uint32_t)(t0 * ncc + cc) * nb_vec4 * 16u;
 #pragma unroll
@@ -294,13 +322,16 @@ __global__ __launch_bounds__(256, 2) void corr_mfma_kernel(const WorkerDev* __re
       compute(acc);
       __syncthreads();  // everyone is done reading this stage
     }
-    const uint32_t obase = ((uint32_t)on * son + (uint32_t)(g.out_base[0] + g.os[0] * oq0) * so0) * 4u;
+    const uint32_t obase = ((uint32_t)on * son + (uint32_t)(g.out_base[0] + g.os[0] * oq0) * so0) * ES;
     if (++oq0 == nq0) oq0 = 0, ++on;
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
       for (int v = 0; v < 16; ++v)
-        __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(acc[mt][v] + bias), rout, soff[mt][v], obase, 0);
+        if constexpr (BF16)
+          __builtin_amdgcn_raw_buffer_store_b16(to_bf16(acc[mt][v] + bias), rout, soff[mt][v], obase, 0);
+        else
+          __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(acc[mt][v] + bias), rout, soff[mt][v], obase, 0);
   }
 }
 
@@ -308,7 +339,8 @@ __global__ __launch_bounds__(256, 2) void corr_mfma_kernel(const WorkerDev* __re
 //   dst[ntile][t0][cc][t1][t2][h][nn][j] = W[tap(t0,t1,t2)][k = cc*8 + 4h + j][n = ntile*32 + nn]
 // with W[tap][k][n] = w[n][k][tap] (forward: n = co, k = ci) or w[k][n][tap]
 // (data gradient: k = co, n = ci), zero beyond the channel counts.
-__global__ __launch_bounds__(256) void corr_weights_kernel(const float* __restrict__ w, float* __restrict__ dst,
+template <bool BF16>
+__global__ __launch_bounds__(256) void corr_weights_kernel(const void* __restrict__ w, float* __restrict__ dst,
                                                            CorrArgs a, int ci_n, int co_n, int taps, int k1, int k2) {
   const int ncc = (a.kc + 7) / 8;
   const int64_t total = (int64_t)a.ntn * a.nt[0] * ncc * a.nt[1] * a.nt[2] * 256;
@@ -335,7 +367,7 @@ __global__ __launch_bounds__(256) void corr_weights_kernel(const float* __restri
   if (k < a.kc && nch < a.nc) {
     const int tap = (a.tapid[0][t0] * k1 + a.tapid[1][t1]) * k2 + a.tapid[2][t2];
     const int co = a.mode == 0 ? nch : k, ci = a.mode == 0 ? k : nch;
-    v = w[((size_t)co * ci_n + ci) * taps + tap];
+    v = load_scalar<BF16>(w, ((size_t)co * ci_n + ci) * taps + tap);
   }
   dst[idx] = v;
 }
@@ -552,12 +584,13 @@ __global__ __launch_bounds__(256, 2) void wgrad_lds_kernel(const WorkerDev* __re
 // vector instructions: ring slots advance in scalar registers, out-of-range rows are switched off through
 // the scalar offset of the buffer load, and every LDS read of the inner loop is an immediate offset.
 // A wave with TW - 1 taps repeats its last tap (never stored), so all waves stay in step.
-template <int TW, int S2>
+template <int TW, int S2, bool BF16>
 __global__ __launch_bounds__(256, 2) void wgrad_taps_kernel(const WorkerDev* __restrict__ workers, void* const* x_bufs,
                                                             void* const* dy_bufs, float* __restrict__ partial,
                                                             WgradArgs a) {
   extern __shared__ float4 wt_lds[];
   constexpr int NX = 5;  // input-row pieces per thread and step
+  constexpr uint32_t ES = BF16 ? 2u : 4u;  // bytes per element in memory (bf16 is widened while it is staged)
   const int tid = threadIdx.x, lane = tid & 63, h = lane >> 5, m = lane & 31;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int t0 = blockIdx.x;
@@ -585,8 +618,8 @@ __global__ __launch_bounds__(256, 2) void wgrad_taps_kernel(const WorkerDev* __r
 
   const uint32_t sx2 = a.ci, sx1 = wd.buf[2] * sx2, sx0 = wd.buf[1] * sx1, sxn = wd.buf[0] * sx0;
   const uint32_t sy2 = a.co, sy1 = wd.out[2] * sy2, sy0 = wd.out[1] * sy1, syn = wd.out[0] * sy0;
-  const __amdgpu_buffer_rsrc_t rx = make_rsrc(x_bufs[worker], (uint32_t)a.n_b * sxn * 4u);
-  const __amdgpu_buffer_rsrc_t ry = make_rsrc(dy_bufs[worker], (uint32_t)a.n_b * syn * 4u);
+  const __amdgpu_buffer_rsrc_t rx = make_rsrc(x_bufs[worker], (uint32_t)a.n_b * sxn * ES);
+  const __amdgpu_buffer_rsrc_t ry = make_rsrc(dy_bufs[worker], (uint32_t)a.n_b * syn * ES);
 
   floatx16 acc[TW];
 #pragma unroll
@@ -616,24 +649,24 @@ __global__ __launch_bounds__(256, 2) void wgrad_taps_kernel(const WorkerDev* __r
       const int cell = prest[i] >> 3, q4 = (prest[i] & 7) * 4;
       pg[i] = kOob;  // pieces beyond the row's cells or channels stage zeros
       if (cell < a.ncell && seg * 32 * S2 + cell < row_cells && ci_t * 32 + q4 < a.ci)
-        pg[i] = ((seg * 32 * S2 + cell) * sx2 + ci_t * 32 + q4) * 4u;
+        pg[i] = ((seg * 32 * S2 + cell) * sx2 + ci_t * 32 + q4) * ES;
     }
     const int pos = tid >> 3, q4 = (tid & 7) * 4;
     pgy = kOob;
-    if (seg * 32 + pos < O2 && co_t * 32 + q4 < a.co) pgy = ((seg * 32 + pos) * sy2 + co_t * 32 + q4) * 4u;
+    if (seg * 32 + pos < O2 && co_t * 32 + q4 < a.co) pgy = ((seg * 32 + pos) * sy2 + co_t * 32 + q4) * ES;
   };
   u32x4 rp[NX], rpy;
   auto fetch = [&](int n, int o0, int o1) {
     const int c0 = wd.origin[0] + o0 * a.s[0] + t0 * a.dil[0];
     const int r_first = wd.origin[1] + o1 * s1 + span - s1;  // buffer row of new row 0
-    const uint32_t xb = ((uint32_t)n * sxn + (uint32_t)c0 * sx0 + (uint32_t)r_first * sx1 + wd.origin[2] * sx2) * 4u;
+    const uint32_t xb = ((uint32_t)n * sxn + (uint32_t)c0 * sx0 + (uint32_t)r_first * sx1 + wd.origin[2] * sx2) * ES;
 #pragma unroll
     for (int i = 0; i < NX; ++i) {
       // rows beyond the buffer (and unused slots) read as zero: the scalar offset fails the range check
-      const uint32_t so = (prr[i] < s1 && r_first + prr[i] < wd.buf[1]) ? xb + (uint32_t)prr[i] * sx1 * 4u : kOob;
-      rp[i] = __builtin_amdgcn_raw_buffer_load_b128(rx, pg[i], so, 0);
+      const uint32_t so = (prr[i] < s1 && r_first + prr[i] < wd.buf[1]) ? xb + (uint32_t)prr[i] * sx1 * ES : kOob;
+      rp[i] = load4<BF16>(rx, pg[i], so);
     }
-    rpy = __builtin_amdgcn_raw_buffer_load_b128(ry, pgy, ((uint32_t)n * syn + (uint32_t)o0 * sy0 + (uint32_t)o1 * sy1) * 4u, 0);
+    rpy = load4<BF16>(ry, pgy, ((uint32_t)n * syn + (uint32_t)o0 * sy0 + (uint32_t)o1 * sy1) * ES);
   };
   int nslot = 0;      // ring slot of the step's new row 0
   int tslot[TW];      // ring slot of the row each tap reads
@@ -666,14 +699,13 @@ __global__ __launch_bounds__(256, 2) void wgrad_taps_kernel(const WorkerDev* __r
           const int wrow = o1_begin * s1 + rr;  // window row, relative to the first tap of output row 0
           const bool row_ok = wd.origin[1] + wrow < wd.buf[1];
           const uint32_t rb = ((uint32_t)n * sxn + (uint32_t)c0 * sx0 + (uint32_t)(wd.origin[1] + wrow) * sx1 +
-                               (wd.origin[2] + seg * 32 * S2) * sx2 + ci_t * 32) * 4u;
+                               (wd.origin[2] + seg * 32 * S2) * sx2 + ci_t * 32) * ES;
           for (int rest = tid; rest < rowp; rest += 256) {
             const int cell = rest >> 3, q4 = (rest & 7) * 4;
             uint32_t off = kOob;
             if (row_ok && cell < a.ncell && seg * 32 * S2 + cell < row_cells && ci_t * 32 + q4 < a.ci)
-              off = (cell * sx2 + q4) * 4u;
-            *(u32x4*)(ldsb + (uint32_t)(wrow % ring) * pitch + (uint32_t)rest * 16u) =
-                __builtin_amdgcn_raw_buffer_load_b128(rx, off, rb, 0);
+              off = (cell * sx2 + q4) * ES;
+            *(u32x4*)(ldsb + (uint32_t)(wrow % ring) * pitch + (uint32_t)rest * 16u) = load4<BF16>(rx, off, rb);
           }
         }
       }
@@ -724,11 +756,12 @@ __global__ __launch_bounds__(256, 2) void wgrad_taps_kernel(const WorkerDev* __r
 
 // db^ partial of one (worker, chunk): sum of dy over the chunk's positions,
 // written to the slot's trailing Co entries.  One block per slot.
+template <bool BF16>
 __global__ __launch_bounds__(256) void bias_partial_kernel(const WorkerDev* __restrict__ workers, void* const* dy_bufs,
                                                            float* __restrict__ partial, WgradArgs a) {
   const int worker = blockIdx.x / a.nchunks, chunk = blockIdx.x - worker * a.nchunks;
   const WorkerDev wd = workers[worker];
-  const float* __restrict__ dy = (const float*)dy_bufs[worker];
+  const void* __restrict__ dy = dy_bufs[worker];
   const int nrows = a.n_b * wd.out[0] * wd.out[1];
   const int per = (nrows + a.nchunks - 1) / a.nchunks;
   const int64_t p0 = (int64_t)chunk * per * wd.out[2];
@@ -744,8 +777,8 @@ __global__ __launch_bounds__(256) void bias_partial_kernel(const WorkerDev* __re
       int64_t p = p0 + (threadIdx.x >> 5);
       for (; p + 56 < p1; p += 64)
 #pragma unroll
-        for (int u = 0; u < 8; ++u) part[u] += dy[(p + 8 * u) * a.co + co];
-      for (; p < p1; p += 8) part[0] += dy[p * a.co + co];
+        for (int u = 0; u < 8; ++u) part[u] += load_scalar<BF16>(dy, (p + 8 * u) * a.co + co);
+      for (; p < p1; p += 8) part[0] += load_scalar<BF16>(dy, p * a.co + co);
       acc = ((part[0] + part[1]) + (part[2] + part[3])) + ((part[4] + part[5]) + (part[6] + part[7]));
     }
     red[threadIdx.x] = acc;
@@ -841,7 +874,7 @@ static void max_nq(const distdl_plan* p, const CorrArgs& a, int& nq1, int& nq2) 
 }
 
 bool corr_mfma_supported(const distdl_plan* p) {
-  if (p->dtype != DISTDL_F32 || p->explicit_halo) return false;
+  if (p->explicit_halo) return false;
   if (p->n_ci % 4 || p->n_co % 4) return false;  // 16-byte channel pieces
   // buffer instructions address one worker's tensor with 31-bit byte offsets
   if ((double)p->n_b * p->max_buf_cells * std::max(p->n_ci, p->n_co) * 4.0 >= 2147480000.0) return false;
@@ -908,7 +941,7 @@ static size_t corr_weight_elems(const CorrArgs& a) {
 // weights + the tap tables (8 + 64 ints), kept 16-byte aligned
 static size_t corr_scratch_elems(const CorrArgs& a) { return corr_weight_elems(a) + 72; }
 
-static int launch_corr(distdl_plan* p, CorrArgs a, const float* w, float* wscratch, const float* bias, void** in_tab,
+static int launch_corr(distdl_plan* p, CorrArgs a, const void* w, float* wscratch, const void* bias, void** in_tab,
                        void** out_tab, const char* name, hipStream_t st) {
   int nq1max, nq2max;
   max_nq(p, a, nq1max, nq2max);
@@ -935,26 +968,36 @@ static int launch_corr(distdl_plan* p, CorrArgs a, const float* w, float* wscrat
   if (a.tiles_max == 0) return DISTDL_OK;
   a.wt = wscratch;
   a.bias = bias;
+  const bool bf16 = p->dtype == DISTDL_BF16;
   const int taps = p->ksize[0] * p->ksize[1] * p->ksize[2];
   const size_t welems = corr_weight_elems(a);
   a.tapinfo = (const int*)(wscratch + welems);
   {
     ProfScope prof("conv_relayout_w", st);
-    hipLaunchKernelGGL(corr_weights_kernel, dim3((unsigned)std::max<size_t>(1, (welems + 255) / 256)), dim3(256), 0,
-                       st, w, wscratch, a, (int)p->n_ci, (int)p->n_co, taps, p->ksize[1], p->ksize[2]);
+    if (bf16)
+      hipLaunchKernelGGL(corr_weights_kernel<true>, dim3((unsigned)std::max<size_t>(1, (welems + 255) / 256)),
+                         dim3(256), 0, st, w, wscratch, a, (int)p->n_ci, (int)p->n_co, taps, p->ksize[1], p->ksize[2]);
+    else
+      hipLaunchKernelGGL(corr_weights_kernel<false>, dim3((unsigned)std::max<size_t>(1, (welems + 255) / 256)),
+                         dim3(256), 0, st, w, wscratch, a, (int)p->n_ci, (int)p->n_co, taps, p->ksize[1], p->ksize[2]);
   }
   int64_t blocks = (int64_t)a.tiles_max * p->n_workers;
   blocks = (blocks + 7) / 8 * 8;
   const int lds = lds_bytes(a);
   const bool small = a.R * a.Cw * 2 <= 4 * 256 && a.nt[1] * a.nt[2] * 64 <= 3 * 256;
   ProfScope prof(name, st);
-#define DISTDL_LAUNCH_CORR(MT_, PA_, PB_, NT_)                                                                       \
+#define DISTDL_LAUNCH_CORR_T(MT_, PA_, PB_, NT_, BF_)                                                                \
   do {                                                                                                               \
     if (lds > 64 * 1024)                                                                                             \
-      DISTDL_HIP_TRY(hipFuncSetAttribute((const void*)corr_mfma_kernel<MT_, PA_, PB_, NT_>,                          \
+      DISTDL_HIP_TRY(hipFuncSetAttribute((const void*)corr_mfma_kernel<MT_, PA_, PB_, NT_, BF_>,                     \
                                          hipFuncAttributeMaxDynamicSharedMemorySize, lds));                          \
-    hipLaunchKernelGGL((corr_mfma_kernel<MT_, PA_, PB_, NT_>), dim3((unsigned)blocks), dim3(256), lds, st,           \
+    hipLaunchKernelGGL((corr_mfma_kernel<MT_, PA_, PB_, NT_, BF_>), dim3((unsigned)blocks), dim3(256), lds, st,      \
                        p->d_workers, in_tab, out_tab, a);                                                            \
+  } while (0)
+#define DISTDL_LAUNCH_CORR(MT_, PA_, PB_, NT_)                                                                       \
+  do {                                                                                                               \
+    if (bf16) DISTDL_LAUNCH_CORR_T(MT_, PA_, PB_, NT_, true);                                                        \
+    else DISTDL_LAUNCH_CORR_T(MT_, PA_, PB_, NT_, false);                                                            \
   } while (0)
   const int ntaps = a.nt[1] * a.nt[2];
   if (mt == 2 && small && ntaps == 9) DISTDL_LAUNCH_CORR(2, 4, 3, 9);
@@ -965,6 +1008,7 @@ static int launch_corr(distdl_plan* p, CorrArgs a, const float* w, float* wscrat
   else if (small) DISTDL_LAUNCH_CORR(1, 4, 3, 0);
   else DISTDL_LAUNCH_CORR(1, kMaxPieces, kMaxBPieces, 0);
 #undef DISTDL_LAUNCH_CORR
+#undef DISTDL_LAUNCH_CORR_T
   return DISTDL_OK;
 }
 
@@ -980,7 +1024,7 @@ int ensure_wscratch(distdl_plan* p, size_t elems) {
   return DISTDL_OK;
 }
 
-int conv_fwd_mfma(distdl_plan* p, const float* w, const float* bias, hipStream_t st) {
+int conv_fwd_mfma(distdl_plan* p, const void* w, const void* bias, hipStream_t st) {
   CorrArgs a = forward_args(p);
   int rc = ensure_wscratch(p, std::max(corr_scratch_elems(a), bwd_scratch_elems(p)));
   if (rc) return rc;
@@ -999,7 +1043,7 @@ size_t bwd_scratch_elems(const distdl_plan* p) {
   return total;
 }
 
-int conv_bwd_data_mfma(distdl_plan* p, const float* w, hipStream_t st) {
+int conv_bwd_data_mfma(distdl_plan* p, const void* w, hipStream_t st) {
   CorrArgs fa = forward_args(p);
   int rc = ensure_wscratch(p, std::max(corr_scratch_elems(fa), bwd_scratch_elems(p)));
   if (rc) return rc;
@@ -1016,8 +1060,13 @@ int conv_bwd_data_mfma(distdl_plan* p, const float* w, hipStream_t st) {
   return DISTDL_OK;
 }
 
+static bool wgrad_rows_shape_ok(const distdl_plan* p);
+
+// bf16 tensors: only the plane-per-workgroup kernel widens its operands while it stages them (it also needs
+// 16-byte aligned arrays, which the caller checks).
 bool wgrad_mfma_supported(const distdl_plan* p) {
-  return p->dtype == DISTDL_F32 && !p->explicit_halo && p->ksize[2] <= kMaxK2;
+  if (p->explicit_halo || p->ksize[2] > kMaxK2) return false;
+  return p->dtype == DISTDL_F32 || wgrad_rows_shape_ok(p);
 }
 
 // Taps per wave of the plane-per-workgroup weight-gradient kernel (0: fewer taps than waves).
@@ -1107,19 +1156,25 @@ int conv_wgrad_mfma(distdl_plan* p, float* partial, hipStream_t st) {
   for (int w = 0; w < p->n_workers && aligned; ++w)
     aligned = (uintptr_t)p->tab_x.host[w] % 16 == 0 && (uintptr_t)p->tab_dy.host[w] % 16 == 0;
   const int lds = 4 * (a.ncell + 32) * 128;
+  const bool bf16 = p->dtype == DISTDL_BF16;
   if (aligned && wgrad_rows_shape_ok(p)) {
     const int rowp = (a.ncell * 8 + 63) & ~63;
     const int rlds = (a.span + a.s[1]) * rowp * 16 + 8192;
     const int tw = wgrad_taps_per_wave(p);
     dim3 rgrid((unsigned)a.k[0], grid.y, grid.z), rblock(256);
     ProfScope prof("conv_bwd_weight_mfma", st);
-#define DISTDL_LAUNCH_TAPS(TW_, S2_)                                                                                \
+#define DISTDL_LAUNCH_TAPS_T(TW_, S2_, BF_)                                                                         \
   do {                                                                                                              \
     if (rlds > 64 * 1024)                                                                                           \
-      DISTDL_HIP_TRY(hipFuncSetAttribute((const void*)wgrad_taps_kernel<TW_, S2_>,                                  \
+      DISTDL_HIP_TRY(hipFuncSetAttribute((const void*)wgrad_taps_kernel<TW_, S2_, BF_>,                             \
                                          hipFuncAttributeMaxDynamicSharedMemorySize, rlds));                        \
-    hipLaunchKernelGGL((wgrad_taps_kernel<TW_, S2_>), rgrid, rblock, rlds, st, p->d_workers, p->tab_x.dev,          \
+    hipLaunchKernelGGL((wgrad_taps_kernel<TW_, S2_, BF_>), rgrid, rblock, rlds, st, p->d_workers, p->tab_x.dev,     \
                        p->tab_dy.dev, partial, a);                                                                  \
+  } while (0)
+#define DISTDL_LAUNCH_TAPS(TW_, S2_)                                                                                \
+  do {                                                                                                              \
+    if (bf16) DISTDL_LAUNCH_TAPS_T(TW_, S2_, true);                                                                 \
+    else DISTDL_LAUNCH_TAPS_T(TW_, S2_, false);                                                                     \
   } while (0)
     if (tw == 3 && a.s[2] == 1) DISTDL_LAUNCH_TAPS(3, 1);
     else if (tw == 3) DISTDL_LAUNCH_TAPS(3, 2);
@@ -1128,7 +1183,9 @@ int conv_wgrad_mfma(distdl_plan* p, float* partial, hipStream_t st) {
     else if (a.s[2] == 1) DISTDL_LAUNCH_TAPS(7, 1);
     else DISTDL_LAUNCH_TAPS(7, 2);
 #undef DISTDL_LAUNCH_TAPS
+#undef DISTDL_LAUNCH_TAPS_T
   } else {
+    if (bf16) return set_error(DISTDL_ERR_UNSUPPORTED, "conv: bf16 weight gradient needs 16-byte aligned arrays");
     ProfScope prof("conv_bwd_weight_mfma", st);
     if (aligned && a.ncell <= 72 && a.k[2] <= 3)
       hipLaunchKernelGGL((wgrad_lds_kernel<3, 9>), grid, dim3(256), lds, st, p->d_workers, p->tab_x.dev,
@@ -1148,8 +1205,12 @@ int conv_wgrad_mfma(distdl_plan* p, float* partial, hipStream_t st) {
   }
   {
     ProfScope prof("conv_bias_partial", st);
-    hipLaunchKernelGGL(bias_partial_kernel, dim3((unsigned)(p->n_workers * a.nchunks)), dim3(256), 0, st, p->d_workers,
-                       p->tab_dy.dev, partial, a);
+    if (bf16)
+      hipLaunchKernelGGL(bias_partial_kernel<true>, dim3((unsigned)(p->n_workers * a.nchunks)), dim3(256), 0, st,
+                         p->d_workers, p->tab_dy.dev, partial, a);
+    else
+      hipLaunchKernelGGL(bias_partial_kernel<false>, dim3((unsigned)(p->n_workers * a.nchunks)), dim3(256), 0, st,
+                         p->d_workers, p->tab_dy.dev, partial, a);
   }
   return DISTDL_OK;
 }

@@ -104,6 +104,56 @@ def test_conv_fwd_bwd_against_partitioned_oracle(name, override, use_bias):
         assert_close(db.cpu().numpy(), db_want, TOL32, "db")
 
 
+CONV_BF16 = [
+    # matrix-core path (channel counts that are multiples of 4), 3-D strided, 2-D, dilated; then the direct kernels
+    ("cfg5", dict(in_shape=(24, 22, 40), P=(2, 2, 1), c_in=32, c_out=32), True),
+    ("cfg5u", dict(in_shape=(21, 23, 22), P=(2, 2, 2), c_in=32, c_out=32), False),
+    ("cfg2", dict(in_shape=(64, 64), n_b=2), True),
+    ("cfg2", dict(in_shape=(23, 41), n_b=2, c_in=4, c_out=40, P=(2, 3), ksize=(3, 4), stride=(2, 1), padding=(1, 2),
+                  dilation=(1, 2)), True),
+    ("cfg2", dict(in_shape=(19, 23), n_b=3, c_in=3, c_out=5, P=(2, 3), ksize=(3, 4), stride=(2, 1), padding=(1, 2),
+                  dilation=(1, 2)), True),
+    ("cfg1", dict(), True),
+]
+
+
+@pytest.mark.parametrize("name,override,use_bias", CONV_BF16, ids=[f"{n}-{i}" for i, (n, _, _) in enumerate(CONV_BF16)])
+def test_conv_bf16_fwd_bwd_against_partitioned_oracle(name, override, use_bias):
+    """bf16 tensors (inputs, weights, bias, outputs, gradients), fp32 accumulation: the oracle runs in fp64 on the
+    same bf16-representable inputs; bar 2e-2."""
+    require_gpu()
+    cfg, part, case = _conv_case(name, **override)
+    bf = torch.bfloat16
+    x, w, dyv = syn.to_bf16_values(case["x"]), syn.to_bf16_values(case["w"]), syn.to_bf16_values(case["dy"])
+    bias = syn.to_bf16_values(case["bias"] + 0.25) if use_bias else None
+    plan = dd.distdl_plan_create(cfg["D"], cfg["n_b"], cfg["c_in"], cfg["c_out"], cfg["in_shape"], cfg["P"],
+                                 cfg["ksize"], cfg["stride"], cfg["padding"], cfg["dilation"], bf)
+    x_bufs = [to_cl(b, bf) for b in prim.scatter_bulk(x, part, fill=np.float32(3.0))]
+    gw = torch.from_numpy(np.ascontiguousarray(w)).to(bf).cuda()
+    gb = torch.from_numpy(np.ascontiguousarray(bias)).to(bf).cuda() if use_bias else None
+    y = [torch.full((cfg["n_b"],) + part.out_shape(wk) + (cfg["c_out"],), 7.0, device="cuda", dtype=bf)
+         for wk in range(part.n_workers)]
+    dd.distdl_conv_fwd(plan, x_bufs, gw, gb, y)
+    dy = [to_cl(t, bf) for t in prim.scatter_out(dyv, part)]
+    dx_bufs = [torch.full_like(b, 5.0) for b in x_bufs]
+    dw = torch.full_like(gw, 9.0)
+    db = torch.full((cfg["c_out"],), 9.0, device="cuda", dtype=bf) if use_bias else None
+    ws = torch.empty(max(dd.distdl_conv_bwd_workspace(plan), 16), dtype=torch.uint8, device="cuda")
+    dd.distdl_conv_bwd(plan, x_bufs, gw, dy, dx_bufs, dw, db, ws)
+    torch.cuda.synchronize()
+    o_bufs = prim.scatter_bulk(x.astype(np.float64), part, fill=np.nan)
+    y_want = layers.dist_conv_forward(o_bufs, w.astype(np.float64), bias, part, cfg["stride"], cfg["dilation"])
+    dx_want, dw_want, db_want = layers.dist_conv_adjoint(o_bufs, w.astype(np.float64), prim.scatter_out(dyv, part), part,
+                                                         cfg["stride"], cfg["dilation"], use_bias)
+    for wk in range(part.n_workers):
+        assert np.array_equal(from_cl(x_bufs[wk]), o_bufs[wk].astype(np.float32)), "x <- H x must be exact"
+        assert_close(from_cl(y[wk]), y_want[wk], TOL16, f"y worker {wk}")
+        assert_close(from_cl(dx_bufs[wk]), dx_want[wk], TOL16, f"dx worker {wk}")
+    assert_close(dw.float().cpu().numpy(), dw_want, TOL16, "dw")
+    if use_bias:
+        assert_close(db.float().cpu().numpy(), db_want, TOL16, "db")
+
+
 def test_conv_cfg2_full_size():
     """cfg2 at its full size against the sequential definition (Sec. 5 claim:
     distributed == sequential)."""
