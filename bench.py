@@ -46,30 +46,31 @@ def _prod(v):
 class ConvWorkload:
     """cfg5 / cfg2: partitioned convolution forward + backward."""
 
-    def __init__(self, name):
+    def __init__(self, name, dtype="f32"):
         import torch
         import paper_2006_03108_amd as dd
         import synthetic_inputs as syn
         self.dd, self.torch, self.name = dd, torch, name
-        self.tag = name
+        self.tag = name if dtype == "f32" else name + "-bf16"
+        tdt = torch.float32 if dtype == "f32" else torch.bfloat16
         c = self.cfg = dict(syn.CONFIGS[name])
         self.plan = dd.distdl_plan_create(c["D"], c["n_b"], c["c_in"], c["c_out"], c["in_shape"], c["P"], c["ksize"],
-                                          c["stride"], c["padding"], c["dilation"])
+                                          c["stride"], c["padding"], c["dilation"], tdt)
         P = self.plan.n_workers
         geoms = [self.plan.query(w) for w in range(P)]
         self.out_global = [max(g["out_start"][d] + g["out_size"][d] for g in geoms) for d in range(c["D"])]
         taps = _prod(c["ksize"])
         w_std = syn.he_normal_std((c["c_out"], c["c_in"]) + tuple(c["ksize"]))
         # channels-last device buffers; bulk = N(0,1), halo / pad cells start as noise and are overwritten by H
-        self.x = [_dev_randn([c["n_b"]] + g["buf_shape"] + [c["c_in"]], 1000 + w) for w, g in enumerate(geoms)]
-        self.dy = [_dev_randn([c["n_b"]] + g["out_size"] + [c["c_out"]], 2000 + w) for w, g in enumerate(geoms)]
+        self.x = [_dev_randn([c["n_b"]] + g["buf_shape"] + [c["c_in"]], 1000 + w).to(tdt) for w, g in enumerate(geoms)]
+        self.dy = [_dev_randn([c["n_b"]] + g["out_size"] + [c["c_out"]], 2000 + w).to(tdt) for w, g in enumerate(geoms)]
         self.y = [torch.empty_like(t) for t in self.dy]
         self.dx = [torch.empty_like(t) for t in self.x]
-        self.w = _dev_randn((c["c_out"], c["c_in"]) + tuple(c["ksize"]), 7, std=w_std)
+        self.w = _dev_randn((c["c_out"], c["c_in"]) + tuple(c["ksize"]), 7, std=w_std).to(tdt)
         self.dw = torch.empty_like(self.w)
         self.ws = torch.empty(max(dd.distdl_conv_bwd_workspace(self.plan), 16), dtype=torch.uint8, device="cuda")
         stats = dd.distdl_plan_stats(self.plan)
-        esz = 4
+        esz = 4 if dtype == "f32" else 2
         per_cell = c["n_b"] * c["c_in"] * esz
         self.flops_fwd = 2.0 * c["n_b"] * c["c_out"] * c["c_in"] * taps * _prod(self.out_global)
         self.flops_step = 3.0 * self.flops_fwd
@@ -88,8 +89,9 @@ class ConvWorkload:
         self.nw = nw
         self.metric = "partitioned conv fwd+bwd TFLOP/s (halo exchange H, H* and dw sum-reduce included)"
         self.unit = "TFLOP/s"
-        self.dtype = "f32"
-        self.describe = {"workload": f"{name}: conv{c['D']}d fwd+bwd fp32 x[{c['n_b']},{c['c_in']}," +
+        self.dtype = "f32"       # the arithmetic type: bf16 tensors are multiplied and accumulated in fp32
+        self.storage = dtype
+        self.describe = {"workload": f"{self.tag}: conv{c['D']}d fwd+bwd {'fp32' if dtype == 'f32' else 'bf16 tensors, fp32 arithmetic,'} x[{c['n_b']},{c['c_in']}," +
                          ",".join(str(v) for v in c["in_shape"]) + f"] w[{c['c_out']},{c['c_in']}," +
                          ",".join(str(v) for v in c["ksize"]) + f"] stride {c['stride'][0]} pad {c['padding'][0]}, " +
                          "P=" + "x".join(str(v) for v in c["P"]) + f" ({P} virtual workers), channels-last",
@@ -599,7 +601,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="cfg5", choices=["cfg5", "cfg2", "cfg3", "cfg3-bf16", "cfg4", "movement"])
+    ap.add_argument("--workload", default="cfg5", choices=["cfg5", "cfg5-bf16", "cfg2", "cfg3", "cfg3-bf16", "cfg4", "movement"])
     ap.add_argument("--no-movement", action="store_true",
                     help="with the default workload: skip the movement kernels' own figures and the other configurations")
     ap.add_argument("--sweep", action="store_true",
@@ -625,6 +627,8 @@ def main():
         wl = SmallCnnWorkload()
     elif args.workload in ("cfg5", "cfg2"):
         wl = ConvWorkload(args.workload)
+    elif args.workload == "cfg5-bf16":
+        wl = ConvWorkload("cfg5", "bf16")
     else:
         wl = AffineWorkload("cfg3", "bf16" if args.workload.endswith("bf16") else "f32")
     if args.calibrate_copy:
@@ -718,6 +722,7 @@ def main():
         # the remaining single-GPU configurations, for reference (same harness, no CPU leg)
         line["other_configs"] = {}
         for tag, make, steps in (("cfg2", lambda: ConvWorkload("cfg2"), 50),
+                                 ("cfg5-bf16", lambda: ConvWorkload("cfg5", "bf16"), 3),
                                  ("cfg3", lambda: AffineWorkload("cfg3", "f32"), 50),
                                  ("cfg3-bf16", lambda: AffineWorkload("cfg3", "bf16"), 50),
                                  ("cfg4", lambda: SmallCnnWorkload(), 50)):

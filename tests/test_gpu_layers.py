@@ -23,19 +23,19 @@ def _conv_case(name, **override):
     return cfg, part, case
 
 
-def _run_conv(cfg, part, case, use_bias):
+def _run_conv(cfg, part, case, use_bias, dtype=torch.float32):
     plan = dd.distdl_plan_create(cfg["D"], cfg["n_b"], cfg["c_in"], cfg["c_out"], cfg["in_shape"], cfg["P"],
-                                 cfg["ksize"], cfg["stride"], cfg["padding"], cfg["dilation"])
-    x_bufs = [to_cl(b) for b in prim.scatter_bulk(case["x"], part, fill=np.float32(3.0))]
-    w = w_to_dev(case["w"])
-    bias = w_to_dev(case["bias"]) if use_bias else None
-    y = [torch.full((cfg["n_b"],) + part.out_shape(wk) + (cfg["c_out"],), 7.0, device="cuda")
+                                 cfg["ksize"], cfg["stride"], cfg["padding"], cfg["dilation"], dtype)
+    x_bufs = [to_cl(b, dtype) for b in prim.scatter_bulk(case["x"], part, fill=np.float32(3.0))]
+    w = w_to_dev(case["w"]).to(dtype)
+    bias = w_to_dev(case["bias"]).to(dtype) if use_bias else None
+    y = [torch.full((cfg["n_b"],) + part.out_shape(wk) + (cfg["c_out"],), 7.0, device="cuda", dtype=dtype)
          for wk in range(part.n_workers)]
     dd.distdl_conv_fwd(plan, x_bufs, w, bias, y)
-    dy = [to_cl(t) for t in prim.scatter_out(case["dy"], part)]
+    dy = [to_cl(t, dtype) for t in prim.scatter_out(case["dy"], part)]
     dx_bufs = [torch.full_like(b, 5.0) for b in x_bufs]
     dw = torch.full_like(w, 9.0)
-    db = torch.full((cfg["c_out"],), 9.0, device="cuda") if use_bias else None
+    db = torch.full((cfg["c_out"],), 9.0, device="cuda", dtype=dtype) if use_bias else None
     ws = torch.empty(max(dd.distdl_conv_bwd_workspace(plan), 16), dtype=torch.uint8, device="cuda")
     dd.distdl_conv_bwd(plan, x_bufs, w, dy, dx_bufs, dw, db, ws)
     torch.cuda.synchronize()
@@ -242,17 +242,22 @@ def _sample_indices(rng, shape, count):
     return [tuple(int(rng.integers(0, s)) for s in shape) for _ in range(count)]
 
 
-@pytest.mark.parametrize("name", ["cfg5", "cfg5u"])
-def test_conv_full_size_sampled(name):
+@pytest.mark.parametrize("name,dtype", [("cfg5", torch.float32), ("cfg5u", torch.float32), ("cfg5", torch.bfloat16)],
+                         ids=["cfg5", "cfg5u", "cfg5-bf16"])
+def test_conv_full_size_sampled(name, dtype):
     """The volumetric configuration at its full size, in the launch configuration the benchmark
     times: sampled outputs against the plain definition of Sec. 4 (cross-correlation and its
-    adjoint), computed one by one in fp64; halo cells against the global tensor (exact)."""
+    adjoint), computed one by one in fp64; halo cells against the global tensor (exact).  bf16: the same on
+    bf16-representable inputs at the bf16 bar."""
     require_gpu()
     cfg = dict(syn.CONFIGS[name])
     part = oracle_partition(cfg)
     case = syn.conv_case(cfg, part.global_out_shape())
+    tol = TOL32 if dtype == torch.float32 else TOL16
+    if dtype == torch.bfloat16:
+        case = {k: (syn.to_bf16_values(v) if isinstance(v, np.ndarray) else v) for k, v in case.items()}
     x, w, dy, bias = case["x"], case["w"].astype(np.float64), case["dy"], case["bias"]
-    x_bufs, y, dx_bufs, dw, db = _run_conv(cfg, part, case, True)
+    x_bufs, y, dx_bufs, dw, db = _run_conv(cfg, part, case, True, dtype)
     s, p, k = cfg["stride"], cfg["padding"], cfg["ksize"]
     n_in, n_out = cfg["in_shape"], part.global_out_shape()
     rng = np.random.default_rng(0)
@@ -287,10 +292,10 @@ def test_conv_full_size_sampled(name):
         got = y_host[wk][(0, slice(None)) + lo]
         errs.append(np.abs(got - want).max())
         y_glob_scale = max(y_glob_scale, np.abs(want).max())
-    assert max(errs) <= TOL32 * y_glob_scale, (max(errs), y_glob_scale)
+    assert max(errs) <= tol * y_glob_scale, (max(errs), y_glob_scale)
 
     # dw: sampled entries; dw[co,ci,kappa] = sum_o dy[co,o] x[ci, o*s - p + kappa]
-    dw_host = dw.cpu().numpy()
+    dw_host = dw.float().cpu().numpy()
     dy64 = dy[0].astype(np.float64)
     worst, scale = 0.0, np.abs(dw_host).max()
     for (co, ci, k0, k1, k2) in _sample_indices(rng, (cfg["c_out"], cfg["c_in"]) + tuple(k), 24):
@@ -302,9 +307,9 @@ def test_conv_full_size_sampled(name):
         isl = tuple(slice(o_lo[d] * s[d] - p[d] + kap[d], o_hi[d] * s[d] - p[d] + kap[d] + 1, s[d]) for d in range(3))
         want = float(np.sum(dy64[(co,) + osl] * x[(0, ci) + isl].astype(np.float64)))
         worst = max(worst, abs(dw_host[co, ci, k0, k1, k2] - want))
-    assert worst <= TOL32 * scale, (worst, scale)
+    assert worst <= tol * scale, (worst, scale)
     db_want = dy64.sum(axis=(1, 2, 3))
-    assert_close(db.cpu().numpy(), db_want, TOL32, "db")
+    assert_close(db.float().cpu().numpy(), db_want, tol, "db")
 
     # dx: sampled input cells; dx[ci,i] = sum_{co,kappa: (i + p - kappa) % s == 0} w[co,ci,kappa] dy[co,(i+p-kappa)/s]
     dx_host = {}
@@ -325,7 +330,7 @@ def test_conv_full_size_sampled(name):
         got = dx_host[wk][(0, slice(None)) + loc]
         worst = max(worst, np.abs(got - want).max())
         scale = max(scale, np.abs(want).max())
-    assert worst <= TOL32 * scale, (worst, scale)
+    assert worst <= tol * scale, (worst, scale)
     # halo and pad cells of dx end cleared (H* ran)
     for wk in list(dx_host)[:4]:
         mask = np.ones(part.buf_shape(wk), dtype=bool)
