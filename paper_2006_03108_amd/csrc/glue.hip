@@ -170,7 +170,18 @@ __global__ __launch_bounds__(256) void pool_bwd_kernel(const WorkerDev* __restri
 
 // Faster forms for channel counts that are multiples of 4 and 16-byte aligned buffers: a thread owns four
 // channels of one cell (one 16-byte access per tap).
-template <bool AVG>
+// streaming accesses for data that is touched once (windows that do not overlap)
+__device__ inline void nt_store4(float4* p, float4 v) {
+  typedef float f32x4 __attribute__((ext_vector_type(4)));
+  __builtin_nontemporal_store(f32x4{v.x, v.y, v.z, v.w}, (f32x4*)p);
+}
+__device__ inline float4 nt_load4(const float4* p) {
+  typedef float f32x4 __attribute__((ext_vector_type(4)));
+  const f32x4 v = __builtin_nontemporal_load((const f32x4*)p);
+  return make_float4(v[0], v[1], v[2], v[3]);
+}
+
+template <bool AVG, bool STREAM>
 __global__ __launch_bounds__(256) void pool_fwd_vec_kernel(const WorkerDev* __restrict__ workers,
                                                            const FastDiv* __restrict__ divs, void* const* x_bufs,
                                                            void* const* y_bufs, PoolDev d) {
@@ -195,9 +206,10 @@ __global__ __launch_bounds__(256) void pool_fwd_vec_kernel(const WorkerDev* __re
   for (int t0 = 0; t0 < d.k[0]; ++t0)
     for (int t1 = 0; t1 < d.k[1]; ++t1)
       for (int t2 = 0; t2 < d.k[2]; ++t2) {
-        const float4 v = x[n * sn + (wd.origin[0] + o0 * d.s[0] + t0 * d.dil[0]) * s0 +
+        const float4* xp = x + n * sn + (wd.origin[0] + o0 * d.s[0] + t0 * d.dil[0]) * s0 +
                            (wd.origin[1] + o1 * d.s[1] + t1 * d.dil[1]) * s1 +
-                           (wd.origin[2] + o2 * d.s[2] + t2 * d.dil[2]) * s2 + c];
+                           (wd.origin[2] + o2 * d.s[2] + t2 * d.dil[2]) * s2 + c;
+        const float4 v = STREAM ? nt_load4(xp) : *xp;
         if (first || v.x > best.x) best.x = v.x;
         if (first || v.y > best.y) best.y = v.y;
         if (first || v.z > best.z) best.z = v.z;
@@ -237,7 +249,7 @@ __global__ __launch_bounds__(256) void pool_bwd_window_kernel(const WorkerDev* _
   const int64_t s2 = c4, s1 = (int64_t)wd.buf[2] * s2, s0 = (int64_t)wd.buf[1] * s1, sn = (int64_t)wd.buf[0] * s0;
   const int64_t base = n * sn + (wd.origin[0] + o0 * d.s[0]) * s0 + (wd.origin[1] + o1 * d.s[1]) * s1 +
                        (wd.origin[2] + o2 * d.s[2]) * s2 + c;
-  const float4 g = dy[idx];
+  const float4 g = nt_load4(dy + idx);
   int ax = 0, ay = 0, az = 0, aw = 0;  // tap of the first maximum, per channel
   if (!AVG) {
     float4 best = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -245,7 +257,7 @@ __global__ __launch_bounds__(256) void pool_bwd_window_kernel(const WorkerDev* _
     for (int u0 = 0; u0 < d.k[0]; ++u0)
       for (int u1 = 0; u1 < d.k[1]; ++u1)
         for (int u2 = 0; u2 < d.k[2]; ++u2, ++u) {
-          const float4 v = x[base + u0 * s0 + u1 * s1 + u2 * s2];
+          const float4 v = nt_load4(x + base + u0 * s0 + u1 * s1 + u2 * s2);
           if (u == 0 || v.x > best.x) best.x = v.x, ax = u;
           if (u == 0 || v.y > best.y) best.y = v.y, ay = u;
           if (u == 0 || v.z > best.z) best.z = v.z, az = u;
@@ -258,8 +270,8 @@ __global__ __launch_bounds__(256) void pool_bwd_window_kernel(const WorkerDev* _
   for (int u0 = 0; u0 < d.k[0]; ++u0)
     for (int u1 = 0; u1 < d.k[1]; ++u1)
       for (int u2 = 0; u2 < d.k[2]; ++u2, ++u)
-        dx[base + u0 * s0 + u1 * s1 + u2 * s2] =
-            AVG ? share : make_float4(u == ax ? g.x : 0.f, u == ay ? g.y : 0.f, u == az ? g.z : 0.f, u == aw ? g.w : 0.f);
+        nt_store4(dx + base + u0 * s0 + u1 * s1 + u2 * s2,  // written once, not read again by this kernel
+                  AVG ? share : make_float4(u == ax ? g.x : 0.f, u == ay ? g.y : 0.f, u == az ? g.z : 0.f, u == aw ? g.w : 0.f));
 }
 
 __global__ __launch_bounds__(256) void pool_bwd_uncovered_kernel(const WorkerDev* __restrict__ workers,
@@ -450,8 +462,16 @@ static int pool_fwd(distdl_plan* plan, void* const x_bufs_dev[], void* const y_d
       all_aligned16((const void* const*)y_dev, plan->n_workers) && total / 4 < (int64_t(1) << 31) &&
       ensure_pooldiv(plan) == DISTDL_OK) {
     dim3 grid((unsigned)((total / 4 + 255) / 256), plan->n_workers);
-    if (avg) hipLaunchKernelGGL(pool_fwd_vec_kernel<true>, grid, dim3(256), 0, st, plan->d_workers, plan->d_pooldiv, plan->tab_x.dev, plan->tab_y.dev, d);
-    else hipLaunchKernelGGL(pool_fwd_vec_kernel<false>, grid, dim3(256), 0, st, plan->d_workers, plan->d_pooldiv, plan->tab_x.dev, plan->tab_y.dev, d);
+    bool stream = true;  // windows that do not overlap: every input is read once
+    for (int i = 0; i < 3; ++i) stream = stream && d.s[i] >= (d.k[i] - 1) * d.dil[i] + 1;
+#define DISTDL_POOL_FWD(A_, S_)                                                                                     \
+  hipLaunchKernelGGL((pool_fwd_vec_kernel<A_, S_>), grid, dim3(256), 0, st, plan->d_workers, plan->d_pooldiv,        \
+                     plan->tab_x.dev, plan->tab_y.dev, d)
+    if (avg && stream) DISTDL_POOL_FWD(true, true);
+    else if (avg) DISTDL_POOL_FWD(true, false);
+    else if (stream) DISTDL_POOL_FWD(false, true);
+    else DISTDL_POOL_FWD(false, false);
+#undef DISTDL_POOL_FWD
     DISTDL_HIP_TRY(hipGetLastError());
     return DISTDL_OK;
   }
@@ -495,8 +515,15 @@ static int pool_bwd(distdl_plan* plan, const void* const x_bufs_dev[], const voi
       else
         hipLaunchKernelGGL(pool_bwd_window_kernel<false>, wgrid, dim3(256), 0, st, plan->d_workers, plan->d_pooldiv,
                            plan->tab_x.dev, plan->tab_dy.dev, plan->tab_dx.dev, d);
-      hipLaunchKernelGGL(pool_bwd_uncovered_kernel, ugrid, dim3(256), 0, st, plan->d_workers, plan->d_pooldiv,
-                         plan->tab_dx.dev, d);
+      // every buffer cell lies in a window (stride == kernel, the windows start at the buffer's first cell and
+      // end at its last): nothing to clear
+      bool covered = true;
+      for (const WorkerDev& wd : plan->workers)
+        for (int i = 0; i < 3; ++i)
+          covered = covered && d.s[i] == d.k[i] && wd.origin[i] == 0 && wd.out[i] * d.s[i] == wd.buf[i];
+      if (!covered)
+        hipLaunchKernelGGL(pool_bwd_uncovered_kernel, ugrid, dim3(256), 0, st, plan->d_workers, plan->d_pooldiv,
+                           plan->tab_dx.dev, d);
     } else {
     dim3 grid((unsigned)((total + 255) / 256), plan->n_workers);
     if (avg)
