@@ -89,9 +89,17 @@ class ConvWorkload:
         self.nw = nw
         self.metric = "partitioned conv fwd+bwd TFLOP/s (halo exchange H, H* and dw sum-reduce included)"
         self.unit = "TFLOP/s"
-        self.dtype = "f32"       # the arithmetic type: bf16 tensors are multiplied and accumulated in fp32
+        # arithmetic types: fp32 throughout for fp32 tensors; bf16 tensors are multiplied in bf16 with fp32
+        # accumulation when the channel counts are multiples of 8, else widened to fp32
+        self.dtype = "f32" if dtype == "f32" else "bf16"
         self.storage = dtype
-        self.describe = {"workload": f"{self.tag}: conv{c['D']}d fwd+bwd {'fp32' if dtype == 'f32' else 'bf16 tensors, fp32 arithmetic,'} x[{c['n_b']},{c['c_in']}," +
+        self.kernel_dtype = {}
+        if dtype == "bf16":
+            self.kernel_dtype = {"conv_fwd": "bf16" if c["c_in"] % 8 == 0 else "f32",
+                                 "conv_bwd_data_mfma": "bf16" if c["c_out"] % 8 == 0 else "f32",
+                                 "conv_bwd_data": "f32",
+                                 "conv_bwd_weight": "bf16" if c["c_in"] % 8 == 0 and c["c_out"] % 8 == 0 else "f32"}
+        self.describe = {"workload": f"{self.tag}: conv{c['D']}d fwd+bwd {'fp32' if dtype == 'f32' else 'bf16 (fp32 accumulation)'} x[{c['n_b']},{c['c_in']}," +
                          ",".join(str(v) for v in c["in_shape"]) + f"] w[{c['c_out']},{c['c_in']}," +
                          ",".join(str(v) for v in c["ksize"]) + f"] stride {c['stride'][0]} pad {c['padding'][0]}, " +
                          "P=" + "x".join(str(v) for v in c["P"]) + f" ({P} virtual workers), channels-last",
@@ -570,9 +578,10 @@ def kernel_rooflines(workload, report, traffic):
                              algorithmic_bytes=work)
             else:
                 ach = work / (avg_ms * 1e-3) / 1e12
-                peak = MFMA_PEAK_TFLOPS[workload.dtype]
+                kdt = getattr(workload, "kernel_dtype", {}).get(key, workload.dtype)   # the MFMA type of this kernel
+                peak = MFMA_PEAK_TFLOPS[kdt]
                 entry.update(bound="mfma", achieved=ach, peak=peak, unit="TFLOP/s", frac=ach / peak,
-                             algorithmic_flops=work)
+                             algorithmic_flops=work, mfma_dtype=kdt)
                 mb = getattr(workload, "min_bytes", {}).get(key)
                 if mb:   # also against min(MFMA peak, arithmetic intensity x HBM peak)
                     roof = min(peak, work / mb * HBM_PEAK_GBS / 1e3)

@@ -21,6 +21,7 @@ struct CorrArgs {
   int32_t par[3];  // parity class (mode 1)
   int32_t tr, tc;  // rows x columns (dimensions 1, 2) of a workgroup's output window
   int32_t g0;      // output planes (dimension 0) a workgroup walks through
+  int32_t ck;      // contraction channels per chunk: 8, or 16 when the launch multiplies in bf16
   int32_t R, Cw, CwQ;  // patch rows, cells per row, cells per residue class of the row
   int32_t a_vec4;      // patch size in 16-byte units
   FastDiv div_cw, div_tc, div_is2;  // exact division by Cw, tc, is[2] in the per-workgroup set-up

@@ -28,6 +28,7 @@
 namespace distdl {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
 __host__ __device__ inline int64_t tiles_of(const PerWorker& g, const CorrArgs& a) {
   // chunks of g0 consecutive (sample, dimension-0 position) planes x windows x channel tiles
@@ -81,12 +82,17 @@ __device__ inline float load_scalar(const void* p, size_t i) {
 // NT: taps per plane (nt[1] * nt[2]) known at compile time, or 0: with NT > 0 the tap loop is unrolled,
 // the LDS address of every (M-tile, tap) operand is computed once per workgroup and the weight operand
 // of tap t is an immediate offset, which removes the per-tap address arithmetic from the stage loop.
-// BF16: the tensors in memory (input, output, bias) are bf16; the weights were widened by the re-layout kernel.
-template <int MT, int PA, int PB, int NT, bool BF16>
+// MODE 0: fp32 tensors.  MODE 1: bf16 tensors (input, output, bias) widened to fp32 while they are staged; the
+// weights were widened by the re-layout kernel.  MODE 2: bf16 tensors multiplied as bf16 on
+// v_mfma_f32_32x32x16_bf16 (fp32 accumulation): a chunk is 16 channels, a 16-byte piece holds 8 of them and is one
+// MFMA operand (A lane l holds A[i = l % 32][k = 8 * (l / 32) ... + 7]); needs channel counts that are multiples of 8.
+template <int MT, int PA, int PB, int NT, int MODE>
 __global__ __launch_bounds__(256, 2) void corr_mfma_kernel(const WorkerDev* __restrict__ workers,
                                                            void* const* in_bufs, void* const* out_bufs, CorrArgs a) {
   extern __shared__ float4 lds[];
+  constexpr bool BF16 = MODE != 0, BFM = MODE == 2;
   constexpr uint32_t ES = BF16 ? 2u : 4u;  // bytes per element in memory
+  constexpr int CK = BFM ? 16 : 8;         // channels per chunk (two 16-byte pieces per cell in LDS)
   // LDS: patch (a_vec4 16-byte units), weights (nb_vec4), one spare unit that absorbs the pieces nobody
   // needs, then the tap table.
   const int nb_vec4 = a.nt[1] * a.nt[2] * 64;
@@ -116,7 +122,7 @@ __global__ __launch_bounds__(256, 2) void corr_mfma_kernel(const WorkerDev* __re
   const uint32_t so2 = a.nc, so1 = g.out_ext[2] * so2, so0 = g.out_ext[1] * so1, son = g.out_ext[0] * so0;
   const __amdgpu_buffer_rsrc_t rin = make_rsrc(in_bufs[worker], (uint32_t)a.n_b * sin * ES);
   const __amdgpu_buffer_rsrc_t rout = make_rsrc(out_bufs[worker], (uint32_t)a.n_b * son * ES);
-  const int ncc = (a.kc + 7) / 8;
+  const int ncc = (a.kc + CK - 1) / CK;
   const int nt0 = a.nt[0];
   const __amdgpu_buffer_rsrc_t rw =
       make_rsrc(a.wt + (size_t)ntile * nt0 * ncc * nb_vec4 * 4, (uint32_t)(nt0 * ncc * nb_vec4) * 16u);
@@ -141,7 +147,7 @@ __global__ __launch_bounds__(256, 2) void corr_mfma_kernel(const WorkerDev* __re
       const int cq = (int)fd_div((uint32_t)c, a.div_is2), cr = c - cq * a.is[2];
       loff[i] = (((rr * 2 + ph) * a.is[2] + cr) * a.CwQ + cq) * 16;
       if (i1 >= 0 && i1 < g.in_ext[1] && i2 >= 0 && i2 < g.in_ext[2])
-        goff[i] = ((i1 * si1 + i2 * si2 + ph * 4) * ES) | ((a.kc & 7) ? ph : 0);
+        goff[i] = ((i1 * si1 + i2 * si2 + ph * (CK / 2)) * ES) | ((a.kc & (CK - 1)) ? ph : 0);
     }
   }
   uint32_t bl[PB];
@@ -180,7 +186,7 @@ __global__ __launch_bounds__(256, 2) void corr_mfma_kernel(const WorkerDev* __re
   const int* __restrict__ tapinfo = a.tapinfo;  // [0..7]: plane offsets, [8..]: patch offset per (t1, t2)
   const int ntaps = a.nt[1] * a.nt[2];
   if (tid < ntaps + 4) tap_tab[tid] = tid < ntaps ? (uint32_t)tapinfo[8 + tid] * 16u : 0u;  // visible after the first barrier below
-  const bool ragged = (a.kc & 7) != 0;
+  const bool ragged = (a.kc & (CK - 1)) != 0;
   char* const ldsb = (char*)lds;
 
   // A stage is one (output plane q0, tap plane t0, 8-channel chunk cc); stages whose input plane lies
@@ -209,17 +215,17 @@ __global__ __launch_bounds__(256, 2) void corr_mfma_kernel(const WorkerDev* __re
   u32x4 ra[PA], rb[PB];
   auto load_stage = [&](const StagePos& sp) {
     const int t0 = sp.t0, cc = sp.cc;
-    const uint32_t sbase = ((uint32_t)sp.n * sin + (uint32_t)plane_of(sp.q0, t0) * si0 + cc * 8) * ES;
+    const uint32_t sbase = ((uint32_t)sp.n * sin + (uint32_t)plane_of(sp.q0, t0) * si0 + cc * CK) * ES;
     if (ragged && cc == ncc - 1) {
 #pragma unroll
       for (int i = 0; i < PA; ++i)
-        ra[i] = load4<BF16>(rin, (goff[i] & 1u) ? kOob : goff[i], sbase);
+        ra[i] = load4<MODE == 1>(rin, (goff[i] & 1u) ? kOob : goff[i], sbase);
     } else if (ragged) {
 #pragma unroll
-      for (int i = 0; i < PA; ++i) ra[i] = load4<BF16>(rin, goff[i] & ~1u, sbase);
+      for (int i = 0; i < PA; ++i) ra[i] = load4<MODE == 1>(rin, goff[i] & ~1u, sbase);
     } else {
 #pragma unroll
-      for (int i = 0; i < PA; ++i) ra[i] = load4<BF16>(rin, goff[i], sbase);
+      for (int i = 0; i < PA; ++i) ra[i] = load4<MODE == 1>(rin, goff[i], sbase);
     }
     const uint32_t wbase = (uint32_t)(t0 * ncc + cc) * nb_vec4 * 16u;
 #pragma unroll
@@ -255,6 +261,21 @@ __global__ __launch_bounds__(256, 2) void corr_mfma_kernel(const WorkerDev* __re
     }
   };
   auto multiply = [&](floatx16 (&acc)[MT], const float4& b, const float4 (&av)[MT]) {
+    if constexpr (BFM) {  // one MFMA per 16-byte operand: 16 channels of the chunk at once
+      union Frag {
+        float4 f;
+        bf16x8 v;
+      };
+      Frag fb;
+      fb.f = b;
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) {
+        Frag fa;
+        fa.f = av[mt];
+        acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa.v, fb.v, acc[mt], 0, 0, 0);
+      }
+      return;
+    }
     // M-tiles interleaved, so that consecutive MFMAs do not depend on each other
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) acc[mt] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[mt].x, b.x, acc[mt], 0, 0, 0);
@@ -339,14 +360,17 @@ __global__ __launch_bounds__(256, 2) void corr_mfma_kernel(const WorkerDev* __re
 //   dst[ntile][t0][cc][t1][t2][h][nn][j] = W[tap(t0,t1,t2)][k = cc*8 + 4h + j][n = ntile*32 + nn]
 // with W[tap][k][n] = w[n][k][tap] (forward: n = co, k = ci) or w[k][n][tap]
 // (data gradient: k = co, n = ci), zero beyond the channel counts.
-template <bool BF16>
+template <int MODE>
 __global__ __launch_bounds__(256) void corr_weights_kernel(const void* __restrict__ w, float* __restrict__ dst,
                                                            CorrArgs a, int ci_n, int co_n, int taps, int k1, int k2) {
-  const int ncc = (a.kc + 7) / 8;
-  const int64_t total = (int64_t)a.ntn * a.nt[0] * ncc * a.nt[1] * a.nt[2] * 256;
+  // elements per 16-byte piece: 4 floats, or 8 bf16 when the kernel multiplies in bf16
+  constexpr int PE = MODE == 2 ? 8 : 4, CK = 2 * PE;
+  const int ncc = (a.kc + CK - 1) / CK;
+  const int64_t units = (int64_t)a.ntn * a.nt[0] * ncc * a.nt[1] * a.nt[2] * 64;  // 16-byte pieces
+  const int64_t total = units * PE;
   int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (blockIdx.x == 0) {  // the tap tables the correlation kernel reads, stored behind the weights
-    int* tapinfo = (int*)(dst + total);
+    int* tapinfo = (int*)(dst + units * 4);
     if (threadIdx.x < 8) tapinfo[threadIdx.x] = threadIdx.x < a.nt[0] ? a.tapoff[0][threadIdx.x] : 0;
     if ((int)threadIdx.x < a.nt[1] * a.nt[2]) {
       const int t1 = threadIdx.x / a.nt[2], t2 = threadIdx.x - t1 * a.nt[2];
@@ -355,21 +379,24 @@ __global__ __launch_bounds__(256) void corr_weights_kernel(const void* __restric
     }
   }
   if (idx >= total) return;
-  const int j = idx & 3, nn = (idx >> 2) & 31, hh = (idx >> 7) & 1;
-  int64_t r = idx >> 8;
+  const int j = idx % PE;
+  int64_t r = idx / PE;
+  const int nn = r & 31, hh = (r >> 5) & 1;
+  r >>= 6;
   const int t2 = r % a.nt[2]; r /= a.nt[2];
   const int t1 = r % a.nt[1]; r /= a.nt[1];
   const int cc = r % ncc; r /= ncc;
   const int t0 = r % a.nt[0];
   const int ntile = (int)(r / a.nt[0]);
-  const int k = cc * 8 + 4 * hh + j, nch = ntile * 32 + nn;
+  const int k = cc * CK + PE * hh + j, nch = ntile * 32 + nn;
   float v = 0.f;
   if (k < a.kc && nch < a.nc) {
     const int tap = (a.tapid[0][t0] * k1 + a.tapid[1][t1]) * k2 + a.tapid[2][t2];
     const int co = a.mode == 0 ? nch : k, ci = a.mode == 0 ? k : nch;
-    v = load_scalar<BF16>(w, ((size_t)co * ci_n + ci) * taps + tap);
+    v = load_scalar<MODE != 0>(w, ((size_t)co * ci_n + ci) * taps + tap);
   }
-  dst[idx] = v;
+  if constexpr (MODE == 2) ((uint16_t*)dst)[idx] = to_bf16(v);  // exact: v is a bf16 value
+  else dst[idx] = v;
 }
 
 // ---- weight gradient ----------------------------------------------------------
@@ -584,13 +611,22 @@ __global__ __launch_bounds__(256, 2) void wgrad_lds_kernel(const WorkerDev* __re
 // vector instructions: ring slots advance in scalar registers, out-of-range rows are switched off through
 // the scalar offset of the buffer load, and every LDS read of the inner loop is an immediate offset.
 // A wave with TW - 1 taps repeats its last tap (never stored), so all waves stay in step.
-template <int TW, int S2, bool BF16>
+// MODE 0: fp32 tensors.  MODE 1: bf16 tensors widened to fp32 while they are staged.  MODE 2: bf16 tensors staged as
+// they are (a 16-byte piece holds 8 channels) and multiplied on v_mfma_f32_32x32x16_bf16, whose operands need 8
+// consecutive *positions* per lane: ds_read_b64_tr_b16 gathers them from the channels-last rows.  Measured lane
+// layout of that load: in every group of 16 lanes, lane 4 * b + a receives, as element v, the a-th 16-bit element
+// of the 8 bytes addressed by lane b + 4 * v of the group.  With lane s of a group addressing channels
+// 4 * (s % 4) ... + 3 of position s / 4, lane t of the group thus receives channel t of four consecutive positions.
+template <int TW, int S2, int MODE>
 __global__ __launch_bounds__(256, 2) void wgrad_taps_kernel(const WorkerDev* __restrict__ workers, void* const* x_bufs,
                                                             void* const* dy_bufs, float* __restrict__ partial,
                                                             WgradArgs a) {
   extern __shared__ float4 wt_lds[];
   constexpr int NX = 5;  // input-row pieces per thread and step
-  constexpr uint32_t ES = BF16 ? 2u : 4u;  // bytes per element in memory (bf16 is widened while it is staged)
+  constexpr bool BFM = MODE == 2;
+  constexpr uint32_t ES = MODE ? 2u : 4u;   // bytes per element in memory
+  constexpr int PCH = BFM ? 8 : 4;          // channels per 16-byte piece in LDS
+  constexpr int PPC = 32 / PCH;             // pieces per cell of a 32-channel tile
   const int tid = threadIdx.x, lane = tid & 63, h = lane >> 5, m = lane & 31;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int t0 = blockIdx.x;
@@ -599,7 +635,7 @@ __global__ __launch_bounds__(256, 2) void wgrad_taps_kernel(const WorkerDev* __r
   const int worker = blockIdx.z / a.nchunks, chunk = blockIdx.z - worker * a.nchunks;
   const WorkerDev wd = workers[worker];
   const int s1 = a.s[1], span = a.span, ring = span + s1;
-  const int rowp = (a.ncell * 8 + 63) & ~63;  // 16-byte pieces per staged row, rounded up to whole waves
+  const int rowp = (a.ncell * PPC + 63) & ~63;  // 16-byte pieces per staged row, rounded up to whole waves
   const uint32_t pitch = (uint32_t)rowp * 16u;
   char* const ldsb = (char*)wt_lds;
   const uint32_t ys_base = (uint32_t)ring * pitch;  // two dy segments of 4 KiB behind the ring
@@ -646,14 +682,14 @@ __global__ __launch_bounds__(256, 2) void wgrad_taps_kernel(const WorkerDev* __r
   auto setup_pieces = [&](int seg) {
 #pragma unroll
     for (int i = 0; i < NX; ++i) {
-      const int cell = prest[i] >> 3, q4 = (prest[i] & 7) * 4;
+      const int cell = prest[i] / PPC, q4 = (prest[i] % PPC) * PCH;
       pg[i] = kOob;  // pieces beyond the row's cells or channels stage zeros
       if (cell < a.ncell && seg * 32 * S2 + cell < row_cells && ci_t * 32 + q4 < a.ci)
         pg[i] = ((seg * 32 * S2 + cell) * sx2 + ci_t * 32 + q4) * ES;
     }
-    const int pos = tid >> 3, q4 = (tid & 7) * 4;
+    const int pos = tid / PPC, q4 = (tid % PPC) * PCH;  // 32 positions; with 8-channel pieces only half the threads
     pgy = kOob;
-    if (seg * 32 + pos < O2 && co_t * 32 + q4 < a.co) pgy = ((seg * 32 + pos) * sy2 + co_t * 32 + q4) * ES;
+    if (pos < 32 && seg * 32 + pos < O2 && co_t * 32 + q4 < a.co) pgy = ((seg * 32 + pos) * sy2 + co_t * 32 + q4) * ES;
   };
   u32x4 rp[NX], rpy;
   auto fetch = [&](int n, int o0, int o1) {
@@ -664,9 +700,9 @@ __global__ __launch_bounds__(256, 2) void wgrad_taps_kernel(const WorkerDev* __r
     for (int i = 0; i < NX; ++i) {
       // rows beyond the buffer (and unused slots) read as zero: the scalar offset fails the range check
       const uint32_t so = (prr[i] < s1 && r_first + prr[i] < wd.buf[1]) ? xb + (uint32_t)prr[i] * sx1 * ES : kOob;
-      rp[i] = load4<BF16>(rx, pg[i], so);
+      rp[i] = load4<MODE == 1>(rx, pg[i], so);
     }
-    rpy = load4<BF16>(ry, pgy, ((uint32_t)n * syn + (uint32_t)o0 * sy0 + (uint32_t)o1 * sy1) * ES);
+    rpy = load4<MODE == 1>(ry, pgy, ((uint32_t)n * syn + (uint32_t)o0 * sy0 + (uint32_t)o1 * sy1) * ES);
   };
   int nslot = 0;      // ring slot of the step's new row 0
   int tslot[TW];      // ring slot of the row each tap reads
@@ -682,7 +718,13 @@ __global__ __launch_bounds__(256, 2) void wgrad_taps_kernel(const WorkerDev* __r
     *(u32x4*)(ldsb + ys_base + (uint32_t)(o1 & 1) * 4096u + (uint32_t)tid * 16u) = rpy;
   };
 
-  const uint32_t lane_x = (uint32_t)(h * S2 * 32 + m) * 4u, lane_y = ys_base + (uint32_t)(h * 32 + m) * 4u;
+  // fp32: lane (h, m) reads channel m of position 2 * pr + h.  bf16 MFMA: lane s of 16-lane group G addresses
+  // channels 16 * (G % 2) + 4 * (s % 4) ... + 3 of position 8 * (G / 2) + s / 4 (64 bytes per cell)
+  const int lg = lane >> 4, ls = lane & 15;
+  const uint32_t lane_x = BFM ? (uint32_t)((8 * (lg >> 1) + (ls >> 2)) * S2 * 64 + (16 * (lg & 1) + 4 * (ls & 3)) * 2)
+                              : (uint32_t)(h * S2 * 32 + m) * 4u;
+  const uint32_t lane_y = ys_base + (BFM ? (uint32_t)((8 * (lg >> 1) + (ls >> 2)) * 64 + (16 * (lg & 1) + 4 * (ls & 3)) * 2)
+                                         : (uint32_t)(h * 32 + m) * 4u);
   for (int unit = chunk * per; unit < unit_end; ++unit) {
     const int plane = unit / nblk1, o1_begin = (unit - plane * nblk1) * a.ob, o1_end = min(O1, o1_begin + a.ob);
     const int o0 = plane % wd.out[0], n = plane / wd.out[0];
@@ -701,11 +743,11 @@ __global__ __launch_bounds__(256, 2) void wgrad_taps_kernel(const WorkerDev* __r
           const uint32_t rb = ((uint32_t)n * sxn + (uint32_t)c0 * sx0 + (uint32_t)(wd.origin[1] + wrow) * sx1 +
                                (wd.origin[2] + seg * 32 * S2) * sx2 + ci_t * 32) * ES;
           for (int rest = tid; rest < rowp; rest += 256) {
-            const int cell = rest >> 3, q4 = (rest & 7) * 4;
+            const int cell = rest / PPC, q4 = (rest % PPC) * PCH;
             uint32_t off = kOob;
             if (row_ok && cell < a.ncell && seg * 32 * S2 + cell < row_cells && ci_t * 32 + q4 < a.ci)
               off = (cell * sx2 + q4) * ES;
-            *(u32x4*)(ldsb + (uint32_t)(wrow % ring) * pitch + (uint32_t)rest * 16u) = load4<BF16>(rx, off, rb);
+            *(u32x4*)(ldsb + (uint32_t)(wrow % ring) * pitch + (uint32_t)rest * 16u) = load4<MODE == 1>(rx, off, rb);
           }
         }
       }
@@ -717,8 +759,30 @@ __global__ __launch_bounds__(256, 2) void wgrad_taps_kernel(const WorkerDev* __r
         const char* ta[TW];
 #pragma unroll
         for (int i = 0; i < TW; ++i)
-          ta[i] = ldsb + (uint32_t)tslot[i] * pitch + (uint32_t)(tap_t2[i] * a.dil[2]) * 128u + lane_x;
+          ta[i] = ldsb + (uint32_t)tslot[i] * pitch + (uint32_t)(tap_t2[i] * a.dil[2]) * (BFM ? 64u : 128u) + lane_x;
         const char* yrow = ldsb + lane_y + (uint32_t)(o1 & 1) * 4096u;
+        if constexpr (BFM) {
+          // two groups of 16 positions; an operand is two transposing loads of four positions each
+          typedef short v4i16 __attribute__((ext_vector_type(4)));
+          typedef __attribute__((address_space(3))) v4i16* lds_v4;
+          union Frag {
+            v4i16 half[2];
+            bf16x8 v;
+          };
+#pragma unroll
+          for (int kg = 0; kg < 2; ++kg) {
+            Frag fb, fa[TW];
+            fb.half[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(yrow + kg * 1024));
+            fb.half[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(yrow + kg * 1024 + 256));
+#pragma unroll
+            for (int i = 0; i < TW; ++i) {
+              fa[i].half[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(ta[i] + kg * (16 * S2 * 64)));
+              fa[i].half[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(ta[i] + kg * (16 * S2 * 64) + 4 * S2 * 64));
+            }
+#pragma unroll
+            for (int i = 0; i < TW; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i].v, fb.v, acc[i], 0, 0, 0);
+          }
+        } else {
         // 16 x two positions: lanes 0-31 take column 2*pr, lanes 32-63 column 2*pr + 1
 #pragma unroll
         for (int pr = 0; pr < 16; ++pr) {
@@ -728,6 +792,7 @@ __global__ __launch_bounds__(256, 2) void wgrad_taps_kernel(const WorkerDev* __r
           for (int i = 0; i < TW; ++i) av[i] = *(const float*)(ta[i] + pr * (2 * S2 * 128));
 #pragma unroll
           for (int i = 0; i < TW; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[i], b, acc[i], 0, 0, 0);
+        }
         }
         nslot += s1;
         if (nslot >= ring) nslot -= ring;
@@ -936,13 +1001,17 @@ static int64_t max_tiles(const distdl_plan* p, const CorrArgs& a) {
 }
 
 static size_t corr_weight_elems(const CorrArgs& a) {
-  return (size_t)a.ntn * a.nt[0] * ((a.kc + 7) / 8) * a.nt[1] * a.nt[2] * 256;
+  const int ck = a.ck ? a.ck : 8;  // channels per chunk; sized for the smaller chunk until the launch has chosen
+  return (size_t)a.ntn * a.nt[0] * ((a.kc + ck - 1) / ck) * a.nt[1] * a.nt[2] * 256;
 }
 // weights + the tap tables (8 + 64 ints), kept 16-byte aligned
 static size_t corr_scratch_elems(const CorrArgs& a) { return corr_weight_elems(a) + 72; }
 
 static int launch_corr(distdl_plan* p, CorrArgs a, const void* w, float* wscratch, const void* bias, void** in_tab,
                        void** out_tab, const char* name, hipStream_t st) {
+  // 0: fp32; 1: bf16 tensors widened to fp32; 2: bf16 MFMAs (contraction channels in 16-byte pieces of 8)
+  const int mode = p->dtype != DISTDL_BF16 ? 0 : (a.kc % 8 == 0 ? 2 : 1);
+  a.ck = mode == 2 ? 16 : 8;
   int nq1max, nq2max;
   max_nq(p, a, nq1max, nq2max);
   const int mt = choose_mt(a, std::max(nq1max, 1), nq2max);
@@ -956,7 +1025,8 @@ static int launch_corr(distdl_plan* p, CorrArgs a, const void* w, float* wscratc
     for (const WorkerDev& wd : p->workers) planes_max = std::max<int64_t>(planes_max, p->n_b * derive(wd, a).nq[0]);
     const int64_t per_plane_wgs = max_tiles(p, a) / std::max<int64_t>(planes_max, 1) * p->n_workers;  // with g0 == 1
     const double setup = 8.0e3;
-    const double per_plane = (double)a.nt[0] * ((a.kc + 7) / 8) * a.nt[1] * a.nt[2] * mt * 4 * 64.0 * 2.0;
+    const double per_plane = (double)a.nt[0] * ((a.kc + a.ck - 1) / a.ck) * a.nt[1] * a.nt[2] * mt *
+                             (a.ck == 16 ? 32.0 : 256.0) * 2.0;
     double best = 1e300;
     for (int64_t g0 = 1; g0 <= planes_max; ++g0) {
       const int64_t wgs = (planes_max + g0 - 1) / g0 * per_plane_wgs;
@@ -968,18 +1038,21 @@ static int launch_corr(distdl_plan* p, CorrArgs a, const void* w, float* wscratc
   if (a.tiles_max == 0) return DISTDL_OK;
   a.wt = wscratch;
   a.bias = bias;
-  const bool bf16 = p->dtype == DISTDL_BF16;
   const int taps = p->ksize[0] * p->ksize[1] * p->ksize[2];
   const size_t welems = corr_weight_elems(a);
   a.tapinfo = (const int*)(wscratch + welems);
   {
     ProfScope prof("conv_relayout_w", st);
-    if (bf16)
-      hipLaunchKernelGGL(corr_weights_kernel<true>, dim3((unsigned)std::max<size_t>(1, (welems + 255) / 256)),
-                         dim3(256), 0, st, w, wscratch, a, (int)p->n_ci, (int)p->n_co, taps, p->ksize[1], p->ksize[2]);
+    const dim3 wgrid((unsigned)std::max<size_t>(1, (welems * (mode == 2 ? 2 : 1) + 255) / 256));
+    if (mode == 2)
+      hipLaunchKernelGGL(corr_weights_kernel<2>, wgrid, dim3(256), 0, st, w, wscratch, a, (int)p->n_ci, (int)p->n_co,
+                         taps, p->ksize[1], p->ksize[2]);
+    else if (mode == 1)
+      hipLaunchKernelGGL(corr_weights_kernel<1>, wgrid, dim3(256), 0, st, w, wscratch, a, (int)p->n_ci, (int)p->n_co,
+                         taps, p->ksize[1], p->ksize[2]);
     else
-      hipLaunchKernelGGL(corr_weights_kernel<false>, dim3((unsigned)std::max<size_t>(1, (welems + 255) / 256)),
-                         dim3(256), 0, st, w, wscratch, a, (int)p->n_ci, (int)p->n_co, taps, p->ksize[1], p->ksize[2]);
+      hipLaunchKernelGGL(corr_weights_kernel<0>, wgrid, dim3(256), 0, st, w, wscratch, a, (int)p->n_ci, (int)p->n_co,
+                         taps, p->ksize[1], p->ksize[2]);
   }
   int64_t blocks = (int64_t)a.tiles_max * p->n_workers;
   blocks = (blocks + 7) / 8 * 8;
@@ -996,8 +1069,9 @@ static int launch_corr(distdl_plan* p, CorrArgs a, const void* w, float* wscratc
   } while (0)
 #define DISTDL_LAUNCH_CORR(MT_, PA_, PB_, NT_)                                                                       \
   do {                                                                                                               \
-    if (bf16) DISTDL_LAUNCH_CORR_T(MT_, PA_, PB_, NT_, true);                                                        \
-    else DISTDL_LAUNCH_CORR_T(MT_, PA_, PB_, NT_, false);                                                            \
+    if (mode == 2) DISTDL_LAUNCH_CORR_T(MT_, PA_, PB_, NT_, 2);                                                      \
+    else if (mode == 1) DISTDL_LAUNCH_CORR_T(MT_, PA_, PB_, NT_, 1);                                                 \
+    else DISTDL_LAUNCH_CORR_T(MT_, PA_, PB_, NT_, 0);                                                                \
   } while (0)
   const int ntaps = a.nt[1] * a.nt[2];
   if (mt == 2 && small && ntaps == 9) DISTDL_LAUNCH_CORR(2, 4, 3, 9);
@@ -1078,10 +1152,16 @@ static int wgrad_taps_per_wave(const distdl_plan* p) {
 // The plane-per-workgroup kernel needs 16-byte channel pieces, a row stride of 1 or 2, a tap count
 // per wave it is instantiated for, s1 new rows per step that fit the five piece slots of a thread,
 // and a ring that fits in LDS.
+// 0: fp32 tensors; 1: bf16 tensors widened to fp32; 2: bf16 MFMAs (channel counts that are multiples of 8)
+static int wgrad_mode(const distdl_plan* p) {
+  if (p->dtype != DISTDL_BF16) return 0;
+  return (p->n_ci % 8 == 0 && p->n_co % 8 == 0) ? 2 : 1;
+}
+
 static bool wgrad_rows_shape_ok(const distdl_plan* p) {
   const int span = (p->ksize[1] - 1) * p->dilation[1] + 1;
   const int ncell = 31 * p->stride[2] + (p->ksize[2] - 1) * p->dilation[2] + 1;
-  const int rowp = (ncell * 8 + 63) & ~63;
+  const int rowp = (ncell * (wgrad_mode(p) == 2 ? 4 : 8) + 63) & ~63;
   const int tw = wgrad_taps_per_wave(p);
   if (p->n_ci % 4 || p->n_co % 4) return false;
   if (tw != 3 && tw != 4 && tw != 7) return false;
@@ -1158,7 +1238,8 @@ int conv_wgrad_mfma(distdl_plan* p, float* partial, hipStream_t st) {
   const int lds = 4 * (a.ncell + 32) * 128;
   const bool bf16 = p->dtype == DISTDL_BF16;
   if (aligned && wgrad_rows_shape_ok(p)) {
-    const int rowp = (a.ncell * 8 + 63) & ~63;
+    const int mode = wgrad_mode(p);
+    const int rowp = (a.ncell * (mode == 2 ? 4 : 8) + 63) & ~63;
     const int rlds = (a.span + a.s[1]) * rowp * 16 + 8192;
     const int tw = wgrad_taps_per_wave(p);
     dim3 rgrid((unsigned)a.k[0], grid.y, grid.z), rblock(256);
@@ -1173,8 +1254,9 @@ int conv_wgrad_mfma(distdl_plan* p, float* partial, hipStream_t st) {
   } while (0)
 #define DISTDL_LAUNCH_TAPS(TW_, S2_)                                                                                \
   do {                                                                                                              \
-    if (bf16) DISTDL_LAUNCH_TAPS_T(TW_, S2_, true);                                                                 \
-    else DISTDL_LAUNCH_TAPS_T(TW_, S2_, false);                                                                     \
+    if (mode == 2) DISTDL_LAUNCH_TAPS_T(TW_, S2_, 2);                                                               \
+    else if (mode == 1) DISTDL_LAUNCH_TAPS_T(TW_, S2_, 1);                                                          \
+    else DISTDL_LAUNCH_TAPS_T(TW_, S2_, 0);                                                                         \
   } while (0)
     if (tw == 3 && a.s[2] == 1) DISTDL_LAUNCH_TAPS(3, 1);
     else if (tw == 3) DISTDL_LAUNCH_TAPS(3, 2);

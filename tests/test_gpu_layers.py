@@ -114,6 +114,9 @@ CONV_BF16 = [
     ("cfg2", dict(in_shape=(19, 23), n_b=3, c_in=3, c_out=5, P=(2, 3), ksize=(3, 4), stride=(2, 1), padding=(1, 2),
                   dilation=(1, 2)), True),
     ("cfg1", dict(), True),
+    # 24 input channels: the last 16-channel chunk of the bf16 matrix-core kernel is half empty
+    ("cfg5", dict(in_shape=(14, 18, 36), P=(2, 1, 2), c_in=24, c_out=8, ksize=(3, 3, 3), stride=(1, 2, 1),
+                  padding=(1, 1, 1)), True),
 ]
 
 
