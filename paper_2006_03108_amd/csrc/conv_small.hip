@@ -685,10 +685,20 @@ bool corr16_shape(const distdl_plan* p, const CorrArgs& c, bool vec, Corr16Shape
     tiles1 = std::max<int64_t>(tiles1, steps * ((g.nq[1] + s.tr - 1) / s.tr) * ((g.nq[2] + s.tc - 1) / s.tc));
   }
   const int64_t steps_max = (planes_max + s.tp - 1) / s.tp;
-  // a workgroup's set-up (its address tables) costs about as much as two window steps of a 3 x 3 kernel, so walk
-  // through several steps when there are more tiles than the chip runs at a time (two workgroups per CU)
-  s.g0 = (int)std::max<int64_t>(1, std::min<int64_t>(steps_max, (tiles1 * p->n_workers + 511) / 512));
-  s.g0 = (int)((steps_max + (steps_max + s.g0 - 1) / s.g0 - 1) / ((steps_max + s.g0 - 1) / s.g0));  // even groups
+  // Window steps per workgroup.  A workgroup's set-up (its address tables) costs about as much as two steps of a
+  // 3 x 3 kernel and the chip runs about 512 workgroups at a time: take the step count with the smallest
+  // estimate of rounds x (set-up + steps), steps dealt evenly to the groups.
+  {
+    const int64_t per_step = std::max<int64_t>(1, tiles1 / std::max<int64_t>(steps_max, 1)) * p->n_workers;
+    double best_cost = 1e300;
+    s.g0 = 1;
+    for (int64_t g0 = 1; g0 <= steps_max; ++g0) {
+      const int64_t groups = (steps_max + g0 - 1) / g0, even = (steps_max + groups - 1) / groups;
+      if (even != g0) continue;
+      const double cost = (double)((groups * per_step + 511) / 512) * (2.0 + (double)g0);
+      if (cost < best_cost - 1e-9) best_cost = cost, s.g0 = (int)g0;
+    }
+  }
   tiles1 = 0;
   for (const WorkerDev& wd : p->workers) {
     const PerWorker g = derive(wd, c);
