@@ -144,7 +144,9 @@ int distdl_sumreduce_adj(const void* const gdst_dev[], void* const gsrc_dev[], c
 
 /* ------------------------------------------------------------------------
  * Partitioned convolution: the Forward / Adjoint Convolution Algorithms of
- * Sec. 4 with the feature space partitioned only (P_co = P_ci = 1), fp32.
+ * Sec. 4 with the feature space partitioned only (P_co = P_ci = 1).  The plan's
+ * dtype is the element type of every array (x, w, b, y and all gradients):
+ * fp32, or bf16 with fp32 accumulation and results rounded to nearest even.
  *
  * conv_fwd: x <- H x in place on x_bufs_dev; w and b are read by every worker
  *   directly (the broadcasts B w, B b without materialised replicas); each
@@ -158,8 +160,9 @@ int distdl_sumreduce_adj(const void* const gdst_dev[], void* const gsrc_dev[], c
  *   gradient in its bulk and zeros in halo and pad cells.  dw_dev has the
  *   shape of w; dbias_dev may be NULL.  workspace_dev must provide
  *   distdl_conv_bwd_workspace(plan) bytes (16-byte aligned).
- * Errors: UNSUPPORTED for a bf16 or explicit plan; INVALID_ARG for a short
- * workspace.
+ *   The workspace holds fp32 partials of dw whatever the dtype.
+ * Errors: UNSUPPORTED for an explicit plan; INVALID_ARG for a short workspace
+ * or arrays that are not aligned to their element size.
  * ---------------------------------------------------------------------- */
 int distdl_conv_fwd(distdl_plan* plan, void* const x_bufs_dev[], const void* w_dev, const void* bias_dev,
                     void* const y_dev[], void* stream);
