@@ -104,6 +104,47 @@ def test_conv_fwd_bwd_against_partitioned_oracle(name, override, use_bias):
         assert_close(db.cpu().numpy(), db_want, TOL32, "db")
 
 
+def _random_small_cases(count):
+    """Seeded random layers with at most 16 channels: D, kernel, dilation, leading-dimension stride, ragged shapes
+    and partitions (the geometry the 16 x 16-tile kernels choose their windows and units from)."""
+    rng = np.random.default_rng(77)
+    cases = []
+    while len(cases) < count:
+        D = int(rng.integers(1, 4))
+        k = tuple(int(rng.choice([1, 3, 5])) if d >= D - 2 else int(rng.choice([1, 2, 3])) for d in range(D))
+        dil = tuple(int(rng.choice([1, 1, 2])) for _ in range(D))
+        stride = tuple(int(rng.choice([1, 2])) if d < D - 2 else 1 for d in range(D))
+        P = tuple(int(rng.integers(1, 4)) for _ in range(D))
+        pad = tuple(int(rng.integers(0, (k[d] - 1) * dil[d] // 2 + 1)) for d in range(D))
+        lo = [max((k[d] - 1) * dil[d] + 1, 2 * P[d] * stride[d] + (k[d] - 1) * dil[d]) for d in range(D)]
+        shape = tuple(int(rng.integers(lo[d], lo[d] + (40 if d == D - 1 else 14))) for d in range(D))
+        cfg = dict(D=D, n_b=int(rng.integers(1, 12)), c_in=int(rng.integers(1, 17)), c_out=int(rng.integers(1, 17)),
+                   in_shape=shape, P=P, ksize=k, stride=stride, padding=pad, dilation=dil, seed=len(cases))
+        try:
+            oracle_partition(cfg)
+        except Exception:
+            continue
+        cases.append(cfg)
+    return cases
+
+
+@pytest.mark.parametrize("cfg", _random_small_cases(24), ids=lambda c: f"D{c['D']}c{c['c_in']}-{c['c_out']}k{'x'.join(map(str, c['ksize']))}")
+def test_conv_small_channel_random_layers(cfg):
+    require_gpu()
+    part = oracle_partition(cfg)
+    case = syn.conv_case(cfg, part.global_out_shape())
+    x_bufs, y, dx_bufs, dw, db = _run_conv(cfg, part, case, True)
+    o_bufs = prim.scatter_bulk(case["x"].astype(np.float64), part, fill=np.nan)
+    y_want = layers.dist_conv_forward(o_bufs, case["w"], case["bias"], part, cfg["stride"], cfg["dilation"])
+    dx_want, dw_want, db_want = layers.dist_conv_adjoint(o_bufs, case["w"], prim.scatter_out(case["dy"], part), part,
+                                                         cfg["stride"], cfg["dilation"], True)
+    for wk in range(part.n_workers):
+        assert_close(from_cl(y[wk]), y_want[wk], TOL32, f"y worker {wk}")
+        assert_close(from_cl(dx_bufs[wk]), dx_want[wk], TOL32, f"dx worker {wk}")
+    assert_close(dw.cpu().numpy(), dw_want, TOL32, "dw")
+    assert_close(db.cpu().numpy(), db_want, TOL32, "db")
+
+
 CONV_BF16 = [
     # matrix-core path (channel counts that are multiples of 4), 3-D strided, 2-D, dilated; then the direct kernels
     ("cfg5", dict(in_shape=(24, 22, 40), P=(2, 2, 1), c_in=32, c_out=32), True),
