@@ -45,7 +45,7 @@ __device__ inline uint32_t f32_to_bf16_rne(float f) {
 
 // BF16 = false: T is float, BK = 32 floats per stage.  BF16 = true: T is bf16 bits, BK = 64 per stage.
 // TM x TN: 32 x 32 MFMA tiles per wave; the workgroup tile is 64*TM x 64*TN (4 waves, 2 x 2).
-// Row pitch in LDS is BK + 16 bytes for the K-contiguous layout, tile extent + 16 bytes for the other.
+// Row pitch in LDS is BK + 16 bytes for the K-contiguous layout, tile extent + 16 (bf16: 32) bytes for the other.
 //
 // nsplit > 1 (grid.y): the K stages of every segment are dealt to nsplit workgroups per tile, each of which
 // writes its fp32 partial tile to `partial` ([block][split][M][N]); gemm_reduce_kernel then sums the splits
@@ -59,8 +59,9 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(const GemmBlock* __restr
   constexpr int VE = 16 / ES;                  // elements per 16-byte piece
   constexpr int TILE_M = 64 * TM, TILE_N = 64 * TN;
   constexpr int PITCH_KC = BK * ES + 16;       // bytes per tile row, K-contiguous staging [row][k]
-  constexpr int PITCH_TA = TILE_M * ES + 16;   // bytes per k line, transposed staging [k][row]
-  constexpr int PITCH_TB = TILE_N * ES + 16;
+  constexpr int TPAD = BF16 ? 32 : 16;         // bf16: four k lines read together fall 8 banks apart
+  constexpr int PITCH_TA = TILE_M * ES + TPAD;  // bytes per k line, transposed staging [k][row]
+  constexpr int PITCH_TB = TILE_N * ES + TPAD;
   constexpr int A_BYTES = A_KC ? TILE_M * PITCH_KC : BK * PITCH_TA;
   constexpr int B_BYTES = B_KC ? TILE_N * PITCH_KC : BK * PITCH_TB;
   constexpr int PA = TILE_M * BK * ES / 16 / 256;  // 16-byte pieces per thread and stage
@@ -216,7 +217,15 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(const GemmBlock* __restr
         __builtin_amdgcn_sched_barrier(0);
         mm(a1, b1);
       } else {
-        union Frag { u32x4 u; bf16x8 v; uint16_t e[8]; };
+        // An operand staged [k][row] (rows contiguous) is read with ds_read_b64_tr_b16.  Measured lane layout of
+        // that load: in every group of 16 lanes, lane 4 * b + a receives, as element v, the a-th 16-bit element of
+        // the 8 bytes addressed by lane b + 4 * v of the group.  Lane s of group G addresses rows
+        // 16 * (G % 2) + 4 * (s % 4) ... + 3 of k line 8 * (G / 2) + s / 4, so lane t of the group receives row
+        // 16 * (G % 2) + t of four consecutive k: two loads make the operand of lane l = (row l % 32, k 8 * (l / 32) ...).
+        typedef short v4i16 __attribute__((ext_vector_type(4)));
+        typedef __attribute__((address_space(3))) v4i16* lds_v4;
+        union Frag { u32x4 u; bf16x8 v; v4i16 t[2]; };
+        const int tk = 8 * (lane >> 5) + ((lane & 15) >> 2), tr = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
         auto rd = [&](int kk, Frag (&av)[TM], Frag (&bv)[TN]) {
 #pragma unroll
           for (int i = 0; i < TM; ++i) {
@@ -224,8 +233,8 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(const GemmBlock* __restr
             if (A_KC) {
               av[i].u = *(const u32x4*)(sa + row * PITCH_KC + (kk + 8 * h) * 2);
             } else {
-#pragma unroll
-              for (int j = 0; j < 8; ++j) av[i].e[j] = *(const uint16_t*)(sa + (kk + 8 * h + j) * PITCH_TA + row * 2);
+              av[i].t[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(sa + (kk + tk) * PITCH_TA + (row - ml + tr) * 2));
+              av[i].t[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(sa + (kk + tk + 4) * PITCH_TA + (row - ml + tr) * 2));
             }
           }
 #pragma unroll
@@ -234,8 +243,8 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(const GemmBlock* __restr
             if (B_KC) {
               bv[i].u = *(const u32x4*)(sb + row * PITCH_KC + (kk + 8 * h) * 2);
             } else {
-#pragma unroll
-              for (int j = 0; j < 8; ++j) bv[i].e[j] = *(const uint16_t*)(sb + (kk + 8 * h + j) * PITCH_TB + row * 2);
+              bv[i].t[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(sb + (kk + tk) * PITCH_TB + (row - ml + tr) * 2));
+              bv[i].t[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(sb + (kk + tk + 4) * PITCH_TB + (row - ml + tr) * 2));
             }
           }
         };
@@ -431,8 +440,8 @@ size_t gemm_mfma_partial_floats(const std::vector<GemmBlock>& blocks, int nsplit
 template <bool BF16, bool A_KC, bool B_KC, int T>
 static int launch_gemm_variant(dim3 grid, const GemmBlock* d_blocks, float* partial, int64_t max_mn, hipStream_t st) {
   constexpr int ES = BF16 ? 2 : 4, BK = BF16 ? 64 : 32, TILE = 64 * T;
-  constexpr int A_BYTES = A_KC ? TILE * (BK * ES + 16) : BK * (TILE * ES + 16);
-  constexpr int B_BYTES = B_KC ? TILE * (BK * ES + 16) : BK * (TILE * ES + 16);
+  constexpr int A_BYTES = A_KC ? TILE * (BK * ES + 16) : BK * (TILE * ES + (BF16 ? 32 : 16));
+  constexpr int B_BYTES = B_KC ? TILE * (BK * ES + 16) : BK * (TILE * ES + (BF16 ? 32 : 16));
   constexpr int LDS = 2 * (A_BYTES + B_BYTES);
   if (LDS > 64 * 1024)
     DISTDL_HIP_TRY(hipFuncSetAttribute((const void*)gemm_mfma_kernel<BF16, A_KC, B_KC, T, T>,
