@@ -257,6 +257,31 @@ class MovementWorkload:
     def value(self, seconds_per_step):
         return self.bytes_step / seconds_per_step / 1e9
 
+    def achievable_copy(self):
+        """What a plain device-to-device copy reaches on this chip (the practical ceiling of any streaming kernel):
+        2 GiB read + 2 GiB written, by the library's own copy (broadcast with k = 1) and by torch's copy_, median
+        of 9 timed with events on the launch stream."""
+        torch, dd = self.torch, self.dd
+        n = 1 << 29                                    # fp32 elements: 2 GiB
+        src = torch.empty(n, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        out = {"bytes_moved": 2 * n * 4}
+        for name, call in (("library_copy", lambda: dd.distdl_bcast_fwd([src], [dst], 1)),
+                           ("torch_copy", lambda: dst.copy_(src))):
+            times = []
+            for _ in range(11):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                call()
+                e1.record()
+                e1.synchronize()
+                times.append(e0.elapsed_time(e1))
+            ms = sorted(times[2:])[len(times[2:]) // 2]
+            out[name + "_GBs"] = 2 * n * 4 / (ms * 1e-3) / 1e9
+        out["best_GBs"] = max(out["library_copy_GBs"], out["torch_copy_GBs"])
+        out["frac_hbm_peak"] = out["best_GBs"] / HBM_PEAK_GBS
+        return out
+
     def sweep(self):
         """B and R over k in {2, 4, 64} replicas of 1 MiB .. 1 GiB (fp32), array sets rotated through a pool of
         20 GiB so that no call finds its operands in the cache; kernel time from the library's HIP events."""
@@ -725,6 +750,12 @@ def main():
         torch.cuda.empty_cache()
         mv, rep = side_run(lambda: MovementWorkload(False), 10)
         rep["frac_hbm_peak"] = rep["value"] / HBM_PEAK_GBS
+        del mv.x, mv.g
+        torch.cuda.empty_cache()
+        rep["achievable_copy"] = mv.achievable_copy()
+        for kern in rep["kernels"].values():
+            if kern.get("bound") == "hbm":
+                kern["frac_of_achievable_copy"] = kern["achieved"] / rep["achievable_copy"]["best_GBs"]
         line["movement"] = rep
         del mv
         torch.cuda.empty_cache()
@@ -743,6 +774,11 @@ def main():
             del w
     if getattr(wl, "sweep_on", False):
         line["sweep"] = wl.sweep()
+    if args.workload == "movement":
+        line["achievable_copy"] = wl.achievable_copy()
+        for kern in line["kernels"].values():
+            if kern.get("bound") == "hbm":
+                kern["frac_of_achievable_copy"] = kern["achieved"] / line["achievable_copy"]["best_GBs"]
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = wl.cpu_baseline()
     print(json.dumps(line))
