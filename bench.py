@@ -87,6 +87,14 @@ class ConvWorkload:
             "conv_relayout_w": ("hbm", 2 * nw * esz),
         }
         self.nw = nw
+        # least bytes each contraction must move (operands once, results once): for the second roofline
+        # min(MFMA peak, arithmetic intensity x HBM peak)
+        xb = sum(t.numel() for t in self.x) * esz
+        yb = sum(t.numel() for t in self.dy) * esz
+        self.min_bytes = {"conv_fwd": xb + yb + nw * esz,
+                          "conv_bwd_data_mfma": (xb + yb) / _prod(c["stride"]) + nw * esz,
+                          "conv_bwd_data": xb + yb + nw * esz,
+                          "conv_bwd_weight": xb + yb + nw * 4}
         self.metric = "partitioned conv fwd+bwd TFLOP/s (halo exchange H, H* and dw sum-reduce included)"
         self.unit = "TFLOP/s"
         # arithmetic types: fp32 throughout for fp32 tensors; bf16 tensors are multiplied in bf16 with fp32
