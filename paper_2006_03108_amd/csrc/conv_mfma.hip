@@ -1078,6 +1078,7 @@ static int launch_corr(distdl_plan* p, CorrArgs a, const void* w, float* wscratc
   else if (mt == 2 && small && ntaps == 6) DISTDL_LAUNCH_CORR(2, 4, 3, 6);
   else if (mt == 2 && small && ntaps == 4) DISTDL_LAUNCH_CORR(2, 4, 3, 4);
   else if (mt == 2 && small) DISTDL_LAUNCH_CORR(2, 4, 3, 0);
+  else if (mt == 2 && ntaps == 25) DISTDL_LAUNCH_CORR(2, kMaxPieces, kMaxBPieces, 25);
   else if (mt == 2) DISTDL_LAUNCH_CORR(2, kMaxPieces, kMaxBPieces, 0);
   else if (small) DISTDL_LAUNCH_CORR(1, 4, 3, 0);
   else DISTDL_LAUNCH_CORR(1, kMaxPieces, kMaxBPieces, 0);
