@@ -246,7 +246,9 @@ int distdl_mse_fwd_bwd(const void* const y_dev[], const void* const t_dev[], voi
 /* ------------------------------------------------------------------------
  * Convolution with the channels partitioned as well (Sec. 4, Forward / Adjoint
  * Convolution Algorithms on a P_co x P_ci x feature-space partition; the
- * weights live on the P_co x P_ci grid, the bias on its ci = 0 column), fp32.
+ * weights live on the P_co x P_ci grid, the bias on its ci = 0 column), fp32 or
+ * bf16 (the partial outputs of the blocks are rounded to bf16 before they are
+ * sum-reduced).
  * Channel blocks follow the balanced rule.  With S = prod P spatial workers:
  *   x_bufs_dev[j*S + s]: padded buffer [n_b][buf..][ci_j] of input block j on
  *       spatial worker s (bulk filled; holds H x afterwards, which bwd expects);

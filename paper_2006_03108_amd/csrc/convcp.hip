@@ -20,8 +20,9 @@ struct distdl_convcp_plan {
   int64_t n_b = 0, n_ci = 0, n_co = 0;
   std::vector<int64_t> co_start, co_size, ci_start, ci_size;
   std::vector<distdl_plan*> sub;  // [i * P_ci + j]
-  float* d_tmp = nullptr;         // y^_ij (forward) or dx^_ij (adjoint) partials
-  size_t tmp_floats = 0;
+  char* d_tmp = nullptr;          // y^_ij (forward) or dx^_ij (adjoint) partials, in the layer's element type
+  size_t tmp_floats = 0;          // its size in bytes
+  distdl_dtype dtype = DISTDL_F32;
   void* d_ws = nullptr;           // workspace of the single-block backward call
   size_t ws_bytes = 0;
 };
@@ -61,7 +62,7 @@ int distdl_convcp_plan_create(distdl_convcp_plan** out, int D, int64_t n_b, int6
                               distdl_dtype dtype) {
   if (!out) return set_error(DISTDL_ERR_NULL, "convcp_plan_create: null argument");
   *out = nullptr;
-  if (dtype != DISTDL_F32) return set_error(DISTDL_ERR_UNSUPPORTED, "convcp: only fp32 is implemented");
+  if (dtype != DISTDL_F32 && dtype != DISTDL_BF16) return set_error(DISTDL_ERR_INVALID_ARG, "convcp: unknown dtype");
   if (P_co < 1 || P_ci < 1) return set_error(DISTDL_ERR_INVALID_ARG, "convcp: P_co = %d, P_ci = %d", P_co, P_ci);
   if (P_co > n_c_out || P_ci > n_c_in)
     return set_error(DISTDL_ERR_EMPTY_PARTITION, "convcp: more channel blocks than channels");
@@ -73,6 +74,7 @@ int distdl_convcp_plan_create(distdl_convcp_plan** out, int D, int64_t n_b, int6
   p->n_b = n_b;
   p->n_ci = n_c_in;
   p->n_co = n_c_out;
+  p->dtype = dtype;
   balanced(n_c_out, P_co, p->co_start, p->co_size);
   balanced(n_c_in, P_ci, p->ci_start, p->ci_size);
   p->sub.assign((size_t)P_co * P_ci, nullptr);
@@ -138,13 +140,14 @@ int distdl_convcp_fwd(distdl_convcp_plan* p, void* const x_bufs_dev[], const voi
       ycount[(size_t)i * S + s] = cells * p->co_size[i];
       tmp += (size_t)ycount[(size_t)i * S + s] * Pci;
     }
-  if (Pci > 1 && (rc = ensure((void**)&p->d_tmp, &p->tmp_floats, tmp * sizeof(float)))) return rc;
+  const size_t esz = p->dtype == DISTDL_BF16 ? 2 : 4;
+  if (Pci > 1 && (rc = ensure((void**)&p->d_tmp, &p->tmp_floats, tmp * esz + 16 * (size_t)Pco * Pci * S))) return rc;
   for (int j = 0; j < Pci; ++j) {  // x_j <- H x_j, once per input block
     distdl_plan* pj = p->sub[j];
     if ((rc = run_halo(pj, false, pj->tab_x, x_bufs_dev + (size_t)j * S, st))) return rc;
   }
   std::vector<void*> parts((size_t)Pco * S * Pci);  // [(i, s)][j]
-  float* at = p->d_tmp;
+  char* at = p->d_tmp;
   for (int i = 0; i < Pco; ++i) {
     for (int j = 0; j < Pci; ++j) {
       std::vector<void*> target(S);
@@ -154,7 +157,7 @@ int distdl_convcp_fwd(distdl_convcp_plan* p, void* const x_bufs_dev[], const voi
         } else {
           target[s] = at;
           parts[((size_t)i * S + s) * Pci + j] = at;
-          at += ycount[(size_t)i * S + s];
+          at += (ycount[(size_t)i * S + s] * esz + 15) / 16 * 16;  // every partial starts 16-byte aligned
         }
       }
       const void* b = (bias_dev && j == 0) ? bias_dev[i] : nullptr;  // the bias lives on the ci = 0 sub-partition
@@ -164,7 +167,7 @@ int distdl_convcp_fwd(distdl_convcp_plan* p, void* const x_bufs_dev[], const voi
     }
   }
   if (Pci > 1)  // y_i <- R over j
-    return distdl_sumreduce_fwd(parts.data(), y_dev, ycount.data(), Pco * S, Pci, DISTDL_F32, 0, stream);
+    return distdl_sumreduce_fwd(parts.data(), y_dev, ycount.data(), Pco * S, Pci, p->dtype, 0, stream);
   return DISTDL_OK;
 }
 
@@ -190,10 +193,11 @@ int distdl_convcp_bwd(distdl_convcp_plan* p, const void* const x_bufs_dev[], con
       tmp += (size_t)xcount[(size_t)j * S + s] * Pco;
     }
   for (distdl_plan* sp : p->sub) ws = std::max(ws, distdl_conv_bwd_workspace(sp));
-  if (Pco > 1 && (rc = ensure((void**)&p->d_tmp, &p->tmp_floats, tmp * sizeof(float)))) return rc;
+  const size_t esz = p->dtype == DISTDL_BF16 ? 2 : 4;
+  if (Pco > 1 && (rc = ensure((void**)&p->d_tmp, &p->tmp_floats, tmp * esz + 16 * (size_t)Pco * Pci * S))) return rc;
   if ((rc = ensure(&p->d_ws, &p->ws_bytes, ws))) return rc;
   std::vector<void*> parts((size_t)Pci * S * Pco);  // [(j, s)][i]
-  float* at = p->d_tmp;
+  char* at = p->d_tmp;
   for (int i = 0; i < Pco; ++i) {
     for (int j = 0; j < Pci; ++j) {
       std::vector<void*> target(S);
@@ -203,7 +207,7 @@ int distdl_convcp_bwd(distdl_convcp_plan* p, const void* const x_bufs_dev[], con
         } else {
           target[s] = at;
           parts[((size_t)j * S + s) * Pco + i] = at;
-          at += xcount[(size_t)j * S + s];
+          at += (xcount[(size_t)j * S + s] * esz + 15) / 16 * 16;
         }
       }
       void* db = (dbias_dev && j == 0) ? dbias_dev[i] : nullptr;
@@ -214,7 +218,7 @@ int distdl_convcp_bwd(distdl_convcp_plan* p, const void* const x_bufs_dev[], con
     }
   }
   if (Pco > 1 &&  // dx_j <- R over i
-      (rc = distdl_sumreduce_fwd(parts.data(), dx_bufs_dev, xcount.data(), Pci * S, Pco, DISTDL_F32, 0, stream)))
+      (rc = distdl_sumreduce_fwd(parts.data(), dx_bufs_dev, xcount.data(), Pci * S, Pco, p->dtype, 0, stream)))
     return rc;
   for (int j = 0; j < Pci; ++j) {  // dx_j <- H* dx_j
     distdl_plan* pj = p->sub[j];
