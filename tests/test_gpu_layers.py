@@ -198,6 +198,25 @@ def test_conv_bf16_fwd_bwd_against_partitioned_oracle(name, override, use_bias):
         assert_close(db.float().cpu().numpy(), db_want, TOL16, "db")
 
 
+@pytest.mark.parametrize("name,override,dtype", [
+    ("cfg2", dict(in_shape=(64, 64), n_b=4), torch.float32),                                   # 16 x 16-tile kernels
+    ("cfg5", dict(in_shape=(24, 22, 40), P=(2, 2, 1)), torch.float32),                          # 32-wide kernels
+    ("cfg5", dict(in_shape=(24, 22, 40), P=(2, 2, 1)), torch.bfloat16),                         # bf16 matrix cores
+    ("cfg2", dict(in_shape=(19, 23), n_b=3, c_in=3, c_out=5, P=(2, 3), stride=(2, 1)), torch.float32),   # direct kernels
+], ids=["small16", "wide", "bf16", "direct"])
+def test_conv_is_run_to_run_identical(name, override, dtype):
+    """No float atomics anywhere: partial sums are combined in a fixed order (Sec. 2 footnote on floating-point
+    addition in parallel), so two runs on the same inputs agree bit for bit."""
+    require_gpu()
+    cfg, part, case = _conv_case(name, **override)
+    if dtype == torch.bfloat16:
+        case = {k: (syn.to_bf16_values(v) if isinstance(v, np.ndarray) else v) for k, v in case.items()}
+    first = _run_conv(cfg, part, case, True, dtype)
+    second = _run_conv(cfg, part, case, True, dtype)
+    for a, b in zip(first[1] + first[2] + [first[3], first[4]], second[1] + second[2] + [second[3], second[4]]):
+        assert torch.equal(a, b)
+
+
 def test_conv_cfg2_full_size():
     """cfg2 at its full size against the sequential definition (Sec. 5 claim:
     distributed == sequential)."""
