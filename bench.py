@@ -341,6 +341,20 @@ class MovementWorkload:
             row.update(extra or {})
             rows.append(row)
 
+        # the halo kernels on the same volume cut along two dimensions only (4 x 4 x 1 workers): every face is made
+        # of whole 32 KB rows, none of 128-256 byte pieces -- what the kernels reach when the access pattern is benign
+        c = self.cfg
+        hp = dd.distdl_plan_create(3, 1, c["c_in"], c["c_in"], c["in_shape"], (4, 4, 1), c["ksize"], c["stride"],
+                                   c["padding"], c["dilation"])
+        hg = [hp.query(w) for w in range(hp.n_workers)]
+        hb = [_dev_randn([1] + g["buf_shape"] + [c["c_in"]], 300 + w) for w, g in enumerate(hg)]
+        hst = dd.distdl_plan_stats(hp)
+        cell = c["c_in"] * 4
+        timed("halo_fwd_rows_only", lambda: dd.distdl_halo_fwd(hp, hb), (2 * hst["halo_cells"] + hst["pad_cells"]) * cell,
+              extra={"P": [4, 4, 1]})
+        timed("halo_adj_rows_only", lambda: dd.distdl_halo_adj(hp, hb),
+              (2 * hst["halo_cells"] + 2 * hst["band_cells"] + hst["pad_cells"]) * cell, extra={"P": [4, 4, 1]})
+        del hb, hp
         # all-reduce A = B R in place over k = 4 replicas of 256 MiB: k reads + k writes
         reps4 = [_dev_randn((1 << 26,), 70 + i) for i in range(4)]
         timed("allreduce", lambda: dd.distdl_allreduce(reps4, 4), 2 * 4 * (1 << 28), extra={"k": 4, "MiB_per_replica": 256})
