@@ -124,15 +124,15 @@ class ConvWorkload:
 
     def cpu_baseline(self):
         """The oracle's distributed conv forward + adjoint on a bounded sample
-        of the same workload: the same channels, kernel and stride on a 64^3
-        (cfg5) or 96^2, batch 2 (cfg2) input over 2 workers per dimension."""
+        of the same workload: the same channels, kernel and stride on an 80^3
+        (cfg5) or 128^2, batch 2 (cfg2) input over 2 workers per dimension."""
         import synthetic_inputs as syn
         from oracle import geometry as geo, layers, primitives as prim
         c = dict(self.cfg)
         if c["D"] == 3:
-            c.update(in_shape=(64, 64, 64), P=(2, 2, 2))
+            c.update(in_shape=(80, 80, 80), P=(2, 2, 2))
         else:
-            c.update(in_shape=(96, 96), n_b=2)
+            c.update(in_shape=(128, 128), n_b=2)
         part = geo.Partition.for_kernel(c["in_shape"], c["P"], c["ksize"], c["stride"], c["padding"], c["dilation"])
         case = syn.conv_case(c, part.global_out_shape())
         t0 = time.perf_counter()
