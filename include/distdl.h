@@ -199,7 +199,8 @@ int distdl_affine_bwd(distdl_affine_plan* plan, const void* const x_dev[], const
 /* ------------------------------------------------------------------------
  * Glue of the example network (Sec. 5, App. C), fp32, channels-last.  Small,
  * latency-bound calls that let a whole partitioned network step run through
- * the library; same conventions as above.
+ * the library; same conventions as above.  The pooling calls also take bf16
+ * plans (bf16 tensors, fp32 arithmetic, results rounded to nearest even).
  *
  * relu_fwd / relu_bwd: point-wise layers need no data movement (Sec. 4):
  *   y = max(x, 0);  dx = x > 0 ? dy : 0, over n arrays of count[i] elements.

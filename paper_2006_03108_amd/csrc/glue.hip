@@ -86,15 +86,15 @@ static PoolDev pool_params(const distdl_plan* p) {
 }
 
 // y[n][o][c] = max over the window of x^[n][origin + o*s + t*dil][c]
-template <bool AVG>
+template <bool AVG, class T>
 __global__ __launch_bounds__(256) void pool_fwd_kernel(const WorkerDev* __restrict__ workers, void* const* x_bufs,
                                                        void* const* y_bufs, PoolDev d) {
   const WorkerDev wd = workers[blockIdx.y];
   const int64_t total = (int64_t)d.n_b * wd.out[0] * wd.out[1] * wd.out[2] * d.c;
   int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (idx >= total) return;
-  const float* __restrict__ x = (const float*)x_bufs[blockIdx.y];
-  float* __restrict__ y = (float*)y_bufs[blockIdx.y];
+  const T* __restrict__ x = (const T*)x_bufs[blockIdx.y];
+  T* __restrict__ y = (T*)y_bufs[blockIdx.y];
   int c = (int)(idx % d.c);
   int64_t r = idx / d.c;
   int o2 = (int)(r % wd.out[2]); r /= wd.out[2];
@@ -107,29 +107,29 @@ __global__ __launch_bounds__(256) void pool_fwd_kernel(const WorkerDev* __restri
   for (int t0 = 0; t0 < d.k[0]; ++t0)
     for (int t1 = 0; t1 < d.k[1]; ++t1)
       for (int t2 = 0; t2 < d.k[2]; ++t2) {
-        const float v = x[n * sn + (wd.origin[0] + o0 * d.s[0] + t0 * d.dil[0]) * s0 +
-                          (wd.origin[1] + o1 * d.s[1] + t1 * d.dil[1]) * s1 +
-                          (wd.origin[2] + o2 * d.s[2] + t2 * d.dil[2]) * s2 + c];
+        const float v = ld(x, n * sn + (wd.origin[0] + o0 * d.s[0] + t0 * d.dil[0]) * s0 +
+                                 (wd.origin[1] + o1 * d.s[1] + t1 * d.dil[1]) * s1 +
+                                 (wd.origin[2] + o2 * d.s[2] + t2 * d.dil[2]) * s2 + c);
         if (first || v > best) best = v;
         sum += v;  // row-major tap order
         first = false;
       }
-  y[idx] = AVG ? sum / (float)(d.k[0] * d.k[1] * d.k[2]) : best;
+  st(y, idx, AVG ? sum / (float)(d.k[0] * d.k[1] * d.k[2]) : best);
 }
 
 // [dPool]* in gather form over the whole padded buffer: a cell receives dy[o] from every window o that
 // contains it and whose first maximum (row-major tap order) it is.
 // For the mean every window that contains the cell contributes dy[o] / window size.
-template <bool AVG>
+template <bool AVG, class T>
 __global__ __launch_bounds__(256) void pool_bwd_kernel(const WorkerDev* __restrict__ workers, void* const* x_bufs,
                                                        void* const* dy_bufs, void* const* dx_bufs, PoolDev d) {
   const WorkerDev wd = workers[blockIdx.y];
   const int64_t total = (int64_t)d.n_b * wd.buf[0] * wd.buf[1] * wd.buf[2] * d.c;
   int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (idx >= total) return;
-  const float* __restrict__ x = AVG ? nullptr : (const float*)x_bufs[blockIdx.y];
-  const float* __restrict__ dy = (const float*)dy_bufs[blockIdx.y];
-  float* __restrict__ dx = (float*)dx_bufs[blockIdx.y];
+  const T* __restrict__ x = AVG ? nullptr : (const T*)x_bufs[blockIdx.y];
+  const T* __restrict__ dy = (const T*)dy_bufs[blockIdx.y];
+  T* __restrict__ dx = (T*)dx_bufs[blockIdx.y];
   int c = (int)(idx % d.c);
   int64_t r = idx / d.c;
   int c2 = (int)(r % wd.buf[2]); r /= wd.buf[2];
@@ -149,7 +149,7 @@ __global__ __launch_bounds__(256) void pool_bwd_kernel(const WorkerDev* __restri
         const int o0 = q0 / d.s[0], o1 = q1 / d.s[1], o2 = q2 / d.s[2];
         if (o0 >= wd.out[0] || o1 >= wd.out[1] || o2 >= wd.out[2]) continue;
         if (AVG) {
-          acc += dy[n * son + o0 * so0 + o1 * so1 + o2 * so2 + c];
+          acc += ld(dy, n * son + o0 * so0 + o1 * so1 + o2 * so2 + c);
           continue;
         }
         // is this cell (tap index `tap`) the first maximum of window o?
@@ -158,14 +158,14 @@ __global__ __launch_bounds__(256) void pool_bwd_kernel(const WorkerDev* __restri
         for (int u0 = 0; u0 < d.k[0]; ++u0)
           for (int u1 = 0; u1 < d.k[1]; ++u1)
             for (int u2 = 0; u2 < d.k[2]; ++u2, ++u) {
-              const float v = x[n * sn + (wd.origin[0] + o0 * d.s[0] + u0 * d.dil[0]) * s0 +
-                                (wd.origin[1] + o1 * d.s[1] + u1 * d.dil[1]) * s1 +
-                                (wd.origin[2] + o2 * d.s[2] + u2 * d.dil[2]) * s2 + c];
+              const float v = ld(x, n * sn + (wd.origin[0] + o0 * d.s[0] + u0 * d.dil[0]) * s0 +
+                                       (wd.origin[1] + o1 * d.s[1] + u1 * d.dil[1]) * s1 +
+                                       (wd.origin[2] + o2 * d.s[2] + u2 * d.dil[2]) * s2 + c);
               if (arg < 0 || v > best) best = v, arg = u;
             }
-        if (arg == tap) acc += dy[n * son + o0 * so0 + o1 * so1 + o2 * so2 + c];
+        if (arg == tap) acc += ld(dy, n * son + o0 * so0 + o1 * so1 + o2 * so2 + c);
       }
-  dx[idx] = AVG ? acc / (float)(d.k[0] * d.k[1] * d.k[2]) : acc;
+  st(dx, idx, AVG ? acc / (float)(d.k[0] * d.k[1] * d.k[2]) : acc);
 }
 
 // Faster forms for channel counts that are multiples of 4 and 16-byte aligned buffers: a thread owns four
@@ -398,7 +398,6 @@ static double* g_mse_partial[64] = {};
 
 static int check_pool_plan(const distdl_plan* p, const char* what) {
   if (p->explicit_halo) return set_error(DISTDL_ERR_UNSUPPORTED, "%s: plan has no kernel (explicit halo plan)", what);
-  if (p->dtype != DISTDL_F32) return set_error(DISTDL_ERR_UNSUPPORTED, "%s: only fp32 is implemented", what);
   if (p->n_ci != p->n_co) return set_error(DISTDL_ERR_INVALID_ARG, "%s: pooling keeps the channel count", what);
   return DISTDL_OK;
 }
@@ -425,9 +424,9 @@ static bool all_aligned16(const void* const* v, int n) {
   return true;
 }
 
-static int check_list(const void* const* v, int n, const char* what) {
+static int check_list(const void* const* v, int n, const char* what, int esz = 4) {
   for (int i = 0; i < n; ++i)
-    if (!v[i] || (uintptr_t)v[i] % 4) return set_error(DISTDL_ERR_NULL, "%s: array %d null or misaligned", what, i);
+    if (!v[i] || (uintptr_t)v[i] % esz) return set_error(DISTDL_ERR_NULL, "%s: array %d null or misaligned", what, i);
   return DISTDL_OK;
 }
 
@@ -451,14 +450,15 @@ static int pool_fwd(distdl_plan* plan, void* const x_bufs_dev[], void* const y_d
   if (!plan || !x_bufs_dev || !y_dev) return set_error(DISTDL_ERR_NULL, "%s: null argument", what);
   int rc = check_pool_plan(plan, what);
   if (rc) return rc;
-  if ((rc = check_list((const void* const*)y_dev, plan->n_workers, what))) return rc;
+  const bool bf16 = plan->dtype == DISTDL_BF16;  // bf16 tensors: the element-wise kernels (fp32 arithmetic)
+  if ((rc = check_list((const void* const*)y_dev, plan->n_workers, what, bf16 ? 2 : 4))) return rc;
   if ((rc = run_halo(plan, false, plan->tab_x, x_bufs_dev, st))) return rc;  // x <- H x
   if ((rc = plan->tab_x.upload((const void* const*)x_bufs_dev, plan->n_workers, st))) return rc;
   if ((rc = plan->tab_y.upload((const void* const*)y_dev, plan->n_workers, st))) return rc;
   PoolDev d = pool_params(plan);
   int64_t total = plan->n_b * plan->max_out_cells * d.c;
   ProfScope prof(what, st);
-  if (d.c % 4 == 0 && all_aligned16((const void* const*)x_bufs_dev, plan->n_workers) &&
+  if (!bf16 && d.c % 4 == 0 && all_aligned16((const void* const*)x_bufs_dev, plan->n_workers) &&
       all_aligned16((const void* const*)y_dev, plan->n_workers) && total / 4 < (int64_t(1) << 31) &&
       ensure_pooldiv(plan) == DISTDL_OK) {
     dim3 grid((unsigned)((total / 4 + 255) / 256), plan->n_workers);
@@ -476,8 +476,14 @@ static int pool_fwd(distdl_plan* plan, void* const x_bufs_dev[], void* const y_d
     return DISTDL_OK;
   }
   dim3 grid((unsigned)((total + 255) / 256), plan->n_workers);
-  if (avg) hipLaunchKernelGGL(pool_fwd_kernel<true>, grid, dim3(256), 0, st, plan->d_workers, plan->tab_x.dev, plan->tab_y.dev, d);
-  else hipLaunchKernelGGL(pool_fwd_kernel<false>, grid, dim3(256), 0, st, plan->d_workers, plan->tab_x.dev, plan->tab_y.dev, d);
+#define DISTDL_POOL_FWD_G(A_, T_)                                                                                   \
+  hipLaunchKernelGGL((pool_fwd_kernel<A_, T_>), grid, dim3(256), 0, st, plan->d_workers, plan->tab_x.dev,            \
+                     plan->tab_y.dev, d)
+  if (avg && bf16) DISTDL_POOL_FWD_G(true, uint16_t);
+  else if (avg) DISTDL_POOL_FWD_G(true, float);
+  else if (bf16) DISTDL_POOL_FWD_G(false, uint16_t);
+  else DISTDL_POOL_FWD_G(false, float);
+#undef DISTDL_POOL_FWD_G
   DISTDL_HIP_TRY(hipGetLastError());
   return DISTDL_OK;
 }
@@ -488,8 +494,11 @@ static int pool_bwd(distdl_plan* plan, const void* const x_bufs_dev[], const voi
   if (!plan || (!avg && !x_bufs_dev) || !dy_dev || !dx_bufs_dev) return set_error(DISTDL_ERR_NULL, "%s: null argument", what);
   int rc = check_pool_plan(plan, what);
   if (rc) return rc;
-  if ((!avg && (rc = check_list(x_bufs_dev, plan->n_workers, what))) || (rc = check_list(dy_dev, plan->n_workers, what)) ||
-      (rc = check_list((const void* const*)dx_bufs_dev, plan->n_workers, what)))
+  const bool bf16 = plan->dtype == DISTDL_BF16;
+  const int esz = bf16 ? 2 : 4;
+  if ((!avg && (rc = check_list(x_bufs_dev, plan->n_workers, what, esz))) ||
+      (rc = check_list(dy_dev, plan->n_workers, what, esz)) ||
+      (rc = check_list((const void* const*)dx_bufs_dev, plan->n_workers, what, esz)))
     return rc;
   if ((rc = plan_prepare_device(plan))) return rc;
   if ((!avg && (rc = plan->tab_x.upload(x_bufs_dev, plan->n_workers, st))) ||
@@ -500,7 +509,7 @@ static int pool_bwd(distdl_plan* plan, const void* const x_bufs_dev[], const voi
   int64_t total = plan->n_b * plan->max_buf_cells * d.c;
   {
     ProfScope prof(what, st);
-    bool tiled = d.c % 4 == 0 && all_aligned16(dy_dev, plan->n_workers) &&
+    bool tiled = !bf16 && d.c % 4 == 0 && all_aligned16(dy_dev, plan->n_workers) &&
                  all_aligned16((const void* const*)dx_bufs_dev, plan->n_workers) &&
                  (avg || all_aligned16(x_bufs_dev, plan->n_workers));
     for (int i = 0; i < 3; ++i) tiled = tiled && d.dil[i] == 1 && d.s[i] >= d.k[i];
@@ -526,12 +535,14 @@ static int pool_bwd(distdl_plan* plan, const void* const x_bufs_dev[], const voi
                            plan->tab_dx.dev, d);
     } else {
     dim3 grid((unsigned)((total + 255) / 256), plan->n_workers);
-    if (avg)
-      hipLaunchKernelGGL(pool_bwd_kernel<true>, grid, dim3(256), 0, st, plan->d_workers, (void* const*)nullptr,
-                         plan->tab_dy.dev, plan->tab_dx.dev, d);
-    else
-      hipLaunchKernelGGL(pool_bwd_kernel<false>, grid, dim3(256), 0, st, plan->d_workers, plan->tab_x.dev,
-                         plan->tab_dy.dev, plan->tab_dx.dev, d);
+#define DISTDL_POOL_BWD_G(A_, T_)                                                                                   \
+  hipLaunchKernelGGL((pool_bwd_kernel<A_, T_>), grid, dim3(256), 0, st, plan->d_workers,                             \
+                     A_ ? (void* const*)nullptr : plan->tab_x.dev, plan->tab_dy.dev, plan->tab_dx.dev, d)
+    if (avg && bf16) DISTDL_POOL_BWD_G(true, uint16_t);
+    else if (avg) DISTDL_POOL_BWD_G(true, float);
+    else if (bf16) DISTDL_POOL_BWD_G(false, uint16_t);
+    else DISTDL_POOL_BWD_G(false, float);
+#undef DISTDL_POOL_BWD_G
     }
   }
   DISTDL_HIP_TRY(hipGetLastError());

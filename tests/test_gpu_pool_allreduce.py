@@ -88,6 +88,42 @@ def test_maxpool_general_kernels(case):
         assert_close(from_cl(g_dx[w]), dx_want[w], TOL32, f"maxpool dx worker {w}")
 
 
+@pytest.mark.parametrize("case", [POOL_CASES[0], POOL_CASES[2], POOL_CASES[4], POOL_CASES[5]],
+                         ids=lambda c: str(c[3]) + "k" + str(c[5]))
+def test_pooling_bf16(case):
+    """bf16 tensors through max and average pooling: the max is exact (a selection), sums round to bf16 (2e-2)."""
+    require_gpu()
+    D, n_b, c, n, P, k, s, p = case
+    one, bf = (1,) * D, torch.bfloat16
+    part = geo.Partition.for_kernel(n, P, k, s, p, one)
+    plan = dd.distdl_plan_create(D, n_b, c, c, n, P, k, s, p, one, bf)
+    r = syn.streams(33, 2)
+    x = syn.to_bf16_values(syn.normal(r[0], (n_b, c) + tuple(n)))
+    dy = syn.to_bf16_values(syn.normal(r[1], (n_b, c) + part.global_out_shape()))
+    bufs_o = prim.scatter_bulk(x.astype(np.float64), part, fill=np.nan)
+    dyo = prim.scatter_out(dy.astype(np.float64), part)
+    shapes = [b.shape for b in bufs_o]
+    ymax, args = layers.dist_maxpool_forward(bufs_o, part, k, s)
+    dxmax = layers.dist_maxpool_adjoint(dyo, args, part, shapes, k, s)
+    yavg = layers.dist_avgpool_forward(bufs_o, part, k, s)
+    dxavg = layers.dist_avgpool_adjoint(dyo, part, shapes, k, s)
+    g_x = [to_cl(b, bf) for b in prim.scatter_bulk(x, part, fill=np.float32(9.0))]
+    new_y = lambda: [torch.empty((n_b,) + part.out_shape(w) + (c,), device="cuda", dtype=bf) for w in range(part.n_workers)]
+    g_dy = [to_cl(t, bf) for t in prim.scatter_out(dy, part)]
+    y1, y2 = new_y(), new_y()
+    dx1, dx2 = [torch.full_like(t, -5.0) for t in g_x], [torch.full_like(t, -5.0) for t in g_x]
+    dd.distdl_maxpool_fwd(plan, g_x, y1)
+    dd.distdl_maxpool_bwd(plan, g_x, g_dy, dx1)
+    dd.distdl_avgpool_fwd(plan, g_x, y2)
+    dd.distdl_avgpool_bwd(plan, g_dy, dx2)
+    torch.cuda.synchronize()
+    for w in range(part.n_workers):
+        assert np.array_equal(from_cl(y1[w]), ymax[w].astype(np.float32)), f"maxpool y worker {w}"
+        assert_close(from_cl(dx1[w]), dxmax[w], 2e-2, f"maxpool dx worker {w}")
+        assert_close(from_cl(y2[w]), yavg[w], 2e-2, f"avgpool y worker {w}")
+        assert_close(from_cl(dx2[w]), dxavg[w], 2e-2, f"avgpool dx worker {w}")
+
+
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
 @pytest.mark.parametrize("count,k,G", [(16, 4, 1), (4099, 3, 2), (1 << 20, 2, 2), (1000, 70, 1), (0, 2, 1)])
 def test_allreduce_matches_oracle_and_is_self_adjoint(count, k, G, dtype):
