@@ -19,6 +19,8 @@ CASES = [
     ((5, 12, 7, 32), (1, 3, 2, 1), (5, 1, 1, 4)),           # wide rows, vector path
     ((2, 9, 31, 33), (2, 1, 4, 3), (1, 3, 2, 5)),           # odd extents: element path
     ((256, 16, 10, 10), (1, 1, 2, 2), (2, 2, 1, 1)),        # the example network's activations, batch split
+    ((3, 8, 20, 12), (1, 1, 1, 1), (1, 2, 3, 2)),           # scatter of a global tensor (Sec. 3) ...
+    ((3, 8, 20, 12), (1, 2, 3, 2), (1, 1, 1, 1)),           # ... and gather
 ]
 
 
