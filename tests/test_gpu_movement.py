@@ -92,6 +92,48 @@ def test_halo_adj_parity_and_adjoint_test(case, dtype):
         assert abs(Fx_y - prim.inner([from_cl(t) for t in gx], y)) <= 1e-9 * np.sqrt(Fx2 * y2)
 
 
+def _random_halo_cases(count):
+    """Seeded random sliding-kernel geometries: rank, partition, kernel, stride, padding, dilation, ragged shapes."""
+    rng = np.random.default_rng(123)
+    cases = []
+    while len(cases) < count:
+        D = int(rng.integers(1, 4))
+        k = tuple(int(rng.integers(1, 6)) for _ in range(D))
+        dil = tuple(int(rng.choice([1, 1, 2])) for _ in range(D))
+        s = tuple(int(rng.integers(1, 4)) for _ in range(D))
+        P = tuple(int(rng.integers(1, 5)) for _ in range(D))
+        p = tuple(int(rng.integers(0, (k[d] - 1) * dil[d] + 1)) for d in range(D))
+        n = tuple(int(rng.integers(P[d] * max(s[d], (k[d] - 1) * dil[d] + 1), P[d] * max(s[d], (k[d] - 1) * dil[d] + 1) + 20))
+                  for d in range(D))
+        try:
+            geo.Partition.for_kernel(n, P, k, s, p, dil)
+        except Exception:
+            continue
+        cases.append((f"rnd{len(cases)}", D, int(rng.integers(1, 4)), int(rng.choice([1, 3, 4, 8])), n, P, k, s, p, dil))
+    return cases
+
+
+@pytest.mark.parametrize("case", _random_halo_cases(24), ids=lambda c: c[0])
+def test_halo_random_geometries(case):
+    """H bit-exact and H* to 1e-5 on random geometries (fp32), against the oracle's nested exchange."""
+    require_gpu()
+    part, plan = _setup(case, torch.float32)
+    name, D, n_b, n_c, n = case[:5]
+    r = syn.streams(21, 2)
+    xg = syn.normal(r[0], (n_b, n_c) + tuple(n))
+    want = prim.halo_exchange(prim.scatter_bulk(xg, part, fill=np.float32(7.5)), part)
+    bufs = [to_cl(b) for b in prim.scatter_bulk(xg, part, fill=np.float32(-3.25))]
+    dd.distdl_halo_fwd(plan, bufs)
+    y = [syn.normal(r[1], (n_b, n_c) + part.buf_shape(w)) for w in range(part.n_workers)]
+    want_adj = prim.halo_exchange_adjoint([t.astype(np.float64) for t in y], part)
+    gy = [to_cl(t) for t in y]
+    dd.distdl_halo_adj(plan, gy)
+    torch.cuda.synchronize()
+    for w in range(part.n_workers):
+        assert np.array_equal(from_cl(bufs[w]), want[w]), f"{name} H worker {w}"
+        assert_close(from_cl(gy[w]), want_adj[w], TOL32, f"{name} H* worker {w}")
+
+
 def test_halo_adj_multiplicities_are_exact_integers():
     require_gpu()
     case = HALO_CASES[3]
