@@ -22,6 +22,12 @@
  *  - Device pointers must be aligned to the element size; 16-byte alignment
  *    (what any allocator gives) enables the vectorised kernels.
  *  - One plan may be used from one host thread at a time.
+ *  - A plan keeps device copies of the pointer arrays it has been called with
+ *    (the last eight per argument, per stream) and whatever scratch it needs;
+ *    the first call with new arrays, on a new stream or with a larger problem
+ *    therefore copies a table or allocates, later calls do neither.  A call
+ *    that has been made once on a stream can be recorded into a HIP graph on
+ *    that stream (no allocation, no host-to-device copy, no memset).
  *
  * Memory layout of sliding-kernel tensors: CHANNELS-LAST.  The paper fixes
  * only the logical shape n_b x n_c x m_0 x ... x m_{D-1} (Sec. 4 "Sparse
