@@ -11,7 +11,7 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libdistdl.so")
 if not os.path.exists(_LIB_PATH):
-    raise ImportError(f"{_LIB_PATH} is missing: build it with `python -m paper_2006_03108_amd.build`")
+    raise ImportError(f"{_LIB_PATH} is missing: build it with `python paper_2006_03108_amd/build.py`")
 lib = C.CDLL(_LIB_PATH)
 
 DISTDL_F32, DISTDL_BF16 = 0, 1
