@@ -763,7 +763,7 @@ def main():
             print(f"bench.py: graph capture failed: {e}", file=sys.stderr)
             return None
 
-    if args.workload in ("cfg2", "cfg4"):
+    if args.workload in ("cfg2", "cfg3", "cfg3-bf16", "cfg4"):
         line["ms_per_step_graph"] = graph_step_ms(wl, args.steps)
     if args.workload == "cfg5" and not args.no_movement:
         # the other half of the metric: the movement primitives on their own (H, H* on this geometry, B, R and
@@ -790,7 +790,7 @@ def main():
                                  ("cfg4", lambda: SmallCnnWorkload(), 50)):
             w, rep = side_run(make, steps)
             rep["kernel_launches_per_step"] = sum(k["launches"] for k in rep["kernels"].values()) / steps
-            if tag in ("cfg2", "cfg4"):
+            if tag in ("cfg2", "cfg3", "cfg3-bf16", "cfg4"):
                 rep["ms_per_step_graph"] = graph_step_ms(w, steps)
             line["other_configs"][tag] = rep
             del w

@@ -3,6 +3,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <cstdarg>
 #include <cstdint>
 #include <cstdio>
@@ -22,6 +23,21 @@ int set_error(int code, const char* fmt, ...);
   } while (0)
 
 inline size_t dtype_size(distdl_dtype t) { return t == DISTDL_F32 ? 4 : 2; }
+
+// Lets kernel `Kernel` be launched with more than 64 KB of dynamic LDS (up to the 160 KB of a compute unit).
+// The attribute is set once per kernel and device: the call is not cheap, and a launch path that made it every
+// time would pay for it on each step.
+template <auto Kernel>
+inline int allow_large_lds() {
+  static std::atomic<uint64_t> done{0};  // one bit per device
+  int dev = 0;
+  DISTDL_HIP_TRY(hipGetDevice(&dev));
+  const uint64_t bit = uint64_t(1) << (dev & 63);
+  if (done.load(std::memory_order_acquire) & bit) return DISTDL_OK;
+  DISTDL_HIP_TRY(hipFuncSetAttribute((const void*)Kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
+  done.fetch_or(bit, std::memory_order_release);
+  return DISTDL_OK;
+}
 
 // ---- exact unsigned division by a runtime constant ------------------------
 // Granlund & Montgomery, "Division by invariant integers using

@@ -1062,8 +1062,7 @@ static int launch_corr(distdl_plan* p, CorrArgs a, const void* w, float* wscratc
 #define DISTDL_LAUNCH_CORR_T(MT_, PA_, PB_, NT_, BF_)                                                                \
   do {                                                                                                               \
     if (lds > 64 * 1024)                                                                                             \
-      DISTDL_HIP_TRY(hipFuncSetAttribute((const void*)corr_mfma_kernel<MT_, PA_, PB_, NT_, BF_>,                     \
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, lds));                          \
+      if (int rc_ = allow_large_lds<corr_mfma_kernel<MT_, PA_, PB_, NT_, BF_>>()) return rc_;                        \
     hipLaunchKernelGGL((corr_mfma_kernel<MT_, PA_, PB_, NT_, BF_>), dim3((unsigned)blocks), dim3(256), lds, st,      \
                        p->d_workers, in_tab, out_tab, a);                                                            \
   } while (0)
@@ -1248,8 +1247,7 @@ int conv_wgrad_mfma(distdl_plan* p, float* partial, hipStream_t st) {
 #define DISTDL_LAUNCH_TAPS_T(TW_, S2_, BF_)                                                                         \
   do {                                                                                                              \
     if (rlds > 64 * 1024)                                                                                           \
-      DISTDL_HIP_TRY(hipFuncSetAttribute((const void*)wgrad_taps_kernel<TW_, S2_, BF_>,                             \
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, rlds));                        \
+      if (int rc_ = allow_large_lds<wgrad_taps_kernel<TW_, S2_, BF_>>()) return rc_;                                \
     hipLaunchKernelGGL((wgrad_taps_kernel<TW_, S2_, BF_>), rgrid, rblock, rlds, st, p->d_workers, p->tab_x.dev,     \
                        p->tab_dy.dev, partial, a);                                                                  \
   } while (0)

@@ -10,8 +10,8 @@
 //   A "K-contiguous":  A[m][k] at a[m*lda + k];   "M-contiguous": a[k*lda + m]
 //   B "K-contiguous":  B[k][n] at b[n*ldb + k];   "N-contiguous": b[k*ldb + n]
 // Tiles are 64 x 64 or 128 x 128 per workgroup (4 waves, 1 or 2 x 2 MFMA tiles of 32 x 32 each), staged through LDS with
-// 16-byte buffer loads (rows beyond the matrix fail the range check and read as zero), double
-// buffered: one barrier per stage.
+// 16-byte buffer loads (rows beyond the matrix fail the range check and read as zero) that run one or two
+// stages ahead in registers; LDS is double buffered: one barrier per stage.
 //
 // fp32: v_mfma_f32_32x32x2_f32, A lane l holds A[i = l%32][k = l/32]; a 16-byte LDS read gives a lane
 //       4 consecutive k, used by 4 MFMAs whose k-pairs are (j, 4+j) -- the same pairing on both operands.
@@ -19,6 +19,7 @@
 // D register v of lane l is D[i = 8*(v/4) + 4*(l/32) + v%4][j = l%32] for both.
 #include <algorithm>
 #include <cstring>
+#include <type_traits>
 
 #include "common.h"
 #include "gemm_mfma.h"
@@ -43,19 +44,34 @@ __device__ inline uint32_t f32_to_bf16_rne(float f) {
   return u >> 16;
 }
 
+// Calls f(std::integral_constant<int, 0>) ... f(std::integral_constant<int, N - 1>): a loop whose index is a
+// compile-time constant in the body (register arrays indexed by it stay in registers).
+template <int N, int I = 0, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (I < N) {
+    f(std::integral_constant<int, I>{});
+    static_for<N, I + 1>(f);
+  }
+}
+
 // BF16 = false: T is float, BK = 32 floats per stage.  BF16 = true: T is bf16 bits, BK = 64 per stage.
 // TM x TN: 32 x 32 MFMA tiles per wave; the workgroup tile is 64*TM x 64*TN (4 waves, 2 x 2).
 // Row pitch in LDS is BK + 16 bytes for the K-contiguous layout, tile extent + 16 (bf16: 32) bytes for the other.
 //
-// nsplit > 1 (grid.y): the K stages of every segment are dealt to nsplit workgroups per tile, each of which
+// D: stages the global loads run ahead of the multiplication (a ring of D register sets).
+//
+// nsplit > 1 (grid.y): the K stages of all segments, taken as one sequence, are cut into nsplit contiguous runs,
+// one workgroup per tile and run, each of which
 // writes its fp32 partial tile to `partial` ([block][split][M][N]); gemm_reduce_kernel then sums the splits
 // in ascending order, adds the bias and rounds.  This is the sum-reduce R of the layer left un-fused: with a
 // small batch a launch has too few tiles to fill the chip, and the splits supply the missing workgroups.
-template <bool BF16, bool A_KC, bool B_KC, int TM, int TN>
+template <bool BF16, bool A_KC, bool B_KC, int TM, int TN, int D>
 __global__ __launch_bounds__(256) void gemm_mfma_kernel(const GemmBlock* __restrict__ blocks, float* __restrict__ partial,
                                                         int64_t partial_stride) {
   constexpr int ES = BF16 ? 2 : 4;             // element size
-  constexpr int BK = BF16 ? 64 : 32;           // k per stage
+  constexpr int GK = BF16 ? 16 : 8;            // k per group: one bf16 MFMA, or four fp32 ones, per tile
+  constexpr int KG = 4;                        // k groups per stage
+  constexpr int BK = GK * KG;                  // k per stage
   constexpr int VE = 16 / ES;                  // elements per 16-byte piece
   constexpr int TILE_M = 64 * TM, TILE_N = 64 * TN;
   constexpr int PITCH_KC = BK * ES + 16;       // bytes per tile row, K-contiguous staging [row][k]
@@ -86,32 +102,63 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(const GemmBlock* __restr
     for (int j = 0; j < TN; ++j)
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
+  // The K stages of all segments form one sequence; this workgroup multiplies the stages [g_first, g_first + n)
+  // of it.  Loads run D stages ahead of the multiplication through a ring of D register sets, so that a
+  // stage's memory latency is spread over D stages of arithmetic.
+  int total = 0;
+  for (int s = 0; s < gb.nseg; ++s) total += (gb.seg[s].K + BK - 1) / BK;
+  const int g_first = (int)((int64_t)total * blockIdx.y / gridDim.y);
+  const int n = (int)((int64_t)total * (blockIdx.y + 1) / gridDim.y) - g_first;
+
   // piece -> (row or k line, 16-byte column) of this thread, fixed
   //   K-contiguous: rows x (BK/VE) pieces per row; transposed: BK lines x (rows/VE) pieces per line
-  u32x4 ra[PA], rb[PB];
+  u32x4 ra[D][PA], rb[D][PB];
   uint32_t a_goff[PA], b_goff[PB], a_loff[PA], b_loff[PB];
   int a_k[PA], b_k[PB];  // k of the piece's first element (to cut the K tail)
+#pragma unroll
+  for (int i = 0; i < PA; ++i) {
+    const int piece = tid + i * 256;
+    if (A_KC) {
+      a_loff[i] = (piece / (BK / VE)) * PITCH_KC + (piece % (BK / VE)) * 16;
+      a_k[i] = (piece % (BK / VE)) * VE;
+    } else {
+      a_loff[i] = (piece / (TILE_M / VE)) * PITCH_TA + (piece % (TILE_M / VE)) * 16;
+      a_k[i] = piece / (TILE_M / VE);
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < PB; ++i) {
+    const int piece = tid + i * 256;
+    if (B_KC) {
+      b_loff[i] = (piece / (BK / VE)) * PITCH_KC + (piece % (BK / VE)) * 16;
+      b_k[i] = (piece % (BK / VE)) * VE;
+    } else {
+      b_loff[i] = (piece / (TILE_N / VE)) * PITCH_TB + (piece % (TILE_N / VE)) * 16;
+      b_k[i] = piece / (TILE_N / VE);
+    }
+  }
 
-  for (int s = 0; s < gb.nseg; ++s) {
-    const GemmSeg& sg = gb.seg[s];
-    const int K = sg.K;
+  // load cursor: segment, stage within it, and what depends on the segment
+  int ls = 0, lin = g_first, l_nst = 0, l_K = 0;
+  uint32_t l_lda = 0, l_ldb = 0;
+  __amdgpu_buffer_rsrc_t ra_rs = gemm_rsrc(nullptr, 0), rb_rs = gemm_rsrc(nullptr, 0);
+  auto enter_segment = [&]() __attribute__((always_inline)) {
+    const GemmSeg& sg = gb.seg[ls];
+    l_K = sg.K;
+    l_nst = (sg.K + BK - 1) / BK;
+    l_lda = (uint32_t)sg.lda;
+    l_ldb = (uint32_t)sg.ldb;
     // resources cover exactly the operand: rows beyond M / N (or k lines beyond K) read as zero
-    const uint32_t a_bytes = (uint32_t)(A_KC ? gb.M : K) * sg.lda * ES;
-    const uint32_t b_bytes = (uint32_t)(B_KC ? gb.N : K) * sg.ldb * ES;
-    const __amdgpu_buffer_rsrc_t ra_rs = gemm_rsrc(sg.a, a_bytes), rb_rs = gemm_rsrc(sg.b, b_bytes);
+    ra_rs = gemm_rsrc(sg.a, (uint32_t)(A_KC ? gb.M : sg.K) * sg.lda * ES);
+    rb_rs = gemm_rsrc(sg.b, (uint32_t)(B_KC ? gb.N : sg.K) * sg.ldb * ES);
 #pragma unroll
     for (int i = 0; i < PA; ++i) {
       const int piece = tid + i * 256;
       if (A_KC) {
-        const int row = piece / (BK / VE), kq = piece % (BK / VE);
-        a_goff[i] = ((uint32_t)(m0 + row) * sg.lda + kq * VE) * ES;
-        a_loff[i] = row * PITCH_KC + kq * 16;
-        a_k[i] = kq * VE;
+        a_goff[i] = ((uint32_t)(m0 + piece / (BK / VE)) * l_lda + a_k[i]) * ES;
       } else {
-        const int kl = piece / (TILE_M / VE), mq = piece % (TILE_M / VE);
-        a_goff[i] = ((uint32_t)kl * sg.lda + m0 + mq * VE) * ES;
-        a_loff[i] = kl * PITCH_TA + mq * 16;
-        a_k[i] = kl;
+        const int mq = piece % (TILE_M / VE);
+        a_goff[i] = ((uint32_t)a_k[i] * l_lda + m0 + mq * VE) * ES;
         if (m0 + mq * VE >= gb.M) a_goff[i] = kGemmOob;  // columns beyond M (whole pieces: M % VE == 0)
       }
     }
@@ -119,49 +166,53 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(const GemmBlock* __restr
     for (int i = 0; i < PB; ++i) {
       const int piece = tid + i * 256;
       if (B_KC) {
-        const int row = piece / (BK / VE), kq = piece % (BK / VE);
-        b_goff[i] = ((uint32_t)(n0 + row) * sg.ldb + kq * VE) * ES;
-        b_loff[i] = row * PITCH_KC + kq * 16;
-        b_k[i] = kq * VE;
+        b_goff[i] = ((uint32_t)(n0 + piece / (BK / VE)) * l_ldb + b_k[i]) * ES;
       } else {
-        const int kl = piece / (TILE_N / VE), nq = piece % (TILE_N / VE);
-        b_goff[i] = ((uint32_t)kl * sg.ldb + n0 + nq * VE) * ES;
-        b_loff[i] = kl * PITCH_TB + nq * 16;
-        b_k[i] = kl;
+        const int nq = piece % (TILE_N / VE);
+        b_goff[i] = ((uint32_t)b_k[i] * l_ldb + n0 + nq * VE) * ES;
         if (n0 + nq * VE >= gb.N) b_goff[i] = kGemmOob;
       }
     }
-    auto load = [&](int k0) {
-      const uint32_t a_base = (uint32_t)k0 * (A_KC ? 1u : sg.lda) * ES;
-      const uint32_t b_base = (uint32_t)k0 * (B_KC ? 1u : sg.ldb) * ES;
-      // K tail: pieces are whole (K % VE == 0 for K-contiguous operands), lines beyond K fail the range check
+  };
+  // Loads the next stage of the sequence into ring slot `slot`.  With `valid` false (past the last stage) the
+  // loads are still issued, with offsets that fail the range check: every path through the loop then has the
+  // same number of loads in flight, which lets the compiler wait for exactly the oldest stage instead of all.
+  auto load = [&](auto slot_c, bool valid) __attribute__((always_inline)) {
+    constexpr int slot = decltype(slot_c)::value;
+    int k0 = 0;
+    if (valid) {  // wave-uniform
+      while (lin >= l_nst) {
+        lin -= l_nst;
+        ++ls;
+        enter_segment();
+      }
+      k0 = lin * BK;
+      ++lin;
+    }
+    const uint32_t a_base = (uint32_t)k0 * (A_KC ? 1u : l_lda) * ES;
+    const uint32_t b_base = (uint32_t)k0 * (B_KC ? 1u : l_ldb) * ES;
+    // K tail: pieces are whole (K % VE == 0 for K-contiguous operands), lines beyond K fail the range check
 #pragma unroll
-      for (int i = 0; i < PA; ++i)
-        ra[i] = __builtin_amdgcn_raw_buffer_load_b128(ra_rs, (A_KC && k0 + a_k[i] >= K) ? kGemmOob : a_goff[i], a_base, 0);
+    for (int i = 0; i < PA; ++i)
+      ra[slot][i] = __builtin_amdgcn_raw_buffer_load_b128(
+          ra_rs, (!valid || (A_KC && k0 + a_k[i] >= l_K)) ? kGemmOob : a_goff[i], a_base, 0);
 #pragma unroll
-      for (int i = 0; i < PB; ++i)
-        rb[i] = __builtin_amdgcn_raw_buffer_load_b128(rb_rs, (B_KC && k0 + b_k[i] >= K) ? kGemmOob : b_goff[i], b_base, 0);
-    };
-    auto stash = [&](int buf) {
-      char* sa = smem + buf * (A_BYTES + B_BYTES);
-      char* sb = sa + A_BYTES;
+    for (int i = 0; i < PB; ++i)
+      rb[slot][i] = __builtin_amdgcn_raw_buffer_load_b128(
+          rb_rs, (!valid || (B_KC && k0 + b_k[i] >= l_K)) ? kGemmOob : b_goff[i], b_base, 0);
+  };
+  auto stash = [&](int buf, auto slot_c) __attribute__((always_inline)) {
+    constexpr int slot = decltype(slot_c)::value;
+    char* sa = smem + buf * (A_BYTES + B_BYTES);
+    char* sb = sa + A_BYTES;
 #pragma unroll
-      for (int i = 0; i < PA; ++i) *(u32x4*)(sa + a_loff[i]) = ra[i];
+    for (int i = 0; i < PA; ++i) *(u32x4*)(sa + a_loff[i]) = ra[slot][i];
 #pragma unroll
-      for (int i = 0; i < PB; ++i) *(u32x4*)(sb + b_loff[i]) = rb[i];
-    };
-    const int nstage_all = (K + BK - 1) / BK;
-    // this workgroup's share of the segment's stages
-    const int st_first = (int)((int64_t)nstage_all * blockIdx.y / gridDim.y);
-    const int nstage = (int)((int64_t)nstage_all * (blockIdx.y + 1) / gridDim.y) - st_first;
-    if (nstage == 0) continue;
-    load(st_first * BK);
-    __syncthreads();  // previous segment's last stage fully consumed
-    stash(0);
-    __syncthreads();
-    for (int st = 0; st < nstage; ++st) {
-      if (st + 1 < nstage) load((st_first + st + 1) * BK);
-      const char* sa = smem + (st & 1) * (A_BYTES + B_BYTES);
+    for (int i = 0; i < PB; ++i) *(u32x4*)(sb + b_loff[i]) = rb[slot][i];
+  };
+  // multiplies the stage held in LDS buffer `buf`
+  auto multiply = [&](int buf) __attribute__((always_inline)) {
+      const char* sa = smem + buf * (A_BYTES + B_BYTES);
       const char* sb = sa + A_BYTES;
       // The LDS reads of k group g + 1 are issued before the MFMAs of group g; the scheduling barriers
       // pin that order (left alone, the compiler sinks the reads to their first use and the LDS latency
@@ -200,22 +251,18 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(const GemmBlock* __restr
               for (int in = 0; in < TN; ++in)
                 acc[im][in] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[im][j], bv[in][j], acc[im][in], 0, 0, 0);
         };
-        float a0[TM][4], b0[TN][4], a1[TM][4], b1[TN][4];
-        static_assert(BK == 32, "four k groups of 8 per stage");
-        rd(0, a0, b0);
-        rd(8, a1, b1);
-        __builtin_amdgcn_sched_barrier(0);
-        mm(a0, b0);
-        __builtin_amdgcn_sched_barrier(0);
-        rd(16, a0, b0);
-        __builtin_amdgcn_sched_barrier(0);
-        mm(a1, b1);
-        __builtin_amdgcn_sched_barrier(0);
-        rd(24, a1, b1);
-        __builtin_amdgcn_sched_barrier(0);
-        mm(a0, b0);
-        __builtin_amdgcn_sched_barrier(0);
-        mm(a1, b1);
+        float av[2][TM][4], bv[2][TN][4];
+        rd(0, av[0], bv[0]);
+        rd(GK, av[1], bv[1]);
+        static_for<KG>([&](auto g) __attribute__((always_inline)) {
+          constexpr int gv = decltype(g)::value;
+          __builtin_amdgcn_sched_barrier(0);
+          mm(av[gv & 1], bv[gv & 1]);
+          if constexpr (gv + 2 < KG) {
+            __builtin_amdgcn_sched_barrier(0);
+            rd((gv + 2) * GK, av[gv & 1], bv[gv & 1]);
+          }
+        });
       } else {
         // An operand staged [k][row] (rows contiguous) is read with ds_read_b64_tr_b16.  Measured lane layout of
         // that load: in every group of 16 lanes, lane 4 * b + a receives, as element v, the a-th 16-bit element of
@@ -255,26 +302,42 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(const GemmBlock* __restr
             for (int in = 0; in < TN; ++in)
               acc[im][in] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[im].v, bv[in].v, acc[im][in], 0, 0, 0);
         };
-        Frag a0[TM], b0[TN], a1[TM], b1[TN];
-        static_assert(BK == 64 || !BF16, "four k groups of 16 per stage");
-        rd(0, a0, b0);
-        rd(16, a1, b1);
-        __builtin_amdgcn_sched_barrier(0);
-        mm(a0, b0);
-        __builtin_amdgcn_sched_barrier(0);
-        rd(32, a0, b0);
-        __builtin_amdgcn_sched_barrier(0);
-        mm(a1, b1);
-        __builtin_amdgcn_sched_barrier(0);
-        rd(48, a1, b1);
-        __builtin_amdgcn_sched_barrier(0);
-        mm(a0, b0);
-        __builtin_amdgcn_sched_barrier(0);
-        mm(a1, b1);
+        Frag av[2][TM], bv[2][TN];
+        rd(0, av[0], bv[0]);
+        rd(GK, av[1], bv[1]);
+        static_for<KG>([&](auto g) __attribute__((always_inline)) {
+          constexpr int gv = decltype(g)::value;
+          __builtin_amdgcn_sched_barrier(0);
+          mm(av[gv & 1], bv[gv & 1]);
+          if constexpr (gv + 2 < KG) {
+            __builtin_amdgcn_sched_barrier(0);
+            rd((gv + 2) * GK, av[gv & 1], bv[gv & 1]);
+          }
+        });
       }
-      if (st + 1 < nstage) stash((st + 1) & 1);
+  };
+
+  if (n > 0) {
+    enter_segment();  // segment 0; the first load walks on to the segment that holds stage g_first
+    static_for<D>([&](auto d) __attribute__((always_inline)) { load(d, decltype(d)::value < n); });
+    stash(0, std::integral_constant<int, 0>{});
+    load(std::integral_constant<int, 0>{}, D < n);
+    __syncthreads();
+    // one stage: multiply it, move stage st + 1 into the other buffer (past the end: zeros nobody reads) and
+    // refill that stage's ring slot
+    auto stage = [&](int st, auto d) __attribute__((always_inline)) {
+      constexpr int next = (decltype(d)::value + 1) % D;
+      multiply(st & 1);
+      stash((st + 1) & 1, std::integral_constant<int, next>{});
+      load(std::integral_constant<int, next>{}, st + 1 + D < n);
       __syncthreads();
-    }
+    };
+    int st0 = 0;
+    for (; st0 + D <= n; st0 += D)  // whole turns of the ring: no branches, so the waits stay exact
+      static_for<D>([&](auto d) __attribute__((always_inline)) { stage(st0 + decltype(d)::value, d); });
+    static_for<D - 1>([&](auto d) __attribute__((always_inline)) {
+      if (st0 + decltype(d)::value < n) stage(st0 + decltype(d)::value, d);
+    });
   }
 
   // epilogue: D register v of lane (h, ml) of MFMA tile (im, in) is
@@ -381,6 +444,7 @@ __global__ __launch_bounds__(256) void colsum_kernel(const ColsumBlock* __restri
 bool gemm_mfma_usable(const std::vector<GemmBlock>& blocks, bool bf16, bool a_kc, bool b_kc) {
   const int ve = bf16 ? 8 : 4;
   const size_t es = bf16 ? 2 : 4;
+  if (!a_kc && b_kc) return false;  // not a layout of the affine layer: not built
   for (const GemmBlock& b : blocks) {
     if (b.nseg < 1 || b.nseg > kGemmMaxSeg) return false;
     if ((uintptr_t)b.c % es) return false;
@@ -398,22 +462,33 @@ bool gemm_mfma_usable(const std::vector<GemmBlock>& blocks, bool bf16, bool a_kc
   return true;
 }
 
-// 128 x 128 workgroup tiles (2 x 2 MFMA tiles per wave) when every block is at least that large.
-static bool gemm_big_tiles(const std::vector<GemmBlock>& blocks) {
+static int64_t count_tiles(const std::vector<GemmBlock>& blocks, int t) {
+  int64_t tiles = 0;
+  for (const GemmBlock& b : blocks) tiles += (int64_t)((b.M + t - 1) / t) * ((b.N + t - 1) / t);
+  return tiles;
+}
+
+// Workgroup tile: 128 x 128 (2 x 2 MFMA tiles per wave) when every block is at least that large.  Exception: a
+// bf16 launch whose 128-tiles would fill at most half the chip but whose 64-tiles fill most of it (the small-batch
+// forward and data-gradient products) takes 64 x 64 tiles over the whole K range: measured at batch 256 with
+// 4096 x 4096 features, one such launch takes 27 us against 34 us for 128-tiles with K splits and a reduction.
+static int gemm_tile(const std::vector<GemmBlock>& blocks, bool bf16) {
   for (const GemmBlock& b : blocks)
-    if (b.M < 128 || b.N < 128) return false;
-  return !blocks.empty();
+    if (b.M < 128 || b.N < 128) return 64;
+  if (blocks.empty()) return 64;
+  if (bf16 && count_tiles(blocks, 128) <= 128 && count_tiles(blocks, 64) >= 192) return 64;
+  return 128;
 }
 
 // Number of K splits for a launch: enough workgroups for about two (large tiles) or four per compute unit,
 // every split at least four stages long, at most 8.
 int gemm_mfma_splits(const std::vector<GemmBlock>& blocks, bool bf16) {
   const int bk = bf16 ? 64 : 32;
-  const int t = gemm_big_tiles(blocks) ? 128 : 64;
-  int64_t tiles = 0, macs = 0;
+  const int t = gemm_tile(blocks, bf16);
+  const int64_t tiles = count_tiles(blocks, t);
+  int64_t macs = 0;
   int min_stages = INT32_MAX;
   for (const GemmBlock& b : blocks) {
-    tiles += (int64_t)((b.M + t - 1) / t) * ((b.N + t - 1) / t);
     int stages = 0;
     for (int s = 0; s < b.nseg; ++s) {
       stages += (b.seg[s].K + bk - 1) / bk;
@@ -422,6 +497,7 @@ int gemm_mfma_splits(const std::vector<GemmBlock>& blocks, bool bf16) {
     min_stages = std::min(min_stages, stages);
     if (b.N % 4) return 1;  // the reduction works on groups of 4 elements of a row
   }
+  if (bf16 && t == 64 && tiles >= 192) return 1;  // bound by LDS traffic, which splits do not reduce
   const int64_t target = t == 128 ? 512 : 1024;
   if (tiles == 0 || tiles >= target * 3 / 4) return 1;
   if (macs < (int64_t(1) << 28)) return 1;  // a launch this small is latency-bound either way: no second kernel
@@ -437,23 +513,23 @@ size_t gemm_mfma_partial_floats(const std::vector<GemmBlock>& blocks, int nsplit
   return (size_t)mx * nsplit * blocks.size();
 }
 
+// T: workgroup tile / 64; the 64-tiles load two stages ahead (one workgroup per compute unit has nothing else
+// to cover a stage's latency with), the 128-tiles one.
 template <bool BF16, bool A_KC, bool B_KC, int T>
 static int launch_gemm_variant(dim3 grid, const GemmBlock* d_blocks, float* partial, int64_t max_mn, hipStream_t st) {
-  constexpr int ES = BF16 ? 2 : 4, BK = BF16 ? 64 : 32, TILE = 64 * T;
+  constexpr int ES = BF16 ? 2 : 4, BK = BF16 ? 64 : 32, TILE = 64 * T, D = T == 1 ? 2 : 1;
   constexpr int A_BYTES = A_KC ? TILE * (BK * ES + 16) : BK * (TILE * ES + (BF16 ? 32 : 16));
   constexpr int B_BYTES = B_KC ? TILE * (BK * ES + 16) : BK * (TILE * ES + (BF16 ? 32 : 16));
   constexpr int LDS = 2 * (A_BYTES + B_BYTES);
   if (LDS > 64 * 1024)
-    DISTDL_HIP_TRY(hipFuncSetAttribute((const void*)gemm_mfma_kernel<BF16, A_KC, B_KC, T, T>,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, LDS));
-  hipLaunchKernelGGL((gemm_mfma_kernel<BF16, A_KC, B_KC, T, T>), grid, dim3(256), LDS, st, d_blocks, partial, max_mn);
+    if (int rc = allow_large_lds<gemm_mfma_kernel<BF16, A_KC, B_KC, T, T, D>>()) return rc;
+  hipLaunchKernelGGL((gemm_mfma_kernel<BF16, A_KC, B_KC, T, T, D>), grid, dim3(256), LDS, st, d_blocks, partial, max_mn);
   return DISTDL_OK;
 }
 
 int launch_gemm_mfma(const GemmBlock* d_blocks, const std::vector<GemmBlock>& blocks, bool bf16, bool a_kc, bool b_kc,
                      int nsplit, float* partial, const char* name, hipStream_t st) {
-  const bool big = gemm_big_tiles(blocks);
-  const int t = big ? 128 : 64;
+  const int t = gemm_tile(blocks, bf16);
   int tiles = 0;
   int64_t max_mn = 0;
   for (const GemmBlock& b : blocks) {
@@ -462,21 +538,21 @@ int launch_gemm_mfma(const GemmBlock* d_blocks, const std::vector<GemmBlock>& bl
   }
   tiles = (tiles + 7) / 8 * 8;
   if (nsplit > 1 && !partial) return set_error(DISTDL_ERR_INVALID_ARG, "gemm: split launch without a partial buffer");
+  if (!a_kc && b_kc) return set_error(DISTDL_ERR_UNSUPPORTED, "gemm: operand layout not built");
   dim3 grid((unsigned)tiles, (unsigned)std::max(nsplit, 1), (unsigned)blocks.size()), block(256);
   ProfScope prof(name, st);
   int rc;
 #define DISTDL_GEMM(BF_, A_, B_)                                                                \
-  rc = big ? launch_gemm_variant<BF_, A_, B_, 2>(grid, d_blocks, partial, max_mn, st)           \
-           : launch_gemm_variant<BF_, A_, B_, 1>(grid, d_blocks, partial, max_mn, st)
+  rc = t == 128 ? launch_gemm_variant<BF_, A_, B_, 2>(grid, d_blocks, partial, max_mn, st)      \
+                : launch_gemm_variant<BF_, A_, B_, 1>(grid, d_blocks, partial, max_mn, st)
+  // the three operand layouts of the affine layer: forward (K, K), data gradient (K, N), weight gradient (M, N)
   if (!bf16) {
     if (a_kc && b_kc) DISTDL_GEMM(false, true, true);
     else if (a_kc) DISTDL_GEMM(false, true, false);
-    else if (b_kc) DISTDL_GEMM(false, false, true);
     else DISTDL_GEMM(false, false, false);
   } else {
     if (a_kc && b_kc) DISTDL_GEMM(true, true, true);
     else if (a_kc) DISTDL_GEMM(true, true, false);
-    else if (b_kc) DISTDL_GEMM(true, false, true);
     else DISTDL_GEMM(true, false, false);
   }
 #undef DISTDL_GEMM
