@@ -251,6 +251,8 @@ AFFINE_CASES = [
     (256, 4096, 4096, 2, 2),       # cfg3
     (256, 400, 120, 2, 2), (256, 120, 84, 2, 2), (256, 84, 10, 2, 2),   # cfg4 / App. C table
     (7, 13, 9, 3, 2), (5, 33, 17, 1, 1), (64, 256, 192, 1, 4), (33, 130, 70, 4, 1),
+    (128, 3000, 1024, 1, 3),       # K splits that straddle the column workers' segments, ragged last K stage
+    (200, 2064, 3096, 1, 2),       # small batch, wide layer: ragged tiles in M, N and K
 ]
 
 
