@@ -611,13 +611,17 @@ __global__ __launch_bounds__(256, 2) void wgrad_lds_kernel(const WorkerDev* __re
 // vector instructions: ring slots advance in scalar registers, out-of-range rows are switched off through
 // the scalar offset of the buffer load, and every LDS read of the inner loop is an immediate offset.
 // A wave with TW - 1 taps repeats its last tap (never stored), so all waves stay in step.
+// SH = 1 (fp32 MFMAs, T = 4 * (TW - 1) + 1 taps, e.g. 3 x 3 and 5 x 5 kernels): every wave owns TW - 1 taps and the
+// last tap is shared, each wave multiplying a quarter of a step's 32 positions for it; the four partial tiles are
+// summed through LDS, in wave order, when the workgroup is done.  That is 16 * (TW - 1) + 4 MFMAs per wave and
+// step instead of 16 * TW.
 // MODE 0: fp32 tensors.  MODE 1: bf16 tensors widened to fp32 while they are staged.  MODE 2: bf16 tensors staged as
 // they are (a 16-byte piece holds 8 channels) and multiplied on v_mfma_f32_32x32x16_bf16, whose operands need 8
 // consecutive *positions* per lane: ds_read_b64_tr_b16 gathers them from the channels-last rows.  Measured lane
 // layout of that load: in every group of 16 lanes, lane 4 * b + a receives, as element v, the a-th 16-bit element
 // of the 8 bytes addressed by lane b + 4 * v of the group.  With lane s of a group addressing channels
 // 4 * (s % 4) ... + 3 of position s / 4, lane t of the group thus receives channel t of four consecutive positions.
-template <int TW, int S2, int MODE>
+template <int TW, int S2, int MODE, int SH>
 __global__ __launch_bounds__(256, 2) void wgrad_taps_kernel(const WorkerDev* __restrict__ workers, void* const* x_bufs,
                                                             void* const* dy_bufs, float* __restrict__ partial,
                                                             WgradArgs a) {
@@ -640,14 +644,16 @@ __global__ __launch_bounds__(256, 2) void wgrad_taps_kernel(const WorkerDev* __r
   char* const ldsb = (char*)wt_lds;
   const uint32_t ys_base = (uint32_t)ring * pitch;  // two dy segments of 4 KiB behind the ring
 
+  static_assert(SH == 0 || (SH == 1 && MODE != 2), "the shared tap is split by position pairs of fp32 MFMAs");
+  constexpr int NOWN = TW - SH;  // accumulators of taps this wave owns; the rest hold its part of the shared tap
   const int T = a.k[1] * a.k[2];
   const int tbase = T >> 2, trem = T & 3;
-  const int tap_first = wave * tbase + min(wave, trem);
-  const int ntw = tbase + (wave < trem ? 1 : 0);
+  const int tap_first = SH ? wave * NOWN : wave * tbase + min(wave, trem);
+  const int ntw = SH ? NOWN : tbase + (wave < trem ? 1 : 0);
   int tap_t1[TW], tap_t2[TW];
 #pragma unroll
   for (int i = 0; i < TW; ++i) {
-    const int j = tap_first + min(i, ntw - 1);
+    const int j = i < NOWN ? tap_first + min(i, ntw - 1) : T - 1;
     tap_t1[i] = j / a.k[2];
     tap_t2[i] = j - tap_t1[i] * a.k[2];
   }
@@ -787,11 +793,21 @@ __global__ __launch_bounds__(256, 2) void wgrad_taps_kernel(const WorkerDev* __r
 #pragma unroll
         for (int pr = 0; pr < 16; ++pr) {
           const float b = *(const float*)(yrow + pr * 256);
-          float av[TW];
+          float av[NOWN];
 #pragma unroll
-          for (int i = 0; i < TW; ++i) av[i] = *(const float*)(ta[i] + pr * (2 * S2 * 128));
+          for (int i = 0; i < NOWN; ++i) av[i] = *(const float*)(ta[i] + pr * (2 * S2 * 128));
 #pragma unroll
-          for (int i = 0; i < TW; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[i], b, acc[i], 0, 0, 0);
+          for (int i = 0; i < NOWN; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[i], b, acc[i], 0, 0, 0);
+        }
+        if constexpr (SH > 0) {  // position pairs 4 * wave ... + 3 of the shared tap
+          const char* tsh = ta[NOWN] + wave * (4 * 2 * S2 * 128);
+          const char* ysh = yrow + wave * (4 * 256);
+#pragma unroll
+          for (int pr = 0; pr < 4; ++pr) {
+            const float b = *(const float*)(ysh + pr * 256);
+            const float av = *(const float*)(tsh + pr * (2 * S2 * 128));
+            acc[NOWN] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, b, acc[NOWN], 0, 0, 0);
+          }
         }
         }
         nslot += s1;
@@ -808,13 +824,32 @@ __global__ __launch_bounds__(256, 2) void wgrad_taps_kernel(const WorkerDev* __r
   const bool co_ok = co < a.co;
   float* pbase = partial + (size_t)blockIdx.z * a.slot;
 #pragma unroll
-  for (int i = 0; i < TW; ++i) {
+  for (int i = 0; i < NOWN; ++i) {
     if (i >= ntw) break;
     const int tap = (t0 * a.k[1] + tap_t1[i]) * a.k[2] + tap_t2[i];
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
       const int cir = ci_t * 32 + 8 * (v / 4) + 4 * h + (v % 4);
       if (cir < a.ci && co_ok) pbase[((size_t)tap * a.ci + cir) * a.co + co] = acc[i][v];
+    }
+  }
+  if constexpr (SH > 0) {
+    // the shared tap: each wave's partial tile goes to LDS as [wave][register][lane]; thread tid then sums, over
+    // the waves in order, the four elements register tid / 64 + 4 * k of lane tid % 64 and stores them
+    float* red = (float*)wt_lds;
+    __syncthreads();  // the ring is no longer read
+#pragma unroll
+    for (int v = 0; v < 16; ++v) red[(wave * 16 + v) * 64 + lane] = acc[NOWN][v];
+    __syncthreads();
+    const int tap = (t0 * a.k[1] + tap_t1[NOWN]) * a.k[2] + tap_t2[NOWN];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const int v = wave + 4 * k;
+      float sum = 0.f;
+#pragma unroll
+      for (int w = 0; w < 4; ++w) sum += red[(w * 16 + v) * 64 + lane];
+      const int cir = ci_t * 32 + 8 * (v / 4) + 4 * h + (v % 4);
+      if (cir < a.ci && co_ok) pbase[((size_t)tap * a.ci + cir) * a.co + co] = sum;
     }
   }
 }
@@ -1244,18 +1279,23 @@ int conv_wgrad_mfma(distdl_plan* p, float* partial, hipStream_t st) {
     const int tw = wgrad_taps_per_wave(p);
     dim3 rgrid((unsigned)a.k[0], grid.y, grid.z), rblock(256);
     ProfScope prof("conv_bwd_weight_mfma", st);
-#define DISTDL_LAUNCH_TAPS_T(TW_, S2_, BF_)                                                                         \
+    // one tap left over after dealing the plane's taps to the four waves: it is shared (fp32 MFMAs only)
+    const int T = a.k[1] * a.k[2];
+    const bool share = mode != 2 && T % 4 == 1 && T / 4 + 1 == tw && rlds >= 4 * 16 * 64 * 4;
+#define DISTDL_LAUNCH_TAPS_T(TW_, S2_, BF_, SH_)                                                                    \
   do {                                                                                                              \
     if (rlds > 64 * 1024)                                                                                           \
-      if (int rc_ = allow_large_lds<wgrad_taps_kernel<TW_, S2_, BF_>>()) return rc_;                                \
-    hipLaunchKernelGGL((wgrad_taps_kernel<TW_, S2_, BF_>), rgrid, rblock, rlds, st, p->d_workers, p->tab_x.dev,     \
-                       p->tab_dy.dev, partial, a);                                                                  \
+      if (int rc_ = allow_large_lds<wgrad_taps_kernel<TW_, S2_, BF_, SH_>>()) return rc_;                           \
+    hipLaunchKernelGGL((wgrad_taps_kernel<TW_, S2_, BF_, SH_>), rgrid, rblock, rlds, st, p->d_workers,              \
+                       p->tab_x.dev, p->tab_dy.dev, partial, a);                                                    \
   } while (0)
 #define DISTDL_LAUNCH_TAPS(TW_, S2_)                                                                                \
   do {                                                                                                              \
-    if (mode == 2) DISTDL_LAUNCH_TAPS_T(TW_, S2_, 2);                                                               \
-    else if (mode == 1) DISTDL_LAUNCH_TAPS_T(TW_, S2_, 1);                                                          \
-    else DISTDL_LAUNCH_TAPS_T(TW_, S2_, 0);                                                                         \
+    if (mode == 2) DISTDL_LAUNCH_TAPS_T(TW_, S2_, 2, 0);                                                            \
+    else if (mode == 1 && share) DISTDL_LAUNCH_TAPS_T(TW_, S2_, 1, 1);                                              \
+    else if (mode == 1) DISTDL_LAUNCH_TAPS_T(TW_, S2_, 1, 0);                                                       \
+    else if (share) DISTDL_LAUNCH_TAPS_T(TW_, S2_, 0, 1);                                                           \
+    else DISTDL_LAUNCH_TAPS_T(TW_, S2_, 0, 0);                                                                      \
   } while (0)
     if (tw == 3 && a.s[2] == 1) DISTDL_LAUNCH_TAPS(3, 1);
     else if (tw == 3) DISTDL_LAUNCH_TAPS(3, 2);
