@@ -20,6 +20,7 @@
 // B lane l holds B[k = l/32][j = l%32], D register v of lane l holds
 // D[i = 8*(v/4) + 4*(l/32) + v%4][j = l%32].
 #include <algorithm>
+#include <mutex>
 
 #include "common.h"
 #include "conv_mfma.h"
@@ -951,7 +952,23 @@ static int choose_tc(int cap, int nq1max, int nq2max) {
 
 // Chooses the rows-per-wave so that two workgroups fit in a CU's LDS when
 // possible; returns 0 when the patch does not fit at all.
-static int choose_mt(CorrArgs& a, int nq1max, int nq2max) {
+static int choose_mt(CorrArgs& a, int nq1max, int nq2max, bool allow3) {
+  if (allow3) {
+    // Three M-tiles per wave (384 positions) when that window wastes clearly fewer of the multiplied positions
+    // than 256 do, e.g. planes of 33 rows: 11-row windows fill three of them exactly, 7-row windows need five.
+    // Built for the small-patch variants only (the parity classes of a strided layer's data gradient), and used
+    // with bf16 MFMAs only: with fp32 MFMAs the third tile's registers cost the third workgroup per compute unit,
+    // which is worth more there than the 5 % of MFMAs (measured on the 5^3 stride-2 layer: +2 % time in fp32,
+    // -9 % in bf16).
+    CorrArgs a3 = a, a2 = a;
+    finish_args(a3, 3, choose_tc(384, nq1max, nq2max));
+    finish_args(a2, 2, choose_tc(256, nq1max, nq2max));
+    const bool small3 = a3.R * a3.Cw * 2 <= 4 * 256 && a3.nt[1] * a3.nt[2] * 64 <= 3 * 256 && lds_bytes(a3) <= 80 * 1024;
+    if (small3 && window_efficiency(384, a3.tc, nq1max, nq2max) > 1.04 * window_efficiency(256, a2.tc, nq1max, nq2max)) {
+      a = a3;
+      return 3;
+    }
+  }
   for (int mt : {2, 1}) {
     finish_args(a, mt, choose_tc(128 * mt, nq1max, nq2max));
     if (lds_bytes(a) <= 80 * 1024 && a.R * a.Cw * 2 <= kMaxPieces * 256) return mt;
@@ -1042,6 +1059,56 @@ static size_t corr_weight_elems(const CorrArgs& a) {
 // weights + the tap tables (8 + 64 ints), kept 16-byte aligned
 static size_t corr_scratch_elems(const CorrArgs& a) { return corr_weight_elems(a) + 72; }
 
+// The kernel variant of a launch: M-tiles per wave, small or large patch, taps per plane known at compile time or
+// not, arithmetic mode.  `large_lds` is set to the function that raises the variant's dynamic LDS limit.
+struct CorrVariant {
+  const void* fn = nullptr;
+  int (*large_lds)() = nullptr;
+};
+template <int MT, int PA, int PB, int NT, int MODE>
+static CorrVariant corr_variant_of() {
+  return CorrVariant{(const void*)corr_mfma_kernel<MT, PA, PB, NT, MODE>, &allow_large_lds<corr_mfma_kernel<MT, PA, PB, NT, MODE>>};
+}
+template <int MODE>
+static CorrVariant corr_variant_mode(int mt, bool small, int ntaps) {
+  if (mt == 2 && small && ntaps == 9) return corr_variant_of<2, 4, 3, 9, MODE>();
+  if (mt == 2 && small && ntaps == 6) return corr_variant_of<2, 4, 3, 6, MODE>();
+  if (mt == 2 && small && ntaps == 4) return corr_variant_of<2, 4, 3, 4, MODE>();
+  if (mt == 2 && small) return corr_variant_of<2, 4, 3, 0, MODE>();
+  if constexpr (MODE == 2) {  // three M-tiles per wave: bf16 MFMAs only
+    if (mt == 3 && ntaps == 9) return corr_variant_of<3, 4, 3, 9, 2>();
+    if (mt == 3 && ntaps == 6) return corr_variant_of<3, 4, 3, 6, 2>();
+    if (mt == 3 && ntaps == 4) return corr_variant_of<3, 4, 3, 4, 2>();
+    if (mt == 3) return corr_variant_of<3, 4, 3, 0, 2>();
+  }
+  if (mt == 2 && ntaps == 25) return corr_variant_of<2, kMaxPieces, kMaxBPieces, 25, MODE>();
+  if (mt == 2) return corr_variant_of<2, kMaxPieces, kMaxBPieces, 0, MODE>();
+  if (small) return corr_variant_of<1, 4, 3, 0, MODE>();
+  return corr_variant_of<1, kMaxPieces, kMaxBPieces, 0, MODE>();
+}
+static CorrVariant corr_variant(int mode, int mt, bool small, int ntaps) {
+  return mode == 2 ? corr_variant_mode<2>(mt, small, ntaps)
+                   : mode == 1 ? corr_variant_mode<1>(mt, small, ntaps) : corr_variant_mode<0>(mt, small, ntaps);
+}
+
+// Workgroups of 256 threads of kernel `fn` that one compute unit holds at a time with `lds` bytes of dynamic LDS
+// (registers and LDS decide); asked of the runtime once per (kernel, LDS size) and remembered.
+static int resident_workgroups(const void* fn, int lds) {
+  struct Entry {
+    const void* fn;
+    int lds, n;
+  };
+  static std::mutex mu;
+  static std::vector<Entry> known;
+  std::lock_guard<std::mutex> lock(mu);
+  for (const Entry& e : known)
+    if (e.fn == fn && e.lds == lds) return e.n;
+  int n = 0;
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, fn, 256, (size_t)lds) != hipSuccess || n < 1) n = 2;
+  known.push_back(Entry{fn, lds, n});
+  return n;
+}
+
 static int launch_corr(distdl_plan* p, CorrArgs a, const void* w, float* wscratch, const void* bias, void** in_tab,
                        void** out_tab, const char* name, hipStream_t st) {
   // 0: fp32; 1: bf16 tensors widened to fp32; 2: bf16 MFMAs (contraction channels in 16-byte pieces of 8)
@@ -1049,10 +1116,22 @@ static int launch_corr(distdl_plan* p, CorrArgs a, const void* w, float* wscratc
   a.ck = mode == 2 ? 16 : 8;
   int nq1max, nq2max;
   max_nq(p, a, nq1max, nq2max);
-  const int mt = choose_mt(a, std::max(nq1max, 1), nq2max);
+  const int mt = choose_mt(a, std::max(nq1max, 1), nq2max, mode == 2);
   if (mt == 0) return set_error(DISTDL_ERR_UNSUPPORTED, "conv: kernel footprint does not fit in LDS");
+  const int lds = lds_bytes(a);
+  const bool small = a.R * a.Cw * 2 <= 4 * 256 && a.nt[1] * a.nt[2] * 64 <= 3 * 256;
+  const CorrVariant kv = corr_variant(mode, mt, small, a.nt[1] * a.nt[2]);
+  if (lds > 64 * 1024)
+    if (int rc = kv.large_lds()) return rc;
+  // Workgroups per compute unit that add throughput: with fp32 MFMAs two already keep the matrix pipes busy (a
+  // third one resident only smooths the stage changes), with bf16 MFMAs the launch is bound by latencies and
+  // every resident workgroup counts.  Measured on the 5^3 stride-2 layer: counting three for fp32 picks chunk
+  // lengths that run 4 % slower, counting two for bf16 3 % slower.
+  int resident = resident_workgroups(kv.fn, lds);
+  if (mode != 2) resident = std::min(resident, 2);
   // Output planes per workgroup.  A workgroup pays a fixed set-up (its address tables, about 8 * 10^3
-  // cycles) and then about `per_plane` cycles per plane; the chip runs about 512 workgroups at a time.
+  // cycles) and then about `per_plane` cycles per plane, its waves sharing the SIMDs with those of the other
+  // resident workgroups; the chip runs 256 * resident workgroups at a time.
   // Pick the chunk length with the smallest estimated time, preferring shorter chunks among near-ties.
   a.g0 = 1;
   {
@@ -1061,11 +1140,12 @@ static int launch_corr(distdl_plan* p, CorrArgs a, const void* w, float* wscratc
     const int64_t per_plane_wgs = max_tiles(p, a) / std::max<int64_t>(planes_max, 1) * p->n_workers;  // with g0 == 1
     const double setup = 8.0e3;
     const double per_plane = (double)a.nt[0] * ((a.kc + a.ck - 1) / a.ck) * a.nt[1] * a.nt[2] * mt *
-                             (a.ck == 16 ? 32.0 : 256.0) * 2.0;
+                             (a.ck == 16 ? 32.0 : 256.0) * resident;
+    const int64_t slots = 256 * (int64_t)resident;
     double best = 1e300;
     for (int64_t g0 = 1; g0 <= planes_max; ++g0) {
       const int64_t wgs = (planes_max + g0 - 1) / g0 * per_plane_wgs;
-      const double cost = (double)((wgs + 511) / 512) * (setup + g0 * per_plane);
+      const double cost = (double)((wgs + slots - 1) / slots) * (setup + g0 * per_plane);
       if (cost < best * 0.97) best = cost, a.g0 = (int32_t)g0;
     }
   }
@@ -1091,33 +1171,9 @@ static int launch_corr(distdl_plan* p, CorrArgs a, const void* w, float* wscratc
   }
   int64_t blocks = (int64_t)a.tiles_max * p->n_workers;
   blocks = (blocks + 7) / 8 * 8;
-  const int lds = lds_bytes(a);
-  const bool small = a.R * a.Cw * 2 <= 4 * 256 && a.nt[1] * a.nt[2] * 64 <= 3 * 256;
   ProfScope prof(name, st);
-#define DISTDL_LAUNCH_CORR_T(MT_, PA_, PB_, NT_, BF_)                                                                \
-  do {                                                                                                               \
-    if (lds > 64 * 1024)                                                                                             \
-      if (int rc_ = allow_large_lds<corr_mfma_kernel<MT_, PA_, PB_, NT_, BF_>>()) return rc_;                        \
-    hipLaunchKernelGGL((corr_mfma_kernel<MT_, PA_, PB_, NT_, BF_>), dim3((unsigned)blocks), dim3(256), lds, st,      \
-                       p->d_workers, in_tab, out_tab, a);                                                            \
-  } while (0)
-#define DISTDL_LAUNCH_CORR(MT_, PA_, PB_, NT_)                                                                       \
-  do {                                                                                                               \
-    if (mode == 2) DISTDL_LAUNCH_CORR_T(MT_, PA_, PB_, NT_, 2);                                                      \
-    else if (mode == 1) DISTDL_LAUNCH_CORR_T(MT_, PA_, PB_, NT_, 1);                                                 \
-    else DISTDL_LAUNCH_CORR_T(MT_, PA_, PB_, NT_, 0);                                                                \
-  } while (0)
-  const int ntaps = a.nt[1] * a.nt[2];
-  if (mt == 2 && small && ntaps == 9) DISTDL_LAUNCH_CORR(2, 4, 3, 9);
-  else if (mt == 2 && small && ntaps == 6) DISTDL_LAUNCH_CORR(2, 4, 3, 6);
-  else if (mt == 2 && small && ntaps == 4) DISTDL_LAUNCH_CORR(2, 4, 3, 4);
-  else if (mt == 2 && small) DISTDL_LAUNCH_CORR(2, 4, 3, 0);
-  else if (mt == 2 && ntaps == 25) DISTDL_LAUNCH_CORR(2, kMaxPieces, kMaxBPieces, 25);
-  else if (mt == 2) DISTDL_LAUNCH_CORR(2, kMaxPieces, kMaxBPieces, 0);
-  else if (small) DISTDL_LAUNCH_CORR(1, 4, 3, 0);
-  else DISTDL_LAUNCH_CORR(1, kMaxPieces, kMaxBPieces, 0);
-#undef DISTDL_LAUNCH_CORR
-#undef DISTDL_LAUNCH_CORR_T
+  void* kargs[] = {(void*)&p->d_workers, (void*)&in_tab, (void*)&out_tab, (void*)&a};
+  DISTDL_HIP_TRY(hipLaunchKernel(kv.fn, dim3((unsigned)blocks), dim3(256), kargs, (size_t)lds, st));
   return DISTDL_OK;
 }
 
