@@ -711,6 +711,12 @@ __global__ __launch_bounds__(256, 2) void wgrad_taps_kernel(const WorkerDev* __r
     }
     rpy = load4<MODE == 1>(ry, pgy, ((uint32_t)n * syn + (uint32_t)o0 * sy0 + (uint32_t)o1 * sy1) * ES);
   };
+  // db^ of this (worker, chunk): the workgroups of kernel plane 0 and input-channel tile 0 see every dy element
+  // of their output-channel tile exactly once, on its way into LDS, and sum it there
+  const bool bias_wg = t0 == 0 && ci_t == 0;
+  float bsum[PCH];
+#pragma unroll
+  for (int j = 0; j < PCH; ++j) bsum[j] = 0.f;
   int nslot = 0;      // ring slot of the step's new row 0
   int tslot[TW];      // ring slot of the row each tap reads
   auto stash = [&](int o1) {
@@ -723,6 +729,18 @@ __global__ __launch_bounds__(256, 2) void wgrad_taps_kernel(const WorkerDev* __r
       }
     }
     *(u32x4*)(ldsb + ys_base + (uint32_t)(o1 & 1) * 4096u + (uint32_t)tid * 16u) = rpy;
+    if (bias_wg) {  // uniform: the dy piece this thread staged joins its part of db^ (pieces out of range are zero)
+      if constexpr (BFM) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          bsum[2 * j] += __uint_as_float(rpy[j] << 16);
+          bsum[2 * j + 1] += __uint_as_float(rpy[j] & 0xffff0000u);
+        }
+      } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) bsum[j] += __uint_as_float(rpy[j]);
+      }
+    }
   };
 
   // fp32: lane (h, m) reads channel m of position 2 * pr + h.  bf16 MFMA: lane s of 16-lane group G addresses
@@ -851,6 +869,22 @@ __global__ __launch_bounds__(256, 2) void wgrad_taps_kernel(const WorkerDev* __r
       for (int w = 0; w < 4; ++w) sum += red[(w * 16 + v) * 64 + lane];
       const int cir = ci_t * 32 + 8 * (v / 4) + 4 * h + (v % 4);
       if (cir < a.ci && co_ok) pbase[((size_t)tap * a.ci + cir) * a.co + co] = sum;
+    }
+  }
+  if (bias_wg) {
+    // thread tid summed channels (tid % PPC) * PCH ... of position tid / PPC of every row segment: add up the 32
+    // positions, in order, and write the slot's trailing co entries
+    float* red = (float*)wt_lds;
+    __syncthreads();
+    if (tid < 32 * PPC) {
+#pragma unroll
+      for (int j = 0; j < PCH; ++j) red[(tid / PPC) * 32 + (tid % PPC) * PCH + j] = bsum[j];
+    }
+    __syncthreads();
+    if (tid < 32 && co_t * 32 + tid < a.co) {
+      float sum = 0.f;
+      for (int pos = 0; pos < 32; ++pos) sum += red[pos * 32 + tid];
+      pbase[(size_t)a.k[0] * a.k[1] * a.k[2] * a.ci * a.co + co_t * 32 + tid] = sum;
     }
   }
 }
@@ -1328,7 +1362,8 @@ int conv_wgrad_mfma(distdl_plan* p, float* partial, hipStream_t st) {
     aligned = (uintptr_t)p->tab_x.host[w] % 16 == 0 && (uintptr_t)p->tab_dy.host[w] % 16 == 0;
   const int lds = 4 * (a.ncell + 32) * 128;
   const bool bf16 = p->dtype == DISTDL_BF16;
-  if (aligned && wgrad_rows_shape_ok(p)) {
+  const bool taps_path = aligned && wgrad_rows_shape_ok(p);
+  if (taps_path) {
     const int mode = wgrad_mode(p);
     const int rowp = (a.ncell * (mode == 2 ? 4 : 8) + 63) & ~63;
     const int rlds = (a.span + a.s[1]) * rowp * 16 + 8192;
@@ -1380,7 +1415,7 @@ int conv_wgrad_mfma(distdl_plan* p, float* partial, hipStream_t st) {
       hipLaunchKernelGGL(wgrad_mfma_kernel<8>, grid, dim3(256), 0, st, p->d_workers, p->tab_x.dev, p->tab_dy.dev,
                          partial, a);
   }
-  {
+  if (!taps_path) {  // the plane-per-workgroup kernel sums db^ itself
     ProfScope prof("conv_bias_partial", st);
     if (bf16)
       hipLaunchKernelGGL(bias_partial_kernel<true>, dim3((unsigned)(p->n_workers * a.nchunks)), dim3(256), 0, st,
