@@ -78,6 +78,9 @@ CONV_FULL = [
     ("cfg2", dict(in_shape=(20, 24), n_b=6, c_in=12, c_out=4, ksize=(1, 1), padding=(0, 0)), True),
     ("cfg2", dict(in_shape=(28, 28), n_b=4, c_in=1, c_out=6, ksize=(5, 5), padding=(2, 2)), True),   # cfg4 conv1
     ("cfg2", dict(in_shape=(14, 14), n_b=4, c_in=6, c_out=16, ksize=(5, 5), padding=(0, 0)), True),  # cfg4 conv2
+    # a single worker per dimension: no neighbour to exchange with, only the padding to clear
+    ("cfg2", dict(in_shape=(40, 44), n_b=1, c_in=16, c_out=16, P=(1, 1)), True),
+    ("cfg5", dict(in_shape=(12, 14, 36), P=(1, 1, 1), c_in=32, c_out=32), True),
     # several channel tiles (the second output tile half full): the weight gradient's shared tap and its db sums
     ("cfg2", dict(in_shape=(40, 70), n_b=2, c_in=64, c_out=48, ksize=(3, 3), padding=(1, 1), P=(2, 2)), True),
     ("cfg2", dict(in_shape=(36, 40), n_b=3, c_in=32, c_out=64, ksize=(5, 5), stride=(2, 2), padding=(2, 2), P=(2, 1)), True),
