@@ -46,6 +46,7 @@ CONV_FULL = [
     ("cfg1", {}, True),
     ("cfg1", {}, False),
     ("cfg2", dict(in_shape=(64, 64), n_b=2), True),
+    ("cfg2", {}, True),            # the 2-D configuration at its full size, every element (the oracle takes seconds)
     ("cfg5", dict(in_shape=(24, 24, 24), P=(2, 2, 2), c_in=8, c_out=8), True),
     ("cfg5u", dict(in_shape=(21, 23, 22), P=(2, 2, 2), c_in=32, c_out=32), False),
     ("cfg2", dict(in_shape=(19, 23), n_b=3, c_in=3, c_out=5, P=(2, 3), ksize=(3, 4), stride=(2, 1),
