@@ -331,8 +331,7 @@ struct Corr16Args {
   int32_t R, Cw;               // patch rows and cells per row of one plane
   int32_t ps;                  // bytes between the four channel groups of the patch in LDS
   int32_t tapmin1, tapmin2;    // smallest tap offset along dimensions 1, 2
-  int32_t g0;                  // window steps along the planes per workgroup
-  int32_t tiles_max, ntaps;    // tiles of the largest worker; taps per kernel plane
+  int32_t wpw, g0, ntaps;      // workgroups per worker; steps per workgroup (large patches); taps per kernel plane
   int32_t tapo[64];            // patch byte offset of tap (t1, t2)
   const float* wt;             // weights: [t0][tap][lane][KM]
   const float* bias;           // may be null
@@ -360,7 +359,7 @@ constexpr int kPA16 = 14, kPB16 = 7;
 constexpr uint32_t kSkip = 0xffffffffu;
 
 // NT: taps per kernel plane known at compile time (tap loop unrolled, offsets in scalar registers), or 0.
-template <int KM, int V, int NT>
+template <int KM, int V, int NT, int PA>
 __global__ __launch_bounds__(256, 2) void corr16_kernel(const WorkerDev* __restrict__ workers, void* const* in_bufs,
                                                         void* const* out_bufs, Corr16Args a) {
   extern __shared__ float lds[];
@@ -371,19 +370,32 @@ __global__ __launch_bounds__(256, 2) void corr16_kernel(const WorkerDev* __restr
   // XCD-aware order: consecutive tiles stay behind one L2
   const uint32_t nblk = gridDim.x;
   const uint32_t rblk = (blockIdx.x & 7u) * (nblk >> 3) + (blockIdx.x >> 3);
-  const uint32_t worker = rblk / a.tiles_max;
-  uint32_t tile = rblk - worker * a.tiles_max;
+  const uint32_t worker = rblk / (uint32_t)a.wpw, slice = rblk - worker * (uint32_t)a.wpw;
   if (worker >= (uint32_t)c.n_workers) return;
   const WorkerDev wd = workers[worker];
   const PerWorker g = derive(wd, c);
   const int nq0 = g.nq[0], planes = c.n_b * nq0;
   const int n2 = (g.nq[2] + a.tc - 1) / a.tc, n1 = (g.nq[1] + a.tr - 1) / a.tr;
   const int nsteps = (planes + a.tp - 1) / a.tp;
-  const int ngrp = (nsteps + a.g0 - 1) / a.g0;
-  if ((int64_t)tile >= (int64_t)ngrp * n1 * n2) return;
-  const int q2_0 = (tile % n2) * a.tc; tile /= n2;
-  const int q1_0 = (tile % n1) * a.tr; tile /= n1;
-  const int step_begin = tile * a.g0, step_end = min(step_begin + a.g0, nsteps);
+  // The worker's (window, step) pairs, window-major, are dealt to its a.wpw workgroups.  Small patches (MULTI):
+  // in contiguous, balanced runs; a run that crosses into the next window sets its address tables up again.
+  // Large patches: a.g0 steps of one window per workgroup (the loop over windows costs registers these variants
+  // do not have).
+  constexpr bool MULTI = PA <= 6;
+  const int64_t total = (int64_t)n1 * n2 * nsteps;
+  int64_t f, f_end;
+  if constexpr (MULTI) {
+    f = total * slice / a.wpw;
+    f_end = total * (slice + 1) / a.wpw;
+  } else {
+    const int ngrp = (nsteps + a.g0 - 1) / a.g0;
+    const int64_t window = slice / (uint32_t)ngrp;
+    f = window * nsteps + (int64_t)(slice - (uint32_t)window * (uint32_t)ngrp) * a.g0;
+    f_end = min(f + a.g0, (window + 1) * nsteps);
+    if (window >= (int64_t)n1 * n2) return;
+  }
+  if (f >= f_end) return;
+  int q1_0 = 0, q2_0 = 0, step_begin = 0, step_end = 0;
 
   const uint32_t si2 = c.kc, si1 = g.in_ext[2] * si2, si0 = g.in_ext[1] * si1, sin = g.in_ext[0] * si0;
   const uint32_t so2 = c.nc, so1 = g.out_ext[2] * so2, so0 = g.out_ext[1] * so1, son = g.out_ext[0] * so0;
@@ -402,12 +414,15 @@ __global__ __launch_bounds__(256, 2) void corr16_kernel(const WorkerDev* __restr
 
   // per-thread patch pieces: global byte offset inside the first plane of a stage (kOobS: the cell lies outside
   // the input and reads as zero) and LDS byte offset with the piece's plane in bits 24-29
-  uint32_t goff[kPA16], loff[kPA16];
+  uint32_t goff[PA], loff[PA];
+  uint32_t abase[4], soff[4][4];
+  const int trtc = a.tr * a.tc, npos = a.tp * trtc;
+  auto setup_window = [&]() {
   {
     const uint32_t ppc = c.kc / V, npieces = ncells * ppc;
     const float r_ppc = 1.0f / (float)ppc, r_pc = 1.0f / (float)plane_cells, r_cw = 1.0f / (float)a.Cw;
 #pragma unroll
-    for (int i = 0; i < kPA16; ++i) {
+    for (int i = 0; i < PA; ++i) {
       const uint32_t q = tid + i * 256;
       goff[i] = kOobS;
       loff[i] = kSkip;
@@ -426,9 +441,7 @@ __global__ __launch_bounds__(256, 2) void corr16_kernel(const WorkerDev* __restr
   }
   // operand addresses and store offsets: lane (ij, kg) multiplies window position (wave * 4 + mt) * 16 + ij and
   // holds, in accumulator register v, position (wave * 4 + mt) * 16 + 4 * kg + v of output channel ij
-  const int trtc = a.tr * a.tc, npos = a.tp * trtc;
   const float r_trtc = 1.0f / (float)trtc, r_tc = 1.0f / (float)a.tc;
-  uint32_t abase[4], soff[4][4];
 #pragma unroll
   for (int mt = 0; mt < 4; ++mt) {
     uint32_t pidx = (wave * 4 + mt) * 16 + ij;
@@ -453,6 +466,7 @@ __global__ __launch_bounds__(256, 2) void corr16_kernel(const WorkerDev* __restr
       }
     }
   }
+  };
   const uint32_t pob = (wave * 4) * 16 + 4 * kg;
   const float bias = (a.bias && ij < c.nc) ? a.bias[ij] : 0.f;
   const uint32_t bread = wl + lane * KM * 4u;
@@ -473,14 +487,14 @@ __global__ __launch_bounds__(256, 2) void corr16_kernel(const WorkerDev* __restr
       t0 = 0;
     }
   };
-  PT ra[kPA16];
+  PT ra[PA];
   u32x4 rb[kPB16];
   auto load_stage = [&](int step, int t0, bool weights) {
     const int n = a.tp > 1 ? step * a.tp : step / nq0;
     const uint32_t pmax = (uint32_t)min(a.tp, planes - step * a.tp);
     const uint32_t sbase = ((uint32_t)n * sin + (uint32_t)in_plane(step, t0) * si0) * 4u;
 #pragma unroll
-    for (int i = 0; i < kPA16; ++i) ra[i] = Piece<V>::load(rin, (loff[i] >> 24) < pmax ? goff[i] : kOobS, sbase);
+    for (int i = 0; i < PA; ++i) ra[i] = Piece<V>::load(rin, (loff[i] >> 24) < pmax ? goff[i] : kOobS, sbase);
     if (weights) {
 #pragma unroll
       for (int i = 0; i < kPB16; ++i) {
@@ -492,7 +506,7 @@ __global__ __launch_bounds__(256, 2) void corr16_kernel(const WorkerDev* __restr
   };
   auto write_stage = [&](bool weights) {
 #pragma unroll
-    for (int i = 0; i < kPA16; ++i)
+    for (int i = 0; i < PA; ++i)
       if (loff[i] != kSkip) {
         const uint32_t o = loff[i] & 0xffffu;
         if constexpr (V == 1 || KM == 4) {
@@ -559,10 +573,21 @@ __global__ __launch_bounds__(256, 2) void corr16_kernel(const WorkerDev* __restr
   };
 
   __syncthreads();  // the zero fill is complete
-  int cs = step_begin, ct0 = 0, staged_t0 = -1;
+  int staged_t0 = -1;  // kernel plane whose weights are in LDS (they stay valid from window to window)
+  do {
+  {
+    const int64_t window = f / nsteps;
+    step_begin = (int)(f - window * nsteps);
+    step_end = (int)min((int64_t)nsteps, step_begin + (f_end - f));
+    q2_0 = (int)(window % n2) * a.tc;
+    q1_0 = (int)(window / n2) * a.tr;
+    f += step_end - step_begin;
+  }
+  setup_window();
+  int cs = step_begin, ct0 = 0;
   if (ntaps == 0) cs = step_end;  // a parity class no tap reaches: zeros
   next_valid(cs, ct0);
-  if (cs < step_end) load_stage(cs, ct0, true);
+  if (cs < step_end) load_stage(cs, ct0, ct0 != staged_t0);
   for (int step = step_begin; step < step_end; ++step) {
 #pragma unroll
     for (int mt = 0; mt < 4; ++mt) acc[mt] = floatx4{0.f, 0.f, 0.f, 0.f};
@@ -589,6 +614,7 @@ __global__ __launch_bounds__(256, 2) void corr16_kernel(const WorkerDev* __restr
         __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(acc[mt][v] + bias), rout,
                                               pob + mt * 16 + v < plimit ? soff[mt][v] : kOobS, obase, 0);
   }
+  } while (MULTI && f < f_end);
 }
 
 // weights in staging order: dst[t0][tap][lane = kg * 16 + j][gk] = W[tap(t0, t1, t2)][k = KM * kg + gk][n = j], with
@@ -616,7 +642,9 @@ __global__ __launch_bounds__(256) void corr16_weights_kernel(const float* __rest
 }
 
 struct Corr16Shape {
-  int km, tp, tr, tc, R, Cw, ps, tapmin1, tapmin2, g0, tiles_max, lds;
+  int km, tp, tr, tc, R, Cw, ps, tapmin1, tapmin2, wpw, g0, lds;
+  int pieces;     // 16-byte (or 4-byte) patch pieces of a stage
+  int64_t steps;  // (window, step) pairs of the largest worker
 };
 
 bool corr16_shape(const distdl_plan* p, const CorrArgs& c, bool vec, Corr16Shape& s) {
@@ -673,23 +701,32 @@ bool corr16_shape(const distdl_plan* p, const CorrArgs& c, bool vec, Corr16Shape
         if (score > best + 1e-12) {
           best = score;
           s.tp = tp, s.tr = tr, s.tc = tc, s.R = R, s.Cw = Cw, s.ps = (int)(4 * psd), s.lds = (int)lds;
+          s.pieces = (int)(cells * (c.kc / V));
         }
         break;  // the largest plane count that fits is the one to score
       }
     }
   if (best < 0.0) return false;
-  int64_t tiles1 = 0;  // tiles of the largest worker with one step per workgroup
+  // Workgroups per worker.  Small patches: a worker's (window, step) pairs are dealt to them in balanced
+  // contiguous runs, so the launch is one even round of two workgroups per compute unit whatever the window
+  // count (a workgroup's set-up, its address tables, costs about as much as two steps of a 3 x 3 kernel).
+  // Large patches: g0 steps of one window per workgroup, g0 from the estimate rounds x (set-up + steps) with
+  // the steps dealt evenly to the groups and about 512 workgroups running at a time.
+  int64_t t_max = 0, windows_max = 0;
   for (const WorkerDev& wd : p->workers) {
     const PerWorker g = derive(wd, c);
     const int64_t steps = ((int64_t)p->n_b * g.nq[0] + s.tp - 1) / s.tp;
-    tiles1 = std::max<int64_t>(tiles1, steps * ((g.nq[1] + s.tr - 1) / s.tr) * ((g.nq[2] + s.tc - 1) / s.tc));
+    const int64_t windows = (int64_t)((g.nq[1] + s.tr - 1) / s.tr) * ((g.nq[2] + s.tc - 1) / s.tc);
+    t_max = std::max(t_max, steps * windows);
+    windows_max = std::max(windows_max, windows);
   }
   const int64_t steps_max = (planes_max + s.tp - 1) / s.tp;
-  // Window steps per workgroup.  A workgroup's set-up (its address tables) costs about as much as two steps of a
-  // 3 x 3 kernel and the chip runs about 512 workgroups at a time: take the step count with the smallest
-  // estimate of rounds x (set-up + steps), steps dealt evenly to the groups.
-  {
-    const int64_t per_step = std::max<int64_t>(1, tiles1 / std::max<int64_t>(steps_max, 1)) * p->n_workers;
+  s.g0 = 0;
+  if (s.pieces <= 6 * 256) {
+    // (measured on the 2-D 16-channel layer: 256, 384, 768 and 1024 workgroups in all are 5 to 35 % slower than 512)
+    s.wpw = (int)std::max<int64_t>(1, std::min<int64_t>(std::max<int64_t>(1, 512 / p->n_workers), t_max));
+  } else {
+    const int64_t per_step = std::max<int64_t>(1, windows_max) * p->n_workers;
     double best_cost = 1e300;
     s.g0 = 1;
     for (int64_t g0 = 1; g0 <= steps_max; ++g0) {
@@ -698,15 +735,11 @@ bool corr16_shape(const distdl_plan* p, const CorrArgs& c, bool vec, Corr16Shape
       const double cost = (double)((groups * per_step + 511) / 512) * (2.0 + (double)g0);
       if (cost < best_cost - 1e-9) best_cost = cost, s.g0 = (int)g0;
     }
+    const int64_t wpw = windows_max * ((steps_max + s.g0 - 1) / s.g0);
+    if (wpw * p->n_workers > 0x7fffff00) return false;
+    s.wpw = (int)wpw;
   }
-  tiles1 = 0;
-  for (const WorkerDev& wd : p->workers) {
-    const PerWorker g = derive(wd, c);
-    const int64_t steps = ((int64_t)p->n_b * g.nq[0] + s.tp - 1) / s.tp;
-    tiles1 = std::max<int64_t>(tiles1, ((steps + s.g0 - 1) / s.g0) * ((g.nq[1] + s.tr - 1) / s.tr) * ((g.nq[2] + s.tc - 1) / s.tc));
-  }
-  if (tiles1 * p->n_workers > 0x7fffff00) return false;
-  s.tiles_max = (int)tiles1;
+  s.steps = t_max;
   return true;
 }
 
@@ -719,13 +752,13 @@ int launch_corr16(distdl_plan* p, const CorrArgs& c, bool vec, const float* w, f
                   void** in_tab, void** out_tab, const char* name, hipStream_t st) {
   Corr16Shape s;
   if (!corr16_shape(p, c, vec, s)) return set_error(DISTDL_ERR_UNSUPPORTED, "conv: shape not covered by the small-channel kernel");
-  if (s.tiles_max == 0) return DISTDL_OK;
+  if (s.steps == 0) return DISTDL_OK;
   Corr16Args a{};
   a.c = c;
   a.tp = s.tp, a.tr = s.tr, a.tc = s.tc, a.R = s.R, a.Cw = s.Cw, a.ps = s.ps;
   a.tapmin1 = s.tapmin1, a.tapmin2 = s.tapmin2;
+  a.wpw = s.wpw;
   a.g0 = s.g0;
-  a.tiles_max = s.tiles_max;
   a.ntaps = c.nt[1] * c.nt[2];
   for (int t1 = 0; t1 < c.nt[1]; ++t1)
     for (int t2 = 0; t2 < c.nt[2]; ++t2)
@@ -739,12 +772,20 @@ int launch_corr16(distdl_plan* p, const CorrArgs& c, bool vec, const float* w, f
     hipLaunchKernelGGL(corr16_weights_kernel, dim3((unsigned)((wtotal + 255) / 256)), dim3(256), 0, st, w, wscratch, c,
                        s.km, (int)p->n_ci, taps, p->ksize[1], p->ksize[2]);
   }
-  int64_t blocks = (int64_t)s.tiles_max * p->n_workers;
+  int64_t blocks = (int64_t)s.wpw * p->n_workers;
   blocks = (blocks + 7) / 8 * 8;
   ProfScope prof(name, st);
+  // patch pieces per thread held in registers between a stage's loads and its LDS writes: 6 covers windows of
+  // 3 x 3 kernels with up to 16 channels; the tables sized for 14 cost 48 registers more
 #define DISTDL_LAUNCH_C16(KM_, V_, NT_)                                                                             \
-  hipLaunchKernelGGL((corr16_kernel<KM_, V_, NT_>), dim3((unsigned)blocks), dim3(256), s.lds, st, p->d_workers,      \
-                     in_tab, out_tab, a)
+  do {                                                                                                               \
+    if (s.pieces <= 6 * 256)                                                                                         \
+      hipLaunchKernelGGL((corr16_kernel<KM_, V_, NT_, 6>), dim3((unsigned)blocks), dim3(256), s.lds, st,             \
+                         p->d_workers, in_tab, out_tab, a);                                                          \
+    else                                                                                                             \
+      hipLaunchKernelGGL((corr16_kernel<KM_, V_, NT_, kPA16>), dim3((unsigned)blocks), dim3(256), s.lds, st,         \
+                         p->d_workers, in_tab, out_tab, a);                                                          \
+  } while (0)
 #define DISTDL_LAUNCH_C16_NT(KM_, V_)                                                                               \
   do {                                                                                                               \
     if (a.ntaps == 9) DISTDL_LAUNCH_C16(KM_, V_, 9);                                                                \
