@@ -410,3 +410,57 @@ def test_conv_full_size_sampled(name, dtype):
         mask = np.ones(part.buf_shape(wk), dtype=bool)
         mask[part.bulk_slices(wk)] = False
         assert not dx_host[wk][:, :, mask].any()
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
+def test_conv_step_replayed_from_a_graph_matches_eager(dtype):
+    """The 32-channel strided layer (matrix-core kernels, eight parity-class launches, fused db sums): a warmed-up
+    forward + backward recorded into a HIP graph and replayed on new data must reproduce the eager step bit for bit."""
+    require_gpu()
+    cfg, part, case = _conv_case("cfg5u", in_shape=(21, 23, 22), P=(2, 2, 2), c_in=32, c_out=32)
+    plan = dd.distdl_plan_create(cfg["D"], cfg["n_b"], cfg["c_in"], cfg["c_out"], cfg["in_shape"], cfg["P"],
+                                 cfg["ksize"], cfg["stride"], cfg["padding"], cfg["dilation"], dtype)
+    rng = np.random.default_rng(3)
+    new_x = lambda: [to_cl(b, dtype) for b in prim.scatter_bulk(rng.standard_normal(case["x"].shape).astype(np.float32),
+                                                                  part, fill=np.float32(3.0))]
+    new_dy = lambda: [to_cl(t, dtype) for t in prim.scatter_out(rng.standard_normal(case["dy"].shape).astype(np.float32),
+                                                                 part)]
+    x_bufs, dy = new_x(), new_dy()
+    w, bias = w_to_dev(case["w"]).to(dtype), w_to_dev(case["bias"]).to(dtype)
+    y = [torch.zeros((cfg["n_b"],) + part.out_shape(wk) + (cfg["c_out"],), device="cuda", dtype=dtype)
+         for wk in range(part.n_workers)]
+    dx = [torch.zeros_like(b) for b in x_bufs]
+    dw, db = torch.zeros_like(w), torch.zeros_like(bias)
+    ws = torch.empty(max(dd.distdl_conv_bwd_workspace(plan), 16), dtype=torch.uint8, device="cuda")
+
+    def step():
+        dd.distdl_conv_fwd(plan, x_bufs, w, bias, y)
+        dd.distdl_conv_bwd(plan, x_bufs, w, dy, dx, dw, db, ws)
+
+    def load(xs, dys):                      # into the recorded buffers, by eager copies
+        for dst, src in zip(x_bufs, xs):
+            dst.copy_(src)
+        for dst, src in zip(dy, dys):
+            dst.copy_(src)
+
+    snapshot = lambda: [t.clone() for t in (y[0], y[-1], dx[0], dx[-1], dw, db, x_bufs[3])]
+    batches = [(new_x(), new_dy()) for _ in range(3)]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    eager = []
+    with torch.cuda.stream(side):
+        for xs, dys in batches:
+            load(xs, dys)
+            step()
+            eager.append(snapshot())
+    side.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        step()
+    for (xs, dys), want in zip(batches, eager):
+        load(xs, dys)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for got, ref in zip(snapshot(), want):
+            assert torch.equal(got, ref)
