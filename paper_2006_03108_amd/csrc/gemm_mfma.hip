@@ -59,13 +59,14 @@ __device__ __forceinline__ void static_for(F&& f) {
 // Row pitch in LDS is BK + 16 bytes for the K-contiguous layout, tile extent + 16 (bf16: 32) bytes for the other.
 //
 // D: stages the global loads run ahead of the multiplication (a ring of D register sets).
+// SB: one LDS buffer and two barriers per stage instead of two buffers and one barrier.
 //
 // nsplit > 1 (grid.y): the K stages of all segments, taken as one sequence, are cut into nsplit contiguous runs,
 // one workgroup per tile and run, each of which
 // writes its fp32 partial tile to `partial` ([block][split][M][N]); gemm_reduce_kernel then sums the splits
 // in ascending order, adds the bias and rounds.  This is the sum-reduce R of the layer left un-fused: with a
 // small batch a launch has too few tiles to fill the chip, and the splits supply the missing workgroups.
-template <bool BF16, bool A_KC, bool B_KC, int TM, int TN, int D>
+template <bool BF16, bool A_KC, bool B_KC, int TM, int TN, int D, bool SB>
 __global__ __launch_bounds__(256) void gemm_mfma_kernel(const GemmBlock* __restrict__ blocks, float* __restrict__ partial,
                                                         int64_t partial_stride) {
   constexpr int ES = BF16 ? 2 : 4;             // element size
@@ -82,7 +83,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(const GemmBlock* __restr
   constexpr int B_BYTES = B_KC ? TILE_N * PITCH_KC : BK * PITCH_TB;
   constexpr int PA = TILE_M * BK * ES / 16 / 256;  // 16-byte pieces per thread and stage
   constexpr int PB = TILE_N * BK * ES / 16 / 256;
-  extern __shared__ __attribute__((aligned(16))) char smem[];  // A0 B0 A1 B1
+  extern __shared__ __attribute__((aligned(16))) char smem[];  // A0 B0 A1 B1 (SB: A0 B0)
 
   const GemmBlock& gb = blocks[blockIdx.z];
   const int tiles_n = (gb.N + TILE_N - 1) / TILE_N, tiles_m = (gb.M + TILE_M - 1) / TILE_M;
@@ -327,10 +328,18 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(const GemmBlock* __restr
     // refill that stage's ring slot
     auto stage = [&](int st, auto d) __attribute__((always_inline)) {
       constexpr int next = (decltype(d)::value + 1) % D;
-      multiply(st & 1);
-      stash((st + 1) & 1, std::integral_constant<int, next>{});
-      load(std::integral_constant<int, next>{}, st + 1 + D < n);
-      __syncthreads();
+      if constexpr (SB) {  // one LDS buffer: the next stage may only be written when everyone has read this one
+        multiply(0);
+        __syncthreads();
+        stash(0, std::integral_constant<int, next>{});
+        load(std::integral_constant<int, next>{}, st + 1 + D < n);
+        __syncthreads();
+      } else {
+        multiply(st & 1);
+        stash((st + 1) & 1, std::integral_constant<int, next>{});
+        load(std::integral_constant<int, next>{}, st + 1 + D < n);
+        __syncthreads();
+      }
     };
     int st0 = 0;
     for (; st0 + D <= n; st0 += D)  // whole turns of the ring: no branches, so the waits stay exact
@@ -520,10 +529,14 @@ static int launch_gemm_variant(dim3 grid, const GemmBlock* d_blocks, float* part
   constexpr int ES = BF16 ? 2 : 4, BK = BF16 ? 64 : 32, TILE = 64 * T, D = T == 1 ? 2 : 1;
   constexpr int A_BYTES = A_KC ? TILE * (BK * ES + 16) : BK * (TILE * ES + (BF16 ? 32 : 16));
   constexpr int B_BYTES = B_KC ? TILE * (BK * ES + 16) : BK * (TILE * ES + (BF16 ? 32 : 16));
-  constexpr int LDS = 2 * (A_BYTES + B_BYTES);
+  // The weight-gradient layout (both operands with their rows contiguous: short K loops, many tiles) keeps one LDS
+  // buffer and pays a second barrier per stage: a third workgroup then fits a compute unit, which is worth 4-5 %
+  // there; the forward and data-gradient layouts lose 1-3 % that way and keep two buffers.
+  constexpr bool SB = !A_KC && !B_KC;
+  constexpr int LDS = (SB ? 1 : 2) * (A_BYTES + B_BYTES);
   if (LDS > 64 * 1024)
-    if (int rc = allow_large_lds<gemm_mfma_kernel<BF16, A_KC, B_KC, T, T, D>>()) return rc;
-  hipLaunchKernelGGL((gemm_mfma_kernel<BF16, A_KC, B_KC, T, T, D>), grid, dim3(256), LDS, st, d_blocks, partial, max_mn);
+    if (int rc = allow_large_lds<gemm_mfma_kernel<BF16, A_KC, B_KC, T, T, D, SB>>()) return rc;
+  hipLaunchKernelGGL((gemm_mfma_kernel<BF16, A_KC, B_KC, T, T, D, SB>), grid, dim3(256), LDS, st, d_blocks, partial, max_mn);
   return DISTDL_OK;
 }
 
