@@ -277,15 +277,36 @@ def dist_conv_cp_adjoint(x_bufs, w_blocks, dy, part, P_co, P_ci, stride, dilatio
 # --------------------------------------------------------------------------
 
 
+def padding_mask(part, wk):
+    """Boolean array over worker wk's buffer (feature dims): True on the cells
+    that lie outside the global domain (the zero padding)."""
+    mask = np.zeros(part.buf_shape(wk), dtype=bool)
+    for d in range(part.D):
+        g = part.g(wk, d)
+        idx = [slice(None)] * part.D
+        idx[d] = slice(0, g["pad"][0])
+        mask[tuple(idx)] = True
+        idx[d] = slice(g["buf"] - g["pad"][1], g["buf"])
+        mask[tuple(idx)] = True
+    return mask
+
+
 def dist_maxpool_forward(x_bufs, part, ksize, stride):
     """Forward Pooling Algorithm of Sec. 4: x <- H x; y <- Pool(x), the local
-    pool starting at each worker's origin (which skips "extra" input)."""
+    pool starting at each worker's origin (which skips "extra" input).
+    Sec. 4 only says that pooling needs padding shims and takes the layer
+    function from the framework it wraps; that framework's max-pool pads with
+    -inf, i.e. the maximum runs over the cells of the tensor itself.  So the
+    padding cells (zeros in the buffer, as every sliding-kernel layer shares
+    one H) are masked to -inf for the local max: they never win and never
+    receive gradient."""
     prim.halo_exchange(x_bufs, part)
     ys, args = [], []
     for wk in range(part.n_workers):
         origin = [part.g(wk, d)["origin"] for d in range(part.D)]
-        y, a = maxpool_valid(np.asarray(x_bufs[wk], dtype=np.float64), ksize, stride,
-                             part.out_shape(wk), origin)
+        xb = np.array(x_bufs[wk], dtype=np.float64)
+        xb[:, :, padding_mask(part, wk)] = -np.inf
+        y, a = maxpool_valid(xb, ksize, stride, part.out_shape(wk), origin)
         ys.append(y)
         args.append(a)
     return ys, args

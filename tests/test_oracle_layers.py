@@ -237,6 +237,44 @@ def test_distributed_maxpool_equals_torch(n, P):
     np.testing.assert_allclose(prim.gather_bulk(dx, part), tx.grad.numpy(), rtol=0, atol=1e-14)
 
 
+@pytest.mark.parametrize("n,P,k,s,p", [((13, 11), (2, 2), (3, 3), (2, 2), (1, 1)), ((9, 12), (3, 2), (2, 2), (2, 2), (1, 1)),
+                                       ((64, 48), (4, 3), (2, 2), (2, 2), (1, 1)), ((12, 7), (3, 1), (4, 3), (2, 1), (2, 1))])
+def test_distributed_maxpool_with_padding_ignores_the_padding(n, P, k, s, p):
+    """Padding cells never win the max and never receive gradient.  Pinned on all-negative inputs (where a zero
+    in the padding would win every border window) against torch's max_pool2d with padding and its autograd, and
+    against a window loop written out here that visits only in-domain cells."""
+    part = geo.Partition.for_kernel(n, P, k, s, p, (1, 1))
+    x = -np.abs(RNG.standard_normal((2, 3) + n)) - 0.5
+    tx = T(x).requires_grad_(True)
+    ty = F.max_pool2d(tx, k, s, p)
+    dy = RNG.standard_normal(tuple(ty.shape))
+    ty.backward(T(dy))
+    bufs = prim.scatter_bulk(x, part, fill=np.nan)
+    ys, args = layers.dist_maxpool_forward(bufs, part, k, s)
+    y = prim.gather_out(ys, part)
+    np.testing.assert_array_equal(y, ty.detach().numpy())
+    assert (y < 0).all(), "a zero from the padding won a window"
+    dx_bufs = layers.dist_maxpool_adjoint(prim.scatter_out(dy, part), args, part, [b.shape for b in bufs], k, s)
+    np.testing.assert_allclose(prim.gather_bulk(dx_bufs, part), tx.grad.numpy(), rtol=0, atol=1e-14)
+    # the definition, cell by cell: first maximum in row-major tap order over the taps inside the domain
+    want = np.empty_like(y)
+    dx_want = np.zeros_like(x)
+    for b, c, o0, o1 in np.ndindex(*y.shape):
+        best, where = None, None
+        for t0 in range(k[0]):
+            for t1 in range(k[1]):
+                i0, i1 = o0 * s[0] - p[0] + t0, o1 * s[1] - p[1] + t1
+                if 0 <= i0 < n[0] and 0 <= i1 < n[1] and (best is None or x[b, c, i0, i1] > best):
+                    best, where = x[b, c, i0, i1], (i0, i1)
+        want[b, c, o0, o1] = best
+        dx_want[(b, c) + where] += dy[b, c, o0, o1]
+    np.testing.assert_array_equal(y, want)
+    np.testing.assert_allclose(prim.gather_bulk(dx_bufs, part), dx_want, rtol=0, atol=1e-14)
+    # with zeros competing the border windows would differ: the reading matters on these inputs
+    zero_pad = F.max_pool2d(F.pad(T(x), (p[1], p[1], p[0], p[0])), k, s).numpy()
+    assert not np.array_equal(zero_pad, y)
+
+
 def test_maxpool_tie_goes_to_first_tap():
     xp = np.zeros((1, 1, 2, 2))
     y, arg = layers.maxpool_valid(xp, (2, 2), (2, 2), (1, 1), (0, 0))
