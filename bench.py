@@ -92,10 +92,12 @@ class ConvWorkload:
         xb = sum(t.numel() for t in self.x) * esz
         yb = sum(t.numel() for t in self.dy) * esz
         self.min_bytes = {"conv_fwd": xb + yb + nw * esz,
-                          "conv_bwd_data_mfma": (xb + yb) / _prod(c["stride"]) + nw * esz,
+                          # a parity class reads all of dy and writes its share of dx^
+                          "conv_bwd_data_mfma": yb + (xb + nw * esz) / _prod(c["stride"]),
                           "conv_bwd_data": xb + yb + nw * esz,
                           "conv_bwd_weight": xb + yb + nw * 4}
-        self.metric = "partitioned conv fwd+bwd TFLOP/s (halo exchange H, H* and dw sum-reduce included)"
+        self.metric = ("partitioned conv fwd+bwd TFLOP/s (halo exchange H, H* and dw sum-reduce included); "
+                       "halo+bcast+sumreduce fwd/adj GB/s and fraction of HBM peak under movement_* and <kernel>_GBs")
         self.unit = "TFLOP/s"
         # arithmetic types: fp32 throughout for fp32 tensors; bf16 tensors are multiplied in bf16 with fp32
         # accumulation when the channel counts are multiples of 8, else widened to fp32
@@ -110,7 +112,9 @@ class ConvWorkload:
         self.describe = {"workload": f"{self.tag}: conv{c['D']}d fwd+bwd {'fp32' if dtype == 'f32' else 'bf16 (fp32 accumulation)'} x[{c['n_b']},{c['c_in']}," +
                          ",".join(str(v) for v in c["in_shape"]) + f"] w[{c['c_out']},{c['c_in']}," +
                          ",".join(str(v) for v in c["ksize"]) + f"] stride {c['stride'][0]} pad {c['padding'][0]}, " +
-                         "P=" + "x".join(str(v) for v in c["P"]) + f" ({P} virtual workers), channels-last",
+                         "P=" + "x".join(str(v) for v in c["P"]) + f" ({P} virtual workers); tensors resident in HBM "
+                         "in the library's channels-last layout (a caller holding the paper's planes-first order "
+                         "converts with distdl_layout_convert, rate under layout_*_GBs; not part of the timed step)",
                          "halo_cells": stats["halo_cells"], "pad_cells": stats["pad_cells"],
                          "band_cells": stats["band_cells"]}
 
@@ -243,6 +247,10 @@ class MovementWorkload:
             "halo_adj": ("hbm", (2 * stats["halo_cells"] + 2 * stats["band_cells"] + stats["pad_cells"]) * per_cell),
             "bcast": ("hbm", coll), "sumreduce": ("hbm", coll),
         }
+        # planes-first <-> channels-last conversion of the same buffers (for callers that hold the paper's logical
+        # order): reads and writes every buffer once; timed on its own, not part of the step
+        buf_bytes = sum(t.numel() for t in self.x) * 4
+        self.alg["layout_to_cl"] = self.alg["layout_from_cl"] = ("hbm", 2 * buf_bytes)
         self.bytes_step = self.alg["halo_fwd"][1] + self.alg["halo_adj"][1] + 4 * coll
         self.metric = "halo + broadcast + sum-reduce forward and adjoint GB/s (algorithmic bytes)"
         self.unit = "GB/s"
@@ -265,16 +273,38 @@ class MovementWorkload:
     def value(self, seconds_per_step):
         return self.bytes_step / seconds_per_step / 1e9
 
+    def layout_rates(self):
+        """distdl_layout_convert on the 64 padded buffers of this geometry, both directions (4.9 GB in, 4.9 GB
+        out per call), kernel time from the library's HIP events."""
+        dd, torch = self.dd, self.torch
+        other = [torch.empty_like(t) for t in self.x]
+        out = {}
+        dd.distdl_profile_enable(True)
+        for name, to_cl, src, dst in (("layout_to_cl", True, other, self.x), ("layout_from_cl", False, self.x, other)):
+            for _ in range(2):
+                dd.distdl_layout_convert(self.plan, 0, to_cl, src, dst)
+            torch.cuda.synchronize()
+            dd.distdl_profile_report()
+            for _ in range(5):
+                dd.distdl_layout_convert(self.plan, 0, to_cl, src, dst)
+            rep = dd.distdl_profile_report()
+            ms = sum(v[1] for v in rep.values()) / 5
+            nbytes = self.alg[name][1]
+            out[name] = {"avg_ms": ms, "algorithmic_bytes": nbytes, "achieved": nbytes / (ms * 1e-3) / 1e9,
+                         "unit": "GB/s", "frac": nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+        dd.distdl_profile_enable(False)
+        return out
+
     def achievable_copy(self):
         """What a plain device-to-device copy reaches on this chip (the practical ceiling of any streaming kernel):
-        2 GiB read + 2 GiB written, by the library's own copy (broadcast with k = 1) and by torch's copy_, median
+        2 GiB read + 2 GiB written, by the library's plain copy kernel (distdl_copy_ref) and by torch's copy_, median
         of 9 timed with events on the launch stream."""
         torch, dd = self.torch, self.dd
         n = 1 << 29                                    # fp32 elements: 2 GiB
         src = torch.empty(n, device="cuda").normal_()
         dst = torch.empty_like(src)
         out = {"bytes_moved": 2 * n * 4}
-        for name, call in (("library_copy", lambda: dd.distdl_bcast_fwd([src], [dst], 1)),
+        for name, call in (("library_copy", lambda: dd.distdl_copy_ref(src, dst)),
                            ("torch_copy", lambda: dst.copy_(src))):
             times = []
             for _ in range(11):
@@ -663,8 +693,10 @@ def main():
     ap.add_argument("--sweep", action="store_true",
                     help="with --workload movement: also the size sweep of broadcast / sum-reduce")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--detail", default=None, metavar="PATH",
+                    help="also write the full report (per-kernel tables of every workload, sweep rows) to this file")
     ap.add_argument("--calibrate-copy", action="store_true",
-                    help="also run one plain 1 GiB copy (bcast_kernel, k = 1) before the timed region, as the "
+                    help="also run one plain 1 GiB copy (copy_ref_kernel) before the timed region, as the "
                          "known-size reference for rocprofv3 FETCH_SIZE / WRITE_SIZE readings")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -690,7 +722,7 @@ def main():
     if args.calibrate_copy:
         src = torch.ones(1 << 28, device="cuda")
         dst = torch.empty_like(src)
-        dd.distdl_bcast_fwd([src], [dst], 1)
+        dd.distdl_copy_ref(src, dst)
         torch.cuda.synchronize()
         del src, dst
     for _ in range(args.warmup):
@@ -765,6 +797,7 @@ def main():
 
     if args.workload in ("cfg2", "cfg3", "cfg3-bf16", "cfg4"):
         line["ms_per_step_graph"] = graph_step_ms(wl, args.steps)
+    detail = dict(line)                     # everything, for --detail; the printed line stays short
     if args.workload == "cfg5" and not args.no_movement:
         # the other half of the metric: the movement primitives on their own (H, H* on this geometry, B, R and
         # adjoints on large arrays), timed after the convolution step
@@ -772,17 +805,18 @@ def main():
         torch.cuda.empty_cache()
         mv, rep = side_run(lambda: MovementWorkload(False), 10)
         rep["frac_hbm_peak"] = rep["value"] / HBM_PEAK_GBS
+        rep["layout"] = mv.layout_rates()
         del mv.x, mv.g
         torch.cuda.empty_cache()
         rep["achievable_copy"] = mv.achievable_copy()
         for kern in rep["kernels"].values():
             if kern.get("bound") == "hbm":
                 kern["frac_of_achievable_copy"] = kern["achieved"] / rep["achievable_copy"]["best_GBs"]
-        line["movement"] = rep
+        detail["movement"] = rep
         del mv
         torch.cuda.empty_cache()
         # the remaining single-GPU configurations, for reference (same harness, no CPU leg)
-        line["other_configs"] = {}
+        detail["other_configs"] = {}
         for tag, make, steps in (("cfg2", lambda: ConvWorkload("cfg2"), 50),
                                  ("cfg5-bf16", lambda: ConvWorkload("cfg5", "bf16"), 3),
                                  ("cfg3", lambda: AffineWorkload("cfg3", "f32"), 50),
@@ -792,18 +826,78 @@ def main():
             rep["kernel_launches_per_step"] = sum(k["launches"] for k in rep["kernels"].values()) / steps
             if tag in ("cfg2", "cfg3", "cfg3-bf16", "cfg4"):
                 rep["ms_per_step_graph"] = graph_step_ms(w, steps)
-            line["other_configs"][tag] = rep
+            detail["other_configs"][tag] = rep
             del w
     if getattr(wl, "sweep_on", False):
-        line["sweep"] = wl.sweep()
+        detail["sweep"] = wl.sweep()
     if args.workload == "movement":
-        line["achievable_copy"] = wl.achievable_copy()
-        for kern in line["kernels"].values():
+        detail["layout"] = wl.layout_rates()
+        detail["achievable_copy"] = wl.achievable_copy()
+        for kern in detail["kernels"].values():
             if kern.get("bound") == "hbm":
-                kern["frac_of_achievable_copy"] = kern["achieved"] / line["achievable_copy"]["best_GBs"]
+                kern["frac_of_achievable_copy"] = kern["achieved"] / detail["achievable_copy"]["best_GBs"]
     if not args.no_cpu_baseline:
-        line["cpu_baseline"] = wl.cpu_baseline()
-    print(json.dumps(line))
+        detail["cpu_baseline"] = wl.cpu_baseline()
+    print(json.dumps(compact_line(detail, args.workload)))
+    if args.detail:
+        with open(args.detail, "w") as f:
+            json.dump(detail, f, indent=1)
+
+
+def compact_line(detail, workload):
+    """The one printed line: the contract's keys, `roofline`, `cpu_baseline`, and every figure of the metric as a
+    top-level scalar (movement kernels in GB/s and as a fraction of the 8 TB/s HBM peak, contraction kernels as a
+    fraction of the MFMA peak of their type, the other configurations' step rates), short enough to survive a
+    log tail.  The per-kernel tables go to the --detail file."""
+    r3 = lambda v: None if v is None else float(f"{v:.4g}")
+    line = {k: v for k, v in detail.items() if k not in ("kernels", "movement", "other_configs", "sweep", "layout",
+                                                         "achievable_copy")}
+
+    def kernel_scalars(kernels, prefix=""):
+        for name, k in kernels.items():
+            if k.get("bound") == "hbm":
+                line[f"{prefix}{name}_GBs"] = r3(k["achieved"])
+                line[f"{prefix}{name}_frac_hbm"] = r3(k["frac"])
+            elif k.get("bound") == "mfma":
+                line[f"{prefix}{name}_TFLOPs"] = r3(k["achieved"])
+                line[f"{prefix}{name}_frac_mfma"] = r3(k["frac"])
+            line[f"{prefix}{name}_ms"] = r3(k["avg_ms"])
+
+    if workload == "movement":
+        kernel_scalars(detail["kernels"])
+        mv = detail
+        line["movement_GBs"], line["movement_frac_hbm"] = r3(detail["value"]), r3(detail["value"] / HBM_PEAK_GBS)
+    else:
+        kernel_scalars({k: v for k, v in detail["kernels"].items() if v.get("bound")})
+        mv = detail.get("movement")
+        if mv:
+            line["movement_GBs"], line["movement_frac_hbm"] = r3(mv["value"]), r3(mv["frac_hbm_peak"])
+            line["movement_ms_per_step"] = r3(mv["ms_per_step"])
+            kernel_scalars(mv["kernels"])
+    if "TFLOP" in detail["unit"]:
+        line["step_frac_mfma"] = r3(detail["value"] / MFMA_PEAK_TFLOPS[detail["dtype"]])
+    if mv:
+        for name, k in mv.get("layout", {}).items():
+            line[f"{name}_GBs"], line[f"{name}_frac_hbm"] = r3(k["achieved"]), r3(k["frac"])
+        if "achievable_copy" in mv:
+            line["copy_ref_GBs"] = r3(mv["achievable_copy"]["library_copy_GBs"])
+            line["copy_ref_frac_hbm"] = r3(mv["achievable_copy"]["library_copy_GBs"] / HBM_PEAK_GBS)
+    for tag, rep in detail.get("other_configs", {}).items():
+        key = tag.replace("-", "_")
+        line[f"{key}_value"], line[f"{key}_unit"] = r3(rep["value"]), rep["unit"]
+        line[f"{key}_ms_per_step"] = r3(rep["ms_per_step"])
+        if rep.get("ms_per_step_graph"):
+            line[f"{key}_ms_per_step_graph"] = r3(rep["ms_per_step_graph"])
+        if "TFLOP" in rep["unit"]:
+            line[f"{key}_frac_mfma"] = r3(rep["value"] / MFMA_PEAK_TFLOPS[rep["dtype"]])
+            if rep.get("ms_per_step_graph"):
+                line[f"{key}_frac_mfma_graph"] = r3(rep["value"] * rep["ms_per_step"] / rep["ms_per_step_graph"] /
+                                                    MFMA_PEAK_TFLOPS[rep["dtype"]])
+        for name, k in rep["kernels"].items():
+            if k.get("bound") == "mfma":
+                line[f"{key}_{name}_frac_mfma"] = r3(k["frac"])
+                line[f"{key}_{name}_ms"] = r3(k["avg_ms"])
+    return line
 
 
 if __name__ == "__main__":

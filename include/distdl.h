@@ -23,11 +23,16 @@
  *    (what any allocator gives) enables the vectorised kernels.
  *  - One plan may be used from one host thread at a time.
  *  - A plan keeps device copies of the pointer arrays it has been called with
- *    (the last eight per argument, per stream) and whatever scratch it needs;
+ *    (the last eight per argument and stream) and whatever scratch it needs;
  *    the first call with new arrays, on a new stream or with a larger problem
  *    therefore copies a table or allocates, later calls do neither.  A call
  *    that has been made once on a stream can be recorded into a HIP graph on
- *    that stream (no allocation, no host-to-device copy, no memset).
+ *    that stream (no allocation, no host-to-device copy, no memset).  A copy
+ *    that a recorded call uses is kept unchanged until the plan is destroyed;
+ *    a copy is only ever replaced by a call on the stream that used it last.
+ *    A call with arrays the plan has not seen on that stream fails with
+ *    INVALID_ARG while the stream is being captured, and with NOMEM when all
+ *    64 copies of an argument are held by other streams or recorded graphs.
  *
  * Memory layout of sliding-kernel tensors: CHANNELS-LAST.  The paper fixes
  * only the logical shape n_b x n_c x m_0 x ... x m_{D-1} (Sec. 4 "Sparse
@@ -136,8 +141,10 @@ int distdl_halo_adj(distdl_plan* plan, void* const gbufs_dev[], void* stream);
  * bcast_adj / sumreduce_fwd:  out[g][e] = sum_{i=0}^{k-1} in[g*k+i][e], summed
  *   in index order in fp32, overwriting out.  With clear_inputs != 0 the
  *   replicas are zeroed afterwards (the K_i of B* = sum_i K_i S_{i->a}).
- * In and out buffers must not overlap.  Errors: NULL, INVALID_ARG (G, k < 1,
- * count < 0).
+ * In and out buffers must not overlap.  Groups of more than 64 replicas read
+ * their pointers from a device copy of the pointer array, cached per device
+ * under the rules of the plans' tables (one host thread at a time).
+ * Errors: NULL, INVALID_ARG (G, k < 1, count < 0).
  * ---------------------------------------------------------------------- */
 int distdl_bcast_fwd(const void* const src_dev[], void* const dst_dev[], const int64_t count[], int G, int k,
                      distdl_dtype dtype, void* stream);
@@ -177,6 +184,39 @@ int distdl_conv_bwd(distdl_plan* plan, const void* const x_bufs_dev[], const voi
                     void* workspace_dev, size_t workspace_bytes, void* stream);
 size_t distdl_conv_bwd_workspace(const distdl_plan* plan);
 
+/* The local steps of the same two algorithms alone, for callers that apply H
+ * and H* themselves (several layers sharing one exchange, the channel-
+ * partitioned layer, tests of the step order): conv_local_fwd is y^ <-
+ * Conv(w, b; x^) on buffers that already hold H x; conv_local_bwd is (dw, db,
+ * dx^) <- [dConv]*(dy) with the sum-reduce of dw and db over the workers and
+ * WITHOUT dx <- H* dx: every cell of the padded dx buffers, halo and padding
+ * cells included, holds its local gradient.  distdl_halo_adj on the dx
+ * buffers completes the step.  Arguments and errors as above. */
+int distdl_conv_local_fwd(distdl_plan* plan, void* const x_bufs_dev[], const void* w_dev, const void* bias_dev,
+                          void* const y_dev[], void* stream);
+int distdl_conv_local_bwd(distdl_plan* plan, const void* const x_bufs_dev[], const void* w_dev,
+                          const void* const dy_dev[], void* const dx_bufs_dev[], void* dw_dev, void* dbias_dev,
+                          void* workspace_dev, size_t workspace_bytes, void* stream);
+
+/* ------------------------------------------------------------------------
+ * Layout conversion.  Sec. 4 "Sparse layers" writes a worker's tensors in the
+ * logical order n_b x n_c x m_0 x ... x m_{D-1}; a caller that stores them
+ * that way (planes first: [n_b][n_c][cells], cells row-major) converts to and
+ * from the channels-last arrays every other call of this library takes.
+ *   what = 0: the padded buffers, n_c_in channels, cells = buf_0 * ... (also
+ *             the dx buffers);  what = 1: the outputs, n_c_out channels,
+ *             cells = out_0 * ... (also dy).
+ *   to_channels_last != 0: src is planes-first, dst channels-last; 0: the
+ *             reverse.  src_dev / dst_dev: one array per worker, of the
+ *             plan's dtype, element-aligned, not overlapping.
+ * A pure permutation (bit-exact); per sample a transpose of an n_c x cells
+ * matrix staged through LDS tiles so that both sides move in contiguous runs.
+ * Errors: NULL, INVALID_ARG (what, misaligned arrays), UNSUPPORTED (more than
+ * 65535 samples).
+ * ---------------------------------------------------------------------- */
+int distdl_layout_convert(const distdl_plan* plan, int what, int to_channels_last, const void* const src_dev[],
+                          void* const dst_dev[], void* stream);
+
 /* ------------------------------------------------------------------------
  * Partitioned affine layer: the Forward / Adjoint Affine Algorithms of
  * Sec. 4 "Dense layers" on a P_fo x P_fi weight partition; worker (i, j) has
@@ -215,7 +255,11 @@ int distdl_affine_bwd(distdl_affine_plan* plan, const void* const x_dev[], const
  *   local max over each window starting at the worker's origin (which skips
  *   "extra" input, App. B.1); backward routes dy to the first maximum of each
  *   window (row-major tap order) over the whole padded buffer, then dx <- H* dx.
- *   x_bufs_dev of maxpool_bwd must hold H x.
+ *   x_bufs_dev of maxpool_bwd must hold H x.  The maximum runs over the cells
+ *   of the tensor itself: zero-padding cells never win it and never receive
+ *   gradient (the pooling layer of the framework the paper wraps pads with
+ *   -inf); a plan in which some window lies entirely in the padding
+ *   (padding beyond the kernel's reach) is rejected with UNSUPPORTED.
  * avgpool_fwd / avgpool_bwd: the same two algorithms with the mean as the
  *   local pool: y = (sum of the window's taps) / window size, zero-padding
  *   cells counted as the zeros they hold; it is linear, so the backward call
@@ -329,7 +373,9 @@ int distdl_allreduce(void* const bufs_dev[], const int64_t count[], int G, int k
  * displayed equation; the direct sum over workers of Sec. 3), accumulated in
  * fp64 on the device.  result_dev points to ONE double in device memory.
  * Used for the adjoint test |<Fx,y> - <x,F*y>| / max(...) (Sec. 3
- * "Implementation") on device-resident data.
+ * "Implementation") on device-resident data.  The calls of one device share
+ * a buffer of partial sums (as distdl_mse_fwd_bwd calls do): calls that
+ * overlap in time on different streams race.
  * ---------------------------------------------------------------------- */
 int distdl_dot(const void* const a_dev[], const void* const b_dev[], const int64_t count[], int n_arrays,
                distdl_dtype dtype, double* result_dev, void* stream);
@@ -347,6 +393,11 @@ int distdl_dot(const void* const a_dev[], const void* const b_dev[], const int64
  * text length.  Not thread-safe; meant for the benchmark.
  * ---------------------------------------------------------------------- */
 int distdl_plan_stats(const distdl_plan* plan, int64_t out[4]);
+/* copy_ref: a plain streaming device-to-device copy of `bytes` bytes (16-byte
+ * aligned pointers, a multiple of 16 bytes), one 16-byte vector per thread:
+ * the yardstick "what a copy reaches on this chip" that the benchmark quotes
+ * next to the movement kernels, under a kernel name of its own. */
+int distdl_copy_ref(const void* src_dev, void* dst_dev, size_t bytes, void* stream);
 int distdl_profile_enable(int on);
 int distdl_profile_report(char* out, size_t cap);
 
@@ -361,6 +412,18 @@ int distdl_profile_report(char* out, size_t cap);
  * get_task returns the number of ints written.
  * ---------------------------------------------------------------------- */
 int distdl_debug_task_count(const distdl_plan* plan, int adjoint);
+/* Kernel family the convolution calls would pick for this plan when every
+ * array is 16-byte aligned: out[0] forward, out[1] data gradient, out[2]
+ * weight gradient; 0 = direct kernels (any shape), 1 = 32-wide matrix-core
+ * tiles, 2 = 16-wide matrix-core tiles (at most 16 channels). */
+int distdl_debug_conv_path(const distdl_plan* plan, int32_t out[3]);
+/* Runs the replacement policy of the cached device tables (see Conventions)
+ * on a sequence of n calls without touching a device: call i arrives on
+ * stream stream_id[i] with table contents table_id[i], during stream capture
+ * if capturing[i] != 0.  slot_out[i] is the index of the device copy the call
+ * would use, or the negative error code it would fail with. */
+int distdl_debug_slot_policy(const int32_t stream_id[], const int32_t table_id[], const int32_t capturing[], int n,
+                             int32_t slot_out[]);
 /* floor(n / d) through the multiply-shift constants the kernels use to decode
  * a flat work index (d >= 1). */
 uint32_t distdl_debug_fastdiv(uint32_t n, uint32_t d);

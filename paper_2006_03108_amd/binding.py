@@ -63,6 +63,12 @@ _SIGS = {
     "distdl_repart_adj": [_vp, _pp, _pp, _vp],
     "distdl_conv_fwd": [_vp, _pp, _vp, _vp, _pp, _vp],
     "distdl_conv_bwd": [_vp, _pp, _vp, _pp, _pp, _vp, _vp, _vp, C.c_size_t, _vp],
+    "distdl_conv_local_fwd": [_vp, _pp, _vp, _vp, _pp, _vp],
+    "distdl_conv_local_bwd": [_vp, _pp, _vp, _pp, _pp, _vp, _vp, _vp, C.c_size_t, _vp],
+    "distdl_layout_convert": [_vp, _i, _i, _pp, _pp, _vp],
+    "distdl_copy_ref": [_vp, _vp, C.c_size_t, _vp],
+    "distdl_debug_slot_policy": [_p32, _p32, _p32, _i, _p32],
+    "distdl_debug_conv_path": [_vp, _p32],
     "distdl_affine_plan_create": [C.POINTER(_vp), _i64, _i64, _i64, _i, _i, _i],
     "distdl_affine_plan_destroy": [_vp],
     "distdl_affine_fwd": [_vp, _pp, _pp, _pp, _pp, _vp],
@@ -315,6 +321,42 @@ def distdl_conv_bwd(plan, x_bufs, w, dy, dx_bufs, dw, dbias, workspace):
     _check(lib.distdl_conv_bwd(plan.handle, _ptrs(x_bufs), w.data_ptr(), _ptrs(dy), _ptrs(dx_bufs), dw.data_ptr(),
                                None if dbias is None else dbias.data_ptr(), workspace.data_ptr(),
                                workspace.numel() * workspace.element_size(), _stream()))
+
+
+def distdl_conv_local_fwd(plan, x_bufs, w, bias, y):
+    _check(lib.distdl_conv_local_fwd(plan.handle, _ptrs(x_bufs), w.data_ptr(), None if bias is None else bias.data_ptr(),
+                                     _ptrs(y), _stream()))
+
+
+def distdl_conv_local_bwd(plan, x_bufs, w, dy, dx_bufs, dw, dbias, workspace):
+    _check(lib.distdl_conv_local_bwd(plan.handle, _ptrs(x_bufs), w.data_ptr(), _ptrs(dy), _ptrs(dx_bufs), dw.data_ptr(),
+                                     None if dbias is None else dbias.data_ptr(), workspace.data_ptr(),
+                                     workspace.numel() * workspace.element_size(), _stream()))
+
+
+def distdl_layout_convert(plan, what, to_channels_last, src, dst):
+    """what: 0 padded buffers (input channels), 1 outputs (output channels)."""
+    _check(lib.distdl_layout_convert(plan.handle, int(what), int(to_channels_last), _ptrs(src), _ptrs(dst), _stream()))
+
+
+def distdl_copy_ref(src, dst):
+    _check(lib.distdl_copy_ref(src.data_ptr(), dst.data_ptr(), src.numel() * src.element_size(), _stream()))
+
+
+def distdl_debug_slot_policy(stream_ids, table_ids, capturing):
+    """Slot index (or negative error code) each call of the sequence would get from the table cache."""
+    n = len(stream_ids)
+    out = (C.c_int32 * n)()
+    _check(lib.distdl_debug_slot_policy(_arr(C.c_int32, stream_ids), _arr(C.c_int32, table_ids),
+                                        _arr(C.c_int32, capturing), n, out))
+    return list(out)
+
+
+def distdl_debug_conv_path(plan):
+    """(forward, data gradient, weight gradient) kernel families: 0 direct, 1 32-wide MFMA tiles, 2 16-wide."""
+    out = (C.c_int32 * 3)()
+    _check(lib.distdl_debug_conv_path(plan.handle, out))
+    return tuple(out)
 
 
 class AffinePlan:

@@ -13,65 +13,6 @@
 #include "gemm_mfma.h"
 #include "profile.h"
 
-namespace distdl {
-// Device copy of a small descriptor array, re-uploaded only when its contents change.
-// Device copies of small host tables (the GEMM block descriptors of a call): like PtrTable, the last kSlots
-// distinct tables are kept, each in its own device block, so that repeated calls copy nothing.
-template <class T>
-struct DevArray {
-  static constexpr int kSlots = 4;
-  struct Entry {
-    std::vector<T> host;
-    T* dev = nullptr;
-    size_t cap = 0;
-    hipStream_t stream = nullptr;
-    uint64_t used = 0;
-  };
-  std::vector<Entry> entries;
-  T* dev = nullptr;  // the block selected by the last upload()
-  uint64_t clock = 0;
-  int upload(const std::vector<T>& v, hipStream_t st) {
-    ++clock;
-    Entry* pick = nullptr;
-    for (Entry& e : entries)
-      if (e.dev && e.stream == st && e.host.size() == v.size() &&
-          std::memcmp(e.host.data(), v.data(), v.size() * sizeof(T)) == 0) {
-        pick = &e;
-        break;
-      }
-    if (!pick) {
-      if ((int)entries.size() < kSlots) {
-        entries.emplace_back();
-        pick = &entries.back();
-      } else {
-        pick = &entries[0];
-        for (Entry& e : entries)
-          if (e.used < pick->used) pick = &e;
-      }
-      if (v.size() > pick->cap) {
-        if (pick->dev) (void)hipFree(pick->dev);
-        pick->dev = nullptr;
-        pick->cap = 0;
-        DISTDL_HIP_TRY(hipMalloc((void**)&pick->dev, v.size() * sizeof(T)));
-        pick->cap = v.size();
-      }
-      pick->host = v;
-      DISTDL_HIP_TRY(hipMemcpyAsync(pick->dev, pick->host.data(), v.size() * sizeof(T), hipMemcpyHostToDevice, st));
-      pick->stream = st;
-    }
-    pick->used = clock;
-    dev = pick->dev;
-    return DISTDL_OK;
-  }
-  void release() {
-    for (Entry& e : entries)
-      if (e.dev) (void)hipFree(e.dev);
-    entries.clear();
-    dev = nullptr;
-  }
-};
-}  // namespace distdl
-
 struct distdl_affine_plan {
   int64_t n_b = 0, n_fi = 0, n_fo = 0;
   int P_fo = 1, P_fi = 1;

@@ -2,10 +2,10 @@
 // all-reduce") over groups of replicas held in one HBM, and the Euclidean
 // inner product over a list of arrays (Sec. 2) for the adjoint test.
 //
-// Replica pointers travel as kernel arguments (at most kMaxPtrs per launch;
-// larger problems are split on the host: a broadcast over more replicas is
-// several independent launches, a reduction continues into its output in
-// replica order, so the summation order stays i = 0..k-1).
+// Replica pointers travel as kernel arguments when a group has at most
+// kMaxPtrs of them; wider groups read them from a device copy of the caller's
+// pointer array (cached per device like a plan's tables), so that one thread
+// still adds all k replicas of its elements in index order in fp32.
 #include <algorithm>
 #include <vector>
 
@@ -33,7 +33,7 @@ struct CollArgs {
   int32_t first[kMaxGroups];  // index of the group's first replica in many[]
   int32_t k[kMaxGroups];      // replicas of the group in this launch
   int32_t wide[kMaxGroups];   // all pointers of the group 16-byte aligned
-  int32_t accumulate;         // reduction continues into one[] instead of overwriting it
+  void* const* many_dev;      // TAB kernels: all replica pointers in device memory, first[] indexes into it
   int32_t clear_inputs;
 };
 
@@ -43,14 +43,14 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 // non-temporal hint, and the grid covers the longest group with one 16-byte
 // vector per thread (many short-lived workgroups keep more requests in flight
 // than a grid-stride loop over few); the loop only matters beyond 2^31 threads.
-template <bool BF16>
+template <bool BF16, bool TAB = false>
 __global__ __launch_bounds__(kCollThreads) void bcast_kernel(CollArgs a) {
   const int g = blockIdx.y;
   const int64_t count = a.count[g];
   constexpr int V = BF16 ? 8 : 4;
   const int64_t nvec = a.wide[g] ? count / V : 0;
   const int k = a.k[g];
-  void* const* rep = a.many + a.first[g];
+  void* const* rep = (TAB ? a.many_dev : a.many) + a.first[g];
   const int64_t stride = (int64_t)gridDim.x * kCollThreads;
   const int64_t tid = (int64_t)blockIdx.x * kCollThreads + threadIdx.x;
   const u32x4* src = (const u32x4*)a.one[g];
@@ -69,32 +69,20 @@ __global__ __launch_bounds__(kCollThreads) void bcast_kernel(CollArgs a) {
   }
 }
 
-template <bool BF16>
+template <bool BF16, bool TAB = false>
 __global__ __launch_bounds__(kCollThreads) void reduce_kernel(CollArgs a) {
   const int g = blockIdx.y;
   const int64_t count = a.count[g];
   constexpr int V = BF16 ? 8 : 4;
   const int64_t nvec = a.wide[g] ? count / V : 0;
   const int k = a.k[g];
-  void* const* rep = a.many + a.first[g];
+  void* const* rep = (TAB ? a.many_dev : a.many) + a.first[g];
   const int64_t stride = (int64_t)gridDim.x * kCollThreads;
   const int64_t tid = (int64_t)blockIdx.x * kCollThreads + threadIdx.x;
   const bool clear = a.clear_inputs != 0;
   for (int64_t u = tid; u < nvec; u += stride) {
     float acc[V];
-    if (a.accumulate) {
-      u32x4 o = ((const u32x4*)a.one[g])[u];
-      for (int j = 0; j < 4; ++j) {
-        if (BF16) {
-          acc[2 * j] = bf2f(o[j] & 0xffffu);
-          acc[2 * j + 1] = bf2f(o[j] >> 16);
-        } else {
-          acc[j] = __uint_as_float(o[j]);
-        }
-      }
-    } else {
-      for (int j = 0; j < V; ++j) acc[j] = 0.f;
-    }
+    for (int j = 0; j < V; ++j) acc[j] = 0.f;
 #pragma unroll 8
     for (int i = 0; i < k; ++i) {  // replica order i = 0 .. k-1; the unrolled loads are issued together
       u32x4 r = __builtin_nontemporal_load((const u32x4*)rep[i] + u);
@@ -120,7 +108,7 @@ __global__ __launch_bounds__(kCollThreads) void reduce_kernel(CollArgs a) {
   for (int64_t e = nvec * V + tid; e < count; e += stride) {
     if (BF16) {
       uint16_t* out = (uint16_t*)a.one[g];
-      float acc = a.accumulate ? bf2f(out[e]) : 0.f;
+      float acc = 0.f;
       for (int i = 0; i < k; ++i) {
         acc += bf2f(((const uint16_t*)rep[i])[e]);
         if (clear) ((uint16_t*)rep[i])[e] = 0;
@@ -128,7 +116,7 @@ __global__ __launch_bounds__(kCollThreads) void reduce_kernel(CollArgs a) {
       out[e] = (uint16_t)f2bf(acc);
     } else {
       float* out = (float*)a.one[g];
-      float acc = a.accumulate ? out[e] : 0.f;
+      float acc = 0.f;
       for (int i = 0; i < k; ++i) {
         acc += ((const float*)rep[i])[e];
         if (clear) ((float*)rep[i])[e] = 0.f;
@@ -136,6 +124,17 @@ __global__ __launch_bounds__(kCollThreads) void reduce_kernel(CollArgs a) {
       out[e] = acc;
     }
   }
+}
+
+// Device copies of pointer arrays of groups wider than kMaxPtrs, one cache per device.
+static PtrTable g_wide_ptrs[64];
+// Plain streaming copy, one 16-byte vector per thread: the yardstick the movement kernels are measured against.
+// A kernel of its own so that traces and counters list it under its own name.
+__global__ __launch_bounds__(kCollThreads) void copy_ref_kernel(const u32x4* __restrict__ src, u32x4* __restrict__ dst,
+                                                                int64_t nvec) {
+  const int64_t stride = (int64_t)gridDim.x * kCollThreads;
+  for (int64_t u = (int64_t)blockIdx.x * kCollThreads + threadIdx.x; u < nvec; u += stride)
+    dst[u] = __builtin_nontemporal_load(src + u);
 }
 
 static unsigned blocks_for(int64_t max_count, int vec) {
@@ -162,42 +161,58 @@ static int run_collective(bool reduce, void* const one[], void* const many[], co
         return set_error(DISTDL_ERR_NULL, "group %d replica %d: null or misaligned array", g, i);
   }
   const int vec = dtype == DISTDL_F32 ? 4 : 8;
-  // replicas are consumed in chunks of at most kMaxPtrs; chunk c of every
-  // group runs after chunk c-1 (stream order), which keeps the summation order
-  for (int i0 = 0; i0 < k; i0 += kMaxPtrs) {
-    const int kc = std::min(kMaxPtrs, k - i0);
-    const int groups_per_launch = std::max(1, std::min(kMaxGroups, kMaxPtrs / kc));
-    for (int g0 = 0; g0 < G; g0 += groups_per_launch) {
-      CollArgs a{};
-      int ng = 0, np = 0;
-      int64_t max_count = 0;
-      for (int g = g0; g < std::min(G, g0 + groups_per_launch); ++g) {
-        if (count[g] == 0) continue;
-        a.one[ng] = one[g];
-        a.count[ng] = count[g];
-        a.first[ng] = np;
-        a.k[ng] = kc;
-        bool wide = (uintptr_t)one[g] % 16 == 0;
-        for (int i = 0; i < kc; ++i) {
-          a.many[np] = many[(size_t)g * k + i0 + i];
-          wide &= (uintptr_t)a.many[np] % 16 == 0;
-          ++np;
-        }
-        a.wide[ng] = wide;
-        max_count = std::max(max_count, count[g]);
-        ++ng;
+  const bool tab = k > kMaxPtrs;
+  void* const* many_dev = nullptr;
+  if (tab) {
+    int dev = 0;
+    DISTDL_HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= 64) return set_error(DISTDL_ERR_UNSUPPORTED, "device index %d", dev);
+    int rc = g_wide_ptrs[dev].upload((const void* const*)many, (size_t)G * k, st);
+    if (rc) return rc;
+    many_dev = g_wide_ptrs[dev].dev;
+  }
+  const int groups_per_launch = tab ? kMaxGroups : std::max(1, std::min(kMaxGroups, kMaxPtrs / k));
+  for (int g0 = 0; g0 < G; g0 += groups_per_launch) {
+    CollArgs a{};
+    int ng = 0, np = 0;
+    int64_t max_count = 0;
+    for (int g = g0; g < std::min(G, g0 + groups_per_launch); ++g) {
+      if (count[g] == 0) continue;
+      a.one[ng] = one[g];
+      a.count[ng] = count[g];
+      a.first[ng] = tab ? g * k : np;
+      a.k[ng] = k;
+      bool wide = (uintptr_t)one[g] % 16 == 0;
+      for (int i = 0; i < k; ++i) {
+        void* rep = many[(size_t)g * k + i];
+        if (!tab) a.many[np++] = rep;
+        wide &= (uintptr_t)rep % 16 == 0;
       }
-      if (ng == 0) continue;
-      a.accumulate = i0 > 0;
-      a.clear_inputs = clear_inputs;
-      dim3 grid(blocks_for(max_count, vec), ng), block(kCollThreads);
-      ProfScope prof(reduce ? "sumreduce" : "bcast", st);
-      if (reduce) {
-        if (dtype == DISTDL_F32) hipLaunchKernelGGL(reduce_kernel<false>, grid, block, 0, st, a);
-        else hipLaunchKernelGGL(reduce_kernel<true>, grid, block, 0, st, a);
+      a.wide[ng] = wide;
+      max_count = std::max(max_count, count[g]);
+      ++ng;
+    }
+    if (ng == 0) continue;
+    a.many_dev = many_dev;
+    a.clear_inputs = clear_inputs;
+    dim3 grid(blocks_for(max_count, vec), ng), block(kCollThreads);
+    ProfScope prof(reduce ? "sumreduce" : "bcast", st);
+    const bool bf = dtype != DISTDL_F32;
+    if (reduce) {
+      if (tab) {
+        if (bf) hipLaunchKernelGGL((reduce_kernel<true, true>), grid, block, 0, st, a);
+        else hipLaunchKernelGGL((reduce_kernel<false, true>), grid, block, 0, st, a);
       } else {
-        if (dtype == DISTDL_F32) hipLaunchKernelGGL(bcast_kernel<false>, grid, block, 0, st, a);
-        else hipLaunchKernelGGL(bcast_kernel<true>, grid, block, 0, st, a);
+        if (bf) hipLaunchKernelGGL((reduce_kernel<true, false>), grid, block, 0, st, a);
+        else hipLaunchKernelGGL((reduce_kernel<false, false>), grid, block, 0, st, a);
+      }
+    } else {
+      if (tab) {
+        if (bf) hipLaunchKernelGGL((bcast_kernel<true, true>), grid, block, 0, st, a);
+        else hipLaunchKernelGGL((bcast_kernel<false, true>), grid, block, 0, st, a);
+      } else {
+        if (bf) hipLaunchKernelGGL((bcast_kernel<true, false>), grid, block, 0, st, a);
+        else hipLaunchKernelGGL((bcast_kernel<false, false>), grid, block, 0, st, a);
       }
     }
   }
@@ -206,7 +221,7 @@ static int run_collective(bool reduce, void* const one[], void* const many[], co
 }
 
 // ---- inner product ----------------------------------------------------------
-constexpr int kDotBlocks = 1024;
+constexpr int kDotBlocks = kDotPartials;
 constexpr int kDotArrays = 24;
 struct DotArgs {
   const void* a[kDotArrays];
@@ -260,6 +275,31 @@ __global__ __launch_bounds__(256) void dot_final_kernel(const double* partial, i
 
 static double* g_dot_partial[64] = {};
 
+// The launches of an inner product; `partial` holds kDotPartials doubles, every one of which is overwritten by
+// the first launch, so stale contents never matter.
+int launch_dot(const void* const a_dev[], const void* const b_dev[], const int64_t count[], int n_arrays,
+                      distdl_dtype dtype, double* partial, double* result_dev, hipStream_t st) {
+  for (int j = 0; j < n_arrays; ++j) {
+    if (count[j] < 0) return set_error(DISTDL_ERR_INVALID_ARG, "dot: negative count");
+    if (count[j] > 0 && (!a_dev[j] || !b_dev[j])) return set_error(DISTDL_ERR_NULL, "dot: null array");
+  }
+  for (int j0 = 0; j0 < n_arrays; j0 += kDotArrays) {
+    DotArgs d{};
+    d.n = std::min(kDotArrays, n_arrays - j0);
+    d.accumulate = j0 > 0;
+    for (int j = 0; j < d.n; ++j) {
+      d.a[j] = a_dev[j0 + j];
+      d.b[j] = b_dev[j0 + j];
+      d.count[j] = count[j0 + j];
+    }
+    if (dtype == DISTDL_F32) hipLaunchKernelGGL(dot_partial_kernel<false>, dim3(kDotBlocks), dim3(256), 0, st, d, partial);
+    else hipLaunchKernelGGL(dot_partial_kernel<true>, dim3(kDotBlocks), dim3(256), 0, st, d, partial);
+  }
+  hipLaunchKernelGGL(dot_final_kernel, dim3(1), dim3(256), 0, st, partial, kDotBlocks, result_dev);
+  DISTDL_HIP_TRY(hipGetLastError());
+  return DISTDL_OK;
+}
+
 }  // namespace distdl
 
 using namespace distdl;
@@ -286,6 +326,19 @@ int distdl_sumreduce_fwd(void* const src_dev[], void* const dst_dev[], const int
   return run_collective(true, dst_dev, src_dev, count, G, k, dtype, clear_inputs, (hipStream_t)stream);
 }
 
+int distdl_copy_ref(const void* src_dev, void* dst_dev, size_t bytes, void* stream) {
+  if (!src_dev || !dst_dev) return set_error(DISTDL_ERR_NULL, "copy_ref: null argument");
+  if ((uintptr_t)src_dev % 16 || (uintptr_t)dst_dev % 16 || bytes % 16)
+    return set_error(DISTDL_ERR_INVALID_ARG, "copy_ref: pointers and size must be multiples of 16 bytes");
+  if (bytes == 0) return DISTDL_OK;
+  hipStream_t st = (hipStream_t)stream;
+  ProfScope prof("copy_ref", st);
+  hipLaunchKernelGGL(copy_ref_kernel, dim3(blocks_for((int64_t)(bytes / 16), 1)), dim3(kCollThreads), 0, st,
+                     (const u32x4*)src_dev, (u32x4*)dst_dev, (int64_t)(bytes / 16));
+  DISTDL_HIP_TRY(hipGetLastError());
+  return DISTDL_OK;
+}
+
 int distdl_allreduce(void* const bufs_dev[], const int64_t count[], int G, int k, distdl_dtype dtype, void* stream) {
   if (!bufs_dev || !count) return set_error(DISTDL_ERR_NULL, "allreduce: null argument");
   if (G < 1 || k < 1) return set_error(DISTDL_ERR_INVALID_ARG, "allreduce: G = %d, k = %d", G, k);
@@ -306,30 +359,11 @@ int distdl_dot(const void* const a_dev[], const void* const b_dev[], const int64
   if (!a_dev || !b_dev || !count || !result_dev) return set_error(DISTDL_ERR_NULL, "dot: null argument");
   if (n_arrays < 1) return set_error(DISTDL_ERR_INVALID_ARG, "dot: n_arrays = %d", n_arrays);
   if (dtype != DISTDL_F32 && dtype != DISTDL_BF16) return set_error(DISTDL_ERR_UNSUPPORTED, "unknown dtype");
-  hipStream_t st = (hipStream_t)stream;
   int dev = 0;
   DISTDL_HIP_TRY(hipGetDevice(&dev));
   if (dev < 0 || dev >= 64) return set_error(DISTDL_ERR_UNSUPPORTED, "device index %d", dev);
   if (!g_dot_partial[dev]) DISTDL_HIP_TRY(hipMalloc((void**)&g_dot_partial[dev], kDotBlocks * sizeof(double)));
-  for (int j0 = 0; j0 < n_arrays; j0 += kDotArrays) {
-    DotArgs d{};
-    d.n = std::min(kDotArrays, n_arrays - j0);
-    d.accumulate = j0 > 0;
-    for (int j = 0; j < d.n; ++j) {
-      if (count[j0 + j] < 0) return set_error(DISTDL_ERR_INVALID_ARG, "dot: negative count");
-      if (count[j0 + j] > 0 && (!a_dev[j0 + j] || !b_dev[j0 + j])) return set_error(DISTDL_ERR_NULL, "dot: null array");
-      d.a[j] = a_dev[j0 + j];
-      d.b[j] = b_dev[j0 + j];
-      d.count[j] = count[j0 + j];
-    }
-    if (dtype == DISTDL_F32)
-      hipLaunchKernelGGL(dot_partial_kernel<false>, dim3(kDotBlocks), dim3(256), 0, st, d, g_dot_partial[dev]);
-    else
-      hipLaunchKernelGGL(dot_partial_kernel<true>, dim3(kDotBlocks), dim3(256), 0, st, d, g_dot_partial[dev]);
-  }
-  hipLaunchKernelGGL(dot_final_kernel, dim3(1), dim3(256), 0, st, g_dot_partial[dev], kDotBlocks, result_dev);
-  DISTDL_HIP_TRY(hipGetLastError());
-  return DISTDL_OK;
+  return launch_dot(a_dev, b_dev, count, n_arrays, dtype, g_dot_partial[dev], result_dev, (hipStream_t)stream);
 }
 
 }  // extern "C"

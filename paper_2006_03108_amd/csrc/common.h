@@ -66,6 +66,12 @@ __host__ __device__ inline uint32_t fd_div(uint32_t n, const FastDiv& f) {
   return (t + ((n - t) >> f.sh1)) >> f.sh2;
 }
 
+// ---- inner product -----------------------------------------------------------
+// Enqueues <a, b> over n_arrays array pairs into *result_dev; `partial` is device scratch of kDotPartials doubles.
+constexpr int kDotPartials = 1024;
+int launch_dot(const void* const a_dev[], const void* const b_dev[], const int64_t count[], int n_arrays,
+               distdl_dtype dtype, double* partial, double* result_dev, hipStream_t st);
+
 // ---- geometry -------------------------------------------------------------
 struct DimGeom {
   int64_t in_start, in_size, out_start, out_size;
@@ -95,7 +101,8 @@ struct WorkerDev {
   int32_t origin[3];  // buffer coordinate of the first tap of the first output
   int32_t bulk_off[3];
   int32_t in_size[3];
-  int32_t pad_;
+  int32_t dom_lo[3], dom_hi[3];  // buffer coordinates [lo, hi) of the cells inside the global domain (the rest is zero padding)
+  int32_t pad_[2];
 };
 
 // One source of a box task: the same box seen in another worker's buffer.
@@ -155,26 +162,70 @@ struct TaskTable {
   int64_t cells_copied = 0, cells_zeroed = 0, cells_band = 0;
 };
 
-// Device copies of a caller's host pointer arrays.  A call site sees a few arrays in turn (the activations of
-// the forward pass, the gradients of the backward pass, ...): the table keeps the last kSlots of them, each in
-// its own device block, so that in steady state upload() finds its array and copies nothing -- which also keeps
-// a warmed-up call free of copies when the caller records it into a graph.  `dev` and `host` are the block and
-// the array selected by the last upload().
-struct PtrTable {
+// Device copies of small host tables (a caller's pointer arrays, the block descriptors of a GEMM launch).  A call
+// site sees a few tables in turn (the activations of the forward pass, the gradients of the backward pass, ...):
+// the cache keeps the last kSlots of them per stream, each in its own device block, so that in steady state
+// upload() finds its table and copies nothing -- which also keeps a warmed-up call free of copies when the caller
+// records it into a graph.  Rules that keep a block from changing under a reader:
+//   - a block is only ever rewritten (or freed and re-allocated) for a call on the stream it was last used on, so
+//     the copy is ordered behind every kernel that reads the old contents;
+//   - a block that was selected while its stream was being captured is pinned: the graph's kernel nodes hold its
+//     address, so it is never rewritten or freed before release();
+//   - a table that is not cached cannot be uploaded during capture (the copy would read host memory at replay):
+//     that call fails, the caller has to make it once eagerly first;
+//   - at most kMaxSlots blocks exist; when none may be reused the call fails instead of evicting a live one.
+struct SlotCache {
   static constexpr int kSlots = 8;
+  static constexpr int kMaxSlots = 64;
   struct Entry {
-    std::vector<const void*> ptrs;
-    void** dev = nullptr;
+    std::vector<unsigned char> host;
+    void* dev = nullptr;
     size_t cap = 0;
     hipStream_t stream = nullptr;
     uint64_t used = 0;
+    bool live = false, pinned = false;
   };
   std::vector<Entry> entries;
-  std::vector<const void*> host;
-  void** dev = nullptr;
   uint64_t clock = 0;
-  int upload(const void* const* ptrs, size_t n, hipStream_t stream);
+  int selected = -1;  // entry chosen by the last upload()
+  // capturing: 1 / 0, or -1 to ask the runtime about `stream`.  simulate: apply the policy only, no HIP call
+  // (host-side tests of the policy).
+  int upload(const void* bytes, size_t nbytes, hipStream_t stream, int capturing = -1, bool simulate = false);
+  void* dev() const { return selected < 0 ? nullptr : entries[selected].dev; }
   void release();
+};
+
+struct PtrTable {
+  SlotCache cache;
+  std::vector<const void*> host;  // the array selected by the last upload()
+  void** dev = nullptr;           // its device copy
+  int upload(const void* const* ptrs, size_t n, hipStream_t stream) {
+    int rc = cache.upload(ptrs, n * sizeof(void*), stream);
+    if (rc) return rc;
+    dev = (void**)cache.dev();
+    host.assign(ptrs, ptrs + n);
+    return DISTDL_OK;
+  }
+  void release() {
+    cache.release();
+    dev = nullptr;
+  }
+};
+
+template <class T>
+struct DevArray {
+  SlotCache cache;
+  T* dev = nullptr;  // the block selected by the last upload()
+  int upload(const std::vector<T>& v, hipStream_t st) {
+    int rc = cache.upload(v.data(), v.size() * sizeof(T), st);
+    if (rc) return rc;
+    dev = (T*)cache.dev();
+    return DISTDL_OK;
+  }
+  void release() {
+    cache.release();
+    dev = nullptr;
+  }
 };
 
 }  // namespace distdl
@@ -202,6 +253,8 @@ struct distdl_plan {
   float* d_wt = nullptr;
   distdl::FastDiv* d_pooldiv = nullptr;  // per worker: division by buf[1], buf[2], out[1], out[2] (pooling kernels)
   size_t wt_elems = 0;
+  mutable int maxpool_ok = -1;    // 1 once every max-pool window is known to hold an in-domain cell
+  mutable int corr_mfma_ok = -1;  // cached answer of corr_mfma_supported(): -1 not asked yet
 
   int coords(int w, int d) const {
     int c[3];

@@ -275,6 +275,30 @@ int distdl_conv_bwd(distdl_plan* plan, const void* const x_bufs_dev[], const voi
                                workspace_bytes, (hipStream_t)stream, true);
 }
 
+int distdl_debug_conv_path(const distdl_plan* plan, int32_t out[3]) {
+  if (!plan || !out) return set_error(DISTDL_ERR_NULL, "conv_path: null argument");
+  if (plan->explicit_halo) return set_error(DISTDL_ERR_UNSUPPORTED, "conv_path: plan has no kernel");
+  // the choices of conv_fwd_core / conv_bwd_core for 16-byte aligned arrays
+  const bool vec = plan->n_ci % 4 == 0 && plan->n_co % 4 == 0;
+  const bool mfma = corr_mfma_supported(plan);
+  out[0] = corr16_fwd_supported(plan, true) ? 2 : mfma ? 1 : 0;
+  out[1] = corr16_bwd_supported(plan, true) ? 2 : mfma ? 1 : 0;
+  out[2] = wgrad16_supported(plan, vec) ? 2 : (wgrad_mfma_supported(plan) && (plan->dtype != DISTDL_BF16 || vec)) ? 1 : 0;
+  return DISTDL_OK;
+}
+
+int distdl_conv_local_fwd(distdl_plan* plan, void* const x_bufs_dev[], const void* w_dev, const void* bias_dev,
+                          void* const y_dev[], void* stream) {
+  return distdl::conv_fwd_core(plan, x_bufs_dev, w_dev, bias_dev, y_dev, (hipStream_t)stream, false);
+}
+
+int distdl_conv_local_bwd(distdl_plan* plan, const void* const x_bufs_dev[], const void* w_dev,
+                          const void* const dy_dev[], void* const dx_bufs_dev[], void* dw_dev, void* dbias_dev,
+                          void* workspace_dev, size_t workspace_bytes, void* stream) {
+  return distdl::conv_bwd_core(plan, x_bufs_dev, w_dev, dy_dev, dx_bufs_dev, dw_dev, dbias_dev, workspace_dev,
+                               workspace_bytes, (hipStream_t)stream, false);
+}
+
 }  // extern "C"
 
 namespace distdl {

@@ -1024,15 +1024,46 @@ static void max_nq(const distdl_plan* p, const CorrArgs& a, int& nq1, int& nq2) 
   }
 }
 
+// Arithmetic mode of a correlation launch.  0: fp32; 1: bf16 tensors widened to fp32; 2: bf16 MFMAs (contraction
+// channels in 16-byte pieces of 8).
+static int corr_mode(const distdl_plan* p, const CorrArgs& a) {
+  return p->dtype != DISTDL_BF16 ? 0 : (a.kc % 8 == 0 ? 2 : 1);
+}
+
+// Window choice of one launch (forward, or one parity class): M-tiles per wave, 0 when no window's patch fits the
+// piece slots of a thread or the LDS of a compute unit (wide dilated kernels).
+static int corr_window(const distdl_plan* p, CorrArgs& a) {
+  const int mode = corr_mode(p, a);
+  a.ck = mode == 2 ? 16 : 8;
+  int nq1max, nq2max;
+  max_nq(p, a, nq1max, nq2max);
+  return choose_mt(a, std::max(nq1max, 1), nq2max, mode == 2);
+}
+
 bool corr_mfma_supported(const distdl_plan* p) {
-  if (p->explicit_halo) return false;
-  if (p->n_ci % 4 || p->n_co % 4) return false;  // 16-byte channel pieces
-  // buffer instructions address one worker's tensor with 31-bit byte offsets
-  if ((double)p->n_b * p->max_buf_cells * std::max(p->n_ci, p->n_co) * 4.0 >= 2147480000.0) return false;
-  for (int d = 0; d < 3; ++d)
-    if (p->ksize[d] > 8) return false;
-  if (p->ksize[1] * p->ksize[2] > kMaxBPieces * 4) return false;  // weight pieces held in registers per stage
-  return true;
+  if (p->corr_mfma_ok >= 0) return p->corr_mfma_ok != 0;
+  auto decide = [&]() {
+    if (p->explicit_halo) return false;
+    if (p->n_ci % 4 || p->n_co % 4) return false;  // 16-byte channel pieces
+    // buffer instructions address one worker's tensor with 31-bit byte offsets
+    if ((double)p->n_b * p->max_buf_cells * std::max(p->n_ci, p->n_co) * 4.0 >= 2147480000.0) return false;
+    for (int d = 0; d < 3; ++d)
+      if (p->ksize[d] > 8) return false;
+    if (p->ksize[1] * p->ksize[2] > kMaxBPieces * 4) return false;  // weight pieces held in registers per stage
+    // every launch of the layer must find a window: the forward one and each parity class of the data gradient
+    CorrArgs fa = forward_args(p);
+    if (corr_window(p, fa) == 0) return false;
+    for (int p0 = 0; p0 < p->stride[0]; ++p0)
+      for (int p1 = 0; p1 < p->stride[1]; ++p1)
+        for (int p2 = 0; p2 < p->stride[2]; ++p2) {
+          const int par[3] = {p0, p1, p2};
+          CorrArgs a = class_args(p, par);
+          if (corr_window(p, a) == 0) return false;
+        }
+    return true;
+  };
+  p->corr_mfma_ok = decide() ? 1 : 0;
+  return p->corr_mfma_ok != 0;
 }
 
 CorrArgs forward_args(const distdl_plan* p) {
@@ -1145,13 +1176,9 @@ static int resident_workgroups(const void* fn, int lds) {
 
 static int launch_corr(distdl_plan* p, CorrArgs a, const void* w, float* wscratch, const void* bias, void** in_tab,
                        void** out_tab, const char* name, hipStream_t st) {
-  // 0: fp32; 1: bf16 tensors widened to fp32; 2: bf16 MFMAs (contraction channels in 16-byte pieces of 8)
-  const int mode = p->dtype != DISTDL_BF16 ? 0 : (a.kc % 8 == 0 ? 2 : 1);
-  a.ck = mode == 2 ? 16 : 8;
-  int nq1max, nq2max;
-  max_nq(p, a, nq1max, nq2max);
-  const int mt = choose_mt(a, std::max(nq1max, 1), nq2max, mode == 2);
-  if (mt == 0) return set_error(DISTDL_ERR_UNSUPPORTED, "conv: kernel footprint does not fit in LDS");
+  const int mode = corr_mode(p, a);
+  const int mt = corr_window(p, a);
+  if (mt == 0) return set_error(DISTDL_ERR_UNSUPPORTED, "conv: kernel footprint does not fit in LDS");  // corr_mfma_supported() rules this out
   const int lds = lds_bytes(a);
   const bool small = a.R * a.Cw * 2 <= 4 * 256 && a.nt[1] * a.nt[2] * 64 <= 3 * 256;
   const CorrVariant kv = corr_variant(mode, mt, small, a.nt[1] * a.nt[2]);

@@ -85,7 +85,14 @@ static PoolDev pool_params(const distdl_plan* p) {
   return d;
 }
 
-// y[n][o][c] = max over the window of x^[n][origin + o*s + t*dil][c]
+// Cells outside the global domain are zero padding: the mean counts them as the zeros they hold, the max
+// leaves them out (the window maximum is taken over the cells of the tensor itself).
+__device__ inline bool in_domain(const WorkerDev& wd, int b0, int b1, int b2) {
+  return b0 >= wd.dom_lo[0] && b0 < wd.dom_hi[0] && b1 >= wd.dom_lo[1] && b1 < wd.dom_hi[1] && b2 >= wd.dom_lo[2] &&
+         b2 < wd.dom_hi[2];
+}
+
+// y[n][o][c] = max over the in-domain cells of the window x^[n][origin + o*s + t*dil][c] (or the window's mean)
 template <bool AVG, class T>
 __global__ __launch_bounds__(256) void pool_fwd_kernel(const WorkerDev* __restrict__ workers, void* const* x_bufs,
                                                        void* const* y_bufs, PoolDev d) {
@@ -107,11 +114,12 @@ __global__ __launch_bounds__(256) void pool_fwd_kernel(const WorkerDev* __restri
   for (int t0 = 0; t0 < d.k[0]; ++t0)
     for (int t1 = 0; t1 < d.k[1]; ++t1)
       for (int t2 = 0; t2 < d.k[2]; ++t2) {
-        const float v = ld(x, n * sn + (wd.origin[0] + o0 * d.s[0] + t0 * d.dil[0]) * s0 +
-                                 (wd.origin[1] + o1 * d.s[1] + t1 * d.dil[1]) * s1 +
-                                 (wd.origin[2] + o2 * d.s[2] + t2 * d.dil[2]) * s2 + c);
+        const int b0 = wd.origin[0] + o0 * d.s[0] + t0 * d.dil[0], b1 = wd.origin[1] + o1 * d.s[1] + t1 * d.dil[1],
+                  b2 = wd.origin[2] + o2 * d.s[2] + t2 * d.dil[2];
+        const float v = ld(x, n * sn + b0 * s0 + b1 * s1 + b2 * s2 + c);
+        sum += v;  // row-major tap order; padding cells hold zeros
+        if (!in_domain(wd, b0, b1, b2)) continue;  // padding never wins the max
         if (first || v > best) best = v;
-        sum += v;  // row-major tap order
         first = false;
       }
   st(y, idx, AVG ? sum / (float)(d.k[0] * d.k[1] * d.k[2]) : best);
@@ -158,9 +166,10 @@ __global__ __launch_bounds__(256) void pool_bwd_kernel(const WorkerDev* __restri
         for (int u0 = 0; u0 < d.k[0]; ++u0)
           for (int u1 = 0; u1 < d.k[1]; ++u1)
             for (int u2 = 0; u2 < d.k[2]; ++u2, ++u) {
-              const float v = ld(x, n * sn + (wd.origin[0] + o0 * d.s[0] + u0 * d.dil[0]) * s0 +
-                                       (wd.origin[1] + o1 * d.s[1] + u1 * d.dil[1]) * s1 +
-                                       (wd.origin[2] + o2 * d.s[2] + u2 * d.dil[2]) * s2 + c);
+              const int b0 = wd.origin[0] + o0 * d.s[0] + u0 * d.dil[0], b1 = wd.origin[1] + o1 * d.s[1] + u1 * d.dil[1],
+                        b2 = wd.origin[2] + o2 * d.s[2] + u2 * d.dil[2];
+              if (!in_domain(wd, b0, b1, b2)) continue;
+              const float v = ld(x, n * sn + b0 * s0 + b1 * s1 + b2 * s2 + c);
               if (arg < 0 || v > best) best = v, arg = u;
             }
         if (arg == tap) acc += ld(dy, n * son + o0 * so0 + o1 * so1 + o2 * so2 + c);
@@ -206,15 +215,16 @@ __global__ __launch_bounds__(256) void pool_fwd_vec_kernel(const WorkerDev* __re
   for (int t0 = 0; t0 < d.k[0]; ++t0)
     for (int t1 = 0; t1 < d.k[1]; ++t1)
       for (int t2 = 0; t2 < d.k[2]; ++t2) {
-        const float4* xp = x + n * sn + (wd.origin[0] + o0 * d.s[0] + t0 * d.dil[0]) * s0 +
-                           (wd.origin[1] + o1 * d.s[1] + t1 * d.dil[1]) * s1 +
-                           (wd.origin[2] + o2 * d.s[2] + t2 * d.dil[2]) * s2 + c;
+        const int b0 = wd.origin[0] + o0 * d.s[0] + t0 * d.dil[0], b1 = wd.origin[1] + o1 * d.s[1] + t1 * d.dil[1],
+                  b2 = wd.origin[2] + o2 * d.s[2] + t2 * d.dil[2];
+        const float4* xp = x + n * sn + b0 * s0 + b1 * s1 + b2 * s2 + c;
         const float4 v = STREAM ? nt_load4(xp) : *xp;
+        sum.x += v.x; sum.y += v.y; sum.z += v.z; sum.w += v.w;  // row-major tap order; padding cells hold zeros
+        if (!AVG && !in_domain(wd, b0, b1, b2)) continue;  // padding never wins the max
         if (first || v.x > best.x) best.x = v.x;
         if (first || v.y > best.y) best.y = v.y;
         if (first || v.z > best.z) best.z = v.z;
         if (first || v.w > best.w) best.w = v.w;
-        sum.x += v.x; sum.y += v.y; sum.z += v.z; sum.w += v.w;  // row-major tap order
         first = false;
       }
   const float inv = (float)(d.k[0] * d.k[1] * d.k[2]);
@@ -254,14 +264,18 @@ __global__ __launch_bounds__(256) void pool_bwd_window_kernel(const WorkerDev* _
   if (!AVG) {
     float4 best = make_float4(0.f, 0.f, 0.f, 0.f);
     int u = 0;
+    bool first = true;
+    const int w0 = wd.origin[0] + o0 * d.s[0], w1 = wd.origin[1] + o1 * d.s[1], w2 = wd.origin[2] + o2 * d.s[2];
     for (int u0 = 0; u0 < d.k[0]; ++u0)
       for (int u1 = 0; u1 < d.k[1]; ++u1)
         for (int u2 = 0; u2 < d.k[2]; ++u2, ++u) {
           const float4 v = nt_load4(x + base + u0 * s0 + u1 * s1 + u2 * s2);
-          if (u == 0 || v.x > best.x) best.x = v.x, ax = u;
-          if (u == 0 || v.y > best.y) best.y = v.y, ay = u;
-          if (u == 0 || v.z > best.z) best.z = v.z, az = u;
-          if (u == 0 || v.w > best.w) best.w = v.w, aw = u;
+          if (!in_domain(wd, w0 + u0, w1 + u1, w2 + u2)) continue;  // padding never wins the max
+          if (first || v.x > best.x) best.x = v.x, ax = u;
+          if (first || v.y > best.y) best.y = v.y, ay = u;
+          if (first || v.z > best.z) best.z = v.z, az = u;
+          if (first || v.w > best.w) best.w = v.w, aw = u;
+          first = false;
         }
   }
   const float inv = (float)(d.k[0] * d.k[1] * d.k[2]);
@@ -402,6 +416,26 @@ static int check_pool_plan(const distdl_plan* p, const char* what) {
   return DISTDL_OK;
 }
 
+// The maximum is taken over the in-domain cells of a window, so every window needs one: per dimension, some tap
+// of every output must land inside the domain (padding of at most half the kernel extent guarantees it).
+static int check_maxpool_windows(const distdl_plan* p, const char* what) {
+  if (p->maxpool_ok > 0) return DISTDL_OK;  // checked before
+  for (const WorkerDev& wd : p->workers)
+    for (int d = 0; d < 3; ++d)
+      for (int o = 0; o < wd.out[d]; ++o) {
+        bool any = false;
+        for (int t = 0; t < p->ksize[d] && !any; ++t) {
+          const int b = wd.origin[d] + o * p->stride[d] + t * p->dilation[d];
+          any = b >= wd.dom_lo[d] && b < wd.dom_hi[d];
+        }
+        if (!any)
+          return set_error(DISTDL_ERR_UNSUPPORTED, "%s: a window lies entirely in the zero padding (dimension %d)", what,
+                           d - (3 - p->D));
+      }
+  p->maxpool_ok = 1;
+  return DISTDL_OK;
+}
+
 // division constants of every worker's buffer and output extents, built on first use
 static int ensure_pooldiv(distdl_plan* p) {
   if (p->d_pooldiv) return DISTDL_OK;
@@ -450,6 +484,7 @@ static int pool_fwd(distdl_plan* plan, void* const x_bufs_dev[], void* const y_d
   if (!plan || !x_bufs_dev || !y_dev) return set_error(DISTDL_ERR_NULL, "%s: null argument", what);
   int rc = check_pool_plan(plan, what);
   if (rc) return rc;
+  if (!avg && (rc = check_maxpool_windows(plan, what))) return rc;
   const bool bf16 = plan->dtype == DISTDL_BF16;  // bf16 tensors: the element-wise kernels (fp32 arithmetic)
   if ((rc = check_list((const void* const*)y_dev, plan->n_workers, what, bf16 ? 2 : 4))) return rc;
   if ((rc = run_halo(plan, false, plan->tab_x, x_bufs_dev, st))) return rc;  // x <- H x
@@ -494,6 +529,7 @@ static int pool_bwd(distdl_plan* plan, const void* const x_bufs_dev[], const voi
   if (!plan || (!avg && !x_bufs_dev) || !dy_dev || !dx_bufs_dev) return set_error(DISTDL_ERR_NULL, "%s: null argument", what);
   int rc = check_pool_plan(plan, what);
   if (rc) return rc;
+  if (!avg && (rc = check_maxpool_windows(plan, what))) return rc;
   const bool bf16 = plan->dtype == DISTDL_BF16;
   const int esz = bf16 ? 2 : 4;
   if ((!avg && (rc = check_list(x_bufs_dev, plan->n_workers, what, esz))) ||

@@ -18,47 +18,74 @@ int set_error(int code, const char* fmt, ...) {
   return code;
 }
 
-int PtrTable::upload(const void* const* ptrs, size_t n, hipStream_t stream) {
+int SlotCache::upload(const void* bytes, size_t nbytes, hipStream_t stream, int capturing, bool simulate) {
   ++clock;
-  Entry* pick = nullptr;
-  for (Entry& e : entries)
-    if (e.dev && e.stream == stream && e.ptrs.size() == n && std::memcmp(e.ptrs.data(), ptrs, n * sizeof(void*)) == 0) {
-      pick = &e;
+  if (capturing < 0) {
+    hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+    DISTDL_HIP_TRY(hipStreamIsCapturing(stream, &cs));
+    capturing = cs != hipStreamCaptureStatusNone;
+  }
+  int pick = -1;
+  for (size_t i = 0; i < entries.size(); ++i) {
+    const Entry& e = entries[i];
+    if (e.live && e.stream == stream && e.host.size() == nbytes && std::memcmp(e.host.data(), bytes, nbytes) == 0) {
+      pick = (int)i;
       break;
     }
-  if (!pick) {
-    if ((int)entries.size() < kSlots) {
-      entries.emplace_back();
-      pick = &entries.back();
-    } else {
-      pick = &entries[0];
-      for (Entry& e : entries)
-        if (e.used < pick->used) pick = &e;  // least recently used
-    }
-    if (n > pick->cap) {
-      if (pick->dev) (void)hipFree(pick->dev);
-      pick->dev = nullptr;
-      pick->cap = 0;
-      DISTDL_HIP_TRY(hipMalloc((void**)&pick->dev, n * sizeof(void*)));
-      pick->cap = n;
-    }
-    pick->ptrs.assign(ptrs, ptrs + n);
-    // pageable source: the runtime stages the bytes before returning, and the copy is ordered on the stream
-    // after earlier kernels that read the block
-    DISTDL_HIP_TRY(hipMemcpyAsync(pick->dev, pick->ptrs.data(), n * sizeof(void*), hipMemcpyHostToDevice, stream));
-    pick->stream = stream;
   }
-  pick->used = clock;
-  dev = pick->dev;
-  host = pick->ptrs;
+  if (pick < 0) {
+    if (capturing)
+      return set_error(DISTDL_ERR_INVALID_ARG,
+                       "a call with new pointer arrays or shapes cannot be recorded into a graph: make it once on "
+                       "this stream before the capture starts");
+    // blocks this call may rewrite: unpinned ones last used on this very stream
+    int lru = -1, mine = 0;
+    for (size_t i = 0; i < entries.size(); ++i) {
+      const Entry& e = entries[i];
+      if (e.pinned || e.stream != stream) continue;
+      ++mine;
+      if (lru < 0 || e.used < entries[lru].used) lru = (int)i;
+    }
+    if (mine >= kSlots || ((int)entries.size() >= kMaxSlots && lru >= 0)) {
+      pick = lru;
+    } else if ((int)entries.size() < kMaxSlots) {
+      entries.emplace_back();
+      pick = (int)entries.size() - 1;
+    } else {
+      return set_error(DISTDL_ERR_NOMEM,
+                       "all %d table blocks of this call site are held by other streams or recorded graphs", kMaxSlots);
+    }
+    Entry& e = entries[pick];
+    if (!simulate) {
+      if (nbytes > e.cap) {
+        if (e.dev) (void)hipFree(e.dev);  // waits for the device
+        e.dev = nullptr;
+        e.cap = 0;
+        e.live = false;
+        DISTDL_HIP_TRY(hipMalloc(&e.dev, std::max<size_t>(nbytes, 16)));
+        e.cap = nbytes;
+      }
+    }
+    e.host.assign((const unsigned char*)bytes, (const unsigned char*)bytes + nbytes);
+    // pageable source: the runtime stages the bytes before returning, and the copy is ordered on the stream
+    // behind earlier kernels that read the block
+    if (!simulate && nbytes)
+      DISTDL_HIP_TRY(hipMemcpyAsync(e.dev, e.host.data(), nbytes, hipMemcpyHostToDevice, stream));
+    e.stream = stream;
+    e.live = true;
+  }
+  Entry& e = entries[pick];
+  e.used = clock;
+  if (capturing) e.pinned = true;
+  selected = pick;
   return DISTDL_OK;
 }
 
-void PtrTable::release() {
+void SlotCache::release() {
   for (Entry& e : entries)
     if (e.dev) (void)hipFree(e.dev);
   entries.clear();
-  dev = nullptr;
+  selected = -1;
 }
 
 // ---- per-dimension geometry ------------------------------------------------
@@ -409,10 +436,12 @@ static int finish_plan(distdl_plan* p) {
       wd.origin[d] = (int32_t)g.origin;
       wd.bulk_off[d] = (int32_t)g.bulk_off;
       wd.in_size[d] = (int32_t)g.in_size;
+      wd.dom_lo[d] = g.pad[0];
+      wd.dom_hi[d] = (int32_t)g.buf - g.pad[1];
       bufc *= g.buf;
       outc *= g.out_size;
     }
-    wd.pad_ = 0;
+    wd.pad_[0] = wd.pad_[1] = 0;
     int64_t cmax = std::max(p->n_ci, p->n_co);
     if (bufc * cmax >= (int64_t(1) << 31) || outc * cmax >= (int64_t(1) << 31))
       return set_error(DISTDL_ERR_UNSUPPORTED, "worker %d: one sample of a partition exceeds 2^31 elements", w);
@@ -586,6 +615,19 @@ int distdl_plan_query(const distdl_plan* plan, int worker, distdl_worker_geom* o
     out->buf_shape[d] = g.buf;
     out->bulk_off[d] = g.bulk_off;
     out->conv_origin[d] = g.origin;
+  }
+  return DISTDL_OK;
+}
+
+int distdl_debug_slot_policy(const int32_t stream_id[], const int32_t table_id[], const int32_t capturing[], int n,
+                             int32_t slot_out[]) {
+  if (!stream_id || !table_id || !capturing || !slot_out) return set_error(DISTDL_ERR_NULL, "slot_policy: null argument");
+  SlotCache cache;
+  for (int i = 0; i < n; ++i) {
+    const int32_t table = table_id[i];
+    int rc = cache.upload(&table, sizeof table, (hipStream_t)(uintptr_t)(0x1000 + 16 * stream_id[i]), capturing[i] != 0,
+                          true);
+    slot_out[i] = rc ? rc : cache.selected;
   }
   return DISTDL_OK;
 }

@@ -85,6 +85,14 @@ CONV_FULL = [
     # several channel tiles (the second output tile half full): the weight gradient's shared tap and its db sums
     ("cfg2", dict(in_shape=(40, 70), n_b=2, c_in=64, c_out=48, ksize=(3, 3), padding=(1, 1), P=(2, 2)), True),
     ("cfg2", dict(in_shape=(36, 40), n_b=3, c_in=32, c_out=64, ksize=(5, 5), stride=(2, 2), padding=(2, 2), P=(2, 1)), True),
+    # three and four workers per dimension in 3-D: interior workers (halo on both sides of every dimension, no
+    # padding), every element compared; uneven bulks in the second
+    ("cfg5", dict(in_shape=(40, 38, 44), P=(3, 3, 3)), True),
+    ("cfg5u", dict(in_shape=(50, 46, 54), P=(4, 4, 4), c_in=8, c_out=16), False),
+    # wide dilated kernels with 32 channels: dilation 12 still finds a (32-wide) window of the matrix-core
+    # correlation, dilation 16 does not and must run on the direct kernels
+    ("cfg2", dict(in_shape=(60, 64), n_b=1, c_in=32, c_out=32, ksize=(3, 3), padding=(12, 12), dilation=(12, 12)), True),
+    ("cfg2", dict(in_shape=(80, 72), n_b=1, c_in=32, c_out=32, ksize=(3, 3), padding=(16, 16), dilation=(16, 16)), True),
 ]
 
 
@@ -410,6 +418,85 @@ def test_conv_full_size_sampled(name, dtype):
         mask = np.ones(part.buf_shape(wk), dtype=bool)
         mask[part.bulk_slices(wk)] = False
         assert not dx_host[wk][:, :, mask].any()
+
+
+@pytest.mark.parametrize("name", ["cfg5", "cfg5u"])
+def test_conv_full_size_whole_workers(name):
+    """The volumetric configuration at its full size, in the launch configuration the benchmark times: every
+    element of a corner, an edge, a face, an interior and the far-corner worker against the oracle -- y from the
+    oracle's local correlation on that worker's buffer after H; the local gradient dx^ over the whole padded
+    buffer (halo and padding cells included) before H*; and dx after H*, whose bulk (band cells that H* adds
+    into included) must equal the sequential layer's gradient on that region, with halo and padding cleared."""
+    require_gpu()
+    cfg = dict(syn.CONFIGS[name])
+    part = oracle_partition(cfg)
+    case = syn.conv_case(cfg, part.global_out_shape())
+    s, p, k, dil = cfg["stride"], cfg["padding"], cfg["ksize"], cfg["dilation"]
+    plan = dd.distdl_plan_create(cfg["D"], cfg["n_b"], cfg["c_in"], cfg["c_out"], cfg["in_shape"], cfg["P"], k, s, p, dil)
+    x_bufs = [to_cl(b) for b in prim.scatter_bulk(case["x"], part, fill=np.float32(3.0))]
+    w, bias = w_to_dev(case["w"]), w_to_dev(case["bias"])
+    y = [torch.full((cfg["n_b"],) + part.out_shape(wk) + (cfg["c_out"],), 7.0, device="cuda")
+         for wk in range(part.n_workers)]
+    dd.distdl_conv_fwd(plan, x_bufs, w, bias, y)
+    dy_parts = prim.scatter_out(case["dy"], part)
+    dy = [to_cl(t) for t in dy_parts]
+    dx_local = [torch.full_like(b, 5.0) for b in x_bufs]
+    dw, db = torch.full_like(w, 9.0), torch.full_like(bias, 9.0)
+    ws = torch.empty(max(dd.distdl_conv_bwd_workspace(plan), 16), dtype=torch.uint8, device="cuda")
+    dd.distdl_conv_local_bwd(plan, x_bufs, w, dy, dx_local, dw, db, ws)      # [dConv]* and R dw, R db; no H*
+    dx = [torch.full_like(b, 5.0) for b in x_bufs]
+    dw2, db2 = torch.full_like(w, 9.0), torch.full_like(bias, 9.0)
+    dd.distdl_conv_bwd(plan, x_bufs, w, dy, dx, dw2, db2, ws)                # the whole adjoint algorithm
+    torch.cuda.synchronize()
+    assert torch.equal(dw, dw2) and torch.equal(db, db2)
+    if name == "cfg5":
+        pick = {"corner": (0, 0, 0), "edge": (0, 0, 1), "face": (0, 1, 2), "interior": (1, 2, 1)}
+    else:   # uneven bulks: an interior worker with a 63 / 62 / 63 bulk and the far corner (right-hand padding)
+        pick = {"interior": (1, 2, 1), "far corner": (3, 3, 3)}
+    n_in, n_out = cfg["in_shape"], part.global_out_shape()
+
+    def oracle_side(wk):
+        """The three oracle results for worker wk (plain calls of oracle.layers; run side by side in threads only
+        to keep the test short, numpy releases the interpreter lock inside them)."""
+        xb = prim.expected_buffer_after_halo(case["x"], part, wk)             # H x, cell by cell from the global tensor
+        origin = [part.g(wk, d)["origin"] for d in range(3)]
+        y_want = layers.conv_valid(xb, case["w"], case["bias"], part.out_shape(wk), s, dil, origin)
+        dxp_want, _, _ = layers.conv_valid_adjoint(xb, case["w"], dy_parts[wk], s, dil, origin)
+        return xb, y_want, dxp_want
+
+    from concurrent.futures import ThreadPoolExecutor
+    with ThreadPoolExecutor(len(pick)) as pool:
+        oracle = dict(zip(pick, pool.map(oracle_side, [part.worker_id(c) for c in pick.values()])))
+    for label, coords in pick.items():
+        wk = part.worker_id(coords)
+        xb, y_want, dxp_want = oracle[label]
+        assert np.array_equal(from_cl(x_bufs[wk]), xb), f"H x, {label} worker"
+        assert_close(from_cl(y[wk]), y_want, TOL32, f"y, {label} worker")
+        assert_close(from_cl(dx_local[wk]), dxp_want, TOL32, f"dx^ before H*, {label} worker")
+        # after H*: the sequential gradient on the worker's bulk.  Outputs that touch the bulk [a0, a1] of a
+        # dimension are o_lo .. o_hi; the sequential adjoint on that slab of dy, cropped to the bulk
+        geom = [part.g(wk, d) for d in range(3)]
+        a0 = [g["in_start"] for g in geom]
+        a1 = [g["in_start"] + g["in_size"] - 1 for g in geom]
+        span = [dil[d] * (k[d] - 1) for d in range(3)]
+        o_lo = [max(0, -((-(a0[d] + p[d] - span[d])) // s[d])) for d in range(3)]
+        o_hi = [min(n_out[d] - 1, (a1[d] + p[d]) // s[d]) for d in range(3)]
+        v0 = [o_lo[d] * s[d] - p[d] for d in range(3)]                          # global index of the slab's first cell
+        vshape = tuple((o_hi[d] - o_lo[d]) * s[d] + span[d] + 1 for d in range(3))
+        dy_slab = case["dy"][(slice(None), slice(None)) + tuple(slice(o_lo[d], o_hi[d] + 1) for d in range(3))]
+        slab, _, _ = layers.conv_valid_adjoint(np.zeros((cfg["n_b"], cfg["c_in"]) + vshape), case["w"], dy_slab, s, dil,
+                                               [0, 0, 0], want_bias=False)
+        crop = tuple(slice(a0[d] - v0[d], a1[d] - v0[d] + 1) for d in range(3))
+        got = from_cl(dx[wk])
+        bulk = (slice(None), slice(None)) + part.bulk_slices(wk)
+        assert_close(got[bulk], slab[(slice(None), slice(None)) + crop], TOL32, f"dx after H*, bulk of the {label} worker")
+        mask = np.ones(part.buf_shape(wk), dtype=bool)
+        mask[part.bulk_slices(wk)] = False
+        assert not got[:, :, mask].any(), f"halo / padding of dx not cleared, {label} worker"
+        # and H* changed exactly the band cells: away from them dx^ is untouched
+        inner = tuple(slice(g["bulk_off"] + 4, g["bulk_off"] + g["in_size"] - 4) for g in geom)
+        assert np.array_equal(got[(slice(None), slice(None)) + inner],
+                              from_cl(dx_local[wk])[(slice(None), slice(None)) + inner])
 
 
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])

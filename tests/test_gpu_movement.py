@@ -182,7 +182,7 @@ def test_halo_run_to_run_deterministic_and_unaligned():
 
 # ---------------------------------------------------------------- broadcast / sum-reduce
 COLL_CASES = [(16, 4, 1), (1, 1, 1), (5, 3, 2), (4099, 2, 3), (256 * 2048, 2, 2), (1000, 64, 1), (37, 100, 1),
-              (9 * 1024, 4, 16)]
+              (9 * 1024, 4, 16), (1003, 130, 2), (520, 65, 20)]
 
 
 @pytest.mark.parametrize("count,k,G", COLL_CASES)
@@ -226,6 +226,31 @@ def test_broadcast_and_sumreduce(count, k, G, dtype):
         Fx = [t.cpu().numpy() for t in g_dst]
         Fsy = [t.cpu().numpy() for t in g_out]
         assert prim.adjoint_test_ratio(Fx, reps, src, Fsy) < TOL32
+
+
+@pytest.mark.parametrize("k,G", [(130, 1), (200, 3)])
+def test_sumreduce_bf16_wide_groups_round_once(k, G):
+    """More replicas than travel as kernel arguments: the sum still runs over all k in fp32 and is rounded to bf16
+    once (Sec. 3: R = sum over the replicas).  Integer-valued replicas make every fp32 partial sum exact, so the
+    result must equal the nearest-even bf16 of the exact sum; rounding a running bf16 sum between batches of
+    replicas would not (the sums pass 256, where bf16 stops holding every integer)."""
+    require_gpu()
+    count = 2051
+    rng = np.random.default_rng(k)
+    reps = [rng.integers(0, 16, size=count).astype(np.float32) for _ in range(G * k)]
+    g_rep = [torch.from_numpy(t).to(torch.bfloat16).cuda() for t in reps]
+    g_out = [torch.full((count,), 5.0, dtype=torch.bfloat16, device="cuda") for _ in range(G)]
+    dd.distdl_sumreduce_fwd(g_rep, g_out, k)
+    g_all = [t.clone() for t in g_rep]
+    dd.distdl_allreduce(g_all, k)
+    torch.cuda.synchronize()
+    for g in range(G):
+        exact = prim.sum_reduce([reps[g * k + i].astype(np.float64) for i in range(k)])
+        want = syn.to_bf16_values(exact.astype(np.float32))
+        assert exact.max() > 600
+        assert np.array_equal(g_out[g].float().cpu().numpy(), want)
+        for i in range(k):
+            assert np.array_equal(g_all[g * k + i].float().cpu().numpy(), want)
 
 
 def test_sumreduce_integer_valued_is_exact_and_unaligned_pointers():
@@ -410,3 +435,60 @@ def test_collectives_full_size_exact(k, count):
     assert np.array_equal(host.astype(np.float64), prim.sum_reduce(list(rows)))    # sampled against the oracle
     for c in copies:
         assert torch.equal(c, out)
+
+
+# ---------------------------------------------------------------- layout conversion
+LAYOUT_CASES = [
+    # D, n_b, c_in, c_out, in_shape, P, k, s, p
+    (3, 1, 32, 32, (30, 28, 33), (2, 2, 2), (5, 5, 5), (2, 2, 2), (2, 2, 2)),     # 128-byte cells, odd cell counts
+    (2, 3, 16, 8, (40, 37), (2, 3), (3, 3), (1, 1), (1, 1)),
+    (2, 2, 5, 7, (19, 23), (2, 2), (3, 4), (2, 1), (1, 2)),                       # channel counts without 16-byte pieces
+    (1, 4, 40, 70, (300,), (3,), (5,), (1,), (2,)),                               # more than one channel tile, ragged
+    (3, 1, 32, 32, (63, 63, 63), (1, 1, 1), (5, 5, 5), (2, 2, 2), (2, 2, 2)),     # one 67^3 buffer of the volumetric case
+]
+
+
+@pytest.mark.parametrize("case", LAYOUT_CASES, ids=[str(c[4]) for c in LAYOUT_CASES])
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
+def test_layout_convert_is_the_axis_permutation(case, dtype):
+    """Planes-first (the order Sec. 4 writes tensors in: n_b x n_c x cells) <-> channels-last, for the padded
+    buffers and for the outputs: bit-exact against numpy's moveaxis, and the two directions are inverse."""
+    require_gpu()
+    D, n_b, c_in, c_out, n, P, k, s, p = case
+    one = (1,) * D
+    part = geo.Partition.for_kernel(n, P, k, s, p, one)
+    plan = dd.distdl_plan_create(D, n_b, c_in, c_out, n, P, k, s, p, one, dtype)
+    rng = np.random.default_rng(5)
+    for what, n_c, shape_of in ((0, c_in, part.buf_shape), (1, c_out, part.out_shape)):
+        planes = [syn.to_bf16_values(rng.standard_normal((n_b, n_c) + shape_of(w)).astype(np.float32))
+                  for w in range(part.n_workers)]
+        g_pf = [torch.from_numpy(a).to(dtype).cuda() for a in planes]
+        g_cl = [torch.full((n_b,) + shape_of(w) + (n_c,), 9.0, dtype=dtype, device="cuda") for w in range(part.n_workers)]
+        dd.distdl_layout_convert(plan, what, True, g_pf, g_cl)
+        g_back = [torch.full_like(t, 7.0) for t in g_pf]
+        dd.distdl_layout_convert(plan, what, False, g_cl, g_back)
+        torch.cuda.synchronize()
+        for w in range(part.n_workers):
+            assert np.array_equal(g_cl[w].float().cpu().numpy(), np.moveaxis(planes[w], 1, -1)), (what, w)
+            assert torch.equal(g_back[w], g_pf[w]), (what, w)
+
+
+def test_layout_convert_unaligned_and_errors():
+    require_gpu()
+    plan = dd.distdl_plan_create(1, 2, 8, 8, [20], [2], [3], [1], [1], [1])
+    part = geo.Partition.for_kernel((20,), (2,), (3,), (1,), (1,), (1,))
+    rng = np.random.default_rng(6)
+    planes = [rng.standard_normal((2, 8) + part.buf_shape(w)).astype(np.float32) for w in range(2)]
+    g_pf = [torch.from_numpy(a).cuda() for a in planes]
+    flat = [torch.zeros(a.size + 1, device="cuda") for a in planes]
+    g_cl = [f[1:].view((2,) + part.buf_shape(w) + (8,)) for w, f in enumerate(flat)]      # 4-byte aligned only
+    dd.distdl_layout_convert(plan, 0, True, g_pf, g_cl)
+    torch.cuda.synchronize()
+    for w in range(2):
+        assert np.array_equal(g_cl[w].cpu().numpy(), np.moveaxis(planes[w], 1, -1))
+    with pytest.raises(dd.DistdlError) as e:
+        dd.distdl_layout_convert(plan, 2, True, g_pf, g_cl)
+    assert e.value.code == dd.ERR_INVALID_ARG
+    with pytest.raises(dd.DistdlError) as e:
+        dd.distdl_layout_convert(plan, 0, True, [g_pf[0], None], g_cl)
+    assert e.value.code == dd.ERR_NULL

@@ -12,7 +12,7 @@ from oracle import geometry as geo
 from oracle import layers
 from oracle import network
 from oracle import primitives as prim
-from tests.gpu_util import assert_close, from_cl, require_gpu, to_cl
+from tests.gpu_util import assert_close, from_cl, rel_errors, require_gpu, to_cl
 
 pytestmark = pytest.mark.gpu
 TOL32 = 1e-5
@@ -46,15 +46,19 @@ def test_small_cnn_step_matches_oracle(n_b):
     join = lambda parts: np.block([[host(parts[i * 2 + j]) for j in range(2)] for i in range(2)])
     assert abs(net.loss.item() - loss_want) <= TOL32 * abs(loss_want)
     assert_close(np.concatenate([host(t) for t in net.ao["y"]], axis=1), out_want, TOL32, "network output")
-    tol = 2e-5     # a chain of five fp32 layers
+    # every gradient at the bar the problem statement sets for fp32 (1e-5); the achieved errors are printed
+    # (pytest -s) so that the margin through the chain of five layers is on record
+    got = {}
     for name, layer in (("out", net.ao), ("f6", net.a6), ("c5", net.a5)):
-        assert_close(join(layer["dW"]), g_want[name + "_w"], tol, "d " + name + "_w")
-        assert_close(cat(layer["db"]), g_want[name + "_b"], tol, "d " + name + "_b")
-    assert_close(host(net.dw3), g_want["c3_w"], tol, "d c3_w")
-    assert_close(host(net.db3), g_want["c3_b"], tol, "d c3_b")
-    assert_close(host(net.dw1), g_want["c1_w"], tol, "d c1_w")
-    assert_close(host(net.db1), g_want["c1_b"], tol, "d c1_b")
-    assert_close(prim.gather_bulk([from_cl(t) for t in net.c1_dx], part1), g_want["images"], tol, "d images")
+        got[name + "_w"] = join(layer["dW"])
+        got[name + "_b"] = cat(layer["db"])
+    got.update(c3_w=host(net.dw3), c3_b=host(net.db3), c1_w=host(net.dw1), c1_b=host(net.db1),
+               images=prim.gather_bulk([from_cl(t) for t in net.c1_dx], part1))
+    errs = {name: rel_errors(val, g_want[name]) for name, val in got.items()}
+    print("small CNN n_b=%d gradient errors (rel l2, rel max): " % n_b +
+          ", ".join(f"{k} {l2:.1e}/{mx:.1e}" for k, (l2, mx) in errs.items()))
+    for name, val in got.items():
+        assert_close(val, g_want[name], TOL32, "d " + name)
 
 
 def test_small_cnn_step_replayed_from_a_graph_matches_eager():

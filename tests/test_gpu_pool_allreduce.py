@@ -88,6 +88,50 @@ def test_maxpool_general_kernels(case):
         assert_close(from_cl(g_dx[w]), dx_want[w], TOL32, f"maxpool dx worker {w}")
 
 
+@pytest.mark.parametrize("case", [POOL_CASES[2], POOL_CASES[3], POOL_CASES[4], POOL_CASES[7]],
+                         ids=lambda c: str(c[3]) + "k" + str(c[5]))
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
+def test_maxpool_padding_never_wins(case, dtype):
+    """Padded plans on all-negative inputs: a zero from the padding would win every border window and swallow its
+    gradient; the maximum runs over in-domain cells only (all four kernel forms: element-wise and 16-byte forward,
+    gather and window backward)."""
+    require_gpu()
+    D, n_b, c, n, P, k, s, p = case
+    one = (1,) * D
+    part = geo.Partition.for_kernel(n, P, k, s, p, one)
+    plan = dd.distdl_plan_create(D, n_b, c, c, n, P, k, s, p, one, dtype)
+    r = syn.streams(35, 2)
+    x = syn.to_bf16_values(-np.abs(syn.normal(r[0], (n_b, c) + tuple(n))) - 0.5)
+    dy = syn.to_bf16_values(syn.normal(r[1], (n_b, c) + part.global_out_shape()))
+    bufs_o = prim.scatter_bulk(x.astype(np.float64), part, fill=np.nan)
+    y_want, args = layers.dist_maxpool_forward(bufs_o, part, k, s)
+    dx_want = layers.dist_maxpool_adjoint(prim.scatter_out(dy.astype(np.float64), part), args, part,
+                                          [b.shape for b in bufs_o], k, s)
+    g_x = [to_cl(b, dtype) for b in prim.scatter_bulk(x, part, fill=np.float32(9.0))]
+    g_y = [torch.empty((n_b,) + part.out_shape(w) + (c,), device="cuda", dtype=dtype) for w in range(part.n_workers)]
+    dd.distdl_maxpool_fwd(plan, g_x, g_y)
+    g_dy = [to_cl(t, dtype) for t in prim.scatter_out(dy, part)]
+    g_dx = [torch.full_like(t, -5.0) for t in g_x]
+    dd.distdl_maxpool_bwd(plan, g_x, g_dy, g_dx)
+    torch.cuda.synchronize()
+    for w in range(part.n_workers):
+        got = from_cl(g_y[w])
+        assert (got < 0).all(), f"a padding zero won a window of worker {w}"
+        assert np.array_equal(got, y_want[w].astype(np.float32)), f"maxpool y worker {w}"
+        assert_close(from_cl(g_dx[w]), dx_want[w], TOL32 if dtype == torch.float32 else 2e-2, f"maxpool dx worker {w}")
+
+
+def test_maxpool_rejects_windows_that_lie_in_the_padding():
+    require_gpu()
+    plan = dd.distdl_plan_create(1, 1, 4, 4, [12], [2], [2], [2], [3], [1])   # padding 3 with a 2-wide window
+    part = geo.Partition.for_kernel((12,), (2,), (2,), (2,), (3,), (1,))
+    g_x = [torch.zeros((1,) + part.buf_shape(w) + (4,), device="cuda") for w in range(2)]
+    g_y = [torch.zeros((1,) + part.out_shape(w) + (4,), device="cuda") for w in range(2)]
+    with pytest.raises(dd.DistdlError) as e:
+        dd.distdl_maxpool_fwd(plan, g_x, g_y)
+    assert e.value.code == dd.ERR_UNSUPPORTED
+
+
 @pytest.mark.parametrize("case", [POOL_CASES[0], POOL_CASES[2], POOL_CASES[4], POOL_CASES[5]],
                          ids=lambda c: str(c[3]) + "k" + str(c[5]))
 def test_pooling_bf16(case):

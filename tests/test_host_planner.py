@@ -217,3 +217,52 @@ def test_repartition_plan_blocks_follow_the_balanced_rule_and_errors():
         dd.distdl_repart_plan_create((3, 4, 5, 6, 7), (1,) * 5, (1,) * 5)
     with pytest.raises(dd.DistdlError):
         dd.distdl_repart_plan_create((0, 4), (1, 1), (1, 1))
+
+
+def test_conv_kernel_family_falls_back_when_no_window_fits():
+    """Layers whose staged patch fits no window of the matrix-core correlation (wide dilated kernels with many
+    channels) must be routed to the direct kernels by the planner, not fail when the launch is prepared."""
+    path = lambda *a, **k: dd.distdl_debug_conv_path(dd.distdl_plan_create(*a, **k))
+    # the volumetric configuration and the 2-D one: 32-wide and 16-wide matrix-core tiles
+    assert path(3, 1, 32, 32, [64, 64, 64], [2, 2, 2], [5] * 3, [2] * 3, [2] * 3, [1] * 3) == (1, 1, 1)
+    assert path(2, 8, 16, 16, [256, 256], [2, 2], [3, 3], [1, 1], [1, 1], [1, 1]) == (2, 2, 2)
+    # channel counts that are no multiples of 4: direct kernels throughout (3 -> 5 channels still fit 16-wide tiles)
+    assert path(2, 2, 33, 35, [40, 40], [2, 2], [3, 3], [1, 1], [1, 1], [1, 1])[:2] == (0, 0)
+    # k = 3 with dilation 16, k = 7 with dilation 6, 32 channels: the patch of even the narrowest window exceeds
+    # the pieces a thread can stage; k = 3 with dilation 3 still fits
+    assert path(2, 1, 32, 32, [80, 80], [2, 2], [3, 3], [1, 1], [16, 16], [16, 16])[:2] == (0, 0)
+    assert path(2, 1, 32, 32, [90, 90], [2, 2], [7, 7], [1, 1], [18, 18], [6, 6])[:2] == (0, 0)
+    assert path(2, 1, 32, 32, [60, 64], [2, 2], [3, 3], [1, 1], [12, 12], [12, 12])[:2] == (1, 1)   # the narrowest window
+    assert path(2, 1, 32, 32, [80, 80], [2, 2], [3, 3], [1, 1], [3, 3], [3, 3])[:2] == (1, 1)
+
+
+def test_table_cache_policy_never_rewrites_a_block_another_reader_may_hold():
+    """The device-table cache (pointer arrays, GEMM descriptors), run without a device: eight blocks per stream with
+    least-recently-used replacement, no replacement across streams, blocks selected during capture pinned for good,
+    unknown tables refused during capture, and an error instead of an eviction when nothing may be reused."""
+    pol = dd.distdl_debug_slot_policy
+    # steady state: a repeated table reuses its block
+    assert pol([0, 0, 0, 0], [7, 8, 7, 8], [0] * 4) == [0, 1, 0, 1]
+    # the ninth distinct table on a stream replaces that stream's least recently used block
+    seq = list(range(1, 10))
+    assert pol([0] * 9, seq, [0] * 9) == [0, 1, 2, 3, 4, 5, 6, 7, 0]
+    assert pol([0] * 10, [1, 2, 3, 4, 5, 6, 7, 8, 1, 9], [0] * 10)[-1] == 1      # table 1 was touched again: 2 goes
+    # another stream never takes over a block: the same table on stream 1 gets a block of its own, and stream 1's
+    # ninth table replaces one of ITS blocks
+    got = pol([0, 1] + [1] * 8, [5, 5] + list(range(10, 18)), [0] * 10)
+    assert got[0] == 0 and got[1] == 1 and got[-1] == 1 and 0 not in got[1:]
+    # a table first seen during capture is refused (its copy would read host memory at replay)
+    assert pol([0, 0], [1, 2], [0, 1]) == [0, dd.ERR_INVALID_ARG]
+    # a block selected during capture is pinned: eight more tables on the stream leave it alone ...
+    got = pol([0] * 11, [1, 1] + list(range(2, 11)), [0, 1] + [0] * 9)
+    assert got[1] == 0 and 0 not in got[2:]
+    # ... and the recorded table is still found afterwards
+    assert pol([0] * 12, [1, 1] + list(range(2, 11)) + [1], [0, 1] + [0] * 10)[-1] == 0
+    # 64 blocks, all pinned by captures: the next new table fails with NOMEM instead of evicting one
+    streams, tables, cap = [], [], []
+    for t in range(64):
+        streams += [0, 0]
+        tables += [100 + t, 100 + t]
+        cap += [0, 1]
+    got = pol(streams + [0], tables + [999], cap + [0])
+    assert sorted(set(got[:-1])) == list(range(64)) and got[-1] == dd.ERR_NOMEM
