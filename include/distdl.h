@@ -380,6 +380,20 @@ int distdl_allreduce(void* const bufs_dev[], const int64_t count[], int G, int k
 int distdl_dot(const void* const a_dev[], const void* const b_dev[], const int64_t count[], int n_arrays,
                distdl_dtype dtype, double* result_dev, void* stream);
 
+/* distdl_dot for callers that cannot allocate device memory: code that runs
+ * under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same arguments, kernels, summation order and result as
+ * distdl_dot; the partial sums live in a device array that is part of the
+ * library's code object (8 KiB per GPU, held until the process ends), so the
+ * call allocates nothing, copies no table and frees nothing.  Limit: at most
+ * 96 array pairs (INVALID_ARG beyond; distdl_dot has no limit).  All calls
+ * on one GPU share that array: it keeps the last call's partial sums, which
+ * the next call overwrites before it reads them, and calls that overlap in
+ * time on one GPU race.  The first call on a device looks the array's address
+ * up; make it before a capture starts. */
+int distdl_dot_static(const void* const a_dev[], const void* const b_dev[], const int64_t count[], int n_arrays,
+                      distdl_dtype dtype, double* result_dev, void* stream);
+
 /* ------------------------------------------------------------------------
  * Measurement support.  plan_stats: cell counts behind the algorithmic-bytes
  * figures of the halo kernels, summed over all workers and per sample and

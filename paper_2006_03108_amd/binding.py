@@ -74,6 +74,7 @@ _SIGS = {
     "distdl_affine_fwd": [_vp, _pp, _pp, _pp, _pp, _vp],
     "distdl_affine_bwd": [_vp, _pp, _pp, _pp, _pp, _pp, _pp, _vp],
     "distdl_dot": [_pp, _pp, _p64, _i, _i, _vp, _vp],
+    "distdl_dot_static": [_pp, _pp, _p64, _i, _i, _vp, _vp],
     "distdl_relu_fwd": [_pp, _pp, _p64, _i, _vp],
     "distdl_relu_bwd": [_pp, _pp, _pp, _p64, _i, _vp],
     "distdl_maxpool_fwd": [_vp, _pp, _pp, _vp],
@@ -439,6 +440,12 @@ def distdl_dot(a, b, result):
     """result: a 1-element float64 device tensor."""
     _check(lib.distdl_dot(_ptrs(a), _ptrs(b), _arr(C.c_int64, [t.numel() for t in a]), len(a),
                           _dtype_code(a[0].dtype), result.data_ptr(), _stream()))
+
+
+def distdl_dot_static(a, b, result):
+    """distdl_dot without any allocation (scratch in a static device array); at most 96 array pairs."""
+    _check(lib.distdl_dot_static(_ptrs(a), _ptrs(b), _arr(C.c_int64, [t.numel() for t in a]), len(a),
+                                 _dtype_code(a[0].dtype), result.data_ptr(), _stream()))
 
 
 def distdl_plan_stats(plan):
