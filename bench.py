@@ -263,12 +263,12 @@ class MovementWorkload:
     def step(self):
         dd, s = self.dd, self.turn % self.SETS
         self.turn += 1
-        dd.distdl_halo_fwd(self.plan, self.x)
-        dd.distdl_halo_adj(self.plan, self.g)
         dd.distdl_bcast_fwd([self.one[s]], self.many[s], self.K)
         dd.distdl_bcast_adj([self.one[s]], self.many[s], self.K, False)
-        dd.distdl_sumreduce_fwd(self.many[s], [self.one[s]], self.K, False)
+        dd.distdl_halo_fwd(self.plan, self.x)
         dd.distdl_sumreduce_adj([self.one[s]], self.many[s], self.K)
+        dd.distdl_sumreduce_fwd(self.many[s], [self.one[s]], self.K, False)
+        dd.distdl_halo_adj(self.plan, self.g)
 
     def value(self, seconds_per_step):
         return self.bytes_step / seconds_per_step / 1e9

@@ -67,8 +67,13 @@ struct BF16x1 {
   __device__ static Store zero() { return 0; }
 };
 
-// Every halo, padding and band cell is touched once per call: stream them past
-// the caches with the non-temporal hint.
+// Every halo, padding and band cell is touched once per call, so loads carry the
+// non-temporal hint.  Stores: the ones that carry data (halo copies, band sums)
+// are plain, the zero fills (padding cells, cleared halo cells) non-temporal.
+// Measured on the 64-worker volumetric geometry, that mix runs the forward
+// kernel at 6.3 TB/s and the adjoint at 6.0 TB/s; with every store non-temporal
+// both stay at 4.9-5.0 TB/s, with every store plain at 5.4 / 4.7 TB/s, and the
+// opposite mix is as fast only when a plan has padding to clear.
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 // The buffers are device allocations: the address-space cast makes these
 // global_load / global_store instead of flat accesses.
@@ -82,6 +87,16 @@ __device__ inline S nt_load(const S* p) {
     return out;
   } else {
     return __builtin_nontemporal_load((const DISTDL_GLOBAL S*)p);
+  }
+}
+template <class S>
+__device__ inline void plain_store(S* p, const S& val) {
+  if constexpr (sizeof(S) == 16) {
+    u32x4 v;
+    __builtin_memcpy(&v, &val, 16);
+    *(DISTDL_GLOBAL u32x4*)p = v;
+  } else {
+    *(DISTDL_GLOBAL S*)p = val;
   }
 }
 template <class S>
@@ -145,7 +160,7 @@ __global__ __launch_bounds__(kThreads) void halo_fwd_kernel(const BlockRef* __re
   }
 #pragma unroll
   for (int i = 0; i < kUnroll; ++i)
-    if (live[i]) nt_store(dst + doff[i], vals[i]);
+    if (live[i]) plain_store(dst + doff[i], vals[i]);
 }
 
 // Adjoint: bulk boxes gather-add their halo copies and clear them; padding
@@ -208,7 +223,7 @@ __global__ __launch_bounds__(kThreads) void halo_adj_kernel(const BlockRef* __re
   }
 #pragma unroll
   for (int i = 0; i < kUnroll; ++i)
-    if (live[i]) nt_store(dst + view_offset(t.dst, pos[i]), E::pack(acc[i]));
+    if (live[i]) plain_store(dst + view_offset(t.dst, pos[i]), E::pack(acc[i]));
 }
 
 int plan_prepare_device(distdl_plan* p);

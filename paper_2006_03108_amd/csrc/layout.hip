@@ -3,7 +3,7 @@
 // plane of feature-space cells per channel); the kernels of this library keep
 // channels last.  A caller that holds planes-first tensors converts them
 // here: per (worker, sample) this is the transpose of an n_c x cells matrix,
-// staged through LDS in tiles of 32 channels x 64 cells so that both sides
+// staged through LDS in tiles of 32 channels x 128 cells so that both sides
 // are read and written in contiguous runs (256-byte runs of one channel's
 // plane; whole cells, as 16-byte pieces, on the channels-last side).
 #include <algorithm>
@@ -14,7 +14,7 @@
 namespace distdl {
 
 constexpr int kLayoutWorkers = 32;  // workers per launch (pointers travel as kernel arguments)
-constexpr int kTileCells = 64, kTileCh = 32;
+constexpr int kTileCells = 256, kTileCh = 32;
 
 struct LayoutArgs {
   const void* src[kLayoutWorkers];
@@ -30,7 +30,12 @@ __global__ __launch_bounds__(256) void layout_kernel(LayoutArgs a) {
   __shared__ T tile[kTileCells][kTileCh + 1];  // [cell][channel], odd pitch: the cell-major side is conflict-free
   const int w = blockIdx.z, n = blockIdx.y;
   const int cells = a.cells[w];
-  const int ct = blockIdx.x / a.ch_tiles, cht = blockIdx.x - ct * a.ch_tiles;
+  // Workgroups are dealt to the eight XCDs round-robin by their index.  Tiles that are neighbours along a plane
+  // share the cache lines their 4-byte-aligned runs straddle, so consecutive tiles are given to one XCD (one L2):
+  // the shared line is fetched once, and the two halves of a written line meet in one cache.
+  const uint32_t r = (blockIdx.x & 7u) * (gridDim.x >> 3) + (blockIdx.x >> 3);
+  if (r >= (uint32_t)a.cell_tiles_max * a.ch_tiles) return;
+  const int ct = r / a.ch_tiles, cht = r - ct * a.ch_tiles;
   const int cell0 = ct * kTileCells, ch0 = cht * kTileCh;
   if (cell0 >= cells) return;
   const int tid = threadIdx.x;
@@ -41,22 +46,36 @@ __global__ __launch_bounds__(256) void layout_kernel(LayoutArgs a) {
   // channels-last side: 32 channels of a cell are contiguous
   const T* cl_src = (const T*)a.src[w] + sample;
   T* cl_dst = (T*)a.dst[w] + sample;
+  // planes-first side: a wave covers 64 consecutive cells of one channel (256 bytes), all loads of a thread are
+  // issued before the first LDS write so that a block has its whole 16 KB tile in flight
   const int pc = tid & 63, pr = tid >> 6;
+  constexpr int kPasses = (kTileCells / 64) * (kTileCh / 4);
   if (TO_CL) {
+    T v[kPasses];
 #pragma unroll
-    for (int i = 0; i < kTileCh / 4; ++i) {
-      const int ch = pr + 4 * i;
-      if (cell0 + pc < cells && ch0 + ch < a.n_c) tile[pc][ch] = pf_src[(size_t)(ch0 + ch) * cells + cell0 + pc];
+    for (int i = 0; i < kPasses; ++i) {
+      const int ch = pr + 4 * (i % (kTileCh / 4)), c = pc + 64 * (i / (kTileCh / 4));
+      v[i] = 0;
+      if (cell0 + c < cells && ch0 + ch < a.n_c)
+        v[i] = __builtin_nontemporal_load(pf_src + (size_t)(ch0 + ch) * cells + cell0 + c);
     }
+#pragma unroll
+    for (int i = 0; i < kPasses; ++i) tile[pc + 64 * (i / (kTileCh / 4))][pr + 4 * (i % (kTileCh / 4))] = v[i];
   } else if (sizeof(T) == 4 && a.vec) {
     const int k4 = (tid & 7) * 4, cc0 = tid >> 3;  // 8 pieces per cell, 32 cells per pass
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    u32x4 v[kTileCells / 32];
 #pragma unroll
     for (int i = 0; i < kTileCells / 32; ++i) {
       const int cc = cc0 + 32 * i;
-      if (cell0 + cc < cells && ch0 + k4 < a.n_c) {
-        const uint4 v = *(const uint4*)(cl_src + (size_t)(cell0 + cc) * a.n_c + ch0 + k4);
-        tile[cc][k4] = (T)v.x, tile[cc][k4 + 1] = (T)v.y, tile[cc][k4 + 2] = (T)v.z, tile[cc][k4 + 3] = (T)v.w;
-      }
+      v[i] = u32x4{0, 0, 0, 0};
+      if (cell0 + cc < cells && ch0 + k4 < a.n_c)
+        v[i] = __builtin_nontemporal_load((const u32x4*)(cl_src + (size_t)(cell0 + cc) * a.n_c + ch0 + k4));
+    }
+#pragma unroll
+    for (int i = 0; i < kTileCells / 32; ++i) {
+      const int cc = cc0 + 32 * i;
+      tile[cc][k4] = (T)v[i][0], tile[cc][k4 + 1] = (T)v[i][1], tile[cc][k4 + 2] = (T)v[i][2], tile[cc][k4 + 3] = (T)v[i][3];
     }
   } else {
     const int k = tid & 31, cc0 = tid >> 5;
@@ -69,9 +88,9 @@ __global__ __launch_bounds__(256) void layout_kernel(LayoutArgs a) {
   __syncthreads();
   if (!TO_CL) {
 #pragma unroll
-    for (int i = 0; i < kTileCh / 4; ++i) {
-      const int ch = pr + 4 * i;
-      if (cell0 + pc < cells && ch0 + ch < a.n_c) pf_dst[(size_t)(ch0 + ch) * cells + cell0 + pc] = tile[pc][ch];
+    for (int i = 0; i < kPasses; ++i) {
+      const int ch = pr + 4 * (i % (kTileCh / 4)), c = pc + 64 * (i / (kTileCh / 4));
+      if (cell0 + c < cells && ch0 + ch < a.n_c) pf_dst[(size_t)(ch0 + ch) * cells + cell0 + c] = tile[c][ch];
     }
   } else if (sizeof(T) == 4 && a.vec) {
     const int k4 = (tid & 7) * 4, cc0 = tid >> 3;
@@ -132,7 +151,7 @@ extern "C" int distdl_layout_convert(const distdl_plan* plan, int what, int to_c
     a.vec = vec;
     const int64_t gx = (int64_t)a.cell_tiles_max * a.ch_tiles;
     if (gx >= (int64_t(1) << 31)) return set_error(DISTDL_ERR_UNSUPPORTED, "layout_convert: tensor too large");
-    const dim3 grid((unsigned)gx, (unsigned)plan->n_b, (unsigned)nw), block(256);
+    const dim3 grid((unsigned)((gx + 7) / 8 * 8), (unsigned)plan->n_b, (unsigned)nw), block(256);
     ProfScope prof(to_channels_last ? "layout_to_cl" : "layout_from_cl", st);
     if (esz == 4) {
       if (to_channels_last) hipLaunchKernelGGL((layout_kernel<uint32_t, true>), grid, block, 0, st, a);
