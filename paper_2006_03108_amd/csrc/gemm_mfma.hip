@@ -353,6 +353,40 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(const GemmBlock* __restr
   //   C[m0 + 32*(wy*TM + im) + 8*(v/4) + 4*h + v%4][n0 + 32*(wx*TN + in) + ml]
   float* pc = nullptr;
   if (gridDim.y > 1) pc = partial + ((size_t)blockIdx.z * gridDim.y + blockIdx.y) * partial_stride;
+  if constexpr (BF16) {
+    // bf16 results: lane = column in the MFMA layout, so storing from registers is one 2-byte store per element
+    // (64 per thread with 128-tiles: measured, that epilogue was 60 % of a weight-gradient workgroup's lifetime).
+    // Instead the tile is rounded into LDS (the stage buffers are done with) and written out in 16-byte pieces,
+    // 256 contiguous bytes per tile row.
+    if (!pc && gb.ldc % 8 == 0 && gb.N % 8 == 0 && ((uintptr_t)gb.c & 15) == 0) {  // uniform
+      constexpr int CP = TILE_N * 2 + 16;  // bytes per staged row
+      static_assert(TILE_M * CP <= (SB ? 1 : 2) * (A_BYTES + B_BYTES), "output tile must fit the stage buffers");
+      __syncthreads();
+#pragma unroll
+      for (int in = 0; in < TN; ++in) {
+        const int cl = 32 * (wx * TN + in) + ml, col = n0 + cl;
+        float bias = 0.f;
+        if (gb.bias && col < gb.N) bias = __uint_as_float((uint32_t)((const uint16_t*)gb.bias)[col] << 16);
+#pragma unroll
+        for (int im = 0; im < TM; ++im)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            const int rl = 32 * (wy * TM + im) + 8 * (v / 4) + 4 * h + (v % 4);
+            *(__bf16*)(smem + rl * CP + cl * 2) = (__bf16)(acc[im][in][v] + bias);  // round to nearest even
+          }
+      }
+      __syncthreads();
+      constexpr int PPR = TILE_N / 8;  // 16-byte pieces per row
+#pragma unroll
+      for (int p = tid; p < TILE_M * PPR; p += 256) {
+        const int rl = p / PPR, q = p - rl * PPR;
+        const int row = m0 + rl, col = n0 + q * 8;
+        if (row < gb.M && col < gb.N)
+          *(u32x4*)((uint16_t*)gb.c + (size_t)row * gb.ldc + col) = *(const u32x4*)(smem + rl * CP + q * 16);
+      }
+      return;
+    }
+  }
 #pragma unroll
   for (int in = 0; in < TN; ++in) {
     const int col = n0 + 32 * (wx * TN + in) + ml;
