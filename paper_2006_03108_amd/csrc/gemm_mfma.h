@@ -37,6 +37,11 @@ int gemm_mfma_splits(const std::vector<GemmBlock>& blocks, bool bf16);
 size_t gemm_mfma_partial_floats(const std::vector<GemmBlock>& blocks, int nsplit);
 int launch_gemm_mfma(const GemmBlock* d_blocks, const std::vector<GemmBlock>& blocks, bool bf16, bool a_kc, bool b_kc,
                      int nsplit, float* partial, const char* name, hipStream_t st);
+// The small-batch bf16 path (gemm_stream.hip): 64 x 64 tiles over the whole K range, every wave its own K-slice
+// pipeline fed by global -> LDS loads.  Usable when A is contiguous along K and every K (and, for an N-contiguous B,
+// N) is a multiple of 8.
+bool gemm_stream_usable(const std::vector<GemmBlock>& blocks, bool a_kc, bool b_kc);
+int launch_gemm_stream(const GemmBlock* d_blocks, const std::vector<GemmBlock>& blocks, bool b_kc, hipStream_t st);
 int launch_colsum(const ColsumBlock* d_blocks, int nblocks, int max_f, bool bf16, hipStream_t st);
 
 }  // namespace distdl

@@ -588,6 +588,9 @@ int launch_gemm_mfma(const GemmBlock* d_blocks, const std::vector<GemmBlock>& bl
   if (!a_kc && b_kc) return set_error(DISTDL_ERR_UNSUPPORTED, "gemm: operand layout not built");
   dim3 grid((unsigned)tiles, (unsigned)std::max(nsplit, 1), (unsigned)blocks.size()), block(256);
   ProfScope prof(name, st);
+  // bf16 launches that take 64-tiles over the whole K range (about one tile per compute unit: the small-batch
+  // forward and data-gradient products) are bound by the operand feed and run on the streaming kernel
+  if (bf16 && t == 64 && nsplit <= 1 && gemm_stream_usable(blocks, a_kc, b_kc)) return launch_gemm_stream(d_blocks, blocks, b_kc, st);
   int rc;
 #define DISTDL_GEMM(BF_, A_, B_)                                                                \
   rc = t == 128 ? launch_gemm_variant<BF_, A_, B_, 2>(grid, d_blocks, partial, max_mn, st)      \

@@ -270,6 +270,7 @@ AFFINE_CASES = [
     (7, 13, 9, 3, 2), (5, 33, 17, 1, 1), (64, 256, 192, 1, 4), (33, 130, 70, 4, 1),
     (128, 3000, 1024, 1, 3),       # K splits that straddle the column workers' segments, ragged last K stage
     (200, 2064, 3096, 1, 2),       # small batch, wide layer: ragged tiles in M, N and K
+    (100, 1048, 528, 2, 1),        # small batch: ragged M, N and K tails in the forward and the data-gradient product, two row workers
 ]
 
 
