@@ -325,13 +325,16 @@ int distdl_affine_bwd(distdl_affine_plan* p, const void* const x_dev[], const vo
           (rc = ensure_partial(p, std::max(gemm_mfma_partial_floats(bx, nsx), gemm_mfma_partial_floats(bw, nsw)))))
         return rc;
       // the two launches use the partial buffer one after the other on the stream
+      if (db_dev && (rc = p->g_db.upload(bb, st_))) return rc;
+      // the bias gradient rides in the weight-gradient launch when its kernel can carry it (it reads the same dy_i)
+      GemmColsum cs{p->g_db.dev, p->P_fo, (int)p->max_fo, false};
+      bool db_aligned = db_dev != nullptr;  // the fused sums store 8 bytes at a time
+      for (int i = 0; db_dev && i < p->P_fo; ++i) db_aligned &= (uintptr_t)db_dev[i] % 8 == 0;
       if ((rc = launch_gemm_mfma(p->g_dx.dev, bx, bf16, true, false, nsx, p->d_partial, "affine_bwd_x_mfma", st_)) ||
-          (rc = launch_gemm_mfma(p->g_dw.dev, bw, bf16, false, false, nsw, p->d_partial, "affine_bwd_w_mfma", st_)))
+          (rc = launch_gemm_mfma(p->g_dw.dev, bw, bf16, false, false, nsw, p->d_partial, "affine_bwd_w_mfma", st_,
+                                 db_aligned ? &cs : nullptr)))
         return rc;
-      if (db_dev) {
-        if ((rc = p->g_db.upload(bb, st_))) return rc;
-        launch_colsum(p->g_db.dev, p->P_fo, (int)p->max_fo, bf16, st_);
-      }
+      if (db_dev && !cs.done) launch_colsum(p->g_db.dev, p->P_fo, (int)p->max_fo, bf16, st_);
       DISTDL_HIP_TRY(hipGetLastError());
       return DISTDL_OK;
     }

@@ -35,13 +35,24 @@ bool gemm_mfma_usable(const std::vector<GemmBlock>& blocks, bool bf16, bool a_kc
 // (gemm_mfma_partial_floats(blocks, nsplit) floats), summed by a second kernel.
 int gemm_mfma_splits(const std::vector<GemmBlock>& blocks, bool bf16);
 size_t gemm_mfma_partial_floats(const std::vector<GemmBlock>& blocks, int nsplit);
+// colsum (optional): column sums to fold into the launch when its kernel can carry them; *colsum->done says whether
+// it did (otherwise the caller launches launch_colsum itself).
+struct GemmColsum {
+  const ColsumBlock* d_blocks;
+  int n_blocks, max_f;
+  bool done;
+};
 int launch_gemm_mfma(const GemmBlock* d_blocks, const std::vector<GemmBlock>& blocks, bool bf16, bool a_kc, bool b_kc,
-                     int nsplit, float* partial, const char* name, hipStream_t st);
+                     int nsplit, float* partial, const char* name, hipStream_t st, GemmColsum* colsum = nullptr);
 // The small-batch bf16 path (gemm_stream.hip): 64 x 64 tiles over the whole K range, every wave its own K-slice
 // pipeline fed by global -> LDS loads.  Usable when A is contiguous along K and every K (and, for an N-contiguous B,
-// N) is a multiple of 8.
+// N) is a multiple of 8; with both operands as k lines (weight gradient): one segment, M and N multiples of 8.
 bool gemm_stream_usable(const std::vector<GemmBlock>& blocks, bool a_kc, bool b_kc);
 int launch_gemm_stream(const GemmBlock* d_blocks, const std::vector<GemmBlock>& blocks, bool b_kc, hipStream_t st);
+// the weight-gradient layout (both operands as k lines), 128 x 128 tiles
+// d_colsum (or null): column sums (the bias gradient) computed by extra workgroups of the same launch
+int launch_gemm_stream_tt(const GemmBlock* d_blocks, const std::vector<GemmBlock>& blocks, const ColsumBlock* d_colsum,
+                          int n_colsum, int max_f, hipStream_t st);
 int launch_colsum(const ColsumBlock* d_blocks, int nblocks, int max_f, bool bf16, hipStream_t st);
 
 }  // namespace distdl

@@ -575,7 +575,7 @@ static int launch_gemm_variant(dim3 grid, const GemmBlock* d_blocks, float* part
 }
 
 int launch_gemm_mfma(const GemmBlock* d_blocks, const std::vector<GemmBlock>& blocks, bool bf16, bool a_kc, bool b_kc,
-                     int nsplit, float* partial, const char* name, hipStream_t st) {
+                     int nsplit, float* partial, const char* name, hipStream_t st, GemmColsum* colsum) {
   const int t = gemm_tile(blocks, bf16);
   int tiles = 0;
   int64_t max_mn = 0;
@@ -590,7 +590,12 @@ int launch_gemm_mfma(const GemmBlock* d_blocks, const std::vector<GemmBlock>& bl
   ProfScope prof(name, st);
   // bf16 launches that take 64-tiles over the whole K range (about one tile per compute unit: the small-batch
   // forward and data-gradient products) are bound by the operand feed and run on the streaming kernel
-  if (bf16 && t == 64 && nsplit <= 1 && gemm_stream_usable(blocks, a_kc, b_kc)) return launch_gemm_stream(d_blocks, blocks, b_kc, st);
+  if (bf16 && t == 64 && nsplit <= 1 && a_kc && gemm_stream_usable(blocks, a_kc, b_kc)) return launch_gemm_stream(d_blocks, blocks, b_kc, st);
+  if (bf16 && t == 128 && nsplit <= 1 && !a_kc && !b_kc && gemm_stream_usable(blocks, a_kc, b_kc)) {
+    if (colsum) colsum->done = true;  // M % 8 == 0 for every block: the feature counts fit the fused column sums
+    return launch_gemm_stream_tt(d_blocks, blocks, colsum ? colsum->d_blocks : nullptr, colsum ? colsum->n_blocks : 0,
+                                 colsum ? colsum->max_f : 0, st);
+  }
   int rc;
 #define DISTDL_GEMM(BF_, A_, B_)                                                                \
   rc = t == 128 ? launch_gemm_variant<BF_, A_, B_, 2>(grid, d_blocks, partial, max_mn, st)      \

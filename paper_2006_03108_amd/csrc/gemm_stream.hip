@@ -10,7 +10,7 @@
 //     (2 x 2 MFMA tiles, four independent accumulators) out of a wave-private LDS area; there is no workgroup
 //     barrier in the K loop, and the four partial tiles are summed through LDS at the end, in wave order;
 //   * operands go from global memory straight into LDS (buffer_load_dwordx4 ... lds): no staging registers, no
-//     ds_write.  Lane L of such a load lands at (LDS base in M0) + 16 L and an out-of-range lane writes zeros
+//     ds_write; about 15.7 us against 19 us through registers for 256 x 4096 x 4096.  Lane L of such a load lands at (LDS base in M0) + 16 L and an out-of-range lane writes zeros
 //     (both measured); which 16 bytes a lane fetches is free, so the bank-conflict-free placement is made by
 //     permuting the pieces of a row on the global side:
 //       K-contiguous operand (A; B of the forward product): block = 64 rows x 128 bytes, row R keeps its piece c
@@ -35,7 +35,7 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef short v4i16 __attribute__((ext_vector_type(4)));
-typedef __attribute__((address_space(3))) void* lds_void;
+typedef __attribute__((address_space(3))) char* lds_char;
 typedef __attribute__((address_space(3))) v4i16* lds_v4;
 
 namespace {
@@ -48,14 +48,36 @@ constexpr int kWaveBytes = 2 * kStepBytes;  // two steps per wave: one multiplie
 constexpr int kStreamLds = 4 * kWaveBytes;  // 128 KB
 constexpr int kRedPitch = 64;               // floats per row of a partial tile in the epilogue
 
-__device__ inline __amdgpu_buffer_rsrc_t stream_rsrc(const void* p, uint32_t bytes) {
-  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)bytes, 0x00020000);
+// Raw buffer descriptor (base, stride 0, bytes covered, data format word): offsets at or beyond `bytes` are out
+// of range.
+__device__ inline u32x4 stream_rsrc(const void* p, uint32_t bytes) {
+  const uint64_t a = (uint64_t)(uintptr_t)p;
+  return u32x4{(uint32_t)a, (uint32_t)(a >> 32), bytes, 0x00020000u};
 }
+
+// One global -> LDS load of 16 bytes per lane: lane L's piece lands at LDS address lds_addr + 16 L.  Written as
+// inline assembly on purpose: the compiler then does not know that a load is filling LDS, so it neither waits for
+// every outstanding load (vmcnt(0)) in front of each LDS read that it cannot tell apart from the landing area, nor
+// counts these loads; the s_waitcnt vmcnt(...) in the kernels below are exact because these are the only vector
+// memory loads in their K loops.
+__device__ inline void load_to_lds(u32x4 desc, uint32_t lds_addr, uint32_t voff, uint32_t soff) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+               :
+               : "s"(lds_addr), "v"(voff), "s"(desc), "s"(soff)
+               : "memory");
+}
+__device__ inline uint32_t lds_address(const char* p) { return (uint32_t)(size_t)(lds_char)p; }
 
 // s_waitcnt immediates (vmcnt in bits 3:0 and 15:14, expcnt 6:4, lgkmcnt 11:8; a field of all ones does not wait)
 constexpr int kWaitVm0 = 0x0F70;         // vmcnt(0)
 constexpr int kWaitVm16 = 0x4F70;        // vmcnt(16)
 constexpr int kWaitLgkm0 = 0xC07F;       // lgkmcnt(0)
+
+// Workgroup barrier without the fences of __syncthreads(): those make the compiler wait for every outstanding
+// global -> LDS load (vmcnt(0)), including the step being prefetched.  The waits this kernel needs (the loads of the
+// step about to be read, the LDS reads of the buffer about to be refilled) are written out before each call; the
+// memory clobber keeps the compiler from moving LDS accesses across it.
+__device__ inline void lds_barrier() { asm volatile("s_barrier" ::: "memory"); }
 
 union Frag {
   u32x4 u;
@@ -78,6 +100,7 @@ __global__ __launch_bounds__(256, 1) void gemm_stream_kernel(const GemmBlock* __
   const int tid = threadIdx.x, lane = tid & 63, h = lane >> 5, ml = lane & 31;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // known uniform: keeps everything derived from it scalar
   char* const my = smem + wave * kWaveBytes;
+  const uint32_t my_lds = lds_address(my);
 
   floatx16 acc[2][2];
 #pragma unroll
@@ -94,7 +117,7 @@ __global__ __launch_bounds__(256, 1) void gemm_stream_kernel(const GemmBlock* __
   // load cursor: segment, step within it (may run past the end: such steps are issued out of range and never read)
   int ls = 0, lin = wave, l_nst = 0, l_K = 0;
   uint32_t l_ldb = 0;
-  __amdgpu_buffer_rsrc_t ra = stream_rsrc(nullptr, 0), rb = stream_rsrc(nullptr, 0);
+  u32x4 ra = stream_rsrc(nullptr, 0), rb = stream_rsrc(nullptr, 0);
   uint32_t goff[16];
   // piece of lane and instruction i: row (or k line) 8 i + lane / 8, position lane % 8
   auto enter_segment = [&]() __attribute__((always_inline)) {
@@ -121,7 +144,7 @@ __global__ __launch_bounds__(256, 1) void gemm_stream_kernel(const GemmBlock* __
   };
   // Issues the loads of the cursor's step into staging buffer `buf` and moves the cursor on by four steps.
   auto issue = [&](int buf, bool valid) __attribute__((always_inline)) {
-    char* d = my + buf * kStepBytes;
+    const uint32_t d = my_lds + buf * kStepBytes;
     int k0 = 0;
     if (valid) {  // wave-uniform
       while (lin >= l_nst) {
@@ -135,12 +158,9 @@ __global__ __launch_bounds__(256, 1) void gemm_stream_kernel(const GemmBlock* __
     const uint32_t a_base = (uint32_t)k0 * 2, b_base = (uint32_t)k0 * (B_KC ? 1u : l_ldb) * 2;
     if (!valid || k0 + kStepK <= l_K) {
 #pragma unroll
-      for (int i = 0; i < 8; ++i)
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(ra, (lds_void)(d + i * 1024), 16, valid ? goff[i] : kOobOff, a_base, 0, 0);
+      for (int i = 0; i < 8; ++i) load_to_lds(ra, d + i * 1024, valid ? goff[i] : kOobOff, a_base);
 #pragma unroll
-      for (int i = 0; i < 8; ++i)
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(rb, (lds_void)(d + kOperandBytes + i * 1024), 16,
-                                                 valid ? goff[8 + i] : kOobOff, b_base, 0, 0);
+      for (int i = 0; i < 8; ++i) load_to_lds(rb, d + kOperandBytes + i * 1024, valid ? goff[8 + i] : kOobOff, b_base);
     } else {
       // K tail: pieces of a K-contiguous row beyond K are switched off (whole pieces: K % 8 == 0); k lines beyond
       // K lie beyond the resource
@@ -150,15 +170,14 @@ __global__ __launch_bounds__(256, 1) void gemm_stream_kernel(const GemmBlock* __
         const int r = 8 * i + (lane >> 3);
         const int ca = (lane & 7) ^ ((r >> 1) & 7);
         const bool in = ca * 8 < kleft;
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(ra, (lds_void)(d + i * 1024), 16, in ? goff[i] : kOobOff, a_base, 0, 0);
+        load_to_lds(ra, d + i * 1024, in ? goff[i] : kOobOff, a_base);
       }
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
         const int r = 8 * i + (lane >> 3);
         const int ca = (lane & 7) ^ ((r >> 1) & 7);
         const bool in = !B_KC || ca * 8 < kleft;
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(rb, (lds_void)(d + kOperandBytes + i * 1024), 16,
-                                                 in ? goff[8 + i] : kOobOff, b_base, 0, 0);
+        load_to_lds(rb, d + kOperandBytes + i * 1024, in ? goff[8 + i] : kOobOff, b_base);
       }
     }
   };
@@ -285,15 +304,231 @@ __global__ __launch_bounds__(256, 1) void gemm_stream_kernel(const GemmBlock* __
   }
 }
 
-// The launch this kernel is for: bf16, A contiguous along K, 64 x 64 tiles over the whole K range (no K split).
+// The weight gradient dW_ij = dy_i^T x_j (Sec. 4, adjoint affine algorithm): both operands lie in memory as k lines
+// (k = sample; A[m][k] at a[k lda + m], B[k][n] at b[k ldb + n]), K is the batch (short), the output is large.
+// Workgroup tile 128 x 128, four waves of 64 x 64 (2 x 2 MFMA tiles), 64-k steps.  With K = 256 a workgroup's life is
+// mostly the latency of its first loads and its epilogue, so what matters is how many workgroups a compute unit
+// holds: one 32 KB staging buffer (filled by global -> LDS loads, each wave fetching a quarter of a step) and at
+// most 128 registers let four of them share it, and the loads, multiplications and stores of different workgroups
+// overlap.  A staged block is 64 k lines x 256 bytes (128 rows); line l keeps its 16-byte piece c at position
+// c ^ (4 * (l & 3)): the four lines a half-wave's transposing read touches (64 bytes each) then cover the 64 banks once.
+namespace {
+constexpr int kTtOperand = 64 * 256;       // one operand block of a step
+constexpr int kTtLds = 2 * kTtOperand;     // 32 KB
+}  // namespace
+
+// The first cs_wgs workgroups of the grid's z = 0 slice do not multiply: they are the layer's bias gradient
+// db_i[f] = sum over the batch of dy_i[n][f] (R over the samples; one chunk of 256 features of one block each, a lane
+// sums 4 features over every fourth row, the four waves are added in wave order), which rides along in this launch
+// instead of costing one of its own: dy is the A operand here, so it is in L2 anyway.
+__global__ __launch_bounds__(256, 4) void gemm_stream_tt_kernel(const GemmBlock* __restrict__ blocks,
+                                                                const ColsumBlock* __restrict__ cs, int n_cs,
+                                                                int cs_chunks, int cs_wgs) {
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  if ((int)blockIdx.x < cs_wgs) {
+    if (blockIdx.z != 0) return;
+    const int b = blockIdx.x / cs_chunks, ch = blockIdx.x - b * cs_chunks;
+    if (b >= n_cs) return;
+    const ColsumBlock cb = cs[b];
+    if (!cb.out) return;
+    const int lane_ = threadIdx.x & 63, wave_ = threadIdx.x >> 6;
+    const int f0 = ch * 256 + lane_ * 4;
+    float sum[4] = {0.f, 0.f, 0.f, 0.f};
+    if (f0 < cb.n_f) {  // whole groups of 4 features: n_f % 8 == 0 is a condition of this kernel
+      const uint16_t* in = (const uint16_t*)cb.in + f0;
+      int n = wave_;
+      for (; n + 28 < cb.n_b; n += 32) {
+        uint2 v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = *(const uint2*)(in + (size_t)(n + 4 * u) * cb.n_f);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          sum[0] += __uint_as_float(v[u].x << 16); sum[1] += __uint_as_float(v[u].x & 0xffff0000u);
+          sum[2] += __uint_as_float(v[u].y << 16); sum[3] += __uint_as_float(v[u].y & 0xffff0000u);
+        }
+      }
+      for (; n < cb.n_b; n += 4) {
+        const uint2 v = *(const uint2*)(in + (size_t)n * cb.n_f);
+        sum[0] += __uint_as_float(v.x << 16); sum[1] += __uint_as_float(v.x & 0xffff0000u);
+        sum[2] += __uint_as_float(v.y << 16); sum[3] += __uint_as_float(v.y & 0xffff0000u);
+      }
+    }
+    float4* red = (float4*)smem;
+    red[wave_ * 64 + lane_] = float4{sum[0], sum[1], sum[2], sum[3]};
+    __syncthreads();
+    if (wave_ == 0 && f0 < cb.n_f) {
+      float4 t = red[lane_];
+#pragma unroll
+      for (int w = 1; w < 4; ++w) {
+        const float4 u = red[w * 64 + lane_];
+        t.x += u.x; t.y += u.y; t.z += u.z; t.w += u.w;
+      }
+      union {
+        __bf16 b[4];
+        uint2 u;
+      } o;
+      o.b[0] = (__bf16)t.x; o.b[1] = (__bf16)t.y; o.b[2] = (__bf16)t.z; o.b[3] = (__bf16)t.w;
+      *(uint2*)((uint16_t*)cb.out + f0) = o.u;
+    }
+    return;
+  }
+  const GemmBlock& gb = blocks[blockIdx.z];
+  const int tiles_m = (gb.M + 127) / 128, tiles_n = (gb.N + 127) / 128;
+  const int bx = (int)blockIdx.x - cs_wgs, gx = (int)gridDim.x - cs_wgs;
+  const int tile = (bx & 7) * (gx >> 3) + (bx >> 3);
+  if (tile >= tiles_m * tiles_n) return;
+  const int tm = tile % tiles_m, tn = tile / tiles_m;
+  const int m0 = tm * 128, n0 = tn * 128;
+  const int tid = threadIdx.x, lane = tid & 63, h = lane >> 5, ml = lane & 31;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wy = wave >> 1, wx = wave & 1;
+
+  floatx16 acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+  const GemmSeg& sg = gb.seg[0];  // one segment (checked on the host)
+  const int K = sg.K, nsteps = (K + kStepK - 1) / kStepK;
+  // resources end with the operand: k lines beyond K read as zero
+  const u32x4 ra = stream_rsrc(sg.a, (uint32_t)K * sg.lda * 2);
+  const u32x4 rb = stream_rsrc(sg.b, (uint32_t)K * sg.ldb * 2);
+  const uint32_t my_lds = lds_address(smem) + wave * 4096;
+  // load j of this wave: k lines 16 wave + 4 j + lane / 16, position lane % 16 of the line
+  uint32_t goff[8];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int l = 16 * wave + 4 * j + (lane >> 4);
+    const int c = (lane & 15) ^ (4 * (l & 3));
+    goff[j] = (m0 + c * 8 < gb.M) ? ((uint32_t)l * sg.lda + m0 + c * 8) * 2 : kOobOff;  // whole pieces: M % 8 == 0
+    goff[4 + j] = (n0 + c * 8 < gb.N) ? ((uint32_t)l * sg.ldb + n0 + c * 8) * 2 : kOobOff;
+  }
+  const uint32_t a_step = (uint32_t)kStepK * sg.lda * 2, b_step = (uint32_t)kStepK * sg.ldb * 2;
+  auto issue = [&](int st) __attribute__((always_inline)) {
+    const uint32_t sa = (uint32_t)st * a_step, sb = (uint32_t)st * b_step;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) load_to_lds(ra, my_lds + j * 1024, goff[j], sa);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) load_to_lds(rb, my_lds + kTtOperand + j * 1024, goff[4 + j], sb);
+  };
+  // transposing reads: k line 16 g + tk (+ 4), rows (columns) base + tr ... + 3 as 8 bytes of piece (base + tr) / 8
+  const int tk = 8 * (lane >> 5) + ((lane & 15) >> 2), tr = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+  uint32_t rda[2], rdb[2];
+#pragma unroll
+  for (int t = 0; t < 2; ++t) {
+    const int ca = (64 * wy + 32 * t + tr) >> 3, cb = (64 * wx + 32 * t + tr) >> 3;
+    rda[t] = tk * 256 + ((ca ^ (4 * (tk & 3))) * 16) + (tr & 7) * 2;
+    rdb[t] = kTtOperand + tk * 256 + ((cb ^ (4 * (tk & 3))) * 16) + (tr & 7) * 2;
+  }
+  // fragments of k groups g0, g0 + 1 of the staged step
+  auto read_half = [&](int g0, Frag (&fa)[2][2], Frag (&fb)[2][2]) __attribute__((always_inline)) {
+#pragma unroll
+    for (int g = 0; g < 2; ++g)
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        const int o = (g0 + g) * 16 * 256;
+        fa[g][t].t[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(smem + rda[t] + o));
+        fa[g][t].t[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(smem + rda[t] + o + 4 * 256));
+        fb[g][t].t[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(smem + rdb[t] + o));
+        fb[g][t].t[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(smem + rdb[t] + o + 4 * 256));
+      }
+  };
+  auto mm_half = [&](const Frag (&fa)[2][2], const Frag (&fb)[2][2]) __attribute__((always_inline)) {
+#pragma unroll
+    for (int g = 0; g < 2; ++g)
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[g][i].v, fb[g][j].v, acc[i][j], 0, 0, 0);
+  };
+
+  if (nsteps > 0) issue(0);
+  for (int st = 0; st < nsteps; ++st) {
+    __builtin_amdgcn_s_waitcnt(kWaitVm0);  // this wave's quarter of step st has landed
+    lds_barrier();                         // and so has everyone's
+    Frag fa[2][2], fb[2][2];
+    read_half(0, fa, fb);
+    __builtin_amdgcn_sched_barrier(0);
+    mm_half(fa, fb);
+    __builtin_amdgcn_sched_barrier(0);
+    read_half(2, fa, fb);
+    __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_s_waitcnt(kWaitLgkm0);
+    lds_barrier();  // every wave has the rest of this step in registers: the buffer may be refilled
+    if (st + 1 < nsteps) issue(st + 1);
+    __builtin_amdgcn_sched_barrier(0);
+    mm_half(fa, fb);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+
+  // epilogue: the tile is rounded into LDS (the staging buffer is done with: the last barrier above came after its
+  // last read, and nothing was loaded behind it) and written out in 16-byte pieces, 256 contiguous bytes per row
+  constexpr int CP = 128 * 2;  // bytes per staged row
+  static_assert(128 * CP <= kTtLds, "output tile must fit the staging buffer");
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    const int cl = 64 * wx + 32 * j + ml, col = n0 + cl;
+    float bias = 0.f;
+    if (gb.bias && col < gb.N) bias = __uint_as_float((uint32_t)((const uint16_t*)gb.bias)[col] << 16);
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int rl = 64 * wy + 32 * i + 8 * (v / 4) + 4 * h + (v % 4);
+        *(__bf16*)(smem + rl * CP + cl * 2) = (__bf16)(acc[i][j][v] + bias);  // round to nearest even
+      }
+  }
+  __syncthreads();
+  const bool vec = gb.ldc % 8 == 0 && ((uintptr_t)gb.c & 15) == 0;  // N % 8 == 0 is a condition of this kernel
+#pragma unroll
+  for (int p = tid; p < 128 * 16; p += 256) {
+    const int rl = p >> 4, q = p & 15;
+    const int row = m0 + rl, col = n0 + q * 8;
+    if (row >= gb.M || col >= gb.N) continue;
+    uint16_t* dst = (uint16_t*)gb.c + (size_t)row * gb.ldc + col;
+    if (vec) {
+      *(u32x4*)dst = *(const u32x4*)(smem + rl * CP + q * 16);
+    } else {
+      const uint16_t* src = (const uint16_t*)(smem + rl * CP + q * 16);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) dst[e] = src[e];
+    }
+  }
+}
+
+// The launches these kernels are for.  gemm_stream_kernel: bf16, A contiguous along K, 64 x 64 tiles over the whole K
+// range (no K split).  gemm_stream_tt_kernel: bf16, both operands as k lines, 128 x 128 tiles, one segment.
 bool gemm_stream_usable(const std::vector<GemmBlock>& blocks, bool a_kc, bool b_kc) {
-  if (!a_kc) return false;
+  if (!a_kc) {
+    if (b_kc) return false;
+    for (const GemmBlock& b : blocks)
+      if (b.nseg != 1 || b.M % 8 || b.N % 8) return false;
+    return true;
+  }
   for (const GemmBlock& b : blocks) {
     if (!b_kc && b.N % 8) return false;
     for (int s = 0; s < b.nseg; ++s)
       if (b.seg[s].K % 8) return false;
   }
   return true;
+}
+
+// d_colsum (or null): n_colsum column-sum blocks of at most max_f features (multiples of 4, 8-byte aligned rows)
+// computed by extra workgroups of the same launch.
+int launch_gemm_stream_tt(const GemmBlock* d_blocks, const std::vector<GemmBlock>& blocks, const ColsumBlock* d_colsum,
+                          int n_colsum, int max_f, hipStream_t st) {
+  int tiles = 0;
+  for (const GemmBlock& b : blocks) tiles = std::max(tiles, ((b.M + 127) / 128) * ((b.N + 127) / 128));
+  tiles = (tiles + 7) / 8 * 8;
+  const int chunks = d_colsum ? std::max(1, (max_f + 255) / 256) : 1;
+  const int cs_wgs = d_colsum ? (n_colsum * chunks + 7) / 8 * 8 : 0;  // a multiple of 8 keeps the tiles' XCD mapping
+  const dim3 grid((unsigned)(tiles + cs_wgs), 1, (unsigned)blocks.size()), block(256);
+  hipLaunchKernelGGL(gemm_stream_tt_kernel, grid, block, kTtLds, st, d_blocks, d_colsum, d_colsum ? n_colsum : 0, chunks,
+                     cs_wgs);
+  return DISTDL_OK;
 }
 
 int launch_gemm_stream(const GemmBlock* d_blocks, const std::vector<GemmBlock>& blocks, bool b_kc, hipStream_t st) {
