@@ -330,11 +330,15 @@ int distdl_affine_bwd(distdl_affine_plan* p, const void* const x_dev[], const vo
       GemmColsum cs{p->g_db.dev, p->P_fo, (int)p->max_fo, false};
       bool db_aligned = db_dev != nullptr;  // the fused sums store 8 bytes at a time
       for (int i = 0; db_dev && i < p->P_fo; ++i) db_aligned &= (uintptr_t)db_dev[i] % 8 == 0;
-      if ((rc = launch_gemm_mfma(p->g_dx.dev, bx, bf16, true, false, nsx, p->d_partial, "affine_bwd_x_mfma", st_)) ||
-          (rc = launch_gemm_mfma(p->g_dw.dev, bw, bf16, false, false, nsw, p->d_partial, "affine_bwd_w_mfma", st_,
-                                 db_aligned ? &cs : nullptr)))
-        return rc;
-      if (db_dev && !cs.done) launch_colsum(p->g_db.dev, p->P_fo, (int)p->max_fo, bf16, st_);
+      // dx and dW on one stream, one after the other.  Measured: dW on a side stream between a fork and a join event
+      // (its 32 KB workgroups fit next to the 128 KB ones of dx) makes the step slower, eager and from a graph
+      // (72 against 61 us at 256 x 4096 x 4096): both launches are bound by what a compute unit can take in.
+      rc = launch_gemm_mfma(p->g_dx.dev, bx, bf16, true, false, nsx, p->d_partial, "affine_bwd_x_mfma", st_);
+      if (!rc)
+        rc = launch_gemm_mfma(p->g_dw.dev, bw, bf16, false, false, nsw, p->d_partial, "affine_bwd_w_mfma", st_,
+                              db_aligned ? &cs : nullptr);
+      if (!rc && db_dev && !cs.done) launch_colsum(p->g_db.dev, p->P_fo, (int)p->max_fo, bf16, st_);
+      if (rc) return rc;
       DISTDL_HIP_TRY(hipGetLastError());
       return DISTDL_OK;
     }

@@ -320,6 +320,77 @@ def test_affine_fwd_bwd(n_b, n_fi, n_fo, P_fo, P_fi, dtype, use_bias):
                  tol, "y vs sequential")
 
 
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
+@pytest.mark.parametrize("n_b,n_fi,n_fo,P_fo,P_fi", [(256, 1024, 768, 2, 2), (100, 1048, 528, 2, 1)])
+def test_affine_step_replayed_from_a_graph_matches_eager(n_b, n_fi, n_fo, P_fo, P_fi, dtype):
+    """A warmed-up affine forward + adjoint (in bf16: the streaming kernels fed by global -> LDS loads, the bias
+    gradient inside the weight-gradient launch) recorded into a HIP graph and replayed on
+    new data, with eager work and synchronisations between the replays, must reproduce the eager step bit for bit;
+    the eager step itself is checked against the oracle."""
+    require_gpu()
+    rows, cols = layers.feature_blocks(n_fo, P_fo), layers.feature_blocks(n_fi, P_fi)
+    rng = np.random.default_rng(11)
+    conv = syn.to_bf16_values if dtype == torch.bfloat16 else (lambda a: a)
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dtype).cuda()
+    W = conv((rng.standard_normal((n_fo, n_fi)) / np.sqrt(n_fi)).astype(np.float32))
+    b = conv(rng.standard_normal(n_fo).astype(np.float32))
+    g_W = [dev(W[r][:, c]) for r in rows for c in cols]
+    g_b = [dev(b[r]) for r in rows]
+    new_batch = lambda: (conv(rng.standard_normal((n_b, n_fi)).astype(np.float32)),
+                         conv(rng.standard_normal((n_b, n_fo)).astype(np.float32)))
+    g_x = [torch.zeros((n_b, c.stop - c.start), dtype=dtype, device="cuda") for c in cols]
+    g_dy = [torch.zeros((n_b, r.stop - r.start), dtype=dtype, device="cuda") for r in rows]
+    g_y = [torch.zeros_like(t) for t in g_dy]
+    g_dx = [torch.zeros_like(t) for t in g_x]
+    g_dW = [torch.zeros_like(t) for t in g_W]
+    g_db = [torch.zeros_like(t) for t in g_b]
+    plan = dd.distdl_affine_plan_create(n_b, n_fi, n_fo, P_fo, P_fi, dtype)
+
+    def step():
+        dd.distdl_affine_fwd(plan, g_x, g_W, g_b, g_y)
+        dd.distdl_affine_bwd(plan, g_x, g_W, g_dy, g_dx, g_dW, g_db)
+
+    def load(x, dy):
+        for dst, c in zip(g_x, cols):
+            dst.copy_(dev(x[:, c]))
+        for dst, r in zip(g_dy, rows):
+            dst.copy_(dev(dy[:, r]))
+
+    snapshot = lambda: [t.clone() for t in g_y + g_dx + g_dW + g_db]
+    batches = [new_batch() for _ in range(3)]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    eager = []
+    with torch.cuda.stream(side):
+        for x, dy in batches:
+            load(x, dy)
+            step()
+            eager.append(snapshot())
+    side.synchronize()
+    # the last eager step against the oracle
+    x, dy = batches[-1]
+    tol = TOL32 if dtype == torch.float32 else TOL16
+    host = lambda t: t.float().cpu().numpy()
+    y_want = layers.affine_forward(x, W, b)
+    assert_close(np.concatenate([host(t) for t in g_y], axis=1), y_want, tol, "y")
+    dx_want, dW_want, db_want = layers.affine_backward(x, W, dy)
+    assert_close(np.concatenate([host(t) for t in g_dx], axis=1), dx_want, tol, "dx")
+    for i, r in enumerate(rows):
+        assert_close(host(g_db[i]), db_want[r], tol, f"db_{i}")
+        for j, c in enumerate(cols):
+            assert_close(host(g_dW[i * P_fi + j]), dW_want[r][:, c], tol, f"dW_{i}{j}")
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        step()
+    for (x, dy), want in zip(batches, eager):
+        load(x, dy)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for got, ref in zip(snapshot(), want):
+            assert torch.equal(got, ref)
+
+
 # ---------------------------------------------------------------- full-size volumetric configuration
 def _sample_indices(rng, shape, count):
     return [tuple(int(rng.integers(0, s)) for s in shape) for _ in range(count)]
