@@ -46,7 +46,6 @@ constexpr int kOperandBytes = 64 * 128;    // one operand block of a step
 constexpr int kStepBytes = 2 * kOperandBytes;
 constexpr int kWaveBytes = 2 * kStepBytes;  // two steps per wave: one multiplied, one landing
 constexpr int kStreamLds = 4 * kWaveBytes;  // 128 KB
-constexpr int kRedPitch = 64;               // floats per row of a partial tile in the epilogue
 
 // Raw buffer descriptor (base, stride 0, bytes covered, data format word): offsets at or beyond `bytes` are out
 // of range.
@@ -216,7 +215,7 @@ __global__ __launch_bounds__(256, 1) void gemm_stream_kernel(const GemmBlock* __
       for (int i = 0; i < 2; ++i)
 #pragma unroll
         for (int j = 0; j < 2; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[g][i].v, fb[g][j].v, acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[g][j].v, fa[g][i].v, acc[i][j], 0, 0, 0);
   };
 
   if (n > 0) {
@@ -249,27 +248,32 @@ __global__ __launch_bounds__(256, 1) void gemm_stream_kernel(const GemmBlock* __
     __builtin_amdgcn_s_waitcnt(kWaitVm0);  // nothing may still land in LDS when the epilogue reuses it
   }
 
-  // Sum of the four waves' partial tiles in wave order, bias, rounding, store.
+  // Sum of the four waves' partial tiles in wave order, bias, rounding, store.  The products were accumulated
+  // transposed (B fragment as the first MFMA operand): register v of lane (h, ml) of tile (i, j) is
+  // C[32 i + ml][32 j + 8 (v / 4) + 4 h + v % 4], four consecutive columns per register quad, so a partial tile goes
+  // to LDS in 16-byte writes.  Row m keeps its float4 number s at position s ^ (m & 15): 16 lanes, 16 bank groups.
   __syncthreads();
-  float* red = (float*)smem;  // [wave][64][kRedPitch]
+  float4* red = (float4*)smem;  // [wave][64 rows][16 float4]
 #pragma unroll
   for (int i = 0; i < 2; ++i)
 #pragma unroll
     for (int j = 0; j < 2; ++j)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int row = 32 * i + 8 * (v / 4) + 4 * h + (v % 4), col = 32 * j + ml;
-        red[(wave * 64 + row) * kRedPitch + col] = acc[i][j][v];
+      for (int q = 0; q < 4; ++q) {
+        const int m = 32 * i + ml, s4 = 8 * j + 2 * q + h;
+        red[(wave * 64 + m) * 16 + (s4 ^ (m & 15))] =
+            float4{acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
       }
   __syncthreads();
   const int row = tid >> 2, c0 = (tid & 3) * 16;
   float s[16];
 #pragma unroll
   for (int q = 0; q < 4; ++q) {
-    float4 t = *(const float4*)(red + (size_t)row * kRedPitch + c0 + 4 * q);
+    const int slot = ((c0 >> 2) + q) ^ (row & 15);
+    float4 t = red[row * 16 + slot];
 #pragma unroll
     for (int w = 1; w < 4; ++w) {
-      const float4 u = *(const float4*)(red + (size_t)(w * 64 + row) * kRedPitch + c0 + 4 * q);
+      const float4 u = red[(w * 64 + row) * 16 + slot];
       t.x += u.x; t.y += u.y; t.z += u.z; t.w += u.w;
     }
     s[4 * q] = t.x; s[4 * q + 1] = t.y; s[4 * q + 2] = t.z; s[4 * q + 3] = t.w;
@@ -306,15 +310,18 @@ __global__ __launch_bounds__(256, 1) void gemm_stream_kernel(const GemmBlock* __
 
 // The weight gradient dW_ij = dy_i^T x_j (Sec. 4, adjoint affine algorithm): both operands lie in memory as k lines
 // (k = sample; A[m][k] at a[k lda + m], B[k][n] at b[k ldb + n]), K is the batch (short), the output is large.
-// Workgroup tile 128 x 128, four waves of 64 x 64 (2 x 2 MFMA tiles), 64-k steps.  With K = 256 a workgroup's life is
-// mostly the latency of its first loads and its epilogue, so what matters is how many workgroups a compute unit
-// holds: one 32 KB staging buffer (filled by global -> LDS loads, each wave fetching a quarter of a step) and at
-// most 128 registers let four of them share it, and the loads, multiplications and stores of different workgroups
-// overlap.  A staged block is 64 k lines x 256 bytes (128 rows); line l keeps its 16-byte piece c at position
+// Workgroup tile 128 x 128, four waves of 64 x 64 (2 x 2 MFMA tiles), 32-k steps.  With K = 256 a workgroup's life is
+// mostly the latency of its loads and its epilogue, so what matters is how many workgroups a compute unit holds and
+// that a step's loads fly while the step before is multiplied: two staging buffers of 16 KB (filled by
+// global -> LDS loads, each wave fetching a quarter of a step) and at most 128 registers let four workgroups share a
+// compute unit.  A staged block is 32 k lines x 256 bytes (128 rows); line l keeps its 16-byte piece c at position
 // c ^ (4 * (l & 3)): the four lines a half-wave's transposing read touches (64 bytes each) then cover the 64 banks once.
 namespace {
-constexpr int kTtOperand = 64 * 256;       // one operand block of a step
-constexpr int kTtLds = 2 * kTtOperand;     // 32 KB
+constexpr int kTtStepK = 32;
+constexpr int kTtOperand = kTtStepK * 256;  // one operand block of a step
+constexpr int kTtStep = 2 * kTtOperand;     // 16 KB
+constexpr int kTtLds = 2 * kTtStep;         // 32 KB
+constexpr int kWaitVm4 = 0x0F74;            // vmcnt(4)
 }  // namespace
 
 // The first cs_wgs workgroups of the grid's z = 0 slice do not multiply: they are the layer's bias gradient
@@ -391,27 +398,28 @@ __global__ __launch_bounds__(256, 4) void gemm_stream_tt_kernel(const GemmBlock*
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
   const GemmSeg& sg = gb.seg[0];  // one segment (checked on the host)
-  const int K = sg.K, nsteps = (K + kStepK - 1) / kStepK;
+  const int K = sg.K, nsteps = (K + kTtStepK - 1) / kTtStepK;
   // resources end with the operand: k lines beyond K read as zero
   const u32x4 ra = stream_rsrc(sg.a, (uint32_t)K * sg.lda * 2);
   const u32x4 rb = stream_rsrc(sg.b, (uint32_t)K * sg.ldb * 2);
-  const uint32_t my_lds = lds_address(smem) + wave * 4096;
-  // load j of this wave: k lines 16 wave + 4 j + lane / 16, position lane % 16 of the line
-  uint32_t goff[8];
+  const uint32_t my_lds = lds_address(smem) + wave * 2048;
+  // load j of this wave: k lines 8 wave + 4 j + lane / 16, position lane % 16 of the line
+  uint32_t goff[4];
 #pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    const int l = 16 * wave + 4 * j + (lane >> 4);
+  for (int j = 0; j < 2; ++j) {
+    const int l = 8 * wave + 4 * j + (lane >> 4);
     const int c = (lane & 15) ^ (4 * (l & 3));
     goff[j] = (m0 + c * 8 < gb.M) ? ((uint32_t)l * sg.lda + m0 + c * 8) * 2 : kOobOff;  // whole pieces: M % 8 == 0
-    goff[4 + j] = (n0 + c * 8 < gb.N) ? ((uint32_t)l * sg.ldb + n0 + c * 8) * 2 : kOobOff;
+    goff[2 + j] = (n0 + c * 8 < gb.N) ? ((uint32_t)l * sg.ldb + n0 + c * 8) * 2 : kOobOff;
   }
-  const uint32_t a_step = (uint32_t)kStepK * sg.lda * 2, b_step = (uint32_t)kStepK * sg.ldb * 2;
+  const uint32_t a_step = (uint32_t)kTtStepK * sg.lda * 2, b_step = (uint32_t)kTtStepK * sg.ldb * 2;
   auto issue = [&](int st) __attribute__((always_inline)) {
+    const uint32_t d = my_lds + (st & 1) * kTtStep;
     const uint32_t sa = (uint32_t)st * a_step, sb = (uint32_t)st * b_step;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) load_to_lds(ra, my_lds + j * 1024, goff[j], sa);
+    for (int j = 0; j < 2; ++j) load_to_lds(ra, d + j * 1024, goff[j], sa);
 #pragma unroll
-    for (int j = 0; j < 4; ++j) load_to_lds(rb, my_lds + kTtOperand + j * 1024, goff[4 + j], sb);
+    for (int j = 0; j < 2; ++j) load_to_lds(rb, d + kTtOperand + j * 1024, goff[2 + j], sb);
   };
   // transposing reads: k line 16 g + tk (+ 4), rows (columns) base + tr ... + 3 as 8 bytes of piece (base + tr) / 8
   const int tk = 8 * (lane >> 5) + ((lane & 15) >> 2), tr = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
@@ -422,65 +430,70 @@ __global__ __launch_bounds__(256, 4) void gemm_stream_tt_kernel(const GemmBlock*
     rda[t] = tk * 256 + ((ca ^ (4 * (tk & 3))) * 16) + (tr & 7) * 2;
     rdb[t] = kTtOperand + tk * 256 + ((cb ^ (4 * (tk & 3))) * 16) + (tr & 7) * 2;
   }
-  // fragments of k groups g0, g0 + 1 of the staged step
-  auto read_half = [&](int g0, Frag (&fa)[2][2], Frag (&fb)[2][2]) __attribute__((always_inline)) {
+
+  if (nsteps > 0) issue(0);
+  if (nsteps > 1) issue(1);
+  for (int st = 0; st < nsteps; ++st) {
+    const char* sbuf = smem + (st & 1) * kTtStep;
+    // this wave's quarter of step st has landed (the four loads of step st + 1 may be in flight)
+    if (st + 1 < nsteps) __builtin_amdgcn_s_waitcnt(kWaitVm4);
+    else __builtin_amdgcn_s_waitcnt(kWaitVm0);
+    lds_barrier();  // and so has everyone's
+    Frag fa[2][2], fb[2][2];
 #pragma unroll
     for (int g = 0; g < 2; ++g)
 #pragma unroll
       for (int t = 0; t < 2; ++t) {
-        const int o = (g0 + g) * 16 * 256;
-        fa[g][t].t[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(smem + rda[t] + o));
-        fa[g][t].t[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(smem + rda[t] + o + 4 * 256));
-        fb[g][t].t[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(smem + rdb[t] + o));
-        fb[g][t].t[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(smem + rdb[t] + o + 4 * 256));
+        const int o = g * 16 * 256;
+        fa[g][t].t[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(sbuf + rda[t] + o));
+        fa[g][t].t[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(sbuf + rda[t] + o + 4 * 256));
+        fb[g][t].t[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(sbuf + rdb[t] + o));
+        fb[g][t].t[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(sbuf + rdb[t] + o + 4 * 256));
       }
-  };
-  auto mm_half = [&](const Frag (&fa)[2][2], const Frag (&fb)[2][2]) __attribute__((always_inline)) {
+    __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_s_waitcnt(kWaitLgkm0);
+    lds_barrier();  // every wave has this step in registers: its buffer may be refilled
+    if (st + 2 < nsteps) issue(st + 2);
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int g = 0; g < 2; ++g)
 #pragma unroll
       for (int i = 0; i < 2; ++i)
 #pragma unroll
         for (int j = 0; j < 2; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[g][i].v, fb[g][j].v, acc[i][j], 0, 0, 0);
-  };
-
-  if (nsteps > 0) issue(0);
-  for (int st = 0; st < nsteps; ++st) {
-    __builtin_amdgcn_s_waitcnt(kWaitVm0);  // this wave's quarter of step st has landed
-    lds_barrier();                         // and so has everyone's
-    Frag fa[2][2], fb[2][2];
-    read_half(0, fa, fb);
-    __builtin_amdgcn_sched_barrier(0);
-    mm_half(fa, fb);
-    __builtin_amdgcn_sched_barrier(0);
-    read_half(2, fa, fb);
-    __builtin_amdgcn_sched_barrier(0);
-    __builtin_amdgcn_s_waitcnt(kWaitLgkm0);
-    lds_barrier();  // every wave has the rest of this step in registers: the buffer may be refilled
-    if (st + 1 < nsteps) issue(st + 1);
-    __builtin_amdgcn_sched_barrier(0);
-    mm_half(fa, fb);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[g][j].v, fa[g][i].v, acc[i][j], 0, 0, 0);
     __builtin_amdgcn_sched_barrier(0);
   }
 
-  // epilogue: the tile is rounded into LDS (the staging buffer is done with: the last barrier above came after its
-  // last read, and nothing was loaded behind it) and written out in 16-byte pieces, 256 contiguous bytes per row
+  // epilogue: the tile is rounded into LDS (the staging buffers are done with: the last barrier above came after
+  // their last read, and nothing was loaded behind it) and written out in 16-byte pieces, 256 contiguous bytes per row.
+  // The products were accumulated transposed (B fragment as the first MFMA operand): register v of lane (h, ml) of
+  // tile (i, j) is C[64 wy + 32 i + ml][64 wx + 32 j + 8 (v / 4) + 4 h + v % 4], so a register quad is four
+  // consecutive columns: one 8-byte LDS write.  Row m keeps its 16-byte piece c at position c ^ (m & 15).
   constexpr int CP = 128 * 2;  // bytes per staged row
   static_assert(128 * CP <= kTtLds, "output tile must fit the staging buffer");
 #pragma unroll
-  for (int j = 0; j < 2; ++j) {
-    const int cl = 64 * wx + 32 * j + ml, col = n0 + cl;
-    float bias = 0.f;
-    if (gb.bias && col < gb.N) bias = __uint_as_float((uint32_t)((const uint16_t*)gb.bias)[col] << 16);
+  for (int j = 0; j < 2; ++j)
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int q = 0; q < 4; ++q) {
+      const int cl = 64 * wx + 32 * j + 8 * q + 4 * h, col = n0 + cl;  // first of the quad's four columns
+      float bias[4] = {0.f, 0.f, 0.f, 0.f};
+      if (gb.bias && col < gb.N) {  // whole quads: N % 8 == 0
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int rl = 64 * wy + 32 * i + 8 * (v / 4) + 4 * h + (v % 4);
-        *(__bf16*)(smem + rl * CP + cl * 2) = (__bf16)(acc[i][j][v] + bias);  // round to nearest even
+        for (int e = 0; e < 4; ++e) bias[e] = __uint_as_float((uint32_t)((const uint16_t*)gb.bias)[col + e] << 16);
       }
-  }
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        const int rl = 64 * wy + 32 * i + ml;
+        union {
+          __bf16 b[4];
+          uint2 u;
+        } o;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) o.b[e] = (__bf16)(acc[i][j][4 * q + e] + bias[e]);  // round to nearest even
+        *(uint2*)(smem + rl * CP + (((cl >> 3) ^ (rl & 15)) * 16) + (cl & 7) * 2) = o.u;
+      }
+    }
   __syncthreads();
   const bool vec = gb.ldc % 8 == 0 && ((uintptr_t)gb.c & 15) == 0;  // N % 8 == 0 is a condition of this kernel
 #pragma unroll
@@ -490,9 +503,9 @@ __global__ __launch_bounds__(256, 4) void gemm_stream_tt_kernel(const GemmBlock*
     if (row >= gb.M || col >= gb.N) continue;
     uint16_t* dst = (uint16_t*)gb.c + (size_t)row * gb.ldc + col;
     if (vec) {
-      *(u32x4*)dst = *(const u32x4*)(smem + rl * CP + q * 16);
+      *(u32x4*)dst = *(const u32x4*)(smem + rl * CP + ((q ^ (rl & 15)) * 16));
     } else {
-      const uint16_t* src = (const uint16_t*)(smem + rl * CP + q * 16);
+      const uint16_t* src = (const uint16_t*)(smem + rl * CP + ((q ^ (rl & 15)) * 16));
 #pragma unroll
       for (int e = 0; e < 8; ++e) dst[e] = src[e];
     }
