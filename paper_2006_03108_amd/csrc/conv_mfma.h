@@ -24,7 +24,9 @@ struct CorrArgs {
   int32_t ck;      // contraction channels per chunk: 8, or 16 when the launch multiplies in bf16
   int32_t R, Cw, CwQ;  // patch rows, cells per row, cells per residue class of the row
   int32_t a_vec4;      // patch size in 16-byte units
-  FastDiv div_cw, div_tc, div_is2;  // exact division by Cw, tc, is[2] in the per-workgroup set-up
+  int32_t a_pad;       // the same, rounded up to whole 64-lane loads (the variant that loads straight into LDS)
+  int32_t bufb;        // bytes of one staging buffer of that variant: patch (a_pad units), then the weights
+  FastDiv div_cw, div_tc, div_is2, div_cwq;  // exact division by Cw, tc, is[2], CwQ in the per-workgroup set-up
   int32_t tiles_max;   // tiles of the largest worker
   const float* wt;     // weights in staging order
   const int* tapinfo;  // device tables behind the weights: 8 plane offsets, then one patch offset per (t1, t2)

@@ -24,6 +24,7 @@
 
 #include "common.h"
 #include "conv_mfma.h"
+#include "lds_direct.h"
 #include "profile.h"
 
 namespace distdl {
@@ -87,17 +88,23 @@ __device__ inline float load_scalar(const void* p, size_t i) {
 // weights were widened by the re-layout kernel.  MODE 2: bf16 tensors multiplied as bf16 on
 // v_mfma_f32_32x32x16_bf16 (fp32 accumulation): a chunk is 16 channels, a 16-byte piece holds 8 of them and is one
 // MFMA operand (A lane l holds A[i = l % 32][k = 8 * (l / 32) ... + 7]); needs channel counts that are multiples of 8.
-template <int MT, int PA, int PB, int NT, int MODE>
+// DMA (small patches with NT > 0, MODE 0 or 2): a stage goes from memory straight into LDS (global -> LDS loads, no
+// staging registers, no ds_write) into one of two staging buffers, the next stage landing while this one is
+// multiplied, one barrier per stage.  The LDS layout of a stage is the same; thread (i, tid) fetches the piece whose
+// slot is i * 256 + tid (a wave's load fills 64 consecutive slots), found by inverting the slot formula.
+template <int MT, int PA, int PB, int NT, int MODE, bool DMA = false>
 __global__ __launch_bounds__(256, 2) void corr_mfma_kernel(const WorkerDev* __restrict__ workers,
                                                            void* const* in_bufs, void* const* out_bufs, CorrArgs a) {
   extern __shared__ float4 lds[];
   constexpr bool BF16 = MODE != 0, BFM = MODE == 2;
   constexpr uint32_t ES = BF16 ? 2u : 4u;  // bytes per element in memory
   constexpr int CK = BFM ? 16 : 8;         // channels per chunk (two 16-byte pieces per cell in LDS)
+  static_assert(!DMA || (NT > 0 && MODE != 1), "the direct-to-LDS variant needs compile-time taps and 16-byte pieces");
   // LDS: patch (a_vec4 16-byte units), weights (nb_vec4), one spare unit that absorbs the pieces nobody
-  // needs, then the tap table.
+  // needs, then the tap table.  DMA: two buffers of (a_pad + nb_vec4) units, then the spare unit and the table.
   const int nb_vec4 = a.nt[1] * a.nt[2] * 64;
-  const int dummy = a.a_vec4 + nb_vec4;
+  const int a_units = DMA ? a.a_pad : a.a_vec4;  // where the weights of a buffer start
+  const int dummy = DMA ? 2 * (a.a_pad + nb_vec4) : a.a_vec4 + nb_vec4;
   uint32_t* tap_tab = (uint32_t*)(lds + dummy + 1);  // byte offset into the patch per (t1, t2), read as a broadcast
 
   // XCD-aware order: consecutive tiles (which share input rows) stay on one XCD, i.e. behind one L2
@@ -133,27 +140,45 @@ __global__ __launch_bounds__(256, 2) void corr_mfma_kernel(const WorkerDev* __re
   // per-thread patch pieces: byte offset inside an input plane and LDS slot, fixed for the whole tile.
   // When the channel count is not a multiple of 8, bit 0 marks the pieces of the upper half of a chunk:
   // in the last chunk they lie beyond the channels and must read as zero.
-  uint32_t goff[PA], loff[PA];
+  uint32_t goff[PA], loff[DMA ? 1 : PA];
   const int npieces = a.R * a.Cw * 2;
 #pragma unroll
   for (int i = 0; i < PA; ++i) {
-    const int piece = tid + i * 256;
     goff[i] = kOob;
-    loff[i] = dummy * 16;
-    if (piece < npieces) {
-      const int ph = piece & 1, cell = piece >> 1;
-      const int rr = (int)fd_div((uint32_t)cell, a.div_cw), c = cell - rr * a.Cw;
+    int ph, rr, c;
+    bool live;
+    if constexpr (DMA) {  // the piece that lives in slot tid + i * 256: slot = ((rr * 2 + ph) * is2 + cr) * CwQ + cq
+      const uint32_t slot = (uint32_t)(tid + i * 256);
+      uint32_t t = fd_div(slot, a.div_cwq);
+      const int cq = (int)(slot - t * a.CwQ);
+      const uint32_t t2 = fd_div(t, a.div_is2);
+      const int cr = (int)(t - t2 * a.is[2]);
+      ph = (int)(t2 & 1u), rr = (int)(t2 >> 1), c = cq * a.is[2] + cr;
+      live = slot < (uint32_t)a.a_vec4 && c < a.Cw;
+    } else {
+      const int piece = tid + i * 256;
+      loff[i] = dummy * 16;
+      ph = piece & 1;
+      const int cell = piece >> 1;
+      rr = (int)fd_div((uint32_t)cell, a.div_cw), c = cell - rr * a.Cw;
+      live = piece < npieces;
+      if (live) {
+        const int cq = (int)fd_div((uint32_t)c, a.div_is2), cr = c - cq * a.is[2];
+        loff[i] = (((rr * 2 + ph) * a.is[2] + cr) * a.CwQ + cq) * 16;
+      }
+    }
+    if (live) {
       const int i1 = g.in_base[1] + q1_0 * a.is[1] + a.tapmin[1] + rr;
       const int i2 = g.in_base[2] + q2_0 * a.is[2] + a.tapmin[2] + c;
-      const int cq = (int)fd_div((uint32_t)c, a.div_is2), cr = c - cq * a.is[2];
-      loff[i] = (((rr * 2 + ph) * a.is[2] + cr) * a.CwQ + cq) * 16;
       if (i1 >= 0 && i1 < g.in_ext[1] && i2 >= 0 && i2 < g.in_ext[2])
         goff[i] = ((i1 * si1 + i2 * si2 + ph * (CK / 2)) * ES) | ((a.kc & (CK - 1)) ? ph : 0);
     }
   }
-  uint32_t bl[PB];
+  uint32_t bl[DMA ? 1 : PB];
+  if constexpr (!DMA) {
 #pragma unroll
-  for (int i = 0; i < PB; ++i) bl[i] = (tid + i * 256 < nb_vec4 ? a.a_vec4 + tid + i * 256 : dummy) * 16;
+    for (int i = 0; i < PB; ++i) bl[i] = (tid + i * 256 < nb_vec4 ? a.a_vec4 + tid + i * 256 : dummy) * 16;
+  }
 
   // The workgroup's 128*MT output positions form a tr x tc window, row-major; lane m of M-tile
   // (wave, mt) multiplies window position (wave*MT + mt)*32 + m, and accumulator register v of lane
@@ -182,7 +207,7 @@ __global__ __launch_bounds__(256, 2) void corr_mfma_kernel(const WorkerDev* __re
     }
   }
   const float bias = (a.bias && ch < a.nc) ? load_scalar<BF16>(a.bias, ch) : 0.f;
-  const uint32_t boff0 = tid * 16, bread = ((h * 32 + m) + a.a_vec4) * 16;  // weight piece / operand addresses
+  const uint32_t boff0 = tid * 16, bread = ((h * 32 + m) + a_units) * 16;  // weight piece / operand addresses
 
   const int* __restrict__ tapinfo = a.tapinfo;  // [0..7]: plane offsets, [8..]: patch offset per (t1, t2)
   const int ntaps = a.nt[1] * a.nt[2];
@@ -213,8 +238,33 @@ __global__ __launch_bounds__(256, 2) void corr_mfma_kernel(const WorkerDev* __re
       if (++sp.q0 == nq0) sp.q0 = 0, ++sp.n;
     }
   };
-  u32x4 ra[PA], rb[PB];
+  // DMA: the loads of stage sp, straight into the staging buffer at byte offset `bufoff`
+  const uint32_t lds0 = lds_address(lds);
+  const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+  const lds_u32x4 din = lds_direct_rsrc(in_bufs[worker], (uint32_t)a.n_b * sin * ES);
+  const lds_u32x4 dw = lds_direct_rsrc(a.wt + (size_t)ntile * nt0 * ncc * nb_vec4 * 4, (uint32_t)(nt0 * ncc * nb_vec4) * 16u);
+  auto issue_stage = [&](const StagePos& sp, uint32_t bufoff) {
+    const int t0 = sp.t0, cc = sp.cc;
+    const uint32_t sbase = ((uint32_t)sp.n * sin + (uint32_t)plane_of(sp.q0, t0) * si0 + cc * CK) * ES;
+    const bool last_ragged = ragged && cc == ncc - 1;
+#pragma unroll
+    for (int i = 0; i < PA; ++i) {
+      const int first = i * 256 + wave_u * 64;  // this wave's 64 slots of load i
+      if (first < a.a_pad) {
+        const uint32_t off = last_ragged ? ((goff[i] & 1u) ? kOob : goff[i]) : (ragged ? goff[i] & ~1u : goff[i]);
+        load_to_lds(din, lds0 + bufoff + first * 16, off, sbase);
+      }
+    }
+    const uint32_t wbase = (uint32_t)(t0 * ncc + cc) * nb_vec4 * 16u;
+#pragma unroll
+    for (int i = 0; i < PB; ++i) {
+      const int first = i * 256 + wave_u * 64;
+      if (first < nb_vec4) load_to_lds(dw, lds0 + bufoff + (a.a_pad + first) * 16, boff0, wbase + i * 4096u);
+    }
+  };
+  u32x4 ra[DMA ? 1 : PA], rb[DMA ? 1 : PB];
   auto load_stage = [&](const StagePos& sp) {
+    if constexpr (DMA) return;  // (register staging: not this variant's path)
     const int t0 = sp.t0, cc = sp.cc;
     const uint32_t sbase = ((uint32_t)sp.n * sin + (uint32_t)plane_of(sp.q0, t0) * si0 + cc * CK) * ES;
     if (ragged && cc == ncc - 1) {
@@ -233,6 +283,7 @@ __global__ __launch_bounds__(256, 2) void corr_mfma_kernel(const WorkerDev* __re
     for (int i = 0; i < PB; ++i) rb[i] = __builtin_amdgcn_raw_buffer_load_b128(rw, boff0, wbase + i * 4096u, 0);
   };
   auto write_stage = [&]() {
+    if constexpr (DMA) return;
 #pragma unroll
     for (int i = 0; i < PA; ++i) *(u32x4*)(ldsb + loff[i]) = ra[i];
 #pragma unroll
@@ -248,11 +299,13 @@ __global__ __launch_bounds__(256, 2) void corr_mfma_kernel(const WorkerDev* __re
       for (int mt = 0; mt < MT; ++mt) aaddr[mt][t] = abase[mt] + tapo;
     }
   }
+  // DMA: after every stage the operand addresses move to the other staging buffer (+ bufb, then - bufb, ...)
+  uint32_t bread_cur = bread;
   // tapo: byte offset of the tap inside the patch (NT == 0: read from the LDS table two taps ahead of
   // its use, so that the table read is never waited for)
   auto read_ops = [&](int tap, uint32_t tapo, float4& b, float4 (&av)[MT]) {
     if constexpr (NT > 0) {
-      b = *(const float4*)(ldsb + bread + tap * 1024);
+      b = *(const float4*)(ldsb + bread_cur + tap * 1024);
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt) av[mt] = *(const float4*)(ldsb + aaddr[mt][tap]);
     } else {
@@ -330,19 +383,40 @@ __global__ __launch_bounds__(256, 2) void corr_mfma_kernel(const WorkerDev* __re
   floatx16 acc[MT];
   StagePos sp{p_begin, p_begin / nq0, p_begin % nq0, -1, ncc - 1};  // the stage whose loads are in flight
   advance(sp);
-  if (sp.p < p_end) load_stage(sp);
+  uint32_t buf_cur = 0, buf_nxt = (uint32_t)a.bufb;  // DMA: where the stage in flight lands, and the other buffer
+  if (sp.p < p_end) {
+    if constexpr (DMA) issue_stage(sp, buf_cur);
+    else load_stage(sp);
+  }
   int on = p_begin / nq0, oq0 = p_begin % nq0;
   for (int po = p_begin; po < p_end; ++po) {  // output planes of this workgroup
 #pragma unroll
     for (int t = 0; t < MT; ++t)
       for (int v = 0; v < 16; ++v) acc[t][v] = 0.f;
     while (sp.p == po) {  // the stages that feed output plane po
-      write_stage();
-      __syncthreads();
-      advance(sp);
-      if (sp.p < p_end) load_stage(sp);  // in flight while this stage multiplies
-      compute(acc);
-      __syncthreads();  // everyone is done reading this stage
+      if constexpr (DMA) {
+        // The only loads in flight are this stage's: wait for mine, then for everyone's.  Past the barrier every
+        // wave has also finished multiplying the stage before, so the other buffer may be refilled.
+        __builtin_amdgcn_s_waitcnt(kWaitVmcnt0);
+        lds_barrier();
+        advance(sp);
+        if (sp.p < p_end) issue_stage(sp, buf_nxt);  // lands while this stage multiplies
+        compute(acc);
+        const uint32_t delta = buf_nxt - buf_cur;  // wraps for the way back: addresses are 32-bit
+#pragma unroll
+        for (int t = 0; t < NT; ++t)
+#pragma unroll
+          for (int mt = 0; mt < MT; ++mt) aaddr[mt][t] += delta;
+        bread_cur += delta;
+        { const uint32_t x = buf_cur; buf_cur = buf_nxt; buf_nxt = x; }
+      } else {
+        write_stage();
+        __syncthreads();
+        advance(sp);
+        if (sp.p < p_end) load_stage(sp);  // in flight while this stage multiplies
+        compute(acc);
+        __syncthreads();  // everyone is done reading this stage
+      }
     }
     const uint32_t obase = ((uint32_t)on * son + (uint32_t)(g.out_base[0] + g.os[0] * oq0) * so0) * ES;
     if (++oq0 == nq0) oq0 = 0, ++on;
@@ -930,6 +1004,8 @@ __global__ __launch_bounds__(256) void bias_partial_kernel(const WorkerDev* __re
 // ---- host side ------------------------------------------------------------------
 
 static int lds_bytes(const CorrArgs& a) { return (a.a_vec4 + a.nt[1] * a.nt[2] * 64 + 1) * 16 + (a.nt[1] * a.nt[2] + 4) * 4; }
+// the variant that loads straight into LDS: two staging buffers
+static int lds_bytes_dma(const CorrArgs& a) { return 2 * a.bufb + 16 + (a.nt[1] * a.nt[2] + 4) * 4; }
 
 // Window of tr x tc output positions (tr * tc <= 128 * mt) and everything derived from it.
 static void finish_args(CorrArgs& a, int mt, int tc) {
@@ -949,6 +1025,9 @@ static void finish_args(CorrArgs& a, int mt, int tc) {
   a.Cw = (a.tc - 1) * a.is[2] + a.tapspan[2] + 1;
   a.CwQ = (a.Cw + a.is[2] - 1) / a.is[2];
   a.a_vec4 = a.R * 2 * a.is[2] * a.CwQ;
+  a.a_pad = (a.a_vec4 + 63) / 64 * 64;
+  a.bufb = (a.a_pad + a.nt[1] * a.nt[2] * 64) * 16;
+  a.div_cwq = make_fastdiv((uint32_t)a.CwQ);
   a.div_cw = make_fastdiv((uint32_t)a.Cw);
   a.div_tc = make_fastdiv((uint32_t)a.tc);
   a.div_is2 = make_fastdiv((uint32_t)a.is[2]);
@@ -997,7 +1076,8 @@ static int choose_mt(CorrArgs& a, int nq1max, int nq2max, bool allow3) {
     CorrArgs a3 = a, a2 = a;
     finish_args(a3, 3, choose_tc(384, nq1max, nq2max));
     finish_args(a2, 2, choose_tc(256, nq1max, nq2max));
-    const bool small3 = a3.R * a3.Cw * 2 <= 4 * 256 && a3.nt[1] * a3.nt[2] * 64 <= 3 * 256 && lds_bytes(a3) <= 80 * 1024;
+    const bool small3 = a3.R * a3.Cw * 2 <= 4 * 256 && a3.a_pad <= 4 * 256 && a3.nt[1] * a3.nt[2] * 64 <= 3 * 256 &&
+                        lds_bytes(a3) <= 80 * 1024;
     if (small3 && window_efficiency(384, a3.tc, nq1max, nq2max) > 1.04 * window_efficiency(256, a2.tc, nq1max, nq2max)) {
       a = a3;
       return 3;
@@ -1129,21 +1209,28 @@ static size_t corr_scratch_elems(const CorrArgs& a) { return corr_weight_elems(a
 struct CorrVariant {
   const void* fn = nullptr;
   int (*large_lds)() = nullptr;
+  bool dma = false;  // stages go straight into LDS (two staging buffers)
 };
-template <int MT, int PA, int PB, int NT, int MODE>
+template <int MT, int PA, int PB, int NT, int MODE, bool DMA = false>
 static CorrVariant corr_variant_of() {
-  return CorrVariant{(const void*)corr_mfma_kernel<MT, PA, PB, NT, MODE>, &allow_large_lds<corr_mfma_kernel<MT, PA, PB, NT, MODE>>};
+  return CorrVariant{(const void*)corr_mfma_kernel<MT, PA, PB, NT, MODE, DMA>,
+                     &allow_large_lds<corr_mfma_kernel<MT, PA, PB, NT, MODE, DMA>>, DMA};
 }
 template <int MODE>
 static CorrVariant corr_variant_mode(int mt, bool small, int ntaps) {
-  if (mt == 2 && small && ntaps == 9) return corr_variant_of<2, 4, 3, 9, MODE>();
-  if (mt == 2 && small && ntaps == 6) return corr_variant_of<2, 4, 3, 6, MODE>();
-  if (mt == 2 && small && ntaps == 4) return corr_variant_of<2, 4, 3, 4, MODE>();
+  // Small patches with the taps known at compile time load straight into LDS when the launch multiplies in bf16.
+  // Measured on the data-gradient classes of the 5^3 stride-2 layer: 0.163 -> 0.153 ms per class in bf16 (stages of
+  // 576 MFMA clocks), 0.692 -> 0.698 ms in fp32 (stages of 2048-4608 clocks: what the stage change costs there is not
+  // the ds_write of the staged pieces), so fp32 keeps the register-staged loop.
+  constexpr bool D = MODE == 2;
+  if (mt == 2 && small && ntaps == 9) return corr_variant_of<2, 4, 3, 9, MODE, D>();
+  if (mt == 2 && small && ntaps == 6) return corr_variant_of<2, 4, 3, 6, MODE, D>();
+  if (mt == 2 && small && ntaps == 4) return corr_variant_of<2, 4, 3, 4, MODE, D>();
   if (mt == 2 && small) return corr_variant_of<2, 4, 3, 0, MODE>();
   if constexpr (MODE == 2) {  // three M-tiles per wave: bf16 MFMAs only
-    if (mt == 3 && ntaps == 9) return corr_variant_of<3, 4, 3, 9, 2>();
-    if (mt == 3 && ntaps == 6) return corr_variant_of<3, 4, 3, 6, 2>();
-    if (mt == 3 && ntaps == 4) return corr_variant_of<3, 4, 3, 4, 2>();
+    if (mt == 3 && ntaps == 9) return corr_variant_of<3, 4, 3, 9, 2, true>();
+    if (mt == 3 && ntaps == 6) return corr_variant_of<3, 4, 3, 6, 2, true>();
+    if (mt == 3 && ntaps == 4) return corr_variant_of<3, 4, 3, 4, 2, true>();
     if (mt == 3) return corr_variant_of<3, 4, 3, 0, 2>();
   }
   if (mt == 2 && ntaps == 25) return corr_variant_of<2, kMaxPieces, kMaxBPieces, 25, MODE>();
@@ -1179,9 +1266,9 @@ static int launch_corr(distdl_plan* p, CorrArgs a, const void* w, float* wscratc
   const int mode = corr_mode(p, a);
   const int mt = corr_window(p, a);
   if (mt == 0) return set_error(DISTDL_ERR_UNSUPPORTED, "conv: kernel footprint does not fit in LDS");  // corr_mfma_supported() rules this out
-  const int lds = lds_bytes(a);
-  const bool small = a.R * a.Cw * 2 <= 4 * 256 && a.nt[1] * a.nt[2] * 64 <= 3 * 256;
+  const bool small = a.R * a.Cw * 2 <= 4 * 256 && a.nt[1] * a.nt[2] * 64 <= 3 * 256 && a.a_pad <= 4 * 256;
   const CorrVariant kv = corr_variant(mode, mt, small, a.nt[1] * a.nt[2]);
+  const int lds = kv.dma ? lds_bytes_dma(a) : lds_bytes(a);
   if (lds > 64 * 1024)
     if (int rc = kv.large_lds()) return rc;
   // Workgroups per compute unit that add throughput: with fp32 MFMAs two already keep the matrix pipes busy (a

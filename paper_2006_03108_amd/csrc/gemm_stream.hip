@@ -27,6 +27,7 @@
 
 #include "common.h"
 #include "gemm_mfma.h"
+#include "lds_direct.h"
 #include "profile.h"
 
 namespace distdl {
@@ -35,7 +36,6 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef short v4i16 __attribute__((ext_vector_type(4)));
-typedef __attribute__((address_space(3))) char* lds_char;
 typedef __attribute__((address_space(3))) v4i16* lds_v4;
 
 namespace {
@@ -46,37 +46,6 @@ constexpr int kOperandBytes = 64 * 128;    // one operand block of a step
 constexpr int kStepBytes = 2 * kOperandBytes;
 constexpr int kWaveBytes = 2 * kStepBytes;  // two steps per wave: one multiplied, one landing
 constexpr int kStreamLds = 4 * kWaveBytes;  // 128 KB
-
-// Raw buffer descriptor (base, stride 0, bytes covered, data format word): offsets at or beyond `bytes` are out
-// of range.
-__device__ inline u32x4 stream_rsrc(const void* p, uint32_t bytes) {
-  const uint64_t a = (uint64_t)(uintptr_t)p;
-  return u32x4{(uint32_t)a, (uint32_t)(a >> 32), bytes, 0x00020000u};
-}
-
-// One global -> LDS load of 16 bytes per lane: lane L's piece lands at LDS address lds_addr + 16 L.  Written as
-// inline assembly on purpose: the compiler then does not know that a load is filling LDS, so it neither waits for
-// every outstanding load (vmcnt(0)) in front of each LDS read that it cannot tell apart from the landing area, nor
-// counts these loads; the s_waitcnt vmcnt(...) in the kernels below are exact because these are the only vector
-// memory loads in their K loops.
-__device__ inline void load_to_lds(u32x4 desc, uint32_t lds_addr, uint32_t voff, uint32_t soff) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
-               :
-               : "s"(lds_addr), "v"(voff), "s"(desc), "s"(soff)
-               : "memory");
-}
-__device__ inline uint32_t lds_address(const char* p) { return (uint32_t)(size_t)(lds_char)p; }
-
-// s_waitcnt immediates (vmcnt in bits 3:0 and 15:14, expcnt 6:4, lgkmcnt 11:8; a field of all ones does not wait)
-constexpr int kWaitVm0 = 0x0F70;         // vmcnt(0)
-constexpr int kWaitVm16 = 0x4F70;        // vmcnt(16)
-constexpr int kWaitLgkm0 = 0xC07F;       // lgkmcnt(0)
-
-// Workgroup barrier without the fences of __syncthreads(): those make the compiler wait for every outstanding
-// global -> LDS load (vmcnt(0)), including the step being prefetched.  The waits this kernel needs (the loads of the
-// step about to be read, the LDS reads of the buffer about to be refilled) are written out before each call; the
-// memory clobber keeps the compiler from moving LDS accesses across it.
-__device__ inline void lds_barrier() { asm volatile("s_barrier" ::: "memory"); }
 
 union Frag {
   u32x4 u;
@@ -116,7 +85,7 @@ __global__ __launch_bounds__(256, 1) void gemm_stream_kernel(const GemmBlock* __
   // load cursor: segment, step within it (may run past the end: such steps are issued out of range and never read)
   int ls = 0, lin = wave, l_nst = 0, l_K = 0;
   uint32_t l_ldb = 0;
-  u32x4 ra = stream_rsrc(nullptr, 0), rb = stream_rsrc(nullptr, 0);
+  u32x4 ra = lds_direct_rsrc(nullptr, 0), rb = lds_direct_rsrc(nullptr, 0);
   uint32_t goff[16];
   // piece of lane and instruction i: row (or k line) 8 i + lane / 8, position lane % 8
   auto enter_segment = [&]() __attribute__((always_inline)) {
@@ -125,8 +94,8 @@ __global__ __launch_bounds__(256, 1) void gemm_stream_kernel(const GemmBlock* __
     l_nst = (sg.K + kStepK - 1) / kStepK;
     l_ldb = (uint32_t)sg.ldb;
     // the resources end with the operand: rows beyond M / N and k lines beyond K read as zero
-    ra = stream_rsrc(sg.a, (uint32_t)gb.M * sg.lda * 2);
-    rb = stream_rsrc(sg.b, (uint32_t)(B_KC ? gb.N : sg.K) * sg.ldb * 2);
+    ra = lds_direct_rsrc(sg.a, (uint32_t)gb.M * sg.lda * 2);
+    rb = lds_direct_rsrc(sg.b, (uint32_t)(B_KC ? gb.N : sg.K) * sg.ldb * 2);
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const int r = 8 * i + (lane >> 3);
@@ -226,14 +195,14 @@ __global__ __launch_bounds__(256, 1) void gemm_stream_kernel(const GemmBlock* __
     // One step: its 16 loads have landed when at most the 16 of the next step are outstanding.  The buffer is
     // handed to the loads of the step after next as soon as every fragment of it is in registers.
     auto step = [&](int st, int buf) __attribute__((always_inline)) {
-      __builtin_amdgcn_s_waitcnt(kWaitVm16);
+      __builtin_amdgcn_s_waitcnt(kWaitVmcnt16);
       __builtin_amdgcn_sched_barrier(0);
       read_half(buf, 0, xa, xb);
       read_half(buf, 2, ya, yb);
       __builtin_amdgcn_sched_barrier(0);
       mm_half(xa, xb);
       __builtin_amdgcn_sched_barrier(0);
-      __builtin_amdgcn_s_waitcnt(kWaitLgkm0);
+      __builtin_amdgcn_s_waitcnt(kWaitLgkmcnt0);
       issue(buf, st + 2 < n);
       __builtin_amdgcn_sched_barrier(0);
       mm_half(ya, yb);
@@ -245,7 +214,7 @@ __global__ __launch_bounds__(256, 1) void gemm_stream_kernel(const GemmBlock* __
       step(st + 1, 1);
     }
     if (st < n) step(st, 0);
-    __builtin_amdgcn_s_waitcnt(kWaitVm0);  // nothing may still land in LDS when the epilogue reuses it
+    __builtin_amdgcn_s_waitcnt(kWaitVmcnt0);  // nothing may still land in LDS when the epilogue reuses it
   }
 
   // Sum of the four waves' partial tiles in wave order, bias, rounding, store.  The products were accumulated
@@ -321,7 +290,6 @@ constexpr int kTtStepK = 32;
 constexpr int kTtOperand = kTtStepK * 256;  // one operand block of a step
 constexpr int kTtStep = 2 * kTtOperand;     // 16 KB
 constexpr int kTtLds = 2 * kTtStep;         // 32 KB
-constexpr int kWaitVm4 = 0x0F74;            // vmcnt(4)
 }  // namespace
 
 // The first cs_wgs workgroups of the grid's z = 0 slice do not multiply: they are the layer's bias gradient
@@ -400,8 +368,8 @@ __global__ __launch_bounds__(256, 4) void gemm_stream_tt_kernel(const GemmBlock*
   const GemmSeg& sg = gb.seg[0];  // one segment (checked on the host)
   const int K = sg.K, nsteps = (K + kTtStepK - 1) / kTtStepK;
   // resources end with the operand: k lines beyond K read as zero
-  const u32x4 ra = stream_rsrc(sg.a, (uint32_t)K * sg.lda * 2);
-  const u32x4 rb = stream_rsrc(sg.b, (uint32_t)K * sg.ldb * 2);
+  const u32x4 ra = lds_direct_rsrc(sg.a, (uint32_t)K * sg.lda * 2);
+  const u32x4 rb = lds_direct_rsrc(sg.b, (uint32_t)K * sg.ldb * 2);
   const uint32_t my_lds = lds_address(smem) + wave * 2048;
   // load j of this wave: k lines 8 wave + 4 j + lane / 16, position lane % 16 of the line
   uint32_t goff[4];
@@ -436,8 +404,8 @@ __global__ __launch_bounds__(256, 4) void gemm_stream_tt_kernel(const GemmBlock*
   for (int st = 0; st < nsteps; ++st) {
     const char* sbuf = smem + (st & 1) * kTtStep;
     // this wave's quarter of step st has landed (the four loads of step st + 1 may be in flight)
-    if (st + 1 < nsteps) __builtin_amdgcn_s_waitcnt(kWaitVm4);
-    else __builtin_amdgcn_s_waitcnt(kWaitVm0);
+    if (st + 1 < nsteps) __builtin_amdgcn_s_waitcnt(kWaitVmcnt4);
+    else __builtin_amdgcn_s_waitcnt(kWaitVmcnt0);
     lds_barrier();  // and so has everyone's
     Frag fa[2][2], fb[2][2];
 #pragma unroll
@@ -451,7 +419,7 @@ __global__ __launch_bounds__(256, 4) void gemm_stream_tt_kernel(const GemmBlock*
         fb[g][t].t[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(sbuf + rdb[t] + o + 4 * 256));
       }
     __builtin_amdgcn_sched_barrier(0);
-    __builtin_amdgcn_s_waitcnt(kWaitLgkm0);
+    __builtin_amdgcn_s_waitcnt(kWaitLgkmcnt0);
     lds_barrier();  // every wave has this step in registers: its buffer may be refilled
     if (st + 2 < nsteps) issue(st + 2);
     __builtin_amdgcn_sched_barrier(0);
