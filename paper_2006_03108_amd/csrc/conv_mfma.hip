@@ -218,7 +218,12 @@ __global__ __launch_bounds__(256, 2) void corr_mfma_kernel(const WorkerDev* __re
   // A stage is one (output plane q0, tap plane t0, 8-channel chunk cc); stages whose input plane lies
   // outside the input contribute zero and are skipped.
   // (the table entry is the same for all lanes: saying so keeps the stage base offsets in scalar registers)
-  auto plane_of = [&](int q0, int t0) { return g.in_base[0] + q0 * a.is[0] + __builtin_amdgcn_readfirstlane(tapinfo[t0]); };
+  // The plane offset of tap t0 is an arithmetic progression in t0 (forward: t0 * dilation; a parity class keeps every
+  // (s / gcd(dilation, s))-th tap of the kernel, whose offsets fall by dilation / gcd(dilation, s) each), so it is
+  // computed from the first two entries of the kernel arguments.  Read from the device table instead, each look-up
+  // was a vector load and a full wait (s_waitcnt vmcnt(0)) on the path of every stage.
+  const int toff0 = a.tapoff[0][0], tstep = a.nt[0] > 1 ? a.tapoff[0][1] - a.tapoff[0][0] : 0;
+  auto plane_of = [&](int q0, int t0) { return g.in_base[0] + q0 * a.is[0] + toff0 + t0 * tstep; };
   // a stage position: plane p = (n, q0), tap plane t0, chunk cc
   struct StagePos {
     int p, n, q0, t0, cc;

@@ -21,7 +21,13 @@ __device__ inline lds_u32x4 lds_direct_rsrc(const void* p, uint32_t bytes) {
 // that a load is filling LDS, so it neither waits for every outstanding load (vmcnt(0)) in front of each LDS read
 // that it cannot tell apart from the landing area, nor counts these loads; kernels that use it wait with explicit
 // s_waitcnt vmcnt(...) counts, which are exact as long as these are the only vector memory loads in flight.
+// The LDS address, the descriptor and soff must be wave-uniform; they are passed through readfirstlane so that they
+// sit in scalar registers also where the compiler computed a uniform value with vector instructions.
 __device__ inline void load_to_lds(lds_u32x4 desc, uint32_t lds_addr, uint32_t voff, uint32_t soff) {
+  lds_addr = __builtin_amdgcn_readfirstlane(lds_addr);
+  soff = __builtin_amdgcn_readfirstlane(soff);
+  desc = lds_u32x4{(uint32_t)__builtin_amdgcn_readfirstlane(desc[0]), (uint32_t)__builtin_amdgcn_readfirstlane(desc[1]),
+                   (uint32_t)__builtin_amdgcn_readfirstlane(desc[2]), (uint32_t)__builtin_amdgcn_readfirstlane(desc[3])};
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
                :
                : "s"(lds_addr), "v"(voff), "s"(desc), "s"(soff)
