@@ -271,6 +271,8 @@ AFFINE_CASES = [
     (128, 3000, 1024, 1, 3),       # K splits that straddle the column workers' segments, ragged last K stage
     (200, 2064, 3096, 1, 2),       # small batch, wide layer: ragged tiles in M, N and K
     (100, 1048, 528, 2, 1),        # small batch: ragged M, N and K tails in the forward and the data-gradient product, two row workers
+    (37, 264, 72, 1, 1),           # one tile, output rows of 72 (no whole 16-column groups at the edge), K tail of 8
+    (48, 192, 264, 3, 1),          # data gradient summed over three row workers whose K (88) ends inside a 64-k step
 ]
 
 
