@@ -21,6 +21,7 @@
 // D[i = 8*(v/4) + 4*(l/32) + v%4][j = l%32].
 #include <algorithm>
 #include <mutex>
+#include <type_traits>
 
 #include "common.h"
 #include "conv_mfma.h"
@@ -68,6 +69,15 @@ __device__ inline uint16_t to_bf16(float v) {
   return (uint16_t)(u >> 16);
 }
 
+// the same rounding by the hardware conversion (one instruction; the epilogues of the bf16 kernels are short of
+// vector-ALU slots: those do not overlap with the matrix instructions of a SIMD)
+__device__ inline uint16_t bf16_bits(float v) {
+  const __bf16 b = (__bf16)v;
+  uint16_t u;
+  __builtin_memcpy(&u, &b, 2);
+  return u;
+}
+
 template <bool BF16>
 __device__ inline float load_scalar(const void* p, size_t i) {
   if constexpr (BF16) return __uint_as_float((uint32_t)((const uint16_t*)p)[i] << 16);
@@ -101,10 +111,13 @@ __global__ __launch_bounds__(256, 2) void corr_mfma_kernel(const WorkerDev* __re
   constexpr int CK = BFM ? 16 : 8;         // channels per chunk (two 16-byte pieces per cell in LDS)
   static_assert(!DMA || (NT > 0 && MODE != 1), "the direct-to-LDS variant needs compile-time taps and 16-byte pieces");
   // LDS: patch (a_vec4 16-byte units), weights (nb_vec4), one spare unit that absorbs the pieces nobody
-  // needs, then the tap table.  DMA: two buffers of (a_pad + nb_vec4) units, then the spare unit and the table.
+  // needs, then the tap table.  DMA: two buffers of (a_pad + nb_vec4) units, the second one at the compile-time
+  // offset kBufPitch (the most a buffer of this variant can hold), so that the operand reads of either buffer are
+  // the same address registers with a different immediate offset; then the spare unit and the table.
+  constexpr uint32_t kBufPitch = (uint32_t)(PA + PB) * 4096u;
   const int nb_vec4 = a.nt[1] * a.nt[2] * 64;
   const int a_units = DMA ? a.a_pad : a.a_vec4;  // where the weights of a buffer start
-  const int dummy = DMA ? 2 * (a.a_pad + nb_vec4) : a.a_vec4 + nb_vec4;
+  const int dummy = DMA ? (int)(kBufPitch / 16) + a.a_pad + nb_vec4 : a.a_vec4 + nb_vec4;
   uint32_t* tap_tab = (uint32_t*)(lds + dummy + 1);  // byte offset into the patch per (t1, t2), read as a broadcast
 
   // XCD-aware order: consecutive tiles (which share input rows) stay on one XCD, i.e. behind one L2
@@ -304,15 +317,15 @@ __global__ __launch_bounds__(256, 2) void corr_mfma_kernel(const WorkerDev* __re
       for (int mt = 0; mt < MT; ++mt) aaddr[mt][t] = abase[mt] + tapo;
     }
   }
-  // DMA: after every stage the operand addresses move to the other staging buffer (+ bufb, then - bufb, ...)
-  uint32_t bread_cur = bread;
+
   // tapo: byte offset of the tap inside the patch (NT == 0: read from the LDS table two taps ahead of
   // its use, so that the table read is never waited for)
-  auto read_ops = [&](int tap, uint32_t tapo, float4& b, float4 (&av)[MT]) {
+  // bo: byte offset of the staging buffer (DMA: 0 or kBufPitch, a compile-time constant at every call)
+  auto read_ops = [&](int tap, uint32_t tapo, float4& b, float4 (&av)[MT], uint32_t bo) {
     if constexpr (NT > 0) {
-      b = *(const float4*)(ldsb + bread_cur + tap * 1024);
+      b = *(const float4*)(ldsb + bread + tap * 1024 + bo);
 #pragma unroll
-      for (int mt = 0; mt < MT; ++mt) av[mt] = *(const float4*)(ldsb + aaddr[mt][tap]);
+      for (int mt = 0; mt < MT; ++mt) av[mt] = *(const float4*)(ldsb + aaddr[mt][tap] + bo);
     } else {
       b = *(const float4*)(ldsb + bread + tap * 1024);
 #pragma unroll
@@ -348,17 +361,18 @@ __global__ __launch_bounds__(256, 2) void corr_mfma_kernel(const WorkerDev* __re
 
   // The operands of tap t + 1 are read while tap t multiplies; the scheduling barriers keep the
   // compiler from sinking the LDS reads down to their first use, which would expose their latency.
-  auto compute = [&](floatx16 (&acc)[MT]) {
+  auto compute = [&](floatx16 (&acc)[MT], auto buf_c) {
+    constexpr uint32_t bo = decltype(buf_c)::value ? kBufPitch : 0u;
     float4 b0, b1, a0[MT], a1[MT];
     if constexpr (NT > 0) {
-      read_ops(0, 0, b0, a0);
+      read_ops(0, 0, b0, a0, bo);
 #pragma unroll
       for (int tap = 0; tap + 1 < NT; tap += 2) {
-        read_ops(tap + 1, 0, b1, a1);
+        read_ops(tap + 1, 0, b1, a1, bo);
         __builtin_amdgcn_sched_barrier(0);
         multiply(acc, b0, a0);
         __builtin_amdgcn_sched_barrier(0);
-        if (tap + 2 < NT) read_ops(tap + 2, 0, b0, a0);
+        if (tap + 2 < NT) read_ops(tap + 2, 0, b0, a0, bo);
         __builtin_amdgcn_sched_barrier(0);
         multiply(acc, b1, a1);
         __builtin_amdgcn_sched_barrier(0);
@@ -367,15 +381,15 @@ __global__ __launch_bounds__(256, 2) void corr_mfma_kernel(const WorkerDev* __re
     } else {
       // tap_tab has two spare entries behind the last tap, so the look-ahead reads stay in the table
       uint32_t o1 = tap_tab[1], o2 = tap_tab[2];
-      read_ops(0, tap_tab[0], b0, a0);
+      read_ops(0, tap_tab[0], b0, a0, 0u);
       int tap = 0;
       for (; tap + 1 < ntaps; tap += 2) {
-        read_ops(tap + 1, o1, b1, a1);
+        read_ops(tap + 1, o1, b1, a1, 0u);
         o1 = tap_tab[tap + 3];
         __builtin_amdgcn_sched_barrier(0);
         multiply(acc, b0, a0);
         __builtin_amdgcn_sched_barrier(0);
-        if (tap + 2 < ntaps) read_ops(tap + 2, o2, b0, a0);
+        if (tap + 2 < ntaps) read_ops(tap + 2, o2, b0, a0, 0u);
         o2 = tap_tab[tap + 4];
         __builtin_amdgcn_sched_barrier(0);
         multiply(acc, b1, a1);
@@ -388,7 +402,7 @@ __global__ __launch_bounds__(256, 2) void corr_mfma_kernel(const WorkerDev* __re
   floatx16 acc[MT];
   StagePos sp{p_begin, p_begin / nq0, p_begin % nq0, -1, ncc - 1};  // the stage whose loads are in flight
   advance(sp);
-  uint32_t buf_cur = 0, buf_nxt = (uint32_t)a.bufb;  // DMA: where the stage in flight lands, and the other buffer
+  uint32_t buf_cur = 0, buf_nxt = kBufPitch;  // DMA: where the stage in flight lands, and the other buffer
   if (sp.p < p_end) {
     if constexpr (DMA) issue_stage(sp, buf_cur);
     else load_stage(sp);
@@ -406,20 +420,15 @@ __global__ __launch_bounds__(256, 2) void corr_mfma_kernel(const WorkerDev* __re
         lds_barrier();
         advance(sp);
         if (sp.p < p_end) issue_stage(sp, buf_nxt);  // lands while this stage multiplies
-        compute(acc);
-        const uint32_t delta = buf_nxt - buf_cur;  // wraps for the way back: addresses are 32-bit
-#pragma unroll
-        for (int t = 0; t < NT; ++t)
-#pragma unroll
-          for (int mt = 0; mt < MT; ++mt) aaddr[mt][t] += delta;
-        bread_cur += delta;
+        if (buf_cur == 0) compute(acc, std::false_type{});  // (uniform: two copies of the loop, one per buffer)
+        else compute(acc, std::true_type{});
         { const uint32_t x = buf_cur; buf_cur = buf_nxt; buf_nxt = x; }
       } else {
         write_stage();
         __syncthreads();
         advance(sp);
         if (sp.p < p_end) load_stage(sp);  // in flight while this stage multiplies
-        compute(acc);
+        compute(acc, std::false_type{});
         __syncthreads();  // everyone is done reading this stage
       }
     }
@@ -430,7 +439,7 @@ __global__ __launch_bounds__(256, 2) void corr_mfma_kernel(const WorkerDev* __re
 #pragma unroll
       for (int v = 0; v < 16; ++v)
         if constexpr (BF16)
-          __builtin_amdgcn_raw_buffer_store_b16(to_bf16(acc[mt][v] + bias), rout, soff[mt][v], obase, 0);
+          __builtin_amdgcn_raw_buffer_store_b16(bf16_bits(acc[mt][v] + bias), rout, soff[mt][v], obase, 0);
         else
           __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(acc[mt][v] + bias), rout, soff[mt][v], obase, 0);
   }
@@ -1010,7 +1019,7 @@ __global__ __launch_bounds__(256) void bias_partial_kernel(const WorkerDev* __re
 
 static int lds_bytes(const CorrArgs& a) { return (a.a_vec4 + a.nt[1] * a.nt[2] * 64 + 1) * 16 + (a.nt[1] * a.nt[2] + 4) * 4; }
 // the variant that loads straight into LDS: two staging buffers
-static int lds_bytes_dma(const CorrArgs& a) { return 2 * a.bufb + 16 + (a.nt[1] * a.nt[2] + 4) * 4; }
+static int lds_bytes_dma(const CorrArgs& a) { return (4 + 3) * 4096 + a.bufb + 16 + (a.nt[1] * a.nt[2] + 4) * 4; }  // PA = 4, PB = 3
 
 // Window of tr x tc output positions (tr * tc <= 128 * mt) and everything derived from it.
 static void finish_args(CorrArgs& a, int mt, int tc) {
