@@ -393,6 +393,85 @@ def test_affine_step_replayed_from_a_graph_matches_eager(n_b, n_fi, n_fo, P_fo, 
             assert torch.equal(got, ref)
 
 
+def _round_bf16(x):
+    """fp64 -> the nearest bf16-representable value, ties to even (8 significant bits), and the spacing there."""
+    m, e = np.frexp(np.asarray(x, dtype=np.float64))
+    return np.ldexp(np.round(m * 256.0) / 256.0, e), np.ldexp(1.0, e - 8)
+
+
+def _assert_rounded_sum(got, want64, what):
+    """A bf16 result is the fp32-accumulated sum rounded once to nearest-even: it equals the oracle's fp64 value
+    rounded the same way, except where the fp32 accumulation error (about 1e-6 of the output scale) carries the sum
+    across a rounding boundary, and then it is the neighbouring bf16 value.  Truncation, or rounding the partial
+    sums, would move a large share of the elements by one step (the planted-mistake check below shows it)."""
+    ref, step = _round_bf16(want64)
+    diff = np.abs(got.astype(np.float64) - ref)
+    scale = float(np.sqrt(np.mean(np.asarray(want64, dtype=np.float64) ** 2)))
+    assert np.all(diff <= step * 1.0001 + 2e-6 * scale), f"{what}: {np.sum(diff > step * 1.0001 + 2e-6 * scale)} elements off by more than one bf16 step"
+    exact = float(np.mean(diff == 0))
+    assert exact >= 0.99, f"{what}: only {exact:.4f} of the elements are the correctly rounded value"
+
+
+def test_bf16_rounding_pin_detects_truncation():
+    """The pin itself: truncating instead of rounding to nearest fails it."""
+    rng = np.random.default_rng(5)
+    v = rng.standard_normal(20000)
+    ok = syn.to_bf16_values(v.astype(np.float32))
+    _assert_rounded_sum(ok, v.astype(np.float32).astype(np.float64), "rounded")
+    trunc = (v.astype(np.float32).view(np.uint32) & np.uint32(0xffff0000)).view(np.float32)
+    with pytest.raises(AssertionError):
+        _assert_rounded_sum(trunc, v.astype(np.float32).astype(np.float64), "truncated")
+
+
+def test_bf16_outputs_are_the_rounded_fp32_sums():
+    """bf16 layers (bf16 MFMAs, fp32 accumulation): every output tensor of the affine layer (streaming kernels) and
+    of a strided 32-channel convolution (forward, data gradient through H*, weight and bias gradient) against the
+    oracle's fp64 result rounded to bf16 with ties to even."""
+    require_gpu()
+    dtype = torch.bfloat16
+    host = lambda t: t.float().cpu().numpy()
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dtype).cuda()
+    # affine
+    n_b, n_fi, n_fo = 64, 256, 192
+    rng = np.random.default_rng(21)
+    x = syn.to_bf16_values(rng.standard_normal((n_b, n_fi)).astype(np.float32))
+    W = syn.to_bf16_values((rng.standard_normal((n_fo, n_fi)) / np.sqrt(n_fi)).astype(np.float32))
+    b = syn.to_bf16_values(rng.standard_normal(n_fo).astype(np.float32))
+    dy = syn.to_bf16_values(rng.standard_normal((n_b, n_fo)).astype(np.float32))
+    g_y, g_dx, g_dW, g_db = (torch.zeros(sh, dtype=dtype, device="cuda") for sh in ((n_b, n_fo), (n_b, n_fi), (n_fo, n_fi), (n_fo,)))
+    plan = dd.distdl_affine_plan_create(n_b, n_fi, n_fo, 1, 1, dtype)
+    dd.distdl_affine_fwd(plan, [dev(x)], [dev(W)], [dev(b)], [g_y])
+    dd.distdl_affine_bwd(plan, [dev(x)], [dev(W)], [dev(dy)], [g_dx], [g_dW], [g_db])
+    torch.cuda.synchronize()
+    dx_w, dW_w, db_w = layers.affine_backward(x, W, dy)
+    for got, want, what in ((g_y, layers.affine_forward(x, W, b), "affine y"), (g_dx, dx_w, "affine dx"),
+                            (g_dW, dW_w, "affine dW"), (g_db, db_w, "affine db")):
+        _assert_rounded_sum(host(got), want, what)
+    # convolution: one worker, so that no halo sum adds a second rounding to dx
+    cfg, part, case = _conv_case("cfg5u", in_shape=(21, 23, 22), P=(1, 1, 1), c_in=32, c_out=32)
+    xc, wc, bc, dyc = (syn.to_bf16_values(case[k]) for k in ("x", "w", "bias", "dy"))
+    plan = dd.distdl_plan_create(cfg["D"], cfg["n_b"], cfg["c_in"], cfg["c_out"], cfg["in_shape"], cfg["P"],
+                                 cfg["ksize"], cfg["stride"], cfg["padding"], cfg["dilation"], dtype)
+    x_bufs = [to_cl(t, dtype) for t in prim.scatter_bulk(xc, part, fill=np.float32(3.0))]
+    g_w, g_bias = w_to_dev(wc).to(dtype), w_to_dev(bc).to(dtype)
+    y = [torch.zeros((cfg["n_b"],) + part.out_shape(0) + (cfg["c_out"],), device="cuda", dtype=dtype)]
+    dd.distdl_conv_fwd(plan, x_bufs, g_w, g_bias, y)
+    g_dy = [to_cl(t, dtype) for t in prim.scatter_out(dyc, part)]
+    dx = [torch.zeros_like(t) for t in x_bufs]
+    dw, db = torch.zeros_like(g_w), torch.zeros_like(g_bias)
+    ws = torch.empty(max(dd.distdl_conv_bwd_workspace(plan), 16), dtype=torch.uint8, device="cuda")
+    dd.distdl_conv_bwd(plan, x_bufs, g_w, g_dy, dx, dw, db, ws)
+    torch.cuda.synchronize()
+    bufs = prim.scatter_bulk(xc.astype(np.float64), part)
+    y_want = layers.dist_conv_forward(bufs, wc, bc, part, cfg["stride"], cfg["dilation"])  # leaves H x in bufs
+    dx_want, dw_want, db_want = layers.dist_conv_adjoint(bufs, wc, prim.scatter_out(dyc.astype(np.float64), part), part,
+                                                         cfg["stride"], cfg["dilation"], True)
+    _assert_rounded_sum(from_cl(y[0]), y_want[0], "conv y")
+    _assert_rounded_sum(from_cl(dx[0]), dx_want[0], "conv dx")
+    _assert_rounded_sum(host(dw), dw_want, "conv dw")
+    _assert_rounded_sum(host(db), db_want, "conv db")
+
+
 # ---------------------------------------------------------------- full-size volumetric configuration
 def _sample_indices(rng, shape, count):
     return [tuple(int(rng.integers(0, s)) for s in shape) for _ in range(count)]
