@@ -21,6 +21,9 @@ __device__ inline lds_u32x4 lds_direct_rsrc(const void* p, uint32_t bytes) {
 // that a load is filling LDS, so it neither waits for every outstanding load (vmcnt(0)) in front of each LDS read
 // that it cannot tell apart from the landing area, nor counts these loads; kernels that use it wait with explicit
 // s_waitcnt vmcnt(...) counts, which are exact as long as these are the only vector memory loads in flight.
+// M0 is written inside the statement and cannot be named as clobbered (the compiler reserves it and refuses it in a
+// clobber list); that is sound because the compiler never keeps a value in M0 across other instructions: it loads M0
+// immediately before each instruction of its own that reads it.
 // The LDS address, the descriptor and soff must be wave-uniform; they are passed through readfirstlane so that they
 // sit in scalar registers also where the compiler computed a uniform value with vector instructions.
 __device__ inline void load_to_lds(lds_u32x4 desc, uint32_t lds_addr, uint32_t voff, uint32_t soff) {
