@@ -262,7 +262,7 @@ int distdl_affine_fwd(distdl_affine_plan* p, const void* const x_dev[], const vo
                            (int32_t)p->fi_size[j], 0};
     }
     if (gemm_mfma_usable(blocks, bf16, true, true)) {
-      const int ns = gemm_mfma_splits(blocks, bf16);
+      const int ns = gemm_mfma_splits(blocks, bf16, true);
       if ((rc = p->g_fwd.upload(blocks, st_)) || (rc = ensure_partial(p, gemm_mfma_partial_floats(blocks, ns)))) return rc;
       if ((rc = launch_gemm_mfma(p->g_fwd.dev, blocks, bf16, true, true, ns, p->d_partial, "affine_fwd_mfma", st_))) return rc;
       DISTDL_HIP_TRY(hipGetLastError());
@@ -320,7 +320,7 @@ int distdl_affine_bwd(distdl_affine_plan* p, const void* const x_dev[], const vo
       bb[i] = ColsumBlock{dy_dev[i], db_dev ? db_dev[i] : nullptr, (int32_t)p->n_b, (int32_t)p->fo_size[i]};
     }
     if (gemm_mfma_usable(bx, bf16, true, false) && gemm_mfma_usable(bw, bf16, false, false)) {
-      const int nsx = gemm_mfma_splits(bx, bf16), nsw = gemm_mfma_splits(bw, bf16);
+      const int nsx = gemm_mfma_splits(bx, bf16, true), nsw = gemm_mfma_splits(bw, bf16, false);
       if ((rc = p->g_dx.upload(bx, st_)) || (rc = p->g_dw.upload(bw, st_)) ||
           (rc = ensure_partial(p, std::max(gemm_mfma_partial_floats(bx, nsx), gemm_mfma_partial_floats(bw, nsw)))))
         return rc;

@@ -33,7 +33,7 @@ bool gemm_mfma_usable(const std::vector<GemmBlock>& blocks, bool bf16, bool a_kc
 // a_kc: A[m][k] is contiguous along k (else along m); b_kc: B[k][n] is contiguous along k (else along n).
 // nsplit > 1: K split over nsplit workgroups per tile through the fp32 buffer `partial`
 // (gemm_mfma_partial_floats(blocks, nsplit) floats), summed by a second kernel.
-int gemm_mfma_splits(const std::vector<GemmBlock>& blocks, bool bf16);
+int gemm_mfma_splits(const std::vector<GemmBlock>& blocks, bool bf16, bool a_kc);
 size_t gemm_mfma_partial_floats(const std::vector<GemmBlock>& blocks, int nsplit);
 // colsum (optional): column sums to fold into the launch when its kernel can carry them; *colsum->done says whether
 // it did (otherwise the caller launches launch_colsum itself).
@@ -44,11 +44,13 @@ struct GemmColsum {
 };
 int launch_gemm_mfma(const GemmBlock* d_blocks, const std::vector<GemmBlock>& blocks, bool bf16, bool a_kc, bool b_kc,
                      int nsplit, float* partial, const char* name, hipStream_t st, GemmColsum* colsum = nullptr);
-// The small-batch bf16 path (gemm_stream.hip): 64 x 64 tiles over the whole K range, every wave its own K-slice
-// pipeline fed by global -> LDS loads.  Usable when A is contiguous along K and every K (and, for an N-contiguous B,
-// N) is a multiple of 8; with both operands as k lines (weight gradient): one segment, M and N multiples of 8.
-bool gemm_stream_usable(const std::vector<GemmBlock>& blocks, bool a_kc, bool b_kc);
-int launch_gemm_stream(const GemmBlock* d_blocks, const std::vector<GemmBlock>& blocks, bool b_kc, hipStream_t st);
+// The small-batch path (gemm_stream.hip): 64 x 64 tiles over the whole K range, every wave its own K-slice pipeline
+// fed by global -> LDS loads, bf16 or fp32.  Usable when A is contiguous along K and every K (and, for an N-contiguous
+// B, N) is a multiple of a 16-byte piece (8 bf16, 4 fp32); with both operands as k lines (weight gradient, bf16 only):
+// one segment, M and N multiples of 8.
+bool gemm_stream_usable(const std::vector<GemmBlock>& blocks, bool bf16, bool a_kc, bool b_kc);
+int launch_gemm_stream(const GemmBlock* d_blocks, const std::vector<GemmBlock>& blocks, bool bf16, bool b_kc,
+                       hipStream_t st);
 // the weight-gradient layout (both operands as k lines), 128 x 128 tiles
 // d_colsum (or null): column sums (the bias gradient) computed by extra workgroups of the same launch
 int launch_gemm_stream_tt(const GemmBlock* d_blocks, const std::vector<GemmBlock>& blocks, const ColsumBlock* d_colsum,

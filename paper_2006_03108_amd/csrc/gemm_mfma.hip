@@ -512,22 +512,23 @@ static int64_t count_tiles(const std::vector<GemmBlock>& blocks, int t) {
 }
 
 // Workgroup tile: 128 x 128 (2 x 2 MFMA tiles per wave) when every block is at least that large.  Exception: a
-// bf16 launch whose 128-tiles would fill at most half the chip but whose 64-tiles fill most of it (the small-batch
-// forward and data-gradient products) takes 64 x 64 tiles over the whole K range: measured at batch 256 with
-// 4096 x 4096 features, one such launch takes 27 us against 34 us for 128-tiles with K splits and a reduction.
-static int gemm_tile(const std::vector<GemmBlock>& blocks, bool bf16) {
+// launch whose 128-tiles would fill at most half the chip but whose 64-tiles fill most of it (the small-batch
+// forward and data-gradient products) takes 64 x 64 tiles over the whole K range on the streaming kernel (bf16 in
+// any layout it was measured in, fp32 where that kernel exists: A contiguous along K): no partial tiles, no
+// second kernel.
+static int gemm_tile(const std::vector<GemmBlock>& blocks, bool bf16, bool a_kc) {
   for (const GemmBlock& b : blocks)
     if (b.M < 128 || b.N < 128) return 64;
   if (blocks.empty()) return 64;
-  if (bf16 && count_tiles(blocks, 128) <= 128 && count_tiles(blocks, 64) >= 192) return 64;
+  if ((bf16 || a_kc) && count_tiles(blocks, 128) <= 128 && count_tiles(blocks, 64) >= 192) return 64;
   return 128;
 }
 
 // Number of K splits for a launch: enough workgroups for about two (large tiles) or four per compute unit,
 // every split at least four stages long, at most 8.
-int gemm_mfma_splits(const std::vector<GemmBlock>& blocks, bool bf16) {
+int gemm_mfma_splits(const std::vector<GemmBlock>& blocks, bool bf16, bool a_kc) {
   const int bk = bf16 ? 64 : 32;
-  const int t = gemm_tile(blocks, bf16);
+  const int t = gemm_tile(blocks, bf16, a_kc);
   const int64_t tiles = count_tiles(blocks, t);
   int64_t macs = 0;
   int min_stages = INT32_MAX;
@@ -540,7 +541,7 @@ int gemm_mfma_splits(const std::vector<GemmBlock>& blocks, bool bf16) {
     min_stages = std::min(min_stages, stages);
     if (b.N % 4) return 1;  // the reduction works on groups of 4 elements of a row
   }
-  if (bf16 && t == 64 && tiles >= 192) return 1;  // bound by LDS traffic, which splits do not reduce
+  if ((bf16 || a_kc) && t == 64 && tiles >= 192) return 1;  // the whole K range per tile: see gemm_tile
   const int64_t target = t == 128 ? 512 : 1024;
   if (tiles == 0 || tiles >= target * 3 / 4) return 1;
   if (macs < (int64_t(1) << 28)) return 1;  // a launch this small is latency-bound either way: no second kernel
@@ -576,7 +577,7 @@ static int launch_gemm_variant(dim3 grid, const GemmBlock* d_blocks, float* part
 
 int launch_gemm_mfma(const GemmBlock* d_blocks, const std::vector<GemmBlock>& blocks, bool bf16, bool a_kc, bool b_kc,
                      int nsplit, float* partial, const char* name, hipStream_t st, GemmColsum* colsum) {
-  const int t = gemm_tile(blocks, bf16);
+  const int t = gemm_tile(blocks, bf16, a_kc);
   int tiles = 0;
   int64_t max_mn = 0;
   for (const GemmBlock& b : blocks) {
@@ -588,10 +589,10 @@ int launch_gemm_mfma(const GemmBlock* d_blocks, const std::vector<GemmBlock>& bl
   if (!a_kc && b_kc) return set_error(DISTDL_ERR_UNSUPPORTED, "gemm: operand layout not built");
   dim3 grid((unsigned)tiles, (unsigned)std::max(nsplit, 1), (unsigned)blocks.size()), block(256);
   ProfScope prof(name, st);
-  // bf16 launches that take 64-tiles over the whole K range (about one tile per compute unit: the small-batch
-  // forward and data-gradient products) are bound by the operand feed and run on the streaming kernel
-  if (bf16 && t == 64 && nsplit <= 1 && a_kc && gemm_stream_usable(blocks, a_kc, b_kc)) return launch_gemm_stream(d_blocks, blocks, b_kc, st);
-  if (bf16 && t == 128 && nsplit <= 1 && !a_kc && !b_kc && gemm_stream_usable(blocks, a_kc, b_kc)) {
+  // launches that take 64-tiles over the whole K range (about one tile per compute unit: the small-batch forward
+  // and data-gradient products) run on the streaming kernel
+  if (t == 64 && nsplit <= 1 && a_kc && gemm_stream_usable(blocks, bf16, a_kc, b_kc)) return launch_gemm_stream(d_blocks, blocks, bf16, b_kc, st);
+  if (bf16 && t == 128 && nsplit <= 1 && !a_kc && !b_kc && gemm_stream_usable(blocks, bf16, a_kc, b_kc)) {
     if (colsum) colsum->done = true;  // M % 8 == 0 for every block: the feature counts fit the fused column sums
     return launch_gemm_stream_tt(d_blocks, blocks, colsum ? colsum->d_blocks : nullptr, colsum ? colsum->n_blocks : 0,
                                  colsum ? colsum->max_f : 0, st);

@@ -41,11 +41,19 @@ typedef __attribute__((address_space(3))) v4i16* lds_v4;
 namespace {
 
 constexpr uint32_t kOobOff = 0x7ffffff0u;  // fails the range check of every buffer (operands are < 2 GiB)
-constexpr int kStepK = 64;                 // k per step
 constexpr int kOperandBytes = 64 * 128;    // one operand block of a step
 constexpr int kStepBytes = 2 * kOperandBytes;
 constexpr int kWaveBytes = 2 * kStepBytes;  // two steps per wave: one multiplied, one landing
 constexpr int kStreamLds = 4 * kWaveBytes;  // 128 KB
+
+// f(integral_constant<int, 0>) ... f(integral_constant<int, 3>)
+template <class F>
+__device__ __forceinline__ void static_for4(F&& f) {
+  f(std::integral_constant<int, 0>{});
+  f(std::integral_constant<int, 1>{});
+  f(std::integral_constant<int, 2>{});
+  f(std::integral_constant<int, 3>{});
+}
 
 union Frag {
   u32x4 u;
@@ -55,9 +63,18 @@ union Frag {
 
 }  // namespace
 
-template <bool B_KC>
+// BF16: bf16 operands and output (v_mfma_f32_32x32x16_bf16, 64 k per step), else fp32 (v_mfma_f32_32x32x2_f32, 32 k
+// per step; a 16-byte fragment read gives a lane four consecutive k, used by four MFMAs whose k pairs are (j, 4 + j),
+// the same pairing on both operands).  Either way a staged row of a K-contiguous operand is 128 bytes (8 pieces),
+// so the staging geometry and its swizzle are the same.  An N-contiguous fp32 B is staged as 32 k lines x 256 bytes
+// (64 columns), line l keeping piece c at position c ^ (8 * ((l >> 2) & 1)), and read one float per lane: the 32
+// lanes of a half-wave read 128 contiguous bytes, and the two half-waves (lines l, l + 4) different bank halves.
+template <bool BF16, bool B_KC>
 __global__ __launch_bounds__(256, 1) void gemm_stream_kernel(const GemmBlock* __restrict__ blocks) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
+  constexpr int ES = BF16 ? 2 : 4;        // element size
+  constexpr int VE = 16 / ES;             // elements per 16-byte piece
+  constexpr int SK = BF16 ? 64 : 32;      // k per step: 128 bytes of a K-contiguous row
   const GemmBlock& gb = blocks[blockIdx.z];
   const int tiles_m = (gb.M + 63) / 64, tiles_n = (gb.N + 63) / 64;
   // consecutive tiles share the B rows (m walks fastest) and stay behind one L2
@@ -77,9 +94,9 @@ __global__ __launch_bounds__(256, 1) void gemm_stream_kernel(const GemmBlock* __
     for (int j = 0; j < 2; ++j)
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-  // The 64-k steps of all segments form one sequence; this wave takes every fourth of them.
+  // The steps of all segments form one sequence; this wave takes every fourth of them.
   int total = 0;
-  for (int s = 0; s < gb.nseg; ++s) total += (gb.seg[s].K + kStepK - 1) / kStepK;
+  for (int s = 0; s < gb.nseg; ++s) total += (gb.seg[s].K + SK - 1) / SK;
   const int n = (total - wave + 3) / 4;
 
   // load cursor: segment, step within it (may run past the end: such steps are issued out of range and never read)
@@ -87,32 +104,43 @@ __global__ __launch_bounds__(256, 1) void gemm_stream_kernel(const GemmBlock* __
   uint32_t l_ldb = 0;
   u32x4 ra = lds_direct_rsrc(nullptr, 0), rb = lds_direct_rsrc(nullptr, 0);
   uint32_t goff[16];
-  // piece of lane and instruction i: row (or k line) 8 i + lane / 8, position lane % 8
+  // K-contiguous operand, load i: row 8 i + lane / 8, position lane % 8.  N-contiguous bf16 B: the same with k
+  // lines for rows; N-contiguous fp32 B: k line 4 i + lane / 16, position lane % 16.
   auto enter_segment = [&]() __attribute__((always_inline)) {
     const GemmSeg& sg = gb.seg[ls];
     l_K = sg.K;
-    l_nst = (sg.K + kStepK - 1) / kStepK;
+    l_nst = (sg.K + SK - 1) / SK;
     l_ldb = (uint32_t)sg.ldb;
     // the resources end with the operand: rows beyond M / N and k lines beyond K read as zero
-    ra = lds_direct_rsrc(sg.a, (uint32_t)gb.M * sg.lda * 2);
-    rb = lds_direct_rsrc(sg.b, (uint32_t)(B_KC ? gb.N : sg.K) * sg.ldb * 2);
+    ra = lds_direct_rsrc(sg.a, (uint32_t)gb.M * sg.lda * ES);
+    rb = lds_direct_rsrc(sg.b, (uint32_t)(B_KC ? gb.N : sg.K) * sg.ldb * ES);
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const int r = 8 * i + (lane >> 3);
       const int ca = (lane & 7) ^ ((r >> 1) & 7);
-      goff[i] = ((uint32_t)(m0 + r) * sg.lda + ca * 8) * 2;
+      goff[i] = ((uint32_t)(m0 + r) * sg.lda + ca * VE) * ES;
       if (B_KC) {
-        goff[8 + i] = ((uint32_t)(n0 + r) * sg.ldb + ca * 8) * 2;
-      } else {
+        goff[8 + i] = ((uint32_t)(n0 + r) * sg.ldb + ca * VE) * ES;
+      } else if (BF16) {
         const int cb = (lane & 7) ^ (4 * ((r >> 1) & 1));
-        goff[8 + i] = ((uint32_t)r * sg.ldb + n0 + cb * 8) * 2;
-        if (n0 + cb * 8 >= gb.N) goff[8 + i] = kOobOff;  // columns beyond N (whole pieces: N % 8 == 0)
+        goff[8 + i] = ((uint32_t)r * sg.ldb + n0 + cb * VE) * ES;
+        if (n0 + cb * VE >= gb.N) goff[8 + i] = kOobOff;  // columns beyond N (whole pieces: N % 8 == 0)
+      } else {
+        const int l = 4 * i + (lane >> 4);
+        const int cb = (lane & 15) ^ (8 * ((l >> 2) & 1));
+        goff[8 + i] = ((uint32_t)l * sg.ldb + n0 + cb * VE) * ES;
+        if (n0 + cb * VE >= gb.N) goff[8 + i] = kOobOff;  // whole pieces: N % 4 == 0
       }
     }
   };
-  // Issues the loads of the cursor's step into staging buffer `buf` and moves the cursor on by four steps.
-  auto issue = [&](int buf, bool valid) __attribute__((always_inline)) {
-    const uint32_t d = my_lds + buf * kStepBytes;
+  // The loads of the cursor's step into staging buffer `buf`: issue_begin moves the cursor on by four steps and
+  // fixes the step's offsets, issue_part(q) issues loads 4 q ... 4 q + 3 of its 16 (A: 0-7, B: 8-15), so that the
+  // fp32 loop can spread them between its MFMAs; issue does it all at once.
+  uint32_t is_d = 0, is_a = 0, is_b = 0;
+  int is_kleft = 0;
+  bool is_valid = false, is_tail = false;
+  auto issue_begin = [&](int buf, bool valid) __attribute__((always_inline)) {
+    is_d = my_lds + buf * kStepBytes;
     int k0 = 0;
     if (valid) {  // wave-uniform
       while (lin >= l_nst) {
@@ -120,34 +148,35 @@ __global__ __launch_bounds__(256, 1) void gemm_stream_kernel(const GemmBlock* __
         ++ls;
         enter_segment();
       }
-      k0 = lin * kStepK;
+      k0 = lin * SK;
       lin += 4;
     }
-    const uint32_t a_base = (uint32_t)k0 * 2, b_base = (uint32_t)k0 * (B_KC ? 1u : l_ldb) * 2;
-    if (!valid || k0 + kStepK <= l_K) {
+    is_a = (uint32_t)k0 * ES;
+    is_b = (uint32_t)k0 * (B_KC ? 1u : l_ldb) * ES;
+    is_valid = valid;
+    // K tail: pieces of a K-contiguous row beyond K are switched off (whole pieces: K % VE == 0); k lines beyond
+    // K lie beyond the resource
+    is_tail = valid && k0 + SK > l_K;
+    is_kleft = l_K - k0;
+  };
+  auto issue_part = [&](auto q_c) __attribute__((always_inline)) {
+    constexpr int q = decltype(q_c)::value;
 #pragma unroll
-      for (int i = 0; i < 8; ++i) load_to_lds(ra, d + i * 1024, valid ? goff[i] : kOobOff, a_base);
-#pragma unroll
-      for (int i = 0; i < 8; ++i) load_to_lds(rb, d + kOperandBytes + i * 1024, valid ? goff[8 + i] : kOobOff, b_base);
-    } else {
-      // K tail: pieces of a K-contiguous row beyond K are switched off (whole pieces: K % 8 == 0); k lines beyond
-      // K lie beyond the resource
-      const int kleft = l_K - k0;
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        const int r = 8 * i + (lane >> 3);
+    for (int i = 4 * q; i < 4 * q + 4; ++i) {
+      const bool is_a_op = i < 8;
+      uint32_t off = is_valid ? goff[i] : kOobOff;
+      if (is_tail && (is_a_op || B_KC)) {  // (uniform condition; the piece test is per lane)
+        const int r = 8 * (i & 7) + (lane >> 3);
         const int ca = (lane & 7) ^ ((r >> 1) & 7);
-        const bool in = ca * 8 < kleft;
-        load_to_lds(ra, d + i * 1024, in ? goff[i] : kOobOff, a_base);
+        if (ca * VE >= is_kleft) off = kOobOff;
       }
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        const int r = 8 * i + (lane >> 3);
-        const int ca = (lane & 7) ^ ((r >> 1) & 7);
-        const bool in = !B_KC || ca * 8 < kleft;
-        load_to_lds(rb, d + kOperandBytes + i * 1024, in ? goff[8 + i] : kOobOff, b_base);
-      }
+      if (is_a_op) load_to_lds(ra, is_d + i * 1024, off, is_a);
+      else load_to_lds(rb, is_d + kOperandBytes + (i - 8) * 1024, off, is_b);
     }
+  };
+  auto issue = [&](int buf, bool valid) __attribute__((always_inline)) {
+    issue_begin(buf, valid);
+    static_for4([&](auto q) __attribute__((always_inline)) { issue_part(q); });
   };
 
   // fragment addresses inside a staging buffer
@@ -155,13 +184,20 @@ __global__ __launch_bounds__(256, 1) void gemm_stream_kernel(const GemmBlock* __
   uint32_t rdk[4];
 #pragma unroll
   for (int g = 0; g < 4; ++g) rdk[g] = ml * 128 + (((2 * g + h) ^ ((ml >> 1) & 7)) * 16);
-  //   B when N-contiguous: k line 16 g + tk (+ 4), columns 32 t + tr ... + 3 (8 bytes) at piece (4 t + tr / 8) ^ f(line)
+  //   bf16 B when N-contiguous: k line 16 g + tk (+ 4), columns 32 t + tr ... + 3 (8 bytes) at piece (4 t + tr / 8) ^ f(line)
   const int tk = 8 * (lane >> 5) + ((lane & 15) >> 2), tr = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
   uint32_t rdt[2];
 #pragma unroll
   for (int t = 0; t < 2; ++t)
     rdt[t] = kOperandBytes + tk * 128 + ((((4 * t + (tr >> 3)) ^ (4 * ((tk >> 1) & 1)))) * 16) + (tr & 7) * 2;
+  //   fp32 B when N-contiguous: k line 8 g + 4 h + j, column 32 t + ml: one float of piece (8 t + ml / 4) ^ (8 h)
+  uint32_t rdn[2];
+#pragma unroll
+  for (int t = 0; t < 2; ++t)
+    rdn[t] = kOperandBytes + 4 * h * 256 + (((8 * t + (ml >> 2)) ^ (8 * h)) * 16) + (ml & 3) * 4;
 
+  // fragments of k groups g0, g0 + 1 of the step in buffer buf.  fp32: fa / fb hold four k per lane; an N-contiguous
+  // fp32 B is read float by float into the same four slots.
   auto read_half = [&](int buf, int g0, Frag (&fa)[2][2], Frag (&fb)[2][2]) __attribute__((always_inline)) {
     const char* s = my + buf * kStepBytes;
 #pragma unroll
@@ -171,20 +207,64 @@ __global__ __launch_bounds__(256, 1) void gemm_stream_kernel(const GemmBlock* __
         fa[g][t].u = *(const u32x4*)(s + rdk[g0 + g] + t * 4096);
         if constexpr (B_KC) {
           fb[g][t].u = *(const u32x4*)(s + kOperandBytes + rdk[g0 + g] + t * 4096);
-        } else {
+        } else if constexpr (BF16) {
           fb[g][t].t[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(s + rdt[t] + (g0 + g) * 16 * 128));
           fb[g][t].t[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(s + rdt[t] + (g0 + g) * 16 * 128 + 4 * 128));
+        } else {
+#pragma unroll
+          for (int j = 0; j < 4; ++j) fb[g][t].u[j] = *(const uint32_t*)(s + rdn[t] + ((g0 + g) * 8 + j) * 256);
         }
       }
   };
+  // accumulated transposed (B fragment as the first MFMA operand): see the epilogue
   auto mm_half = [&](const Frag (&fa)[2][2], const Frag (&fb)[2][2]) __attribute__((always_inline)) {
 #pragma unroll
-    for (int g = 0; g < 2; ++g)
+    for (int g = 0; g < 2; ++g) {
+      if constexpr (BF16) {
 #pragma unroll
-      for (int i = 0; i < 2; ++i)
+        for (int i = 0; i < 2; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[g][j].v, fa[g][i].v, acc[i][j], 0, 0, 0);
+          for (int j = 0; j < 2; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[g][j].v, fa[g][i].v, acc[i][j], 0, 0, 0);
+      } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+#pragma unroll
+          for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+              acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(fb[g][j].u[e]), __uint_as_float(fa[g][i].u[e]),
+                                                               acc[i][j], 0, 0, 0);
+      }
+    }
+  };
+
+  // reads of one k group g of the step in buffer buf into slot g & 1 of (fa, fb): the A fragments, or the B fragments
+  auto read_a = [&](int buf, int g, Frag (&fa)[2][2]) __attribute__((always_inline)) {
+    const char* s = my + buf * kStepBytes;
+#pragma unroll
+    for (int t = 0; t < 2; ++t) fa[g & 1][t].u = *(const u32x4*)(s + rdk[g] + t * 4096);
+  };
+  auto read_b = [&](int buf, int g, Frag (&fb)[2][2]) __attribute__((always_inline)) {
+    const char* s = my + buf * kStepBytes;
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      if constexpr (B_KC) {
+        fb[g & 1][t].u = *(const u32x4*)(s + kOperandBytes + rdk[g] + t * 4096);
+      } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) fb[g & 1][t].u[j] = *(const uint32_t*)(s + rdn[t] + (g * 8 + j) * 256);
+      }
+    }
+  };
+  // the four fp32 MFMAs of k pair e of fragment slot g
+  auto mm_pair = [&](const Frag (&fa)[2][2], const Frag (&fb)[2][2], int g, int e) __attribute__((always_inline)) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(fb[g][j].u[e]), __uint_as_float(fa[g][i].u[e]),
+                                                         acc[i][j], 0, 0, 0);
   };
 
   if (n > 0) {
@@ -192,28 +272,76 @@ __global__ __launch_bounds__(256, 1) void gemm_stream_kernel(const GemmBlock* __
     issue(0, true);
     issue(1, 1 < n);
     Frag xa[2][2], xb[2][2], ya[2][2], yb[2][2];
-    // One step: its 16 loads have landed when at most the 16 of the next step are outstanding.  The buffer is
-    // handed to the loads of the step after next as soon as every fragment of it is in registers.
-    auto step = [&](int st, int buf) __attribute__((always_inline)) {
-      __builtin_amdgcn_s_waitcnt(kWaitVmcnt16);
-      __builtin_amdgcn_sched_barrier(0);
-      read_half(buf, 0, xa, xb);
-      read_half(buf, 2, ya, yb);
-      __builtin_amdgcn_sched_barrier(0);
-      mm_half(xa, xb);
-      __builtin_amdgcn_sched_barrier(0);
-      __builtin_amdgcn_s_waitcnt(kWaitLgkmcnt0);
-      issue(buf, st + 2 < n);
-      __builtin_amdgcn_sched_barrier(0);
-      mm_half(ya, yb);
-      __builtin_amdgcn_sched_barrier(0);
-    };
-    int st = 0;
-    for (; st + 2 <= n; st += 2) {
-      step(st, 0);
-      step(st + 1, 1);
+    if constexpr (BF16 || B_KC) {
+      // One step: its 16 loads have landed when at most the 16 of the next step are outstanding.  The buffer is
+      // handed to the loads of the step after next as soon as every fragment of it is in registers.
+      auto step = [&](int st, int buf) __attribute__((always_inline)) {
+        __builtin_amdgcn_s_waitcnt(kWaitVmcnt16);
+        __builtin_amdgcn_sched_barrier(0);
+        read_half(buf, 0, xa, xb);
+        read_half(buf, 2, ya, yb);
+        __builtin_amdgcn_sched_barrier(0);
+        mm_half(xa, xb);
+        __builtin_amdgcn_sched_barrier(0);
+        __builtin_amdgcn_s_waitcnt(kWaitLgkmcnt0);
+        issue(buf, st + 2 < n);
+        __builtin_amdgcn_sched_barrier(0);
+        mm_half(ya, yb);
+        __builtin_amdgcn_sched_barrier(0);
+      };
+      int st = 0;
+      for (; st + 2 <= n; st += 2) {
+        step(st, 0);
+        step(st + 1, 1);
+      }
+      if (st < n) step(st, 0);
+    } else {
+      // fp32 with B as k lines, whose fragments are read float by float (measured 80.6 against 83.6 us on the data
+      // gradient of a 1024 x 2048 x 2048 product; the K-contiguous forward product lost 4 us with this schedule and
+      // keeps the plain step above).  A step is 64 MFMAs of 64 clocks and this wave is alone on its SIMD, so
+      // everything else is issued in the shadow of the MFMAs, a few instructions after every four of them (eight
+      // slots per half step):
+      //   first half (k groups 0, 1, fragments read during the step before): the fragment reads of groups 2, 3;
+      //   second half (groups 2, 3): the fragment reads of groups 0, 1 of the next step from the other buffer
+      //   (its loads, issued a step ago, are the only ones outstanding: vmcnt(0)), then the 16 loads of the step
+      //   after next into this buffer, whose fragments are all in registers by then.
+      __builtin_amdgcn_s_waitcnt(kWaitVmcnt16);  // step 0 has landed
+      read_half(0, 0, xa, xb);
+      auto step = [&](int st, int buf) __attribute__((always_inline)) {
+#pragma unroll
+        for (int slot = 0; slot < 8; ++slot) {
+          mm_pair(xa, xb, slot >> 2, slot & 3);
+          __builtin_amdgcn_sched_barrier(0);
+          if (slot == 0) read_a(buf, 2, ya);
+          if (slot == 1) read_b(buf, 2, yb);
+          if (slot == 2) read_a(buf, 3, ya);
+          if (slot == 3) read_b(buf, 3, yb);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+        __builtin_amdgcn_s_waitcnt(kWaitVmcnt0);
+        issue_begin(buf, st + 2 < n);
+#pragma unroll
+        for (int slot = 0; slot < 8; ++slot) {
+          mm_pair(ya, yb, slot >> 2, slot & 3);
+          __builtin_amdgcn_sched_barrier(0);
+          if (slot == 0) read_a(buf ^ 1, 0, xa);
+          if (slot == 1) read_b(buf ^ 1, 0, xb);
+          if (slot == 2) read_a(buf ^ 1, 1, xa);
+          if (slot == 3) read_b(buf ^ 1, 1, xb);
+          if (slot == 4) issue_part(std::integral_constant<int, 0>{});
+          if (slot == 5) issue_part(std::integral_constant<int, 1>{});
+          if (slot == 6) issue_part(std::integral_constant<int, 2>{});
+          if (slot == 7) issue_part(std::integral_constant<int, 3>{});
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      };
+      int st = 0;
+      for (; st + 2 <= n; st += 2) {
+        step(st, 0);
+        step(st + 1, 1);
+      }
+      if (st < n) step(st, 0);
     }
-    if (st < n) step(st, 0);
     __builtin_amdgcn_s_waitcnt(kWaitVmcnt0);  // nothing may still land in LDS when the epilogue reuses it
   }
 
@@ -251,29 +379,51 @@ __global__ __launch_bounds__(256, 1) void gemm_stream_kernel(const GemmBlock* __
   if (grow >= gb.M || gcol >= gb.N) return;
   const bool full = gcol + 16 <= gb.N;
   if (gb.bias) {
-    const uint16_t* bp = (const uint16_t*)gb.bias + gcol;
-    if (full) {
+    if constexpr (BF16) {
+      const uint16_t* bp = (const uint16_t*)gb.bias + gcol;
+      if (full) {
 #pragma unroll
-      for (int q = 0; q < 16; ++q) s[q] += __uint_as_float((uint32_t)bp[q] << 16);
+        for (int q = 0; q < 16; ++q) s[q] += __uint_as_float((uint32_t)bp[q] << 16);
+      } else {
+        for (int q = 0; gcol + q < gb.N; ++q) s[q] += __uint_as_float((uint32_t)bp[q] << 16);
+      }
     } else {
-      for (int q = 0; gcol + q < gb.N; ++q) s[q] += __uint_as_float((uint32_t)bp[q] << 16);
+      const float* bp = (const float*)gb.bias + gcol;
+      if (full) {
+#pragma unroll
+        for (int q = 0; q < 16; ++q) s[q] += bp[q];
+      } else {
+        for (int q = 0; gcol + q < gb.N; ++q) s[q] += bp[q];
+      }
     }
   }
-  union {
-    __bf16 b[16];
-    uint16_t h16[16];
-    u32x4 u[2];
-  } o;
+  if constexpr (BF16) {
+    union {
+      __bf16 b[16];
+      uint16_t h16[16];
+      u32x4 u[2];
+    } o;
 #pragma unroll
-  for (int q = 0; q < 16; ++q) o.b[q] = (__bf16)s[q];  // round to nearest even
-  uint16_t* dst = (uint16_t*)gb.c + (size_t)grow * gb.ldc + gcol;
-  if (full && gb.ldc % 8 == 0 && ((uintptr_t)gb.c & 15) == 0) {
-    ((u32x4*)dst)[0] = o.u[0];
-    ((u32x4*)dst)[1] = o.u[1];
+    for (int q = 0; q < 16; ++q) o.b[q] = (__bf16)s[q];  // round to nearest even
+    uint16_t* dst = (uint16_t*)gb.c + (size_t)grow * gb.ldc + gcol;
+    if (full && gb.ldc % 8 == 0 && ((uintptr_t)gb.c & 15) == 0) {
+      ((u32x4*)dst)[0] = o.u[0];
+      ((u32x4*)dst)[1] = o.u[1];
+    } else {
+#pragma unroll
+      for (int q = 0; q < 16; ++q)
+        if (gcol + q < gb.N) dst[q] = o.h16[q];
+    }
   } else {
+    float* dst = (float*)gb.c + (size_t)grow * gb.ldc + gcol;
+    if (full && gb.ldc % 4 == 0 && ((uintptr_t)gb.c & 15) == 0) {
 #pragma unroll
-    for (int q = 0; q < 16; ++q)
-      if (gcol + q < gb.N) dst[q] = o.h16[q];
+      for (int q = 0; q < 4; ++q) ((float4*)dst)[q] = float4{s[4 * q], s[4 * q + 1], s[4 * q + 2], s[4 * q + 3]};
+    } else {
+#pragma unroll
+      for (int q = 0; q < 16; ++q)
+        if (gcol + q < gb.N) dst[q] = s[q];
+    }
   }
 }
 
@@ -482,17 +632,18 @@ __global__ __launch_bounds__(256, 4) void gemm_stream_tt_kernel(const GemmBlock*
 
 // The launches these kernels are for.  gemm_stream_kernel: bf16, A contiguous along K, 64 x 64 tiles over the whole K
 // range (no K split).  gemm_stream_tt_kernel: bf16, both operands as k lines, 128 x 128 tiles, one segment.
-bool gemm_stream_usable(const std::vector<GemmBlock>& blocks, bool a_kc, bool b_kc) {
+bool gemm_stream_usable(const std::vector<GemmBlock>& blocks, bool bf16, bool a_kc, bool b_kc) {
+  const int ve = bf16 ? 8 : 4;  // elements per 16-byte piece
   if (!a_kc) {
-    if (b_kc) return false;
+    if (b_kc || !bf16) return false;
     for (const GemmBlock& b : blocks)
       if (b.nseg != 1 || b.M % 8 || b.N % 8) return false;
     return true;
   }
   for (const GemmBlock& b : blocks) {
-    if (!b_kc && b.N % 8) return false;
+    if (!b_kc && b.N % ve) return false;
     for (int s = 0; s < b.nseg; ++s)
-      if (b.seg[s].K % 8) return false;
+      if (b.seg[s].K % ve) return false;
   }
   return true;
 }
@@ -512,19 +663,21 @@ int launch_gemm_stream_tt(const GemmBlock* d_blocks, const std::vector<GemmBlock
   return DISTDL_OK;
 }
 
-int launch_gemm_stream(const GemmBlock* d_blocks, const std::vector<GemmBlock>& blocks, bool b_kc, hipStream_t st) {
+template <bool BF16, bool B_KC>
+static int launch_stream_variant(dim3 grid, const GemmBlock* d_blocks, hipStream_t st) {
+  if (int rc = allow_large_lds<gemm_stream_kernel<BF16, B_KC>>()) return rc;
+  hipLaunchKernelGGL((gemm_stream_kernel<BF16, B_KC>), grid, dim3(256), kStreamLds, st, d_blocks);
+  return DISTDL_OK;
+}
+
+int launch_gemm_stream(const GemmBlock* d_blocks, const std::vector<GemmBlock>& blocks, bool bf16, bool b_kc,
+                       hipStream_t st) {
   int tiles = 0;
   for (const GemmBlock& b : blocks) tiles = std::max(tiles, ((b.M + 63) / 64) * ((b.N + 63) / 64));
   tiles = (tiles + 7) / 8 * 8;
-  const dim3 grid((unsigned)tiles, 1, (unsigned)blocks.size()), block(256);
-  if (b_kc) {
-    if (int rc = allow_large_lds<gemm_stream_kernel<true>>()) return rc;
-    hipLaunchKernelGGL(gemm_stream_kernel<true>, grid, block, kStreamLds, st, d_blocks);
-  } else {
-    if (int rc = allow_large_lds<gemm_stream_kernel<false>>()) return rc;
-    hipLaunchKernelGGL(gemm_stream_kernel<false>, grid, block, kStreamLds, st, d_blocks);
-  }
-  return DISTDL_OK;
+  const dim3 grid((unsigned)tiles, 1, (unsigned)blocks.size());
+  if (bf16) return b_kc ? launch_stream_variant<true, true>(grid, d_blocks, st) : launch_stream_variant<true, false>(grid, d_blocks, st);
+  return b_kc ? launch_stream_variant<false, true>(grid, d_blocks, st) : launch_stream_variant<false, false>(grid, d_blocks, st);
 }
 
 }  // namespace distdl
