@@ -323,7 +323,10 @@ bool wgrad16_shape(const distdl_plan* p, bool vec, Wgrad16Shape& s) {
 // the 256 positions of a workgroup.  A lane reads KM consecutive channels of its cell (KM = 1, 2, 4 for
 // kc <= 4, 8, 16) and issues KM MFMAs per tap.  The patch is kept in LDS as four channel groups (group kg =
 // channels KM * kg ... of every cell, groups a.ps bytes apart), so that the 16 lanes of a group read
-// consecutive addresses.
+// consecutive addresses.  The tile is accumulated transposed (the weights are the first MFMA operand): a lane
+// then holds four consecutive output channels of one position and stores them as 16 bytes when the output
+// channel count is a multiple of 4 (sixteen 4-byte stores per step and lane before: the store instructions of
+// a step took about as long to issue as half of its MFMAs), and its set-up needs 4 store offsets, not 16.
 
 struct Corr16Args {
   CorrArgs c;                  // taps, steps and parity class of the launch
@@ -415,10 +418,9 @@ __global__ __launch_bounds__(256, 2) void corr16_kernel(const WorkerDev* __restr
   // per-thread patch pieces: global byte offset inside the first plane of a stage (kOobS: the cell lies outside
   // the input and reads as zero) and LDS byte offset with the piece's plane in bits 24-29
   uint32_t goff[PA], loff[PA];
-  uint32_t abase[4], soff[4][4];
+  uint32_t abase[4], soff[4];
   const int trtc = a.tr * a.tc, npos = a.tp * trtc;
-  auto setup_window = [&]() {
-  {
+  auto setup_pieces = [&]() {
     const uint32_t ppc = c.kc / V, npieces = ncells * ppc;
     const float r_ppc = 1.0f / (float)ppc, r_pc = 1.0f / (float)plane_cells, r_cw = 1.0f / (float)a.Cw;
 #pragma unroll
@@ -438,37 +440,34 @@ __global__ __launch_bounds__(256, 2) void corr16_kernel(const WorkerDev* __restr
           goff[i] = (wp * sin + (uint32_t)i1 * si1 + (uint32_t)i2 * si2 + part * V) * 4u;
       }
     }
-  }
-  // operand addresses and store offsets: lane (ij, kg) multiplies window position (wave * 4 + mt) * 16 + ij and
-  // holds, in accumulator register v, position (wave * 4 + mt) * 16 + 4 * kg + v of output channel ij
+  };
+  // operand addresses and store offsets: lane (ij, kg) multiplies window position (wave * 4 + mt) * 16 + ij.  The
+  // products are accumulated transposed (weights as the first MFMA operand), so accumulator register v of that lane
+  // is output channel 4 * kg + v of the same position: four consecutive channels, one 16-byte store.
+  auto setup_operands = [&]() {
   const float r_trtc = 1.0f / (float)trtc, r_tc = 1.0f / (float)a.tc;
 #pragma unroll
   for (int mt = 0; mt < 4; ++mt) {
-    uint32_t pidx = (wave * 4 + mt) * 16 + ij;
-    if (pidx >= (uint32_t)npos) pidx = 0;  // idle position: multiplies something in range, never stored
-    const uint32_t wp = div_small(pidx, trtc, r_trtc), rem = pidx - wp * trtc;
+    const uint32_t pidx = (wave * 4 + mt) * 16 + ij;
+    const bool live = pidx < (uint32_t)npos;
+    const uint32_t pp = live ? pidx : 0;  // idle position: multiplies something in range, never stored
+    const uint32_t wp = div_small(pp, trtc, r_trtc), rem = pp - wp * trtc;
     const uint32_t wr = div_small(rem, a.tc, r_tc), wc = rem - wr * a.tc;
     abase[mt] = ((wp * a.R + wr * c.is[1]) * a.Cw + wc * c.is[2]) * CG + kg * ps;
-    // the four positions of this lane's accumulator registers are consecutive: walk (plane, row, column)
-    uint32_t po = (wave * 4 + mt) * 16 + 4 * kg;
-    uint32_t op = div_small(po, trtc, r_trtc);
-    uint32_t orow = div_small(po - op * trtc, a.tc, r_tc), ocol = po - op * trtc - orow * a.tc;
-#pragma unroll
-    for (int v = 0; v < 4; ++v) {
-      soff[mt][v] = kOobS;
-      const int q1 = q1_0 + (int)orow, q2 = q2_0 + (int)ocol;
-      if (po + v < (uint32_t)npos && q1 < g.nq[1] && q2 < g.nq[2] && ij < c.nc)
-        soff[mt][v] = (op * son + (uint32_t)(g.out_base[1] + g.os[1] * q1) * so1 +
-                       (uint32_t)(g.out_base[2] + g.os[2] * q2) * so2 + ij) * 4u;
-      if (++ocol == (uint32_t)a.tc) {
-        ocol = 0;
-        if (++orow == (uint32_t)a.tr) orow = 0, ++op;
-      }
-    }
+    const int q1 = q1_0 + (int)wr, q2 = q2_0 + (int)wc;
+    soff[mt] = kOobS;
+    if (live && q1 < g.nq[1] && q2 < g.nq[2] && 4 * kg < c.nc)
+      soff[mt] = (wp * son + (uint32_t)(g.out_base[1] + g.os[1] * q1) * so1 +
+                  (uint32_t)(g.out_base[2] + g.os[2] * q2) * so2 + 4 * kg) * 4u;
   }
   };
-  const uint32_t pob = (wave * 4) * 16 + 4 * kg;
-  const float bias = (a.bias && ij < c.nc) ? a.bias[ij] : 0.f;
+  const uint32_t ppos = (wave * 4) * 16 + ij;  // this lane's window position in M-tile 0
+  // 16-byte stores need whole channel quads (V == 4 vouches for the alignment of the arrays, and for the input
+  // channel count only)
+  const bool wide = V == 4 && (c.nc & 3) == 0;
+  float bias[4];
+#pragma unroll
+  for (int v = 0; v < 4; ++v) bias[v] = (a.bias && 4 * kg + v < c.nc) ? a.bias[4 * kg + v] : 0.f;
   const uint32_t bread = wl + lane * KM * 4u;
 
   // a stage is (window step, kernel plane t0); stages whose input plane lies outside the input are skipped
@@ -529,6 +528,30 @@ __global__ __launch_bounds__(256, 2) void corr16_kernel(const WorkerDev* __restr
   };
 
   floatx4 acc[4];
+  auto store_tile = [&](const floatx4 (&t)[4], uint32_t obase, uint32_t plimit) {
+    // The step's offset is added into the per-lane offset: a 16-byte buffer store that takes it from a scalar
+    // register has been seen to pick up, in its first data register, a value written there two instructions
+    // later (the compiler inserts the wait states only for stores without a scalar offset).
+    uint32_t off[4];
+#pragma unroll
+    for (int mt = 0; mt < 4; ++mt) off[mt] = (ppos + mt * 16 < plimit ? soff[mt] : kOobS) + obase;
+    if (wide) {
+#pragma unroll
+      for (int mt = 0; mt < 4; ++mt) {
+        u32x4 o;
+#pragma unroll
+        for (int v = 0; v < 4; ++v) o[v] = __float_as_uint(t[mt][v] + bias[v]);
+        __builtin_amdgcn_raw_buffer_store_b128(o, rout, off[mt], 0, 0);
+      }
+    } else {
+#pragma unroll
+      for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+        for (int v = 0; v < 4; ++v)
+          __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(t[mt][v] + bias[v]), rout,
+                                                4 * kg + v < c.nc ? off[mt] + 4u * v : kOobS, 0, 0);
+    }
+  };
   auto read_ops = [&](int tap, OT& b, OT (&av)[4]) {
     const uint32_t tapo = NT > 0 ? (uint32_t)a.tapo[tap] : (uint32_t)__builtin_amdgcn_readfirstlane(a.tapo[tap]);
     b = *(const OT*)(ldsb + bread + tap * (64 * KM * 4));
@@ -540,7 +563,7 @@ __global__ __launch_bounds__(256, 2) void corr16_kernel(const WorkerDev* __restr
     for (int gk = 0; gk < KM; ++gk)
 #pragma unroll
       for (int mt = 0; mt < 4; ++mt)
-        acc[mt] = __builtin_amdgcn_mfma_f32_16x16x4f32(comp(av[mt], gk), comp(b, gk), acc[mt], 0, 0, 0);
+        acc[mt] = __builtin_amdgcn_mfma_f32_16x16x4f32(comp(b, gk), comp(av[mt], gk), acc[mt], 0, 0, 0);
   };
   // operands of tap t + 1 are read while tap t multiplies (scheduling barriers keep the reads where they are)
   auto compute = [&]() {
@@ -583,11 +606,12 @@ __global__ __launch_bounds__(256, 2) void corr16_kernel(const WorkerDev* __restr
     q1_0 = (int)(window / n2) * a.tr;
     f += step_end - step_begin;
   }
-  setup_window();
+  setup_pieces();
   int cs = step_begin, ct0 = 0;
   if (ntaps == 0) cs = step_end;  // a parity class no tap reaches: zeros
   next_valid(cs, ct0);
   if (cs < step_end) load_stage(cs, ct0, ct0 != staged_t0);
+  setup_operands();  // while the first stage is on its way
   for (int step = step_begin; step < step_end; ++step) {
 #pragma unroll
     for (int mt = 0; mt < 4; ++mt) acc[mt] = floatx4{0.f, 0.f, 0.f, 0.f};
@@ -605,14 +629,8 @@ __global__ __launch_bounds__(256, 2) void corr16_kernel(const WorkerDev* __restr
       ct0 = nt;
     }
     const int n = a.tp > 1 ? step * a.tp : step / nq0, q0 = a.tp > 1 ? 0 : step % nq0;
-    const uint32_t obase = ((uint32_t)n * son + (uint32_t)(g.out_base[0] + g.os[0] * q0) * so0) * 4u;
-    const uint32_t plimit = (uint32_t)min(a.tp, planes - step * a.tp) * trtc;
-#pragma unroll
-    for (int mt = 0; mt < 4; ++mt)
-#pragma unroll
-      for (int v = 0; v < 4; ++v)
-        __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(acc[mt][v] + bias), rout,
-                                              pob + mt * 16 + v < plimit ? soff[mt][v] : kOobS, obase, 0);
+    store_tile(acc, ((uint32_t)n * son + (uint32_t)(g.out_base[0] + g.os[0] * q0) * so0) * 4u,
+               (uint32_t)min(a.tp, planes - step * a.tp) * trtc);
   }
   } while (MULTI && f < f_end);
 }

@@ -119,6 +119,34 @@ def test_conv_fwd_bwd_against_partitioned_oracle(name, override, use_bias):
         assert_close(db.cpu().numpy(), db_want, TOL32, "db")
 
 
+@pytest.mark.gpu
+def test_small_channel_conv_repeated_launches_give_identical_bits():
+    """The 16-channel kernels are deterministic (fixed summation order, one writer per cell): any difference between
+    repeated launches of the 2-D configuration at full size (ragged windows in the data gradient) is a hazard."""
+    require_gpu()
+    cfg, part, case = _conv_case("cfg2")
+    plan = dd.distdl_plan_create(cfg["D"], cfg["n_b"], cfg["c_in"], cfg["c_out"], cfg["in_shape"], cfg["P"],
+                                 cfg["ksize"], cfg["stride"], cfg["padding"], cfg["dilation"], torch.float32)
+    x_bufs = [to_cl(b, torch.float32) for b in prim.scatter_bulk(case["x"], part, fill=np.float32(3.0))]
+    w = w_to_dev(case["w"])
+    dy = [to_cl(t, torch.float32) for t in prim.scatter_out(case["dy"], part)]
+    ws = torch.empty(max(dd.distdl_conv_bwd_workspace(plan), 16), dtype=torch.uint8, device="cuda")
+
+    def run():
+        y = [torch.full_like(t, float("nan")) for t in dy]
+        dx = [torch.full_like(b, float("nan")) for b in x_bufs]
+        dw = torch.full_like(w, float("nan"))
+        dd.distdl_conv_fwd(plan, x_bufs, w, None, y)
+        dd.distdl_conv_bwd(plan, x_bufs, w, dy, dx, dw, None, ws)
+        torch.cuda.synchronize()
+        return y + dx + [dw]
+
+    first = run()
+    assert not any(bool(torch.isnan(t).any()) for t in first)
+    for _ in range(20):
+        assert all(torch.equal(a, b) for a, b in zip(run(), first))
+
+
 def _random_small_cases(count):
     """Seeded random layers with at most 16 channels: D, kernel, dilation, leading-dimension stride, ragged shapes
     and partitions (the geometry the 16 x 16-tile kernels choose their windows and units from)."""
