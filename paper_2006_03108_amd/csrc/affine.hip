@@ -328,8 +328,8 @@ int distdl_affine_bwd(distdl_affine_plan* p, const void* const x_dev[], const vo
       if (db_dev && (rc = p->g_db.upload(bb, st_))) return rc;
       // the bias gradient rides in the weight-gradient launch when its kernel can carry it (it reads the same dy_i)
       GemmColsum cs{p->g_db.dev, p->P_fo, (int)p->max_fo, false};
-      bool db_aligned = db_dev != nullptr;  // the fused sums store 8 bytes at a time
-      for (int i = 0; db_dev && i < p->P_fo; ++i) db_aligned &= (uintptr_t)db_dev[i] % 8 == 0;
+      bool db_aligned = db_dev != nullptr;  // the fused sums store four features (8 or 16 bytes) at a time
+      for (int i = 0; db_dev && i < p->P_fo; ++i) db_aligned &= (uintptr_t)db_dev[i] % (bf16 ? 8 : 16) == 0;
       // dx and dW on one stream, one after the other.  Measured: dW on a side stream between a fork and a join event
       // (its 32 KB workgroups fit next to the 128 KB ones of dx) makes the step slower, eager and from a graph
       // (72 against 61 us at 256 x 4096 x 4096): both launches are bound by what a compute unit can take in.

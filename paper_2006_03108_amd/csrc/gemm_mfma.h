@@ -53,8 +53,8 @@ int launch_gemm_stream(const GemmBlock* d_blocks, const std::vector<GemmBlock>& 
                        hipStream_t st);
 // the weight-gradient layout (both operands as k lines), 128 x 128 tiles
 // d_colsum (or null): column sums (the bias gradient) computed by extra workgroups of the same launch
-int launch_gemm_stream_tt(const GemmBlock* d_blocks, const std::vector<GemmBlock>& blocks, const ColsumBlock* d_colsum,
-                          int n_colsum, int max_f, hipStream_t st);
+int launch_gemm_stream_tt(const GemmBlock* d_blocks, const std::vector<GemmBlock>& blocks, bool bf16,
+                          const ColsumBlock* d_colsum, int n_colsum, int max_f, hipStream_t st);
 int launch_colsum(const ColsumBlock* d_blocks, int nblocks, int max_f, bool bf16, hipStream_t st);
 
 }  // namespace distdl

@@ -592,10 +592,10 @@ int launch_gemm_mfma(const GemmBlock* d_blocks, const std::vector<GemmBlock>& bl
   // launches that take 64-tiles over the whole K range (about one tile per compute unit: the small-batch forward
   // and data-gradient products) run on the streaming kernel
   if (t == 64 && nsplit <= 1 && a_kc && gemm_stream_usable(blocks, bf16, a_kc, b_kc)) return launch_gemm_stream(d_blocks, blocks, bf16, b_kc, st);
-  if (bf16 && t == 128 && nsplit <= 1 && !a_kc && !b_kc && gemm_stream_usable(blocks, bf16, a_kc, b_kc)) {
-    if (colsum) colsum->done = true;  // M % 8 == 0 for every block: the feature counts fit the fused column sums
-    return launch_gemm_stream_tt(d_blocks, blocks, colsum ? colsum->d_blocks : nullptr, colsum ? colsum->n_blocks : 0,
-                                 colsum ? colsum->max_f : 0, st);
+  if (t == 128 && nsplit <= 1 && !a_kc && !b_kc && gemm_stream_usable(blocks, bf16, a_kc, b_kc)) {
+    if (colsum) colsum->done = true;  // M is a multiple of a piece for every block: the feature counts fit the fused column sums
+    return launch_gemm_stream_tt(d_blocks, blocks, bf16, colsum ? colsum->d_blocks : nullptr,
+                                 colsum ? colsum->n_blocks : 0, colsum ? colsum->max_f : 0, st);
   }
   int rc;
 #define DISTDL_GEMM(BF_, A_, B_)                                                                \

@@ -435,17 +435,20 @@ __global__ __launch_bounds__(256, 1) void gemm_stream_kernel(const GemmBlock* __
 // global -> LDS loads, each wave fetching a quarter of a step) and at most 128 registers let four workgroups share a
 // compute unit.  A staged block is 32 k lines x 256 bytes (128 rows); line l keeps its 16-byte piece c at position
 // c ^ (4 * (l & 3)): the four lines a half-wave's transposing read touches (64 bytes each) then cover the 64 banks once.
+// fp32: steps of 16 k (a block is 16 lines x 512 bytes), 32x32x2 MFMAs whose operand is one float per lane
+// (row lane % 32 of k line 2 p + lane / 32 for k pair p): a half-wave reads 128 consecutive bytes of its line, and
+// odd lines keep piece c at c ^ 8, so that the two half-waves use different halves of the banks.
 namespace {
-constexpr int kTtStepK = 32;
-constexpr int kTtOperand = kTtStepK * 256;  // one operand block of a step
-constexpr int kTtStep = 2 * kTtOperand;     // 16 KB
-constexpr int kTtLds = 2 * kTtStep;         // 32 KB
+constexpr int kTtOperand = 8192;         // one operand block of a step: 32 (bf16) or 16 (fp32) k lines of 128 elements
+constexpr int kTtStep = 2 * kTtOperand;  // 16 KB
+constexpr int kTtLds = 2 * kTtStep;      // 32 KB
 }  // namespace
 
 // The first cs_wgs workgroups of the grid's z = 0 slice do not multiply: they are the layer's bias gradient
 // db_i[f] = sum over the batch of dy_i[n][f] (R over the samples; one chunk of 256 features of one block each, a lane
 // sums 4 features over every fourth row, the four waves are added in wave order), which rides along in this launch
 // instead of costing one of its own: dy is the A operand here, so it is in L2 anyway.
+template <bool BF16>
 __global__ __launch_bounds__(256, 4) void gemm_stream_tt_kernel(const GemmBlock* __restrict__ blocks,
                                                                 const ColsumBlock* __restrict__ cs, int n_cs,
                                                                 int cs_chunks, int cs_wgs) {
@@ -459,7 +462,23 @@ __global__ __launch_bounds__(256, 4) void gemm_stream_tt_kernel(const GemmBlock*
     const int lane_ = threadIdx.x & 63, wave_ = threadIdx.x >> 6;
     const int f0 = ch * 256 + lane_ * 4;
     float sum[4] = {0.f, 0.f, 0.f, 0.f};
-    if (f0 < cb.n_f) {  // whole groups of 4 features: n_f % 8 == 0 is a condition of this kernel
+    if constexpr (!BF16) {
+      if (f0 < cb.n_f) {  // whole groups of 4 features: n_f % 4 == 0 is a condition of this kernel
+        const float* in = (const float*)cb.in + f0;
+        int n = wave_;
+        for (; n + 28 < cb.n_b; n += 32) {
+          float4 v[8];
+#pragma unroll
+          for (int u = 0; u < 8; ++u) v[u] = *(const float4*)(in + (size_t)(n + 4 * u) * cb.n_f);
+#pragma unroll
+          for (int u = 0; u < 8; ++u) sum[0] += v[u].x, sum[1] += v[u].y, sum[2] += v[u].z, sum[3] += v[u].w;
+        }
+        for (; n < cb.n_b; n += 4) {
+          const float4 v = *(const float4*)(in + (size_t)n * cb.n_f);
+          sum[0] += v.x, sum[1] += v.y, sum[2] += v.z, sum[3] += v.w;
+        }
+      }
+    } else if (f0 < cb.n_f) {  // whole groups of 4 features: n_f % 8 == 0 is a condition of this kernel
       const uint16_t* in = (const uint16_t*)cb.in + f0;
       int n = wave_;
       for (; n + 28 < cb.n_b; n += 32) {
@@ -488,12 +507,16 @@ __global__ __launch_bounds__(256, 4) void gemm_stream_tt_kernel(const GemmBlock*
         const float4 u = red[w * 64 + lane_];
         t.x += u.x; t.y += u.y; t.z += u.z; t.w += u.w;
       }
-      union {
-        __bf16 b[4];
-        uint2 u;
-      } o;
-      o.b[0] = (__bf16)t.x; o.b[1] = (__bf16)t.y; o.b[2] = (__bf16)t.z; o.b[3] = (__bf16)t.w;
-      *(uint2*)((uint16_t*)cb.out + f0) = o.u;
+      if constexpr (BF16) {
+        union {
+          __bf16 b[4];
+          uint2 u;
+        } o;
+        o.b[0] = (__bf16)t.x; o.b[1] = (__bf16)t.y; o.b[2] = (__bf16)t.z; o.b[3] = (__bf16)t.w;
+        *(uint2*)((uint16_t*)cb.out + f0) = o.u;
+      } else {
+        *(float4*)((float*)cb.out + f0) = t;
+      }
     }
     return;
   }
@@ -515,22 +538,26 @@ __global__ __launch_bounds__(256, 4) void gemm_stream_tt_kernel(const GemmBlock*
     for (int j = 0; j < 2; ++j)
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
+  constexpr int ES = BF16 ? 2 : 4, VE = 16 / ES, SK = BF16 ? 32 : 16;  // element bytes, elements per piece, k per step
+  constexpr int LB = 128 * ES;                                         // bytes of a staged k line
   const GemmSeg& sg = gb.seg[0];  // one segment (checked on the host)
-  const int K = sg.K, nsteps = (K + kTtStepK - 1) / kTtStepK;
+  const int K = sg.K, nsteps = (K + SK - 1) / SK;
   // resources end with the operand: k lines beyond K read as zero
-  const u32x4 ra = lds_direct_rsrc(sg.a, (uint32_t)K * sg.lda * 2);
-  const u32x4 rb = lds_direct_rsrc(sg.b, (uint32_t)K * sg.ldb * 2);
+  const u32x4 ra = lds_direct_rsrc(sg.a, (uint32_t)K * sg.lda * ES);
+  const u32x4 rb = lds_direct_rsrc(sg.b, (uint32_t)K * sg.ldb * ES);
   const uint32_t my_lds = lds_address(smem) + wave * 2048;
-  // load j of this wave: k lines 8 wave + 4 j + lane / 16, position lane % 16 of the line
+  // load j of this wave (1 KB): bf16 k lines 8 wave + 4 j + lane / 16, position lane % 16 of the line;
+  // fp32 k lines 4 wave + 2 j + lane / 32, position lane % 32
   uint32_t goff[4];
 #pragma unroll
   for (int j = 0; j < 2; ++j) {
-    const int l = 8 * wave + 4 * j + (lane >> 4);
-    const int c = (lane & 15) ^ (4 * (l & 3));
-    goff[j] = (m0 + c * 8 < gb.M) ? ((uint32_t)l * sg.lda + m0 + c * 8) * 2 : kOobOff;  // whole pieces: M % 8 == 0
-    goff[2 + j] = (n0 + c * 8 < gb.N) ? ((uint32_t)l * sg.ldb + n0 + c * 8) * 2 : kOobOff;
+    const int l = BF16 ? 8 * wave + 4 * j + (lane >> 4) : 4 * wave + 2 * j + (lane >> 5);
+    const int c = BF16 ? (lane & 15) ^ (4 * (l & 3)) : (lane & 31) ^ (8 * (l & 1));
+    // whole pieces: M and N are multiples of a piece
+    goff[j] = (m0 + c * VE < gb.M) ? ((uint32_t)l * sg.lda + m0 + c * VE) * ES : kOobOff;
+    goff[2 + j] = (n0 + c * VE < gb.N) ? ((uint32_t)l * sg.ldb + n0 + c * VE) * ES : kOobOff;
   }
-  const uint32_t a_step = (uint32_t)kTtStepK * sg.lda * 2, b_step = (uint32_t)kTtStepK * sg.ldb * 2;
+  const uint32_t a_step = (uint32_t)SK * sg.lda * ES, b_step = (uint32_t)SK * sg.ldb * ES;
   auto issue = [&](int st) __attribute__((always_inline)) {
     const uint32_t d = my_lds + (st & 1) * kTtStep;
     const uint32_t sa = (uint32_t)st * a_step, sb = (uint32_t)st * b_step;
@@ -541,12 +568,19 @@ __global__ __launch_bounds__(256, 4) void gemm_stream_tt_kernel(const GemmBlock*
   };
   // transposing reads: k line 16 g + tk (+ 4), rows (columns) base + tr ... + 3 as 8 bytes of piece (base + tr) / 8
   const int tk = 8 * (lane >> 5) + ((lane & 15) >> 2), tr = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+  // (fp32: k line 2 p + h of pair p, row (column) base + ml: one float)
   uint32_t rda[2], rdb[2];
 #pragma unroll
   for (int t = 0; t < 2; ++t) {
-    const int ca = (64 * wy + 32 * t + tr) >> 3, cb = (64 * wx + 32 * t + tr) >> 3;
-    rda[t] = tk * 256 + ((ca ^ (4 * (tk & 3))) * 16) + (tr & 7) * 2;
-    rdb[t] = kTtOperand + tk * 256 + ((cb ^ (4 * (tk & 3))) * 16) + (tr & 7) * 2;
+    if constexpr (BF16) {
+      const int ca = (64 * wy + 32 * t + tr) >> 3, cb = (64 * wx + 32 * t + tr) >> 3;
+      rda[t] = tk * 256 + ((ca ^ (4 * (tk & 3))) * 16) + (tr & 7) * 2;
+      rdb[t] = kTtOperand + tk * 256 + ((cb ^ (4 * (tk & 3))) * 16) + (tr & 7) * 2;
+    } else {
+      const int fa_ = 64 * wy + 32 * t + ml, fb_ = 64 * wx + 32 * t + ml;
+      rda[t] = h * LB + (((fa_ >> 2) ^ (8 * h)) * 16) + (fa_ & 3) * 4;
+      rdb[t] = kTtOperand + h * LB + (((fb_ >> 2) ^ (8 * h)) * 16) + (fb_ & 3) * 4;
+    }
   }
 
   if (nsteps > 0) issue(0);
@@ -557,30 +591,54 @@ __global__ __launch_bounds__(256, 4) void gemm_stream_tt_kernel(const GemmBlock*
     if (st + 1 < nsteps) __builtin_amdgcn_s_waitcnt(kWaitVmcnt4);
     else __builtin_amdgcn_s_waitcnt(kWaitVmcnt0);
     lds_barrier();  // and so has everyone's
-    Frag fa[2][2], fb[2][2];
+    if constexpr (BF16) {
+      Frag fa[2][2], fb[2][2];
 #pragma unroll
-    for (int g = 0; g < 2; ++g)
+      for (int g = 0; g < 2; ++g)
 #pragma unroll
-      for (int t = 0; t < 2; ++t) {
-        const int o = g * 16 * 256;
-        fa[g][t].t[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(sbuf + rda[t] + o));
-        fa[g][t].t[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(sbuf + rda[t] + o + 4 * 256));
-        fb[g][t].t[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(sbuf + rdb[t] + o));
-        fb[g][t].t[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(sbuf + rdb[t] + o + 4 * 256));
-      }
-    __builtin_amdgcn_sched_barrier(0);
-    __builtin_amdgcn_s_waitcnt(kWaitLgkmcnt0);
-    lds_barrier();  // every wave has this step in registers: its buffer may be refilled
-    if (st + 2 < nsteps) issue(st + 2);
-    __builtin_amdgcn_sched_barrier(0);
+        for (int t = 0; t < 2; ++t) {
+          const int o = g * 16 * 256;
+          fa[g][t].t[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(sbuf + rda[t] + o));
+          fa[g][t].t[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(sbuf + rda[t] + o + 4 * 256));
+          fb[g][t].t[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(sbuf + rdb[t] + o));
+          fb[g][t].t[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(sbuf + rdb[t] + o + 4 * 256));
+        }
+      __builtin_amdgcn_sched_barrier(0);
+      __builtin_amdgcn_s_waitcnt(kWaitLgkmcnt0);
+      lds_barrier();  // every wave has this step in registers: its buffer may be refilled
+      if (st + 2 < nsteps) issue(st + 2);
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int g = 0; g < 2; ++g)
+      for (int g = 0; g < 2; ++g)
 #pragma unroll
-      for (int i = 0; i < 2; ++i)
+        for (int i = 0; i < 2; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[g][j].v, fa[g][i].v, acc[i][j], 0, 0, 0);
-    __builtin_amdgcn_sched_barrier(0);
+          for (int j = 0; j < 2; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[g][j].v, fa[g][i].v, acc[i][j], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+    } else {
+      float fa[8][2], fb[8][2];
+#pragma unroll
+      for (int p = 0; p < 8; ++p)
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+          fa[p][t] = *(const float*)(sbuf + rda[t] + p * 2 * LB);
+          fb[p][t] = *(const float*)(sbuf + rdb[t] + p * 2 * LB);
+        }
+      __builtin_amdgcn_sched_barrier(0);
+      __builtin_amdgcn_s_waitcnt(kWaitLgkmcnt0);
+      lds_barrier();  // every wave has this step in registers: its buffer may be refilled
+      if (st + 2 < nsteps) issue(st + 2);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int p = 0; p < 8; ++p)
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+          for (int j = 0; j < 2; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fb[p][j], fa[p][i], acc[i][j], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+    }
   }
 
   // epilogue: the tile is rounded into LDS (the staging buffers are done with: the last barrier above came after
@@ -588,6 +646,37 @@ __global__ __launch_bounds__(256, 4) void gemm_stream_tt_kernel(const GemmBlock*
   // The products were accumulated transposed (B fragment as the first MFMA operand): register v of lane (h, ml) of
   // tile (i, j) is C[64 wy + 32 i + ml][64 wx + 32 j + 8 (v / 4) + 4 h + v % 4], so a register quad is four
   // consecutive columns: one 8-byte LDS write.  Row m keeps its 16-byte piece c at position c ^ (m & 15).
+  if constexpr (!BF16) {
+    // fp32: the tile (64 KB) does not fit the staging buffers, so each wave stages its 64 x 64 part 32 rows at a
+    // time in its own quarter of them (8 KB: rows of 256 bytes, row r keeps its 16-byte piece c at c ^ (r & 15)) and
+    // stores it in 16-byte pieces, 256 contiguous bytes per row; no workgroup barrier is needed (the last one above
+    // came after everyone's last read of the buffers).
+    char* const mine = smem + wave * 8192;
+    const bool vec4 = gb.ldc % 4 == 0 && ((uintptr_t)gb.c & 15) == 0;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int c = 8 * j + 2 * q + h;
+          *(float4*)(mine + ml * 256 + ((c ^ (ml & 15)) * 16)) =
+              float4{acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
+        }
+#pragma unroll
+      for (int r8 = 0; r8 < 8; ++r8) {
+        const int r = 4 * r8 + (lane >> 4), c = lane & 15;
+        const float4 v = *(const float4*)(mine + r * 256 + ((c ^ (r & 15)) * 16));
+        const int row = m0 + 64 * wy + 32 * i + r, col = n0 + 64 * wx + 4 * c;
+        if (row < gb.M && col < gb.N) {  // whole quads: N % 4 == 0
+          float* dst = (float*)gb.c + (size_t)row * gb.ldc + col;
+          if (vec4) __builtin_nontemporal_store(__builtin_bit_cast(u32x4, v), (u32x4*)dst);
+          else dst[0] = v.x, dst[1] = v.y, dst[2] = v.z, dst[3] = v.w;
+        }
+      }
+    }
+    return;
+  }
   constexpr int CP = 128 * 2;  // bytes per staged row
   static_assert(128 * CP <= kTtLds, "output tile must fit the staging buffer");
 #pragma unroll
@@ -635,9 +724,9 @@ __global__ __launch_bounds__(256, 4) void gemm_stream_tt_kernel(const GemmBlock*
 bool gemm_stream_usable(const std::vector<GemmBlock>& blocks, bool bf16, bool a_kc, bool b_kc) {
   const int ve = bf16 ? 8 : 4;  // elements per 16-byte piece
   if (!a_kc) {
-    if (b_kc || !bf16) return false;
+    if (b_kc) return false;
     for (const GemmBlock& b : blocks)
-      if (b.nseg != 1 || b.M % 8 || b.N % 8) return false;
+      if (b.nseg != 1 || b.M % ve || b.N % ve || (!bf16 && b.bias)) return false;
     return true;
   }
   for (const GemmBlock& b : blocks) {
@@ -650,16 +739,20 @@ bool gemm_stream_usable(const std::vector<GemmBlock>& blocks, bool bf16, bool a_
 
 // d_colsum (or null): n_colsum column-sum blocks of at most max_f features (multiples of 4, 8-byte aligned rows)
 // computed by extra workgroups of the same launch.
-int launch_gemm_stream_tt(const GemmBlock* d_blocks, const std::vector<GemmBlock>& blocks, const ColsumBlock* d_colsum,
-                          int n_colsum, int max_f, hipStream_t st) {
+int launch_gemm_stream_tt(const GemmBlock* d_blocks, const std::vector<GemmBlock>& blocks, bool bf16,
+                          const ColsumBlock* d_colsum, int n_colsum, int max_f, hipStream_t st) {
   int tiles = 0;
   for (const GemmBlock& b : blocks) tiles = std::max(tiles, ((b.M + 127) / 128) * ((b.N + 127) / 128));
   tiles = (tiles + 7) / 8 * 8;
   const int chunks = d_colsum ? std::max(1, (max_f + 255) / 256) : 1;
   const int cs_wgs = d_colsum ? (n_colsum * chunks + 7) / 8 * 8 : 0;  // a multiple of 8 keeps the tiles' XCD mapping
   const dim3 grid((unsigned)(tiles + cs_wgs), 1, (unsigned)blocks.size()), block(256);
-  hipLaunchKernelGGL(gemm_stream_tt_kernel, grid, block, kTtLds, st, d_blocks, d_colsum, d_colsum ? n_colsum : 0, chunks,
-                     cs_wgs);
+  if (bf16)
+    hipLaunchKernelGGL(gemm_stream_tt_kernel<true>, grid, block, kTtLds, st, d_blocks, d_colsum, d_colsum ? n_colsum : 0,
+                       chunks, cs_wgs);
+  else
+    hipLaunchKernelGGL(gemm_stream_tt_kernel<false>, grid, block, kTtLds, st, d_blocks, d_colsum, d_colsum ? n_colsum : 0,
+                       chunks, cs_wgs);
   return DISTDL_OK;
 }
 
