@@ -710,7 +710,7 @@ __global__ __launch_bounds__(256, 4) void gemm_stream_tt_kernel(const GemmBlock*
     if (row >= gb.M || col >= gb.N) continue;
     uint16_t* dst = (uint16_t*)gb.c + (size_t)row * gb.ldc + col;
     if (vec) {
-      *(u32x4*)dst = *(const u32x4*)(smem + rl * CP + ((q ^ (rl & 15)) * 16));
+      __builtin_nontemporal_store(*(const u32x4*)(smem + rl * CP + ((q ^ (rl & 15)) * 16)), (u32x4*)dst);
     } else {
       const uint16_t* src = (const uint16_t*)(smem + rl * CP + ((q ^ (rl & 15)) * 16));
 #pragma unroll
