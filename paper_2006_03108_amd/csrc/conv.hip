@@ -323,10 +323,10 @@ int conv_fwd_core(distdl_plan* plan, void* const x_bufs_dev[], const void* w_dev
   }
   if ((rc = plan->tab_x.upload((const void* const*)x_bufs_dev, plan->n_workers, st))) return rc;
   if ((rc = plan->tab_y.upload((const void* const*)y_dev, plan->n_workers, st))) return rc;
-  bool aligned = (uintptr_t)w_dev % 16 == 0;
-  for (int w = 0; w < plan->n_workers; ++w) aligned &= (uintptr_t)x_bufs_dev[w] % 16 == 0;
+  // 16-byte pieces on both sides: the matrix-core kernels load x in them and store y in them
   bool xvec = true;
-  for (int w = 0; w < plan->n_workers; ++w) xvec &= (uintptr_t)x_bufs_dev[w] % 16 == 0;
+  for (int w = 0; w < plan->n_workers; ++w) xvec &= (uintptr_t)x_bufs_dev[w] % 16 == 0 && (uintptr_t)y_dev[w] % 16 == 0;
+  const bool aligned = xvec && (uintptr_t)w_dev % 16 == 0;
   if (corr16_fwd_supported(plan, xvec)) {  // few channels: 16 x 16 tiles
     if ((rc = conv_fwd16(plan, (const float*)w_dev, (const float*)bias_dev, xvec, st))) return rc;
     DISTDL_HIP_TRY(hipGetLastError());
@@ -374,8 +374,8 @@ int conv_bwd_core(distdl_plan* plan, const void* const x_bufs_dev[], const void*
   if ((rc = plan->tab_dy.upload(dy_dev, plan->n_workers, st))) return rc;
   if ((rc = plan->tab_dx.upload((const void* const*)dx_bufs_dev, plan->n_workers, st))) return rc;
   ConvDev c = conv_params(plan);
-  bool aligned = true;
-  for (int w = 0; w < plan->n_workers; ++w) aligned &= (uintptr_t)dy_dev[w] % 16 == 0;
+  bool aligned = true;  // dy is loaded, dx^ stored in 16-byte pieces
+  for (int w = 0; w < plan->n_workers; ++w) aligned &= (uintptr_t)dy_dev[w] % 16 == 0 && (uintptr_t)dx_bufs_dev[w] % 16 == 0;
   const bool data_mfma = aligned && corr_mfma_supported(plan);
   bool vec16 = aligned && plan->n_ci % 4 == 0 && plan->n_co % 4 == 0;
   for (int w = 0; w < plan->n_workers; ++w) vec16 &= (uintptr_t)x_bufs_dev[w] % 16 == 0;

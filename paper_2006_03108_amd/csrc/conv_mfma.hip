@@ -44,6 +44,7 @@ constexpr int kMaxBPieces = 8;  // weight pieces per thread held in registers (3
 constexpr uint32_t kOob = 0x7ffffff0u;  // buffer offset that always fails the range check (buffers are < 2 GiB)
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 __device__ inline __amdgpu_buffer_rsrc_t make_rsrc(const void* p, uint32_t bytes) {
   return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)bytes, 0x00020000);
@@ -102,8 +103,11 @@ __device__ inline float load_scalar(const void* p, size_t i) {
 // staging registers, no ds_write) into one of two staging buffers, the next stage landing while this one is
 // multiplied, one barrier per stage.  The LDS layout of a stage is the same; thread (i, tid) fetches the piece whose
 // slot is i * 256 + tid (a wave's load fills 64 consecutive slots), found by inverting the slot formula.
+// Registers: the fp32 variants with small patches and compile-time taps (the parity classes of the data gradient)
+// are held to 128 so that four workgroups share a compute unit (0.684 -> 0.666 ms per class on the 5^3 stride-2
+// layer; they need 132 without the limit).
 template <int MT, int PA, int PB, int NT, int MODE, bool DMA = false>
-__global__ __launch_bounds__(256, 2) void corr_mfma_kernel(const WorkerDev* __restrict__ workers,
+__global__ __launch_bounds__(256, (PA <= 4 && MT == 2 && MODE == 0 && NT > 0) ? 4 : 2) void corr_mfma_kernel(const WorkerDev* __restrict__ workers,
                                                            void* const* in_bufs, void* const* out_bufs, CorrArgs a) {
   extern __shared__ float4 lds[];
   constexpr bool BF16 = MODE != 0, BFM = MODE == 2;
@@ -194,32 +198,31 @@ __global__ __launch_bounds__(256, 2) void corr_mfma_kernel(const WorkerDev* __re
   }
 
   // The workgroup's 128*MT output positions form a tr x tc window, row-major; lane m of M-tile
-  // (wave, mt) multiplies window position (wave*MT + mt)*32 + m, and accumulator register v of lane
-  // (h, m) is window position (wave*MT + mt)*32 + 8*(v/4) + 4*h + v%4, channel ntile*32 + m.
+  // (wave, mt) multiplies window position (wave*MT + mt)*32 + m.  The tile is accumulated transposed (the
+  // weights are the first MFMA operand), so accumulator register v of lane (h, m) is channel
+  // ntile*32 + 8*(v/4) + 4*h + v%4 of that same position: a register quad is four consecutive channels and
+  // goes out as one 16-byte (bf16: 8-byte) store, and a lane needs one store offset per M-tile.
   uint32_t abase[MT];
-  const int ch = ntile * 32 + m;
+  uint32_t soff[MT];  // of channel ntile*32 + 4*h of the lane's position (kOob: nothing to store)
+  const int ch0 = ntile * 32 + 4 * h;
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) {
     const int pidx = (wave * MT + mt) * 32 + m;
     int wr = (int)fd_div((uint32_t)pidx, a.div_tc), wc = pidx - wr * a.tc;
+    const int q1 = q1_0 + wr, q2 = q2_0 + wc;
+    soff[mt] = kOob;
+    if (wr < a.tr && q1 < g.nq[1] && q2 < g.nq[2])
+      soff[mt] = ((g.out_base[1] + g.os[1] * q1) * so1 + (g.out_base[2] + g.os[2] * q2) * so2 + ch0) * ES;
     if (wr >= a.tr) wr = 0, wc = 0;  // idle position: multiplies something in range, never stored
     abase[mt] = (wr * a.is[1] * 2 * a.is[2] * a.CwQ + wc + h * a.is[2] * a.CwQ) * 16;
   }
-  // store offset of accumulator register v of M-tile mt (kOob: nothing to store)
-  uint32_t soff[MT][16];
+  // channel quads of this lane (channel counts are multiples of 4, so a quad is whole or absent)
+  float bias[4][4];
 #pragma unroll
-  for (int mt = 0; mt < MT; ++mt) {
+  for (int q = 0; q < 4; ++q)
 #pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      const int po = (wave * MT + mt) * 32 + 8 * (v / 4) + 4 * h + (v % 4);
-      const int orow = (int)fd_div((uint32_t)po, a.div_tc), ocol = po - orow * a.tc;
-      const int q1 = q1_0 + orow, q2 = q2_0 + ocol;
-      soff[mt][v] = kOob;
-      if (orow < a.tr && q1 < g.nq[1] && q2 < g.nq[2] && ch < a.nc)
-        soff[mt][v] = ((g.out_base[1] + g.os[1] * q1) * so1 + (g.out_base[2] + g.os[2] * q2) * so2 + ch) * ES;
-    }
-  }
-  const float bias = (a.bias && ch < a.nc) ? load_scalar<BF16>(a.bias, ch) : 0.f;
+    for (int e = 0; e < 4; ++e)
+      bias[q][e] = (a.bias && ch0 + 8 * q + e < a.nc) ? load_scalar<BF16>(a.bias, ch0 + 8 * q + e) : 0.f;
   const uint32_t boff0 = tid * 16, bread = ((h * 32 + m) + a_units) * 16;  // weight piece / operand addresses
 
   const int* __restrict__ tapinfo = a.tapinfo;  // [0..7]: plane offsets, [8..]: patch offset per (t1, t2)
@@ -344,19 +347,19 @@ __global__ __launch_bounds__(256, 2) void corr_mfma_kernel(const WorkerDev* __re
       for (int mt = 0; mt < MT; ++mt) {
         Frag fa;
         fa.f = av[mt];
-        acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa.v, fb.v, acc[mt], 0, 0, 0);
+        acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb.v, fa.v, acc[mt], 0, 0, 0);
       }
       return;
     }
     // M-tiles interleaved, so that consecutive MFMAs do not depend on each other
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) acc[mt] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[mt].x, b.x, acc[mt], 0, 0, 0);
+    for (int mt = 0; mt < MT; ++mt) acc[mt] = __builtin_amdgcn_mfma_f32_32x32x2f32(b.x, av[mt].x, acc[mt], 0, 0, 0);
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) acc[mt] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[mt].y, b.y, acc[mt], 0, 0, 0);
+    for (int mt = 0; mt < MT; ++mt) acc[mt] = __builtin_amdgcn_mfma_f32_32x32x2f32(b.y, av[mt].y, acc[mt], 0, 0, 0);
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) acc[mt] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[mt].z, b.z, acc[mt], 0, 0, 0);
+    for (int mt = 0; mt < MT; ++mt) acc[mt] = __builtin_amdgcn_mfma_f32_32x32x2f32(b.z, av[mt].z, acc[mt], 0, 0, 0);
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) acc[mt] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[mt].w, b.w, acc[mt], 0, 0, 0);
+    for (int mt = 0; mt < MT; ++mt) acc[mt] = __builtin_amdgcn_mfma_f32_32x32x2f32(b.w, av[mt].w, acc[mt], 0, 0, 0);
   };
 
   // The operands of tap t + 1 are read while tap t multiplies; the scheduling barriers keep the
@@ -434,14 +437,28 @@ __global__ __launch_bounds__(256, 2) void corr_mfma_kernel(const WorkerDev* __re
     }
     const uint32_t obase = ((uint32_t)on * son + (uint32_t)(g.out_base[0] + g.os[0] * oq0) * so0) * ES;
     if (++oq0 == nq0) oq0 = 0, ++on;
+    // (the plane's offset is added into the per-lane offset: with a scalar offset the compiler leaves out the wait
+    // states a 16-byte store needs before its data registers are written again)
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-      for (int v = 0; v < 16; ++v)
-        if constexpr (BF16)
-          __builtin_amdgcn_raw_buffer_store_b16(bf16_bits(acc[mt][v] + bias), rout, soff[mt][v], obase, 0);
-        else
-          __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(acc[mt][v] + bias), rout, soff[mt][v], obase, 0);
+      for (int q = 0; q < 4; ++q) {
+        const uint32_t off = (ch0 + 8 * q < a.nc ? soff[mt] + (uint32_t)(8 * q) * ES : kOob) + obase;
+        if constexpr (BF16) {
+          union {
+            __bf16 b[4];
+            u32x2 u;
+          } o;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) o.b[e] = (__bf16)(acc[mt][4 * q + e] + bias[q][e]);
+          __builtin_amdgcn_raw_buffer_store_b64(o.u, rout, off, 0, 0);
+        } else {
+          u32x4 o;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) o[e] = __float_as_uint(acc[mt][4 * q + e] + bias[q][e]);
+          __builtin_amdgcn_raw_buffer_store_b128(o, rout, off, 0, 0);
+        }
+      }
   }
 }
 
@@ -1286,9 +1303,9 @@ static int launch_corr(distdl_plan* p, CorrArgs a, const void* w, float* wscratc
   if (lds > 64 * 1024)
     if (int rc = kv.large_lds()) return rc;
   // Workgroups per compute unit that add throughput: with fp32 MFMAs two already keep the matrix pipes busy (a
-  // third one resident only smooths the stage changes), with bf16 MFMAs the launch is bound by latencies and
-  // every resident workgroup counts.  Measured on the 5^3 stride-2 layer: counting three for fp32 picks chunk
-  // lengths that run 4 % slower, counting two for bf16 3 % slower.
+  // third and fourth one resident only smooth the stage changes), with bf16 MFMAs the launch is bound by latencies
+  // and every resident workgroup counts.  Measured on the 5^3 stride-2 layer: counting three or four for fp32 picks
+  // chunk lengths that run 1.5 - 3.5 % slower, counting two for bf16 3 % slower.
   int resident = resident_workgroups(kv.fn, lds);
   if (mode != 2) resident = std::min(resident, 2);
   // Output planes per workgroup.  A workgroup pays a fixed set-up (its address tables, about 8 * 10^3
