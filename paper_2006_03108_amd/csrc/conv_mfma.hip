@@ -104,10 +104,10 @@ __device__ inline float load_scalar(const void* p, size_t i) {
 // multiplied, one barrier per stage.  The LDS layout of a stage is the same; thread (i, tid) fetches the piece whose
 // slot is i * 256 + tid (a wave's load fills 64 consecutive slots), found by inverting the slot formula.
 // Registers: the fp32 variants with small patches and compile-time taps (the parity classes of the data gradient)
-// are held to 128 so that four workgroups share a compute unit (0.684 -> 0.666 ms per class on the 5^3 stride-2
-// layer; they need 132 without the limit).
+// are held to 128 (two M-tiles; they need 132 without the limit) or 168 (three) so that four or three workgroups
+// share a compute unit (0.684 -> 0.666 ms per class on the 5^3 stride-2 layer with two M-tiles).
 template <int MT, int PA, int PB, int NT, int MODE, bool DMA = false>
-__global__ __launch_bounds__(256, (PA <= 4 && MT == 2 && MODE == 0 && NT > 0) ? 4 : 2) void corr_mfma_kernel(const WorkerDev* __restrict__ workers,
+__global__ __launch_bounds__(256, (PA <= 4 && MT == 2 && MODE == 0 && NT > 0) ? 4 : (PA <= 4 && MT == 3 && MODE == 0 && NT > 0) ? 3 : 2) void corr_mfma_kernel(const WorkerDev* __restrict__ workers,
                                                            void* const* in_bufs, void* const* out_bufs, CorrArgs a) {
   extern __shared__ float4 lds[];
   constexpr bool BF16 = MODE != 0, BFM = MODE == 2;
@@ -1100,10 +1100,10 @@ static int choose_mt(CorrArgs& a, int nq1max, int nq2max, bool allow3) {
   if (allow3) {
     // Three M-tiles per wave (384 positions) when that window wastes clearly fewer of the multiplied positions
     // than 256 do, e.g. planes of 33 rows: 11-row windows fill three of them exactly, 7-row windows need five.
-    // Built for the small-patch variants only (the parity classes of a strided layer's data gradient), and used
-    // with bf16 MFMAs only: with fp32 MFMAs the third tile's registers cost the third workgroup per compute unit,
-    // which is worth more there than the 5 % of MFMAs (measured on the 5^3 stride-2 layer: +2 % time in fp32,
-    // -9 % in bf16).
+    // Built for the small-patch variants only (the parity classes of a strided layer's data gradient), not for
+    // bf16 tensors widened to fp32.  Measured on the 5^3 stride-2 layer: -9 % time in bf16, -3 % in fp32 (three
+    // resident workgroups of 384 positions against four of 256; while a lane still kept 16 store offsets per
+    // M-tile the third tile cost the third resident workgroup and the time went up 2 %).
     CorrArgs a3 = a, a2 = a;
     finish_args(a3, 3, choose_tc(384, nq1max, nq2max));
     finish_args(a2, 2, choose_tc(256, nq1max, nq2max));
@@ -1148,7 +1148,7 @@ static int corr_window(const distdl_plan* p, CorrArgs& a) {
   a.ck = mode == 2 ? 16 : 8;
   int nq1max, nq2max;
   max_nq(p, a, nq1max, nq2max);
-  return choose_mt(a, std::max(nq1max, 1), nq2max, mode == 2);
+  return choose_mt(a, std::max(nq1max, 1), nq2max, mode != 1);
 }
 
 bool corr_mfma_supported(const distdl_plan* p) {
@@ -1258,11 +1258,17 @@ static CorrVariant corr_variant_mode(int mt, bool small, int ntaps) {
   if (mt == 2 && small && ntaps == 6) return corr_variant_of<2, 4, 3, 6, MODE, D>();
   if (mt == 2 && small && ntaps == 4) return corr_variant_of<2, 4, 3, 4, MODE, D>();
   if (mt == 2 && small) return corr_variant_of<2, 4, 3, 0, MODE>();
-  if constexpr (MODE == 2) {  // three M-tiles per wave: bf16 MFMAs only
+  if constexpr (MODE == 2) {  // three M-tiles per wave
     if (mt == 3 && ntaps == 9) return corr_variant_of<3, 4, 3, 9, 2, true>();
     if (mt == 3 && ntaps == 6) return corr_variant_of<3, 4, 3, 6, 2, true>();
     if (mt == 3 && ntaps == 4) return corr_variant_of<3, 4, 3, 4, 2, true>();
     if (mt == 3) return corr_variant_of<3, 4, 3, 0, 2>();
+  }
+  if constexpr (MODE == 0) {
+    if (mt == 3 && ntaps == 9) return corr_variant_of<3, 4, 3, 9, 0>();
+    if (mt == 3 && ntaps == 6) return corr_variant_of<3, 4, 3, 6, 0>();
+    if (mt == 3 && ntaps == 4) return corr_variant_of<3, 4, 3, 4, 0>();
+    if (mt == 3) return corr_variant_of<3, 4, 3, 0, 0>();
   }
   if (mt == 2 && ntaps == 25) return corr_variant_of<2, kMaxPieces, kMaxBPieces, 25, MODE>();
   if (mt == 2) return corr_variant_of<2, kMaxPieces, kMaxBPieces, 0, MODE>();
