@@ -138,7 +138,7 @@ __global__ __launch_bounds__(256, 1) void gemm_stream_kernel(const GemmBlock* __
   // fp32 loop can spread them between its MFMAs; issue does it all at once.
   uint32_t is_d = 0, is_a = 0, is_b = 0;
   int is_kleft = 0;
-  bool is_valid = false, is_tail = false;
+  bool is_tail = false;
   auto issue_begin = [&](int buf, bool valid) __attribute__((always_inline)) {
     is_d = my_lds + buf * kStepBytes;
     int k0 = 0;
@@ -151,9 +151,10 @@ __global__ __launch_bounds__(256, 1) void gemm_stream_kernel(const GemmBlock* __
       k0 = lin * SK;
       lin += 4;
     }
-    is_a = (uint32_t)k0 * ES;
-    is_b = (uint32_t)k0 * (B_KC ? 1u : l_ldb) * ES;
-    is_valid = valid;
+    // (a step past the end is switched off through the scalar part of the offset, which the range check includes:
+    // no per-lane select on the path of the loads)
+    is_a = valid ? (uint32_t)k0 * ES : kOobOff;
+    is_b = valid ? (uint32_t)k0 * (B_KC ? 1u : l_ldb) * ES : kOobOff;
     // K tail: pieces of a K-contiguous row beyond K are switched off (whole pieces: K % VE == 0); k lines beyond
     // K lie beyond the resource
     is_tail = valid && k0 + SK > l_K;
@@ -161,17 +162,22 @@ __global__ __launch_bounds__(256, 1) void gemm_stream_kernel(const GemmBlock* __
   };
   auto issue_part = [&](auto q_c) __attribute__((always_inline)) {
     constexpr int q = decltype(q_c)::value;
+    constexpr bool kc_op = q < 2 || B_KC;  // loads of a K-contiguous operand
+    if (kc_op && is_tail) {               // (uniform: the last step of a segment; the piece test is per lane)
 #pragma unroll
-    for (int i = 4 * q; i < 4 * q + 4; ++i) {
-      const bool is_a_op = i < 8;
-      uint32_t off = is_valid ? goff[i] : kOobOff;
-      if (is_tail && (is_a_op || B_KC)) {  // (uniform condition; the piece test is per lane)
+      for (int i = 4 * q; i < 4 * q + 4; ++i) {
         const int r = 8 * (i & 7) + (lane >> 3);
         const int ca = (lane & 7) ^ ((r >> 1) & 7);
-        if (ca * VE >= is_kleft) off = kOobOff;
+        const uint32_t off = ca * VE >= is_kleft ? kOobOff : goff[i];
+        if (i < 8) load_to_lds(ra, is_d + i * 1024, off, is_a);
+        else load_to_lds(rb, is_d + kOperandBytes + (i - 8) * 1024, off, is_b);
       }
-      if (is_a_op) load_to_lds(ra, is_d + i * 1024, off, is_a);
-      else load_to_lds(rb, is_d + kOperandBytes + (i - 8) * 1024, off, is_b);
+    } else {
+#pragma unroll
+      for (int i = 4 * q; i < 4 * q + 4; ++i) {
+        if (i < 8) load_to_lds(ra, is_d + i * 1024, goff[i], is_a);
+        else load_to_lds(rb, is_d + kOperandBytes + (i - 8) * 1024, goff[i], is_b);
+      }
     }
   };
   auto issue = [&](int buf, bool valid) __attribute__((always_inline)) {
