@@ -245,40 +245,12 @@ __global__ __launch_bounds__(256, 1) void gemm_stream_kernel(const GemmBlock* __
     }
   };
 
-  // reads of one k group g of the step in buffer buf into slot g & 1 of (fa, fb): the A fragments, or the B fragments
-  auto read_a = [&](int buf, int g, Frag (&fa)[2][2]) __attribute__((always_inline)) {
-    const char* s = my + buf * kStepBytes;
-#pragma unroll
-    for (int t = 0; t < 2; ++t) fa[g & 1][t].u = *(const u32x4*)(s + rdk[g] + t * 4096);
-  };
-  auto read_b = [&](int buf, int g, Frag (&fb)[2][2]) __attribute__((always_inline)) {
-    const char* s = my + buf * kStepBytes;
-#pragma unroll
-    for (int t = 0; t < 2; ++t) {
-      if constexpr (B_KC) {
-        fb[g & 1][t].u = *(const u32x4*)(s + kOperandBytes + rdk[g] + t * 4096);
-      } else {
-#pragma unroll
-        for (int j = 0; j < 4; ++j) fb[g & 1][t].u[j] = *(const uint32_t*)(s + rdn[t] + (g * 8 + j) * 256);
-      }
-    }
-  };
-  // the four fp32 MFMAs of k pair e of fragment slot g
-  auto mm_pair = [&](const Frag (&fa)[2][2], const Frag (&fb)[2][2], int g, int e) __attribute__((always_inline)) {
-#pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-      for (int j = 0; j < 2; ++j)
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(fb[g][j].u[e]), __uint_as_float(fa[g][i].u[e]),
-                                                         acc[i][j], 0, 0, 0);
-  };
-
   if (n > 0) {
     enter_segment();
     issue(0, true);
     issue(1, 1 < n);
-    Frag xa[2][2], xb[2][2], ya[2][2], yb[2][2];
-    if constexpr (BF16 || B_KC) {
+    if constexpr (BF16) {
+      Frag xa[2][2], xb[2][2], ya[2][2], yb[2][2];
       // One step: its 16 loads have landed when at most the 16 of the next step are outstanding.  The buffer is
       // handed to the loads of the step after next as soon as every fragment of it is in registers.
       auto step = [&](int st, int buf) __attribute__((always_inline)) {
@@ -302,51 +274,75 @@ __global__ __launch_bounds__(256, 1) void gemm_stream_kernel(const GemmBlock* __
       }
       if (st < n) step(st, 0);
     } else {
-      // fp32 with B as k lines, whose fragments are read float by float (measured 80.6 against 83.6 us on the data
-      // gradient of a 1024 x 2048 x 2048 product; the K-contiguous forward product lost 4 us with this schedule and
-      // keeps the plain step above).  A step is 64 MFMAs of 64 clocks and this wave is alone on its SIMD, so
-      // everything else is issued in the shadow of the MFMAs, a few instructions after every four of them (eight
-      // slots per half step):
-      //   first half (k groups 0, 1, fragments read during the step before): the fragment reads of groups 2, 3;
-      //   second half (groups 2, 3): the fragment reads of groups 0, 1 of the next step from the other buffer
-      //   (its loads, issued a step ago, are the only ones outstanding: vmcnt(0)), then the 16 loads of the step
-      //   after next into this buffer, whose fragments are all in registers by then.
-      __builtin_amdgcn_s_waitcnt(kWaitVmcnt16);  // step 0 has landed
-      read_half(0, 0, xa, xb);
-      auto step = [&](int st, int buf) __attribute__((always_inline)) {
+      // fp32: a step is 64 MFMAs of 64 clocks and this wave is alone on its SIMD (512 registers), so the pipeline is
+      // one step deeper in registers and everything else is issued in the shadow of the MFMAs, in 16 slots, one
+      // after every four of them.  While step s multiplies out of one register set, the fragments of step s + 1 are
+      // read from the other staging buffer into the other set (its loads were issued during step s - 2: at most the
+      // 16 of step s + 2 are outstanding when they have landed), and when those reads are done the buffer takes the
+      // loads of step s + 3.  Every load has more than a step to land and every LDS read a step before its use.
+      Frag pa[4][2], pb[4][2], qa[4][2], qb[4][2];
+      auto rd_a = [&](int buf, int g, Frag (&fa)[4][2]) __attribute__((always_inline)) {
+        const char* s = my + buf * kStepBytes;
 #pragma unroll
-        for (int slot = 0; slot < 8; ++slot) {
-          mm_pair(xa, xb, slot >> 2, slot & 3);
-          __builtin_amdgcn_sched_barrier(0);
-          if (slot == 0) read_a(buf, 2, ya);
-          if (slot == 1) read_b(buf, 2, yb);
-          if (slot == 2) read_a(buf, 3, ya);
-          if (slot == 3) read_b(buf, 3, yb);
-          __builtin_amdgcn_sched_barrier(0);
+        for (int t = 0; t < 2; ++t) fa[g][t].u = *(const u32x4*)(s + rdk[g] + t * 4096);
+      };
+      auto rd_b = [&](int buf, int g, Frag (&fb)[4][2]) __attribute__((always_inline)) {
+        const char* s = my + buf * kStepBytes;
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+          if constexpr (B_KC) {
+            fb[g][t].u = *(const u32x4*)(s + kOperandBytes + rdk[g] + t * 4096);
+          } else {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) fb[g][t].u[j] = *(const uint32_t*)(s + rdn[t] + (g * 8 + j) * 256);
+          }
         }
-        __builtin_amdgcn_s_waitcnt(kWaitVmcnt0);
-        issue_begin(buf, st + 2 < n);
+      };
+      auto mm4 = [&](const Frag (&fa)[4][2], const Frag (&fb)[4][2], int g, int e) __attribute__((always_inline)) {
 #pragma unroll
-        for (int slot = 0; slot < 8; ++slot) {
-          mm_pair(ya, yb, slot >> 2, slot & 3);
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+          for (int j = 0; j < 2; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(fb[g][j].u[e]), __uint_as_float(fa[g][i].u[e]),
+                                                             acc[i][j], 0, 0, 0);
+      };
+      __builtin_amdgcn_s_waitcnt(kWaitVmcnt16);  // step 0 has landed
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        rd_a(0, g, pa);
+        rd_b(0, g, pb);
+      }
+      __builtin_amdgcn_s_waitcnt(kWaitLgkmcnt0);
+      issue(0, 2 < n);
+      // step st out of (ca, cb), whose buffer is buf; (na, nb) take step st + 1
+      auto step = [&](int st, int buf, const Frag (&ca)[4][2], const Frag (&cb)[4][2], Frag (&na)[4][2],
+                      Frag (&nb)[4][2]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int slot = 0; slot < 16; ++slot) {
+          mm4(ca, cb, slot >> 2, slot & 3);
           __builtin_amdgcn_sched_barrier(0);
-          if (slot == 0) read_a(buf ^ 1, 0, xa);
-          if (slot == 1) read_b(buf ^ 1, 0, xb);
-          if (slot == 2) read_a(buf ^ 1, 1, xa);
-          if (slot == 3) read_b(buf ^ 1, 1, xb);
-          if (slot == 4) issue_part(std::integral_constant<int, 0>{});
-          if (slot == 5) issue_part(std::integral_constant<int, 1>{});
-          if (slot == 6) issue_part(std::integral_constant<int, 2>{});
-          if (slot == 7) issue_part(std::integral_constant<int, 3>{});
+          if (slot == 0) __builtin_amdgcn_s_waitcnt(kWaitVmcnt16);
+          if (slot >= 1 && slot <= 8) {
+            if ((slot - 1) & 1) rd_b(buf ^ 1, (slot - 1) >> 1, nb);
+            else rd_a(buf ^ 1, (slot - 1) >> 1, na);
+          }
+          if (slot == 10) {
+            __builtin_amdgcn_s_waitcnt(kWaitLgkmcnt0);
+            issue_begin(buf ^ 1, st + 3 < n);
+          }
+          if (slot == 11) issue_part(std::integral_constant<int, 0>{});
+          if (slot == 12) issue_part(std::integral_constant<int, 1>{});
+          if (slot == 13) issue_part(std::integral_constant<int, 2>{});
+          if (slot == 14) issue_part(std::integral_constant<int, 3>{});
           __builtin_amdgcn_sched_barrier(0);
         }
       };
       int st = 0;
       for (; st + 2 <= n; st += 2) {
-        step(st, 0);
-        step(st + 1, 1);
+        step(st, 0, pa, pb, qa, qb);
+        step(st + 1, 1, qa, qb, pa, pb);
       }
-      if (st < n) step(st, 0);
+      if (st < n) step(st, 0, pa, pb, qa, qb);
     }
     __builtin_amdgcn_s_waitcnt(kWaitVmcnt0);  // nothing may still land in LDS when the epilogue reuses it
   }
