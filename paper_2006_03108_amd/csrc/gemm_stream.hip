@@ -180,6 +180,22 @@ __global__ __launch_bounds__(256, 1) void gemm_stream_kernel(const GemmBlock* __
       }
     }
   };
+  // loads 2 k and 2 k + 1 of the step; TAIL (compile time) says whether the K-tail select is needed at all
+  auto issue_pair = [&](auto k_c, auto tail_c) __attribute__((always_inline)) {
+    constexpr int k = decltype(k_c)::value;
+    constexpr bool TAIL = decltype(tail_c)::value && (k < 4 || B_KC);
+#pragma unroll
+    for (int i = 2 * k; i < 2 * k + 2; ++i) {
+      uint32_t off = goff[i];
+      if constexpr (TAIL) {
+        const int r = 8 * (i & 7) + (lane >> 3);
+        const int ca = (lane & 7) ^ ((r >> 1) & 7);
+        if (ca * VE >= is_kleft) off = kOobOff;
+      }
+      if (i < 8) load_to_lds(ra, is_d + i * 1024, off, is_a);
+      else load_to_lds(rb, is_d + kOperandBytes + (i - 8) * 1024, off, is_b);
+    }
+  };
   auto issue = [&](int buf, bool valid) __attribute__((always_inline)) {
     issue_begin(buf, valid);
     static_for4([&](auto q) __attribute__((always_inline)) { issue_part(q); });
@@ -314,28 +330,38 @@ __global__ __launch_bounds__(256, 1) void gemm_stream_kernel(const GemmBlock* __
       }
       __builtin_amdgcn_s_waitcnt(kWaitLgkmcnt0);
       issue(0, 2 < n);
-      // step st out of (ca, cb), whose buffer is buf; (na, nb) take step st + 1
-      auto step = [&](int st, int buf, const Frag (&ca)[4][2], const Frag (&cb)[4][2], Frag (&na)[4][2],
-                      Frag (&nb)[4][2]) __attribute__((always_inline)) {
+      // step st out of (ca, cb), whose buffer is buf; (na, nb) take step st + 1.  Slots: 0 waits for the loads of
+      // step st + 1, 1 - 4 read its fragments, 6 - 13 issue two loads each.  The wave has about 60 clocks per slot
+      // before the matrix pipe runs dry, and a taken branch costs a good part of that, so the one decision of the
+      // step (does its load have a K tail) is taken once, in front of two copies of the body.
+      auto body = [&](int buf, const Frag (&ca)[4][2], const Frag (&cb)[4][2], Frag (&na)[4][2], Frag (&nb)[4][2],
+                      auto tail_c) __attribute__((always_inline)) {
 #pragma unroll
         for (int slot = 0; slot < 16; ++slot) {
           mm4(ca, cb, slot >> 2, slot & 3);
           __builtin_amdgcn_sched_barrier(0);
           if (slot == 0) __builtin_amdgcn_s_waitcnt(kWaitVmcnt16);
-          if (slot >= 1 && slot <= 8) {
-            if ((slot - 1) & 1) rd_b(buf ^ 1, (slot - 1) >> 1, nb);
-            else rd_a(buf ^ 1, (slot - 1) >> 1, na);
+          if (slot >= 1 && slot <= 4) {
+            rd_a(buf ^ 1, slot - 1, na);
+            rd_b(buf ^ 1, slot - 1, nb);
           }
-          if (slot == 10) {
-            __builtin_amdgcn_s_waitcnt(kWaitLgkmcnt0);
-            issue_begin(buf ^ 1, st + 3 < n);
-          }
-          if (slot == 11) issue_part(std::integral_constant<int, 0>{});
-          if (slot == 12) issue_part(std::integral_constant<int, 1>{});
-          if (slot == 13) issue_part(std::integral_constant<int, 2>{});
-          if (slot == 14) issue_part(std::integral_constant<int, 3>{});
+          if (slot == 6) __builtin_amdgcn_s_waitcnt(kWaitLgkmcnt0);
+          if (slot == 6) issue_pair(std::integral_constant<int, 0>{}, tail_c);
+          if (slot == 7) issue_pair(std::integral_constant<int, 1>{}, tail_c);
+          if (slot == 8) issue_pair(std::integral_constant<int, 2>{}, tail_c);
+          if (slot == 9) issue_pair(std::integral_constant<int, 3>{}, tail_c);
+          if (slot == 10) issue_pair(std::integral_constant<int, 4>{}, tail_c);
+          if (slot == 11) issue_pair(std::integral_constant<int, 5>{}, tail_c);
+          if (slot == 12) issue_pair(std::integral_constant<int, 6>{}, tail_c);
+          if (slot == 13) issue_pair(std::integral_constant<int, 7>{}, tail_c);
           __builtin_amdgcn_sched_barrier(0);
         }
+      };
+      auto step = [&](int st, int buf, const Frag (&ca)[4][2], const Frag (&cb)[4][2], Frag (&na)[4][2],
+                      Frag (&nb)[4][2]) __attribute__((always_inline)) {
+        issue_begin(buf ^ 1, st + 3 < n);  // (scalars only; the loads follow in the body)
+        if (is_tail) body(buf, ca, cb, na, nb, std::true_type{});
+        else body(buf, ca, cb, na, nb, std::false_type{});
       };
       int st = 0;
       for (; st + 2 <= n; st += 2) {
