@@ -23,17 +23,30 @@ def _conv_case(name, **override):
     return cfg, part, case
 
 
-def _run_conv(cfg, part, case, use_bias, dtype=torch.float32):
+def _off_by_one_element(shape, value, dtype):
+    """A tensor of that shape whose storage starts one element into an allocation: aligned to its element only."""
+    n = int(np.prod(shape))
+    flat = torch.full((n + 1,), value, device="cuda", dtype=dtype)
+    return flat[1:].view(shape)
+
+
+def _run_conv(cfg, part, case, use_bias, dtype=torch.float32, misaligned_outputs=False):
     plan = dd.distdl_plan_create(cfg["D"], cfg["n_b"], cfg["c_in"], cfg["c_out"], cfg["in_shape"], cfg["P"],
                                  cfg["ksize"], cfg["stride"], cfg["padding"], cfg["dilation"], dtype)
     x_bufs = [to_cl(b, dtype) for b in prim.scatter_bulk(case["x"], part, fill=np.float32(3.0))]
     w = w_to_dev(case["w"]).to(dtype)
     bias = w_to_dev(case["bias"]).to(dtype) if use_bias else None
-    y = [torch.full((cfg["n_b"],) + part.out_shape(wk) + (cfg["c_out"],), 7.0, device="cuda", dtype=dtype)
-         for wk in range(part.n_workers)]
+    y_shapes = [(cfg["n_b"],) + part.out_shape(wk) + (cfg["c_out"],) for wk in range(part.n_workers)]
+    if misaligned_outputs:
+        y = [_off_by_one_element(sh, 7.0, dtype) for sh in y_shapes]
+    else:
+        y = [torch.full(sh, 7.0, device="cuda", dtype=dtype) for sh in y_shapes]
     dd.distdl_conv_fwd(plan, x_bufs, w, bias, y)
     dy = [to_cl(t, dtype) for t in prim.scatter_out(case["dy"], part)]
-    dx_bufs = [torch.full_like(b, 5.0) for b in x_bufs]
+    if misaligned_outputs:
+        dx_bufs = [_off_by_one_element(tuple(b.shape), 5.0, dtype) for b in x_bufs]
+    else:
+        dx_bufs = [torch.full_like(b, 5.0) for b in x_bufs]
     dw = torch.full_like(w, 9.0)
     db = torch.full((cfg["c_out"],), 9.0, device="cuda", dtype=dtype) if use_bias else None
     ws = torch.empty(max(dd.distdl_conv_bwd_workspace(plan), 16), dtype=torch.uint8, device="cuda")
@@ -145,6 +158,26 @@ def test_small_channel_conv_repeated_launches_give_identical_bits():
     assert not any(bool(torch.isnan(t).any()) for t in first)
     for _ in range(20):
         assert all(torch.equal(a, b) for a, b in zip(run(), first))
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("idx", [2, 10])  # a 16-channel 2-D layer and a 32-channel strided 3-D layer
+def test_conv_outputs_aligned_to_their_element_only(idx):
+    """y and dx^ that start 4 bytes into an allocation: the kernels that store 16 bytes at a time must not be chosen."""
+    require_gpu()
+    name, override, use_bias = CONV_FULL[idx]
+    cfg, part, case = _conv_case(name, **override)
+    x_bufs, y, dx_bufs, dw, db = _run_conv(cfg, part, case, use_bias, misaligned_outputs=True)
+    o_bufs = prim.scatter_bulk(case["x"].astype(np.float64), part, fill=np.nan)
+    bias = case["bias"] if use_bias else None
+    y_want = layers.dist_conv_forward(o_bufs, case["w"], bias, part, cfg["stride"], cfg["dilation"])
+    dx_want, dw_want, _ = layers.dist_conv_adjoint(o_bufs, case["w"], prim.scatter_out(case["dy"], part), part,
+                                                   cfg["stride"], cfg["dilation"], use_bias)
+    for wk in range(part.n_workers):
+        assert y[wk].data_ptr() % 16 != 0 and dx_bufs[wk].data_ptr() % 16 != 0
+        assert_close(from_cl(y[wk]), y_want[wk], TOL32, f"y worker {wk}")
+        assert_close(from_cl(dx_bufs[wk]), dx_want[wk], TOL32, f"dx worker {wk}")
+    assert_close(dw.cpu().numpy(), dw_want, TOL32, "dw")
 
 
 def _random_small_cases(count):
