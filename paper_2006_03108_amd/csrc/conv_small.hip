@@ -471,27 +471,39 @@ __global__ __launch_bounds__(256, 2) void corr16_kernel(const WorkerDev* __restr
   const uint32_t bread = wl + lane * KM * 4u;
 
   // a stage is (window step, kernel plane t0); stages whose input plane lies outside the input are skipped
-  auto in_plane = [&](int step, int t0) {
-    const int q0 = a.tp > 1 ? 0 : step % nq0;
-    return g.in_base[0] + q0 * c.is[0] + c.tapoff[0][t0];
+  // A stage position carries its sample and output plane along (stepped, not divided out of the step number: a
+  // division on the scalar unit is some thirty instructions, and there were three on the path of every step), and
+  // the plane offset of tap t0 is an arithmetic progression in t0 (see corr_mfma_kernel), not a table look-up.
+  struct StagePos {
+    int step, n, q0, t0;
   };
-  auto next_valid = [&](int& step, int& t0) {
-    while (step < step_end) {
-      while (t0 < nt0) {
-        const int i0 = in_plane(step, t0);
+  const int toff0 = c.tapoff[0][0], tstep = c.nt[0] > 1 ? c.tapoff[0][1] - c.tapoff[0][0] : 0;
+  auto in_plane = [&](int q0, int t0) { return g.in_base[0] + q0 * c.is[0] + toff0 + t0 * tstep; };
+  auto pos_of = [&](int step) {  // (set-up: once per window)
+    return a.tp > 1 ? StagePos{step, step * a.tp, 0, 0} : StagePos{step, step / nq0, step % nq0, 0};
+  };
+  auto next_step = [&](StagePos& sp) {
+    ++sp.step;
+    sp.t0 = 0;
+    if (a.tp > 1) sp.n += a.tp;
+    else if (++sp.q0 == nq0) sp.q0 = 0, ++sp.n;
+  };
+  auto next_valid = [&](StagePos& sp) {  // the first stage at or behind sp whose input plane exists
+    while (sp.step < step_end) {
+      while (sp.t0 < nt0) {
+        const int i0 = in_plane(sp.q0, sp.t0);
         if (i0 >= 0 && i0 < g.in_ext[0]) return;
-        ++t0;
+        ++sp.t0;
       }
-      ++step;
-      t0 = 0;
+      next_step(sp);
     }
   };
   PT ra[PA];
   u32x4 rb[kPB16];
-  auto load_stage = [&](int step, int t0, bool weights) {
-    const int n = a.tp > 1 ? step * a.tp : step / nq0;
-    const uint32_t pmax = (uint32_t)min(a.tp, planes - step * a.tp);
-    const uint32_t sbase = ((uint32_t)n * sin + (uint32_t)in_plane(step, t0) * si0) * 4u;
+  auto load_stage = [&](const StagePos& sp, bool weights) {
+    const int t0 = sp.t0;
+    const uint32_t pmax = (uint32_t)min(a.tp, planes - sp.step * a.tp);
+    const uint32_t sbase = ((uint32_t)sp.n * sin + (uint32_t)in_plane(sp.q0, t0) * si0) * 4u;
 #pragma unroll
     for (int i = 0; i < PA; ++i) ra[i] = Piece<V>::load(rin, (loff[i] >> 24) < pmax ? goff[i] : kOobS, sbase);
     if (weights) {
@@ -607,30 +619,28 @@ __global__ __launch_bounds__(256, 2) void corr16_kernel(const WorkerDev* __restr
     f += step_end - step_begin;
   }
   setup_pieces();
-  int cs = step_begin, ct0 = 0;
-  if (ntaps == 0) cs = step_end;  // a parity class no tap reaches: zeros
-  next_valid(cs, ct0);
-  if (cs < step_end) load_stage(cs, ct0, ct0 != staged_t0);
+  StagePos cur = pos_of(step_begin), out = cur;  // the stage in flight; the step that is being accumulated
+  if (ntaps == 0) cur.step = step_end;           // a parity class no tap reaches: zeros
+  next_valid(cur);
+  if (cur.step < step_end) load_stage(cur, cur.t0 != staged_t0);
   setup_operands();  // while the first stage is on its way
   for (int step = step_begin; step < step_end; ++step) {
 #pragma unroll
     for (int mt = 0; mt < 4; ++mt) acc[mt] = floatx4{0.f, 0.f, 0.f, 0.f};
-    while (cs == step) {
-      const bool wnow = ct0 != staged_t0;
+    while (cur.step == step) {
+      const bool wnow = cur.t0 != staged_t0;
       write_stage(wnow);
-      staged_t0 = ct0;
+      staged_t0 = cur.t0;
       __syncthreads();
-      int ns = cs, nt = ct0 + 1;
-      next_valid(ns, nt);
-      if (ns < step_end) load_stage(ns, nt, nt != staged_t0);  // in flight while this stage multiplies
+      ++cur.t0;
+      next_valid(cur);
+      if (cur.step < step_end) load_stage(cur, cur.t0 != staged_t0);  // in flight while this stage multiplies
       compute();
       __syncthreads();  // everyone is done reading this stage
-      cs = ns;
-      ct0 = nt;
     }
-    const int n = a.tp > 1 ? step * a.tp : step / nq0, q0 = a.tp > 1 ? 0 : step % nq0;
-    store_tile(acc, ((uint32_t)n * son + (uint32_t)(g.out_base[0] + g.os[0] * q0) * so0) * 4u,
+    store_tile(acc, ((uint32_t)out.n * son + (uint32_t)(g.out_base[0] + g.os[0] * out.q0) * so0) * 4u,
                (uint32_t)min(a.tp, planes - step * a.tp) * trtc);
+    next_step(out);
   }
   } while (MULTI && f < f_end);
 }
