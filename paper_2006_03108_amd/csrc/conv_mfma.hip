@@ -117,7 +117,7 @@ __global__ __launch_bounds__(256, (PA <= 4 && MT == 2 && MODE == 0 && NT > 0) ? 
   // needs, then the tap table.  DMA: two buffers of (a_pad + nb_vec4) units, the second one at the compile-time
   // offset kBufPitch (the most a buffer of this variant can hold), so that the operand reads of either buffer are
   // the same address registers with a different immediate offset; then the spare unit and the table.
-  constexpr uint32_t kBufPitch = (uint32_t)(PA + PB) * 4096u;
+  constexpr uint32_t kBufPitch = (uint32_t)(PA * 256 + (NT > 0 ? NT : PB * 4) * 64) * 16u;
   const int nb_vec4 = a.nt[1] * a.nt[2] * 64;
   const int a_units = DMA ? a.a_pad : a.a_vec4;  // where the weights of a buffer start
   const int dummy = DMA ? (int)(kBufPitch / 16) + a.a_pad + nb_vec4 : a.a_vec4 + nb_vec4;
@@ -1063,7 +1063,7 @@ __global__ __launch_bounds__(256) void bias_partial_kernel(const WorkerDev* __re
 
 static int lds_bytes(const CorrArgs& a) { return (a.a_vec4 + a.nt[1] * a.nt[2] * 64 + 1) * 16 + (a.nt[1] * a.nt[2] + 4) * 4; }
 // the variant that loads straight into LDS: two staging buffers
-static int lds_bytes_dma(const CorrArgs& a) { return (4 + 3) * 4096 + a.bufb + 16 + (a.nt[1] * a.nt[2] + 4) * 4; }  // PA = 4, PB = 3
+static int lds_bytes_dma(const CorrArgs& a) { return (4 * 256 + a.nt[1] * a.nt[2] * 64) * 16 + a.bufb + 16 + (a.nt[1] * a.nt[2] + 4) * 4; }  // PA = 4
 
 // Window of tr x tc output positions (tr * tc <= 128 * mt) and everything derived from it.
 static void finish_args(CorrArgs& a, int mt, int tc) {
