@@ -24,8 +24,13 @@ static hipEvent_t get_event() {
     g_free_events.pop_back();
     return e;
   }
+  // Timing-only events: without the system-scope fence a record does not write back and invalidate the caches
+  // between two kernels, which would be charged to the kernel that follows.
   hipEvent_t e = nullptr;
-  (void)hipEventCreate(&e);
+  if (hipEventCreateWithFlags(&e, hipEventDisableSystemFence) != hipSuccess) {
+    (void)hipGetLastError();
+    (void)hipEventCreate(&e);
+  }
   return e;
 }
 
