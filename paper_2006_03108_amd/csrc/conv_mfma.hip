@@ -106,7 +106,7 @@ __device__ inline float load_scalar(const void* p, size_t i) {
 // are held to 128 (two M-tiles; they need 132 without the limit) or 168 (three) so that four or three workgroups
 // share a compute unit (0.684 -> 0.666 ms per class on the 5^3 stride-2 layer with two M-tiles).
 template <int MT, int PA, int PB, int NT, int MODE, bool DMA = false>
-__global__ __launch_bounds__(256, (PA <= 4 && MT == 2 && MODE == 0 && NT > 0) ? 4 : (PA <= 4 && MT == 3 && MODE == 0 && NT > 0) ? 3 : 2) void corr_mfma_kernel(const WorkerDev* __restrict__ workers,
+__global__ __launch_bounds__(256, (PA <= 4 && MT == 2 && MODE == 0 && NT > 0) ? 4 : (PA <= 4 && MT == 3 && (MODE == 0 || DMA) && NT > 0) ? 3 : 2) void corr_mfma_kernel(const WorkerDev* __restrict__ workers,
                                                            void* const* in_bufs, void* const* out_bufs, CorrArgs a) {
   extern __shared__ float4 lds[];
   constexpr bool BF16 = MODE != 0, BFM = MODE == 2;
@@ -198,56 +198,36 @@ __global__ __launch_bounds__(256, (PA <= 4 && MT == 2 && MODE == 0 && NT > 0) ? 
 
   // The workgroup's 128*MT output positions form a tr x tc window, row-major; lane m of M-tile
   // (wave, mt) multiplies window position (wave*MT + mt)*32 + m.
-  // fp32 tensors (TR): the tile is accumulated transposed (the weights are the first MFMA operand), so accumulator
-  // register v of lane (h, m) is channel ntile*32 + 8*(v/4) + 4*h + v%4 of that same position: a register quad is
-  // four consecutive channels and goes out as one 16-byte store, and a lane needs one store offset per M-tile
-  // (36 registers fewer than sixteen).
-  // bf16 tensors: register v of lane (h, m) is window position (wave*MT + mt)*32 + 8*(v/4) + 4*h + v%4, channel
-  // ntile*32 + m, stored 2 bytes at a time: an instruction then writes the 64 contiguous bytes of a position, where
-  // 8-byte quads would be 64 pieces in 64 different lines (measured on the bf16 data-gradient classes of the 5^3
-  // stride-2 layer: 0.140 against 0.148 ms).
-  constexpr bool TR = !BF16;
+  // The tile is accumulated transposed (the weights are the first MFMA operand), so accumulator register v of lane
+  // (h, m) is channel ntile*32 + 8*(v/4) + 4*h + v%4 of that same position: a register quad is four consecutive
+  // channels, and a lane needs one store offset per M-tile (sixteen with the tile the other way round: 36 - 45
+  // registers and most of the set-up arithmetic).  fp32: a quad goes out as one 16-byte store.  bf16: a quad is 8
+  // bytes; the lanes (0, m) and (1, m) exchange one quad of each pair (v_permlane32_swap), after which lane (h, m)
+  // holds the eight channels 16*p + 8*h ... + 7 of pair p = 0, 1: two 16-byte stores per M-tile where 2-byte stores
+  // took sixteen (a plane's epilogue then took as long as three of its six stages on the bf16 data-gradient classes
+  // of the 5^3 stride-2 layer).  Channel counts that are not a multiple of 8 store the quads as they are, 8 bytes each.
+  const bool pairs = BF16 && (a.nc & 7) == 0;
   uint32_t abase[MT];
-  uint32_t soff[MT][TR ? 1 : 16];  // TR: of channel ntile*32 + 4*h of the lane's position (kOob: nothing to store)
-  const int ch0 = ntile * 32 + 4 * h, ch = ntile * 32 + m;
+  uint32_t soff[MT];  // of the first channel this lane stores at its position (kOob: nothing to store)
+  const int ch0 = ntile * 32 + 4 * h, chs = pairs ? ntile * 32 + 8 * h : ch0;
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) {
     const int pidx = (wave * MT + mt) * 32 + m;
     int wr = (int)fd_div((uint32_t)pidx, a.div_tc), wc = pidx - wr * a.tc;
-    if constexpr (TR) {
-      const int q1 = q1_0 + wr, q2 = q2_0 + wc;
-      soff[mt][0] = kOob;
-      if (wr < a.tr && q1 < g.nq[1] && q2 < g.nq[2])
-        soff[mt][0] = ((g.out_base[1] + g.os[1] * q1) * so1 + (g.out_base[2] + g.os[2] * q2) * so2 + ch0) * ES;
-    }
+    const int q1 = q1_0 + wr, q2 = q2_0 + wc;
+    soff[mt] = kOob;
+    if (wr < a.tr && q1 < g.nq[1] && q2 < g.nq[2])
+      soff[mt] = ((g.out_base[1] + g.os[1] * q1) * so1 + (g.out_base[2] + g.os[2] * q2) * so2 + chs) * ES;
     if (wr >= a.tr) wr = 0, wc = 0;  // idle position: multiplies something in range, never stored
     abase[mt] = (wr * a.is[1] * 2 * a.is[2] * a.CwQ + wc + h * a.is[2] * a.CwQ) * 16;
   }
-  if constexpr (!TR) {
+  // the channel quads of this lane (channel counts are multiples of 4, so a quad is whole or absent)
+  float bias[4][4];
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
+  for (int q = 0; q < 4; ++q)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int po = (wave * MT + mt) * 32 + 8 * (v / 4) + 4 * h + (v % 4);
-        const int orow = (int)fd_div((uint32_t)po, a.div_tc), ocol = po - orow * a.tc;
-        const int q1 = q1_0 + orow, q2 = q2_0 + ocol;
-        soff[mt][v] = kOob;
-        if (orow < a.tr && q1 < g.nq[1] && q2 < g.nq[2] && ch < a.nc)
-          soff[mt][v] = ((g.out_base[1] + g.os[1] * q1) * so1 + (g.out_base[2] + g.os[2] * q2) * so2 + ch) * ES;
-      }
-    }
-  }
-  // TR: the channel quads of this lane (channel counts are multiples of 4, so a quad is whole or absent)
-  float bias[TR ? 4 : 1][TR ? 4 : 1];
-  if constexpr (TR) {
-#pragma unroll
-    for (int q = 0; q < 4; ++q)
-#pragma unroll
-      for (int e = 0; e < 4; ++e)
-        bias[q][e] = (a.bias && ch0 + 8 * q + e < a.nc) ? load_scalar<BF16>(a.bias, ch0 + 8 * q + e) : 0.f;
-  } else {
-    bias[0][0] = (a.bias && ch < a.nc) ? load_scalar<BF16>(a.bias, ch) : 0.f;
-  }
+    for (int e = 0; e < 4; ++e)
+      bias[q][e] = (a.bias && ch0 + 8 * q + e < a.nc) ? load_scalar<BF16>(a.bias, ch0 + 8 * q + e) : 0.f;
   const uint32_t boff0 = tid * 16, bread = ((h * 32 + m) + a_units) * 16;  // weight piece / operand addresses
 
   const int* __restrict__ tapinfo = a.tapinfo;  // [0..7]: plane offsets, [8..]: patch offset per (t1, t2)
@@ -372,23 +352,19 @@ __global__ __launch_bounds__(256, (PA <= 4 && MT == 2 && MODE == 0 && NT > 0) ? 
       for (int mt = 0; mt < MT; ++mt) {
         Frag fa;
         fa.f = av[mt];
-        acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa.v, fb.v, acc[mt], 0, 0, 0);
+        acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb.v, fa.v, acc[mt], 0, 0, 0);
       }
       return;
     }
     // M-tiles interleaved, so that consecutive MFMAs do not depend on each other
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) acc[mt] = TR ? __builtin_amdgcn_mfma_f32_32x32x2f32(b.x, av[mt].x, acc[mt], 0, 0, 0)
-                     : __builtin_amdgcn_mfma_f32_32x32x2f32(av[mt].x, b.x, acc[mt], 0, 0, 0);
+    for (int mt = 0; mt < MT; ++mt) acc[mt] = __builtin_amdgcn_mfma_f32_32x32x2f32(b.x, av[mt].x, acc[mt], 0, 0, 0);
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) acc[mt] = TR ? __builtin_amdgcn_mfma_f32_32x32x2f32(b.y, av[mt].y, acc[mt], 0, 0, 0)
-                     : __builtin_amdgcn_mfma_f32_32x32x2f32(av[mt].y, b.y, acc[mt], 0, 0, 0);
+    for (int mt = 0; mt < MT; ++mt) acc[mt] = __builtin_amdgcn_mfma_f32_32x32x2f32(b.y, av[mt].y, acc[mt], 0, 0, 0);
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) acc[mt] = TR ? __builtin_amdgcn_mfma_f32_32x32x2f32(b.z, av[mt].z, acc[mt], 0, 0, 0)
-                     : __builtin_amdgcn_mfma_f32_32x32x2f32(av[mt].z, b.z, acc[mt], 0, 0, 0);
+    for (int mt = 0; mt < MT; ++mt) acc[mt] = __builtin_amdgcn_mfma_f32_32x32x2f32(b.z, av[mt].z, acc[mt], 0, 0, 0);
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) acc[mt] = TR ? __builtin_amdgcn_mfma_f32_32x32x2f32(b.w, av[mt].w, acc[mt], 0, 0, 0)
-                     : __builtin_amdgcn_mfma_f32_32x32x2f32(av[mt].w, b.w, acc[mt], 0, 0, 0);
+    for (int mt = 0; mt < MT; ++mt) acc[mt] = __builtin_amdgcn_mfma_f32_32x32x2f32(b.w, av[mt].w, acc[mt], 0, 0, 0);
   };
 
   // The operands of tap t + 1 are read while tap t multiplies; the scheduling barriers keep the
@@ -434,46 +410,23 @@ __global__ __launch_bounds__(256, (PA <= 4 && MT == 2 && MODE == 0 && NT > 0) ? 
   floatx16 acc[MT];
   StagePos sp{p_begin, p_begin / nq0, p_begin % nq0, -1, ncc - 1};  // the stage whose loads are in flight
   advance(sp);
-  uint32_t buf_cur = 0, buf_nxt = kBufPitch;  // DMA: where the stage in flight lands, and the other buffer
-  if (sp.p < p_end) {
-    if constexpr (DMA) issue_stage(sp, buf_cur);
-    else load_stage(sp);
-  }
-  int on = p_begin / nq0, oq0 = p_begin % nq0;
-  for (int po = p_begin; po < p_end; ++po) {  // output planes of this workgroup
+  int on = p_begin / nq0, oq0 = p_begin % nq0;  // the output plane that is stored next
+  auto zero_acc = [&]() {
 #pragma unroll
     for (int t = 0; t < MT; ++t)
       for (int v = 0; v < 16; ++v) acc[t][v] = 0.f;
-    while (sp.p == po) {  // the stages that feed output plane po
-      if constexpr (DMA) {
-        // The only loads in flight are this stage's: wait for mine, then for everyone's.  Past the barrier every
-        // wave has also finished multiplying the stage before, so the other buffer may be refilled.
-        __builtin_amdgcn_s_waitcnt(kWaitVmcnt0);
-        lds_barrier();
-        advance(sp);
-        if (sp.p < p_end) issue_stage(sp, buf_nxt);  // lands while this stage multiplies
-        if (buf_cur == 0) compute(acc, std::false_type{});  // (uniform: two copies of the loop, one per buffer)
-        else compute(acc, std::true_type{});
-        { const uint32_t x = buf_cur; buf_cur = buf_nxt; buf_nxt = x; }
-      } else {
-        write_stage();
-        __syncthreads();
-        advance(sp);
-        if (sp.p < p_end) load_stage(sp);  // in flight while this stage multiplies
-        compute(acc, std::false_type{});
-        __syncthreads();  // everyone is done reading this stage
-      }
-    }
+  };
+  auto store_plane = [&]() {
     const uint32_t obase = ((uint32_t)on * son + (uint32_t)(g.out_base[0] + g.os[0] * oq0) * so0) * ES;
     if (++oq0 == nq0) oq0 = 0, ++on;
     // (the plane's offset is added into the per-lane offset: with a scalar offset the compiler leaves out the wait
     // states a 16-byte store needs before its data registers are written again)
-    if constexpr (TR) {
+    if constexpr (!BF16) {
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-          const uint32_t off = (ch0 + 8 * q < a.nc ? soff[mt][0] + (uint32_t)(8 * q) * ES : kOob) + obase;
+          const uint32_t off = (ch0 + 8 * q < a.nc ? soff[mt] + (uint32_t)(8 * q) * ES : kOob) + obase;
           u32x4 o;
 #pragma unroll
           for (int e = 0; e < 4; ++e) o[e] = __float_as_uint(acc[mt][4 * q + e] + bias[q][e]);
@@ -481,10 +434,80 @@ __global__ __launch_bounds__(256, (PA <= 4 && MT == 2 && MODE == 0 && NT > 0) ? 
         }
     } else {
 #pragma unroll
-      for (int mt = 0; mt < MT; ++mt)
+      for (int mt = 0; mt < MT; ++mt) {
+        uint32_t pk[4][2];  // quad q as four bf16
 #pragma unroll
-        for (int v = 0; v < 16; ++v)
-          __builtin_amdgcn_raw_buffer_store_b16(bf16_bits(acc[mt][v] + bias[0][0]), rout, soff[mt][v], obase, 0);
+        for (int q = 0; q < 4; ++q)
+#pragma unroll
+          for (int d = 0; d < 2; ++d)
+            pk[q][d] = (uint32_t)bf16_bits(acc[mt][4 * q + 2 * d] + bias[q][2 * d]) |
+                       ((uint32_t)bf16_bits(acc[mt][4 * q + 2 * d + 1] + bias[q][2 * d + 1]) << 16);
+        if (pairs) {
+#pragma unroll
+          for (int pr = 0; pr < 2; ++pr) {
+            // the even quad's upper lanes (h = 1) change places with the odd quad's lower lanes (h = 0)
+            u32x4 o;
+#pragma unroll
+            for (int d = 0; d < 2; ++d) {
+              const auto sw = __builtin_amdgcn_permlane32_swap(pk[2 * pr][d], pk[2 * pr + 1][d], false, false);
+              o[d] = sw[0];
+              o[2 + d] = sw[1];
+            }
+            const uint32_t off = (chs + 16 * pr < a.nc ? soff[mt] + (uint32_t)(16 * pr) * ES : kOob) + obase;
+            __builtin_amdgcn_raw_buffer_store_b128(o, rout, off, 0, 0);
+          }
+        } else {
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+            const uint32_t off = (ch0 + 8 * q < a.nc ? soff[mt] + (uint32_t)(8 * q) * ES : kOob) + obase;
+            __builtin_amdgcn_raw_buffer_store_b64(u32x2{pk[q][0], pk[q][1]}, rout, off, 0, 0);
+          }
+        }
+      }
+    }
+  };
+  if constexpr (DMA) {
+    // Two stages per trip of the loop, one from each buffer, written out one behind the other: with a branch to one
+    // of two copies of the tap loop the compiler kept the accumulators of the copies in different registers and
+    // moved all of them across at every stage (48 - 96 moves for 18 - 27 MFMAs).
+    int po = p_begin;
+    zero_acc();
+    if (sp.p < p_end) issue_stage(sp, 0u);
+    for (; po < sp.p; ++po) store_plane();  // leading planes that no stage feeds (sp.p <= p_end)
+    // At the top of a half, `sp` is the stage in flight into the half's buffer and belongs to output plane po.
+    auto half = [&](auto buf_c) {
+      // The only loads in flight are this stage's: wait for mine, then for everyone's.  Past the barrier every
+      // wave has also finished multiplying the stage before, so the other buffer may be refilled.
+      __builtin_amdgcn_s_waitcnt(kWaitVmcnt0);
+      lds_barrier();
+      advance(sp);
+      if (sp.p < p_end) issue_stage(sp, decltype(buf_c)::value ? 0u : kBufPitch);  // lands while this stage multiplies
+      compute(acc, buf_c);
+      if (sp.p != po) {  // that was the last stage of plane po
+        store_plane();
+        zero_acc();
+        for (++po; po < sp.p; ++po) store_plane();  // planes without a stage: the bias alone
+      }
+    };
+    while (po < p_end) {
+      half(std::false_type{});
+      if (po >= p_end) break;
+      half(std::true_type{});
+    }
+  } else {
+    if (sp.p < p_end) load_stage(sp);
+    for (int po = p_begin; po < p_end; ++po) {  // output planes of this workgroup
+      zero_acc();
+      while (sp.p == po) {  // the stages that feed output plane po
+        write_stage();
+        __syncthreads();
+        advance(sp);
+        if (sp.p < p_end) load_stage(sp);  // in flight while this stage multiplies
+        compute(acc, std::false_type{});
+        __syncthreads();  // everyone is done reading this stage
+      }
+      store_plane();
     }
   }
 }
