@@ -236,6 +236,9 @@ CONV_BF16 = [
                   padding=(1, 1, 1)), True),
     # several channel tiles, the second output tile half full: db sums of the weight-gradient kernel per tile
     ("cfg2", dict(in_shape=(40, 70), n_b=2, c_in=64, c_out=48, ksize=(3, 3), padding=(1, 1), P=(2, 2)), True),
+    # 20 output channels: not a multiple of 8, so the forward kernel stores 8-byte channel quads instead of 16-byte
+    # pieces, and the data gradient (20 contraction channels) widens bf16 to fp32 while staging
+    ("cfg2", dict(in_shape=(37, 45), n_b=2, c_in=40, c_out=20, ksize=(3, 3), padding=(1, 1), stride=(2, 1), P=(2, 2)), True),
 ]
 
 
