@@ -100,8 +100,9 @@ __device__ inline float load_scalar(const void* p, size_t i) {
 // MFMA operand (A lane l holds A[i = l % 32][k = 8 * (l / 32) ... + 7]); needs channel counts that are multiples of 8.
 // DMA (small patches with NT > 0, MODE 0 or 2): a stage goes from memory straight into LDS (global -> LDS loads, no
 // staging registers, no ds_write) into one of two staging buffers, the next stage landing while this one is
-// multiplied, one barrier per stage.  The LDS layout of a stage is the same; thread (i, tid) fetches the piece whose
-// slot is i * 256 + tid (a wave's load fills 64 consecutive slots), found by inverting the slot formula.
+// multiplied, one barrier per stage.  Thread (i, tid) fetches the piece whose slot is i * 256 + tid (a wave's load
+// fills 64 consecutive slots); the patch is laid out in blocks of 32 cells so that such a load reads 32 contiguous
+// bytes per cell.
 // Registers: the fp32 variants with small patches and compile-time taps (the parity classes of the data gradient)
 // are held to 128 (two M-tiles; they need 132 without the limit) or 168 (three) so that four or three workgroups
 // share a compute unit (0.684 -> 0.666 ms per class on the 5^3 stride-2 layer with two M-tiles).
@@ -163,14 +164,17 @@ __global__ __launch_bounds__(256, (PA <= 4 && MT == 2 && MODE == 0 && NT > 0) ? 
     goff[i] = kOob;
     int ph, rr, c;
     bool live;
-    if constexpr (DMA) {  // the piece that lives in slot tid + i * 256: slot = ((rr * 2 + ph) * is2 + cr) * CwQ + cq
+    if constexpr (DMA) {
+      // The piece that lives in slot tid + i * 256.  The patch's cells, row-major, are cut into blocks of 32; a block
+      // is 64 slots, the first halves (ph = 0) of its cells, then the second halves: the 64 lanes of a load fetch 32
+      // contiguous bytes from each of 32 neighbouring cells (with the halves in planes of their own a load touched
+      // 64 cells, 16 bytes each, and issuing a stage's loads took half of a workgroup's life), and the 32 positions
+      // of an operand read fall into consecutive 16-byte slots.
       const uint32_t slot = (uint32_t)(tid + i * 256);
-      uint32_t t = fd_div(slot, a.div_cwq);
-      const int cq = (int)(slot - t * a.CwQ);
-      const uint32_t t2 = fd_div(t, a.div_is2);
-      const int cr = (int)(t - t2 * a.is[2]);
-      ph = (int)(t2 & 1u), rr = (int)(t2 >> 1), c = cq * a.is[2] + cr;
-      live = slot < (uint32_t)a.a_vec4 && c < a.Cw;
+      const uint32_t x = (slot >> 6) * 32u + (slot & 31u);  // cell
+      ph = (int)((slot >> 5) & 1u);
+      rr = (int)fd_div(x, a.div_cw), c = (int)x - rr * a.Cw;
+      live = x < (uint32_t)(a.R * a.Cw);
     } else {
       const int piece = tid + i * 256;
       loff[i] = dummy * 16;
@@ -219,7 +223,8 @@ __global__ __launch_bounds__(256, (PA <= 4 && MT == 2 && MODE == 0 && NT > 0) ? 
     if (wr < a.tr && q1 < g.nq[1] && q2 < g.nq[2])
       soff[mt] = ((g.out_base[1] + g.os[1] * q1) * so1 + (g.out_base[2] + g.os[2] * q2) * so2 + chs) * ES;
     if (wr >= a.tr) wr = 0, wc = 0;  // idle position: multiplies something in range, never stored
-    abase[mt] = (wr * a.is[1] * 2 * a.is[2] * a.CwQ + wc + h * a.is[2] * a.CwQ) * 16;
+    if constexpr (DMA) abase[mt] = wr * a.is[1] * a.Cw + wc * a.is[2];  // (the cell the position reads with a zero tap offset)
+    else abase[mt] = (wr * a.is[1] * 2 * a.is[2] * a.CwQ + wc + h * a.is[2] * a.CwQ) * 16;
   }
   // the channel quads of this lane (channel counts are multiples of 4, so a quad is whole or absent)
   float bias[4][4];
@@ -320,9 +325,19 @@ __global__ __launch_bounds__(256, (PA <= 4 && MT == 2 && MODE == 0 && NT > 0) ? 
   if constexpr (NT > 0) {
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
-      const uint32_t tapo = (uint32_t)tapinfo[8 + t] * 16u;
+      if constexpr (DMA) {  // block layout: cell x sits in block x / 32, half h of it at slot 32 * h + x % 32
+        const int t1 = t / a.nt[2], t2 = t - t1 * a.nt[2];
+        const uint32_t tapx = (uint32_t)((a.tapoff[1][t1] - a.tapmin[1]) * a.Cw + a.tapoff[2][t2] - a.tapmin[2]);
 #pragma unroll
-      for (int mt = 0; mt < MT; ++mt) aaddr[mt][t] = abase[mt] + tapo;
+        for (int mt = 0; mt < MT; ++mt) {
+          const uint32_t x = abase[mt] + tapx;
+          aaddr[mt][t] = ((x >> 5) * 64u + (uint32_t)h * 32u + (x & 31u)) * 16u;
+        }
+      } else {
+        const uint32_t tapo = (uint32_t)tapinfo[8 + t] * 16u;
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) aaddr[mt][t] = abase[mt] + tapo;
+      }
     }
   }
 
@@ -1106,7 +1121,7 @@ static void finish_args(CorrArgs& a, int mt, int tc) {
   a.Cw = (a.tc - 1) * a.is[2] + a.tapspan[2] + 1;
   a.CwQ = (a.Cw + a.is[2] - 1) / a.is[2];
   a.a_vec4 = a.R * 2 * a.is[2] * a.CwQ;
-  a.a_pad = (a.a_vec4 + 63) / 64 * 64;
+  a.a_pad = std::max((a.a_vec4 + 63) / 64 * 64, (a.R * a.Cw + 31) / 32 * 64);  // (blocks of 32 cells, 64 slots each)
   a.bufb = (a.a_pad + a.nt[1] * a.nt[2] * 64) * 16;
   a.div_cwq = make_fastdiv((uint32_t)a.CwQ);
   a.div_cw = make_fastdiv((uint32_t)a.Cw);
