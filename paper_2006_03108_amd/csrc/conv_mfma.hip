@@ -804,10 +804,27 @@ __global__ __launch_bounds__(256, 2) void wgrad_taps_kernel(const WorkerDev* __r
   constexpr int PPC = 32 / PCH;             // pieces per cell of a 32-channel tile
   const int tid = threadIdx.x, lane = tid & 63, h = lane >> 5, m = lane & 31;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int t0 = blockIdx.x;
+  // The workgroups of the k0 kernel planes that share a (worker, chunk, channel tile) read the same input planes:
+  // (o0, t0) and (o0 + 1, t0 - s0 / dil0) are the same plane.  They are given consecutive places in an XCD-aware
+  // order (consecutive places stay on one XCD, i.e. behind one L2), and each walks its chunk's units in a rotated
+  // order (below) so that at the same moment they are on the same input plane: the first to touch a line fetches it
+  // for all of them.
+  uint32_t bx = blockIdx.x, by = blockIdx.y, bz = blockIdx.z;
+  {
+    const uint32_t nblk = gridDim.x * gridDim.y * gridDim.z;
+    if ((nblk & 7u) == 0) {
+      const uint32_t lin = bx + gridDim.x * (by + gridDim.y * bz);
+      const uint32_t r = (lin & 7u) * (nblk >> 3) + (lin >> 3);
+      bx = r % gridDim.x;
+      const uint32_t rest = r / gridDim.x;
+      by = rest % gridDim.y;
+      bz = rest / gridDim.y;
+    }
+  }
+  const int t0 = (int)bx;
   const int nco_t = (a.co + 31) / 32;
-  const int ci_t = blockIdx.y / nco_t, co_t = blockIdx.y - ci_t * nco_t;
-  const int worker = blockIdx.z / a.nchunks, chunk = blockIdx.z - worker * a.nchunks;
+  const int ci_t = (int)by / nco_t, co_t = (int)by - ci_t * nco_t;
+  const int worker = (int)bz / a.nchunks, chunk = (int)bz - worker * a.nchunks;
   const WorkerDev wd = workers[worker];
   const int s1 = a.s[1], span = a.span, ring = span + s1;
   const int rowp = (a.ncell * PPC + 63) & ~63;  // 16-byte pieces per staged row, rounded up to whole waves
@@ -920,7 +937,11 @@ __global__ __launch_bounds__(256, 2) void wgrad_taps_kernel(const WorkerDev* __r
                               : (uint32_t)(h * S2 * 32 + m) * 4u;
   const uint32_t lane_y = ys_base + (BFM ? (uint32_t)((8 * (lg >> 1) + (ls >> 2)) * 64 + (16 * (lg & 1) + 4 * (ls & 3)) * 2)
                                          : (uint32_t)(h * 32 + m) * 4u);
-  for (int unit = chunk * per; unit < unit_end; ++unit) {
+  // unit order of this kernel plane: rotated by the output planes that the last kernel plane is ahead of it
+  const int unit_begin = chunk * per, unit_cnt = unit_end - unit_begin;
+  const int skew = unit_cnt > 0 ? (((a.k[0] - 1 - t0) * a.dil[0]) / a.s[0] * nblk1) % unit_cnt : 0;
+  for (int uj = 0; uj < unit_cnt; ++uj) {
+    const int unit = unit_begin + (uj + skew < unit_cnt ? uj + skew : uj + skew - unit_cnt);
     const int plane = unit / nblk1, o1_begin = (unit - plane * nblk1) * a.ob, o1_end = min(O1, o1_begin + a.ob);
     const int o0 = plane % wd.out[0], n = plane / wd.out[0];
     for (int seg = 0; seg < nseg; ++seg) {
@@ -1011,7 +1032,7 @@ __global__ __launch_bounds__(256, 2) void wgrad_taps_kernel(const WorkerDev* __r
   }
   const int co = co_t * 32 + m;
   const bool co_ok = co < a.co;
-  float* pbase = partial + (size_t)blockIdx.z * a.slot;
+  float* pbase = partial + (size_t)bz * a.slot;
 #pragma unroll
   for (int i = 0; i < NOWN; ++i) {
     if (i >= ntw) break;
