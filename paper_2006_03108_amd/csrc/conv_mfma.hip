@@ -251,22 +251,34 @@ __global__ __launch_bounds__(256, (PA <= 4 && MT == 2 && MODE == 0 && NT > 0) ? 
   const int toff0 = a.tapoff[0][0], tstep = a.nt[0] > 1 ? a.tapoff[0][1] - a.tapoff[0][0] : 0;
   auto plane_of = [&](int q0, int t0) { return g.in_base[0] + q0 * a.is[0] + toff0 + t0 * tstep; };
   // a stage position: plane p = (n, q0), tap plane t0, chunk cc
+  // Workgroups that own one output plane each (g0 == 1) run side by side on neighbouring planes, and the input plane
+  // of (q0, t0) is that of (q0 + 1, t0 - d), d = step / tap spacing.  Each walks its kernel planes in a rotated
+  // order, starting d * q0 behind, so that neighbours stand on the same input plane at the same moment and the first
+  // to touch a line fetches it for all behind that L2 (every plane of the 5^3 stride-2 layer is then fetched for 2.5
+  // output planes at once instead of 2.5 times).  j counts the kernel planes visited, t0 = (j + sk) mod nt0.
+  const int rot_d = (a.g0 == 1 && nt0 > 1 && tstep != 0 && a.is[0] % tstep == 0) ? (a.is[0] / tstep) % nt0 : 0;
+  auto skew_of = [&](int q0) {
+    const int r = (int)(((int64_t)rot_d * q0) % nt0);  // (once per workgroup)
+    return r == 0 ? 0 : (r > 0 ? nt0 - r : -r);          // (-d * q0) mod nt0
+  };
   struct StagePos {
-    int p, n, q0, t0, cc;
+    int p, n, q0, t0, cc, j, sk;
   };
   auto advance = [&](StagePos& sp) {  // next valid stage after sp, or sp.p == p_end
     if (++sp.cc < ncc) return;  // same plane, next chunk
     sp.cc = 0;
-    ++sp.t0;
+    ++sp.j;
     while (sp.p < p_end) {
-      while (sp.t0 < nt0) {
+      while (sp.j < nt0) {
+        sp.t0 = sp.j + sp.sk < nt0 ? sp.j + sp.sk : sp.j + sp.sk - nt0;
         const int i0 = plane_of(sp.q0, sp.t0);
         if (i0 >= 0 && i0 < g.in_ext[0]) return;
-        ++sp.t0;
+        ++sp.j;
       }
       ++sp.p;
-      sp.t0 = 0;
+      sp.j = 0;
       if (++sp.q0 == nq0) sp.q0 = 0, ++sp.n;
+      sp.sk = rot_d ? skew_of(sp.q0) : 0;
     }
   };
   // DMA: the loads of stage sp, straight into the staging buffer at byte offset `bufoff`
@@ -423,7 +435,8 @@ __global__ __launch_bounds__(256, (PA <= 4 && MT == 2 && MODE == 0 && NT > 0) ? 
   };
 
   floatx16 acc[MT];
-  StagePos sp{p_begin, p_begin / nq0, p_begin % nq0, -1, ncc - 1};  // the stage whose loads are in flight
+  StagePos sp{p_begin, p_begin / nq0, p_begin % nq0, 0, ncc - 1, -1, 0};  // the stage whose loads are in flight
+  sp.sk = rot_d ? skew_of(sp.q0) : 0;
   advance(sp);
   int on = p_begin / nq0, oq0 = p_begin % nq0;  // the output plane that is stored next
   auto zero_acc = [&]() {
