@@ -138,9 +138,9 @@ __global__ __launch_bounds__(256, (PA <= 4 && MT == 2 && MODE == 0 && NT > 0) ? 
   const int q2_0 = (tile % nt2tiles) * a.tc; tile /= nt2tiles;
   const int q1_0 = (tile % nt1tiles) * a.tr; tile /= nt1tiles;
   const int ntile = tile % a.ntn; tile /= a.ntn;
-  // output planes of this workgroup: p = n * nq[0] + q0 in [p_begin, p_end)
+  // output planes p = n * nq[0] + q0 of the worker; `tile` is now this workgroup's place among the plane groups
   const int nq0 = g.nq[0];
-  const int p_begin = tile * a.g0, p_end = min(p_begin + a.g0, a.n_b * nq0);
+  const int ptotal = a.n_b * nq0, ngroups = (ptotal + a.g0 - 1) / a.g0;
 
   const int si2 = a.kc, si1 = g.in_ext[2] * si2, si0 = g.in_ext[1] * si1;
   const uint32_t sin = (uint32_t)g.in_ext[0] * si0;
@@ -251,12 +251,18 @@ __global__ __launch_bounds__(256, (PA <= 4 && MT == 2 && MODE == 0 && NT > 0) ? 
   const int toff0 = a.tapoff[0][0], tstep = a.nt[0] > 1 ? a.tapoff[0][1] - a.tapoff[0][0] : 0;
   auto plane_of = [&](int q0, int t0) { return g.in_base[0] + q0 * a.is[0] + toff0 + t0 * tstep; };
   // a stage position: plane p = (n, q0), tap plane t0, chunk cc
-  // Workgroups that own one output plane each (g0 == 1) run side by side on neighbouring planes, and the input plane
-  // of (q0, t0) is that of (q0 + 1, t0 - d), d = step / tap spacing.  Each walks its kernel planes in a rotated
-  // order, starting d * q0 behind, so that neighbours stand on the same input plane at the same moment and the first
-  // to touch a line fetches it for all behind that L2 (every plane of the 5^3 stride-2 layer is then fetched for 2.5
-  // output planes at once instead of 2.5 times).  j counts the kernel planes visited, t0 = (j + sk) mod nt0.
-  const int rot_d = (a.g0 == 1 && nt0 > 1 && tstep != 0 && a.is[0] % tstep == 0) ? (a.is[0] / tstep) % nt0 : 0;
+  // The workgroups of a worker's plane groups run side by side, and the input plane of (q0, t0) is that of
+  // (q0 + 1, t0 - d), d = step / tap spacing.  So the planes are dealt to the groups in turn (group k takes planes k,
+  // k + ngroups, ...: at any moment the groups work on neighbouring planes), and each plane's kernel planes are
+  // walked in a rotated order, starting d * q0 behind: neighbours then stand on the same input plane at the same
+  // moment and the first to touch a line fetches it for all behind that L2 (every input plane of the 5^3 stride-2
+  // layer is then fetched for 2.5 output planes at once instead of 2.5 times: 7.8 GB instead of 23.1 GB per forward
+  // launch).  j counts the kernel planes visited, t0 = (j + sk) mod nt0.
+  const int rot_d = (nt0 > 1 && tstep != 0 && a.is[0] % tstep == 0) ? (a.is[0] / tstep) % nt0 : 0;
+  const bool dealt = rot_d != 0 && ngroups > 1;
+  const int pfirst = dealt ? (int)tile : (int)tile * a.g0, pstride = dealt ? ngroups : 1;
+  // this workgroup's planes: pfirst + i * pstride, i in [0, pcnt)
+  const int pcnt = dealt ? (ptotal - (int)tile + ngroups - 1) / ngroups : min(a.g0, ptotal - (int)tile * a.g0);
   auto skew_of = [&](int q0) {
     const int r = (int)(((int64_t)rot_d * q0) % nt0);  // (once per workgroup)
     return r == 0 ? 0 : (r > 0 ? nt0 - r : -r);          // (-d * q0) mod nt0
@@ -264,11 +270,11 @@ __global__ __launch_bounds__(256, (PA <= 4 && MT == 2 && MODE == 0 && NT > 0) ? 
   struct StagePos {
     int p, n, q0, t0, cc, j, sk;
   };
-  auto advance = [&](StagePos& sp) {  // next valid stage after sp, or sp.p == p_end
+  auto advance = [&](StagePos& sp) {  // next valid stage after sp, or sp.p == pcnt (p counts this workgroup's planes)
     if (++sp.cc < ncc) return;  // same plane, next chunk
     sp.cc = 0;
     ++sp.j;
-    while (sp.p < p_end) {
+    while (sp.p < pcnt) {
       while (sp.j < nt0) {
         sp.t0 = sp.j + sp.sk < nt0 ? sp.j + sp.sk : sp.j + sp.sk - nt0;
         const int i0 = plane_of(sp.q0, sp.t0);
@@ -277,7 +283,8 @@ __global__ __launch_bounds__(256, (PA <= 4 && MT == 2 && MODE == 0 && NT > 0) ? 
       }
       ++sp.p;
       sp.j = 0;
-      if (++sp.q0 == nq0) sp.q0 = 0, ++sp.n;
+      sp.q0 += pstride;
+      while (sp.q0 >= nq0) sp.q0 -= nq0, ++sp.n;
       sp.sk = rot_d ? skew_of(sp.q0) : 0;
     }
   };
@@ -435,10 +442,10 @@ __global__ __launch_bounds__(256, (PA <= 4 && MT == 2 && MODE == 0 && NT > 0) ? 
   };
 
   floatx16 acc[MT];
-  StagePos sp{p_begin, p_begin / nq0, p_begin % nq0, 0, ncc - 1, -1, 0};  // the stage whose loads are in flight
+  StagePos sp{0, pfirst / nq0, pfirst % nq0, 0, ncc - 1, -1, 0};  // the stage whose loads are in flight
   sp.sk = rot_d ? skew_of(sp.q0) : 0;
   advance(sp);
-  int on = p_begin / nq0, oq0 = p_begin % nq0;  // the output plane that is stored next
+  int on = pfirst / nq0, oq0 = pfirst % nq0;  // the output plane that is stored next
   auto zero_acc = [&]() {
 #pragma unroll
     for (int t = 0; t < MT; ++t)
@@ -446,7 +453,8 @@ __global__ __launch_bounds__(256, (PA <= 4 && MT == 2 && MODE == 0 && NT > 0) ? 
   };
   auto store_plane = [&]() {
     const uint32_t obase = ((uint32_t)on * son + (uint32_t)(g.out_base[0] + g.os[0] * oq0) * so0) * ES;
-    if (++oq0 == nq0) oq0 = 0, ++on;
+    oq0 += pstride;
+    while (oq0 >= nq0) oq0 -= nq0, ++on;
     // (the plane's offset is added into the per-lane offset: with a scalar offset the compiler leaves out the wait
     // states a 16-byte store needs before its data registers are written again)
     if constexpr (!BF16) {
@@ -499,10 +507,10 @@ __global__ __launch_bounds__(256, (PA <= 4 && MT == 2 && MODE == 0 && NT > 0) ? 
     // Two stages per trip of the loop, one from each buffer, written out one behind the other: with a branch to one
     // of two copies of the tap loop the compiler kept the accumulators of the copies in different registers and
     // moved all of them across at every stage (48 - 96 moves for 18 - 27 MFMAs).
-    int po = p_begin;
+    int po = 0;
     zero_acc();
-    if (sp.p < p_end) issue_stage(sp, 0u);
-    for (; po < sp.p; ++po) store_plane();  // leading planes that no stage feeds (sp.p <= p_end)
+    if (sp.p < pcnt) issue_stage(sp, 0u);
+    for (; po < sp.p; ++po) store_plane();  // leading planes that no stage feeds (sp.p <= pcnt)
     // At the top of a half, `sp` is the stage in flight into the half's buffer and belongs to output plane po.
     auto half = [&](auto buf_c) {
       // The only loads in flight are this stage's: wait for mine, then for everyone's.  Past the barrier every
@@ -510,7 +518,7 @@ __global__ __launch_bounds__(256, (PA <= 4 && MT == 2 && MODE == 0 && NT > 0) ? 
       __builtin_amdgcn_s_waitcnt(kWaitVmcnt0);
       lds_barrier();
       advance(sp);
-      if (sp.p < p_end) issue_stage(sp, decltype(buf_c)::value ? 0u : kBufPitch);  // lands while this stage multiplies
+      if (sp.p < pcnt) issue_stage(sp, decltype(buf_c)::value ? 0u : kBufPitch);  // lands while this stage multiplies
       compute(acc, buf_c);
       if (sp.p != po) {  // that was the last stage of plane po
         store_plane();
@@ -518,20 +526,20 @@ __global__ __launch_bounds__(256, (PA <= 4 && MT == 2 && MODE == 0 && NT > 0) ? 
         for (++po; po < sp.p; ++po) store_plane();  // planes without a stage: the bias alone
       }
     };
-    while (po < p_end) {
+    while (po < pcnt) {
       half(std::false_type{});
-      if (po >= p_end) break;
+      if (po >= pcnt) break;
       half(std::true_type{});
     }
   } else {
-    if (sp.p < p_end) load_stage(sp);
-    for (int po = p_begin; po < p_end; ++po) {  // output planes of this workgroup
+    if (sp.p < pcnt) load_stage(sp);
+    for (int po = 0; po < pcnt; ++po) {  // output planes of this workgroup
       zero_acc();
       while (sp.p == po) {  // the stages that feed output plane po
         write_stage();
         __syncthreads();
         advance(sp);
-        if (sp.p < p_end) load_stage(sp);  // in flight while this stage multiplies
+        if (sp.p < pcnt) load_stage(sp);  // in flight while this stage multiplies
         compute(acc, std::false_type{});
         __syncthreads();  // everyone is done reading this stage
       }
