@@ -833,7 +833,7 @@ def main():
         # the remaining single-GPU configurations, for reference (same harness, no CPU leg)
         detail["other_configs"] = {}
         for tag, make, steps in (("cfg2", lambda: ConvWorkload("cfg2"), 50),
-                                 ("cfg5-bf16", lambda: ConvWorkload("cfg5", "bf16"), 3),
+                                 ("cfg5-bf16", lambda: ConvWorkload("cfg5", "bf16"), 20),
                                  ("cfg3", lambda: AffineWorkload("cfg3", "f32"), 50),
                                  ("cfg3-bf16", lambda: AffineWorkload("cfg3", "bf16"), 50),
                                  ("cfg4", lambda: SmallCnnWorkload(), 50)):
